@@ -1,0 +1,104 @@
+"""Seeded synthetic inputs and the named parameter presets.
+
+This module serves both the GPU library's tests/benchmark and the CPU oracle's
+tests.  It holds NONE of the method's arithmetic: it only draws the random
+numbers the scheme consumes (secret, errors, uniform polynomials, slot values,
+layer weights, rotation offsets) and names the workload shapes.  Everything the
+method computes from these draws is computed separately by each side.
+
+Distributions (paper section 2.1 leaves them open; these are the readings used):
+  secret s, encryption randomness r : i.i.d. uniform on {-1, 0, 1}
+  errors e, e0, e1                  : round(N(0, 3.2^2)), redrawn while |e| > 19
+  a (public key / switching keys)   : uniform on [0, q) per limb, independently
+  slot values                       : uniform on the stated interval
+  conv / FC weights                 : N(0, 0.05^2), encoded as round(w * q_last)
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+BASE_SEED = 20191126
+
+
+@dataclass(frozen=True)
+class Preset:
+    name: str
+    logN: int
+    n_q: int
+    q_bits: int
+    k: int
+    special_bits: int
+    alpha: int
+    log_scale: int
+    batch: int
+
+    @property
+    def N(self):
+        return 1 << self.logN
+
+
+# the five workload shapes; k/alpha/special size where a shape leaves them open
+# follow the hybrid form "alpha primes per digit, k = alpha special primes of
+# q_bits+1 bits"
+PRESETS = {
+    "tiny": Preset("tiny", 12, 3, 40, 1, 41, 1, 30, 16),
+    "hmul_rot_2e14": Preset("hmul_rot_2e14", 14, 8, 50, 1, 51, 1, 40, 256),
+    "conv_2e15": Preset("conv_2e15", 15, 16, 50, 0, 51, 1, 40, 16384),
+    "act_2e16": Preset("act_2e16", 16, 24, 50, 3, 51, 3, 50, 64),
+    "cnn_2e16": Preset("cnn_2e16", 16, 30, 50, 3, 51, 3, 50, 32768),
+}
+
+
+def rng(seed, *stream):
+    return np.random.Generator(np.random.Philox(key=[(BASE_SEED + int(seed)) & (2**64 - 1), hash_stream(stream)]))
+
+
+def hash_stream(stream):
+    h = 0xCBF29CE484222325
+    for s in stream:
+        for ch in str(s).encode():
+            h = ((h ^ ch) * 0x100000001B3) & (2**64 - 1)
+        h = ((h ^ 0xFF) * 0x100000001B3) & (2**64 - 1)
+    return h
+
+
+def ternary(N, seed, *stream):
+    return rng(seed, "ternary", *stream).integers(-1, 2, size=N, dtype=np.int64)
+
+
+def gaussian_error(shape, seed, *stream, sigma=3.2, bound=19):
+    g = rng(seed, "error", *stream)
+    e = np.rint(g.normal(0.0, sigma, size=shape)).astype(np.int64)
+    bad = np.abs(e) > bound
+    while bad.any():
+        e[bad] = np.rint(g.normal(0.0, sigma, size=int(bad.sum()))).astype(np.int64)
+        bad = np.abs(e) > bound
+    return e
+
+
+def uniform_limbs(moduli, N, seed, *stream, lead=()):
+    """uint64 array [*lead][len(moduli)][N], limb i uniform on [0, moduli[i])."""
+    g = rng(seed, "uniform", *stream)
+    out = np.empty(tuple(lead) + (len(moduli), N), dtype=np.uint64)
+    for i, q in enumerate(moduli):
+        out[..., i, :] = g.integers(0, int(q), size=tuple(lead) + (N,), dtype=np.uint64)
+    return out
+
+
+def slots_complex(n_slots, seed, *stream, lo=-1.0, hi=1.0):
+    g = rng(seed, "slots", *stream)
+    return g.uniform(lo, hi, n_slots) + 1j * g.uniform(lo, hi, n_slots)
+
+
+def slots_real(n_slots, seed, *stream, lo=-1.0, hi=1.0):
+    return rng(seed, "slots", *stream).uniform(lo, hi, n_slots).astype(np.complex128)
+
+
+def weights_float(shape, seed, *stream, sigma=0.05):
+    return rng(seed, "weights", *stream).normal(0.0, sigma, size=shape)
+
+
+def rotation_offsets(n_slots, count, seed):
+    """`count` distinct slot offsets in [1, n_slots)."""
+    g = rng(seed, "rot")
+    return sorted(int(x) for x in g.choice(np.arange(1, n_slots), size=count, replace=False))

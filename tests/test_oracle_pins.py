@@ -1,0 +1,562 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+other than itself -- Python big-integer arithmetic, closed forms, brute force on
+tiny inputs, invariants of the scheme -- so that a dropped term, a wrong sign or
+index, or a transposed operand in the oracle fails at least one of them.
+CPU only."""
+import math
+import random
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_1911_11377_amd import workloads as wl
+from helpers import Material, poly_mul_negacyclic_int
+
+# (bits, logN of the workload shape the prime belongs to)
+SHAPE_PRIMES = [(40, 12), (41, 12), (50, 14), (51, 14), (50, 15), (50, 16), (51, 16)]
+
+
+# ---------------------------------------------------------------- arithmetic
+def test_modular_arithmetic_matches_python_ints():
+    rnd = random.Random(1)
+    L = orc.lib()
+    for _ in range(2000):
+        q = rnd.randrange(3, 1 << rnd.choice([20, 40, 51, 62, 64]))
+        a, b = rnd.randrange(q), rnd.randrange(q)
+        assert L.orc_mulmod(a, b, q) == a * b % q
+        assert L.orc_addmod(a, b, q) == (a + b) % q
+        assert L.orc_submod(a, b, q) == (a - b) % q
+        e = rnd.randrange(1 << 64)
+        assert L.orc_powmod(a, e, q) == pow(a, e, q)
+        v = rnd.randrange(-(1 << 63), 1 << 63)
+        assert L.orc_signed_mod(v, q) == v % q
+    assert L.orc_signed_mod(-(1 << 63), 1000003) == (-(1 << 63)) % 1000003
+
+
+def _lucas_certificate(q, logN):
+    """q is prime iff some g has g^(q-1) = 1 and g^((q-1)/r) != 1 for every prime r | q-1."""
+    m = (q - 1) >> (logN + 1)
+    fac = {2}
+    r = 2
+    while r * r <= m:
+        while m % r == 0:
+            fac.add(r)
+            m //= r
+        r += 1 if r == 2 else 2
+    if m > 1:
+        fac.add(m)
+    for g in range(2, 200):
+        if pow(g, q - 1, q) == 1 and all(pow(g, (q - 1) // r, q) != 1 for r in fac):
+            return True
+    return False
+
+
+@pytest.mark.parametrize("bits,logN", SHAPE_PRIMES)
+def test_prime_rule(bits, logN):
+    count = 4
+    ps = orc.find_primes(bits, logN, count)
+    twoN = 2 << logN
+    assert ps == sorted(ps, reverse=True) and len(set(ps)) == count
+    for q in ps:
+        assert (1 << (bits - 1)) < q < (1 << bits) and q % twoN == 1
+        assert _lucas_certificate(q, logN)
+    # nothing skipped: every candidate above the last prime that is not listed is composite
+    c = (1 << bits) - twoN + 1
+    while c > ps[-1]:
+        if c not in ps:
+            assert pow(2, c - 1, c) != 1 or not _lucas_certificate(c, logN)
+        c -= twoN
+    # exclusion list
+    assert orc.find_primes(bits, logN, 2, exclude=[ps[0]]) == ps[1:3]
+
+
+@pytest.mark.parametrize("bits,logN", SHAPE_PRIMES)
+def test_psi_rule(bits, logN):
+    q = orc.find_primes(bits, logN, 1)[0]
+    N = 1 << logN
+    psi = orc.find_psi(q, logN)
+    assert pow(psi, N, q) == q - 1 and pow(psi, 2 * N, q) == 1
+    x = 2
+    while True:
+        cand = pow(x, (q - 1) // (2 * N), q)
+        if pow(cand, N, q) == q - 1:
+            break
+        x += 1
+    assert cand == psi
+
+
+# ---------------------------------------------------------------- transform
+def test_direct_transform_is_polynomial_evaluation():
+    """definition vs Horner evaluation with Python ints, N = 8"""
+    logN, N = 3, 8
+    q = orc.find_primes(40, 12, 1)[0]
+    psi = pow(orc.find_psi(q, 12), (1 << 12) // N, q)
+    rnd = random.Random(2)
+    a = [rnd.randrange(q) for _ in range(N)]
+    got = orc.ntt_direct(a, logN, q, psi)
+    for j in range(N):
+        br = int(format(j, "03b")[::-1], 2)
+        x = pow(psi, 2 * br + 1, q)
+        assert int(got[j]) == sum(a[t] * pow(x, t, q) for t in range(N)) % q
+    assert [int(v) for v in orc.intt_direct(got, logN, q, psi)] == a
+
+
+@pytest.mark.parametrize("bits,shape_logN", SHAPE_PRIMES)
+@pytest.mark.parametrize("logN", [2, 5, 8])
+def test_fast_transform_matches_definition(bits, shape_logN, logN):
+    q = orc.find_primes(bits, shape_logN, 2)[1]
+    psi = pow(orc.find_psi(q, shape_logN), (1 << shape_logN) >> logN, q)
+    N = 1 << logN
+    a = wl.uniform_limbs([q], N, 3, bits, logN)[0]
+    f = orc.ntt(a, logN, q, psi)
+    assert np.array_equal(f, orc.ntt_direct(a, logN, q, psi))
+    assert np.array_equal(orc.intt(f, logN, q, psi), a)
+    assert np.array_equal(orc.intt_direct(f, logN, q, psi), a)
+
+
+def test_fast_transform_matches_definition_n1024():
+    logN = 10
+    q = orc.find_primes(50, 16, 1)[0]
+    psi = pow(orc.find_psi(q, 16), 1 << 6, q)
+    a = wl.uniform_limbs([q], 1 << logN, 4)[0]
+    assert np.array_equal(orc.ntt(a, logN, q, psi), orc.ntt_direct(a, logN, q, psi))
+
+
+def test_transform_closed_forms():
+    logN, N = 12, 1 << 12
+    q = orc.find_primes(40, logN, 1)[0]
+    psi = orc.find_psi(q, logN)
+    X = np.zeros(N, dtype=np.uint64)
+    X[1] = 1
+    want = [pow(psi, 2 * orc.brev(j, logN) + 1, q) for j in range(N)]
+    assert [int(v) for v in orc.ntt(X, logN, q, psi)] == want
+    c = np.zeros(N, dtype=np.uint64)
+    c[0] = 12345
+    assert (orc.ntt(c, logN, q, psi) == 12345).all()
+    # linearity
+    a = wl.uniform_limbs([q], N, 5, "a")[0]
+    b = wl.uniform_limbs([q], N, 5, "b")[0]
+    s = (a.astype(object) + b.astype(object)) % q
+    fa, fb = orc.ntt(a, logN, q, psi), orc.ntt(b, logN, q, psi)
+    assert np.array_equal(orc.ntt(s.astype(np.uint64), logN, q, psi), ((fa.astype(object) + fb.astype(object)) % q).astype(np.uint64))
+
+
+def test_schoolbook_is_the_ring_product():
+    """schoolbook negacyclic vs exact integer polynomial product, N = 16"""
+    logN, N = 4, 16
+    q = orc.find_primes(50, 14, 1)[0]
+    rnd = random.Random(6)
+    a = [rnd.randrange(q) for _ in range(N)]
+    b = [rnd.randrange(q) for _ in range(N)]
+    want = [v % q for v in poly_mul_negacyclic_int(a, b)]
+    assert [int(v) for v in orc.negacyclic_schoolbook(a, b, logN, q)] == want
+    # X^(N-1) * X = -1
+    x1 = [0] * N
+    x1[1] = 1
+    xl = [0] * N
+    xl[N - 1] = 1
+    r = orc.negacyclic_schoolbook(x1, xl, logN, q)
+    assert int(r[0]) == q - 1 and not r[1:].any()
+
+
+@pytest.mark.parametrize("bits,special", [(40, False), (41, True)])
+def test_convolution_theorem_at_tiny_shape_size(bits, special):
+    """iNTT(NTT(a) * NTT(b)) equals the schoolbook negacyclic product at N = 2^12."""
+    logN, N = 12, 1 << 12
+    q = orc.find_primes(bits, logN, 3)[2 if not special else 0]
+    psi = orc.find_psi(q, logN)
+    a = wl.uniform_limbs([q], N, 7, "a", bits)[0]
+    b = wl.uniform_limbs([q], N, 7, "b", bits)[0]
+    fa, fb = orc.ntt(a, logN, q, psi), orc.ntt(b, logN, q, psi)
+    prod = np.array([int(x) * int(y) % q for x, y in zip(fa, fb)], dtype=np.uint64)
+    assert np.array_equal(orc.intt(prod, logN, q, psi), orc.negacyclic_schoolbook(a, b, logN, q))
+
+
+# ---------------------------------------------------------------- RNS steps
+def _small_oracle(alpha=2, k=2, n_q=5, logN=4):
+    return orc.Oracle(logN, n_q, 20, k, 21, alpha)
+
+
+@pytest.mark.parametrize("alpha,k,n_q,level", [(1, 1, 3, 3), (2, 2, 5, 5), (2, 2, 5, 3), (3, 3, 7, 7), (3, 3, 7, 5)])
+def test_modup_is_d_plus_u_QD(alpha, k, n_q, level):
+    O = _small_oracle(alpha, k, n_q)
+    d = wl.uniform_limbs(O.q[:level], O.N, 8, alpha, level)
+    for j in range(O.beta(level)):
+        D = list(range(j * alpha, min(level, (j + 1) * alpha)))
+        out = O.modup(d, level, j)
+        QD = math.prod(O.q[i] for i in D)
+        dint = orc.crt_reconstruct(d[D], [O.q[i] for i in D], centered=False)
+        ext = O.ext_moduli(level)
+        for n in range(O.N):
+            # the integer the conversion represents, recomputed with big integers
+            v = sum(((int(d[i][n]) * pow(QD // O.q[i], -1, O.q[i])) % O.q[i]) * (QD // O.q[i]) for i in D)
+            u, rem = divmod(v - dint[n], QD)
+            assert rem == 0 and 0 <= u < len(D)
+            for x, t in enumerate(ext):
+                if x in D:
+                    assert int(out[x][n]) == int(d[x][n])
+                else:
+                    assert int(out[x][n]) == v % t
+
+
+@pytest.mark.parametrize("nb", [1, 2, 3])
+def test_divround_is_rounded_division(nb):
+    O = _small_oracle(alpha=nb, k=nb, n_q=4)
+    cidx = [0, 1, 2]
+    for bidx in ([O.n_q + m for m in range(nb)], [3] if nb == 1 else None):
+        if bidx is None:
+            continue
+        mods = [O.moduli[i] for i in cidx + bidx]
+        B = math.prod(O.moduli[i] for i in bidx)
+        h = B // 2
+        x = wl.uniform_limbs(mods, O.N, 9, nb, bidx[0])
+        xint = orc.crt_reconstruct(x, mods, centered=False)
+        out = O.divround_coef(x, cidx, bidx)
+        QC = math.prod(O.moduli[i] for i in cidx)
+        seen = set()
+        for n in range(O.N):
+            exact = (xint[n] + h) // B
+            cands = [u for u in range(nb) if all(int(out[i][n]) == (exact - u) % O.moduli[c] for i, c in enumerate(cidx))]
+            assert cands, "no u in [0,|B|-1] explains the output"
+            seen.add(cands[0])
+            if nb == 1:
+                assert cands == [0]
+                # exact round-to-nearest: |x/B - out| < 1/2 (B odd, no ties)
+                got = orc.crt_reconstruct(out[:, n : n + 1], [O.moduli[c] for c in cidx], centered=False)[0]
+                assert got == exact % QC and abs(xint[n] - exact * B) <= B // 2
+
+
+def test_switching_key_identity():
+    """b_j + a_j*s - e_j = [t in digit j] * (P mod t) * s' exactly, by schoolbook products."""
+    M = Material(4, 5, 20, 2, 21, 2, seed=10, rotations=(1,))
+    O = M.O
+    T = O.n_q + O.k
+    P = math.prod(O.p)
+    g = orc.galois_element(4, 1)
+    s_int = [int(v) for v in M.s]
+    s2 = poly_mul_negacyclic_int(s_int, s_int)
+    sg = [0] * O.N
+    for t in range(O.N):
+        i = (t * g) % (2 * O.N)
+        if i < O.N:
+            sg[i] = s_int[t]
+        else:
+            sg[i - O.N] = -s_int[t]
+    for key, sp, a_in in ((M.rlk, s2, M.rlk_a), (M.gk[1], sg, None)):
+        for j in range(O.beta_top):
+            for t in range(T):
+                q = O.moduli[t]
+                b = O.intt_limbs(key[j, 0, t : t + 1], [t])[0]
+                a = O.intt_limbs(key[j, 1, t : t + 1], [t])[0]
+                if a_in is not None:
+                    assert np.array_equal(key[j, 1, t], a_in[j, t])
+                as_ = orc.negacyclic_schoolbook(a, [v % q for v in s_int], 4, q)
+                lhs = [(int(b[n]) + int(as_[n])) % q for n in range(O.N)]
+                in_digit = t < O.n_q and t // O.alpha == j
+                if a_in is not None:
+                    e = M.rlk_e[j]
+                    want = [(int(e[n]) + (P % q) * sp[n] * in_digit) % q for n in range(O.N)]
+                    assert lhs == want
+                else:
+                    # error is small and centred; the gadget term is exact
+                    diff = [(lhs[n] - (P % q) * sp[n] * in_digit) % q for n in range(O.N)]
+                    assert all(min(v, q - v) <= 19 for v in diff)
+
+
+def test_tensor_identity():
+    """d0 + d1*s + d2*s^2 = (a0 + a1*s)(b0 + b1*s) exactly mod Q"""
+    M = Material(4, 4, 20, 2, 21, 2, seed=11)
+    O = M.O
+    level = 4
+    a = wl.uniform_limbs(O.q[:level], O.N, 11, "a", lead=(2,))
+    b = wl.uniform_limbs(O.q[:level], O.N, 11, "b", lead=(2,))
+    d = O.tensor(a, b, level)
+    Q = math.prod(O.q[:level])
+    ma, mb, md = M.decrypt_poly(a, level), M.decrypt_poly(b, level), M.decrypt_poly(d, level)
+    prod = poly_mul_negacyclic_int(ma, mb)
+    assert all((prod[n] - md[n]) % Q == 0 for n in range(O.N))
+    # and the decryption helper itself: c0 + c1*s by schoolbook
+    s_int = [int(v) for v in M.s]
+    for i in range(level):
+        q = O.q[i]
+        c0 = O.intt_limbs(a[0, i : i + 1], [i])[0]
+        c1 = O.intt_limbs(a[1, i : i + 1], [i])[0]
+        want = [(int(c0[n]) + int(v)) % q for n, v in enumerate(orc.negacyclic_schoolbook(c1, [x % q for x in s_int], 4, q))]
+        assert [x % q for x in ma] == want
+
+
+@pytest.mark.parametrize("alpha,k,n_q,level", [(1, 1, 3, 3), (2, 2, 5, 5), (2, 2, 5, 4), (3, 3, 7, 7), (3, 3, 7, 2)])
+def test_keyswitch_noise_is_small(alpha, k, n_q, level):
+    M = Material(4, n_q, 20, k, 21, alpha, seed=12)
+    O = M.O
+    d = wl.uniform_limbs(O.q[:level], O.N, 12, "d", level)
+    ks = O.keyswitch(d, M.rlk, level)
+    Q = math.prod(O.q[:level])
+    s_int = [int(v) for v in M.s]
+    s2 = poly_mul_negacyclic_int(s_int, s_int)
+    dint = orc.crt_reconstruct(O.intt_limbs(d, list(range(level))), O.q[:level])
+    want = poly_mul_negacyclic_int(dint, s2)
+    got = M.decrypt_poly(ks, level)
+    err = [((got[n] - want[n] + Q // 2) % Q) - Q // 2 for n in range(O.N)]
+    P = math.prod(O.p)
+    maxQD = max(math.prod(O.q[j * alpha : min(level, (j + 1) * alpha)]) for j in range(O.beta(level)))
+    bound = O.beta(level) * O.N * 19 * alpha * maxQD / P + (k + 0.5) * (1 + sum(abs(v) for v in s_int))
+    assert max(abs(e) for e in err) <= bound
+    assert max(abs(e) for e in err) < 2**12
+
+
+def test_rescale_divides_message_by_last_prime():
+    M = Material(4, 4, 20, 1, 21, 1, seed=13)
+    O = M.O
+    level = 4
+    ct = wl.uniform_limbs(O.q[:level], O.N, 13, "ct", lead=(2,))
+    out = O.rescale(ct, level)
+    ql = O.q[level - 1]
+    Qn = math.prod(O.q[: level - 1])
+    for c in range(2):
+        xin = orc.crt_reconstruct(O.intt_limbs(ct[c], list(range(level))), O.q[:level], centered=False)
+        xo = orc.crt_reconstruct(O.intt_limbs(out[c], list(range(level - 1))), O.q[: level - 1], centered=False)
+        for n in range(O.N):
+            assert xo[n] == ((xin[n] + ql // 2) // ql) % Qn
+
+
+# ---------------------------------------------------------------- encoding
+def test_encode_closed_forms_and_direct_definition():
+    logN, N = 5, 32
+    scale = 2.0**30
+    c = orc.encode(np.full(N // 2, 0.75 + 0j), scale, logN)
+    assert c[0] == round(0.75 * scale) and not any(c[1:])
+    zeta = np.exp(1j * np.pi / N)
+    z = np.array([zeta**e for e in orc.slot_exponents(logN)])
+    c = orc.encode(z, scale, logN)
+    assert c[1] == round(scale) and not any(c[:1] + c[2:])
+    z = wl.slots_complex(N // 2, 14)
+    assert orc.encode(z, scale, logN) == orc.encode_direct(z, scale, logN)
+    back = orc.decode(orc.encode(z, scale, logN), scale, logN)
+    assert np.max(np.abs(back - z)) < N / scale
+    assert np.max(np.abs(orc.decode_direct(orc.encode(z, scale, logN), scale, logN) - back)) < 1e-9
+    # slot k sits at zeta^(5^k): conjugate-symmetric values give real coefficients by construction,
+    # and rotating the slot vector left by one equals the automorphism X -> X^5 on coefficients
+    m = orc.encode(z, scale, logN)
+    rot = [0] * N
+    for t in range(N):
+        i = (t * 5) % (2 * N)
+        if i < N:
+            rot[i] = m[t]
+        else:
+            rot[i - N] = -m[t]
+    assert np.max(np.abs(orc.decode(rot, scale, logN) - np.roll(z, -1))) < N / scale
+
+
+# ---------------------------------------------------------------- encryption
+def test_encryption_noise_is_exactly_r_e_plus_e0_plus_e1_s():
+    M = Material(4, 3, 20, 1, 21, 1, seed=15)
+    O = M.O
+    level = 3
+    z = wl.slots_complex(O.N // 2, 15)
+    scale = 2.0**30
+    m = orc.encode(z, scale, 4)
+    pt = O.ntt_limbs(orc.to_rns(m, O.q[:level]), list(range(level)))
+    r = wl.ternary(O.N, 15, "r")
+    e0 = wl.gaussian_error(O.N, 15, "e0")
+    e1 = wl.gaussian_error(O.N, 15, "e1")
+    ct = O.encrypt(M.pk, pt, r, e0, e1, level)
+    e = wl.gaussian_error(O.N, 15, "pk.e")  # the draw Material used for the public key
+    s_int = [int(v) for v in M.s]
+    noise = poly_mul_negacyclic_int([int(v) for v in r], [int(v) for v in e])
+    e1s = poly_mul_negacyclic_int([int(v) for v in e1], s_int)
+    want = [m[n] + noise[n] + int(e0[n]) + e1s[n] for n in range(O.N)]
+    assert M.decrypt_poly(ct, level) == want
+
+
+def test_decrypt_encrypt_roundtrip_config_sizes():
+    """decrypt(encrypt(m)) recovers m within 1e-6 at scale 2^40 (N = 2^12 here)."""
+    M = Material(12, 3, 50, 1, 51, 1, seed=16)
+    z = wl.slots_complex(M.N // 2, 16)
+    ct = M.encrypt(z, 2.0**40, 3, "x")
+    assert np.max(np.abs(M.decrypt(ct, 2.0**40, 3) - z)) < 1e-6
+
+
+# ---------------------------------------------------------------- end to end
+def test_hmul_relin_rescale_decrypts_to_product_tiny_shape():
+    """the tiny workload shape: N=2^12, 3x40-bit + 41-bit special, scale 2^30 -> 1e-2 (output scale ~2^20)"""
+    p = wl.PRESETS["tiny"]
+    M = Material(p.logN, p.n_q, p.q_bits, p.k, p.special_bits, p.alpha, seed=1)
+    scale = 2.0**p.log_scale
+    za, zb = wl.slots_complex(M.N // 2, 1, "a"), wl.slots_complex(M.N // 2, 1, "b")
+    a, b = M.encrypt(za, scale, 3, "a"), M.encrypt(zb, scale, 3, "b")
+    out = M.O.hmul_relin_rescale(a, b, M.rlk, 3)
+    got = M.decrypt(out, scale * scale / M.O.q[2], 2)
+    assert np.max(np.abs(got - za * zb)) < 1e-2
+    # the composite is the strict sequence
+    seq = M.O.rescale(M.O.relin(M.O.tensor(a, b, 3), M.rlk, 3), 3)
+    assert np.array_equal(seq, out)
+
+
+def test_hmul_at_scale_2e40_within_1e3():
+    M = Material(11, 4, 50, 1, 51, 1, seed=17)
+    scale = 2.0**40
+    za, zb = wl.slots_real(M.N // 2, 17, "a"), wl.slots_real(M.N // 2, 17, "b")
+    a, b = M.encrypt(za, scale, 4, "a"), M.encrypt(zb, scale, 4, "b")
+    out = M.O.hmul_relin_rescale(a, b, M.rlk, 4)
+    got = M.decrypt(out, scale * scale / M.O.q[3], 3)
+    assert np.max(np.abs(got - za * zb)) < 1e-3
+    assert np.max(np.abs(got - za * zb)) < 1e-5  # expected size of the error at this N
+
+
+def test_hybrid_keyswitch_alpha3_end_to_end():
+    M = Material(8, 6, 50, 3, 51, 3, seed=18, rotations=(3,))
+    scale = 2.0**50
+    za, zb = wl.slots_real(M.N // 2, 18, "a"), wl.slots_real(M.N // 2, 18, "b")
+    for level in (6, 5, 4):
+        a, b = M.encrypt(za, scale, level, "a"), M.encrypt(zb, scale, level, "b")
+        out = M.O.hmul_relin_rescale(a, b, M.rlk, level)
+        got = M.decrypt(out, scale * scale / M.O.q[level - 1], level - 1)
+        assert np.max(np.abs(got - za * zb)) < 1e-6
+    r = M.O.rotate(a, 3, M.gk[3], 4)
+    assert np.max(np.abs(M.decrypt(r, scale, 4) - np.roll(za, -3))) < 1e-6
+
+
+def test_rotation_permutation_formula_and_direction():
+    M = Material(6, 3, 30, 1, 31, 1, seed=19, rotations=(1, 5))
+    O = M.O
+    for r in (1, 5):
+        g = orc.galois_element(6, r)
+        assert g == pow(5, r, 2 * O.N)
+        for t in range(3):
+            a = wl.uniform_limbs([O.q[t]], O.N, 19, r, t)[0]
+            via_coef = O.ntt_limbs(O.automorphism_coef(O.intt_limbs(a[None], [t])[0], g, t)[None], [t])[0]
+            assert np.array_equal(O.automorphism_eval(a, g), via_coef)
+        z = wl.slots_complex(O.N // 2, 19, r)
+        ct = M.encrypt(z, 2.0**25, 3, r)
+        out = O.rotate(ct, r, M.gk[r], 3)
+        assert np.max(np.abs(M.decrypt(out, 2.0**25, 3) - np.roll(z, -r))) < 1e-3
+
+
+def test_elementwise_ops_on_decrypted_polynomials():
+    M = Material(5, 3, 30, 1, 31, 1, seed=20)
+    O = M.O
+    level = 3
+    Q = math.prod(O.q[:level])
+    a = wl.uniform_limbs(O.q[:level], O.N, 20, "a", lead=(2,))
+    b = wl.uniform_limbs(O.q[:level], O.N, 20, "b", lead=(2,))
+    ma, mb = M.decrypt_poly(a, level), M.decrypt_poly(b, level)
+    eq = lambda x, y: all((u - v) % Q == 0 for u, v in zip(x, y))
+    assert eq(M.decrypt_poly(O.add(a, b, level), level), [u + v for u, v in zip(ma, mb)])
+    assert eq(M.decrypt_poly(O.sub(a, b, level), level), [u - v for u, v in zip(ma, mb)])
+    assert eq(M.decrypt_poly(O.mul_scalar(a, -12345678901, level), level), [-12345678901 * u for u in ma])
+    assert eq(M.decrypt_poly(O.add_const(a, -77, level), level), [ma[0] - 77] + ma[1:])
+    pt_coef = [int(v) for v in wl.gaussian_error(O.N, 20, "pt")]
+    pt = O.ntt_limbs(orc.to_rns(pt_coef, O.q[:level]), list(range(level)))
+    assert eq(M.decrypt_poly(O.mul_plain(a, pt, level), level), poly_mul_negacyclic_int(ma, pt_coef))
+    dropped = O.mod_drop(a, 3, 2)
+    assert np.array_equal(dropped, a[:, :2])
+
+
+def _conv_reference(x, w, stride, pad):
+    C_, H, W = x.shape[:3]
+    O_, _, kh, kw = w.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    out = np.zeros((O_, Ho, Wo) + x.shape[3:], dtype=x.dtype)
+    for o in range(O_):
+        for y in range(Ho):
+            for xx in range(Wo):
+                for c in range(C_):
+                    for u in range(kh):
+                        for v in range(kw):
+                            iy, ix = y * stride + u - pad, xx * stride + v - pad
+                            if 0 <= iy < H and 0 <= ix < W:
+                                out[o, y, xx] = out[o, y, xx] + w[o, c, u, v] * x[c, iy, ix]
+    return out
+
+
+@pytest.mark.parametrize("stride,pad", [(2, 0), (1, 1)])
+def test_conv_mac_is_linear_in_decrypted_polynomials(stride, pad):
+    M = Material(4, 3, 30, 1, 31, 1, seed=21)
+    O = M.O
+    level = 3
+    Q = math.prod(O.q[:level])
+    Cc, H, W, Oc, kh = 2, 5, 5, 3, 3
+    x = wl.uniform_limbs(O.q[:level], O.N, 21, "x", lead=(Cc, H, W, 2))
+    w = wl.rng(21, "w").integers(-(2**29), 2**29, size=(Oc, Cc, kh, kh), dtype=np.int64)
+    out = O.conv2d_mac(x, w, stride, pad, level)
+    mx = np.array([[[M.decrypt_poly(x[c, y, xx], level) for xx in range(W)] for y in range(H)] for c in range(Cc)], dtype=object)
+    want = _conv_reference(mx, w.astype(object), stride, pad)
+    assert out.shape[:3] == want.shape[:3]
+    for o in range(out.shape[0]):
+        for y in range(out.shape[1]):
+            for xx in range(out.shape[2]):
+                got = M.decrypt_poly(out[o, y, xx], level)
+                assert all((int(g) - int(v)) % Q == 0 for g, v in zip(got, want[o, y, xx]))
+    # FC = flat 1x1 case
+    f = x[:, 0, 0]
+    wf = w[:, :, 0, 0]
+    fc = O.fc_mac(f, wf, level)
+    for o in range(Oc):
+        got = M.decrypt_poly(fc[o], level)
+        want_o = [sum(int(wf[o, c]) * mx[c, 0, 0][n] for c in range(Cc)) for n in range(O.N)]
+        assert all((g - v) % Q == 0 for g, v in zip(got, want_o))
+
+
+def test_conv_layer_decrypts_to_float_convolution():
+    """slots-as-batch conv + rescale vs a float convolution of the slot values"""
+    M = Material(6, 3, 40, 0, 41, 1, seed=22)
+    O = M.O
+    level = 3
+    scale = 2.0**30
+    Cc, H, W, Oc, kh, stride = 2, 6, 6, 2, 3, 2
+    imgs = wl.rng(22, "img").uniform(0, 1, size=(Cc, H, W, O.N // 2))
+    x = np.array([[[M.encrypt(imgs[c, y, xx].astype(np.complex128), scale, level, (c, y, xx)) for xx in range(W)] for y in range(H)] for c in range(Cc)])
+    wf = wl.weights_float((Oc, Cc, kh, kh), 22)
+    wi = np.rint(wf * O.q[level - 1]).astype(np.int64)
+    out = O.conv2d_mac(x, wi, stride, 0, level)
+    want = _conv_reference(imgs, wf, stride, 0)
+    for o in range(Oc):
+        for y in range(out.shape[1]):
+            for xx in range(out.shape[2]):
+                got = M.decrypt(O.rescale(out[o, y, xx], level), scale, level - 1)
+                assert np.max(np.abs(got.real - want[o, y, xx])) < 1e-3
+
+
+def test_activation_schedules_match_float_polynomials():
+    M = Material(8, 6, 50, 3, 51, 3, seed=23)
+    O = M.O
+    level = 6
+    s = 2.0**50
+    z = wl.slots_real(O.N // 2, 23)
+    x = M.encrypt(z, s, level, "x")
+    y = O.square(x, M.rlk, level)  # level 5
+    s_y = s * s / O.q[5]
+    assert np.max(np.abs(M.decrypt(y, s_y, 5) - z * z)) < 1e-6
+    s_2 = s_y * s_y / O.q[4]
+    s_3 = s_2 * s_y / O.q[3]
+    c_m002 = round(-0.02 * O.q[4])
+    c_025 = round(0.25 * s_2)
+    c_05 = round(0.5 * s_3)
+    out = O.poly3(y, M.rlk, 5, c_m002, c_025, c_05)
+    yv = (z * z).real
+    want = 0.5 + 0.25 * yv - 0.02 * yv**3
+    assert np.max(np.abs(M.decrypt(out, s_3, 3).real - want)) < 1e-5
+
+
+def test_paper_degree2_activation_polynomial():
+    """the degree-2 ReLU substitute printed in the paper's section 3.1, coefficients from tests/golden"""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "activation_poly_deg2.txt")
+    vals = [float(l.split()[1]) for l in open(path) if l.strip() and not l.startswith("#")]
+    c2, c1 = vals
+    M = Material(8, 4, 50, 1, 51, 1, seed=24)
+    O = M.O
+    level = 4
+    s = 2.0**40
+    z = wl.slots_real(O.N // 2, 24, lo=-4.0, hi=4.0)
+    x = M.encrypt(z, s, level, "x")
+    # c2*x^2: RS(Relin(x*x)) then scalar (scale q_2 so the rescale restores the scale); c1*x likewise
+    x2 = O.square(x, M.rlk, level)
+    s2 = s * s / O.q[3]
+    t2 = O.rescale(O.mul_scalar(x2, round(c2 * O.q[2]), 3), 3)  # level 2, scale s2
+    t1 = O.rescale(O.mul_scalar(O.mod_drop(x, 4, 3), round(c1 * s2 / s * O.q[2]), 3), 3)  # level 2, scale s2
+    out = O.add(t2, t1, 2)
+    want = c2 * z.real**2 + c1 * z.real
+    assert np.max(np.abs(M.decrypt(out, s2, 2).real - want)) < 1e-4
