@@ -1,0 +1,204 @@
+/*
+ * ckksmi.h -- C ABI of the MI355X-native RNS-CKKS ciphertext-arithmetic library.
+ *
+ * What it is for: the cloud side of encrypted CNN inference as the paper poses it
+ * (abstract, section 1): the client encodes and encrypts, the server evaluates
+ * convolution / polynomial-activation / fully-connected layers on ciphertexts,
+ * the client decrypts.  The scheme is CKKS (paper section 2.1), used as a leveled
+ * scheme without bootstrapping (section 2.1, first paragraph), in its RNS form.
+ *
+ * Conventions
+ *   - Plain C, every function returns int: 0 = CKKSMI_OK, negative = error code
+ *     below.  Nothing throws across the boundary.  Arguments are validated on the
+ *     host before anything is enqueued; a failed call enqueues nothing.
+ *   - Ring R = Z[X]/(X^N+1), N = 2^logN.  Moduli: ciphertext primes q_0..q_{n_q-1}
+ *     then special primes p_0..p_{k-1}; "modulus index" t runs over that list.
+ *     Every prime is < 2^51 and = 1 mod 2N.
+ *   - word  = one residue, uint64_t, canonical representative in [0, modulus).
+ *     limb  = N words.  A polynomial at `level` l is [l][N] (limb i mod q_i).
+ *     A ciphertext is [2][l][N]; a degree-2 ciphertext (tensor output) [3][l][N];
+ *     a batch is a dense array of those, batch index outermost.
+ *   - Unless stated otherwise polynomials are in EVALUATION form: word j of limb i
+ *     is the polynomial evaluated at psi_i^(2*brev(j)+1) mod q_i, brev = logN-bit
+ *     reversal, psi_i the primitive 2N-th root reported by ckksmi_get_moduli.
+ *   - Decryption convention of the paper (section 2.1): m ~ c0 + c1*s.
+ *   - "host" pointers are ordinary memory; "device" pointers are HIP device
+ *     memory on the context's GPU.  The library never allocates ciphertext or
+ *     workspace memory: the caller passes device buffers and a hipStream_t (as
+ *     void*; NULL = the default stream).  Device calls enqueue on that stream and
+ *     return without synchronising.  The context owns only its constant tables.
+ *   - Scale is caller-side metadata; level and batch are explicit arguments.
+ *   - A context created with device = -1 is host-only: the host functions work,
+ *     every device function returns CKKSMI_EDEVICE.  There is no CPU fallback for
+ *     the device functions.
+ */
+#ifndef CKKSMI_H
+#define CKKSMI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CKKSMI_OK 0
+#define CKKSMI_EINVAL (-1)       /* null pointer, bad shape or parameter */
+#define CKKSMI_ELEVEL (-2)       /* level out of range for the operation */
+#define CKKSMI_ENOKEY (-3)       /* no Galois key registered for that rotation */
+#define CKKSMI_EWORKSPACE (-4)   /* workspace too small for even one item */
+#define CKKSMI_EDEVICE (-5)      /* HIP error (see ckksmi_last_device_error) or host-only context */
+#define CKKSMI_EUNSUPPORTED (-6) /* valid request this build does not implement */
+
+typedef struct ckksmi_ctx ckksmi_ctx;
+
+typedef struct {
+    int logN;         /* 2 .. 17 */
+    int n_q;          /* number of ciphertext primes (fresh level), 1 .. 62 */
+    int q_bits;       /* 2^(q_bits-1) < q_i < 2^q_bits, q_bits <= 51 */
+    int n_special;    /* k, 0 .. 4; 0 disables key switching */
+    int special_bits; /* <= 51 */
+    int alpha;        /* ciphertext primes per key-switch digit, 1 .. 4 and <= max(k,1) */
+    const uint64_t *moduli_override; /* optional: n_q + k primes to use instead of the search rule */
+    const uint64_t *psi_override;    /* optional with moduli_override: their 2N-th roots */
+    int device;       /* HIP device ordinal, or -1 for a host-only context */
+} ckksmi_params;
+
+/* operations for ckksmi_workspace_bytes */
+#define CKKSMI_OP_RELIN 1
+#define CKKSMI_OP_RESCALE 2
+#define CKKSMI_OP_HMUL_RELIN_RESCALE 3
+#define CKKSMI_OP_ROTATE 4
+#define CKKSMI_OP_CONV2D_MAC 5 /* `batch` = number of weights O*C*kh*kw (or O*F) */
+
+/* ------------------------------------------------------------------ context */
+/* Primes: the n_q largest q_bits-bit primes = 1 mod 2N in descending order, then
+ * the k largest special_bits-bit ones (skipping any already taken); psi_t = x^((p-1)/2N)
+ * for the first x = 2,3,.. whose power has order exactly 2N. */
+int ckksmi_ctx_create(const ckksmi_params *params, ckksmi_ctx **out);
+void ckksmi_ctx_destroy(ckksmi_ctx *ctx);
+/* moduli, psi: host arrays of n_q + k words (either may be NULL) */
+int ckksmi_get_moduli(const ckksmi_ctx *ctx, uint64_t *moduli, uint64_t *psi);
+const char *ckksmi_strerror(int code);
+/* last hipError_t seen by this context (0 = none) */
+int ckksmi_last_device_error(const ckksmi_ctx *ctx);
+
+/* ------------------------------------------------------------------ host side
+ * All pointers are host pointers.  Randomness is an input: the samplers below
+ * draw it from a seed, keygen/encrypt consume explicit polynomials, so that the
+ * same draws can be given to any other implementation.  Paper section 2.1. */
+
+/* i.i.d. uniform {-1,0,1} */
+int ckksmi_sample_ternary(const ckksmi_ctx *ctx, uint64_t seed, int64_t *out /*[N]*/);
+/* round(N(0, 3.2^2)) redrawn while |e| > 19 */
+int ckksmi_sample_error(const ckksmi_ctx *ctx, uint64_t seed, int64_t *out /*[N]*/);
+/* limb x uniform on [0, modulus[index[x]]) */
+int ckksmi_sample_uniform(const ckksmi_ctx *ctx, uint64_t seed, const int *index, int n_limbs, uint64_t *out /*[n_limbs][N]*/);
+
+/* m = round(scale * phi^-1(z)), z_k = re[k] + i*im[k] (im may be NULL) for the
+ * N/2 slots, slot k evaluated at zeta^(5^k), zeta = exp(i*pi/N); written as a
+ * plaintext at `level` in evaluation form. */
+int ckksmi_encode(const ckksmi_ctx *ctx, const double *re, const double *im, double scale, int level, uint64_t *pt /*[level][N]*/);
+/* inverse of the above on a decrypted polynomial (evaluation form): CRT to the
+ * centred representative, then z_k = m(zeta^(5^k)) / scale. */
+int ckksmi_decode(const ckksmi_ctx *ctx, const uint64_t *pt /*[level][N]*/, int level, double scale, double *re /*[N/2]*/, double *im /*[N/2] or NULL*/);
+
+/* pk = (b = -a*s + e, a) over q_0..q_{n_q-1}; a in evaluation form. */
+int ckksmi_keygen_public(const ckksmi_ctx *ctx, const int64_t *s /*[N]*/, const uint64_t *a /*[n_q][N]*/, const int64_t *e /*[N]*/, uint64_t *pk /*[2][n_q][N]*/);
+/* Switching keys, layout [beta][2][n_q+k][N], beta = ceil(n_q/alpha):
+ *   key[j][1][t] = a[j][t]
+ *   key[j][0][t] = -a[j][t]*s + e[j] + [t = q_i, i in digit j]*(P mod q_i)*s'
+ * digit j = {j*alpha .. min(n_q,(j+1)*alpha)-1}, P = product of special primes.
+ * relin: s' = s^2.  galois: s' = s(X^g), g = 5^rot mod 2N (left rotation by rot slots). */
+int ckksmi_keygen_relin(const ckksmi_ctx *ctx, const int64_t *s, const uint64_t *a /*[beta][n_q+k][N]*/, const int64_t *e /*[beta][N]*/, uint64_t *evk);
+int ckksmi_keygen_galois(const ckksmi_ctx *ctx, const int64_t *s, int rot, const uint64_t *a, const int64_t *e, uint64_t *gk);
+/* ct = (r*b + e0 + m, r*a + e1) on the first `level` limbs */
+int ckksmi_encrypt(const ckksmi_ctx *ctx, const uint64_t *pk, const uint64_t *pt /*[level][N]*/, const int64_t *r, const int64_t *e0, const int64_t *e1, int level, uint64_t *ct /*[2][level][N]*/);
+/* pt = c0 + c1*s (+ c2*s^2 when n_comp = 3), evaluation form */
+int ckksmi_decrypt(const ckksmi_ctx *ctx, const int64_t *s, const uint64_t *ct, int level, int n_comp, uint64_t *pt /*[level][N]*/);
+
+/* ------------------------------------------------------------------ device side
+ * All data pointers are device pointers unless marked host.  `batch` = number of
+ * ciphertexts.  In-place use (out == input) is allowed where noted. */
+
+/* Remember the device address of the Galois key for left rotation by `rot` slots
+ * (the key memory stays the caller's and must outlive its use). */
+int ckksmi_galois_key_register(ckksmi_ctx *ctx, int rot, const uint64_t *gk_dev);
+
+/* Forward / inverse negacyclic transform of n_limbs*batch limbs laid out
+ * [batch][n_limbs][N]; limb x uses modulus index index[x] (host array).  In place.
+ * forward: coefficient (natural) order -> evaluation order; inverse includes 1/N. */
+int ckksmi_ntt(ckksmi_ctx *ctx, uint64_t *limbs, const int *index, int n_limbs, int batch, void *stream);
+int ckksmi_intt(ckksmi_ctx *ctx, uint64_t *limbs, const int *index, int n_limbs, int batch, void *stream);
+
+/* limb-wise ciphertext operations (paper section 2.1: addition of ciphertexts);
+ * out may alias an input */
+int ckksmi_add(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, uint64_t *out, int level, int batch, void *stream);
+int ckksmi_sub(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, uint64_t *out, int level, int batch, void *stream);
+/* both components times a plaintext [level][N]; pt_stride = words between the
+ * plaintexts of consecutive items, 0 = one plaintext for the whole batch */
+int ckksmi_mul_plain(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *pt, size_t pt_stride, uint64_t *out, int level, int batch, void *stream);
+/* every word times the signed constant c (reduced mod each q_i) */
+int ckksmi_mul_scalar(ckksmi_ctx *ctx, const uint64_t *a, int64_t c, uint64_t *out, int level, int batch, void *stream);
+/* add the constant polynomial c to component 0 (every slot += c/scale) */
+int ckksmi_add_const(ckksmi_ctx *ctx, const uint64_t *a, int64_t c, uint64_t *out, int level, int batch, void *stream);
+/* keep the first level_out limbs of each component; out must not alias a */
+int ckksmi_mod_drop(ckksmi_ctx *ctx, const uint64_t *a, int level_in, int level_out, uint64_t *out, int batch, void *stream);
+
+/* ct x ct tensor: d = (a0*b0, a0*b1 + a1*b0, a1*b1), [3][level][N] per item */
+int ckksmi_hmul(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, uint64_t *d, int level, int batch, void *stream);
+/* out = (d0 + ks0, d1 + ks1), ks = KeySwitch(d2) with evk (hybrid: ModUp per
+ * digit, inner product with the key, ModDown = divide by P with rounding) */
+int ckksmi_relin(ckksmi_ctx *ctx, const uint64_t *d, const uint64_t *evk, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* divide by q_{level-1} with rounding to nearest: level -> level-1.  out may alias a
+ * only when batch == 1 */
+int ckksmi_rescale(ckksmi_ctx *ctx, const uint64_t *a, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* the strict sequence hmul -> relin -> rescale, bit-identical to the three calls */
+int ckksmi_hmul_relin_rescale(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out /*[2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* left rotation of item i by rot[i] slots (host array; each needs a registered
+ * key): automorphism X -> X^g first, then key switch of the second component */
+int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [batch]*/, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+
+/* Convolution / fully-connected layers of the paper's network (Table 1) over
+ * per-pixel ciphertexts (slot s = image s), integer plaintext weights (device,
+ * int64): out[o,y,x] = sum_{c,u,v} w[o,c,u,v] * in[c, y*stride+u-pad, x*stride+v-pad],
+ * taps outside the image skipped; out at the same level (rescale separately).
+ * in: [C][H][W] ciphertexts, out: [O][Ho][Wo], Ho = (H+2*pad-kh)/stride+1. */
+int ckksmi_conv2d_mac(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride, int pad, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
+/* in: [F] ciphertexts, w: [O][F], out: [O] ciphertexts */
+int ckksmi_fc_mac(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int F, int O, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
+
+/* bytes of workspace that lets `op` process the whole batch in one sweep; with
+ * less (but at least one item's worth, else CKKSMI_EWORKSPACE) the call splits
+ * the batch into several sweeps. */
+int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, size_t *bytes);
+
+/* ------------------------------------------------------------------ measurement
+ * Per-kernel timing for roofline reports: while enabled, every kernel launch is
+ * bracketed by two HIP events recorded on the launch stream.  ckksmi_profile_enable
+ * also discards what was recorded so far.  ckksmi_profile_read waits for the recorded
+ * events of one kernel class and returns their summed duration, the number of
+ * launches and the summed units of work (limbs for the transforms and limb-wise
+ * kernels).  Not thread-safe; meant for benchmarks. */
+#define CKKSMI_K_NTT_FWD_COL 0 /* forward transform, strided first pass */
+#define CKKSMI_K_NTT_FWD_ROW 1 /* forward transform, contiguous pass */
+#define CKKSMI_K_NTT_INV_ROW 2
+#define CKKSMI_K_NTT_INV_COL 3
+#define CKKSMI_K_TENSOR 4
+#define CKKSMI_K_MODUP 5
+#define CKKSMI_K_INNER 6
+#define CKKSMI_K_DIVCONV 7
+#define CKKSMI_K_DIVFINAL 8
+#define CKKSMI_K_AUTOMORPH 9
+#define CKKSMI_K_MACPREP 10
+#define CKKSMI_K_MAC 11
+#define CKKSMI_K_ELEMWISE 12
+#define CKKSMI_K_COUNT 13
+int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
+int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
+const char *ckksmi_kernel_class_name(int kernel_class);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

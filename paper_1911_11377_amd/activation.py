@@ -1,0 +1,64 @@
+"""Polynomial activations as sequences of library calls (argument marshalling only).
+
+The paper replaces every non-linear activation by a low-degree polynomial (section 2.2
+and the degree-2 polynomial of section 3.1).  Two schedules are provided:
+  square : y = RS(Relin(x*x))                                          level l -> l-1
+  poly3  : 0.5 + 0.25*y - 0.02*y^3 for y at level l, scale s_y          level l -> l-2
+             y2 = RS(Relin(y*y))                       level l-1, scale s_2 = s_y^2/q_{l-1}
+             t  = RS(y * round(-0.02*q_{l-1}))         level l-1, scale s_y
+             y3 = RS(Relin(y2*t))                      level l-2, scale s_3 = s_2*s_y/q_{l-2}
+             u  = RS(drop(y -> l-1) * round(0.25*s_2)) level l-2, scale s_y*s_2/q_{l-2} = s_3
+             out = y3 + u + round(0.5*s_3)
+The integer constants depend only on the moduli and the tracked scale.
+"""
+from dataclasses import dataclass
+
+from . import ckksmi
+
+
+@dataclass(frozen=True)
+class Poly3Constants:
+    c_m002: int
+    c_025: int
+    c_05: int
+    out_scale: float
+
+
+def poly3_constants(q, level, s_y):
+    """q: list of ciphertext primes, level: level of y, s_y: its scale"""
+    s_2 = s_y * s_y / q[level - 1]
+    s_3 = s_2 * s_y / q[level - 2]
+    return Poly3Constants(round(-0.02 * q[level - 1]), round(0.25 * s_2), round(0.5 * s_3), s_3)
+
+
+def workspace_bytes(ctx, level, batch):
+    n = ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch)
+    return n + 8 * batch * 2 * ctx.N * (4 * level)
+
+
+def _carve(ws, words):
+    """split a flat int64 torch tensor: first `words` elements, rest"""
+    return ws[:words], ws[words:]
+
+
+def square(ctx, x, evk, y, level, batch, ws, stream=None):
+    ctx.hmul_relin_rescale(x, x, evk, y, level, batch, ws, stream=stream)
+
+
+def poly3(ctx, y, evk, out, level, batch, consts, ws, stream=None):
+    ct = batch * 2 * ctx.N
+    y2, ws = _carve(ws, ct * (level - 1))
+    t_full, ws = _carve(ws, ct * level)
+    t, ws = _carve(ws, ct * (level - 1))
+    y3 = out
+    ctx.hmul_relin_rescale(y, y, evk, y2, level, batch, ws, stream=stream)
+    ctx.mul_scalar(y, consts.c_m002, t_full, level, batch, stream=stream)
+    ctx.rescale(t_full, t, level, batch, ws, stream=stream)
+    ctx.hmul_relin_rescale(y2, t, evk, y3, level - 1, batch, ws, stream=stream)
+    yd, rest = _carve(t_full, ct * (level - 1))  # t_full is free again
+    ctx.mod_drop(y, level, level - 1, yd, batch, stream=stream)
+    ctx.mul_scalar(yd, consts.c_025, yd, level - 1, batch, stream=stream)
+    u = y2[: ct * (level - 2)]                   # y2 is free again
+    ctx.rescale(yd, u, level - 1, batch, ws, stream=stream)
+    ctx.add(y3, u, out, level - 2, batch, stream=stream)
+    ctx.add_const(out, consts.c_05, out, level - 2, batch, stream=stream)

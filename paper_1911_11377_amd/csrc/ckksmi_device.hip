@@ -1,0 +1,631 @@
+// Device side of the C ABI: constant-table upload, argument validation and the
+// kernel launch sequences of every ciphertext operation.
+#ifndef CKKSMI_EMULATE
+#include <hip/hip_runtime.h>
+#define CKKSMI_LAUNCH(kern, grid, block, stream, ...) hipLaunchKernelGGL(kern, grid, block, 0, stream, __VA_ARGS__)
+#endif
+
+#include <algorithm>
+#include <cstring>
+
+#include "ckksmi_internal.h"
+#include "kernels.h"
+
+// Launch `kern`; when profiling is on, bracket it with two events on the same stream and
+// remember them under kernel class `kid` together with `units` of algorithmic work.
+#define KL(c, kid, units, kern, grid, block, st, ...)                                   \
+    do {                                                                                \
+        ProfRec *pr_ = (c)->prof_on ? prof_begin((c), (kid), (double)(units), (st)) : nullptr; \
+        CKKSMI_LAUNCH(kern, grid, block, st, __VA_ARGS__);                              \
+        if (pr_) (void)hipEventRecord((hipEvent_t)pr_->stop, (st));                     \
+    } while (0)
+
+namespace {
+
+ProfRec *prof_begin(ckksmi_ctx *c, int kid, double units, hipStream_t st) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return nullptr;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return nullptr; }
+    (void)hipEventRecord(a, st);
+    c->prof.push_back(ProfRec{kid, units, (void *)a, (void *)b});
+    return &c->prof.back();
+}
+
+struct Guard {  // records the first HIP error of a call
+    ckksmi_ctx *c;
+    bool ok = true;
+    explicit Guard(ckksmi_ctx *ctx) : c(ctx) {}
+    void check(hipError_t e) {
+        if (e != hipSuccess && ok) { ok = false; c->last_hip_error = (int)e; }
+    }
+    int rc() {
+        check(hipGetLastError());
+        return ok ? CKKSMI_OK : CKKSMI_EDEVICE;
+    }
+};
+
+template <class Tp>
+Tp *upload(ckksmi_ctx *c, const Tp *host, size_t count, bool &ok) {
+    void *p = nullptr;
+    const size_t bytes = count ? count * sizeof(Tp) : 16;
+    if (hipMalloc(&p, bytes) != hipSuccess) { ok = false; return nullptr; }
+    c->dev_allocs.push_back(p);
+    if (count && hipMemcpy(p, host, count * sizeof(Tp), hipMemcpyHostToDevice) != hipSuccess) ok = false;
+    return (Tp *)p;
+}
+
+inline int la_for(int logN) { return logN <= 12 ? 0 : std::min(8, logN - 8); }
+
+inline bool dev_ok(const ckksmi_ctx *c) { return c && c->device >= 0; }
+inline hipStream_t S(void *s) { return (hipStream_t)s; }
+
+LimbMap table_map(const int *index, int n_limbs, size_t src_stride, size_t dst_stride) {
+    LimbMap M;
+    memset(&M, 0, sizeof(M));
+    M.per_item = n_limbs;
+    M.mode = 0;
+    M.src_item_stride = src_stride;
+    M.dst_item_stride = dst_stride;
+    for (int i = 0; i < n_limbs; i++) M.modidx[i] = (unsigned char)index[i];
+    return M;
+}
+
+// transform `items` groups of map.per_item limbs; forward: coefficient -> evaluation
+void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const LimbMap &M, size_t items, hipStream_t st) {
+    if (items == 0 || M.per_item == 0) return;
+    NttArgs A;
+    A.src = (const u64d *)src;
+    A.dst = (u64d *)dst;
+    A.modc = c->d_mod;
+    A.tw = forward ? c->d_tw_fwd : c->d_tw_inv;
+    A.tw_last = c->d_tw_inv_last;
+    A.logN = c->logN;
+    A.LA = la_for(c->logN);
+    A.map = M;
+    const unsigned N = 1u << c->logN, N1 = 1u << A.LA, N2 = N >> A.LA;
+    const unsigned R = N2 >= NTT_TILE ? 1u : NTT_TILE / N2;
+    const unsigned limbs = (unsigned)(items * M.per_item);
+    // limbs actually transformed (the key-switch map skips the limbs of each digit itself)
+    const double limbs_work = M.mode == 1 ? (double)items * ((double)M.per_item - M.level) : (double)limbs;
+    dim3 grow(limbs, (N1 + R - 1) / R), gcol(limbs, N2 / NTT_TC);
+    if (forward) {
+        if (A.LA) {
+            KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, ntt_fwd_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
+            // second pass works in place on dst
+            A.src = (const u64d *)dst;
+            A.map.src_item_stride = A.map.dst_item_stride;
+        }
+        KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, ntt_fwd_kernel<false>, grow, dim3(NTT_THREADS), st, A);
+    } else {
+        KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
+        if (A.LA) {
+            A.src = (const u64d *)dst;
+            A.map.src_item_stride = A.map.dst_item_stride;
+            KL(c, CKKSMI_K_NTT_INV_COL, limbs_work, ntt_inv_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
+        }
+    }
+}
+
+inline unsigned ew_blocks(size_t total) { return (unsigned)((total + EW_THREADS - 1) / EW_THREADS); }
+
+ScalarTab scalar_tab(const ckksmi_ctx *c, int64_t v, int level) {
+    ScalarTab Sx;
+    memset(&Sx, 0, sizeof(Sx));
+    for (int i = 0; i < level; i++) {
+        u64 r = hm::signed_mod(v, c->mod[i]);
+        Sx.c[i] = make_wmul(r, c->mod[i]);
+        Sx.cpos[i] = (double)r;
+    }
+    return Sx;
+}
+
+// words of workspace one item needs
+size_t ks_words_per_item(const ckksmi_ctx *c, int level) {
+    const size_t N = c->N, E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    return N * ((size_t)level + beta * E + 2 * E + 2 * (size_t)level);
+}
+size_t rescale_words_per_item(const ckksmi_ctx *c, int level) { return c->N * (2 + 2 * (size_t)(level - 1)); }
+
+// Key switch of `items` polynomials.  d_eval: item i's polynomial ([level][N], evaluation
+// form) at d_eval + i*d_stride.  out[i][c][l] = ks_c (+ addend).  ws: ks_words_per_item*items.
+void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
+             size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st) {
+    const size_t N = c->N;
+    const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    u64 *dcoef = ws;
+    u64 *dt = dcoef + (size_t)items * level * N;
+    u64 *acc = dt + (size_t)items * beta * E * N;
+    u64 *tmp = acc + (size_t)items * 2 * E * N;
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < level; i++) idx[i] = i;
+    // 1. d -> coefficient form
+    launch_ntt(c, false, d_eval, dcoef, table_map(idx, level, d_stride, (size_t)level * N), items, st);
+    // 2. ModUp every digit
+    ModUpArgs MU;
+    MU.d_coef = (const u64d *)dcoef;
+    MU.d_eval = (const u64d *)d_eval;
+    MU.d_eval_item_stride = d_stride;
+    MU.out = (u64d *)dt;
+    MU.modc = c->d_mod;
+    MU.inv = c->d_modup_inv;
+    MU.cc = c->d_modup_c;
+    MU.logN = c->logN; MU.level = level; MU.E = E; MU.n_q = c->n_q; MU.alpha = c->alpha; MU.beta = beta; MU.T = c->T;
+    KL(c, CKKSMI_K_MODUP, (double)items * beta * E, modup_kernel, dim3(ew_blocks(N), beta, items), dim3(EW_THREADS), st, MU);
+    // 3. converted limbs -> evaluation form (limbs of the digit itself were copied as such)
+    LimbMap M1;
+    memset(&M1, 0, sizeof(M1));
+    M1.per_item = beta * E; M1.mode = 1; M1.level = level; M1.E = E; M1.n_q = c->n_q; M1.alpha = c->alpha;
+    M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
+    launch_ntt(c, true, dt, dt, M1, items, st);
+    // 4. inner product with the key
+    InnerArgs IA;
+    IA.dt = (const u64d *)dt; IA.acc = (u64d *)acc; IA.modc = c->d_mod;
+    IA.logN = c->logN; IA.level = level; IA.E = E; IA.n_q = c->n_q; IA.beta = beta; IA.T = c->T;
+    KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, items), dim3(EW_THREADS), st, IA, K);
+    // 5. ModDown: special limbs -> coefficient form, convert, back to evaluation form, combine
+    int sidx[CKKSMI_MAX_SPECIAL];
+    for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
+    launch_ntt(c, false, acc + (size_t)level * N, acc + (size_t)level * N, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N),
+               (size_t)items * 2, st);
+    DivConvArgs DC;
+    DC.b_limbs = (const u64d *)(acc + (size_t)level * N);
+    DC.b_row_stride = (size_t)E * N;
+    DC.tmp = (u64d *)tmp;
+    DC.modc = c->d_mod;
+    DC.D = c->divround[0];
+    DC.logN = c->logN; DC.nc = level; DC.T = c->T;
+    KL(c, CKKSMI_K_DIVCONV, (double)items * 2 * DC.nc, divround_conv_kernel, dim3(ew_blocks(N), items * 2), dim3(EW_THREADS), st, DC);
+    launch_ntt(c, true, tmp, tmp, table_map(idx, level, (size_t)level * N, (size_t)level * N), (size_t)items * 2, st);
+    DivFinalArgs DF;
+    DF.x = (const u64d *)acc; DF.x_row_stride = (size_t)E * N;
+    DF.tmp = (const u64d *)tmp;
+    DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride;
+    DF.add_both = add_both;
+    DF.out = (u64d *)out;
+    DF.modc = c->d_mod; DF.Binv = c->divround[0].Binv;
+    DF.logN = c->logN; DF.nc = level;
+    KL(c, CKKSMI_K_DIVFINAL, (double)items * 2 * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level, items * 2), dim3(EW_THREADS), st, DF);
+}
+
+// out[i] = DivRound_{q_{level-1}}(a[i]); ws: rescale_words_per_item*items
+void rescale_core(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u64 *ws, hipStream_t st) {
+    const size_t N = c->N;
+    u64 *last = ws;
+    u64 *tmp = last + (size_t)items * 2 * N;
+    int lidx[1] = {level - 1};
+    launch_ntt(c, false, a + (size_t)(level - 1) * N, last, table_map(lidx, 1, (size_t)level * N, N), (size_t)items * 2, st);
+    DivConvArgs DC;
+    DC.b_limbs = (const u64d *)last; DC.b_row_stride = N;
+    DC.tmp = (u64d *)tmp; DC.modc = c->d_mod;
+    DC.D = c->divround[1 + (level - 1)];
+    DC.logN = c->logN; DC.nc = level - 1; DC.T = c->T;
+    KL(c, CKKSMI_K_DIVCONV, (double)items * 2 * DC.nc, divround_conv_kernel, dim3(ew_blocks(N), items * 2), dim3(EW_THREADS), st, DC);
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < level - 1; i++) idx[i] = i;
+    launch_ntt(c, true, tmp, tmp, table_map(idx, level - 1, (size_t)(level - 1) * N, (size_t)(level - 1) * N), (size_t)items * 2, st);
+    DivFinalArgs DF;
+    DF.x = (const u64d *)a; DF.x_row_stride = (size_t)level * N;
+    DF.tmp = (const u64d *)tmp;
+    DF.addend = nullptr; DF.add_item_stride = DF.add_comp_stride = 0; DF.add_both = 0;
+    DF.out = (u64d *)out;
+    DF.modc = c->d_mod; DF.Binv = c->divround[1 + (level - 1)].Binv;
+    DF.logN = c->logN; DF.nc = level - 1;
+    KL(c, CKKSMI_K_DIVFINAL, (double)items * 2 * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level - 1, items * 2), dim3(EW_THREADS), st, DF);
+}
+
+void launch_tensor(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, int level, int items, hipStream_t st) {
+    const size_t total = (size_t)items * level * c->N;
+    KL(c, CKKSMI_K_TENSOR, (double)items * level, tensor_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)a, (const u64d *)b, (u64d *)d, c->d_mod,
+                  c->logN, level, total);
+}
+
+int sweep_items(size_t ws_bytes, size_t words_per_item, int batch) {
+    size_t fit = ws_bytes / 8 / words_per_item;
+    if (fit > (size_t)batch) fit = batch;
+    if (fit > CKKSMI_MAX_ITEMS) fit = CKKSMI_MAX_ITEMS;
+    return (int)fit;
+}
+
+u64 galois_element_of(const ckksmi_ctx *c, int rot) {
+    const i64 half = (i64)(c->N / 2);
+    i64 r = ((i64)rot % half + half) % half;
+    return hm::powmod(5, (u64)r, 2 * c->N);
+}
+int norm_rot(const ckksmi_ctx *c, int rot) {
+    const i64 half = (i64)(c->N / 2);
+    return (int)(((i64)rot % half + half) % half);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ tables
+int dev_upload_tables(ckksmi_ctx *c) {
+    if (hipSetDevice(c->device) != hipSuccess) return CKKSMI_EDEVICE;
+    bool ok = true;
+    const size_t N = c->N;
+    const int T = c->T;
+    c->d_mod = upload(c, c->h_modc, T, ok);
+    std::vector<WMul> fwd((size_t)T * N), inv((size_t)T * N), last(T);
+    for (int t = 0; t < T; t++) {
+        const u64 q = c->mod[t];
+        for (size_t x = 0; x < N; x++) {
+            fwd[(size_t)t * N + x] = make_wmul(c->h_fwd[t][x], q);
+            inv[(size_t)t * N + x] = make_wmul(c->h_inv[t][x], q);
+        }
+        inv[(size_t)t * N] = make_wmul(c->h_ninv[t], q);
+        last[t] = make_wmul(hm::mulmod(c->h_inv[t][1], c->h_ninv[t], q), q);
+    }
+    c->d_tw_fwd = upload(c, fwd.data(), fwd.size(), ok);
+    c->d_tw_inv = upload(c, inv.data(), inv.size(), ok);
+    c->d_tw_inv_last = upload(c, last.data(), last.size(), ok);
+    if (c->k > 0) {
+        std::vector<WMul> mi, mc;
+        make_modup_tables(c, mi, mc);
+        c->d_modup_inv = upload(c, mi.data(), mi.size(), ok);
+        c->d_modup_c = upload(c, mc.data(), mc.size(), ok);
+    }
+    // DivRound tables: 0 = ModDown over the special primes, 1+i = rescale dropping q_i
+    c->divround.assign(1 + c->n_q, DivRoundDev());
+    for (int which = 0; which <= c->n_q; which++) {
+        std::vector<int> b;
+        if (which == 0) {
+            for (int m = 0; m < c->k; m++) b.push_back(c->n_q + m);
+            if (b.empty()) { memset(&c->divround[0], 0, sizeof(DivRoundDev)); continue; }
+        } else {
+            b.push_back(which - 1);
+        }
+        DivRoundHost h = make_divround(c, b);
+        DivRoundDev d;
+        memset(&d, 0, sizeof(d));
+        d.nb = h.nb;
+        for (int m = 0; m < h.nb; m++) { d.b_idx[m] = h.b_idx[m]; d.hb[m] = h.hb[m]; d.invb[m] = h.invb[m]; }
+        d.conv = upload(c, h.conv.data(), h.conv.size(), ok);
+        d.hc = upload(c, h.hc.data(), h.hc.size(), ok);
+        d.Binv = upload(c, h.Binv.data(), h.Binv.size(), ok);
+        c->divround[which] = d;
+    }
+    if (!ok) { c->last_hip_error = (int)hipGetLastError(); return CKKSMI_EDEVICE; }
+    return CKKSMI_OK;
+}
+
+void dev_free_tables(ckksmi_ctx *c) {
+    for (ProfRec &r : c->prof) { (void)hipEventDestroy((hipEvent_t)r.start); (void)hipEventDestroy((hipEvent_t)r.stop); }
+    c->prof.clear();
+    for (void *p : c->dev_allocs) (void)hipFree(p);
+    c->dev_allocs.clear();
+}
+
+// ------------------------------------------------------------------ C ABI, device side
+extern "C" int ckksmi_galois_key_register(ckksmi_ctx *c, int rot, const uint64_t *gk_dev) {
+    if (!c || !gk_dev) return CKKSMI_EINVAL;
+    if (c->k == 0) return CKKSMI_EUNSUPPORTED;
+    const int r = norm_rot(c, rot);
+    for (auto &e : c->galois)
+        if (e.first == r) { e.second = gk_dev; return CKKSMI_OK; }
+    c->galois.push_back(std::make_pair(r, (const u64 *)gk_dev));
+    return CKKSMI_OK;
+}
+
+static int ntt_api(ckksmi_ctx *c, bool fwd, uint64_t *limbs, const int *index, int n_limbs, int batch, void *stream) {
+    if (!c || !limbs || !index || n_limbs < 1 || n_limbs > CKKSMI_MAX_MODULI || batch < 0) return CKKSMI_EINVAL;
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    for (int i = 0; i < n_limbs; i++)
+        if (index[i] < 0 || index[i] >= c->T) return CKKSMI_EINVAL;
+    if ((size_t)batch * n_limbs > 0x7fffffffu) return CKKSMI_EINVAL;
+    Guard g(c);
+    const size_t stride = (size_t)n_limbs * c->N;
+    launch_ntt(c, fwd, limbs, limbs, table_map(index, n_limbs, stride, stride), batch, S(stream));
+    return g.rc();
+}
+extern "C" int ckksmi_ntt(ckksmi_ctx *c, uint64_t *limbs, const int *index, int n_limbs, int batch, void *stream) {
+    return ntt_api(c, true, limbs, index, n_limbs, batch, stream);
+}
+extern "C" int ckksmi_intt(ckksmi_ctx *c, uint64_t *limbs, const int *index, int n_limbs, int batch, void *stream) {
+    return ntt_api(c, false, limbs, index, n_limbs, batch, stream);
+}
+
+static int ct_args_ok(const ckksmi_ctx *c, int level, int batch) {
+    if (!c || batch < 0) return CKKSMI_EINVAL;
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
+    if ((size_t)batch * 3 * level * c->N / EW_THREADS > 0x7fffffffu) return CKKSMI_EINVAL;
+    return CKKSMI_OK;
+}
+
+static int addsub_api(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, uint64_t *out, int level, int batch, void *stream, int sub) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!a || !b || !out) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    Guard g(c);
+    const size_t total = (size_t)batch * 2 * level * c->N;
+    KL(c, CKKSMI_K_ELEMWISE, (double)batch * 2 * level, addsub_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)a, (const u64d *)b, (u64d *)out,
+                  c->d_mod, c->logN, level, total, sub);
+    return g.rc();
+}
+extern "C" int ckksmi_add(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, uint64_t *out, int level, int batch, void *stream) {
+    return addsub_api(c, a, b, out, level, batch, stream, 0);
+}
+extern "C" int ckksmi_sub(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, uint64_t *out, int level, int batch, void *stream) {
+    return addsub_api(c, a, b, out, level, batch, stream, 1);
+}
+
+extern "C" int ckksmi_mul_plain(ckksmi_ctx *c, const uint64_t *a, const uint64_t *pt, size_t pt_stride, uint64_t *out, int level,
+                                int batch, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!a || !pt || !out) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    Guard g(c);
+    const size_t total = (size_t)batch * 2 * level * c->N;
+    KL(c, CKKSMI_K_ELEMWISE, (double)batch * 2 * level, mul_plain_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)a, (const u64d *)pt, pt_stride,
+                  (u64d *)out, c->d_mod, c->logN, level, total);
+    return g.rc();
+}
+
+extern "C" int ckksmi_mul_scalar(ckksmi_ctx *c, const uint64_t *a, int64_t v, uint64_t *out, int level, int batch, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!a || !out) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    Guard g(c);
+    const size_t total = (size_t)batch * 2 * level * c->N;
+    KL(c, CKKSMI_K_ELEMWISE, (double)batch * 2 * level, mul_scalar_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)a, (u64d *)out, c->d_mod,
+                  scalar_tab(c, v, level), c->logN, level, total);
+    return g.rc();
+}
+
+extern "C" int ckksmi_add_const(ckksmi_ctx *c, const uint64_t *a, int64_t v, uint64_t *out, int level, int batch, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!a || !out) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    Guard g(c);
+    const size_t total = (size_t)batch * 2 * level * c->N;
+    KL(c, CKKSMI_K_ELEMWISE, (double)batch * 2 * level, add_const_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)a, (u64d *)out, c->d_mod,
+                  scalar_tab(c, v, level), c->logN, level, total);
+    return g.rc();
+}
+
+extern "C" int ckksmi_mod_drop(ckksmi_ctx *c, const uint64_t *a, int level_in, int level_out, uint64_t *out, int batch, void *stream) {
+    int rc = ct_args_ok(c, level_in, batch);
+    if (rc) return rc;
+    if (level_out < 1 || level_out > level_in) return CKKSMI_ELEVEL;
+    if (!a || !out || a == out) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    Guard g(c);
+    const size_t total = (size_t)batch * 2 * level_out * c->N;
+    KL(c, CKKSMI_K_ELEMWISE, (double)batch * 2 * level_out, mod_drop_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)a, (u64d *)out, c->logN, level_in,
+                  level_out, total);
+    return g.rc();
+}
+
+extern "C" int ckksmi_hmul(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, uint64_t *d, int level, int batch, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!a || !b || !d) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    Guard g(c);
+    launch_tensor(c, a, b, d, level, batch, S(stream));
+    return g.rc();
+}
+
+extern "C" int ckksmi_workspace_bytes(const ckksmi_ctx *c, int op, int level, int batch, size_t *bytes) {
+    if (!c || !bytes || batch < 0) return CKKSMI_EINVAL;
+    if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
+    const size_t N = c->N;
+    size_t per = 0;
+    switch (op) {
+        case CKKSMI_OP_RELIN: per = ks_words_per_item(c, level); break;
+        case CKKSMI_OP_RESCALE:
+            if (level < 2) return CKKSMI_ELEVEL;
+            per = rescale_words_per_item(c, level);
+            break;
+        case CKKSMI_OP_HMUL_RELIN_RESCALE:
+            if (level < 2) return CKKSMI_ELEVEL;
+            per = 5 * (size_t)level * N + std::max(ks_words_per_item(c, level), rescale_words_per_item(c, level));
+            break;
+        case CKKSMI_OP_ROTATE: per = 2 * (size_t)level * N + ks_words_per_item(c, level); break;
+        case CKKSMI_OP_CONV2D_MAC:
+            *bytes = (size_t)batch * level * sizeof(WMul);
+            return CKKSMI_OK;
+        default: return CKKSMI_EINVAL;
+    }
+    if ((op == CKKSMI_OP_RELIN || op == CKKSMI_OP_HMUL_RELIN_RESCALE || op == CKKSMI_OP_ROTATE) && c->k == 0) return CKKSMI_EUNSUPPORTED;
+    *bytes = per * 8 * (size_t)batch;
+    return CKKSMI_OK;
+}
+
+extern "C" int ckksmi_relin(ckksmi_ctx *c, const uint64_t *d, const uint64_t *evk, uint64_t *out, int level, int batch, void *ws,
+                            size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (c->k == 0) return CKKSMI_EUNSUPPORTED;
+    if (!d || !evk || !out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N, per = ks_words_per_item(c, level);
+    const int chunk = sweep_items(ws_bytes, per, batch);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    KeyTab K;
+    memset(&K, 0, sizeof(K));
+    K.key[0] = (const u64d *)evk;
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        const u64 *di = d + (size_t)b0 * 3 * level * N;
+        ks_core(c, di + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, di, (size_t)3 * level * N, (size_t)level * N, 1,
+                out + (size_t)b0 * 2 * level * N, (u64 *)ws, S(stream));
+    }
+    return g.rc();
+}
+
+extern "C" int ckksmi_rescale(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes,
+                              void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (level < 2) return CKKSMI_ELEVEL;
+    if (!a || !out || a == out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N, per = rescale_words_per_item(c, level);
+    const int chunk = sweep_items(ws_bytes, per, batch);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        rescale_core(c, a + (size_t)b0 * 2 * level * N, out + (size_t)b0 * 2 * (level - 1) * N, items, level, (u64 *)ws, S(stream));
+    }
+    return g.rc();
+}
+
+extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level,
+                                         int batch, void *ws, size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (c->k == 0) return CKKSMI_EUNSUPPORTED;
+    if (level < 2) return CKKSMI_ELEVEL;
+    if (!a || !b || !evk || !out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N;
+    const size_t per = 5 * (size_t)level * N + std::max(ks_words_per_item(c, level), rescale_words_per_item(c, level));
+    const int chunk = sweep_items(ws_bytes, per, batch);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    KeyTab K;
+    memset(&K, 0, sizeof(K));
+    K.key[0] = (const u64d *)evk;
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        u64 *d = (u64 *)ws;                              // [items][3][level][N]
+        u64 *r = d + (size_t)items * 3 * level * N;      // [items][2][level][N]
+        u64 *rest = r + (size_t)items * 2 * level * N;
+        launch_tensor(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, level, items, S(stream));
+        ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r, rest,
+                S(stream));
+        rescale_core(c, r, out + (size_t)b0 * 2 * (level - 1) * N, items, level, rest, S(stream));
+    }
+    return g.rc();
+}
+
+extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, uint64_t *out, int level, int batch, void *ws,
+                             size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (c->k == 0) return CKKSMI_EUNSUPPORTED;
+    if (!a || !rot || !out || a == out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    // every rotation needs its key before anything is enqueued
+    std::vector<int> key_of(batch);
+    for (int i = 0; i < batch; i++) {
+        const int r = norm_rot(c, rot[i]);
+        int found = -1;
+        for (size_t e = 0; e < c->galois.size(); e++)
+            if (c->galois[e].first == r) found = (int)e;
+        if (found < 0) return CKKSMI_ENOKEY;
+        key_of[i] = found;
+    }
+    const size_t N = c->N;
+    const size_t per = 2 * (size_t)level * N + ks_words_per_item(c, level);
+    const int chunk = sweep_items(ws_bytes, per, batch);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    int b0 = 0;
+    while (b0 < batch) {
+        // longest run from b0 that fits the sweep and addresses at most CKKSMI_MAX_KEYS distinct keys
+        KeyTab K;
+        GaloisTab G;
+        memset(&K, 0, sizeof(K));
+        memset(&G, 0, sizeof(G));
+        int used[CKKSMI_MAX_KEYS], n_used = 0, items = 0;
+        while (b0 + items < batch && items < chunk) {
+            const int kidx = key_of[b0 + items];
+            int slot = -1;
+            for (int u = 0; u < n_used; u++)
+                if (used[u] == kidx) slot = u;
+            if (slot < 0) {
+                if (n_used == CKKSMI_MAX_KEYS) break;
+                slot = n_used;
+                used[n_used++] = kidx;
+                K.key[slot] = (const u64d *)c->galois[kidx].second;
+            }
+            K.slot[items] = (unsigned char)slot;
+            G.g[items] = (unsigned)galois_element_of(c, rot[b0 + items]);
+            items++;
+        }
+        u64 *sig = (u64 *)ws;  // [items][2][level][N]
+        u64 *rest = sig + (size_t)items * 2 * level * N;
+        const size_t total = (size_t)items * 2 * level * N;
+        KL(c, CKKSMI_K_AUTOMORPH, (double)items * 2 * level, automorphism_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)(a + (size_t)b0 * 2 * level * N),
+                      (u64d *)sig, G, c->logN, 2 * level, total);
+        ks_core(c, sig + (size_t)level * N, (size_t)2 * level * N, K, items, level, sig, (size_t)2 * level * N, 0, 0,
+                out + (size_t)b0 * 2 * level * N, rest, S(stream));
+        b0 += items;
+    }
+    return g.rc();
+}
+
+extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride,
+                                 int pad, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream) {
+    if (!c) return CKKSMI_EINVAL;
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
+    if (!in || !w || !out || !ws || in == out) return CKKSMI_EINVAL;
+    if (C < 1 || H < 1 || W < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0) return CKKSMI_EINVAL;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return CKKSMI_EINVAL;
+    const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    const size_t n_weights = (size_t)O * C * kh * kw;
+    if (ws_bytes < n_weights * level * sizeof(WMul)) return CKKSMI_EWORKSPACE;
+    const size_t zdim = (size_t)Ho * Wo * ((O + MAC_OC - 1) / MAC_OC);
+    if (zdim > 65535 || 2 * level > 65535) return CKKSMI_EUNSUPPORTED;
+    Guard g(c);
+    KL(c, CKKSMI_K_MACPREP, 1, mac_prepare_kernel, dim3(ew_blocks(n_weights * level)), dim3(EW_THREADS), S(stream), (const long long *)w, (WMul *)ws,
+                  c->d_mod, level, n_weights);
+    MacArgs A;
+    A.in = (const u64d *)in; A.out = (u64d *)out; A.wtab = (const WMul *)ws; A.modc = c->d_mod;
+    A.logN = c->logN; A.level = level;
+    A.C = C; A.H = H; A.W = W; A.O = O; A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.Ho = Ho; A.Wo = Wo;
+    KL(c, CKKSMI_K_MAC, (double)O * Ho * Wo * 2 * level, conv_mac_kernel, dim3(ew_blocks(c->N), 2 * level, (unsigned)zdim), dim3(EW_THREADS), S(stream), A);
+    return g.rc();
+}
+
+extern "C" int ckksmi_fc_mac(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int F, int O, uint64_t *out, int level, void *ws,
+                             size_t ws_bytes, void *stream) {
+    return ckksmi_conv2d_mac(c, in, w, F, 1, 1, O, 1, 1, 1, 0, out, level, ws, ws_bytes, stream);
+}
+
+// ------------------------------------------------------------------ per-kernel timing
+extern "C" int ckksmi_profile_enable(ckksmi_ctx *c, int on) {
+    if (!c) return CKKSMI_EINVAL;
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    for (ProfRec &r : c->prof) { (void)hipEventDestroy((hipEvent_t)r.start); (void)hipEventDestroy((hipEvent_t)r.stop); }
+    c->prof.clear();
+    c->prof_on = on != 0;
+    return CKKSMI_OK;
+}
+
+extern "C" int ckksmi_profile_read(ckksmi_ctx *c, int kernel_class, double *total_ms, long long *launches, double *units) {
+    if (!c || kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return CKKSMI_EINVAL;
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    double ms = 0, u = 0;
+    long long n = 0;
+    for (ProfRec &r : c->prof) {
+        if (r.kid != kernel_class) continue;
+        if (hipEventSynchronize((hipEvent_t)r.stop) != hipSuccess) return CKKSMI_EDEVICE;
+        float dt = 0;
+        if (hipEventElapsedTime(&dt, (hipEvent_t)r.start, (hipEvent_t)r.stop) != hipSuccess) return CKKSMI_EDEVICE;
+        ms += dt;
+        u += r.units;
+        n++;
+    }
+    if (total_ms) *total_ms = ms;
+    if (launches) *launches = n;
+    if (units) *units = u;
+    return CKKSMI_OK;
+}
+
+extern "C" const char *ckksmi_kernel_class_name(int kernel_class) {
+    static const char *names[CKKSMI_K_COUNT] = {"ntt_fwd_kernel<true>", "ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_inv_kernel<true>",
+                                                "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
+                                                "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
+                                                "elementwise kernels"};
+    return (kernel_class >= 0 && kernel_class < CKKSMI_K_COUNT) ? names[kernel_class] : "";
+}

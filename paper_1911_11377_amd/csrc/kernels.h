@@ -1,0 +1,529 @@
+// HIP kernels of the RNS-CKKS hot path (gfx950).  All modular arithmetic runs on the
+// FP64 vector ALU (device_arith.h); words in HBM are canonical uint64 residues.
+#pragma once
+#include "device_arith.h"
+
+typedef unsigned long long u64d;
+
+#define NTT_THREADS 256
+#define NTT_TILE 4096   // doubles staged in LDS per workgroup (32 KiB)
+#define NTT_TC 16       // contiguous words per row segment in the strided (column) pass
+
+// How the limb handled by blockIdx.x maps to memory and to a modulus.
+//   limb = item * per_item + li;  address = base + item * item_stride + li * N
+//   mode 0: modulus index = modidx[li]
+//   mode 1: key-switch extended basis: li = j*E + x, modulus = x < level ? x : n_q + x - level,
+//           and the limb is skipped when x belongs to digit j (it is already in evaluation form)
+struct LimbMap {
+    int per_item;
+    int mode;
+    int level, E, n_q, alpha;
+    unsigned long long src_item_stride, dst_item_stride;
+    unsigned char modidx[CKKSMI_MAX_MODULI];
+};
+
+struct NttArgs {
+    const u64d *src;
+    u64d *dst;
+    const ModConst *modc;
+    const WMul *tw;       // [T][N]
+    const WMul *tw_last;  // [T] inverse only: psi^-brev(1) / N
+    int logN, LA;         // LA = stages done by the strided pass (0 = none)
+    LimbMap map;
+};
+
+__device__ __forceinline__ int resolve_limb(const LimbMap &M, unsigned limb, unsigned &item, unsigned &li) {
+    item = limb / (unsigned)M.per_item;
+    li = limb % (unsigned)M.per_item;
+    if (M.mode == 0) return M.modidx[li];
+    unsigned j = li / (unsigned)M.E, x = li % (unsigned)M.E;
+    if ((int)x < M.level) return ((int)(x / (unsigned)M.alpha) == (int)j) ? -1 : (int)x;
+    return M.n_q + (int)x - M.level;
+}
+
+// ---------------------------------------------------------------- forward transform
+// Decimation in time with the negacyclic twist merged into the twiddles: stage s has
+// m = 2^s blocks of span N/(2m); block i multiplies its upper half by psi^brev(m+i).
+// COL = true : stages [0, LA) on a strided tile (2^LA rows x NTT_TC columns)
+// COL = false: stages [LA, logN) on contiguous rows of N2 = N >> LA words
+template <bool COL>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_kernel(NttArgs A) {
+    __shared__ double tile[NTT_TILE];
+    unsigned item, li;
+    const int t = resolve_limb(A.map, blockIdx.x, item, li);
+    if (t < 0) return;
+    const unsigned N = 1u << A.logN;
+    const u64d *src = A.src + (size_t)item * A.map.src_item_stride + (size_t)li * N;
+    u64d *dst = A.dst + (size_t)item * A.map.dst_item_stride + (size_t)li * N;
+    const double p = A.modc[t].p, pinv = A.modc[t].pinv;
+    const WMul *tw = A.tw + (size_t)t * N;
+    const unsigned tid = threadIdx.x;
+    if (COL) {
+        const unsigned N1 = 1u << A.LA, N2 = N >> A.LA;
+        const unsigned c0 = blockIdx.y * NTT_TC;
+        for (unsigned e = tid; e < N1 * NTT_TC; e += NTT_THREADS) {
+            unsigned r = e / NTT_TC, c = e % NTT_TC;
+            tile[e] = u2d(src[(size_t)r * N2 + c0 + c]);
+        }
+        __syncthreads();
+        for (int s = 0; s < A.LA; s++) {
+            const unsigned m = 1u << s, tr = N1 >> (s + 1);
+            const bool red = (s & 1) != 0;
+            for (unsigned b = tid; b < (N1 / 2) * NTT_TC; b += NTT_THREADS) {
+                unsigned c = b % NTT_TC, rb = b / NTT_TC;
+                unsigned i = rb / tr, jr = rb % tr;
+                unsigned lo = (i * 2 * tr + jr) * NTT_TC + c, hi = lo + tr * NTT_TC;
+                WMul W = tw[m + i];
+                double x = tile[lo], v = mulmod_w(tile[hi], W.w, W.wp, p);
+                double X = x + v, Y = x - v;
+                if (red) { X = reduce_balanced(X, p, pinv); Y = reduce_balanced(Y, p, pinv); }
+                tile[lo] = X;
+                tile[hi] = Y;
+            }
+            __syncthreads();
+        }
+        for (unsigned e = tid; e < N1 * NTT_TC; e += NTT_THREADS) {
+            unsigned r = e / NTT_TC, c = e % NTT_TC;
+            dst[(size_t)r * N2 + c0 + c] = d2u(canon(tile[e], p, pinv));
+        }
+    } else {
+        const unsigned N2 = N >> A.LA, N1 = 1u << A.LA;
+        const unsigned R = (N2 >= NTT_TILE) ? 1u : NTT_TILE / N2;  // rows per workgroup
+        const unsigned rows_here = (N1 - blockIdx.y * R < R) ? N1 - blockIdx.y * R : R;
+        const unsigned row0 = blockIdx.y * R;
+        const unsigned cnt = rows_here * N2;
+        const size_t g0 = (size_t)row0 * N2;
+        for (unsigned e = tid; e < cnt; e += NTT_THREADS) tile[e] = u2d(src[g0 + e]);
+        __syncthreads();
+        const int LB = A.logN - A.LA;
+        for (int s = 0; s < LB; s++) {
+            const unsigned mp = 1u << s, tt = N2 >> (s + 1);
+            const bool red = (s & 1) != 0;
+            for (unsigned b = tid; b < cnt / 2; b += NTT_THREADS) {
+                unsigned rr = b / (N2 / 2), bb = b % (N2 / 2);
+                unsigned i = bb / tt, j = bb % tt;
+                unsigned lo = rr * N2 + i * 2 * tt + j, hi = lo + tt;
+                WMul W = tw[mp * (N1 + row0 + rr) + i];
+                double x = tile[lo], v = mulmod_w(tile[hi], W.w, W.wp, p);
+                double X = x + v, Y = x - v;
+                if (red) { X = reduce_balanced(X, p, pinv); Y = reduce_balanced(Y, p, pinv); }
+                tile[lo] = X;
+                tile[hi] = Y;
+            }
+            __syncthreads();
+        }
+        for (unsigned e = tid; e < cnt; e += NTT_THREADS) dst[g0 + e] = d2u(canon(tile[e], p, pinv));
+    }
+}
+
+// ---------------------------------------------------------------- inverse transform
+// Gentleman-Sande butterflies undoing the forward stages last to first; the factor
+// 1/N is folded into the very last stage (m = 1).
+// COL = false runs first: stages logN-1 .. LA on contiguous rows;
+// COL = true  second   : stages LA-1 .. 0 on the strided tile.
+template <bool COL>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_kernel(NttArgs A) {
+    __shared__ double tile[NTT_TILE];
+    unsigned item, li;
+    const int t = resolve_limb(A.map, blockIdx.x, item, li);
+    if (t < 0) return;
+    const unsigned N = 1u << A.logN;
+    const u64d *src = A.src + (size_t)item * A.map.src_item_stride + (size_t)li * N;
+    u64d *dst = A.dst + (size_t)item * A.map.dst_item_stride + (size_t)li * N;
+    const double p = A.modc[t].p, pinv = A.modc[t].pinv;
+    const WMul *tw = A.tw + (size_t)t * N;
+    const WMul ninv = tw[0], wlast = A.tw_last[t];
+    const unsigned tid = threadIdx.x;
+    if (!COL) {
+        const unsigned N2 = N >> A.LA, N1 = 1u << A.LA;
+        const unsigned R = (N2 >= NTT_TILE) ? 1u : NTT_TILE / N2;
+        const unsigned rows_here = (N1 - blockIdx.y * R < R) ? N1 - blockIdx.y * R : R;
+        const unsigned row0 = blockIdx.y * R;
+        const unsigned cnt = rows_here * N2;
+        const size_t g0 = (size_t)row0 * N2;
+        for (unsigned e = tid; e < cnt; e += NTT_THREADS) tile[e] = u2d(src[g0 + e]);
+        __syncthreads();
+        const int LB = A.logN - A.LA;
+        int done = 0;
+        for (int s = LB - 1; s >= 0; s--, done++) {
+            const unsigned mp = 1u << s, tt = N2 >> (s + 1);
+            const bool red = (done & 1) != 0;
+            const bool final_stage = (A.LA == 0 && s == 0);
+            for (unsigned b = tid; b < cnt / 2; b += NTT_THREADS) {
+                unsigned rr = b / (N2 / 2), bb = b % (N2 / 2);
+                unsigned i = bb / tt, j = bb % tt;
+                unsigned lo = rr * N2 + i * 2 * tt + j, hi = lo + tt;
+                double x = tile[lo], y = tile[hi];
+                double X, Y;
+                if (final_stage) {
+                    X = mulmod_w(x + y, ninv.w, ninv.wp, p);
+                    Y = mulmod_w(x - y, wlast.w, wlast.wp, p);
+                } else {
+                    WMul W = tw[mp * (N1 + row0 + rr) + i];
+                    X = x + y;
+                    Y = mulmod_w(x - y, W.w, W.wp, p);
+                    if (red) { X = reduce_balanced(X, p, pinv); Y = reduce_balanced(Y, p, pinv); }
+                }
+                tile[lo] = X;
+                tile[hi] = Y;
+            }
+            __syncthreads();
+        }
+        for (unsigned e = tid; e < cnt; e += NTT_THREADS) dst[g0 + e] = d2u(canon(tile[e], p, pinv));
+    } else {
+        const unsigned N1 = 1u << A.LA, N2 = N >> A.LA;
+        const unsigned c0 = blockIdx.y * NTT_TC;
+        for (unsigned e = tid; e < N1 * NTT_TC; e += NTT_THREADS) {
+            unsigned r = e / NTT_TC, c = e % NTT_TC;
+            tile[e] = u2d(src[(size_t)r * N2 + c0 + c]);
+        }
+        __syncthreads();
+        int done = 0;
+        for (int s = A.LA - 1; s >= 0; s--, done++) {
+            const unsigned m = 1u << s, tr = N1 >> (s + 1);
+            const bool red = (done & 1) != 0;
+            for (unsigned b = tid; b < (N1 / 2) * NTT_TC; b += NTT_THREADS) {
+                unsigned c = b % NTT_TC, rb = b / NTT_TC;
+                unsigned i = rb / tr, jr = rb % tr;
+                unsigned lo = (i * 2 * tr + jr) * NTT_TC + c, hi = lo + tr * NTT_TC;
+                double x = tile[lo], y = tile[hi];
+                double X, Y;
+                if (s == 0) {
+                    X = mulmod_w(x + y, ninv.w, ninv.wp, p);
+                    Y = mulmod_w(x - y, wlast.w, wlast.wp, p);
+                } else {
+                    WMul W = tw[m + i];
+                    X = x + y;
+                    Y = mulmod_w(x - y, W.w, W.wp, p);
+                    if (red) { X = reduce_balanced(X, p, pinv); Y = reduce_balanced(Y, p, pinv); }
+                }
+                tile[lo] = X;
+                tile[hi] = Y;
+            }
+            __syncthreads();
+        }
+        for (unsigned e = tid; e < N1 * NTT_TC; e += NTT_THREADS) {
+            unsigned r = e / NTT_TC, c = e % NTT_TC;
+            dst[(size_t)r * N2 + c0 + c] = d2u(canon(tile[e], p, pinv));
+        }
+    }
+}
+
+// ---------------------------------------------------------------- limb-wise kernels
+// Arrays are [rows][level][N] with row = (item, component); word w of the array belongs
+// to limb (w / N) % level.
+#define EW_THREADS 256
+
+struct ScalarTab { WMul c[64]; double cpos[64]; };  // per limb: constant as multiplicand / canonical value
+
+__global__ __launch_bounds__(EW_THREADS) void addsub_kernel(const u64d *a, const u64d *b, u64d *out, const ModConst *modc,
+                                                             int logN, int level, size_t total, int sub) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const u64d q = (u64d)modc[(w >> logN) % level].p;
+    u64d x = a[w], y = b[w];
+    u64d r = sub ? (x >= y ? x - y : x + q - y) : (x + y >= q ? x + y - q : x + y);
+    out[w] = r;
+}
+
+// out = a * pt ; pt is [level][N], pt_stride words between items (0 = shared)
+__global__ __launch_bounds__(EW_THREADS) void mul_plain_kernel(const u64d *a, const u64d *pt, size_t pt_stride, u64d *out,
+                                                               const ModConst *modc, int logN, int level, size_t total) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const size_t N = (size_t)1 << logN;
+    const size_t limb = w >> logN, i = limb % level, item = limb / (2 * (size_t)level);
+    const ModConst mc = modc[i];
+    double x = u2d(a[w]), y = u2d(pt[item * pt_stride + i * N + (w & (N - 1))]);
+    out[w] = d2u(canon(mulmod(x, y, mc.p, mc.pinv), mc.p, mc.pinv));
+}
+
+__global__ __launch_bounds__(EW_THREADS) void mul_scalar_kernel(const u64d *a, u64d *out, const ModConst *modc, ScalarTab S,
+                                                                int logN, int level, size_t total) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const int i = (int)((w >> logN) % level);
+    const ModConst mc = modc[i];
+    out[w] = d2u(canon(mulmod_w(u2d(a[w]), S.c[i].w, S.c[i].wp, mc.p), mc.p, mc.pinv));
+}
+
+// out = a, plus the constant on component 0
+__global__ __launch_bounds__(EW_THREADS) void add_const_kernel(const u64d *a, u64d *out, const ModConst *modc, ScalarTab S,
+                                                               int logN, int level, size_t total) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const size_t limb = w >> logN;
+    const int i = (int)(limb % level);
+    u64d x = a[w];
+    if ((limb / level) % 2 == 0) {
+        const u64d q = (u64d)modc[i].p, c = (u64d)S.cpos[i];
+        x = (x + c >= q) ? x + c - q : x + c;
+    }
+    out[w] = x;
+}
+
+// rows of level_in limbs -> rows of level_out limbs (first limbs kept)
+__global__ __launch_bounds__(EW_THREADS) void mod_drop_kernel(const u64d *a, u64d *out, int logN, int level_in, int level_out,
+                                                              size_t total_out) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total_out) return;
+    const size_t N = (size_t)1 << logN;
+    const size_t limb = w >> logN, row = limb / level_out, i = limb % level_out;
+    out[w] = a[(row * level_in + i) * N + (w & (N - 1))];
+}
+
+// d = (a0*b0, a0*b1 + a1*b0, a1*b1); a, b: [batch][2][level][N], d: [batch][3][level][N]
+__global__ __launch_bounds__(EW_THREADS) void tensor_kernel(const u64d *a, const u64d *b, u64d *d, const ModConst *modc, int logN,
+                                                            int level, size_t total /* batch*level*N */) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const size_t N = (size_t)1 << logN;
+    const size_t limb = w >> logN, item = limb / level, i = limb % level, n = w & (N - 1);
+    const ModConst mc = modc[i];
+    const size_t ia = (item * 2 * level + i) * N + n, st = (size_t)level * N;
+    double a0 = u2d(a[ia]), a1 = u2d(a[ia + st]), b0 = u2d(b[ia]), b1 = u2d(b[ia + st]);
+    double d0 = mulmod(a0, b0, mc.p, mc.pinv);
+    double d1 = mulmod(a0, b1, mc.p, mc.pinv) + mulmod(a1, b0, mc.p, mc.pinv);
+    double d2 = mulmod(a1, b1, mc.p, mc.pinv);
+    const size_t id = (item * 3 * level + i) * N + n;
+    d[id] = d2u(canon(d0, mc.p, mc.pinv));
+    d[id + st] = d2u(canon(d1, mc.p, mc.pinv));
+    d[id + 2 * st] = d2u(canon(d2, mc.p, mc.pinv));
+}
+
+// Evaluation-form automorphism X -> X^g: out[j] = in[pi(j)],
+// pi(j) = brev(((2*brev(j)+1)*g mod 2N - 1)/2).  Rows = (item, comp, limb); g per item.
+struct GaloisTab { unsigned g[CKKSMI_MAX_ITEMS]; };
+
+__global__ __launch_bounds__(EW_THREADS) void automorphism_kernel(const u64d *in, u64d *out, GaloisTab G, int logN, int limbs_per_item,
+                                                                  size_t total) {
+    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const unsigned N = 1u << logN;
+    const size_t limb = w >> logN;
+    const unsigned j = (unsigned)(w & (N - 1));
+    const unsigned g = G.g[limb / limbs_per_item];
+    const unsigned bj = __brev(j) >> (32 - logN);
+    const unsigned e = ((2u * bj + 1u) * g) & (2u * N - 1u);
+    const unsigned src = __brev((e - 1u) >> 1) >> (32 - logN);
+    out[w] = in[limb * N + src];
+}
+
+// ---------------------------------------------------------------- key switching
+// ModUp of one item's polynomial d (coefficient form, [level][N]) into the extended
+// basis for every digit: out [beta][E][N].  Limbs that belong to the digit are copied
+// from the evaluation-form source (they need no transform).
+struct ModUpArgs {
+    const u64d *d_coef;      // [items][level][N]
+    const u64d *d_eval;      // evaluation-form source of the same polynomial
+    unsigned long long d_eval_item_stride;
+    u64d *out;               // [items][beta][E][N]
+    const ModConst *modc;
+    const WMul *inv;         // [beta_top][alpha][alpha]
+    const WMul *cc;          // [beta_top][alpha][alpha][T]
+    int logN, level, E, n_q, alpha, beta, T;
+};
+
+__global__ __launch_bounds__(EW_THREADS) void modup_kernel(ModUpArgs A) {
+    const unsigned N = 1u << A.logN;
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= N) return;
+    const unsigned j = blockIdx.y, item = blockIdx.z;
+    const int lo = (int)j * A.alpha;
+    const int nd = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
+    const size_t row = ((size_t)j * A.alpha + (nd - 1)) * A.alpha;
+    const u64d *dc = A.d_coef + (size_t)item * A.level * N;
+    const u64d *de = A.d_eval + (size_t)item * A.d_eval_item_stride;
+    u64d *out = A.out + ((size_t)item * A.beta + j) * A.E * N;
+    double y[CKKSMI_MAX_ALPHA];
+    for (int a = 0; a < nd; a++) {
+        const ModConst mc = A.modc[lo + a];
+        const WMul W = A.inv[row + a];
+        // canonical representative in [0, q): the integer sum_a y_a*qhat_a is what gets reduced
+        y[a] = canon(mulmod_w(u2d(dc[(size_t)(lo + a) * N + n]), W.w, W.wp, mc.p), mc.p, mc.pinv);
+    }
+    for (int x = 0; x < A.E; x++) {
+        if (x >= lo && x < lo + nd) {
+            out[(size_t)x * N + n] = de[(size_t)x * N + n];
+            continue;
+        }
+        const int t = x < A.level ? x : A.n_q + x - A.level;
+        const ModConst mc = A.modc[t];
+        double acc = 0.0;
+        for (int a = 0; a < nd; a++) {
+            const WMul W = A.cc[(row + a) * A.T + t];
+            acc += mulmod_w(y[a], W.w, W.wp, mc.p);
+        }
+        out[(size_t)x * N + n] = d2u(canon(acc, mc.p, mc.pinv));
+    }
+}
+
+// acc_c[x] = sum_j dt_j[x] * key_j,c[T(x)]   (evaluation form, extended basis)
+struct KeyTab {
+    const u64d *key[CKKSMI_MAX_KEYS];
+    unsigned char slot[CKKSMI_MAX_ITEMS];
+};
+
+struct InnerArgs {
+    const u64d *dt;  // [items][beta][E][N]
+    u64d *acc;       // [items][2][E][N]
+    const ModConst *modc;
+    int logN, level, E, n_q, beta, T;
+};
+
+__global__ __launch_bounds__(EW_THREADS) void inner_product_kernel(InnerArgs A, KeyTab K) {
+    const unsigned N = 1u << A.logN;
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= N) return;
+    const unsigned x = blockIdx.y, item = blockIdx.z;
+    const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+    const ModConst mc = A.modc[t];
+    const u64d *key = K.key[K.slot[item]];
+    double a0 = 0.0, a1 = 0.0;
+    for (int j = 0; j < A.beta; j++) {
+        const double v = u2d(A.dt[(((size_t)item * A.beta + j) * A.E + x) * N + n]);
+        const double k0 = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + n]);
+        const double k1 = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + n]);
+        a0 = reduce_balanced(a0 + mulmod(v, k0, mc.p, mc.pinv), mc.p, mc.pinv);
+        a1 = reduce_balanced(a1 + mulmod(v, k1, mc.p, mc.pinv), mc.p, mc.pinv);
+    }
+    A.acc[(((size_t)item * 2 + 0) * A.E + x) * N + n] = d2u(canon_small(a0, mc.p));
+    A.acc[(((size_t)item * 2 + 1) * A.E + x) * N + n] = d2u(canon_small(a1, mc.p));
+}
+
+// ---------------------------------------------------------------- DivRound
+// Rows = (item, component).  Step 1 (coefficient form): from the nb dropped limbs of a
+// row compute, for each kept limb i, r_i - h where r_i = [(x + h) mod Bbar] mod c_i by fast
+// basis conversion.  Step 2 (evaluation form, after transforming step 1's output):
+// out_i = (x_i - NTT(r_i - h)) * Bbar^-1 mod c_i, optionally + addend_i.
+struct DivConvArgs {
+    const u64d *b_limbs;  // dropped limbs, coefficient form: row r, limb m at b_limbs + r*b_row_stride + m*N
+    unsigned long long b_row_stride;
+    u64d *tmp;            // [rows][nc][N]
+    const ModConst *modc;
+    DivRoundDev D;
+    int logN, nc, T;      // kept limbs are modulus indices 0 .. nc-1
+};
+
+__global__ __launch_bounds__(EW_THREADS) void divround_conv_kernel(DivConvArgs A) {
+    const unsigned N = 1u << A.logN;
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= N) return;
+    const unsigned row = blockIdx.y;
+    double y[CKKSMI_MAX_SPECIAL];
+    for (int m = 0; m < A.D.nb; m++) {
+        const ModConst mc = A.modc[A.D.b_idx[m]];
+        double x = u2d(A.b_limbs[(size_t)row * A.b_row_stride + (size_t)m * N + n]) + A.D.hb[m];
+        x = x >= mc.p ? x - mc.p : x;
+        y[m] = canon(mulmod_w(x, A.D.invb[m].w, A.D.invb[m].wp, mc.p), mc.p, mc.pinv);
+    }
+    for (int i = 0; i < A.nc; i++) {
+        const ModConst mc = A.modc[i];
+        double acc = -A.D.hc[i];
+        for (int m = 0; m < A.D.nb; m++) {
+            const WMul W = A.D.conv[(size_t)m * A.T + i];
+            acc += mulmod_w(y[m], W.w, W.wp, mc.p);
+        }
+        A.tmp[((size_t)row * A.nc + i) * N + n] = d2u(canon(acc, mc.p, mc.pinv));
+    }
+}
+
+struct DivFinalArgs {
+    const u64d *x;       // kept limbs, evaluation form: row r, limb i at x + r*x_row_stride + i*N
+    unsigned long long x_row_stride;
+    const u64d *tmp;     // [rows][nc][N] evaluation form
+    const u64d *addend;  // optional, row r limb i at addend + (r/2)*add_item_stride + (r%2)*add_comp_stride + i*N
+    unsigned long long add_item_stride, add_comp_stride;
+    int add_both;        // 1: both components receive the addend, 0: component 0 only
+    u64d *out;           // [rows][nc][N]
+    const ModConst *modc;
+    const WMul *Binv;    // [T]
+    int logN, nc;
+};
+
+__global__ __launch_bounds__(EW_THREADS) void divround_final_kernel(DivFinalArgs A) {
+    const unsigned N = 1u << A.logN;
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= N) return;
+    const unsigned i = blockIdx.y, row = blockIdx.z;
+    const ModConst mc = A.modc[i];
+    const WMul W = A.Binv[i];
+    double x = u2d(A.x[(size_t)row * A.x_row_stride + (size_t)i * N + n]);
+    double r = u2d(A.tmp[((size_t)row * A.nc + i) * N + n]);
+    double v = canon(mulmod_w(x - r, W.w, W.wp, mc.p), mc.p, mc.pinv);
+    if (A.addend && (A.add_both || (row & 1u) == 0)) {
+        v += u2d(A.addend[(size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + n]);
+        v = v >= mc.p ? v - mc.p : v;
+    }
+    A.out[((size_t)row * A.nc + i) * N + n] = d2u(v);
+}
+
+// out[row][i] = a[row][i] + b[row][i] for rows of `level` limbs where only component 0
+// rows (even rows) receive the addend; used by rotation: (sigma(c0) + ks0, ks1)
+// is produced directly by divround_final's addend with add_comp_stride, so no kernel here.
+
+// ---------------------------------------------------------------- conv / FC multiply-accumulate
+// Weights prepared per limb: wtab[i][widx] = (w mod q_i balanced, that / q_i)
+__global__ __launch_bounds__(EW_THREADS) void mac_prepare_kernel(const long long *w, WMul *wtab, const ModConst *modc, int level,
+                                                                 size_t n_weights) {
+    size_t idx = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (idx >= n_weights * (size_t)level) return;
+    const int i = (int)(idx / n_weights);
+    const long long q = (long long)modc[i].p;
+    long long r = w[idx % n_weights] % q;  // (-q, q)
+    if (r > q / 2) r -= q;
+    if (r < -(q / 2)) r += q;
+    const double rb = (double)r;
+    wtab[idx] = WMul{rb, rb / modc[i].p};
+}
+
+#define MAC_OC 8  // output channels accumulated per thread
+
+struct MacArgs {
+    const u64d *in;   // [C][H][W] ciphertexts of 2*level limbs
+    u64d *out;        // [O][Ho][Wo]
+    const WMul *wtab; // [level][O*C*kh*kw]
+    const ModConst *modc;
+    int logN, level;
+    int C, H, W, O, kh, kw, stride, pad, Ho, Wo;
+};
+
+// grid: x = N / EW_THREADS, y = 2*level (component-major limb), z = Ho*Wo*ceil(O/MAC_OC)
+__global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
+    const unsigned N = 1u << A.logN;
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= N) return;
+    const unsigned lc = blockIdx.y, i = lc % (unsigned)A.level;
+    const unsigned ogroups = (unsigned)(A.O + MAC_OC - 1) / MAC_OC;
+    const unsigned og = blockIdx.z % ogroups, pos = blockIdx.z / ogroups;
+    const int oy = (int)(pos / (unsigned)A.Wo), ox = (int)(pos % (unsigned)A.Wo);
+    const int o0 = (int)og * MAC_OC;
+    const ModConst mc = A.modc[i];
+    const size_t ctw = (size_t)2 * A.level * N;
+    const size_t taps = (size_t)A.C * A.kh * A.kw;
+    const WMul *wt = A.wtab + (size_t)i * A.O * taps;
+    double acc[MAC_OC];
+    for (int o = 0; o < MAC_OC; o++) acc[o] = 0.0;
+    int pending = 0;
+    for (int c = 0; c < A.C; c++)
+        for (int u = 0; u < A.kh; u++)
+            for (int v = 0; v < A.kw; v++) {
+                const int iy = oy * A.stride + u - A.pad, ix = ox * A.stride + v - A.pad;
+                if (iy < 0 || iy >= A.H || ix < 0 || ix >= A.W) continue;
+                const double xv = u2d(A.in[(((size_t)c * A.H + iy) * A.W + ix) * ctw + (size_t)lc * N + n]);
+                const size_t tap = ((size_t)c * A.kh + u) * A.kw + v;
+                for (int o = 0; o < MAC_OC; o++) {
+                    if (o0 + o < A.O) {
+                        const WMul Wt = wt[(size_t)(o0 + o) * taps + tap];
+                        acc[o] += mulmod_w(xv, Wt.w, Wt.wp, mc.p);
+                    }
+                }
+                if (++pending == 4) {  // each term is below 0.75p: four terms on a reduced value stay under 4p
+                    for (int o = 0; o < MAC_OC; o++) acc[o] = reduce_balanced(acc[o], mc.p, mc.pinv);
+                    pending = 0;
+                }
+            }
+    for (int o = 0; o < MAC_OC; o++)
+        if (o0 + o < A.O)
+            A.out[((((size_t)(o0 + o) * A.Ho + oy) * A.Wo + ox) * ctw) + (size_t)lc * N + n] = d2u(canon(acc[o], mc.p, mc.pinv));
+}

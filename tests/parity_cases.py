@@ -1,0 +1,260 @@
+"""Parity cases shared by the GPU tests and by the CPU-emulated kernel checks: each
+function runs one operation of the library through its C ABI on buffers supplied by a
+backend and compares the result word for word with the CPU oracle on the same seeded
+inputs.  Bit-exact is the bar: all ciphertext arithmetic is integer mod q_i."""
+import numpy as np
+
+from oracle import oracle as orc
+from paper_1911_11377_amd import ckksmi
+from paper_1911_11377_amd import workloads as wl
+from helpers import Material
+
+
+class GpuBackend:
+    """device buffers are torch tensors on cuda:0"""
+
+    def __init__(self):
+        import torch
+
+        self.torch = torch
+        assert torch.cuda.is_available(), "GPU tests need a GPU"
+        self.lib_path = None
+
+    def context(self, logN, n_q, q_bits, k, special_bits, alpha):
+        return ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=0)
+
+    def to_dev(self, arr, dtype=np.uint64):
+        a = np.ascontiguousarray(arr, dtype=dtype)
+        return self.torch.from_numpy(a.view(np.int64)).to("cuda:0")
+
+    def empty(self, *shape):
+        return self.torch.empty(shape, dtype=self.torch.int64, device="cuda:0")
+
+    def ws(self, nbytes):
+        return self.torch.empty(max(nbytes // 8, 1), dtype=self.torch.int64, device="cuda:0")
+
+    def to_host(self, buf):
+        self.torch.cuda.synchronize()
+        return buf.cpu().numpy().view(np.uint64)
+
+    stream = None
+
+
+class EmuBackend:
+    """'device' buffers are guard-paged host memory; kernels run as CPU fibers"""
+
+    def __init__(self):
+        import emu_support
+
+        self.es = emu_support
+        self.lib_path = emu_support.emu_lib_path()
+        self.lib = ckksmi.load(self.lib_path)
+
+    def context(self, logN, n_q, q_bits, k, special_bits, alpha):
+        return ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=0, lib=self.lib_path)
+
+    def to_dev(self, arr, dtype=np.uint64):
+        return self.es.to_emu(self.lib, arr, dtype)
+
+    def empty(self, *shape):
+        b = self.es.EmuBuf(self.lib, shape)
+        b.np[...] = 0xDEADBEEFDEADBEEF
+        return b
+
+    def ws(self, nbytes):
+        return self.es.EmuBuf(self.lib, (max(nbytes // 8, 1),))
+
+    def to_host(self, buf):
+        return buf.np.copy()
+
+    stream = 0
+
+
+def make_material(shape, seed, rotations=()):
+    logN, n_q, q_bits, k, special_bits, alpha = shape
+    return Material(logN, n_q, q_bits, k, special_bits, alpha, seed=seed, rotations=rotations)
+
+
+def random_cts(M, level, batch, seed, tag, comps=2):
+    """uniform residues: ciphertexts are pseudorandom, and parity does not need them to decrypt"""
+    return wl.uniform_limbs(M.O.q[:level], M.N, seed, tag, lead=(batch, comps))
+
+
+def check_moduli(ctx, M):
+    assert ctx.moduli == M.O.moduli and ctx.psis == M.O.psis
+
+
+def case_ntt(be, shape, seed, batch=2):
+    logN, n_q, q_bits, k, special_bits, alpha = shape
+    O = orc.Oracle(logN, n_q, q_bits, k, special_bits, alpha)
+    ctx = be.context(*shape)
+    assert ctx.moduli == O.moduli and ctx.psis == O.psis
+    idx = list(range(O.n_q + O.k))
+    idx = idx[::-1][: min(len(idx), 5)]  # a few limbs, special primes first
+    x = wl.uniform_limbs([O.moduli[t] for t in idx], O.N, seed, "ntt", lead=(batch,))
+    d = be.to_dev(x)
+    ctx.ntt(d, idx, batch, stream=be.stream)
+    got = be.to_host(d).reshape(x.shape)
+    for b in range(batch):
+        want = O.ntt_limbs(x[b], idx)
+        assert np.array_equal(got[b], want), "forward transform differs from the oracle"
+    ctx.intt(d, idx, batch, stream=be.stream)
+    assert np.array_equal(be.to_host(d).reshape(x.shape), x), "inverse(forward(x)) != x"
+    # inverse against the oracle on fresh data
+    d2 = be.to_dev(x)
+    ctx.intt(d2, idx, batch, stream=be.stream)
+    got = be.to_host(d2).reshape(x.shape)
+    assert np.array_equal(got[0], O.intt_limbs(x[0], idx))
+    ctx.close()
+
+
+def case_elementwise(be, shape, seed, batch=3):
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    level = O.n_q
+    a, b = random_cts(M, level, batch, seed, "a"), random_cts(M, level, batch, seed, "b")
+    da, db = be.to_dev(a), be.to_dev(b)
+    out = be.empty(batch, 2, level, O.N)
+    ctx.add(da, db, out, level, batch, stream=be.stream)
+    got = be.to_host(out).reshape(a.shape)
+    assert all(np.array_equal(got[i], O.add(a[i], b[i], level)) for i in range(batch))
+    ctx.sub(da, db, out, level, batch, stream=be.stream)
+    got = be.to_host(out).reshape(a.shape)
+    assert all(np.array_equal(got[i], O.sub(a[i], b[i], level)) for i in range(batch))
+    for cst in (-123456789012345, 3, -(1 << 62) + 12345):
+        ctx.mul_scalar(da, cst, out, level, batch, stream=be.stream)
+        got = be.to_host(out).reshape(a.shape)
+        assert all(np.array_equal(got[i], O.mul_scalar(a[i], cst, level)) for i in range(batch))
+        ctx.add_const(da, cst, out, level, batch, stream=be.stream)
+        got = be.to_host(out).reshape(a.shape)
+        assert all(np.array_equal(got[i], O.add_const(a[i], cst, level)) for i in range(batch))
+    pt = wl.uniform_limbs(O.q[:level], O.N, seed, "pt", lead=(batch,))
+    dpt = be.to_dev(pt)
+    ctx.mul_plain(da, dpt, level * O.N, out, level, batch, stream=be.stream)
+    got = be.to_host(out).reshape(a.shape)
+    assert all(np.array_equal(got[i], O.mul_plain(a[i], pt[i], level)) for i in range(batch))
+    ctx.mul_plain(da, dpt, 0, out, level, batch, stream=be.stream)
+    got = be.to_host(out).reshape(a.shape)
+    assert all(np.array_equal(got[i], O.mul_plain(a[i], pt[0], level)) for i in range(batch))
+    if level > 1:
+        lo = level - 1
+        outd = be.empty(batch, 2, lo, O.N)
+        ctx.mod_drop(da, level, lo, outd, batch, stream=be.stream)
+        got = be.to_host(outd).reshape(batch, 2, lo, O.N)
+        assert all(np.array_equal(got[i], O.mod_drop(a[i], level, lo)) for i in range(batch))
+    d3 = be.empty(batch, 3, level, O.N)
+    ctx.hmul(da, db, d3, level, batch, stream=be.stream)
+    got = be.to_host(d3).reshape(batch, 3, level, O.N)
+    assert all(np.array_equal(got[i], O.tensor(a[i], b[i], level)) for i in range(batch))
+    ctx.close()
+
+
+def case_rescale(be, shape, seed, batch=2, levels=None):
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    for level in levels or [O.n_q, 2]:
+        if level < 2 or level > O.n_q:
+            continue
+        a = random_cts(M, level, batch, seed, ("rs", level))
+        da = be.to_dev(a)
+        out = be.empty(batch, 2, level - 1, O.N)
+        ws = be.ws(ctx.workspace_bytes(ckksmi.OP_RESCALE, level, batch))
+        ctx.rescale(da, out, level, batch, ws, stream=be.stream)
+        got = be.to_host(out).reshape(batch, 2, level - 1, O.N)
+        for i in range(batch):
+            assert np.array_equal(got[i], O.rescale(a[i], level)), "rescale differs at level %d" % level
+        assert np.array_equal(be.to_host(da).reshape(a.shape), a), "rescale modified its input"
+    ctx.close()
+
+
+def case_relin_and_composite(be, shape, seed, batch=2, levels=None, small_ws=False):
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    evk = be.to_dev(M.rlk)
+    for level in levels or [O.n_q]:
+        a, b = random_cts(M, level, batch, seed, ("a", level)), random_cts(M, level, batch, seed, ("b", level))
+        da, db = be.to_dev(a), be.to_dev(b)
+        d = be.empty(batch, 3, level, O.N)
+        ctx.hmul(da, db, d, level, batch, stream=be.stream)
+        r = be.empty(batch, 2, level, O.N)
+        nbytes = ctx.workspace_bytes(ckksmi.OP_RELIN, level, batch)
+        if small_ws and batch > 1:
+            nbytes = nbytes // batch + 8  # forces one item per sweep
+        ws = be.ws(nbytes)
+        ctx.relin(d, evk, r, level, batch, ws, stream=be.stream)
+        got_r = be.to_host(r).reshape(batch, 2, level, O.N)
+        hd = be.to_host(d).reshape(batch, 3, level, O.N)
+        for i in range(batch):
+            assert np.array_equal(got_r[i], O.relin(hd[i], M.rlk, level)), "relin differs at level %d item %d" % (level, i)
+        if level >= 2:
+            out = be.empty(batch, 2, level - 1, O.N)
+            ws2 = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+            ctx.hmul_relin_rescale(da, db, evk, out, level, batch, ws2, stream=be.stream)
+            got = be.to_host(out).reshape(batch, 2, level - 1, O.N)
+            for i in range(batch):
+                assert np.array_equal(got[i], O.hmul_relin_rescale(a[i], b[i], M.rlk, level)), "composite differs"
+            # and equals the three-call sequence
+            out3 = be.empty(batch, 2, level - 1, O.N)
+            ws3 = be.ws(ctx.workspace_bytes(ckksmi.OP_RESCALE, level, batch))
+            ctx.rescale(r, out3, level, batch, ws3, stream=be.stream)
+            assert np.array_equal(be.to_host(out3), be.to_host(out))
+    ctx.close()
+
+
+def case_rotate(be, shape, seed, rotations, batch=4, level=None):
+    M = make_material(shape, seed, rotations=rotations)
+    O = M.O
+    ctx = be.context(*shape)
+    level = level or O.n_q
+    keys = {r: be.to_dev(M.gk[r]) for r in rotations}
+    for r in rotations:
+        ctx.galois_key_register(r, keys[r])
+    a = random_cts(M, level, batch, seed, "rot")
+    da = be.to_dev(a)
+    rots = [rotations[i % len(rotations)] for i in range(batch)]
+    out = be.empty(batch, 2, level, O.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_ROTATE, level, batch))
+    ctx.rotate(da, rots, out, level, batch, ws, stream=be.stream)
+    got = be.to_host(out).reshape(batch, 2, level, O.N)
+    for i in range(batch):
+        assert np.array_equal(got[i], O.rotate(a[i], rots[i], M.gk[rots[i]], level)), "rotate item %d by %d differs" % (i, rots[i])
+    # a rotation without a key is refused before anything runs
+    try:
+        ctx.rotate(da, [rotations[0] + 1] * batch, out, level, batch, ws, stream=be.stream)
+        raise AssertionError("missing key not reported")
+    except ckksmi.CkksmiError as e:
+        assert e.code == ckksmi.ENOKEY
+    ctx.close()
+
+
+def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    level = level or O.n_q
+    x = wl.uniform_limbs(O.q[:level], O.N, seed, "x", lead=(Cin, H, W, 2))
+    wf = wl.weights_float((Oc, Cin, kh, kh), seed)
+    wi = np.rint(wf * O.q[level - 1]).astype(np.int64)
+    wi.flat[0] = -(1 << 62) + 7  # a weight far outside (-q/2, q/2)
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kh) // stride + 1
+    dx, dw = be.to_dev(x), be.to_dev(wi, np.int64)
+    out = be.empty(Oc, Ho, Wo, 2, level, O.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, level, wi.size))
+    ctx.conv2d_mac(dx, dw, Cin, H, W, Oc, kh, kh, stride, pad, out, level, ws, stream=be.stream)
+    got = be.to_host(out).reshape(Oc, Ho, Wo, 2, level, O.N)
+    assert np.array_equal(got, O.conv2d_mac(x, wi, stride, pad, level)), "conv MAC differs from the oracle"
+    # FC: flat features
+    F = Cin * H
+    xf = x[:, :, 0].reshape(F, 2, level, O.N)
+    wfc = np.rint(wl.weights_float((Oc, F), seed, "fc") * O.q[level - 1]).astype(np.int64)
+    dxf, dwf = be.to_dev(xf), be.to_dev(wfc, np.int64)
+    outf = be.empty(Oc, 2, level, O.N)
+    wsf = be.ws(ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, level, wfc.size))
+    ctx.fc_mac(dxf, dwf, F, Oc, outf, level, wsf, stream=be.stream)
+    assert np.array_equal(be.to_host(outf).reshape(Oc, 2, level, O.N), O.fc_mac(xf, wfc, level)), "FC MAC differs"
+    ctx.close()

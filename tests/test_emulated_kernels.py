@@ -1,0 +1,56 @@
+"""The library's kernel sources, compiled against the CPU stand-in under tests/emu
+and run fibre by fibre on tiny shapes with guard pages behind every buffer, compared
+with the oracle.  This checks indexing and launch shapes on the CPU before a GPU ever
+runs them; the parity claims themselves come from the GPU tests."""
+import pytest
+
+import parity_cases as pc
+
+# (logN, n_q, q_bits, k, special_bits, alpha)
+TINY = (6, 3, 30, 1, 31, 1)
+HYBRID = (5, 5, 40, 2, 41, 2)
+HYBRID3 = (4, 7, 50, 3, 51, 3)
+TWO_PASS = (13, 2, 50, 1, 51, 1)
+
+
+@pytest.fixture(scope="module")
+def be():
+    return pc.EmuBackend()
+
+
+@pytest.mark.parametrize("shape", [TINY, (2, 2, 20, 1, 21, 1), (9, 2, 50, 1, 51, 1), (12, 1, 40, 1, 41, 1), TWO_PASS])
+def test_emulated_ntt(be, shape):
+    pc.case_ntt(be, shape, seed=100)
+
+
+@pytest.mark.parametrize("shape", [TINY, HYBRID3])
+def test_emulated_elementwise(be, shape):
+    pc.case_elementwise(be, shape, seed=101)
+
+
+@pytest.mark.parametrize("shape", [TINY, HYBRID])
+def test_emulated_rescale(be, shape):
+    pc.case_rescale(be, shape, seed=102)
+
+
+@pytest.mark.parametrize("shape,levels", [(TINY, [3, 1]), (HYBRID, [5, 4, 3]), (HYBRID3, [7, 5, 2])])
+def test_emulated_relin_and_composite(be, shape, levels):
+    pc.case_relin_and_composite(be, shape, seed=103, levels=levels)
+
+
+def test_emulated_relin_small_workspace(be):
+    pc.case_relin_and_composite(be, HYBRID, seed=104, batch=3, levels=[5], small_ws=True)
+
+
+def test_emulated_two_pass_composite(be):
+    pc.case_relin_and_composite(be, TWO_PASS, seed=105, batch=1, levels=[2])
+
+
+@pytest.mark.parametrize("shape,level", [(TINY, 3), (HYBRID3, 5)])
+def test_emulated_rotate(be, shape, level):
+    pc.case_rotate(be, shape, seed=106, rotations=[1, 3, 7], batch=4, level=level)
+
+
+def test_emulated_conv(be):
+    pc.case_conv(be, TINY, seed=107, Cin=2, H=5, W=5, Oc=9, kh=3, stride=2, pad=0)
+    pc.case_conv(be, TINY, seed=108, Cin=1, H=4, W=4, Oc=2, kh=3, stride=1, pad=1, level=2)

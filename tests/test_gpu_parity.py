@@ -1,0 +1,226 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  Ciphertext words must match bit for bit; decrypted slot values
+must match the cleartext computation within 1e-3 at scale 2^40 (1e-2 for the tiny
+shape, whose output scale is only about 2^20)."""
+import numpy as np
+import pytest
+
+import parity_cases as pc
+from oracle import oracle as orc
+from paper_1911_11377_amd import ckksmi
+from paper_1911_11377_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TINY = (12, 3, 40, 1, 41, 1)            # N=2^12, 3x40-bit + one 41-bit special prime
+C2 = (14, 8, 50, 1, 51, 1)              # N=2^14, 8x50-bit + one special prime
+C3 = (15, 16, 50, 0, 51, 1)             # N=2^15, 16x50-bit, no key switching
+C4 = (16, 24, 50, 3, 51, 3)             # N=2^16, 24x50-bit + 3 special primes, 8 digits
+
+
+@pytest.fixture(scope="module")
+def be():
+    return pc.GpuBackend()
+
+
+def announce(msg):
+    print("[case] " + msg, flush=True)
+
+
+@pytest.mark.parametrize("shape", [(4, 2, 20, 1, 21, 1), (9, 2, 50, 1, 51, 1), TINY, (13, 2, 50, 1, 51, 1), (14, 2, 50, 1, 51, 1),
+                                   (15, 2, 50, 1, 51, 1), (16, 2, 50, 2, 51, 2), (17, 1, 50, 1, 51, 1)])
+def test_ntt_matches_oracle(be, shape):
+    announce("ntt %r" % (shape,))
+    pc.case_ntt(be, shape, seed=300, batch=3)
+
+
+@pytest.mark.parametrize("shape", [TINY, (14, 3, 50, 1, 51, 1), (5, 7, 50, 3, 51, 3)])
+def test_elementwise_matches_oracle(be, shape):
+    announce("elementwise %r" % (shape,))
+    pc.case_elementwise(be, shape, seed=301, batch=3)
+
+
+@pytest.mark.parametrize("shape,levels", [(TINY, [3, 2]), ((14, 4, 50, 1, 51, 1), [4]), ((8, 5, 40, 2, 41, 2), [5, 3])])
+def test_rescale_matches_oracle(be, shape, levels):
+    announce("rescale %r" % (shape,))
+    pc.case_rescale(be, shape, seed=302, batch=3, levels=levels)
+
+
+def test_tiny_shape_full_batch(be):
+    """the tiny workload: 16 ciphertext pairs, HMult + relin + rescale, every word compared"""
+    announce("tiny shape, batch 16")
+    pc.case_relin_and_composite(be, TINY, seed=1, batch=16, levels=[3])
+
+
+@pytest.mark.parametrize("shape,levels,batch", [
+    (TINY, [2, 1], 2),
+    ((10, 5, 40, 2, 41, 2), [5, 4, 3, 1], 3),
+    ((9, 7, 50, 3, 51, 3), [7, 6, 5, 2], 2),
+    ((13, 3, 50, 1, 51, 1), [3], 2),
+    ((15, 3, 50, 3, 51, 3), [3, 2], 1),
+])
+def test_relin_and_composite_levels_and_digits(be, shape, levels, batch):
+    announce("relin/composite %r levels %r" % (shape, levels))
+    pc.case_relin_and_composite(be, shape, seed=303, batch=batch, levels=levels)
+
+
+def test_ragged_sweeps_with_small_workspace(be):
+    announce("relin with a workspace that holds one item")
+    pc.case_relin_and_composite(be, (10, 5, 40, 2, 41, 2), seed=304, batch=5, levels=[5], small_ws=True)
+
+
+def test_rotate_matches_oracle(be):
+    announce("rotate tiny + hybrid")
+    pc.case_rotate(be, TINY, seed=305, rotations=[1, 2, 100, 2047], batch=6)
+    pc.case_rotate(be, (9, 7, 50, 3, 51, 3), seed=306, rotations=[1, 3, 255], batch=4, level=5)
+
+
+def test_conv_and_fc_match_oracle(be):
+    announce("conv small")
+    pc.case_conv(be, (10, 3, 40, 0, 41, 1), seed=307, Cin=3, H=7, W=7, Oc=10, kh=5, stride=2, pad=0)
+    pc.case_conv(be, (8, 2, 50, 1, 51, 1), seed=308, Cin=2, H=4, W=5, Oc=3, kh=3, stride=1, pad=1)
+
+
+def test_conv_at_layer_shape_slice(be):
+    """N=2^15, 16x50-bit limbs, 3 input channels, 5x5 stride 2: one output position, three filters"""
+    announce("conv N=2^15 level 16 slice")
+    pc.case_conv(be, C3, seed=309, Cin=3, H=5, W=5, Oc=3, kh=5, stride=2, pad=0)
+
+
+def _encrypt_batch(M, zs, scale, level, tag):
+    return np.stack([M.encrypt(z, scale, level, (tag, i)) for i, z in enumerate(zs)])
+
+
+def test_tiny_shape_decrypts_to_product(be):
+    announce("tiny: decrypt(HMult) vs float product")
+    p = wl.PRESETS["tiny"]
+    M = pc.make_material(TINY, 1)
+    ctx = be.context(*TINY)
+    scale = 2.0**p.log_scale
+    za = [wl.slots_complex(M.N // 2, 1, "a", i) for i in range(4)]
+    zb = [wl.slots_complex(M.N // 2, 1, "b", i) for i in range(4)]
+    a, b = _encrypt_batch(M, za, scale, 3, "a"), _encrypt_batch(M, zb, scale, 3, "b")
+    out = be.empty(4, 2, 2, M.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, 3, 4))
+    ctx.hmul_relin_rescale(be.to_dev(a), be.to_dev(b), be.to_dev(M.rlk), out, 3, 4, ws)
+    got = be.to_host(out).reshape(4, 2, 2, M.N)
+    for i in range(4):
+        assert np.array_equal(got[i], M.O.hmul_relin_rescale(a[i], b[i], M.rlk, 3))
+        dec = ctx.decode(ctx.decrypt(M.s, got[i], 2), 2, scale * scale / M.O.q[2])
+        assert np.max(np.abs(dec - za[i] * zb[i])) < 1e-2
+
+
+def test_2e14_shape_hmul_and_rotations(be):
+    """N=2^14, 8x50-bit + special, scale 2^40: the launch shape of the full batch of 256,
+    outputs sampled for the oracle; decrypted values within 1e-3"""
+    announce("N=2^14 batch 256, sampled parity")
+    p = wl.PRESETS["hmul_rot_2e14"]
+    rots = wl.rotation_offsets(p.N // 2, 8, 2)
+    M = pc.make_material(C2, 2, rotations=rots)
+    ctx = be.context(*C2)
+    scale = 2.0**p.log_scale
+    batch, level = p.batch, p.n_q
+    # real encryptions for the sampled items, uniform residues (pseudorandom, like any RLWE ciphertext) elsewhere
+    a = pc.random_cts(M, level, batch, 2, "a")
+    b = pc.random_cts(M, level, batch, 2, "b")
+    sample = [0, 101, batch - 1]
+    zs = {}
+    for i in sample:
+        zs[i] = (wl.slots_real(M.N // 2, 2, "a", i), wl.slots_real(M.N // 2, 2, "b", i))
+        a[i] = M.encrypt(zs[i][0], scale, level, ("a", i))
+        b[i] = M.encrypt(zs[i][1], scale, level, ("b", i))
+    da, db = be.to_dev(a), be.to_dev(b)
+    out = be.empty(batch, 2, level - 1, M.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+    ctx.hmul_relin_rescale(da, db, be.to_dev(M.rlk), out, level, batch, ws)
+    got = be.to_host(out).reshape(batch, 2, level - 1, M.N)
+    for i in sample:
+        assert np.array_equal(got[i], M.O.hmul_relin_rescale(a[i], b[i], M.rlk, level)), "item %d" % i
+        dec = ctx.decode(ctx.decrypt(M.s, got[i], level - 1), level - 1, scale * scale / M.O.q[level - 1])
+        assert np.max(np.abs(dec - zs[i][0] * zs[i][1])) < 1e-3
+    # deterministic: a second run gives the same bits everywhere
+    out2 = be.empty(batch, 2, level - 1, M.N)
+    ctx.hmul_relin_rescale(da, db, be.to_dev(M.rlk), out2, level, batch, ws)
+    assert np.array_equal(be.to_host(out2).reshape(got.shape), got)
+    # rotations: every ciphertext by one of the 8 offsets
+    announce("N=2^14 rotations")
+    for r in rots:
+        ctx.galois_key_register(r, be.to_dev(M.gk[r]))
+    pick = wl.rng(2, "rot.pick").integers(0, len(rots), size=batch)
+    rot = [rots[j] for j in pick]
+    outr = be.empty(batch, 2, level, M.N)
+    wsr = be.ws(ctx.workspace_bytes(ckksmi.OP_ROTATE, level, batch))
+    ctx.rotate(da, rot, outr, level, batch, wsr)
+    gotr = be.to_host(outr).reshape(batch, 2, level, M.N)
+    for i in sample:
+        assert np.array_equal(gotr[i], M.O.rotate(a[i], rot[i], M.gk[rot[i]], level)), "rotation of item %d" % i
+        dec = ctx.decode(ctx.decrypt(M.s, gotr[i], level), level, scale)
+        assert np.max(np.abs(dec - np.roll(zs[i][0], -rot[i]))) < 1e-3
+
+
+def test_2e16_hybrid_shape_sampled(be):
+    """N=2^16, 24x50-bit + 3 special primes (8 digits of 3): batch 64 in the benchmark's launch
+    configuration, one item compared word for word with the oracle at levels 24 and 23"""
+    announce("N=2^16 hybrid batch 64, sampled parity")
+    p = wl.PRESETS["act_2e16"]
+    M = pc.make_material(C4, 4)
+    ctx = be.context(*C4)
+    batch = p.batch
+    evk = be.to_dev(M.rlk)
+    for level, pick in ((24, 17), (23, 63)):
+        a = pc.random_cts(M, level, batch, 4, ("a", level))
+        b = pc.random_cts(M, level, batch, 4, ("b", level))
+        out = be.empty(batch, 2, level - 1, M.N)
+        ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+        ctx.hmul_relin_rescale(be.to_dev(a), be.to_dev(b), evk, out, level, batch, ws)
+        got = be.to_host(out).reshape(batch, 2, level - 1, M.N)
+        announce("oracle for item %d at level %d" % (pick, level))
+        assert np.array_equal(got[pick], M.O.hmul_relin_rescale(a[pick], b[pick], M.rlk, level))
+        del ws, out
+
+
+def test_activation_schedule_on_gpu(be):
+    """x^2 then 0.5 + 0.25y - 0.02y^3 with relin + rescale at each level, against the oracle's
+    composition (bit-exact) and the float polynomial"""
+    announce("activation schedule")
+    from paper_1911_11377_amd import activation
+
+    shape = (10, 6, 50, 3, 51, 3)
+    M = pc.make_material(shape, 5)
+    O = M.O
+    ctx = be.context(*shape)
+    level, s, batch = 6, 2.0**50, 3
+    zs = [wl.slots_real(O.N // 2, 5, i) for i in range(batch)]
+    x = _encrypt_batch(M, zs, s, level, "x")
+    consts = activation.poly3_constants(O.q, level - 1, s * s / O.q[level - 1])
+    dx, evk = be.to_dev(x), be.to_dev(M.rlk)
+    y = be.empty(batch, 2, level - 1, O.N)
+    out = be.empty(batch, 2, level - 3, O.N)
+    ws = be.ws(activation.workspace_bytes(ctx, level, batch))
+    activation.square(ctx, dx, evk, y, level, batch, ws)
+    activation.poly3(ctx, y, evk, out, level - 1, batch, consts, ws)
+    gy = be.to_host(y).reshape(batch, 2, level - 1, O.N)
+    go = be.to_host(out).reshape(batch, 2, level - 3, O.N)
+    for i in range(batch):
+        oy = O.square(x[i], M.rlk, level)
+        assert np.array_equal(gy[i], oy)
+        assert np.array_equal(go[i], O.poly3(oy, M.rlk, level - 1, consts.c_m002, consts.c_025, consts.c_05))
+        yv = zs[i].real ** 2
+        dec = ctx.decode(ctx.decrypt(M.s, go[i], level - 3), level - 3, consts.out_scale)
+        assert np.max(np.abs(dec.real - (0.5 + 0.25 * yv - 0.02 * yv**3))) < 1e-3
+
+
+def test_edge_cases(be):
+    announce("edge cases")
+    ctx = be.context(*TINY)
+    buf = be.empty(2, 2, 3, 4096)
+    ctx.add(buf, buf, buf, 3, 0)  # empty batch: nothing enqueued
+    with pytest.raises(ckksmi.CkksmiError) as e:
+        ctx.rescale(buf, be.empty(2, 2, 2, 4096), 1, 2, be.ws(1 << 20))
+    assert e.value.code == ckksmi.ELEVEL
+    with pytest.raises(ckksmi.CkksmiError) as e:
+        ctx.relin(be.empty(2, 3, 3, 4096), buf, buf, 3, 2, be.ws(64))
+    assert e.value.code == ckksmi.EWORKSPACE
+    with pytest.raises(ckksmi.CkksmiError) as e:
+        ctx.add(buf, buf, buf, 4, 1)
+    assert e.value.code == ckksmi.ELEVEL
