@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweep (keeps a profile to the timed steps)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of the input batch (known size) so that profiler byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (every ciphertext is independent, "
@@ -113,11 +116,17 @@ def main():
                 "all_transforms_GBps": round(16 * N * ntt_limbs / (ntt_ms * 1e-3) / 1e9, 1),
                 "kernels": kernels}
 
+    if args.copy_probe:
+        probe = torch.empty_like(a)
+        probe.copy_(a)  # reads and writes a.numel()*8 bytes
+        torch.cuda.synchronize()
+        del probe
+
     # ---- plain transform sweep: batch x 2 x (level + k) limbs, forward then inverse, in place
     idx = list(range(level)) + [p.n_q + m for m in range(p.k)]
     limbs = uniform_residues(torch, [ctx.moduli[t] for t in idx], (batch * 2,), N, gen)
     ntt = {}
-    for name, fn in (("fwd", ctx.ntt), ("inv", ctx.intt)):
+    for name, fn in (() if args.no_sweep else (("fwd", ctx.ntt), ("inv", ctx.intt))):
         fn(limbs, idx, batch * 2)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
