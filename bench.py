@@ -37,6 +37,7 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         # a limb transform reads and writes its limb once (16N bytes); it is done in two
         # kernels here, each credited with half of that
         "ntt_fwd_kernel<true>": w, "ntt_fwd_kernel<false>": w, "ntt_inv_kernel<false>": w, "ntt_inv_kernel<true>": w,
+        "ntt_v2_kernel<false, true>": w, "ntt_v2_kernel<false, false>": w, "ntt_v2_kernel<true, false>": w, "ntt_v2_kernel<true, true>": w,
         "tensor_kernel": 7 * w,                       # 4 limbs in, 3 out
         "modup_kernel": w * (1.0 / E * min(alpha, level) + 1),   # per output limb: its share of the digit's source limbs + itself
         "inner_product_kernel": w * (beta + 2 + 2.0 * beta / batch),  # beta inputs, 2 outputs, key read once per batch
@@ -109,7 +110,7 @@ def main():
     bpu = bytes_per_unit(dom, N, level, p.k, p.alpha, batch)
     achieved = bpu * units / (ms * 1e-3) / 1e9
     ntt_ms = sum(prof[n][0] for n in prof if n.startswith("ntt_"))
-    ntt_limbs = sum(prof[n][2] for n in prof if n in ("ntt_fwd_kernel<false>", "ntt_inv_kernel<false>"))
+    ntt_limbs = sum(prof[n][2] for n in prof if n in ("ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>"))
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "avg_launch_ms": round(ms / launches, 4), "bytes_per_launch": bpu * units / launches,

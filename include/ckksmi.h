@@ -196,7 +196,8 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_COUNT 13
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
-const char *ckksmi_kernel_class_name(int kernel_class);
+/* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */
+const char *ckksmi_kernel_class_name(const ckksmi_ctx *ctx, int kernel_class);
 
 #ifdef __cplusplus
 }

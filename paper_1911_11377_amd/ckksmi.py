@@ -76,7 +76,7 @@ SIGNATURES = {
     "ckksmi_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_profile_enable": [VP, C.c_int],
     "ckksmi_profile_read": [VP, C.c_int, f64p, C.POINTER(C.c_longlong), f64p],
-    "ckksmi_kernel_class_name": [C.c_int],
+    "ckksmi_kernel_class_name": [VP, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
 K_COUNT = 13
@@ -328,5 +328,5 @@ class Context:
             ms, n, u = C.c_double(0), C.c_longlong(0), C.c_double(0)
             self._call("ckksmi_profile_read", self._h, kid, C.byref(ms), C.byref(n), C.byref(u))
             if n.value:
-                out[self._L.ckksmi_kernel_class_name(kid).decode()] = (ms.value, n.value, u.value)
+                out[self._L.ckksmi_kernel_class_name(self._h, kid).decode()] = (ms.value, n.value, u.value)
         return out

@@ -10,6 +10,7 @@
 
 #include "ckksmi_internal.h"
 #include "kernels.h"
+#include "ntt_v2.h"
 
 // Launch `kern`; when profiling is on, bracket it with two events on the same stream and
 // remember them under kernel class `kid` together with `units` of algorithmic work.
@@ -88,20 +89,41 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     // limbs actually transformed (the key-switch map skips the limbs of each digit itself)
     const double limbs_work = M.mode == 1 ? (double)items * ((double)M.per_item - M.level) : (double)limbs;
     dim3 grow(limbs, (N1 + R - 1) / R), gcol(limbs, N2 / NTT_TC);
+    // register-tiled kernels: rows of 256 for 2^13 <= N <= 2^16, columns of 256 for N = 2^16
+    const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = c->logN == 16;
+    NttV2Args V;
+    V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = A.tw; V.tw_last = A.tw_last; V.logN = A.logN; V.map = M;
+    V.items = (int)items;
+    const unsigned tiles = N >= 4096u ? N / 4096u : 1u;
+    // enough workgroups to fill the chip, otherwise as many items per workgroup as possible (twiddle reuse)
+    unsigned zchunks = ((unsigned)c->ntt_target_wgs + tiles * M.per_item - 1) / (tiles * M.per_item);
+    if (zchunks > items) zchunks = (unsigned)items;
+    if (zchunks < 1) zchunks = 1;
+    V.items_per_z = (int)((items + zchunks - 1) / zchunks);
+    zchunks = (unsigned)((items + V.items_per_z - 1) / V.items_per_z);
+    dim3 gv2(tiles, M.per_item, zchunks);
     if (forward) {
         if (A.LA) {
-            KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, ntt_fwd_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
+            if (v2_cols) KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, (ntt_v2_kernel<false, true>), gv2, dim3(V2_THREADS), st, V);
+            else KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, ntt_fwd_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
             // second pass works in place on dst
             A.src = (const u64d *)dst;
             A.map.src_item_stride = A.map.dst_item_stride;
+            V.src = A.src;
+            V.map.src_item_stride = V.map.dst_item_stride;
         }
-        KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, ntt_fwd_kernel<false>, grow, dim3(NTT_THREADS), st, A);
+        if (v2_rows) KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, (ntt_v2_kernel<false, false>), gv2, dim3(V2_THREADS), st, V);
+        else KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, ntt_fwd_kernel<false>, grow, dim3(NTT_THREADS), st, A);
     } else {
-        KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
+        if (v2_rows) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, (ntt_v2_kernel<true, false>), gv2, dim3(V2_THREADS), st, V);
+        else KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
         if (A.LA) {
             A.src = (const u64d *)dst;
             A.map.src_item_stride = A.map.dst_item_stride;
-            KL(c, CKKSMI_K_NTT_INV_COL, limbs_work, ntt_inv_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
+            V.src = A.src;
+            V.map.src_item_stride = V.map.dst_item_stride;
+            if (v2_cols) KL(c, CKKSMI_K_NTT_INV_COL, limbs_work, (ntt_v2_kernel<true, true>), gv2, dim3(V2_THREADS), st, V);
+            else KL(c, CKKSMI_K_NTT_INV_COL, limbs_work, ntt_inv_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
         }
     }
 }
@@ -622,7 +644,13 @@ extern "C" int ckksmi_profile_read(ckksmi_ctx *c, int kernel_class, double *tota
     return CKKSMI_OK;
 }
 
-extern "C" const char *ckksmi_kernel_class_name(int kernel_class) {
+extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_class) {
+    if (c && kernel_class >= 0 && kernel_class < 4) {
+        static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
+                                    "ntt_v2_kernel<true, true>"};
+        const bool cols = kernel_class == CKKSMI_K_NTT_FWD_COL || kernel_class == CKKSMI_K_NTT_INV_COL;
+        if (cols ? c->logN == 16 : (c->logN >= 13 && c->logN <= 16)) return v2[kernel_class];
+    }
     static const char *names[CKKSMI_K_COUNT] = {"ntt_fwd_kernel<true>", "ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_inv_kernel<true>",
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",

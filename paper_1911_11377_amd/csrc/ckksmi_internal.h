@@ -63,6 +63,7 @@ struct ProfRec { int kid; double units; void *start, *stop; };
 
 struct ckksmi_ctx {
     bool prof_on = false;
+    int ntt_target_wgs = 4096;  // workgroups a transform launch aims for before it starts looping over items
     std::vector<ProfRec> prof;
 
     int logN = 0, n_q = 0, k = 0, alpha = 1, T = 0, beta_top = 0;

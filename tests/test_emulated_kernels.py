@@ -18,7 +18,8 @@ def be():
     return pc.EmuBackend()
 
 
-@pytest.mark.parametrize("shape", [TINY, (2, 2, 20, 1, 21, 1), (9, 2, 50, 1, 51, 1), (12, 1, 40, 1, 41, 1), TWO_PASS])
+@pytest.mark.parametrize("shape", [TINY, (2, 2, 20, 1, 21, 1), (9, 2, 50, 1, 51, 1), (12, 1, 40, 1, 41, 1), TWO_PASS,
+                                   (14, 1, 50, 1, 51, 1), (16, 1, 50, 1, 51, 1), (16, 2, 30, 0, 31, 1)])
 def test_emulated_ntt(be, shape):
     pc.case_ntt(be, shape, seed=100)
 
@@ -54,3 +55,11 @@ def test_emulated_rotate(be, shape, level):
 def test_emulated_conv(be):
     pc.case_conv(be, TINY, seed=107, Cin=2, H=5, W=5, Oc=9, kh=3, stride=2, pad=0)
     pc.case_conv(be, TINY, seed=108, Cin=1, H=4, W=4, Oc=2, kh=3, stride=1, pad=1, level=2)
+
+
+def test_emulated_item_loop_and_composite_at_2e16(be, monkeypatch):
+    """N = 2^16: both register-tiled passes, with workgroups looping over several items"""
+    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "16")
+    pc.case_ntt(be, (16, 1, 50, 1, 51, 1), seed=109, batch=3)
+    pc.case_ntt(be, (13, 2, 50, 1, 51, 1), seed=110, batch=3)
+    pc.case_relin_and_composite(be, (16, 2, 50, 1, 51, 1), seed=111, batch=2, levels=[2])
