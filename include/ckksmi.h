@@ -193,7 +193,11 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_MACPREP 10
 #define CKKSMI_K_MAC 11
 #define CKKSMI_K_ELEMWISE 12
-#define CKKSMI_K_COUNT 13
+#define CKKSMI_K_CONV_COLS_MODUP 13 /* ModUp fused into the strided pass of the forward transform */
+#define CKKSMI_K_CONV_COLS_DIV 14   /* DivRound conversion fused likewise */
+#define CKKSMI_K_ROWS_INNER 15      /* contiguous pass fused with the inner product */
+#define CKKSMI_K_ROWS_FINAL 16      /* contiguous pass fused with DivRound's last step */
+#define CKKSMI_K_COUNT 17
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

@@ -6,11 +6,13 @@
 #endif
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "ckksmi_internal.h"
 #include "kernels.h"
 #include "ntt_v2.h"
+#include "ks_fused.h"
 
 // Launch `kern`; when profiling is on, bracket it with two events on the same stream and
 // remember them under kernel class `kid` together with `units` of algorithmic work.
@@ -72,7 +74,9 @@ LimbMap table_map(const int *index, int n_limbs, size_t src_stride, size_t dst_s
 }
 
 // transform `items` groups of map.per_item limbs; forward: coefficient -> evaluation
-void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const LimbMap &M, size_t items, hipStream_t st) {
+// passes: 3 = whole transform, 1 = strided (column) pass only, 2 = contiguous (row) pass only
+void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const LimbMap &M, size_t items, hipStream_t st,
+                const FinConst *fin = nullptr, int passes = 3) {
     if (items == 0 || M.per_item == 0) return;
     NttArgs A;
     A.src = (const u64d *)src;
@@ -92,7 +96,7 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     // register-tiled kernels: rows of 256 for 2^13 <= N <= 2^16, columns of 256 for N = 2^16
     const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = c->logN == 16;
     NttV2Args V;
-    V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = A.tw; V.tw_last = A.tw_last; V.logN = A.logN; V.map = M;
+    V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = A.tw; V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M;
     V.items = (int)items;
     const unsigned tiles = N >= 4096u ? N / 4096u : 1u;
     // enough workgroups to fill the chip, otherwise as many items per workgroup as possible (twiddle reuse)
@@ -103,7 +107,7 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     zchunks = (unsigned)((items + V.items_per_z - 1) / V.items_per_z);
     dim3 gv2(tiles, M.per_item, zchunks);
     if (forward) {
-        if (A.LA) {
+        if (A.LA && (passes & 1)) {
             if (v2_cols) KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, (ntt_v2_kernel<false, true>), gv2, dim3(V2_THREADS), st, V);
             else KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, ntt_fwd_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
             // second pass works in place on dst
@@ -112,8 +116,10 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
             V.src = A.src;
             V.map.src_item_stride = V.map.dst_item_stride;
         }
-        if (v2_rows) KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, (ntt_v2_kernel<false, false>), gv2, dim3(V2_THREADS), st, V);
-        else KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, ntt_fwd_kernel<false>, grow, dim3(NTT_THREADS), st, A);
+        if (passes & 2) {
+            if (v2_rows) KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, (ntt_v2_kernel<false, false>), gv2, dim3(V2_THREADS), st, V);
+            else KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, ntt_fwd_kernel<false>, grow, dim3(NTT_THREADS), st, A);
+        }
     } else {
         if (v2_rows) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, (ntt_v2_kernel<true, false>), gv2, dim3(V2_THREADS), st, V);
         else KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
@@ -148,10 +154,154 @@ size_t ks_words_per_item(const ckksmi_ctx *c, int level) {
 }
 size_t rescale_words_per_item(const ckksmi_ctx *c, int level) { return c->N * (2 + 2 * (size_t)(level - 1)); }
 
+
+// ---- fused path, N = 2^16 -------------------------------------------------------------
+unsigned zchunks_for(const ckksmi_ctx *c, unsigned wgs_per_item, size_t items, int &items_per_z) {
+    unsigned z = ((unsigned)c->ntt_target_wgs + wgs_per_item - 1) / wgs_per_item;
+    if (z > items) z = (unsigned)items;
+    if (z < 1) z = 1;
+    items_per_z = (int)((items + z - 1) / z);
+    return (unsigned)((items + items_per_z - 1) / items_per_z);
+}
+
+void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t dst_stride, int slots, size_t items,
+                      int level, const DivRoundDev *D, double units, hipStream_t st) {
+    ConvColsArgs A;
+    memset(&A, 0, sizeof(A));
+    A.y = (const u64d *)y; A.y_item_stride = y_stride;
+    A.dst = (u64d *)dst; A.dst_item_stride = dst_stride;
+    A.modc = c->d_mod; A.tw = c->d_tw_fwd;
+    A.logN = c->logN; A.items = (int)items;
+    A.mode = mode;
+    A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.cc = c->d_modup_c;
+    if (D) A.D = *D;
+    const unsigned z = zchunks_for(c, 16u * slots, items, A.items_per_z);
+    KL(c, mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : CKKSMI_K_CONV_COLS_DIV, units, conv_cols_kernel, dim3(16, slots, z), dim3(V2_THREADS), st, A);
+}
+
+void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
+                       size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st) {
+    RowsFinalArgs A;
+    A.tmpA = (const u64d *)tmpA; A.x = (const u64d *)x; A.x_row_stride = x_row_stride;
+    A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride; A.add_both = add_both;
+    A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tw_fwd; A.Binv = Binv; A.logN = c->logN; A.nc = nc;
+    A.rows = rows;
+    const unsigned xch = zchunks_for(c, 16u * nc, rows, A.rows_per_x);
+    KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nc, rows_final_kernel, dim3(xch, 16, nc), dim3(V2_THREADS), st, A);
+}
+
+// fusion switches (ckksmi_ctx::fuse): which limb-wise steps ride on a transform pass
+enum { FUSE_MODUP = 1, FUSE_INNER = 2, FUSE_DIVCONV = 4, FUSE_FINAL = 8 };
+
+void launch_modup(ckksmi_ctx *c, const u64 *dcoef, const u64 *d_eval, size_t d_stride, u64 *dt, int items, int level, hipStream_t st) {
+    const size_t N = c->N;
+    const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    ModUpArgs MU;
+    MU.d_coef = (const u64d *)dcoef; MU.d_eval = (const u64d *)d_eval; MU.d_eval_item_stride = d_stride; MU.out = (u64d *)dt;
+    MU.modc = c->d_mod; MU.inv = c->d_modup_inv; MU.cc = c->d_modup_c;
+    MU.logN = c->logN; MU.level = level; MU.E = E; MU.n_q = c->n_q; MU.alpha = c->alpha; MU.beta = beta; MU.T = c->T;
+    KL(c, CKKSMI_K_MODUP, (double)items * beta * E, modup_kernel, dim3(ew_blocks(N), beta, items), dim3(EW_THREADS), st, MU);
+}
+
+// DivRound of `rows` rows: dropped limbs (evaluation form) at b_limbs + r*b_stride (nb limbs, in place scratch allowed when
+// b_scratch == b_limbs), kept limbs at x + r*x_stride; out[r][i] = (x_i - NTT(r_i - h)) * Bbar^-1 (+ addend).
+void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, const int *bidx, const u64 *b_limbs, size_t b_stride,
+                   u64 *b_scratch, size_t bs_stride, const u64 *x, size_t x_stride, u64 *tmp, int nc, int rows, const u64 *addend,
+                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, hipStream_t st) {
+    const size_t N = c->N;
+    const bool fconv = (c->fuse & FUSE_DIVCONV) != 0, ffinal = (c->fuse & FUSE_FINAL) != 0;
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < nc; i++) idx[i] = i;
+    launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fconv ? fin : nullptr);
+    if (fconv) {
+        launch_conv_cols(c, 1, b_scratch, bs_stride, tmp, (size_t)nc * N, nc, rows, 0, &D, (double)rows * nc, st);
+    } else {
+        DivConvArgs DC;
+        DC.b_limbs = (const u64d *)b_scratch; DC.b_row_stride = bs_stride; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
+        DC.logN = c->logN; DC.nc = nc; DC.T = c->T;
+        KL(c, CKKSMI_K_DIVCONV, (double)rows * nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
+        launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 1);
+    }
+    if (ffinal) {
+        launch_rows_final(c, tmp, x, x_stride, addend, add_item_stride, add_comp_stride, add_both, out, D.Binv, nc, rows, st);
+    } else {
+        launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 2);
+        DivFinalArgs DF;
+        DF.x = (const u64d *)x; DF.x_row_stride = x_stride; DF.tmp = (const u64d *)tmp;
+        DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride; DF.add_both = add_both;
+        DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.logN = c->logN; DF.nc = nc;
+        KL(c, CKKSMI_K_DIVFINAL, (double)rows * nc, divround_final_kernel, dim3(ew_blocks(N), nc, rows), dim3(EW_THREADS), st, DF);
+    }
+}
+
+void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
+                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st) {
+    const size_t N = c->N;
+    const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    u64 *ycoef = ws;
+    u64 *dtA = ycoef + (size_t)items * level * N;
+    u64 *acc = dtA + (size_t)items * beta * E * N;
+    u64 *tmp = acc + (size_t)items * 2 * E * N;
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < level; i++) idx[i] = i;
+    LimbMap M1;
+    memset(&M1, 0, sizeof(M1));
+    M1.per_item = beta * E; M1.mode = 1; M1.level = level; M1.E = E; M1.n_q = c->n_q; M1.alpha = c->alpha;
+    M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
+    if (c->fuse & FUSE_MODUP) {
+        // y_i = d_i * qhat_i^-1 straight out of the inverse transform; conversion rides on the column pass
+        launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
+                   c->d_fin_modup + (size_t)level * c->n_q);
+        launch_conv_cols(c, 0, ycoef, (size_t)level * N, dtA, (size_t)beta * E * N, beta * E, items, level, nullptr,
+                         (double)items * (beta * E - level), st);
+    } else {
+        launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st);
+        launch_modup(c, ycoef, d_eval, d_stride, dtA, items, level, st);
+        launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 1);
+    }
+    if (c->fuse & FUSE_INNER) {
+        RowsInnerArgs RI;
+        RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
+        RI.modc = c->d_mod; RI.tw = c->d_tw_fwd;
+        RI.logN = c->logN; RI.level = level; RI.E = E; RI.n_q = c->n_q; RI.alpha = c->alpha; RI.beta = beta; RI.T = c->T;
+        KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(items, 16, E), dim3(V2_THREADS), st, RI, K);
+    } else {
+        launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
+        if (c->fuse & FUSE_MODUP) {
+            // the digit's own limbs were not copied by a ModUp kernel: the inner product reads them from d_eval
+        }
+        InnerArgs IA;
+        IA.dt = (const u64d *)dtA; IA.d_eval = (c->fuse & FUSE_MODUP) ? (const u64d *)d_eval : nullptr; IA.d_eval_item_stride = d_stride;
+        IA.alpha = c->alpha;
+        IA.acc = (u64d *)acc; IA.modc = c->d_mod;
+        IA.logN = c->logN; IA.level = level; IA.E = E; IA.n_q = c->n_q; IA.beta = beta; IA.T = c->T;
+        IA.items = items;
+        const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
+        KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
+    }
+    int sidx[CKKSMI_MAX_SPECIAL];
+    for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
+    divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
+                  acc, (size_t)E * N, tmp, level, items * 2, addend, add_item_stride, add_comp_stride, add_both, out, st);
+}
+
+void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u64 *ws, hipStream_t st) {
+    const size_t N = c->N;
+    u64 *last = ws;
+    u64 *tmp = last + (size_t)items * 2 * N;
+    int lidx[1] = {level - 1};
+    divround_rows(c, c->divround[1 + (level - 1)], c->d_fin_rescale + (level - 1), lidx, a + (size_t)(level - 1) * N, (size_t)level * N, last,
+                  N, a, (size_t)level * N, tmp, level - 1, items * 2, nullptr, 0, 0, 0, out, st);
+}
+
 // Key switch of `items` polynomials.  d_eval: item i's polynomial ([level][N], evaluation
 // form) at d_eval + i*d_stride.  out[i][c][l] = ks_c (+ addend).  ws: ks_words_per_item*items.
 void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
              size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st) {
+    if (c->fused) {
+        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st);
+        return;
+    }
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     u64 *dcoef = ws;
@@ -181,9 +331,11 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     launch_ntt(c, true, dt, dt, M1, items, st);
     // 4. inner product with the key
     InnerArgs IA;
-    IA.dt = (const u64d *)dt; IA.acc = (u64d *)acc; IA.modc = c->d_mod;
+    IA.dt = (const u64d *)dt; IA.d_eval = nullptr; IA.d_eval_item_stride = 0; IA.alpha = c->alpha; IA.acc = (u64d *)acc; IA.modc = c->d_mod;
     IA.logN = c->logN; IA.level = level; IA.E = E; IA.n_q = c->n_q; IA.beta = beta; IA.T = c->T;
-    KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, items), dim3(EW_THREADS), st, IA, K);
+    IA.items = items;
+    const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
+    KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
     // 5. ModDown: special limbs -> coefficient form, convert, back to evaluation form, combine
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
@@ -211,6 +363,10 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
 
 // out[i] = DivRound_{q_{level-1}}(a[i]); ws: rescale_words_per_item*items
 void rescale_core(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u64 *ws, hipStream_t st) {
+    if (c->fused) {
+        rescale_core_fused(c, a, out, items, level, ws, st);
+        return;
+    }
     const size_t N = c->N;
     u64 *last = ws;
     u64 *tmp = last + (size_t)items * 2 * N;
@@ -305,6 +461,46 @@ int dev_upload_tables(ckksmi_ctx *c) {
         d.hc = upload(c, h.hc.data(), h.hc.size(), ok);
         d.Binv = upload(c, h.Binv.data(), h.Binv.size(), ok);
         c->divround[which] = d;
+    }
+    // fused path: constants folded into the last stage of the inverse transforms
+    c->fused = c->logN == 16 && !getenv("CKKSMI_NO_FUSION");
+    if (const char *e = getenv("CKKSMI_FUSE")) c->fuse = atoi(e) & 15;  // tuning / test knob
+    if (c->fused) {
+        auto fin = [&](int t, u64 mult, u64 add) {
+            const u64 q = c->mod[t];
+            FinConst f;
+            f.ninv = make_wmul(hm::mulmod(c->h_ninv[t], mult, q), q);
+            f.wlast = make_wmul(hm::mulmod(hm::mulmod(c->h_inv[t][1], c->h_ninv[t], q), mult, q), q);
+            f.cadd = (double)add;
+            f.pad = 0.0;
+            return f;
+        };
+        std::vector<FinConst> fm((size_t)(c->n_q + 1) * c->n_q, fin(0, 1, 0));
+        for (int level = 1; level <= c->n_q; level++)
+            for (int i = 0; i < level; i++) {
+                const int lo = (i / c->alpha) * c->alpha;
+                const int nd = std::min(c->alpha, level - lo);
+                const u64 q = c->mod[i];
+                u64 hat = 1;
+                for (int b = 0; b < nd; b++)
+                    if (lo + b != i) hat = hm::mulmod(hat, c->mod[lo + b] % q, q);
+                fm[(size_t)level * c->n_q + i] = fin(i, hm::invmod(hat, q), 0);
+            }
+        c->d_fin_modup = upload(c, fm.data(), fm.size(), ok);
+        std::vector<FinConst> fd;
+        for (int m = 0; m < c->k; m++) {
+            const int t = c->n_q + m;
+            const u64 bm = c->mod[t];
+            u64 bhat = 1;
+            for (int m2 = 0; m2 < c->k; m2++)
+                if (m2 != m) bhat = hm::mulmod(bhat, c->mod[c->n_q + m2] % bm, bm);
+            const u64 inv = hm::invmod(bhat, bm);
+            fd.push_back(fin(t, inv, hm::mulmod((bm - 1) / 2, inv, bm)));
+        }
+        c->d_fin_moddown = upload(c, fd.data(), fd.size(), ok);
+        std::vector<FinConst> fr;
+        for (int i = 0; i < c->n_q; i++) fr.push_back(fin(i, 1, (c->mod[i] - 1) / 2));
+        c->d_fin_rescale = upload(c, fr.data(), fr.size(), ok);
     }
     if (!ok) { c->last_hip_error = (int)hipGetLastError(); return CKKSMI_EDEVICE; }
     return CKKSMI_OK;
@@ -654,6 +850,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
     static const char *names[CKKSMI_K_COUNT] = {"ntt_fwd_kernel<true>", "ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_inv_kernel<true>",
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
-                                                "elementwise kernels"};
+                                                "elementwise kernels", "conv_cols_kernel(ModUp)", "conv_cols_kernel(DivRound)",
+                                                "rows_inner_kernel", "rows_final_kernel"};
     return (kernel_class >= 0 && kernel_class < CKKSMI_K_COUNT) ? names[kernel_class] : "";
 }

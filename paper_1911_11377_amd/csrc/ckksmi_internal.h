@@ -59,6 +59,10 @@ struct DivRoundDev {
     const WMul *Binv;  // device [T]
 };
 
+// Last-stage constants of an inverse transform that also multiplies by a constant c and adds a
+// constant to every coefficient: ninv = c/N, wlast = c*psi^-brev(1)/N, result + cadd.
+struct FinConst { WMul ninv, wlast; double cadd, pad; };
+
 struct ProfRec { int kid; double units; void *start, *stop; };
 
 struct ckksmi_ctx {
@@ -87,6 +91,13 @@ struct ckksmi_ctx {
     // DivRound tables: index 0 = ModDown over specials, 1 + i = rescale dropping q_i
     std::vector<DivRoundDev> divround;
     std::vector<void *> dev_allocs;
+
+    // fused path (N = 2^16): last-stage constants of the inverse transforms that produce conversion inputs
+    FinConst *d_fin_modup = nullptr;    // [n_q + 1][n_q]  level, limb
+    FinConst *d_fin_moddown = nullptr;  // [k]
+    FinConst *d_fin_rescale = nullptr;  // [n_q]  dropped limb
+    bool fused = false;  // N = 2^16: register-tiled passes for everything, steps below optionally fused into them
+    int fuse = 13;       // bit 0 ModUp, 1 inner product, 2 DivRound conversion, 3 DivRound final step
 
     // registered Galois keys
     std::vector<std::pair<int, const u64 *>> galois;

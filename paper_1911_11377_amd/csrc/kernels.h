@@ -366,29 +366,106 @@ struct KeyTab {
 
 struct InnerArgs {
     const u64d *dt;  // [items][beta][E][N]
+    const u64d *d_eval;  // optional: when set, the limbs that belong to a digit are read from here (item i at + i*stride, [level][N])
+    unsigned long long d_eval_item_stride;
+    int alpha;
     u64d *acc;       // [items][2][E][N]
     const ModConst *modc;
     int logN, level, E, n_q, beta, T;
+    int items, items_per_z;
 };
 
-__global__ __launch_bounds__(EW_THREADS) void inner_product_kernel(InnerArgs A, KeyTab K) {
+// grid: x = word block, y = extended limb, z = chunk of items.  A thread keeps the key words of its
+// position (2*beta values) in registers and loops over the items of its chunk, so the key is read
+// once per chunk instead of once per item.
+#define INNER_MAX_BETA 16
+template <int BETA>
+__device__ __forceinline__ void inner_product_body(const InnerArgs &A, const KeyTab &K) {
     const unsigned N = 1u << A.logN;
     const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
     if (n >= N) return;
-    const unsigned x = blockIdx.y, item = blockIdx.z;
+    const unsigned x = blockIdx.y;
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
     const ModConst mc = A.modc[t];
-    const u64d *key = K.key[K.slot[item]];
-    double a0 = 0.0, a1 = 0.0;
-    for (int j = 0; j < A.beta; j++) {
-        const double v = u2d(A.dt[(((size_t)item * A.beta + j) * A.E + x) * N + n]);
-        const double k0 = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + n]);
-        const double k1 = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + n]);
-        a0 = reduce_balanced(a0 + mulmod(v, k0, mc.p, mc.pinv), mc.p, mc.pinv);
-        a1 = reduce_balanced(a1 + mulmod(v, k1, mc.p, mc.pinv), mc.p, mc.pinv);
+    const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
+    const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
+    const u64d *key_loaded = nullptr;
+    double k0[BETA], k1[BETA];
+    for (unsigned item = i0; item < i1; item++) {
+        const u64d *key = K.key[K.slot[item]];
+        if (key != key_loaded) {  // uniform across the workgroup
+#pragma unroll
+            for (int j = 0; j < BETA; j++) {
+                k0[j] = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + n]);
+                k1[j] = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + n]);
+            }
+            key_loaded = key;
+        }
+        double v[BETA];
+#pragma unroll
+        for (int j = 0; j < BETA; j++) {
+            const bool own = A.d_eval && (int)x < A.level && (int)x / A.alpha == j;
+            v[j] = own ? u2d(A.d_eval[(size_t)item * A.d_eval_item_stride + (size_t)x * N + n])
+                       : u2d(A.dt[(((size_t)item * BETA + j) * A.E + x) * N + n]);
+        }
+        double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+        for (int j = 0; j < BETA; j++) {
+            a0 = reduce_balanced(a0 + mulmod(v[j], k0[j], mc.p, mc.pinv), mc.p, mc.pinv);
+            a1 = reduce_balanced(a1 + mulmod(v[j], k1[j], mc.p, mc.pinv), mc.p, mc.pinv);
+        }
+        A.acc[(((size_t)item * 2 + 0) * A.E + x) * N + n] = d2u(canon_small(a0, mc.p));
+        A.acc[(((size_t)item * 2 + 1) * A.E + x) * N + n] = d2u(canon_small(a1, mc.p));
     }
-    A.acc[(((size_t)item * 2 + 0) * A.E + x) * N + n] = d2u(canon_small(a0, mc.p));
-    A.acc[(((size_t)item * 2 + 1) * A.E + x) * N + n] = d2u(canon_small(a1, mc.p));
+}
+
+// any number of digits: no key caching
+__device__ __forceinline__ void inner_product_generic(const InnerArgs &A, const KeyTab &K) {
+    const unsigned N = 1u << A.logN;
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= N) return;
+    const unsigned x = blockIdx.y;
+    const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+    const ModConst mc = A.modc[t];
+    const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
+    const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
+    for (unsigned item = i0; item < i1; item++) {
+        const u64d *key = K.key[K.slot[item]];
+        double a0 = 0.0, a1 = 0.0;
+        for (int j = 0; j < A.beta; j++) {
+            const bool own = A.d_eval && (int)x < A.level && (int)x / A.alpha == j;
+            const double v = own ? u2d(A.d_eval[(size_t)item * A.d_eval_item_stride + (size_t)x * N + n])
+                                 : u2d(A.dt[(((size_t)item * A.beta + j) * A.E + x) * N + n]);
+            const double k0 = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + n]);
+            const double k1 = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + n]);
+            a0 = reduce_balanced(a0 + mulmod(v, k0, mc.p, mc.pinv), mc.p, mc.pinv);
+            a1 = reduce_balanced(a1 + mulmod(v, k1, mc.p, mc.pinv), mc.p, mc.pinv);
+        }
+        A.acc[(((size_t)item * 2 + 0) * A.E + x) * N + n] = d2u(canon_small(a0, mc.p));
+        A.acc[(((size_t)item * 2 + 1) * A.E + x) * N + n] = d2u(canon_small(a1, mc.p));
+    }
+}
+
+__global__ __launch_bounds__(EW_THREADS) void inner_product_kernel(InnerArgs A, KeyTab K) {
+    switch (A.beta) {
+        case 1: inner_product_body<1>(A, K); break;
+        case 2: inner_product_body<2>(A, K); break;
+        case 3: inner_product_body<3>(A, K); break;
+        case 4: inner_product_body<4>(A, K); break;
+        case 5: inner_product_body<5>(A, K); break;
+        case 6: inner_product_body<6>(A, K); break;
+        case 7: inner_product_body<7>(A, K); break;
+        case 8: inner_product_body<8>(A, K); break;
+        case 9: inner_product_body<9>(A, K); break;
+        case 10: inner_product_body<10>(A, K); break;
+        case 11: inner_product_body<11>(A, K); break;
+        case 12: inner_product_body<12>(A, K); break;
+        case 13: inner_product_body<13>(A, K); break;
+        case 14: inner_product_body<14>(A, K); break;
+        case 15: inner_product_body<15>(A, K); break;
+        case 16: inner_product_body<16>(A, K); break;
+        default: inner_product_generic(A, K); break;
+    }
 }
 
 // ---------------------------------------------------------------- DivRound

@@ -1,0 +1,318 @@
+// Fused key-switch / DivRound kernels for N = 2^16 (256 x 256), built on the register-tiled
+// transform passes of ntt_v2.h.  They remove the HBM round trips between a transform and the
+// limb-wise step next to it:
+//
+//   conv_cols_kernel   : fast basis conversion (ModUp of a digit, or the conversion step of
+//                        DivRound) computed while loading the column pass of the forward
+//                        transform of its result -- the converted limb is never stored in
+//                        coefficient form;
+//   rows_inner_kernel  : row pass of the forward transform of every digit's extended limb,
+//                        multiplied by the switching key and accumulated over the digits in
+//                        registers -- the transformed limbs are never stored;
+//   rows_final_kernel  : row pass fused with DivRound's last step
+//                        out = (x - NTT(r - h)) * Bbar^-1 (+ addend).
+//
+// The conversion inputs y (y_i = d_i * qhat_i^-1 mod q_i, canonical) are produced by the inverse
+// transform itself: its last stage multiplies by 1/N anyway, so the extra constant rides along
+// (NttV2Args::fin).
+#pragma once
+#include "ntt_v2.h"
+
+#ifdef CKKSMI_EMULATE
+#define SCHED_FENCE() ((void)0)
+#else
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+
+// ------------------------------------------------------------------ column pass with conversion
+struct ConvColsArgs {
+    const u64d *y;                // source limbs, coefficient form, canonical; item i at y + i*y_item_stride
+    unsigned long long y_item_stride;
+    u64d *dst;                    // [items][slots][N] (column pass output, to be finished by a row pass)
+    unsigned long long dst_item_stride;
+    const ModConst *modc;
+    const WMul *tw;               // forward table [T][N]
+    int logN, items, items_per_z;
+    int mode;                     // 0: ModUp (slot = j*E + x), 1: DivRound (slot = kept limb i)
+    int level, E, n_q, alpha, T;  // ModUp
+    const WMul *cc;               // ModUp constants [beta_top][alpha][alpha][T]
+    DivRoundDev D;                // DivRound constants; its nb source limbs are y's limbs 0..nb-1
+};
+
+template <bool P51, int NSRC>
+__device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *lds, int t, unsigned slot, unsigned first_src, const WMul *W,
+                                               double hsub) {
+    const unsigned N = 1u << A.logN;
+    const double p = A.modc[t].p, pinv = A.modc[t].pinv;
+    const WMul *tw = A.tw + (size_t)t * N;
+    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
+    WMul tw1[15], tw2[15];
+    load_twiddles(tw, 1u, hi4, tw1, tw2);
+    WMul Wc[NSRC];
+#pragma unroll
+    for (int a = 0; a < NSRC; a++) Wc[a] = W[a];
+    const unsigned c = blockIdx.x * 16 + lo4;
+    const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
+    const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
+    constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
+    for (unsigned it = i0; it < i1; it++) {
+        const u64d *ysrc = A.y + (size_t)it * A.y_item_stride + (size_t)first_src * N;
+        u64d *dst = A.dst + (size_t)it * A.dst_item_stride + (size_t)slot * N;
+        // all source words first (one memory latency instead of one per source limb), then the arithmetic
+        u64d raw[NSRC][16];
+#pragma unroll
+        for (int a = 0; a < NSRC; a++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) raw[a][e] = ysrc[(size_t)a * N + (size_t)(hi4 + 16 * e) * 256 + c];
+        double x[16];
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            double v = -hsub;
+#pragma unroll
+            for (int a = 0; a < NSRC; a++) v += mulmod_w(u2d(raw[a][e]), Wc[a].w, Wc[a].wp, p);
+            // |v| <= p + NSRC*0.75p < 2^53: bring into the balanced range the round schedule assumes
+            x[e] = reduce_balanced(v, p, pinv);
+        }
+        fwd_round<F1>(x, tw1, p, pinv);
+#pragma unroll
+        for (int e = 0; e < 16; e++) lds[(hi4 + 16 * e) * 16 + lo4] = x[e];
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 16; e++) x[e] = lds[(16 * hi4 + e) * 16 + lo4];
+        fwd_round<F2>(x, tw2, p, pinv);
+#pragma unroll
+        for (int e = 0; e < 16; e++) dst[(size_t)(16 * hi4 + e) * 256 + c] = d2u(canon(x[e], p, pinv));
+        __syncthreads();
+    }
+}
+
+template <bool P51>
+__device__ __forceinline__ void conv_cols_dispatch(const ConvColsArgs &A, double *lds, int t, unsigned slot, unsigned first_src, int nsrc,
+                                                   const WMul *W, double hsub) {
+    switch (nsrc) {
+        case 1: conv_cols_body<P51, 1>(A, lds, t, slot, first_src, W, hsub); break;
+        case 2: conv_cols_body<P51, 2>(A, lds, t, slot, first_src, W, hsub); break;
+        case 3: conv_cols_body<P51, 3>(A, lds, t, slot, first_src, W, hsub); break;
+        default: conv_cols_body<P51, 4>(A, lds, t, slot, first_src, W, hsub); break;
+    }
+}
+
+// grid: x = column tile (16), y = slot, z = chunk of items
+__global__ __launch_bounds__(V2_THREADS) void conv_cols_kernel(ConvColsArgs A) {
+    __shared__ double lds[16 * V2_GS];
+    const unsigned slot = blockIdx.y;
+    int t, nsrc;
+    unsigned first_src;
+    double hsub = 0.0;
+    WMul W[CKKSMI_MAX_ALPHA];
+#pragma unroll
+    for (int a = 0; a < CKKSMI_MAX_ALPHA; a++) W[a] = WMul{0.0, 0.0};
+    if (A.mode == 0) {
+        const unsigned j = slot / (unsigned)A.E, x = slot % (unsigned)A.E;
+        const int lo = (int)j * A.alpha;
+        nsrc = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
+        if ((int)x >= lo && (int)x < lo + nsrc) return;  // limb of the digit itself: already in evaluation form
+        t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+        first_src = (unsigned)lo;
+        const size_t row = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
+#pragma unroll
+        for (int a = 0; a < CKKSMI_MAX_ALPHA; a++)
+            if (a < nsrc) W[a] = A.cc[(row + a) * A.T + t];
+    } else {
+        t = (int)slot;
+        nsrc = A.D.nb;
+        first_src = 0;
+#pragma unroll
+        for (int a = 0; a < CKKSMI_MAX_ALPHA; a++)
+            if (a < nsrc) W[a] = A.D.conv[(size_t)a * A.T + t];
+        hsub = A.D.hc[t];
+    }
+    if (A.modc[t].p >= 1125899906842624.0)
+        conv_cols_dispatch<true>(A, lds, t, slot, first_src, nsrc, W, hsub);
+    else
+        conv_cols_dispatch<false>(A, lds, t, slot, first_src, nsrc, W, hsub);
+}
+
+// ------------------------------------------------------------------ row pass helper
+// round-2 twiddles of a thread (registers) and the round-1 twiddles of the tile's 16 rows (LDS, [16][16])
+__device__ __forceinline__ void load_row_twiddles(const WMul *tw, unsigned N1, unsigned tile, unsigned hi4, unsigned lo4, WMul *tw1_lds,
+                                                  WMul (&tw2)[15]) {
+    const unsigned base1 = N1 + tile * 16 + hi4;
+#pragma unroll
+    for (int s = 0; s < 4; s++)
+#pragma unroll
+        for (int b = 0; b < (1 << s); b++) tw2[(1 << s) - 1 + b] = tw[((16u * base1 + lo4) << s) + b];
+    if (lo4 < 15) {
+        // entry i = (1<<s)-1+b  ->  tw[(base1 << s) + b]
+        const unsigned i = lo4, s = (i >= 7) ? 3 : (i >= 3) ? 2 : (i >= 1) ? 1 : 0, b = i - ((1u << s) - 1);
+        tw1_lds[hi4 * 16 + i] = tw[(base1 << s) + b];
+    }
+    __syncthreads();
+}
+
+// Finish the forward transform of one 16-row tile (column pass already done) and leave the
+// canonical results in LDS in the padded layout: word (row g, position q) at g*V2_GS + (q/16)*17 + q%16.
+// Ends with a barrier; the caller must put a barrier before the next call.
+template <bool P51>
+__device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, const WMul *tw1_lds, const WMul (&tw2)[15], double p,
+                                                double pinv, unsigned hi4, unsigned lo4) {
+    constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
+    double *grp = lds + hi4 * V2_GS;
+    double x[16];
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = u2d(tile[hi4 * 256 + lo4 + 16 * e]);
+    {
+        // round-1 twiddles are the same for the 16 lanes of a row: kept in LDS, not in registers
+        WMul tw1[15];
+#pragma unroll
+        for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
+        fwd_round<F1>(x, tw1, p, pinv);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = x[e];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
+    fwd_round<F2>(x, tw2, p, pinv);
+#pragma unroll
+    for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(x[e], p, pinv);
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------ row pass + inner product
+struct RowsInnerArgs {
+    const u64d *dtA;     // [items][beta][E][N] column-pass output of the converted limbs
+    const u64d *d_eval;  // evaluation-form source polynomial, item i at d_eval + i*d_eval_item_stride, [level][N]
+    unsigned long long d_eval_item_stride;
+    u64d *acc;           // [items][2][E][N]
+    const ModConst *modc;
+    const WMul *tw;      // forward table
+    int logN, level, E, n_q, alpha, beta, T;
+};
+
+template <bool P51>
+__device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const KeyTab &K, double *lds, WMul *tw1_lds, int t, unsigned x) {
+    const unsigned N = 1u << A.logN, N1 = N >> 8;
+    const double p = A.modc[t].p, pinv = A.modc[t].pinv;
+    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
+    const unsigned item = blockIdx.x, tile = blockIdx.y;
+    WMul tw2[15];
+    load_row_twiddles(A.tw + (size_t)t * N, N1, tile, hi4, lo4, tw1_lds, tw2);
+    const u64d *key = K.key[K.slot[item]];
+    const size_t tile0 = (size_t)tile * 4096;
+    double a0[16], a1[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) a0[i] = a1[i] = 0.0;
+    for (int j = 0; j < A.beta; j++) {
+        const int lo = j * A.alpha;
+        const bool own = (int)x >= lo && (int)x < lo + A.alpha && (int)x < A.level;
+        const u64d *k0 = key + (((size_t)j * 2 + 0) * A.T + t) * N + tile0;
+        const u64d *k1 = key + (((size_t)j * 2 + 1) * A.T + t) * N + tile0;
+        if (own) {
+            const u64d *src = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0;
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const double v = u2d(src[i * 256 + tid]);
+                a0[i] = reduce_balanced(a0[i] + mulmod(v, u2d(k0[i * 256 + tid]), p, pinv), p, pinv);
+                a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(k1[i * 256 + tid]), p, pinv), p, pinv);
+                if ((i & 3) == 3) SCHED_FENCE();  // keep at most four positions' loads in flight (register pressure)
+            }
+        } else {
+            const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
+            rows_fwd_to_lds<P51>(src, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const double v = lds[i * V2_GS + hi4 * 17 + lo4];
+                a0[i] = reduce_balanced(a0[i] + mulmod(v, u2d(k0[i * 256 + tid]), p, pinv), p, pinv);
+                a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(k1[i * 256 + tid]), p, pinv), p, pinv);
+                if ((i & 3) == 3) SCHED_FENCE();
+            }
+            __syncthreads();
+        }
+    }
+    u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
+    u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        o0[i * 256 + tid] = d2u(canon_small(a0[i], p));
+        o1[i * 256 + tid] = d2u(canon_small(a1[i], p));
+    }
+}
+
+// grid: x = item (fastest: workgroups sharing a key tile run together), y = row tile (16), z = extended limb
+__global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_kernel(RowsInnerArgs A, KeyTab K) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ WMul tw1_lds[16 * 16];
+    const unsigned x = blockIdx.z;
+    const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+    if (A.modc[t].p >= 1125899906842624.0)
+        rows_inner_body<true>(A, K, lds, tw1_lds, t, x);
+    else
+        rows_inner_body<false>(A, K, lds, tw1_lds, t, x);
+}
+
+// ------------------------------------------------------------------ row pass + DivRound final step
+struct RowsFinalArgs {
+    const u64d *tmpA;    // [rows][nc][N] column-pass output of (r_i - h)
+    const u64d *x;       // kept limbs, evaluation form: row r, limb i at x + r*x_row_stride + i*N
+    unsigned long long x_row_stride;
+    const u64d *addend;  // optional: row r limb i at addend + (r/2)*add_item_stride + (r%2)*add_comp_stride + i*N
+    unsigned long long add_item_stride, add_comp_stride;
+    int add_both;
+    u64d *out;           // [rows][nc][N]
+    const ModConst *modc;
+    const WMul *tw;
+    const WMul *Binv;    // [T]
+    int logN, nc;
+    int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
+};
+
+template <bool P51>
+__device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *lds, WMul *tw1_lds, int i) {
+    const unsigned N = 1u << A.logN, N1 = N >> 8;
+    const double p = A.modc[i].p, pinv = A.modc[i].pinv;
+    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
+    const unsigned tile = blockIdx.y;
+    WMul tw2[15];
+    load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
+    const size_t tile0 = (size_t)tile * 4096;
+    const WMul W = A.Binv[i];
+    const unsigned r0 = blockIdx.x * (unsigned)A.rows_per_x;
+    const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
+    for (unsigned row = r0; row < r1; row++) {
+        const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
+        u64d *out = A.out + ((size_t)row * A.nc + i) * N + tile0;
+        const bool add = A.addend && (A.add_both || (row & 1u) == 0);
+        const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
+        // operands of the last step are requested before the transform so that their latency overlaps it
+        u64d xr[16], ar[16];
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            xr[q] = xin[q * 256 + tid];
+            ar[q] = ad[q * 256 + tid];
+        }
+        rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.nc + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            const double r = lds[q * V2_GS + hi4 * 17 + lo4];
+            double v = canon(mulmod_w(u2d(xr[q]) - r, W.w, W.wp, p), p, pinv);
+            if (add) {
+                v += u2d(ar[q]);
+                v = v >= p ? v - p : v;
+            }
+            out[q * 256 + tid] = d2u(v);
+        }
+        __syncthreads();
+    }
+}
+
+// grid: x = chunk of rows (item, component), y = row tile (16), z = kept limb
+__global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ WMul tw1_lds[16 * 16];
+    const int i = (int)blockIdx.z;
+    if (A.modc[i].p >= 1125899906842624.0)
+        rows_final_body<true>(A, lds, tw1_lds, i);
+    else
+        rows_final_body<false>(A, lds, tw1_lds, i);
+}

@@ -29,6 +29,7 @@ struct NttV2Args {
     const ModConst *modc;
     const WMul *tw;       // [T][N] table of the direction
     const WMul *tw_last;  // [T] inverse only
+    const FinConst *fin;  // optional, inverse column pass: per limb slot, replaces the 1/N constants of the last stage
     int logN;
     int items, items_per_z;
     LimbMap map;
@@ -109,7 +110,11 @@ __device__ __forceinline__ void ntt_v2_body(const NttV2Args &A, double *lds, int
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
     WMul tw1[15], tw2[15];
     WMul ninv = tw[0], wlast = tw[0];
-    if (INV) wlast = A.tw_last[t];
+    double cadd = 0.0;
+    if (INV) {
+        wlast = A.tw_last[t];
+        if (COLS && A.fin) { ninv = A.fin[li].ninv; wlast = A.fin[li].wlast; cadd = A.fin[li].cadd; }
+    }
     // COLS: column c = lo4 of tile blockIdx.x, lane = hi4.  rows: sub-transform = row hi4 of the tile, lane = lo4.
     const unsigned lane = COLS ? hi4 : lo4;
     const unsigned row = blockIdx.x * 16 + hi4;  // rows pass only
@@ -148,7 +153,7 @@ __device__ __forceinline__ void ntt_v2_body(const NttV2Args &A, double *lds, int
                 for (int e = 0; e < 16; e++) x[e] = lds[(hi4 + 16 * e) * 16 + lo4];
                 inv_round<I2, true>(x, tw1, p, pinv, ninv, wlast);
 #pragma unroll
-                for (int e = 0; e < 16; e++) dst[(size_t)(hi4 + 16 * e) * 256 + c] = d2u(canon(x[e], p, pinv));
+                for (int e = 0; e < 16; e++) dst[(size_t)(hi4 + 16 * e) * 256 + c] = d2u(canon(x[e] + cadd, p, pinv));
             }
             __syncthreads();
         } else {

@@ -63,3 +63,22 @@ def test_emulated_item_loop_and_composite_at_2e16(be, monkeypatch):
     pc.case_ntt(be, (16, 1, 50, 1, 51, 1), seed=109, batch=3)
     pc.case_ntt(be, (13, 2, 50, 1, 51, 1), seed=110, batch=3)
     pc.case_relin_and_composite(be, (16, 2, 50, 1, 51, 1), seed=111, batch=2, levels=[2])
+
+
+def test_emulated_fused_hybrid_at_2e16(be, monkeypatch):
+    """N = 2^16 with 3-prime digits: fused ModUp / inner product / ModDown / rescale kernels, partial last digit"""
+    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "64")
+    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=112, batch=2, levels=[4, 2])
+    pc.case_rescale(be, (16, 3, 50, 0, 51, 1), seed=113, batch=2, levels=[3])
+
+
+def test_emulated_unfused_path_at_2e16(be, monkeypatch):
+    monkeypatch.setenv("CKKSMI_NO_FUSION", "1")
+    pc.case_relin_and_composite(be, (16, 2, 50, 2, 51, 2), seed=114, batch=1, levels=[2])
+
+
+@pytest.mark.parametrize("fuse", [0, 1, 2, 4, 8, 5, 10])
+def test_emulated_partial_fusion(be, monkeypatch, fuse):
+    """every fusion switch on its own and in pairs gives the oracle's bits"""
+    monkeypatch.setenv("CKKSMI_FUSE", str(fuse))
+    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=115, batch=1, levels=[4 if fuse % 2 else 3])
