@@ -54,6 +54,89 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
     return table.get(name)
 
 
+def timed(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
+    """the other rows of the hot path, each timed on its own workload shape (uniform residues, resident in HBM)"""
+    from paper_1911_11377_amd import activation
+
+    out = {}
+    # polynomial activation on the main shape: x^2 then 0.5 + 0.25y - 0.02y^3, 64 ciphertexts from level 24 to 21
+    p4 = wl.PRESETS["act_2e16"]
+    L, B, N = p4.n_q, p4.batch, p4.N
+    s = 2.0 ** p4.log_scale
+    consts = activation.poly3_constants(ctx.q, L - 1, s * s / ctx.q[L - 1])
+    y = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    o3 = torch.empty((B, 2, L - 3, N), dtype=torch.int64, device="cuda:0")
+    wsa = torch.empty(activation.workspace_bytes(ctx, L, B) // 8, dtype=torch.int64, device="cuda:0")
+
+    def act():
+        activation.square(ctx, a, evk, y, L, B, wsa)
+        activation.poly3(ctx, y, evk, o3, L - 1, B, consts, wsa)
+
+    ms = timed(torch, act, 2)
+    out["activation_2e16"] = {"ciphertexts_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 2),
+                              "what": "square then degree-3 polynomial, 3 HMult+relin+rescale + 2 scalar rescales per ciphertext, level 24 -> 21"}
+    del y, o3, wsa
+
+    # N = 2^14, 8x50-bit + special prime: batch 256, HMult+relin+rescale and rotations by 8 random offsets
+    p2 = wl.PRESETS["hmul_rot_2e14"]
+    c2 = ckksmi.Context(p2.logN, p2.n_q, p2.q_bits, p2.k, p2.special_bits, p2.alpha, device=0)
+    L, B, N = p2.n_q, p2.batch, p2.N
+    a2 = uniform_residues(torch, c2.q, (B, 2), N, gen)
+    b2 = uniform_residues(torch, c2.q, (B, 2), N, gen)
+    k2 = uniform_residues(torch, c2.moduli, (c2.beta_top, 2), N, gen)
+    rots = wl.rotation_offsets(N // 2, 8, 2)
+    gks = [uniform_residues(torch, c2.moduli, (c2.beta_top, 2), N, gen) for _ in rots]
+    for r, g in zip(rots, gks):
+        c2.galois_key_register(r, g)
+    pick = wl.rng(2, "rot.pick").integers(0, len(rots), size=B)
+    rot = [rots[j] for j in pick]
+    o2 = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    or2 = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda:0")
+    w2 = torch.empty(max(c2.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, L, B), c2.workspace_bytes(ckksmi.OP_ROTATE, L, B)) // 8,
+                     dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: c2.hmul_relin_rescale(a2, b2, k2, o2, L, B, w2), 3)
+    out["hmul_relin_rescale_2e14"] = {"ops_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 3)}
+    ms = timed(torch, lambda: c2.rotate(a2, rot, or2, L, B, w2), 3)
+    out["rotate_2e14"] = {"ops_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 3), "keys": len(rots)}
+    del a2, b2, k2, gks, o2, or2, w2
+    c2.close()
+
+    # conv layer, slots-as-batch: N = 2^15, 16x50-bit, 3x32x32 pixel ciphertexts (16384 images), 3 -> 32 channels 5x5 stride 2, then rescale
+    p3 = wl.PRESETS["conv_2e15"]
+    c3 = ckksmi.Context(p3.logN, p3.n_q, p3.q_bits, p3.k, p3.special_bits, p3.alpha, device=0)
+    L, N = p3.n_q, p3.N
+    Cin, H, W, O, kh, stride = 3, 32, 32, 32, 5, 2
+    Ho = (H - kh) // stride + 1
+    xin = uniform_residues(torch, c3.q, (Cin * H * W, 2), N, gen)
+    wts = torch.from_numpy(__import__("numpy").rint(wl.weights_float((O, Cin, kh, kh), 3) * c3.q[L - 1]).astype("int64")).to("cuda:0")
+    co = torch.empty((O * Ho * Ho, 2, L, N), dtype=torch.int64, device="cuda:0")
+    cr = torch.empty((O * Ho * Ho, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    wm = torch.empty(c3.workspace_bytes(ckksmi.OP_CONV2D_MAC, L, wts.numel()) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    wr = torch.empty(c3.workspace_bytes(ckksmi.OP_RESCALE, L, 256) // 8, dtype=torch.int64, device="cuda:0")
+    ms_mac = timed(torch, lambda: c3.conv2d_mac(xin, wts, Cin, H, W, O, kh, kh, stride, 0, co, L, wm), 1)
+    ms_rs = timed(torch, lambda: c3.rescale(co, cr, L, O * Ho * Ho, wr), 1)
+    mac_count = float(O) * Ho * Ho * Cin * kh * kh * 2 * L * N
+    out["conv_layer_2e15"] = {"encrypted_images_per_s": round((N // 2) / ((ms_mac + ms_rs) * 1e-3), 1), "ms_mac": round(ms_mac, 2),
+                              "ms_rescale": round(ms_rs, 2), "word_macs_per_s": round(mac_count / (ms_mac * 1e-3), 0),
+                              "alu_frac": round(mac_count * 7 / (ms_mac * 1e-3) / FP64_PEAK_LANEOPS, 4),
+                              "what": "3x32x32 pixel ciphertexts -> 32x14x14, 5x5 stride 2, ptxt x ct MAC + rescale, 16384 images per pass"}
+    del xin, co, cr, wm, wr
+    c3.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +144,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweep (keeps a profile to the timed steps)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (rotation at N=2^14, conv layer at N=2^15, activation schedule)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input batch (known size) so that profiler byte counters can be scaled")
     args = ap.parse_args()
@@ -145,6 +229,10 @@ def main():
         ntt[name] = {"GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
     del limbs
 
+    extras = None
+    if not (args.no_extras or args.no_sweep):
+        extras = secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen)
+
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -174,7 +262,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "act_2e16: N=2^16, 24x50-bit primes + 3x51-bit special primes, 8 digits of 3, batch 64, level 24",
                    "op": "tensor -> key switch (ModUp, inner product, ModDown) -> add -> rescale"},
-        "roofline": roofline, "ntt_sweep": ntt, "cpu_baseline": cpu,
+        "roofline": roofline, "ntt_sweep": ntt, "cpu_baseline": cpu, "extras": extras,
     }
     print(json.dumps(line))
 

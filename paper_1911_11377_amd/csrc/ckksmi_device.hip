@@ -793,7 +793,7 @@ extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_
     const size_t n_weights = (size_t)O * C * kh * kw;
     if (ws_bytes < n_weights * level * sizeof(WMul)) return CKKSMI_EWORKSPACE;
     const size_t zdim = (size_t)Ho * Wo * ((O + MAC_OC - 1) / MAC_OC);
-    if (zdim > 65535 || 2 * level > 65535) return CKKSMI_EUNSUPPORTED;
+    if (zdim > 0x7fffffffu || ew_blocks(c->N) > 65535) return CKKSMI_EUNSUPPORTED;
     Guard g(c);
     KL(c, CKKSMI_K_MACPREP, 1, mac_prepare_kernel, dim3(ew_blocks(n_weights * level)), dim3(EW_THREADS), S(stream), (const long long *)w, (WMul *)ws,
                   c->d_mod, level, n_weights);
@@ -801,7 +801,7 @@ extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_
     A.in = (const u64d *)in; A.out = (u64d *)out; A.wtab = (const WMul *)ws; A.modc = c->d_mod;
     A.logN = c->logN; A.level = level;
     A.C = C; A.H = H; A.W = W; A.O = O; A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.Ho = Ho; A.Wo = Wo;
-    KL(c, CKKSMI_K_MAC, (double)O * Ho * Wo * 2 * level, conv_mac_kernel, dim3(ew_blocks(c->N), 2 * level, (unsigned)zdim), dim3(EW_THREADS), S(stream), A);
+    KL(c, CKKSMI_K_MAC, (double)O * Ho * Wo * 2 * level, conv_mac_kernel, dim3((unsigned)zdim, ew_blocks(c->N), 2 * level), dim3(EW_THREADS), S(stream), A);
     return g.rc();
 }
 

@@ -554,7 +554,7 @@ __global__ __launch_bounds__(EW_THREADS) void mac_prepare_kernel(const long long
     wtab[idx] = WMul{rb, rb / modc[i].p};
 }
 
-#define MAC_OC 8  // output channels accumulated per thread
+#define MAC_OC 32  // output channels accumulated per thread (each input word is loaded once per 32 outputs)
 
 struct MacArgs {
     const u64d *in;   // [C][H][W] ciphertexts of 2*level limbs
@@ -565,14 +565,15 @@ struct MacArgs {
     int C, H, W, O, kh, kw, stride, pad, Ho, Wo;
 };
 
-// grid: x = N / EW_THREADS, y = 2*level (component-major limb), z = Ho*Wo*ceil(O/MAC_OC)
+// grid: x = Ho*Wo*ceil(O/MAC_OC) (fastest: workgroups that share input words run together), y = N / EW_THREADS,
+// z = 2*level (component-major limb)
 __global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
     const unsigned N = 1u << A.logN;
-    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const unsigned n = blockIdx.y * EW_THREADS + threadIdx.x;
     if (n >= N) return;
-    const unsigned lc = blockIdx.y, i = lc % (unsigned)A.level;
+    const unsigned lc = blockIdx.z, i = lc % (unsigned)A.level;
     const unsigned ogroups = (unsigned)(A.O + MAC_OC - 1) / MAC_OC;
-    const unsigned og = blockIdx.z % ogroups, pos = blockIdx.z / ogroups;
+    const unsigned og = blockIdx.x % ogroups, pos = blockIdx.x / ogroups;
     const int oy = (int)(pos / (unsigned)A.Wo), ox = (int)(pos % (unsigned)A.Wo);
     const int o0 = (int)og * MAC_OC;
     const ModConst mc = A.modc[i];

@@ -17,7 +17,7 @@ def build(force=False):
         return LIB
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = ["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-mfma", "-ffp-contract=off", "-DCKKSMI_EMULATE",
-           "-include", os.path.join(HERE, "hip_emu.h"), "-Wall", "-Wno-unused-function", "-Wno-unknown-pragmas", "-x", "c++"] + srcs + ["-o", tmp]
+           "-include", os.path.join(HERE, "hip_emu.h"), "-Wall", "-Wno-unused-function", "-Wno-unknown-pragmas", "-Wno-maybe-uninitialized", "-x", "c++"] + srcs + ["-o", tmp]
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
     return LIB
