@@ -93,8 +93,8 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     // limbs actually transformed (the key-switch map skips the limbs of each digit itself)
     const double limbs_work = M.mode == 1 ? (double)items * ((double)M.per_item - M.level) : (double)limbs;
     dim3 grow(limbs, (N1 + R - 1) / R), gcol(limbs, N2 / NTT_TC);
-    // register-tiled kernels: rows of 256 for 2^13 <= N <= 2^16, columns of 256 for N = 2^16
-    const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = c->logN == 16;
+    // register-tiled kernels for 2^13 <= N <= 2^16
+    const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = v2_rows;
     NttV2Args V;
     V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = A.tw; V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M;
     V.items = (int)items;
@@ -175,8 +175,21 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
     A.mode = mode;
     A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.cc = c->d_modup_c;
     if (D) A.D = *D;
-    const unsigned z = zchunks_for(c, 16u * slots, items, A.items_per_z);
-    KL(c, mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : CKKSMI_K_CONV_COLS_DIV, units, conv_cols_kernel, dim3(16, slots, z), dim3(V2_THREADS), st, A);
+    const unsigned tiles = (unsigned)(c->N / 4096);
+    const unsigned z = zchunks_for(c, tiles * slots, items, A.items_per_z);
+    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : CKKSMI_K_CONV_COLS_DIV;
+    const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count): registers sized for it
+    const dim3 grid(tiles, slots, z), block(V2_THREADS);
+#define CONV_COLS_CASE(Q, NS) \
+    case (Q) * 8 + (NS): KL(c, kid, units, (conv_cols_kernel<Q, NS>), grid, block, st, A); break;
+    switch ((c->logN - 12) * 8 + nsrc) {
+        CONV_COLS_CASE(1, 1) CONV_COLS_CASE(1, 2) CONV_COLS_CASE(1, 3) CONV_COLS_CASE(1, 4)
+        CONV_COLS_CASE(2, 1) CONV_COLS_CASE(2, 2) CONV_COLS_CASE(2, 3) CONV_COLS_CASE(2, 4)
+        CONV_COLS_CASE(3, 1) CONV_COLS_CASE(3, 2) CONV_COLS_CASE(3, 3) CONV_COLS_CASE(3, 4)
+        CONV_COLS_CASE(4, 1) CONV_COLS_CASE(4, 2) CONV_COLS_CASE(4, 3) CONV_COLS_CASE(4, 4)
+        default: break;
+    }
+#undef CONV_COLS_CASE
 }
 
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
@@ -186,8 +199,9 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
     A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride; A.add_both = add_both;
     A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tw_fwd; A.Binv = Binv; A.logN = c->logN; A.nc = nc;
     A.rows = rows;
-    const unsigned xch = zchunks_for(c, 16u * nc, rows, A.rows_per_x);
-    KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nc, rows_final_kernel, dim3(xch, 16, nc), dim3(V2_THREADS), st, A);
+    const unsigned tiles = (unsigned)(c->N / 4096);
+    const unsigned xch = zchunks_for(c, tiles * nc, rows, A.rows_per_x);
+    KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nc, rows_final_kernel, dim3(xch, tiles, nc), dim3(V2_THREADS), st, A);
 }
 
 // fusion switches (ckksmi_ctx::fuse): which limb-wise steps ride on a transform pass
@@ -264,7 +278,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
         RI.modc = c->d_mod; RI.tw = c->d_tw_fwd;
         RI.logN = c->logN; RI.level = level; RI.E = E; RI.n_q = c->n_q; RI.alpha = c->alpha; RI.beta = beta; RI.T = c->T;
-        KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(items, 16, E), dim3(V2_THREADS), st, RI, K);
+        KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(items, (unsigned)(N / 4096), E), dim3(V2_THREADS), st, RI, K);
     } else {
         launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
         if (c->fuse & FUSE_MODUP) {
@@ -463,7 +477,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
         c->divround[which] = d;
     }
     // fused path: constants folded into the last stage of the inverse transforms
-    c->fused = c->logN == 16 && !getenv("CKKSMI_NO_FUSION");
+    c->fused = c->logN >= 13 && c->logN <= 16 && !getenv("CKKSMI_NO_FUSION");
     if (const char *e = getenv("CKKSMI_FUSE")) c->fuse = atoi(e) & 15;  // tuning / test knob
     if (c->fused) {
         auto fin = [&](int t, u64 mult, u64 add) {
@@ -844,8 +858,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
     if (c && kernel_class >= 0 && kernel_class < 4) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
                                     "ntt_v2_kernel<true, true>"};
-        const bool cols = kernel_class == CKKSMI_K_NTT_FWD_COL || kernel_class == CKKSMI_K_NTT_INV_COL;
-        if (cols ? c->logN == 16 : (c->logN >= 13 && c->logN <= 16)) return v2[kernel_class];
+        if (c->logN >= 13 && c->logN <= 16) return v2[kernel_class];
     }
     static const char *names[CKKSMI_K_COUNT] = {"ntt_fwd_kernel<true>", "ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_inv_kernel<true>",
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",

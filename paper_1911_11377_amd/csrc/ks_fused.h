@@ -1,4 +1,4 @@
-// Fused key-switch / DivRound kernels for N = 2^16 (256 x 256), built on the register-tiled
+// Fused key-switch / DivRound kernels for 2^13 <= N <= 2^16, built on the register-tiled
 // transform passes of ntt_v2.h.  They remove the HBM round trips between a transform and the
 // limb-wise step next to it:
 //
@@ -39,31 +39,35 @@ struct ConvColsArgs {
     DivRoundDev D;                // DivRound constants; its nb source limbs are y's limbs 0..nb-1
 };
 
-template <bool P51, int NSRC>
-__device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *lds, int t, unsigned slot, unsigned first_src, const WMul *W,
-                                               double hsub) {
+template <bool P51, int NSRC, int Q>
+__device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *lds, int t, unsigned slot, unsigned first_src, int nsrc,
+                                               const WMul *W, double hsub) {
+    typedef ColsGeom<Q> Geo;
+    typedef ColsMasks<Q, P51> Mk;
     const unsigned N = 1u << A.logN;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const WMul *tw = A.tw + (size_t)t * N;
-    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
+    const Geo geo(threadIdx.x, blockIdx.x);
     WMul tw1[15], tw2[15];
-    load_twiddles(tw, 1u, hi4, tw1, tw2);
+    load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
     WMul Wc[NSRC];
 #pragma unroll
     for (int a = 0; a < NSRC; a++) Wc[a] = W[a];
-    const unsigned c = blockIdx.x * 16 + lo4;
     const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
     const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
-    constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
     for (unsigned it = i0; it < i1; it++) {
         const u64d *ysrc = A.y + (size_t)it * A.y_item_stride + (size_t)first_src * N;
         u64d *dst = A.dst + (size_t)it * A.dst_item_stride + (size_t)slot * N;
-        // all source words first (one memory latency instead of one per source limb), then the arithmetic
+        // all source words first (one memory latency instead of one per source limb), then the arithmetic;
+        // a digit cut short by the level has nsrc < NSRC sources (its missing constants are zero)
         u64d raw[NSRC][16];
 #pragma unroll
-        for (int a = 0; a < NSRC; a++)
+        for (int a = 0; a < NSRC; a++) {
+            const u64d *ya = ysrc + (size_t)(a < nsrc ? a : 0) * N;  // a missing source re-reads limb 0; its constant is zero
 #pragma unroll
-            for (int e = 0; e < 16; e++) raw[a][e] = ysrc[(size_t)a * N + (size_t)(hi4 + 16 * e) * 256 + c];
+            for (int e = 0; e < 16; e++) raw[a][e] = ya[geo.g1(e)];
+        }
+        SCHED_FENCE();  // keep every load above the arithmetic
         double x[16];
 #pragma unroll
         for (int e = 0; e < 16; e++) {
@@ -73,40 +77,30 @@ __device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *ld
             // |v| <= p + NSRC*0.75p < 2^53: bring into the balanced range the round schedule assumes
             x[e] = reduce_balanced(v, p, pinv);
         }
-        fwd_round<F1>(x, tw1, p, pinv);
+        fwd_round<Mk::F1>(x, tw1, p, pinv);
 #pragma unroll
-        for (int e = 0; e < 16; e++) lds[(hi4 + 16 * e) * 16 + lo4] = x[e];
+        for (int e = 0; e < 16; e++) lds[geo.l1(e)] = x[e];
         __syncthreads();
 #pragma unroll
-        for (int e = 0; e < 16; e++) x[e] = lds[(16 * hi4 + e) * 16 + lo4];
-        fwd_round<F2>(x, tw2, p, pinv);
+        for (int i = 0; i < 16; i++) x[i] = lds[geo.l2(i)];
+        fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
 #pragma unroll
-        for (int e = 0; e < 16; e++) dst[(size_t)(16 * hi4 + e) * 256 + c] = d2u(canon(x[e], p, pinv));
+        for (int i = 0; i < 16; i++) dst[geo.g2(i)] = d2u(canon(x[i], p, pinv));
         __syncthreads();
     }
 }
 
-template <bool P51>
-__device__ __forceinline__ void conv_cols_dispatch(const ConvColsArgs &A, double *lds, int t, unsigned slot, unsigned first_src, int nsrc,
-                                                   const WMul *W, double hsub) {
-    switch (nsrc) {
-        case 1: conv_cols_body<P51, 1>(A, lds, t, slot, first_src, W, hsub); break;
-        case 2: conv_cols_body<P51, 2>(A, lds, t, slot, first_src, W, hsub); break;
-        case 3: conv_cols_body<P51, 3>(A, lds, t, slot, first_src, W, hsub); break;
-        default: conv_cols_body<P51, 4>(A, lds, t, slot, first_src, W, hsub); break;
-    }
-}
-
-// grid: x = column tile (16), y = slot, z = chunk of items
-__global__ __launch_bounds__(V2_THREADS) void conv_cols_kernel(ConvColsArgs A) {
+// grid: x = column tile (N/4096), y = slot, z = chunk of items.  Q = logN - 12; NSRC = most source limbs any slot has
+template <int Q, int NSRC>
+__global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A) {
     __shared__ double lds[16 * V2_GS];
     const unsigned slot = blockIdx.y;
     int t, nsrc;
     unsigned first_src;
     double hsub = 0.0;
-    WMul W[CKKSMI_MAX_ALPHA];
+    WMul W[NSRC];
 #pragma unroll
-    for (int a = 0; a < CKKSMI_MAX_ALPHA; a++) W[a] = WMul{0.0, 0.0};
+    for (int a = 0; a < NSRC; a++) W[a] = WMul{0.0, 0.0};
     if (A.mode == 0) {
         const unsigned j = slot / (unsigned)A.E, x = slot % (unsigned)A.E;
         const int lo = (int)j * A.alpha;
@@ -116,21 +110,21 @@ __global__ __launch_bounds__(V2_THREADS) void conv_cols_kernel(ConvColsArgs A) {
         first_src = (unsigned)lo;
         const size_t row = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
 #pragma unroll
-        for (int a = 0; a < CKKSMI_MAX_ALPHA; a++)
+        for (int a = 0; a < NSRC; a++)
             if (a < nsrc) W[a] = A.cc[(row + a) * A.T + t];
     } else {
         t = (int)slot;
         nsrc = A.D.nb;
         first_src = 0;
 #pragma unroll
-        for (int a = 0; a < CKKSMI_MAX_ALPHA; a++)
+        for (int a = 0; a < NSRC; a++)
             if (a < nsrc) W[a] = A.D.conv[(size_t)a * A.T + t];
         hsub = A.D.hc[t];
     }
     if (A.modc[t].p >= 1125899906842624.0)
-        conv_cols_dispatch<true>(A, lds, t, slot, first_src, nsrc, W, hsub);
+        conv_cols_body<true, NSRC, Q>(A, lds, t, slot, first_src, nsrc, W, hsub);
     else
-        conv_cols_dispatch<false>(A, lds, t, slot, first_src, nsrc, W, hsub);
+        conv_cols_body<false, NSRC, Q>(A, lds, t, slot, first_src, nsrc, W, hsub);
 }
 
 // ------------------------------------------------------------------ row pass helper
@@ -239,7 +233,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     }
 }
 
-// grid: x = item (fastest: workgroups sharing a key tile run together), y = row tile (16), z = extended limb
+// grid: x = item (fastest: workgroups sharing a key tile run together), y = row tile (N/4096), z = extended limb
 __global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_kernel(RowsInnerArgs A, KeyTab K) {
     __shared__ double lds[16 * V2_GS];
     __shared__ WMul tw1_lds[16 * 16];
@@ -291,6 +285,7 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
             xr[q] = xin[q * 256 + tid];
             ar[q] = ad[q * 256 + tid];
         }
+        SCHED_FENCE();
         rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.nc + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
 #pragma unroll
         for (int q = 0; q < 16; q++) {
@@ -306,7 +301,7 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
     }
 }
 
-// grid: x = chunk of rows (item, component), y = row tile (16), z = kept limb
+// grid: x = chunk of rows (item, component), y = row tile (N/4096), z = kept limb
 __global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A) {
     __shared__ double lds[16 * V2_GS];
     __shared__ WMul tw1_lds[16 * 16];

@@ -1,27 +1,31 @@
-// Register-tiled limb transforms for N = N1 x 256 (gfx950).
+// Register-tiled limb transforms for N = N1 x 256, N1 = 32 .. 256 (2^13 <= N <= 2^16), gfx950.
 //
 // A transform of N = 2^logN points is split into a strided pass over columns (the first
-// logN-8 stages) and a contiguous pass over rows of 256 words (the last 8 stages).  In
-// both, a workgroup of 256 threads works on 16 independent 256-point sub-transforms
-// (4096 words): every thread keeps 16 words in registers and does four butterfly stages
-// on them without touching memory ("round"); one exchange through LDS regroups the words
-// for the second round of four stages.  Viewing a 256-point sub-transform as a 16x16
-// matrix M[a][b] (point index 16a+b), the round on stages with span >= 16 works along a
-// (a thread owns a column b), the round on spans < 16 works along b (a thread owns a row).
+// k = logN-8 stages, N1 = 2^k-point sub-transforms down the columns of the N1 x 256 matrix)
+// and a contiguous pass over rows of 256 words (the last 8 stages).  In both, a workgroup of
+// 256 threads works on a tile of 4096 words: every thread keeps 16 words in registers and does
+// up to four butterfly stages on them without touching memory ("round"); one exchange through
+// LDS regroups the words for the second round.
 //
-// Twiddles: stage s of the whole transform multiplies block i by psi^brev(2^s + i).  For a
-// thread they reduce to 15 values per round that depend only on the sub-transform's
-// position and the thread's lane, so they are loaded into registers once per workgroup
-// and reused for every item the workgroup loops over (same modulus, same tile): twiddle
-// traffic is amortised over the batch.
+//   row pass   : tile = 16 rows.  A row is a 16x16 matrix M[a][b] (position 16a+b); round 1
+//                (spans >= 16) works along a, round 2 (spans < 16) along b.
+//   column pass: tile = N1 rows x C columns, C = 4096/N1.  With G = N1/16 = 2^Q: round 1 does the
+//                first four stages on the rows {r + G*e}; round 2 does the remaining Q stages on
+//                groups of G consecutive rows, a thread holding 16/G columns of one group.
 //
-// Lazy ranges (units of p, see device_arith.h): for p < 2^50 values may reach 8p, for
-// p < 2^51 only 4p, so the reduction points differ (template parameter P51).
+// Twiddles: stage s of the whole transform multiplies block i by psi^brev(2^s + i).  For a thread
+// they reduce to at most 15 values per round that depend only on the tile position and the lane,
+// so they are loaded into registers once per workgroup and reused for every item the workgroup
+// loops over (same modulus, same tile): twiddle traffic is amortised over the batch.
+//
+// Lazy ranges (units of p, see device_arith.h): a butterfly stage maps a bound B to
+// B + (1/2 + B*p/2^53) forward and to 2B inverse; values must stay below 2^53, i.e. 8p for
+// p < 2^50 and 4p for p < 2^51, so the reduction points differ (template parameter P51).
 #pragma once
 #include "device_arith.h"
 
 #define V2_THREADS 256
-#define V2_GS 272  // doubles per padded 16x17 group in LDS
+#define V2_GS 272  // doubles per padded 16x17 group in LDS (row pass)
 
 struct NttV2Args {
     const u64d *src;
@@ -40,12 +44,12 @@ __device__ __forceinline__ void reduce16(double (&x)[16], double p, double pinv)
     for (int e = 0; e < 16; e++) x[e] = reduce_balanced(x[e], p, pinv);
 }
 
-// four decimation-in-time stages (spans 8,4,2,1 over the register index); MASK bit s:
-// reduce all words after stage s
-template <int MASK>
-__device__ __forceinline__ void fwd_round(double (&x)[16], const WMul (&tw)[15], double p, double pinv) {
+// decimation-in-time stages S0..3 of a 16-point round (spans 8 >> s over the register index);
+// MASK bit s: reduce all words after stage s
+template <int S0, int MASK>
+__device__ __forceinline__ void fwd_stages(double (&x)[16], const WMul (&tw)[15], double p, double pinv) {
 #pragma unroll
-    for (int s = 0; s < 4; s++) {
+    for (int s = S0; s < 4; s++) {
         const int span = 8 >> s;
 #pragma unroll
         for (int b = 0; b < (1 << s); b++) {
@@ -62,13 +66,17 @@ __device__ __forceinline__ void fwd_round(double (&x)[16], const WMul (&tw)[15],
         if (MASK & (1 << s)) reduce16(x, p, pinv);
     }
 }
+template <int MASK>
+__device__ __forceinline__ void fwd_round(double (&x)[16], const WMul (&tw)[15], double p, double pinv) {
+    fwd_stages<0, MASK>(x, tw, p, pinv);
+}
 
-// the same four stages undone (spans 1,2,4,8); MASK bit k: reduce after the k-th executed
-// stage; FINAL folds 1/N into the very last stage of the whole transform
-template <int MASK, bool FINAL>
-__device__ __forceinline__ void inv_round(double (&x)[16], const WMul (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
+// the same stages undone, 3 down to S0 (spans 1,2,..); MASK bit k: reduce after the k-th executed
+// stage; FINAL folds 1/N into the very last stage (s = 0) of the whole transform
+template <int S0, int MASK, bool FINAL>
+__device__ __forceinline__ void inv_stages(double (&x)[16], const WMul (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
+    for (int k = 0; k < 4 - S0; k++) {
         const int s = 3 - k, span = 8 >> s;
 #pragma unroll
         for (int b = 0; b < (1 << s); b++) {
@@ -89,9 +97,13 @@ __device__ __forceinline__ void inv_round(double (&x)[16], const WMul (&tw)[15],
         if (MASK & (1 << k)) reduce16(x, p, pinv);
     }
 }
+template <int MASK, bool FINAL>
+__device__ __forceinline__ void inv_round(double (&x)[16], const WMul (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
+    inv_stages<0, MASK, FINAL>(x, tw, p, pinv, ninv, wlast);
+}
 
-// twiddles of one thread: base1 = position of the sub-transform in the stage numbering
-// (1 for the column pass, N1 + row for the row pass), lane = the thread's row a in round 2
+// ------------------------------------------------------------------ row pass twiddles
+// base1 = N1 + row; round 1 uses tw[(base1 << s) + b], round 2 (lane = the thread's a) tw[((16*base1 + lane) << s) + b]
 __device__ __forceinline__ void load_twiddles(const WMul *tw, unsigned base1, unsigned lane, WMul (&tw1)[15], WMul (&tw2)[15]) {
 #pragma unroll
     for (int s = 0; s < 4; s++)
@@ -102,109 +114,172 @@ __device__ __forceinline__ void load_twiddles(const WMul *tw, unsigned base1, un
         }
 }
 
-template <bool INV, bool COLS, bool P51>
-__device__ __forceinline__ void ntt_v2_body(const NttV2Args &A, double *lds, int t, unsigned li) {
+// ------------------------------------------------------------------ column pass geometry
+// Q = log2(N1/16).  Round 1: register e <-> row r + G*e, column c0 + c   (r = tid / C, c = tid % C).
+// Round 2: register pp*G + g <-> row G*a + g, column c0 + l16 + 16*pp     (a = tid >> 4, l16 = tid & 15).
+template <int Q>
+struct ColsGeom {
+    static constexpr unsigned G = 1u << Q, C = 256u >> Q, P = 16u >> Q;
+    static constexpr int S0 = 4 - Q;  // first register stage of round 2
+    unsigned r, c, a, l16, c0;
+    __device__ __forceinline__ ColsGeom(unsigned tid, unsigned tile) : r(tid / C), c(tid % C), a(tid >> 4), l16(tid & 15), c0(tile * C) {}
+    __device__ __forceinline__ size_t g1(int e) const { return (size_t)(r + G * e) * 256 + c0 + c; }                       // global, round-1 register e
+    __device__ __forceinline__ size_t g2(int i) const { return (size_t)(G * a + (i % G)) * 256 + c0 + l16 + 16 * (i / G); }  // global, round-2 register i
+    __device__ __forceinline__ unsigned l1(int e) const { return (r + G * e) * C + c; }                                    // LDS [N1][C]
+    __device__ __forceinline__ unsigned l2(int i) const { return (G * a + (i % G)) * C + l16 + 16 * (i / G); }
+};
+
+// round 1: the first four stages, block b of stage s uses tw[2^s + b] (same for every thread);
+// round 2: register stage s = S0 + u is transform stage 4 + u, block = a*2^u + (b mod 2^u)
+template <int Q>
+__device__ __forceinline__ void load_cols_twiddles(const WMul *tw, unsigned a, WMul (&tw1)[15], WMul (&tw2)[15]) {
+#pragma unroll
+    for (int s = 0; s < 4; s++)
+#pragma unroll
+        for (int b = 0; b < (1 << s); b++) {
+            tw1[(1 << s) - 1 + b] = tw[(1u << s) + b];
+            if (s >= 4 - Q) {
+                const int u = s - (4 - Q);
+                tw2[(1 << s) - 1 + b] = tw[(16u << u) + (a << u) + (b & ((1 << u) - 1))];
+            } else {
+                tw2[(1 << s) - 1 + b] = WMul{0.0, 0.0};
+            }
+        }
+}
+
+// lazy-range reduction points of the column pass (see header comment)
+template <int Q, bool P51>
+struct ColsMasks {
+    static constexpr int F1 = P51 ? 0xA : 0x8;            // forward round 1 from canonical input, ends reduced
+    static constexpr int F2 = (P51 && Q == 4) ? 0x2 : 0;  // forward round 2 (Q stages) from a reduced value
+    // inverse round 2 (Q stages, executed first, canonical input); always followed by a reduction
+    static constexpr int I1 = P51 ? (Q >= 3 ? 0x2 : 0) : (Q == 4 ? 0x4 : 0);
+    static constexpr int I2 = P51 ? 0x2 : 0;              // inverse round 1 from a reduced value, last stage multiplies
+};
+
+template <bool INV, int Q, bool P51>
+__device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int t, unsigned li) {
+    typedef ColsGeom<Q> Geo;
+    typedef ColsMasks<Q, P51> Mk;
+    const unsigned N = 1u << A.logN;
+    const double p = A.modc[t].p, pinv = A.modc[t].pinv;
+    const WMul *tw = A.tw + (size_t)t * N;
+    const Geo geo(threadIdx.x, blockIdx.x);
+    WMul tw1[15], tw2[15];
+    load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
+    WMul ninv = tw[0], wlast = tw[0];
+    double cadd = 0.0;
+    if (INV) {
+        wlast = A.tw_last[t];
+        if (A.fin) { ninv = A.fin[li].ninv; wlast = A.fin[li].wlast; cadd = A.fin[li].cadd; }
+    }
+    const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
+    const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
+    for (unsigned it = i0; it < i1; it++) {
+        const u64d *src = A.src + (size_t)it * A.map.src_item_stride + (size_t)li * N;
+        u64d *dst = A.dst + (size_t)it * A.map.dst_item_stride + (size_t)li * N;
+        double x[16];
+        if (!INV) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) x[e] = u2d(src[geo.g1(e)]);
+            fwd_round<Mk::F1>(x, tw1, p, pinv);
+#pragma unroll
+            for (int e = 0; e < 16; e++) lds[geo.l1(e)] = x[e];
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) x[i] = lds[geo.l2(i)];
+            fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
+#pragma unroll
+            for (int i = 0; i < 16; i++) dst[geo.g2(i)] = d2u(canon(x[i], p, pinv));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; i++) x[i] = u2d(src[geo.g2(i)]);
+            inv_stages<Geo::S0, Mk::I1, false>(x, tw2, p, pinv, ninv, wlast);
+            reduce16(x, p, pinv);
+#pragma unroll
+            for (int i = 0; i < 16; i++) lds[geo.l2(i)] = x[i];
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; e++) x[e] = lds[geo.l1(e)];
+            inv_round<Mk::I2, true>(x, tw1, p, pinv, ninv, wlast);
+#pragma unroll
+            for (int e = 0; e < 16; e++) dst[geo.g1(e)] = d2u(canon(x[e] + cadd, p, pinv));
+        }
+        __syncthreads();
+    }
+}
+
+template <bool INV, bool P51>
+__device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int t, unsigned li) {
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const WMul *tw = A.tw + (size_t)t * N;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
     WMul tw1[15], tw2[15];
-    WMul ninv = tw[0], wlast = tw[0];
-    double cadd = 0.0;
-    if (INV) {
-        wlast = A.tw_last[t];
-        if (COLS && A.fin) { ninv = A.fin[li].ninv; wlast = A.fin[li].wlast; cadd = A.fin[li].cadd; }
-    }
-    // COLS: column c = lo4 of tile blockIdx.x, lane = hi4.  rows: sub-transform = row hi4 of the tile, lane = lo4.
-    const unsigned lane = COLS ? hi4 : lo4;
-    const unsigned row = blockIdx.x * 16 + hi4;  // rows pass only
-    load_twiddles(tw, COLS ? 1u : N1 + row, lane, tw1, tw2);
+    const WMul unused = tw[0];
+    load_twiddles(tw, N1 + blockIdx.x * 16 + hi4, lo4, tw1, tw2);
     const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
     const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
-    // lazy-range reduction points (see header comment)
     constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
     constexpr int I1 = P51 ? 0x2 : 0x4, I2 = P51 ? 0x1 : 0x4;
+    const size_t tile0 = (size_t)blockIdx.x * 4096;
+    double *grp = lds + hi4 * V2_GS;
     for (unsigned it = i0; it < i1; it++) {
         const u64d *src = A.src + (size_t)it * A.map.src_item_stride + (size_t)li * N;
         u64d *dst = A.dst + (size_t)it * A.map.dst_item_stride + (size_t)li * N;
         double x[16];
-        if (COLS) {
-            const unsigned c = blockIdx.x * 16 + lo4;  // column of the N1 x 256 matrix (N1 = 256 here)
-            if (!INV) {
+        if (!INV) {
 #pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = u2d(src[(size_t)(hi4 + 16 * e) * 256 + c]);
-                fwd_round<F1>(x, tw1, p, pinv);
+            for (int e = 0; e < 16; e++) x[e] = u2d(src[tile0 + hi4 * 256 + lo4 + 16 * e]);
+            fwd_round<F1>(x, tw1, p, pinv);
 #pragma unroll
-                for (int e = 0; e < 16; e++) lds[(hi4 + 16 * e) * 16 + lo4] = x[e];
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = lds[(16 * hi4 + e) * 16 + lo4];
-                fwd_round<F2>(x, tw2, p, pinv);
-#pragma unroll
-                for (int e = 0; e < 16; e++) dst[(size_t)(16 * hi4 + e) * 256 + c] = d2u(canon(x[e], p, pinv));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = u2d(src[(size_t)(16 * hi4 + e) * 256 + c]);
-                inv_round<I1, false>(x, tw2, p, pinv, ninv, wlast);
-#pragma unroll
-                for (int e = 0; e < 16; e++) lds[(16 * hi4 + e) * 16 + lo4] = x[e];
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = lds[(hi4 + 16 * e) * 16 + lo4];
-                inv_round<I2, true>(x, tw1, p, pinv, ninv, wlast);
-#pragma unroll
-                for (int e = 0; e < 16; e++) dst[(size_t)(hi4 + 16 * e) * 256 + c] = d2u(canon(x[e] + cadd, p, pinv));
-            }
+            for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = x[e];
             __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
+            fwd_round<F2>(x, tw2, p, pinv);
+#pragma unroll
+            for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(x[e], p, pinv);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) dst[tile0 + i * 256 + tid] = d2u(lds[i * V2_GS + hi4 * 17 + lo4]);
         } else {
-            const size_t tile0 = (size_t)blockIdx.x * 4096;
-            double *grp = lds + hi4 * V2_GS;
-            if (!INV) {
 #pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = u2d(src[tile0 + hi4 * 256 + lo4 + 16 * e]);
-                fwd_round<F1>(x, tw1, p, pinv);
-#pragma unroll
-                for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = x[e];
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
-                fwd_round<F2>(x, tw2, p, pinv);
-#pragma unroll
-                for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(x[e], p, pinv);
-                __syncthreads();
-#pragma unroll
-                for (int i = 0; i < 16; i++) dst[tile0 + i * 256 + tid] = d2u(lds[i * V2_GS + hi4 * 17 + lo4]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; i++) lds[i * V2_GS + hi4 * 17 + lo4] = u2d(src[tile0 + i * 256 + tid]);
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
-                inv_round<I1, false>(x, tw2, p, pinv, ninv, wlast);
-#pragma unroll
-                for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = x[e];
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < 16; e++) x[e] = grp[e * 17 + lo4];
-                inv_round<I2, false>(x, tw1, p, pinv, ninv, wlast);
-#pragma unroll
-                for (int e = 0; e < 16; e++) dst[tile0 + hi4 * 256 + lo4 + 16 * e] = d2u(canon(x[e], p, pinv));
-            }
+            for (int i = 0; i < 16; i++) lds[i * V2_GS + hi4 * 17 + lo4] = u2d(src[tile0 + i * 256 + tid]);
             __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
+            inv_round<I1, false>(x, tw2, p, pinv, unused, unused);
+#pragma unroll
+            for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = x[e];
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; e++) x[e] = grp[e * 17 + lo4];
+            inv_round<I2, false>(x, tw1, p, pinv, unused, unused);
+#pragma unroll
+            for (int e = 0; e < 16; e++) dst[tile0 + hi4 * 256 + lo4 + 16 * e] = d2u(canon(x[e], p, pinv));
         }
+        __syncthreads();
     }
 }
 
 // grid: x = tile (N/4096), y = limb slot within an item, z = chunk of items
-// COLS requires N1 = 256 (logN = 16); the row pass works for any N1 >= 16
 template <bool INV, bool COLS>
 __global__ __launch_bounds__(V2_THREADS) void ntt_v2_kernel(NttV2Args A) {
     __shared__ double lds[16 * V2_GS];
     unsigned item_unused, li;
     const int t = resolve_limb(A.map, blockIdx.y, item_unused, li);
     if (t < 0) return;
-    if (A.modc[t].p >= 1125899906842624.0)  // 2^50
-        ntt_v2_body<INV, COLS, true>(A, lds, t, li);
-    else
-        ntt_v2_body<INV, COLS, false>(A, lds, t, li);
+    const bool p51 = A.modc[t].p >= 1125899906842624.0;  // 2^50
+    if (!COLS) {
+        if (p51) ntt_v2_rows<INV, true>(A, lds, t, li);
+        else ntt_v2_rows<INV, false>(A, lds, t, li);
+    } else {
+        switch (A.logN) {
+            case 13: if (p51) ntt_v2_cols<INV, 1, true>(A, lds, t, li); else ntt_v2_cols<INV, 1, false>(A, lds, t, li); break;
+            case 14: if (p51) ntt_v2_cols<INV, 2, true>(A, lds, t, li); else ntt_v2_cols<INV, 2, false>(A, lds, t, li); break;
+            case 15: if (p51) ntt_v2_cols<INV, 3, true>(A, lds, t, li); else ntt_v2_cols<INV, 3, false>(A, lds, t, li); break;
+            default: if (p51) ntt_v2_cols<INV, 4, true>(A, lds, t, li); else ntt_v2_cols<INV, 4, false>(A, lds, t, li); break;
+        }
+    }
 }

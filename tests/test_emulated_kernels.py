@@ -82,3 +82,13 @@ def test_emulated_partial_fusion(be, monkeypatch, fuse):
     """every fusion switch on its own and in pairs gives the oracle's bits"""
     monkeypatch.setenv("CKKSMI_FUSE", str(fuse))
     pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=115, batch=1, levels=[4 if fuse % 2 else 3])
+
+
+@pytest.mark.parametrize("logN", [13, 14, 15])
+def test_emulated_fused_path_other_sizes(be, monkeypatch, logN):
+    """2^13 <= N < 2^16: general column geometry (N1 = 32, 64, 128), fused and unfused, 50- and 51-bit primes"""
+    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "8")
+    pc.case_ntt(be, (logN, 2, 50, 1, 51, 1), seed=116, batch=3)
+    pc.case_relin_and_composite(be, (logN, 3, 50, 2, 51, 2), seed=117, batch=2, levels=[3, 2])
+    monkeypatch.setenv("CKKSMI_FUSE", "0")
+    pc.case_relin_and_composite(be, (logN, 2, 40, 1, 41, 1), seed=118, batch=1, levels=[2])
