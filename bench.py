@@ -169,7 +169,8 @@ def main():
     b = uniform_residues(torch, ctx.q[:level], (batch, 2), N, gen)
     evk = uniform_residues(torch, ctx.moduli, (ctx.beta_top, 2), N, gen)
     out = torch.empty((batch, 2, level - 1, N), dtype=torch.int64, device="cuda:0")
-    ws = torch.empty(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch) // 8, dtype=torch.int64, device="cuda:0")
+    ws_items = int(os.environ.get("CKKSMI_BENCH_WS_ITEMS", batch))  # tuning: a smaller workspace makes the call sweep the batch in chunks
+    ws = torch.empty(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, ws_items) // 8, dtype=torch.int64, device="cuda:0")
 
     def step():
         ctx.hmul_relin_rescale(a, b, evk, out, level, batch, ws)

@@ -96,7 +96,8 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     // register-tiled kernels for 2^13 <= N <= 2^16
     const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = v2_rows;
     NttV2Args V;
-    V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = A.tw; V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M;
+    V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = forward ? c->d_tww_fwd : c->d_tww_inv; V.tw_ninv = c->d_tw_ninv;
+    V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M;
     V.items = (int)items;
     const unsigned tiles = N >= 4096u ? N / 4096u : 1u;
     // enough workgroups to fill the chip, otherwise as many items per workgroup as possible (twiddle reuse)
@@ -170,7 +171,7 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
     memset(&A, 0, sizeof(A));
     A.y = (const u64d *)y; A.y_item_stride = y_stride;
     A.dst = (u64d *)dst; A.dst_item_stride = dst_stride;
-    A.modc = c->d_mod; A.tw = c->d_tw_fwd;
+    A.modc = c->d_mod; A.tw = c->d_tww_fwd;
     A.logN = c->logN; A.items = (int)items;
     A.mode = mode;
     A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.cc = c->d_modup_c;
@@ -197,7 +198,7 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
     RowsFinalArgs A;
     A.tmpA = (const u64d *)tmpA; A.x = (const u64d *)x; A.x_row_stride = x_row_stride;
     A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride; A.add_both = add_both;
-    A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tw_fwd; A.Binv = Binv; A.logN = c->logN; A.nc = nc;
+    A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.Binv = Binv; A.logN = c->logN; A.nc = nc;
     A.rows = rows;
     const unsigned tiles = (unsigned)(c->N / 4096);
     const unsigned xch = zchunks_for(c, tiles * nc, rows, A.rows_per_x);
@@ -276,7 +277,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     if (c->fuse & FUSE_INNER) {
         RowsInnerArgs RI;
         RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
-        RI.modc = c->d_mod; RI.tw = c->d_tw_fwd;
+        RI.modc = c->d_mod; RI.tw = c->d_tww_fwd;
         RI.logN = c->logN; RI.level = level; RI.E = E; RI.n_q = c->n_q; RI.alpha = c->alpha; RI.beta = beta; RI.T = c->T;
         KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(items, (unsigned)(N / 4096), E), dim3(V2_THREADS), st, RI, K);
     } else {
@@ -450,6 +451,20 @@ int dev_upload_tables(ckksmi_ctx *c) {
     c->d_tw_fwd = upload(c, fwd.data(), fwd.size(), ok);
     c->d_tw_inv = upload(c, inv.data(), inv.size(), ok);
     c->d_tw_inv_last = upload(c, last.data(), last.size(), ok);
+    {
+        std::vector<double> fw((size_t)T * N), iw((size_t)T * N);
+        std::vector<WMul> ni(T);
+        for (int t = 0; t < T; t++) {
+            for (size_t x = 0; x < N; x++) {
+                fw[(size_t)t * N + x] = make_wmul(c->h_fwd[t][x], c->mod[t]).w;
+                iw[(size_t)t * N + x] = make_wmul(c->h_inv[t][x], c->mod[t]).w;
+            }
+            ni[t] = make_wmul(c->h_ninv[t], c->mod[t]);
+        }
+        c->d_tww_fwd = upload(c, fw.data(), fw.size(), ok);
+        c->d_tww_inv = upload(c, iw.data(), iw.size(), ok);
+        c->d_tw_ninv = upload(c, ni.data(), ni.size(), ok);
+    }
     if (c->k > 0) {
         std::vector<WMul> mi, mc;
         make_modup_tables(c, mi, mc);

@@ -85,6 +85,9 @@ struct ckksmi_ctx {
     WMul *d_tw_fwd = nullptr;    // [T][N]  psi^brev(x), x in [1,N)
     WMul *d_tw_inv = nullptr;    // [T][N]  psi^-brev(x); entry 0 holds N^-1
     WMul *d_tw_inv_last = nullptr;  // [T]   psi^-brev(1) * N^-1  (last inverse stage)
+    WMul *d_tw_ninv = nullptr;      // [T]   N^-1
+    double *d_tww_fwd = nullptr;    // [T][N] balanced twiddles only (register-tiled kernels recompute w/p)
+    double *d_tww_inv = nullptr;    // [T][N]
     // ModUp: digit j, number of limbs present nd (1..alpha), source a, target t
     WMul *d_modup_inv = nullptr; // [beta_top][alpha][alpha]
     WMul *d_modup_c = nullptr;   // [beta_top][alpha][alpha][T]
@@ -97,7 +100,7 @@ struct ckksmi_ctx {
     FinConst *d_fin_moddown = nullptr;  // [k]
     FinConst *d_fin_rescale = nullptr;  // [n_q]  dropped limb
     bool fused = false;  // N = 2^16: register-tiled passes for everything, steps below optionally fused into them
-    int fuse = 13;       // bit 0 ModUp, 1 inner product, 2 DivRound conversion, 3 DivRound final step
+    int fuse = 15;       // bit 0 ModUp, 1 inner product, 2 DivRound conversion, 3 DivRound final step
 
     // registered Galois keys
     std::vector<std::pair<int, const u64 *>> galois;

@@ -31,7 +31,7 @@ struct ConvColsArgs {
     u64d *dst;                    // [items][slots][N] (column pass output, to be finished by a row pass)
     unsigned long long dst_item_stride;
     const ModConst *modc;
-    const WMul *tw;               // forward table [T][N]
+    const double *tw;             // forward twiddles [T][N]
     int logN, items, items_per_z;
     int mode;                     // 0: ModUp (slot = j*E + x), 1: DivRound (slot = kept limb i)
     int level, E, n_q, alpha, T;  // ModUp
@@ -46,9 +46,9 @@ __device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *ld
     typedef ColsMasks<Q, P51> Mk;
     const unsigned N = 1u << A.logN;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
-    const WMul *tw = A.tw + (size_t)t * N;
+    const double *tw = A.tw + (size_t)t * N;
     const Geo geo(threadIdx.x, blockIdx.x);
-    WMul tw1[15], tw2[15];
+    double tw1[15], tw2[15];
     load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
     WMul Wc[NSRC];
 #pragma unroll
@@ -129,8 +129,8 @@ __global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A
 
 // ------------------------------------------------------------------ row pass helper
 // round-2 twiddles of a thread (registers) and the round-1 twiddles of the tile's 16 rows (LDS, [16][16])
-__device__ __forceinline__ void load_row_twiddles(const WMul *tw, unsigned N1, unsigned tile, unsigned hi4, unsigned lo4, WMul *tw1_lds,
-                                                  WMul (&tw2)[15]) {
+__device__ __forceinline__ void load_row_twiddles(const double *tw, unsigned N1, unsigned tile, unsigned hi4, unsigned lo4, double *tw1_lds,
+                                                  double (&tw2)[15]) {
     const unsigned base1 = N1 + tile * 16 + hi4;
 #pragma unroll
     for (int s = 0; s < 4; s++)
@@ -148,7 +148,7 @@ __device__ __forceinline__ void load_row_twiddles(const WMul *tw, unsigned N1, u
 // canonical results in LDS in the padded layout: word (row g, position q) at g*V2_GS + (q/16)*17 + q%16.
 // Ends with a barrier; the caller must put a barrier before the next call.
 template <bool P51>
-__device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, const WMul *tw1_lds, const WMul (&tw2)[15], double p,
+__device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, const double *tw1_lds, const double (&tw2)[15], double p,
                                                 double pinv, unsigned hi4, unsigned lo4) {
     constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
     double *grp = lds + hi4 * V2_GS;
@@ -157,7 +157,7 @@ __device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, c
     for (int e = 0; e < 16; e++) x[e] = u2d(tile[hi4 * 256 + lo4 + 16 * e]);
     {
         // round-1 twiddles are the same for the 16 lanes of a row: kept in LDS, not in registers
-        WMul tw1[15];
+        double tw1[15];
 #pragma unroll
         for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
         fwd_round<F1>(x, tw1, p, pinv);
@@ -180,20 +180,22 @@ struct RowsInnerArgs {
     unsigned long long d_eval_item_stride;
     u64d *acc;           // [items][2][E][N]
     const ModConst *modc;
-    const WMul *tw;      // forward table
+    const double *tw;    // forward twiddles
     int logN, level, E, n_q, alpha, beta, T;
 };
 
 template <bool P51>
-__device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const KeyTab &K, double *lds, WMul *tw1_lds, int t, unsigned x) {
+__device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const KeyTab &K, double *lds, double *tw1_lds, int t, unsigned x) {
+    constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
     const unsigned item = blockIdx.x, tile = blockIdx.y;
-    WMul tw2[15];
+    double tw2[15];
     load_row_twiddles(A.tw + (size_t)t * N, N1, tile, hi4, lo4, tw1_lds, tw2);
     const u64d *key = K.key[K.slot[item]];
     const size_t tile0 = (size_t)tile * 4096;
+    double *grp = lds + hi4 * V2_GS;
     double a0[16], a1[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) a0[i] = a1[i] = 0.0;
@@ -202,27 +204,52 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         const bool own = (int)x >= lo && (int)x < lo + A.alpha && (int)x < A.level;
         const u64d *k0 = key + (((size_t)j * 2 + 0) * A.T + t) * N + tile0;
         const u64d *k1 = key + (((size_t)j * 2 + 1) * A.T + t) * N + tile0;
-        if (own) {
-            const u64d *src = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0;
+        // every operand of this digit is requested up front: the key words (position layout i*256+tid) and the
+        // limb itself -- in position layout when it is the digit's own limb (no transform needed), otherwise in the
+        // register layout of the row pass
+        const u64d *src = own ? A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0
+                              : A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
+        const unsigned base = own ? tid : hi4 * 256 + lo4, step = own ? 256u : 16u;
+        u64d kr0[16], kr1[16], xr[16];
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const double v = u2d(src[i * 256 + tid]);
-                a0[i] = reduce_balanced(a0[i] + mulmod(v, u2d(k0[i * 256 + tid]), p, pinv), p, pinv);
-                a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(k1[i * 256 + tid]), p, pinv), p, pinv);
-                if ((i & 3) == 3) SCHED_FENCE();  // keep at most four positions' loads in flight (register pressure)
-            }
-        } else {
-            const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
-            rows_fwd_to_lds<P51>(src, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const double v = lds[i * V2_GS + hi4 * 17 + lo4];
-                a0[i] = reduce_balanced(a0[i] + mulmod(v, u2d(k0[i * 256 + tid]), p, pinv), p, pinv);
-                a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(k1[i * 256 + tid]), p, pinv), p, pinv);
-                if ((i & 3) == 3) SCHED_FENCE();
-            }
-            __syncthreads();
+        for (int i = 0; i < 16; i++) {
+            xr[i] = src[base + step * i];
+            kr0[i] = k0[i * 256 + tid];
+            kr1[i] = k1[i * 256 + tid];
         }
+        SCHED_FENCE();
+        double v[16];
+        if (own) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = u2d(xr[i]);
+        } else {
+            double xx[16];
+#pragma unroll
+            for (int e = 0; e < 16; e++) xx[e] = u2d(xr[e]);
+            {
+                double tw1[15];
+#pragma unroll
+                for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
+                fwd_round<F1>(xx, tw1, p, pinv);
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = xx[e];
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
+            fwd_round<F2>(xx, tw2, p, pinv);
+#pragma unroll
+            for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(xx[e], p, pinv);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = lds[i * V2_GS + hi4 * 17 + lo4];
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            a0[i] = reduce_balanced(a0[i] + mulmod(v[i], u2d(kr0[i]), p, pinv), p, pinv);
+            a1[i] = reduce_balanced(a1[i] + mulmod(v[i], u2d(kr1[i]), p, pinv), p, pinv);
+        }
+        if (!own) __syncthreads();
     }
     u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
@@ -236,7 +263,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
 // grid: x = item (fastest: workgroups sharing a key tile run together), y = row tile (N/4096), z = extended limb
 __global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_kernel(RowsInnerArgs A, KeyTab K) {
     __shared__ double lds[16 * V2_GS];
-    __shared__ WMul tw1_lds[16 * 16];
+    __shared__ double tw1_lds[16 * 16];
     const unsigned x = blockIdx.z;
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
     if (A.modc[t].p >= 1125899906842624.0)
@@ -255,19 +282,19 @@ struct RowsFinalArgs {
     int add_both;
     u64d *out;           // [rows][nc][N]
     const ModConst *modc;
-    const WMul *tw;
+    const double *tw;
     const WMul *Binv;    // [T]
     int logN, nc;
     int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
 };
 
 template <bool P51>
-__device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *lds, WMul *tw1_lds, int i) {
+__device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *lds, double *tw1_lds, int i) {
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[i].p, pinv = A.modc[i].pinv;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
     const unsigned tile = blockIdx.y;
-    WMul tw2[15];
+    double tw2[15];
     load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
     const size_t tile0 = (size_t)tile * 4096;
     const WMul W = A.Binv[i];
@@ -304,7 +331,7 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
 // grid: x = chunk of rows (item, component), y = row tile (N/4096), z = kept limb
 __global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A) {
     __shared__ double lds[16 * V2_GS];
-    __shared__ WMul tw1_lds[16 * 16];
+    __shared__ double tw1_lds[16 * 16];
     const int i = (int)blockIdx.z;
     if (A.modc[i].p >= 1125899906842624.0)
         rows_final_body<true>(A, lds, tw1_lds, i);

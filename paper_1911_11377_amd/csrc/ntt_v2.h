@@ -18,8 +18,9 @@
 // so they are loaded into registers once per workgroup and reused for every item the workgroup
 // loops over (same modulus, same tile): twiddle traffic is amortised over the batch.
 //
-// Lazy ranges (units of p, see device_arith.h): a butterfly stage maps a bound B to
-// B + (1/2 + B*p/2^53) forward and to 2B inverse; values must stay below 2^53, i.e. 8p for
+// Lazy ranges (units of p, see device_arith.h): with the quotient w/p recomputed in registers a twiddle
+// product of y is bounded by (1/2 + 1.5*|y|/2^53) p, so a butterfly stage maps a bound B to
+// B + 1/2 + 1.5*B*p/2^53 forward and to 2B inverse; values must stay below 2^53, i.e. 8p for
 // p < 2^50 and 4p for p < 2^51, so the reduction points differ (template parameter P51).
 #pragma once
 #include "device_arith.h"
@@ -31,8 +32,9 @@ struct NttV2Args {
     const u64d *src;
     u64d *dst;
     const ModConst *modc;
-    const WMul *tw;       // [T][N] table of the direction
-    const WMul *tw_last;  // [T] inverse only
+    const double *tw;     // [T][N] twiddles of the direction, balanced representatives
+    const WMul *tw_ninv;  // [T] inverse only: 1/N
+    const WMul *tw_last;  // [T] inverse only: psi^-brev(1)/N
     const FinConst *fin;  // optional, inverse column pass: per limb slot, replaces the 1/N constants of the last stage
     int logN;
     int items, items_per_z;
@@ -47,17 +49,18 @@ __device__ __forceinline__ void reduce16(double (&x)[16], double p, double pinv)
 // decimation-in-time stages S0..3 of a 16-point round (spans 8 >> s over the register index);
 // MASK bit s: reduce all words after stage s
 template <int S0, int MASK>
-__device__ __forceinline__ void fwd_stages(double (&x)[16], const WMul (&tw)[15], double p, double pinv) {
+__device__ __forceinline__ void fwd_stages(double (&x)[16], const double (&tw)[15], double p, double pinv) {
 #pragma unroll
     for (int s = S0; s < 4; s++) {
         const int span = 8 >> s;
 #pragma unroll
         for (int b = 0; b < (1 << s); b++) {
-            const WMul W = tw[(1 << s) - 1 + b];
+            // registers hold w only; w/p is recomputed per block (one multiply, within 3 ulp of w/p)
+            const double Ww = tw[(1 << s) - 1 + b], Wp = Ww * pinv;
 #pragma unroll
             for (int j = 0; j < span; j++) {
                 const int lo = b * 2 * span + j, hi = lo + span;
-                const double v = mulmod_w(x[hi], W.w, W.wp, p);
+                const double v = mulmod_w(x[hi], Ww, Wp, p);
                 const double u = x[lo];
                 x[lo] = u + v;
                 x[hi] = u - v;
@@ -67,20 +70,20 @@ __device__ __forceinline__ void fwd_stages(double (&x)[16], const WMul (&tw)[15]
     }
 }
 template <int MASK>
-__device__ __forceinline__ void fwd_round(double (&x)[16], const WMul (&tw)[15], double p, double pinv) {
+__device__ __forceinline__ void fwd_round(double (&x)[16], const double (&tw)[15], double p, double pinv) {
     fwd_stages<0, MASK>(x, tw, p, pinv);
 }
 
 // the same stages undone, 3 down to S0 (spans 1,2,..); MASK bit k: reduce after the k-th executed
 // stage; FINAL folds 1/N into the very last stage (s = 0) of the whole transform
 template <int S0, int MASK, bool FINAL>
-__device__ __forceinline__ void inv_stages(double (&x)[16], const WMul (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
+__device__ __forceinline__ void inv_stages(double (&x)[16], const double (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
 #pragma unroll
     for (int k = 0; k < 4 - S0; k++) {
         const int s = 3 - k, span = 8 >> s;
 #pragma unroll
         for (int b = 0; b < (1 << s); b++) {
-            const WMul W = tw[(1 << s) - 1 + b];
+            const double Ww = tw[(1 << s) - 1 + b], Wp = Ww * pinv;
 #pragma unroll
             for (int j = 0; j < span; j++) {
                 const int lo = b * 2 * span + j, hi = lo + span;
@@ -90,7 +93,7 @@ __device__ __forceinline__ void inv_stages(double (&x)[16], const WMul (&tw)[15]
                     x[hi] = mulmod_w(u - v, wlast.w, wlast.wp, p);
                 } else {
                     x[lo] = u + v;
-                    x[hi] = mulmod_w(u - v, W.w, W.wp, p);
+                    x[hi] = mulmod_w(u - v, Ww, Wp, p);
                 }
             }
         }
@@ -98,13 +101,13 @@ __device__ __forceinline__ void inv_stages(double (&x)[16], const WMul (&tw)[15]
     }
 }
 template <int MASK, bool FINAL>
-__device__ __forceinline__ void inv_round(double (&x)[16], const WMul (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
+__device__ __forceinline__ void inv_round(double (&x)[16], const double (&tw)[15], double p, double pinv, WMul ninv, WMul wlast) {
     inv_stages<0, MASK, FINAL>(x, tw, p, pinv, ninv, wlast);
 }
 
 // ------------------------------------------------------------------ row pass twiddles
 // base1 = N1 + row; round 1 uses tw[(base1 << s) + b], round 2 (lane = the thread's a) tw[((16*base1 + lane) << s) + b]
-__device__ __forceinline__ void load_twiddles(const WMul *tw, unsigned base1, unsigned lane, WMul (&tw1)[15], WMul (&tw2)[15]) {
+__device__ __forceinline__ void load_twiddles(const double *tw, unsigned base1, unsigned lane, double (&tw1)[15], double (&tw2)[15]) {
 #pragma unroll
     for (int s = 0; s < 4; s++)
 #pragma unroll
@@ -132,7 +135,7 @@ struct ColsGeom {
 // round 1: the first four stages, block b of stage s uses tw[2^s + b] (same for every thread);
 // round 2: register stage s = S0 + u is transform stage 4 + u, block = a*2^u + (b mod 2^u)
 template <int Q>
-__device__ __forceinline__ void load_cols_twiddles(const WMul *tw, unsigned a, WMul (&tw1)[15], WMul (&tw2)[15]) {
+__device__ __forceinline__ void load_cols_twiddles(const double *tw, unsigned a, double (&tw1)[15], double (&tw2)[15]) {
 #pragma unroll
     for (int s = 0; s < 4; s++)
 #pragma unroll
@@ -142,7 +145,7 @@ __device__ __forceinline__ void load_cols_twiddles(const WMul *tw, unsigned a, W
                 const int u = s - (4 - Q);
                 tw2[(1 << s) - 1 + b] = tw[(16u << u) + (a << u) + (b & ((1 << u) - 1))];
             } else {
-                tw2[(1 << s) - 1 + b] = WMul{0.0, 0.0};
+                tw2[(1 << s) - 1 + b] = 0.0;
             }
         }
 }
@@ -163,13 +166,14 @@ __device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int
     typedef ColsMasks<Q, P51> Mk;
     const unsigned N = 1u << A.logN;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
-    const WMul *tw = A.tw + (size_t)t * N;
+    const double *tw = A.tw + (size_t)t * N;
     const Geo geo(threadIdx.x, blockIdx.x);
-    WMul tw1[15], tw2[15];
+    double tw1[15], tw2[15];
     load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
-    WMul ninv = tw[0], wlast = tw[0];
+    WMul ninv = WMul{0.0, 0.0}, wlast = WMul{0.0, 0.0};
     double cadd = 0.0;
     if (INV) {
+        ninv = A.tw_ninv[t];
         wlast = A.tw_last[t];
         if (A.fin) { ninv = A.fin[li].ninv; wlast = A.fin[li].wlast; cadd = A.fin[li].cadd; }
     }
@@ -213,10 +217,10 @@ template <bool INV, bool P51>
 __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int t, unsigned li) {
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
-    const WMul *tw = A.tw + (size_t)t * N;
+    const double *tw = A.tw + (size_t)t * N;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
-    WMul tw1[15], tw2[15];
-    const WMul unused = tw[0];
+    double tw1[15], tw2[15];
+    const WMul unused = WMul{0.0, 0.0};
     load_twiddles(tw, N1 + blockIdx.x * 16 + hi4, lo4, tw1, tw2);
     const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
     const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
