@@ -45,8 +45,9 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "divround_final_kernel": 4 * w,               # x, tmp, addend in; out
         "automorphism_kernel": 2 * w,
         # fused kernels: the converted limb is written once (column-pass output) plus its share of the source limbs
-        "conv_cols_kernel(ModUp)": w * (1 + float(level) / (beta * E - level)),
-        "conv_cols_kernel(DivRound)": w * (1 + float(k) / level),
+        "conv_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),   # ModUp
+        "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
+        "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
         "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
         "rows_final_kernel": 4 * w,                                  # column-pass output, x, addend in; out
         "elementwise kernels": 3 * w,

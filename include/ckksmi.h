@@ -197,7 +197,8 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_CONV_COLS_DIV 14   /* DivRound conversion fused likewise */
 #define CKKSMI_K_ROWS_INNER 15      /* contiguous pass fused with the inner product */
 #define CKKSMI_K_ROWS_FINAL 16      /* contiguous pass fused with DivRound's last step */
-#define CKKSMI_K_COUNT 17
+#define CKKSMI_K_CONV_COLS_RESCALE 17 /* the same with a single dropped prime (rescale) */
+#define CKKSMI_K_COUNT 18
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

@@ -6,6 +6,7 @@
 #endif
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 
@@ -178,11 +179,14 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
     if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
     const unsigned z = zchunks_for(c, tiles * slots, items, A.items_per_z);
-    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : CKKSMI_K_CONV_COLS_DIV;
-    const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count): registers sized for it
+    const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count, mode): registers sized for it
+    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
     const dim3 grid(tiles, slots, z), block(V2_THREADS);
-#define CONV_COLS_CASE(Q, NS) \
-    case (Q) * 8 + (NS): KL(c, kid, units, (conv_cols_kernel<Q, NS>), grid, block, st, A); break;
+#define CONV_COLS_CASE(Q, NS)                                                                                \
+    case (Q) * 8 + (NS):                                                                                     \
+        if (mode == 0) KL(c, kid, units, (conv_cols_kernel<Q, NS, 0>), grid, block, st, A);                  \
+        else KL(c, kid, units, (conv_cols_kernel<Q, NS, 1>), grid, block, st, A);                            \
+        break;
     switch ((c->logN - 12) * 8 + nsrc) {
         CONV_COLS_CASE(1, 1) CONV_COLS_CASE(1, 2) CONV_COLS_CASE(1, 3) CONV_COLS_CASE(1, 4)
         CONV_COLS_CASE(2, 1) CONV_COLS_CASE(2, 2) CONV_COLS_CASE(2, 3) CONV_COLS_CASE(2, 4)
@@ -870,15 +874,22 @@ extern "C" int ckksmi_profile_read(ckksmi_ctx *c, int kernel_class, double *tota
 }
 
 extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_class) {
-    if (c && kernel_class >= 0 && kernel_class < 4) {
-        static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
-                                    "ntt_v2_kernel<true, true>"};
-        if (c->logN >= 13 && c->logN <= 16) return v2[kernel_class];
-    }
     static const char *names[CKKSMI_K_COUNT] = {"ntt_fwd_kernel<true>", "ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_inv_kernel<true>",
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
-                                                "elementwise kernels", "conv_cols_kernel(ModUp)", "conv_cols_kernel(DivRound)",
-                                                "rows_inner_kernel", "rows_final_kernel"};
-    return (kernel_class >= 0 && kernel_class < CKKSMI_K_COUNT) ? names[kernel_class] : "";
+                                                "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
+                                                "rows_final_kernel", "conv_cols_kernel"};
+    if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
+    if (c && c->logN >= 13 && c->logN <= 16) {
+        static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
+                                    "ntt_v2_kernel<true, true>"};
+        if (kernel_class < 4) return v2[kernel_class];
+        // the conversion kernels are instantiated per (size, source limbs, mode): report the symbol that runs
+        static thread_local char buf[64];
+        const int q = c->logN - 12;
+        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 0>", q, c->alpha); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 1>", q, c->k); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, 1, 1>", q); return buf; }
+    }
+    return names[kernel_class];
 }

@@ -90,8 +90,9 @@ __device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *ld
     }
 }
 
-// grid: x = column tile (N/4096), y = slot, z = chunk of items.  Q = logN - 12; NSRC = most source limbs any slot has
-template <int Q, int NSRC>
+// grid: x = column tile (N/4096), y = slot, z = chunk of items.  Q = logN - 12; NSRC = most source limbs any slot has;
+// MODE 0: ModUp, 1: DivRound conversion
+template <int Q, int NSRC, int MODE>
 __global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A) {
     __shared__ double lds[16 * V2_GS];
     const unsigned slot = blockIdx.y;
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A
     WMul W[NSRC];
 #pragma unroll
     for (int a = 0; a < NSRC; a++) W[a] = WMul{0.0, 0.0};
-    if (A.mode == 0) {
+    if (MODE == 0) {
         const unsigned j = slot / (unsigned)A.E, x = slot % (unsigned)A.E;
         const int lo = (int)j * A.alpha;
         nsrc = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
@@ -185,14 +186,21 @@ struct RowsInnerArgs {
 };
 
 template <bool P51>
-__device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const KeyTab &K, double *lds, double *tw1_lds, int t, unsigned x) {
+__device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const KeyTab &K, double *lds, double *tw1_lds, double *tw2_lds, int t,
+                                                unsigned x) {
     constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
     const unsigned item = blockIdx.x, tile = blockIdx.y;
-    double tw2[15];
-    load_row_twiddles(A.tw + (size_t)t * N, N1, tile, hi4, lo4, tw1_lds, tw2);
+    {
+        // both rounds' twiddles live in LDS here (round 2: [15][256], conflict-free): the registers are needed for the
+        // accumulators and the operands in flight
+        double tw2[15];
+        load_row_twiddles(A.tw + (size_t)t * N, N1, tile, hi4, lo4, tw1_lds, tw2);
+#pragma unroll
+        for (int i = 0; i < 15; i++) tw2_lds[i * 256 + tid] = tw2[i];
+    }
     const u64d *key = K.key[K.slot[item]];
     const size_t tile0 = (size_t)tile * 4096;
     double *grp = lds + hi4 * V2_GS;
@@ -237,7 +245,12 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
             __syncthreads();
 #pragma unroll
             for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
-            fwd_round<F2>(xx, tw2, p, pinv);
+            {
+                double tw2[15];
+#pragma unroll
+                for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[i * 256 + tid];
+                fwd_round<F2>(xx, tw2, p, pinv);
+            }
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(xx[e], p, pinv);
             __syncthreads();
@@ -264,12 +277,13 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
 __global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_kernel(RowsInnerArgs A, KeyTab K) {
     __shared__ double lds[16 * V2_GS];
     __shared__ double tw1_lds[16 * 16];
+    __shared__ double tw2_lds[15 * 256];
     const unsigned x = blockIdx.z;
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
     if (A.modc[t].p >= 1125899906842624.0)
-        rows_inner_body<true>(A, K, lds, tw1_lds, t, x);
+        rows_inner_body<true>(A, K, lds, tw1_lds, tw2_lds, t, x);
     else
-        rows_inner_body<false>(A, K, lds, tw1_lds, t, x);
+        rows_inner_body<false>(A, K, lds, tw1_lds, tw2_lds, t, x);
 }
 
 // ------------------------------------------------------------------ row pass + DivRound final step
