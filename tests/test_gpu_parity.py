@@ -64,6 +64,22 @@ def test_relin_and_composite_levels_and_digits(be, shape, levels, batch):
     pc.case_relin_and_composite(be, shape, seed=303, batch=batch, levels=levels)
 
 
+@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "6"}, {"CKKSMI_NTT_TARGET_WGS": "64"}])
+def test_alternative_kernel_paths_give_the_same_bits(be, monkeypatch, env):
+    """the unfused kernels, partial fusion and long per-workgroup item loops must all match the oracle too"""
+    announce("alternative paths %r" % (env,))
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=310, batch=3, levels=[4, 2])
+    pc.case_relin_and_composite(be, (14, 3, 50, 2, 51, 2), seed=311, batch=5, levels=[3])
+    pc.case_rotate(be, (13, 3, 50, 1, 51, 1), seed=312, rotations=[5, 9], batch=3)
+
+
+def test_largest_ring_uses_generic_kernels(be):
+    announce("N=2^17 generic path")
+    pc.case_relin_and_composite(be, (17, 2, 50, 1, 51, 1), seed=313, batch=1, levels=[2])
+
+
 def test_ragged_sweeps_with_small_workspace(be):
     announce("relin with a workspace that holds one item")
     pc.case_relin_and_composite(be, (10, 5, 40, 2, 41, 2), seed=304, batch=5, levels=[5], small_ws=True)
