@@ -98,7 +98,7 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = v2_rows;
     NttV2Args V;
     V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = forward ? c->d_tww_fwd : c->d_tww_inv; V.tw_ninv = c->d_tw_ninv;
-    V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M;
+    V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M; V.p51 = c->p51mask;
     V.items = (int)items;
     const unsigned tiles = N >= 4096u ? N / 4096u : 1u;
     // enough workgroups to fill the chip, otherwise as many items per workgroup as possible (twiddle reuse)
@@ -175,10 +175,15 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
     A.modc = c->d_mod; A.tw = c->d_tww_fwd;
     A.logN = c->logN; A.items = (int)items;
     A.mode = mode;
+    A.p51 = c->p51mask;
     A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.cc = c->d_modup_c;
     if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
-    const unsigned z = zchunks_for(c, tiles * slots, items, A.items_per_z);
+    // the column pass needs only the first N1 table entries per modulus (cache-resident), so nothing is gained by
+    // looping over items; with the item as the slowest grid index all targets of a digit run together and share
+    // their source tiles in L2
+    A.items_per_z = c->conv_items_per_wg < (int)items ? c->conv_items_per_wg : (int)items;
+    const unsigned z = (unsigned)((items + A.items_per_z - 1) / A.items_per_z);
     const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count, mode): registers sized for it
     const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
     const dim3 grid(tiles, slots, z), block(V2_THREADS);
@@ -204,6 +209,7 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
     A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride; A.add_both = add_both;
     A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.Binv = Binv; A.logN = c->logN; A.nc = nc;
     A.rows = rows;
+    A.p51 = c->p51mask;
     const unsigned tiles = (unsigned)(c->N / 4096);
     const unsigned xch = zchunks_for(c, tiles * nc, rows, A.rows_per_x);
     KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nc, rows_final_kernel, dim3(xch, tiles, nc), dim3(V2_THREADS), st, A);
@@ -283,7 +289,10 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
         RI.modc = c->d_mod; RI.tw = c->d_tww_fwd;
         RI.logN = c->logN; RI.level = level; RI.E = E; RI.n_q = c->n_q; RI.alpha = c->alpha; RI.beta = beta; RI.T = c->T;
-        KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(items, (unsigned)(N / 4096), E), dim3(V2_THREADS), st, RI, K);
+        const unsigned tiles = (unsigned)(N / 4096);
+        RI.kt = tiles < 8 ? tiles : 8;
+        RI.p51 = c->p51mask;
+        KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
     } else {
         launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
         if (c->fuse & FUSE_MODUP) {
@@ -442,6 +451,8 @@ int dev_upload_tables(ckksmi_ctx *c) {
     const size_t N = c->N;
     const int T = c->T;
     c->d_mod = upload(c, c->h_modc, T, ok);
+    for (int t = 0; t < T; t++)
+        if (c->mod[t] >= ((u64)1 << 50)) c->p51mask.w[t >> 6] |= 1ull << (t & 63);
     std::vector<WMul> fwd((size_t)T * N), inv((size_t)T * N), last(T);
     for (int t = 0; t < T; t++) {
         const u64 q = c->mod[t];

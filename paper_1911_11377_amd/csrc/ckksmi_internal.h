@@ -63,11 +63,16 @@ struct DivRoundDev {
 // constant to every coefficient: ninv = c/N, wlast = c*psi^-brev(1)/N, result + cadd.
 struct FinConst { WMul ninv, wlast; double cadd, pad; };
 
+// bit t set: modulus t is >= 2^50 (tighter lazy-reduction schedule).  Travels in kernel arguments so that the choice
+// of code path does not wait for a memory load.
+struct P51Mask { unsigned long long w[2]; };
+
 struct ProfRec { int kid; double units; void *start, *stop; };
 
 struct ckksmi_ctx {
     bool prof_on = false;
-    int ntt_target_wgs = 4096;  // workgroups a transform launch aims for before it starts looping over items
+    int ntt_target_wgs = 8192;
+    int conv_items_per_wg = 1;  // items a conversion workgroup loops over (1: item-major dispatch keeps a digit's source tiles shared in L2)  // workgroups a transform launch aims for before it starts looping over items
     std::vector<ProfRec> prof;
 
     int logN = 0, n_q = 0, k = 0, alpha = 1, T = 0, beta_top = 0;
@@ -99,6 +104,7 @@ struct ckksmi_ctx {
     FinConst *d_fin_modup = nullptr;    // [n_q + 1][n_q]  level, limb
     FinConst *d_fin_moddown = nullptr;  // [k]
     FinConst *d_fin_rescale = nullptr;  // [n_q]  dropped limb
+    P51Mask p51mask = {{0, 0}};
     bool fused = false;  // N = 2^16: register-tiled passes for everything, steps below optionally fused into them
     int fuse = 15;       // bit 0 ModUp, 1 inner product, 2 DivRound conversion, 3 DivRound final step
 

@@ -53,3 +53,5 @@ __device__ __forceinline__ double canon(double x, double p, double pinv) {
 
 // value known to lie in (-p, p)
 __device__ __forceinline__ double canon_small(double r, double p) { return r < 0.0 ? r + p : r; }
+
+__device__ __forceinline__ bool is_p51(const P51Mask &m, int t) { return (m.w[t >> 6] >> (t & 63)) & 1ull; }

@@ -37,6 +37,7 @@ struct ConvColsArgs {
     int level, E, n_q, alpha, T;  // ModUp
     const WMul *cc;               // ModUp constants [beta_top][alpha][alpha][T]
     DivRoundDev D;                // DivRound constants; its nb source limbs are y's limbs 0..nb-1
+    P51Mask p51;
 };
 
 template <bool P51, int NSRC, int Q>
@@ -59,7 +60,9 @@ __device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *ld
         const u64d *ysrc = A.y + (size_t)it * A.y_item_stride + (size_t)first_src * N;
         u64d *dst = A.dst + (size_t)it * A.dst_item_stride + (size_t)slot * N;
         // all source words first (one memory latency instead of one per source limb), then the arithmetic;
-        // a digit cut short by the level has nsrc < NSRC sources (its missing constants are zero)
+        // a digit cut short by the level has nsrc < NSRC sources (its missing constants are zero).
+        // (Requesting the next item's words before this item's butterflies was tried: the extra live registers
+        // spill and the kernel gets slower.)
         u64d raw[NSRC][16];
 #pragma unroll
         for (int a = 0; a < NSRC; a++) {
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A
             if (a < nsrc) W[a] = A.D.conv[(size_t)a * A.T + t];
         hsub = A.D.hc[t];
     }
-    if (A.modc[t].p >= 1125899906842624.0)
+    if (is_p51(A.p51, t))
         conv_cols_body<true, NSRC, Q>(A, lds, t, slot, first_src, nsrc, W, hsub);
     else
         conv_cols_body<false, NSRC, Q>(A, lds, t, slot, first_src, nsrc, W, hsub);
@@ -183,6 +186,8 @@ struct RowsInnerArgs {
     const ModConst *modc;
     const double *tw;    // forward twiddles
     int logN, level, E, n_q, alpha, beta, T;
+    unsigned kt;         // min(N/4096, 8): see the grid mapping in rows_inner_body
+    P51Mask p51;
 };
 
 template <bool P51>
@@ -192,7 +197,11 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
-    const unsigned item = blockIdx.x, tile = blockIdx.y;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  blockIdx.x packs
+    // (row tile mod KT, item) with KT = min(tiles, 8) in the low position, so that all items' workgroups for one key
+    // tile (same extended limb, same row tile) land on the same XCD and the key tile is fetched from HBM once.
+    const unsigned KT = A.kt;
+    const unsigned item = blockIdx.x / KT, tile = blockIdx.x % KT + KT * blockIdx.y;
     {
         // both rounds' twiddles live in LDS here (round 2: [15][256], conflict-free): the registers are needed for the
         // accumulators and the operands in flight
@@ -273,14 +282,14 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     }
 }
 
-// grid: x = item (fastest: workgroups sharing a key tile run together), y = row tile (N/4096), z = extended limb
+// grid: x = (row tile mod kt) + kt * item, y = row tile / kt, z = extended limb
 __global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_kernel(RowsInnerArgs A, KeyTab K) {
     __shared__ double lds[16 * V2_GS];
     __shared__ double tw1_lds[16 * 16];
     __shared__ double tw2_lds[15 * 256];
     const unsigned x = blockIdx.z;
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
-    if (A.modc[t].p >= 1125899906842624.0)
+    if (is_p51(A.p51, t))
         rows_inner_body<true>(A, K, lds, tw1_lds, tw2_lds, t, x);
     else
         rows_inner_body<false>(A, K, lds, tw1_lds, tw2_lds, t, x);
@@ -300,6 +309,7 @@ struct RowsFinalArgs {
     const WMul *Binv;    // [T]
     int logN, nc;
     int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
+    P51Mask p51;
 };
 
 template <bool P51>
@@ -347,7 +357,7 @@ __global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A)
     __shared__ double lds[16 * V2_GS];
     __shared__ double tw1_lds[16 * 16];
     const int i = (int)blockIdx.z;
-    if (A.modc[i].p >= 1125899906842624.0)
+    if (is_p51(A.p51, i))
         rows_final_body<true>(A, lds, tw1_lds, i);
     else
         rows_final_body<false>(A, lds, tw1_lds, i);

@@ -38,6 +38,7 @@ struct NttV2Args {
     const FinConst *fin;  // optional, inverse column pass: per limb slot, replaces the 1/N constants of the last stage
     int logN;
     int items, items_per_z;
+    P51Mask p51;
     LimbMap map;
 };
 
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(V2_THREADS) void ntt_v2_kernel(NttV2Args A) {
     unsigned item_unused, li;
     const int t = resolve_limb(A.map, blockIdx.y, item_unused, li);
     if (t < 0) return;
-    const bool p51 = A.modc[t].p >= 1125899906842624.0;  // 2^50
+    const bool p51 = is_p51(A.p51, t);
     if (!COLS) {
         if (p51) ntt_v2_rows<INV, true>(A, lds, t, li);
         else ntt_v2_rows<INV, false>(A, lds, t, li);
