@@ -55,6 +55,31 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
     return table.get(name)
 
 
+def laneops_per_unit(name, N, level, k, alpha):
+    """FP64 vector instructions per unit of work (counted from the kernel source, per word: conversions u64<->f64 2 each,
+    twiddle product 6, butterfly add/sub 2, reduction 3, canonical form 7) for the kernels where the ALU can bind"""
+    beta = -(-level // alpha)
+    xform_pass = 2 + 8 * 4 + 3 + 9          # load conversion, 8 stages at 4 per word, one mid reduction, canonical store
+    table = {
+        "conv_cols_kernel<4, %d, 0>" % alpha: N * (9 * alpha + 3 + xform_pass - 2),
+        "conv_cols_kernel<4, %d, 1>" % k: N * (9 * k + 3 + xform_pass - 2),
+        "conv_cols_kernel<4, 1, 1>": N * (9 + 3 + xform_pass - 2),
+        "rows_inner_kernel": N * beta * (xform_pass + 2 * (2 + 6 + 1 + 3)),
+        "rows_final_kernel": N * (xform_pass + 2 + 1 + 6 + 7 + 2 + 3),
+    }
+    return table.get(name)
+
+
+# HBM bytes per launch of the kernels that dominate the default workload (act_2e16, batch 64, level 24), measured with
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
+# 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
+MEASURED_TRAFFIC = {
+    "conv_cols_kernel<4, 3, 0>": (2.0 * 398537 + 6291456) * 1024,
+    "rows_inner_kernel": (2.0 * 3760086 + 1824768) * 1024,
+    "rows_final_kernel": (2.0 * 3968672 + 3080192) * 1024 / 2,
+}
+
+
 def timed(torch, fn, reps):
     fn()
     torch.cuda.synchronize()
@@ -200,13 +225,25 @@ def main():
     ms, launches, units = prof[dom]
     bpu = bytes_per_unit(dom, N, level, p.k, p.alpha, batch)
     achieved = bpu * units / (ms * 1e-3) / 1e9
+    lpu = laneops_per_unit(dom, N, level, p.k, p.alpha)
+    alu_rate = lpu * units / (ms * 1e-3) if lpu else None
+    hbm_frac = achieved / HBM_PEAK_GBPS
+    alu_frac = alu_rate / FP64_PEAK_LANEOPS if alu_rate else 0.0
     ntt_ms = sum(prof[n][0] for n in prof if n.startswith("ntt_"))
     ntt_limbs = sum(prof[n][2] for n in prof if n in ("ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>"))
-    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "avg_launch_ms": round(ms / launches, 4), "bytes_per_launch": bpu * units / launches,
-                "all_transforms_GBps": round(16 * N * ntt_limbs / (ntt_ms * 1e-3) / 1e9, 1),
-                "kernels": kernels}
+    traffic = MEASURED_TRAFFIC.get(dom) if (level, batch, p.logN) == (24, 64, 16) else None
+    if alu_frac > hbm_frac:
+        # the kernel does more FP64 work per byte than the machine balance: the vector ALU binds.  Peak = 256 CUs x 64
+        # lanes x 2.4 GHz = 39.3 T FP64 instructions/s (half the 78.6 TFLOP/s FMA figure); unit: T instructions/s
+        roofline = {"kernel": dom, "bound": "alu", "achieved": round(alu_rate / 1e12, 2), "peak": FP64_PEAK_LANEOPS / 1e12,
+                    "unit": "T FP64 lane-instr/s", "frac": round(alu_frac, 4)}
+    else:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(hbm_frac, 4)}
+    roofline.update({"traffic": traffic, "hbm_GBps": round(achieved, 1), "hbm_frac": round(hbm_frac, 4), "alu_frac": round(alu_frac, 4),
+                     "avg_launch_ms": round(ms / launches, 4), "bytes_per_launch": bpu * units / launches,
+                     "all_transforms_GBps": round(16 * N * ntt_limbs / (ntt_ms * 1e-3) / 1e9, 1) if ntt_ms else None,
+                     "kernels": kernels})
 
     if args.copy_probe:
         probe = torch.empty_like(a)
