@@ -55,3 +55,10 @@ __device__ __forceinline__ double canon(double x, double p, double pinv) {
 __device__ __forceinline__ double canon_small(double r, double p) { return r < 0.0 ? r + p : r; }
 
 __device__ __forceinline__ bool is_p51(const P51Mask &m, int t) { return (m.w[t >> 6] >> (t & 63)) & 1ull; }
+
+// Intermediate between the two passes of a transform (never visible outside the library): the balanced-reduced
+// value stored as the bits of the double itself.  Saves the canonical form and both integer conversions.
+__device__ __forceinline__ unsigned long long mid_store(double x, double p, double pinv) {
+    return (unsigned long long)__double_as_longlong(reduce_balanced(x, p, pinv));
+}
+__device__ __forceinline__ double mid_load(unsigned long long bits) { return __longlong_as_double((long long)bits); }

@@ -41,16 +41,24 @@ struct ConvColsArgs {
 };
 
 template <bool P51, int NSRC, int Q>
-__device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *lds, int t, unsigned slot, unsigned first_src, int nsrc,
-                                               const WMul *W, double hsub) {
+__device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *lds, double *tw2_lds, int t, unsigned slot, unsigned first_src,
+                                               int nsrc, const WMul *W, double hsub) {
     typedef ColsGeom<Q> Geo;
     typedef ColsMasks<Q, P51> Mk;
     const unsigned N = 1u << A.logN;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const double *tw = A.tw + (size_t)t * N;
     const Geo geo(threadIdx.x, blockIdx.x);
-    double tw1[15], tw2[15];
-    load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
+    double tw1[15];
+    {
+        // round-2 twiddles depend only on a = tid / 16: kept in LDS ([16][16] doubles) to free registers
+        double tw2[15];
+        load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
+#pragma unroll
+        for (int i = 0; i < 15; i++)
+            if (geo.l16 == (unsigned)i) tw2_lds[geo.a * 16 + i] = tw2[i];
+        __syncthreads();
+    }
     WMul Wc[NSRC];
 #pragma unroll
     for (int a = 0; a < NSRC; a++) Wc[a] = W[a];
@@ -86,9 +94,14 @@ __device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *ld
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 16; i++) x[i] = lds[geo.l2(i)];
-        fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
+        {
+            double tw2[15];
 #pragma unroll
-        for (int i = 0; i < 16; i++) dst[geo.g2(i)] = d2u(canon(x[i], p, pinv));
+            for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[geo.a * 16 + i];
+            fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i++) dst[geo.g2(i)] = mid_store(x[i], p, pinv);
         __syncthreads();
     }
 }
@@ -96,8 +109,9 @@ __device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *ld
 // grid: x = column tile (N/4096), y = slot, z = chunk of items.  Q = logN - 12; NSRC = most source limbs any slot has;
 // MODE 0: ModUp, 1: DivRound conversion
 template <int Q, int NSRC, int MODE>
-__global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A) {
+__global__ __launch_bounds__(V2_THREADS, 3) void conv_cols_kernel(ConvColsArgs A) {
     __shared__ double lds[16 * V2_GS];
+    __shared__ double tw2_lds[16 * 16];
     const unsigned slot = blockIdx.y;
     int t, nsrc;
     unsigned first_src;
@@ -126,9 +140,9 @@ __global__ __launch_bounds__(V2_THREADS, 2) void conv_cols_kernel(ConvColsArgs A
         hsub = A.D.hc[t];
     }
     if (is_p51(A.p51, t))
-        conv_cols_body<true, NSRC, Q>(A, lds, t, slot, first_src, nsrc, W, hsub);
+        conv_cols_body<true, NSRC, Q>(A, lds, tw2_lds, t, slot, first_src, nsrc, W, hsub);
     else
-        conv_cols_body<false, NSRC, Q>(A, lds, t, slot, first_src, nsrc, W, hsub);
+        conv_cols_body<false, NSRC, Q>(A, lds, tw2_lds, t, slot, first_src, nsrc, W, hsub);
 }
 
 // ------------------------------------------------------------------ row pass helper
@@ -149,7 +163,7 @@ __device__ __forceinline__ void load_row_twiddles(const double *tw, unsigned N1,
 }
 
 // Finish the forward transform of one 16-row tile (column pass already done) and leave the
-// canonical results in LDS in the padded layout: word (row g, position q) at g*V2_GS + (q/16)*17 + q%16.
+// balanced-reduced results in LDS in the padded layout: word (row g, position q) at g*V2_GS + (q/16)*17 + q%16.
 // Ends with a barrier; the caller must put a barrier before the next call.
 template <bool P51>
 __device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, const double *tw1_lds, const double (&tw2)[15], double p,
@@ -158,7 +172,7 @@ __device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, c
     double *grp = lds + hi4 * V2_GS;
     double x[16];
 #pragma unroll
-    for (int e = 0; e < 16; e++) x[e] = u2d(tile[hi4 * 256 + lo4 + 16 * e]);
+    for (int e = 0; e < 16; e++) x[e] = mid_load(tile[hi4 * 256 + lo4 + 16 * e]);
     {
         // round-1 twiddles are the same for the 16 lanes of a row: kept in LDS, not in registers
         double tw1[15];
@@ -173,7 +187,7 @@ __device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, c
     for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
     fwd_round<F2>(x, tw2, p, pinv);
 #pragma unroll
-    for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(x[e], p, pinv);
+    for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = reduce_balanced(x[e], p, pinv);
     __syncthreads();
 }
 
@@ -216,62 +230,73 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     double a0[16], a1[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) a0[i] = a1[i] = 0.0;
-    for (int j = 0; j < A.beta; j++) {
-        const int lo = j * A.alpha;
-        const bool own = (int)x >= lo && (int)x < lo + A.alpha && (int)x < A.level;
-        const u64d *k0 = key + (((size_t)j * 2 + 0) * A.T + t) * N + tile0;
-        const u64d *k1 = key + (((size_t)j * 2 + 1) * A.T + t) * N + tile0;
-        // every operand of this digit is requested up front: the key words (position layout i*256+tid) and the
-        // limb itself -- in position layout when it is the digit's own limb (no transform needed), otherwise in the
-        // register layout of the row pass
-        const u64d *src = own ? A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0
-                              : A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
-        const unsigned base = own ? tid : hi4 * 256 + lo4, step = own ? 256u : 16u;
+    // The digit that contains this limb needs no transform: its operand is the source polynomial itself, read in
+    // position layout (word i*256+tid) like the key.
+    const int j_own = (int)x < A.level ? (int)x / A.alpha : -1;
+    if (j_own >= 0) {
+        const u64d *k0 = key + (((size_t)j_own * 2 + 0) * A.T + t) * N + tile0;
+        const u64d *k1 = key + (((size_t)j_own * 2 + 1) * A.T + t) * N + tile0;
+        const u64d *src = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0;
         u64d kr0[16], kr1[16], xr[16];
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            xr[i] = src[base + step * i];
+            xr[i] = src[i * 256 + tid];
             kr0[i] = k0[i * 256 + tid];
             kr1[i] = k1[i * 256 + tid];
         }
         SCHED_FENCE();
-        double v[16];
-        if (own) {
-#pragma unroll
-            for (int i = 0; i < 16; i++) v[i] = u2d(xr[i]);
-        } else {
-            double xx[16];
-#pragma unroll
-            for (int e = 0; e < 16; e++) xx[e] = u2d(xr[e]);
-            {
-                double tw1[15];
-#pragma unroll
-                for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
-                fwd_round<F1>(xx, tw1, p, pinv);
-            }
-#pragma unroll
-            for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = xx[e];
-            __syncthreads();
-#pragma unroll
-            for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
-            {
-                double tw2[15];
-#pragma unroll
-                for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[i * 256 + tid];
-                fwd_round<F2>(xx, tw2, p, pinv);
-            }
-#pragma unroll
-            for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(xx[e], p, pinv);
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < 16; i++) v[i] = lds[i * V2_GS + hi4 * 17 + lo4];
-        }
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            a0[i] = reduce_balanced(a0[i] + mulmod(v[i], u2d(kr0[i]), p, pinv), p, pinv);
-            a1[i] = reduce_balanced(a1[i] + mulmod(v[i], u2d(kr1[i]), p, pinv), p, pinv);
+            const double v = u2d(xr[i]);
+            a0[i] = reduce_balanced(mulmod(v, u2d(kr0[i]), p, pinv), p, pinv);
+            a1[i] = reduce_balanced(mulmod(v, u2d(kr1[i]), p, pinv), p, pinv);
         }
-        if (!own) __syncthreads();
+    }
+    for (int j = 0; j < A.beta; j++) {
+        if (j == j_own) continue;
+        const u64d *k0 = key + (((size_t)j * 2 + 0) * A.T + t) * N + tile0;
+        const u64d *k1 = key + (((size_t)j * 2 + 1) * A.T + t) * N + tile0;
+        // every operand of this digit is requested up front: the key words (position layout i*256+tid) and the
+        // column-pass output of the converted limb in the register layout of the row pass
+        const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
+        u64d kr0[16], kr1[16], xr[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            xr[i] = src[hi4 * 256 + lo4 + 16 * i];
+            kr0[i] = k0[i * 256 + tid];
+            kr1[i] = k1[i * 256 + tid];
+        }
+        SCHED_FENCE();
+        double xx[16];
+#pragma unroll
+        for (int e = 0; e < 16; e++) xx[e] = mid_load(xr[e]);
+        {
+            double tw1[15];
+#pragma unroll
+            for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
+            fwd_round<F1>(xx, tw1, p, pinv);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = xx[e];
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
+        {
+            double tw2[15];
+#pragma unroll
+            for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[i * 256 + tid];
+            fwd_round<F2>(xx, tw2, p, pinv);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = reduce_balanced(xx[e], p, pinv);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const double v = lds[i * V2_GS + hi4 * 17 + lo4];
+            a0[i] = reduce_balanced(a0[i] + mulmod(v, u2d(kr0[i]), p, pinv), p, pinv);
+            a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(kr1[i]), p, pinv), p, pinv);
+        }
+        __syncthreads();
     }
     u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
@@ -341,12 +366,9 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
 #pragma unroll
         for (int q = 0; q < 16; q++) {
             const double r = lds[q * V2_GS + hi4 * 17 + lo4];
-            double v = canon(mulmod_w(u2d(xr[q]) - r, W.w, W.wp, p), p, pinv);
-            if (add) {
-                v += u2d(ar[q]);
-                v = v >= p ? v - p : v;
-            }
-            out[q * 256 + tid] = d2u(v);
+            double v = mulmod_w(u2d(xr[q]) - r, W.w, W.wp, p);
+            if (add) v += u2d(ar[q]);
+            out[q * 256 + tid] = d2u(canon(v, p, pinv));
         }
         __syncthreads();
     }

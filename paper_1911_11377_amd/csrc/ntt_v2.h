@@ -18,6 +18,9 @@
 // so they are loaded into registers once per workgroup and reused for every item the workgroup
 // loops over (same modulus, same tile): twiddle traffic is amortised over the batch.
 //
+// Between the two passes the words are stored as balanced-reduced doubles (mid_store / mid_load), not as canonical
+// integers: that intermediate never leaves the library.
+//
 // Lazy ranges (units of p, see device_arith.h): with the quotient w/p recomputed in registers a twiddle
 // product of y is bounded by (1/2 + 1.5*|y|/2^53) p, so a butterfly stage maps a bound B to
 // B + 1/2 + 1.5*B*p/2^53 forward and to 2B inverse; values must stay below 2^53, i.e. 8p for
@@ -195,10 +198,10 @@ __device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int
             for (int i = 0; i < 16; i++) x[i] = lds[geo.l2(i)];
             fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
 #pragma unroll
-            for (int i = 0; i < 16; i++) dst[geo.g2(i)] = d2u(canon(x[i], p, pinv));
+            for (int i = 0; i < 16; i++) dst[geo.g2(i)] = mid_store(x[i], p, pinv);
         } else {
 #pragma unroll
-            for (int i = 0; i < 16; i++) x[i] = u2d(src[geo.g2(i)]);
+            for (int i = 0; i < 16; i++) x[i] = mid_load(src[geo.g2(i)]);
             inv_stages<Geo::S0, Mk::I1, false>(x, tw2, p, pinv, ninv, wlast);
             reduce16(x, p, pinv);
 #pragma unroll
@@ -235,7 +238,7 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
         double x[16];
         if (!INV) {
 #pragma unroll
-            for (int e = 0; e < 16; e++) x[e] = u2d(src[tile0 + hi4 * 256 + lo4 + 16 * e]);
+            for (int e = 0; e < 16; e++) x[e] = mid_load(src[tile0 + hi4 * 256 + lo4 + 16 * e]);
             fwd_round<F1>(x, tw1, p, pinv);
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = x[e];
@@ -262,7 +265,7 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
             for (int e = 0; e < 16; e++) x[e] = grp[e * 17 + lo4];
             inv_round<I2, false>(x, tw1, p, pinv, unused, unused);
 #pragma unroll
-            for (int e = 0; e < 16; e++) dst[tile0 + hi4 * 256 + lo4 + 16 * e] = d2u(canon(x[e], p, pinv));
+            for (int e = 0; e < 16; e++) dst[tile0 + hi4 * 256 + lo4 + 16 * e] = mid_store(x[e], p, pinv);
         }
         __syncthreads();
     }
