@@ -223,6 +223,7 @@ class Oracle:
             "orc_add_const": [V, u64p, C.c_int64, I, u64p],
             "orc_conv2d_mac": [V, u64p, i64p] + [I] * 8 + [I, u64p],
             "orc_fc_mac": [V, u64p, i64p, I, I, I, u64p],
+            "orc_sum_pool2d": [V, u64p, I, I, I, I, I, u64p],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -434,6 +435,66 @@ class Oracle:
         out = np.empty((O, 2, level, self.N), dtype=np.uint64)
         self._L.orc_fc_mac(self._h, _p64(x), _pi64(w), F, O, level, _p64(out))
         return out
+
+    def sum_pool2d(self, x, k, level):
+        """k x k pooling as a sum of ciphertexts (Table 1's average pooling without its 1/k^2)."""
+        x = _u64(x)
+        Cc, H, W = x.shape[:3]
+        assert x.shape[3:] == (2, level, self.N)
+        out = np.empty((Cc, H // k, W // k, 2, level, self.N), dtype=np.uint64)
+        self._L.orc_sum_pool2d(self._h, _p64(x), Cc, H, W, k, level, _p64(out))
+        return out
+
+    def rescale_each(self, cts, level):
+        """Rescale every ciphertext of an array [...][2][level][N]."""
+        cts = _u64(cts)
+        lead = cts.shape[:-3]
+        flat = cts.reshape((-1, 2, level, self.N))
+        out = np.empty((flat.shape[0], 2, level - 1, self.N), dtype=np.uint64)
+        for b in range(flat.shape[0]):
+            out[b] = self.rescale(flat[b], level)
+        return out.reshape(lead + (2, level - 1, self.N))
+
+    def square_each(self, cts, rlk, level):
+        cts = _u64(cts)
+        lead = cts.shape[:-3]
+        flat = cts.reshape((-1, 2, level, self.N))
+        out = np.empty((flat.shape[0], 2, level - 1, self.N), dtype=np.uint64)
+        for b in range(flat.shape[0]):
+            out[b] = self.hmul_relin_rescale(flat[b], flat[b], rlk, level)
+        return out.reshape(lead + (2, level - 1, self.N))
+
+    def cnn_forward(self, x, layers, rlk, level):
+        """A feed-forward network over per-pixel ciphertexts (section 3: convolution, pooling, polynomial activation
+        and fully connected layers in sequence), slot s = image s.
+
+        x: [C][H][W][2][level][N].  layers: a list of
+          ("conv", w_int [O][C][kh][kw], stride, pad)  convolution MAC, then rescale of every output   level -> level-1
+          ("square",)                                  activation x^2 with relinearisation and rescale  level -> level-1
+          ("pool", k)                                  k x k sum pooling                                level unchanged
+          ("fc", w_int [O][F])                         flatten [C][H][W] in that order, MAC, rescale    level -> level-1
+        Integer weights are prepared by the caller (round(w * dropped modulus)).  Returns (cts, level).
+        """
+        x = _u64(x)
+        for layer in layers:
+            kind = layer[0]
+            if kind == "conv":
+                _, w, stride, pad = layer
+                x = self.rescale_each(self.conv2d_mac(x, w, stride, pad, level), level)
+                level -= 1
+            elif kind == "square":
+                x = self.square_each(x, rlk, level)
+                level -= 1
+            elif kind == "pool":
+                x = self.sum_pool2d(x, layer[1], level)
+            elif kind == "fc":
+                flat = x.reshape((-1, 2, level, self.N))
+                x = self.rescale_each(self.fc_mac(flat, layer[1], level), level)
+                level -= 1
+                x = x.reshape((x.shape[0], 1, 1, 2, level, self.N))
+            else:
+                raise ValueError(kind)
+        return x, level
 
     # ---- activation schedules (compositions; constants are passed in) ----
     def square(self, x, rlk, level):

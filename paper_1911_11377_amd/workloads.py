@@ -102,3 +102,57 @@ def rotation_offsets(n_slots, count, seed):
     """`count` distinct slot offsets in [1, n_slots)."""
     g = rng(seed, "rot")
     return sorted(int(x) for x in g.choice(np.arange(1, n_slots), size=count, replace=False))
+
+
+# ---------------------------------------------------------------------------
+# Network shapes (layer lists only: no arithmetic of the method lives here)
+# ---------------------------------------------------------------------------
+# ("conv", out_channels, kernel, stride, pad) | ("square",) | ("pool", k) | ("fc", out_features)
+CNN_TOPOLOGIES = {
+    # the AlexNet-like network of the 2^16 workload: 3x64x64 -> 32x30x30 -> 64x14x14 -> 64x14x14 -> pool 64x7x7 -> 256 -> 2
+    "cnn_2e16": {"input": (3, 64, 64),
+                 "layers": [("conv", 32, 5, 2, 0), ("square",), ("conv", 64, 3, 2, 0), ("square",), ("conv", 64, 3, 1, 1),
+                            ("pool", 2), ("fc", 256), ("square",), ("fc", 2)]},
+    # same layer sequence and depth, small enough for a CPU reference
+    "cnn_reduced": {"input": (3, 16, 16),
+                    "layers": [("conv", 6, 5, 2, 0), ("square",), ("conv", 8, 3, 2, 0), ("square",), ("conv", 8, 3, 1, 1),
+                               ("pool", 2), ("fc", 16), ("square",), ("fc", 2)]},
+    "cnn_tiny": {"input": (3, 16, 16),
+                 "layers": [("conv", 4, 5, 2, 0), ("square",), ("conv", 4, 3, 2, 0), ("square",), ("conv", 4, 3, 1, 1),
+                            ("pool", 2), ("fc", 6), ("square",), ("fc", 2)]},
+}
+
+
+def cnn_shapes(name):
+    """[(layer, input shape (C,H,W), output shape (C,H,W))] for a topology."""
+    topo = CNN_TOPOLOGIES[name]
+    c, h, w = topo["input"]
+    out = []
+    for layer in topo["layers"]:
+        kind = layer[0]
+        if kind == "conv":
+            _, o, k, s, p = layer
+            nxt = (o, (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1)
+        elif kind == "pool":
+            nxt = (c, h // layer[1], w // layer[1])
+        elif kind == "fc":
+            nxt = (layer[1], 1, 1)
+        else:
+            nxt = (c, h, w)
+        out.append((layer, (c, h, w), nxt))
+        c, h, w = nxt
+    return out
+
+
+def cnn_weights_float(name, seed, sigma=0.05):
+    """Float weights per layer (None for layers without weights): conv [O][C][k][k], fc [O][C*H*W]."""
+    ws = []
+    for li, (layer, (c, h, w), _) in enumerate(cnn_shapes(name)):
+        if layer[0] == "conv":
+            ws.append(weights_float((layer[1], c, layer[2], layer[2]), seed, "cnn", li, sigma=sigma))
+        elif layer[0] == "fc":
+            ws.append(weights_float((layer[1], c * h * w), seed, "cnn", li, sigma=sigma))
+        else:
+            ws.append(None)
+    return ws
+

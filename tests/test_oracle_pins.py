@@ -560,3 +560,84 @@ def test_paper_degree2_activation_polynomial():
     out = O.add(t2, t1, 2)
     want = c2 * z.real**2 + c1 * z.real
     assert np.max(np.abs(M.decrypt(out, s2, 2).real - want)) < 1e-4
+
+
+def test_sum_pool_is_sum_of_decrypted_polynomials():
+    M = Material(4, 3, 30, 1, 31, 1, seed=25)
+    O = M.O
+    level = 3
+    Q = math.prod(O.q[:level])
+    x = wl.uniform_limbs(O.q[:level], O.N, 25, "x", lead=(2, 5, 4, 2))
+    out = O.sum_pool2d(x, 2, level)
+    assert out.shape[:3] == (2, 2, 2)
+    for c in range(2):
+        for y in range(2):
+            for xx in range(2):
+                got = M.decrypt_poly(out[c, y, xx], level)
+                parts = [M.decrypt_poly(x[c, 2 * y + u, 2 * xx + v], level) for u in range(2) for v in range(2)]
+                assert all((g - sum(p[n] for p in parts)) % Q == 0 for n, g in enumerate(got))
+
+
+def _float_network(imgs, layers_f):
+    """cleartext float network over arrays [C][H][W][images]; average pooling as in Table 1"""
+    x = imgs
+    for layer in layers_f:
+        if layer[0] == "conv":
+            x = _conv_reference(x, layer[1], layer[2], layer[3])
+        elif layer[0] == "square":
+            x = x * x
+        elif layer[0] == "pool":
+            k = layer[1]
+            Cc, H, W = x.shape[:3]
+            x = x[:, : H // k * k, : W // k * k].reshape(Cc, H // k, k, W // k, k, -1).mean(axis=(2, 4))
+        elif layer[0] == "fc":
+            x = np.tensordot(layer[1], x.reshape(-1, x.shape[-1]), axes=1).reshape(layer[1].shape[0], 1, 1, -1)
+    return x
+
+
+def test_network_decrypts_to_float_network():
+    """conv - square - conv - square - conv - pool - fc - square - fc over per-pixel ciphertexts against the same
+    network on the slot values in floating point (section 3: the layer types of Table 1 with polynomial activations);
+    the average pooling's 1/4 is folded into the next layer's integer weights"""
+    name = "cnn_tiny"
+    M = Material(6, 10, 50, 3, 51, 3, seed=26)
+    O = M.O
+    level = 10
+    scale = 2.0**50
+    Cc, H, W = wl.CNN_TOPOLOGIES[name]["input"]
+    imgs = wl.rng(26, "img").uniform(0, 1, size=(Cc, H, W, O.N // 2))
+    x = np.array([[[M.encrypt(imgs[c, y, xx].astype(np.complex128), scale, level, (c, y, xx)) for xx in range(W)] for y in range(H)] for c in range(Cc)])
+    shapes = wl.cnn_shapes(name)
+    wf = wl.cnn_weights_float(name, 26, sigma=1.0)
+    layers_f, layers_i = [], []
+    lvl, s, fold = level, scale, 1.0
+    for (layer, (c, h, w), _), wt in zip(shapes, wf):
+        if layer[0] in ("conv", "fc"):
+            fan_in = wt[0].size
+            wt = wt * (1.0 / math.sqrt(fan_in))  # keeps the activations of this random network near 0.1 .. 1
+            wi = np.rint(wt * fold * O.q[lvl - 1]).astype(np.int64)
+            fold = 1.0
+            if layer[0] == "conv":
+                layers_f.append(("conv", wt, layer[3], layer[4]))
+                layers_i.append(("conv", wi, layer[3], layer[4]))
+            else:
+                layers_f.append(("fc", wt))
+                layers_i.append(("fc", wi))
+            lvl -= 1  # scale unchanged: the integer weight carries the dropped modulus
+        elif layer[0] == "square":
+            layers_f.append(layer)
+            layers_i.append(layer)
+            s = s * s / O.q[lvl - 1]
+            lvl -= 1
+        else:
+            layers_f.append(layer)
+            layers_i.append(layer)
+            fold = 1.0 / (layer[1] * layer[1])
+    out, out_level = O.cnn_forward(x, layers_i, M.rlk, level)
+    assert out_level == lvl == 2 and out.shape[:3] == (2, 1, 1)
+    want = _float_network(imgs, layers_f)
+    assert 1e-3 < np.max(np.abs(want)) < 0.4  # a meaningful, decodable output at the last level
+    for o in range(2):
+        got = M.decrypt(out[o, 0, 0], s, out_level).real
+        assert np.max(np.abs(got - want[o, 0, 0])) < 1e-6 * max(1.0, np.max(np.abs(want)))
+
