@@ -165,8 +165,18 @@ int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [bat
  * taps outside the image skipped; out at the same level (rescale separately).
  * in: [C][H][W] ciphertexts, out: [O][Ho][Wo], Ho = (H+2*pad-kh)/stride+1. */
 int ckksmi_conv2d_mac(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride, int pad, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
+/* The same convolution restricted to output rows out_row0 .. out_row0+out_rows-1, for layers whose activations do
+ * not fit in device memory at once: `in` holds only image rows in_row0 .. in_row0+in_rows-1 as [C][in_rows][W]
+ * ciphertexts and `out` receives [O][out_rows][Wo].  H is still the height of the whole image (it decides where
+ * the zero padding starts).  CKKSMI_EINVAL if a tap of the requested rows falls on an image row outside the strip. */
+int ckksmi_conv2d_mac_rows(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride, int pad, int in_row0, int in_rows, int out_row0, int out_rows, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
 /* in: [F] ciphertexts, w: [O][F], out: [O] ciphertexts */
 int ckksmi_fc_mac(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int F, int O, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
+/* Pooling layers of the paper's network (Table 1: 2x2 average pooling) as a sum of ciphertexts:
+ * out[c,y,x] = sum_{u,v<k} in[c, k*y+u, k*x+v]; the 1/k^2 of the average is left to the caller, who folds it into
+ * the next layer's plaintext weights.  in: [C][H][W] ciphertexts, out: [C][H/k][W/k] at the same level; rows and
+ * columns beyond k*(H/k), k*(W/k) are ignored; 1 <= k <= 16. */
+int ckksmi_sum_pool2d(ckksmi_ctx *ctx, const uint64_t *in, int C, int H, int W, int k, uint64_t *out, int level, void *stream);
 
 /* bytes of workspace that lets `op` process the whole batch in one sweep; with
  * less (but at least one item's worth, else CKKSMI_EWORKSPACE) the call splits

@@ -445,26 +445,50 @@ class Oracle:
         self._L.orc_sum_pool2d(self._h, _p64(x), Cc, H, W, k, level, _p64(out))
         return out
 
-    def rescale_each(self, cts, level):
+    def _map(self, fn, n, workers):
+        """fn(b) for b < n; independent ciphertexts may be spread over threads (the C calls release the GIL)"""
+        if workers <= 1:
+            for b in range(n):
+                fn(b)
+        else:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(workers) as ex:
+                list(ex.map(fn, range(n)))
+
+    def rescale_each(self, cts, level, workers=1):
         """Rescale every ciphertext of an array [...][2][level][N]."""
         cts = _u64(cts)
         lead = cts.shape[:-3]
         flat = cts.reshape((-1, 2, level, self.N))
         out = np.empty((flat.shape[0], 2, level - 1, self.N), dtype=np.uint64)
-        for b in range(flat.shape[0]):
+
+        def one(b):
             out[b] = self.rescale(flat[b], level)
+        self._map(one, flat.shape[0], workers)
         return out.reshape(lead + (2, level - 1, self.N))
 
-    def square_each(self, cts, rlk, level):
+    def square_each(self, cts, rlk, level, workers=1):
         cts = _u64(cts)
         lead = cts.shape[:-3]
         flat = cts.reshape((-1, 2, level, self.N))
         out = np.empty((flat.shape[0], 2, level - 1, self.N), dtype=np.uint64)
-        for b in range(flat.shape[0]):
+
+        def one(b):
             out[b] = self.hmul_relin_rescale(flat[b], flat[b], rlk, level)
+        self._map(one, flat.shape[0], workers)
         return out.reshape(lead + (2, level - 1, self.N))
 
-    def cnn_forward(self, x, layers, rlk, level):
+    def conv2d_mac_each(self, x, w, stride, pad, level, workers=1):
+        """conv2d_mac, one output channel per call"""
+        w = _i64(w)
+        parts = [None] * w.shape[0]
+
+        def one(o):
+            parts[o] = self.conv2d_mac(x, w[o:o + 1], stride, pad, level)
+        self._map(one, w.shape[0], workers)
+        return np.concatenate(parts, axis=0)
+
+    def cnn_forward(self, x, layers, rlk, level, workers=1):
         """A feed-forward network over per-pixel ciphertexts (section 3: convolution, pooling, polynomial activation
         and fully connected layers in sequence), slot s = image s.
 
@@ -474,22 +498,23 @@ class Oracle:
           ("pool", k)                                  k x k sum pooling                                level unchanged
           ("fc", w_int [O][F])                         flatten [C][H][W] in that order, MAC, rescale    level -> level-1
         Integer weights are prepared by the caller (round(w * dropped modulus)).  Returns (cts, level).
+        workers > 1 only spreads independent ciphertexts over threads.
         """
         x = _u64(x)
         for layer in layers:
             kind = layer[0]
             if kind == "conv":
                 _, w, stride, pad = layer
-                x = self.rescale_each(self.conv2d_mac(x, w, stride, pad, level), level)
+                x = self.rescale_each(self.conv2d_mac_each(x, w, stride, pad, level, workers), level, workers)
                 level -= 1
             elif kind == "square":
-                x = self.square_each(x, rlk, level)
+                x = self.square_each(x, rlk, level, workers)
                 level -= 1
             elif kind == "pool":
                 x = self.sum_pool2d(x, layer[1], level)
             elif kind == "fc":
                 flat = x.reshape((-1, 2, level, self.N))
-                x = self.rescale_each(self.fc_mac(flat, layer[1], level), level)
+                x = self.rescale_each(self.fc_mac(flat, layer[1], level), level, workers)
                 level -= 1
                 x = x.reshape((x.shape[0], 1, 1, 2, level, self.N))
             else:

@@ -825,8 +825,9 @@ extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, u
     return g.rc();
 }
 
-extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride,
-                                 int pad, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream) {
+extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw,
+                                      int stride, int pad, int in_row0, int in_rows, int out_row0, int out_rows, uint64_t *out, int level,
+                                      void *ws, size_t ws_bytes, void *stream) {
     if (!c) return CKKSMI_EINVAL;
     if (!dev_ok(c)) return CKKSMI_EDEVICE;
     if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
@@ -834,9 +835,15 @@ extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_
     if (C < 1 || H < 1 || W < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0) return CKKSMI_EINVAL;
     if (H + 2 * pad < kh || W + 2 * pad < kw) return CKKSMI_EINVAL;
     const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    if (out_row0 < 0 || out_rows < 1 || out_row0 > Ho - out_rows) return CKKSMI_EINVAL;
+    if (in_row0 < 0 || in_rows < 1 || in_row0 > H - in_rows) return CKKSMI_EINVAL;
+    // every image row that a tap of the requested output rows can touch must lie inside the strip
+    const long long first = std::max(0LL, (long long)out_row0 * stride - pad);
+    const long long last = std::min((long long)H - 1, (long long)(out_row0 + out_rows - 1) * stride - pad + kh - 1);
+    if (first <= last && (first < in_row0 || last >= (long long)in_row0 + in_rows)) return CKKSMI_EINVAL;
     const size_t n_weights = (size_t)O * C * kh * kw;
     if (ws_bytes < n_weights * level * sizeof(WMul)) return CKKSMI_EWORKSPACE;
-    const size_t zdim = (size_t)Ho * Wo * ((O + MAC_OC - 1) / MAC_OC);
+    const size_t zdim = (size_t)out_rows * Wo * ((O + MAC_OC - 1) / MAC_OC);
     if (zdim > 0x7fffffffu || ew_blocks(c->N) > 65535) return CKKSMI_EUNSUPPORTED;
     Guard g(c);
     KL(c, CKKSMI_K_MACPREP, 1, mac_prepare_kernel, dim3(ew_blocks(n_weights * level)), dim3(EW_THREADS), S(stream), (const long long *)w, (WMul *)ws,
@@ -845,7 +852,30 @@ extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_
     A.in = (const u64d *)in; A.out = (u64d *)out; A.wtab = (const WMul *)ws; A.modc = c->d_mod;
     A.logN = c->logN; A.level = level;
     A.C = C; A.H = H; A.W = W; A.O = O; A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.Ho = Ho; A.Wo = Wo;
-    KL(c, CKKSMI_K_MAC, (double)O * Ho * Wo * 2 * level, conv_mac_kernel, dim3((unsigned)zdim, ew_blocks(c->N), 2 * level), dim3(EW_THREADS), S(stream), A);
+    A.in_row0 = in_row0; A.in_rows = in_rows; A.out_row0 = out_row0; A.out_rows = out_rows;
+    KL(c, CKKSMI_K_MAC, (double)O * out_rows * Wo * 2 * level, conv_mac_kernel, dim3((unsigned)zdim, ew_blocks(c->N), 2 * level), dim3(EW_THREADS), S(stream), A);
+    return g.rc();
+}
+
+extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride,
+                                 int pad, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream) {
+    if (H < 1 || kh < 1 || stride < 1 || pad < 0 || H + 2 * pad < kh) return CKKSMI_EINVAL;
+    const int Ho = (H + 2 * pad - kh) / stride + 1;
+    return ckksmi_conv2d_mac_rows(c, in, w, C, H, W, O, kh, kw, stride, pad, 0, H, 0, Ho, out, level, ws, ws_bytes, stream);
+}
+
+extern "C" int ckksmi_sum_pool2d(ckksmi_ctx *c, const uint64_t *in, int C, int H, int W, int k, uint64_t *out, int level, void *stream) {
+    if (!c) return CKKSMI_EINVAL;
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
+    if (!in || !out || in == out) return CKKSMI_EINVAL;
+    if (C < 1 || H < 1 || W < 1 || k < 1 || k > 16 || H < k || W < k) return CKKSMI_EINVAL;
+    const int Ho = H / k, Wo = W / k;
+    const size_t total = (size_t)C * Ho * Wo * 2 * level * c->N;
+    if (ew_blocks(total) > 0x7fffffffu) return CKKSMI_EUNSUPPORTED;
+    Guard g(c);
+    KL(c, CKKSMI_K_ELEMWISE, (double)C * Ho * Wo * 2 * level, sum_pool_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)in,
+                  (u64d *)out, c->d_mod, c->logN, level, H, W, k, Ho, Wo, total);
     return g.rc();
 }
 

@@ -557,15 +557,16 @@ __global__ __launch_bounds__(EW_THREADS) void mac_prepare_kernel(const long long
 #define MAC_OC 32  // output channels accumulated per thread (each input word is loaded once per 32 outputs)
 
 struct MacArgs {
-    const u64d *in;   // [C][H][W] ciphertexts of 2*level limbs
-    u64d *out;        // [O][Ho][Wo]
+    const u64d *in;   // [C][in_rows][W] ciphertexts of 2*level limbs: image rows in_row0 .. in_row0+in_rows-1
+    u64d *out;        // [O][out_rows][Wo]: output rows out_row0 .. out_row0+out_rows-1
     const WMul *wtab; // [level][O*C*kh*kw]
     const ModConst *modc;
     int logN, level;
     int C, H, W, O, kh, kw, stride, pad, Ho, Wo;
+    int in_row0, in_rows, out_row0, out_rows;
 };
 
-// grid: x = Ho*Wo*ceil(O/MAC_OC) (fastest: workgroups that share input words run together), y = N / EW_THREADS,
+// grid: x = out_rows*Wo*ceil(O/MAC_OC) (fastest: workgroups that share input words run together), y = N / EW_THREADS,
 // z = 2*level (component-major limb)
 __global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
     const unsigned N = 1u << A.logN;
@@ -574,7 +575,8 @@ __global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
     const unsigned lc = blockIdx.z, i = lc % (unsigned)A.level;
     const unsigned ogroups = (unsigned)(A.O + MAC_OC - 1) / MAC_OC;
     const unsigned og = blockIdx.x % ogroups, pos = blockIdx.x / ogroups;
-    const int oy = (int)(pos / (unsigned)A.Wo), ox = (int)(pos % (unsigned)A.Wo);
+    const int oyl = (int)(pos / (unsigned)A.Wo), ox = (int)(pos % (unsigned)A.Wo);
+    const int oy = A.out_row0 + oyl;
     const int o0 = (int)og * MAC_OC;
     const ModConst mc = A.modc[i];
     const size_t ctw = (size_t)2 * A.level * N;
@@ -588,7 +590,8 @@ __global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
             for (int v = 0; v < A.kw; v++) {
                 const int iy = oy * A.stride + u - A.pad, ix = ox * A.stride + v - A.pad;
                 if (iy < 0 || iy >= A.H || ix < 0 || ix >= A.W) continue;
-                const double xv = u2d(A.in[(((size_t)c * A.H + iy) * A.W + ix) * ctw + (size_t)lc * N + n]);
+                // the host has checked that every image row a tap can touch lies inside the strip
+                const double xv = u2d(A.in[(((size_t)c * A.in_rows + (iy - A.in_row0)) * A.W + ix) * ctw + (size_t)lc * N + n]);
                 const size_t tap = ((size_t)c * A.kh + u) * A.kw + v;
                 for (int o = 0; o < MAC_OC; o++) {
                     if (o0 + o < A.O) {
@@ -603,5 +606,25 @@ __global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
             }
     for (int o = 0; o < MAC_OC; o++)
         if (o0 + o < A.O)
-            A.out[((((size_t)(o0 + o) * A.Ho + oy) * A.Wo + ox) * ctw) + (size_t)lc * N + n] = d2u(canon(acc[o], mc.p, mc.pinv));
+            A.out[((((size_t)(o0 + o) * A.out_rows + oyl) * A.Wo + ox) * ctw) + (size_t)lc * N + n] = d2u(canon(acc[o], mc.p, mc.pinv));
+}
+
+// k x k sum pooling of per-pixel ciphertexts: out[c][y][x] = sum_{u,v<k} in[c][k*y+u][k*x+v], word by word.
+// one thread per output word; idx runs over [C*Ho*Wo][2*level][N]
+__global__ __launch_bounds__(EW_THREADS) void sum_pool_kernel(const u64d *in, u64d *out, const ModConst *modc, int logN, int level, int H, int W,
+                                                              int k, int Ho, int Wo, size_t total) {
+    const size_t idx = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (idx >= total) return;
+    const size_t N = (size_t)1 << logN, ctw = (size_t)2 * level * N;
+    const size_t ct = idx / ctw, off = idx % ctw;
+    const unsigned i = (unsigned)((off >> logN) % (unsigned)level);
+    const u64d p = (u64d)modc[i].p;
+    const size_t x = ct % Wo, y = (ct / Wo) % Ho, c = ct / ((size_t)Wo * Ho);
+    u64d acc = 0;
+    for (int u = 0; u < k; u++)
+        for (int v = 0; v < k; v++) {
+            acc += in[((c * H + (k * y + u)) * W + (k * x + v)) * ctw + off];
+            acc = acc >= p ? acc - p : acc;
+        }
+    out[idx] = acc;
 }

@@ -258,3 +258,84 @@ def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
     ctx.fc_mac(dxf, dwf, F, Oc, outf, level, wsf, stream=be.stream)
     assert np.array_equal(be.to_host(outf).reshape(Oc, 2, level, O.N), O.fc_mac(xf, wfc, level)), "FC MAC differs"
     ctx.close()
+
+
+def case_cnn(be, shape, seed, topology, workers=1):
+    """conv - square - conv - square - conv - pool - fc - square - fc on per-pixel ciphertexts, every activation
+    resident, against the oracle's layer-by-layer network; plus the first conv layer again in strips of rows"""
+    from paper_1911_11377_amd import cnn
+
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    level = O.n_q
+    Cc, H, W = wl.CNN_TOPOLOGIES[topology]["input"]
+    x = wl.uniform_limbs(O.q[:level], O.N, seed, "cnn.x", lead=(Cc, H, W, 2))
+    shapes = wl.cnn_shapes(topology)
+    wf = wl.cnn_weights_float(topology, seed)
+    # the test's own integer weights for the oracle: round(w * q_dropped), the pooling's 1/k^2 folded forward
+    layers_i, lvl, fold = [], level, 1.0
+    for (layer, _, _), wt in zip(shapes, wf):
+        if layer[0] in ("conv", "fc"):
+            wi = np.rint(wt * fold * float(O.q[lvl - 1])).astype(np.int64)
+            fold = 1.0
+            layers_i.append(("conv", wi, layer[3], layer[4]) if layer[0] == "conv" else ("fc", wi))
+            lvl -= 1
+        elif layer[0] == "square":
+            layers_i.append(layer)
+            lvl -= 1
+        else:
+            layers_i.append(layer)
+            fold = 1.0 / (layer[1] * layer[1])
+    plans, out_level, _ = cnn.plan(shapes, wf, O.q, level, 2.0**50)
+    assert out_level == lvl
+    for p, li in zip(plans, layers_i):
+        if p.w_int is not None:
+            assert np.array_equal(p.w_int, li[1]), "integer weights differ"
+    want, want_level = O.cnn_forward(x, layers_i, M.rlk, level, workers=workers)
+    assert want_level == out_level
+    ws = be.ws(cnn.workspace_bytes(ctx, plans, max_items=16))
+    evk = be.to_dev(M.rlk)
+    dx = be.to_dev(x)
+    out = cnn.forward(ctx, dx, plans, evk, be.empty, lambda a: be.to_dev(a, np.int64), ws, stream=be.stream)
+    got = be.to_host(out).reshape(want.shape)
+    assert np.array_equal(got, want), "network output differs from the oracle"
+
+    # first layer in strips: every output row from only the input rows it needs
+    p = plans[0]
+    assert p.kind == "conv"
+    O1, Ho, Wo = p.out_shape
+    ref = O.rescale_each(O.conv2d_mac_each(x, layers_i[0][1], p.stride, p.pad, level, workers), level, workers)
+    wdev = be.to_dev(p.w_int, np.int64)
+    rows_per = 2
+    for r0 in range(0, Ho, rows_per):
+        rows = min(rows_per, Ho - r0)
+        i0 = max(0, r0 * p.stride - p.pad)
+        i1 = min(H - 1, (r0 + rows - 1) * p.stride - p.pad + p.kernel - 1)
+        strip = be.to_dev(np.ascontiguousarray(x[:, i0:i1 + 1]))
+        mac = be.empty(O1, rows, Wo, 2, level, O.N)
+        y = be.empty(O1, rows, Wo, 2, level - 1, O.N)
+        cnn.conv_rows(ctx, p, strip, wdev, i0, i1 - i0 + 1, r0, rows, mac, y, ws, stream=be.stream)
+        assert np.array_equal(be.to_host(y).reshape(O1, rows, Wo, 2, level - 1, O.N), ref[:, r0:r0 + rows]), "strip rows differ"
+    # a strip that lacks a needed input row is refused before anything is enqueued
+    if Ho >= 2:
+        try:
+            ctx.conv2d_mac_rows(strip, wdev, Cc, H, W, O1, p.kernel, p.kernel, p.stride, p.pad, 0, 1, 0, 2, mac, level, ws, stream=be.stream)
+            raise AssertionError("incomplete strip accepted")
+        except ckksmi.CkksmiError as e:
+            assert e.code == ckksmi.EINVAL
+    ctx.close()
+
+
+def case_pool(be, shape, seed, Cin, H, W, k, level=None):
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    level = level or O.n_q
+    x = wl.uniform_limbs(O.q[:level], O.N, seed, "pool.x", lead=(Cin, H, W, 2))
+    out = be.empty(Cin, H // k, W // k, 2, level, O.N)
+    ctx.sum_pool2d(be.to_dev(x), Cin, H, W, k, out, level, stream=be.stream)
+    assert np.array_equal(be.to_host(out).reshape(Cin, H // k, W // k, 2, level, O.N), O.sum_pool2d(x, k, level)), "pooling differs"
+    ctx.close()
+

@@ -57,6 +57,12 @@ def test_emulated_conv(be):
     pc.case_conv(be, TINY, seed=108, Cin=1, H=4, W=4, Oc=2, kh=3, stride=1, pad=1, level=2)
 
 
+def test_emulated_pool_and_network(be):
+    pc.case_pool(be, TINY, seed=112, Cin=2, H=5, W=4, k=2)
+    pc.case_pool(be, TINY, seed=113, Cin=1, H=3, W=3, k=3, level=2)
+    pc.case_cnn(be, (6, 10, 50, 3, 51, 3), seed=114, topology="cnn_tiny")
+
+
 def test_emulated_item_loop_and_composite_at_2e16(be, monkeypatch):
     """N = 2^16: both register-tiled passes, with workgroups looping over several items"""
     monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "16")

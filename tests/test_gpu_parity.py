@@ -103,6 +103,14 @@ def test_conv_at_layer_shape_slice(be):
     pc.case_conv(be, C3, seed=309, Cin=3, H=5, W=5, Oc=3, kh=5, stride=2, pad=0)
 
 
+def test_pool_and_network_match_oracle(be):
+    """the AlexNet-like layer sequence at reduced width, N=2^13 (fused key-switching kernels), 10 levels deep"""
+    announce("pool")
+    pc.case_pool(be, (10, 3, 40, 0, 41, 1), seed=310, Cin=3, H=6, W=7, k=2)
+    announce("network cnn_reduced N=2^13")
+    pc.case_cnn(be, (13, 10, 50, 3, 51, 3), seed=311, topology="cnn_reduced", workers=16)
+
+
 def _encrypt_batch(M, zs, scale, level, tag):
     return np.stack([M.encrypt(z, scale, level, (tag, i)) for i, z in enumerate(zs)])
 
