@@ -163,6 +163,95 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     return out
 
 
+def cnn_in_strips(torch, ckksmi, wl, gen):
+    """The AlexNet-like network at its real shape (N=2^16, 30x50-bit primes, 32768 images per pass, one ciphertext
+    per pixel).  Its activations (up to 0.8 TB per layer) do not fit on one GPU, so every layer runs strip by strip over
+    ALL of its output positions on buffers of uniform residues that are reused from strip to strip (ciphertexts are
+    pseudorandom and no kernel branches on data); the time is the sum over the strips of every layer."""
+    import numpy as np
+
+    from paper_1911_11377_amd import cnn
+
+    p5 = wl.PRESETS["cnn_2e16"]
+    c5 = ckksmi.Context(p5.logN, p5.n_q, p5.q_bits, p5.k, p5.special_bits, p5.alpha, device=0)
+    N, L = p5.N, p5.n_q
+    shapes = wl.cnn_shapes("cnn_2e16")
+    plans, out_level, _ = cnn.plan(shapes, wl.cnn_weights_float("cnn_2e16", 5), c5.q, L, 2.0 ** p5.log_scale)
+    evk = uniform_residues(torch, c5.moduli, (c5.beta_top, 2), N, gen)
+    ct_words = lambda level: 2 * level * N
+    SQ_BATCH = 256
+
+    # strip sizes: one output row per conv strip, two input rows per pooling strip, SQ_BATCH ciphertexts per square call
+    def strip_words(pl):
+        C, H, W = pl.in_shape
+        O, Ho, Wo = pl.out_shape
+        if pl.kind == "conv":
+            rows_in = min(H, pl.kernel)
+            return C * rows_in * W * ct_words(pl.level_in), O * Wo * ct_words(pl.level_in), O * Wo * ct_words(pl.level_out)
+        if pl.kind == "fc":
+            return C * H * W * ct_words(pl.level_in), O * ct_words(pl.level_in), O * ct_words(pl.level_out)
+        if pl.kind == "square":
+            n = min(SQ_BATCH, C * H * W)
+            return n * ct_words(pl.level_in), 0, n * ct_words(pl.level_out)
+        return C * pl.kernel * W * ct_words(pl.level_in), 0, O * Wo * ct_words(pl.level_out)
+
+    need = [strip_words(pl) for pl in plans]
+    ws_bytes = cnn.workspace_bytes(c5, plans, max_items=64)
+    in_words, mac_words, out_words = (max(n[i] for n in need) for i in range(3))
+    xin = torch.empty(in_words, dtype=torch.int64, device="cuda:0")
+    step = 1 << 27
+    for o in range(0, in_words, step):  # canonical for every prime: all of them exceed 2^49
+        xin[o:o + step].random_(0, 1 << 49, generator=gen)
+    mac = torch.empty(max(mac_words, 1), dtype=torch.int64, device="cuda:0")
+    out = torch.empty(out_words, dtype=torch.int64, device="cuda:0")
+    ws = torch.empty(ws_bytes // 8 + 1, dtype=torch.int64, device="cuda:0")
+    layers = []
+    total_ms = 0.0
+    for pl in plans:
+        C, H, W = pl.in_shape
+        O, Ho, Wo = pl.out_shape
+        wdev = torch.from_numpy(pl.w_int).to("cuda:0") if pl.w_int is not None else None
+        calls = []
+        if pl.kind == "conv":
+            for r in range(Ho):
+                i0 = max(0, r * pl.stride - pl.pad)
+                i1 = min(H - 1, r * pl.stride - pl.pad + pl.kernel - 1)
+                calls.append(lambda r=r, i0=i0, i1=i1: cnn.conv_rows(c5, pl, xin, wdev, i0, i1 - i0 + 1, r, 1, mac, out, ws))
+        elif pl.kind == "fc":
+            def fc():
+                c5.fc_mac(xin, wdev, C * H * W, O, mac, pl.level_in, ws)
+                c5.rescale(mac, out, pl.level_in, O, ws)
+            calls.append(fc)
+        elif pl.kind == "square":
+            n_ct = C * H * W
+            for b0 in range(0, n_ct, SQ_BATCH):
+                n = min(SQ_BATCH, n_ct - b0)
+                calls.append(lambda n=n: c5.hmul_relin_rescale(xin, xin, evk, out, pl.level_in, n, ws))
+        else:
+            for r in range(Ho):
+                calls.append(lambda: c5.sum_pool2d(xin, C, pl.kernel, W, pl.kernel, out, pl.level_in))
+        calls[0]()  # warm-up of this layer's kernels
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for f in calls:
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        total_ms += ms
+        layers.append({"layer": pl.kind, "in": list(pl.in_shape), "out": list(pl.out_shape), "level": pl.level_in, "strips": len(calls),
+                       "ms": round(ms, 1)})
+    images = N // 2
+    res = {"encrypted_images_per_s": round(images / (total_ms * 1e-3), 1), "images_per_pass": images, "s_per_pass": round(total_ms * 1e-3, 2),
+           "levels": [L, out_level], "layers": layers,
+           "what": "conv 3->32 5x5 s2, x^2, conv 32->64 3x3 s2, x^2, conv 64->64 3x3 pad 1, 2x2 sum pool, FC 3136->256, x^2, FC 256->2; "
+                   "every layer at its real shape over all output positions, strip by strip on reused synthetic buffers"}
+    del xin, mac, out, ws, evk
+    c5.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -171,6 +260,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweep (keeps a profile to the timed steps)")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (rotation at N=2^14, conv layer at N=2^15, activation schedule)")
+    ap.add_argument("--no-cnn", action="store_true", help="skip the full-size network in strips (about a minute of GPU time, 130 GB of HBM)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input batch (known size) so that profiler byte counters can be scaled")
     args = ap.parse_args()
@@ -294,6 +384,11 @@ def main():
         cpu = {"value": round(cores / (c1 - c0), 4), "unit": "ops/s", "cores": cores, "kind": "oracle",
                "sample": "%d of the %d HMult+relin+rescale of one step, one per thread, same inputs" % (cores, batch),
                "matches_gpu_bits": bool(match)}
+
+    if extras is not None and not args.no_cnn:
+        del a, b, evk, out, ws
+        torch.cuda.empty_cache()
+        extras["cnn_2e16_in_strips"] = cnn_in_strips(torch, ckksmi, wl, gen)
 
     line = {
         "metric": "HMult+relin+rescale ops/s at N=2^16", "value": round(value, 2), "unit": "ops/s", "n_gpus": 1,
