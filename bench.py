@@ -149,7 +149,7 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     wts = torch.from_numpy(__import__("numpy").rint(wl.weights_float((O, Cin, kh, kh), 3) * c3.q[L - 1]).astype("int64")).to("cuda:0")
     co = torch.empty((O * Ho * Ho, 2, L, N), dtype=torch.int64, device="cuda:0")
     cr = torch.empty((O * Ho * Ho, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
-    wm = torch.empty(c3.workspace_bytes(ckksmi.OP_CONV2D_MAC, L, wts.numel()) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    wm = torch.empty(c3.conv2d_workspace_bytes(Cin, O, kh, kh, L) // 8 + 1, dtype=torch.int64, device="cuda:0")
     wr = torch.empty(c3.workspace_bytes(ckksmi.OP_RESCALE, L, 256) // 8, dtype=torch.int64, device="cuda:0")
     ms_mac = timed(torch, lambda: c3.conv2d_mac(xin, wts, Cin, H, W, O, kh, kh, stride, 0, co, L, wm), 1)
     ms_rs = timed(torch, lambda: c3.rescale(co, cr, L, O * Ho * Ho, wr), 1)

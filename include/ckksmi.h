@@ -165,6 +165,11 @@ int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [bat
  * taps outside the image skipped; out at the same level (rescale separately).
  * in: [C][H][W] ciphertexts, out: [O][Ho][Wo], Ho = (H+2*pad-kh)/stride+1. */
 int ckksmi_conv2d_mac(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride, int pad, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
+/* Workspace for ckksmi_conv2d_mac / _rows / ckksmi_fc_mac (FC: C = F, kh = kw = 1) of this layer shape.  With at
+ * least this much the multiply-accumulate runs on the matrix cores where the shape allows (ring degree >= 64, at
+ * least 8 output channels, at most 16321 taps); with only ckksmi_workspace_bytes(CKKSMI_OP_CONV2D_MAC, ...) it runs
+ * on the vector ALU.  Both produce the same words. */
+int ckksmi_conv2d_workspace_bytes(const ckksmi_ctx *ctx, int C, int O, int kh, int kw, int level, size_t *bytes);
 /* The same convolution restricted to output rows out_row0 .. out_row0+out_rows-1, for layers whose activations do
  * not fit in device memory at once: `in` holds only image rows in_row0 .. in_row0+in_rows-1 as [C][in_rows][W]
  * ciphertexts and `out` receives [O][out_rows][Wo].  H is still the height of the whole image (it decides where
@@ -208,7 +213,9 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_ROWS_INNER 15      /* contiguous pass fused with the inner product */
 #define CKKSMI_K_ROWS_FINAL 16      /* contiguous pass fused with DivRound's last step */
 #define CKKSMI_K_CONV_COLS_RESCALE 17 /* the same with a single dropped prime (rescale) */
-#define CKKSMI_K_COUNT 18
+#define CKKSMI_K_MAC_MFMA 18      /* conv / FC multiply-accumulate on the matrix cores */
+#define CKKSMI_K_MACPREP_MFMA 19  /* its weight digits and tap table */
+#define CKKSMI_K_COUNT 20
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

@@ -72,6 +72,7 @@ SIGNATURES = {
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rotate": [VP, VP, intp, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_mac": [VP, VP, VP] + [C.c_int] * 8 + [VP, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_conv2d_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_conv2d_mac_rows": [VP, VP, VP] + [C.c_int] * 12 + [VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_fc_mac": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_sum_pool2d": [VP, VP, C.c_int, C.c_int, C.c_int, C.c_int, VP, C.c_int, VP],
@@ -81,7 +82,7 @@ SIGNATURES = {
     "ckksmi_kernel_class_name": [VP, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
-K_COUNT = 18
+K_COUNT = 20
 
 _LIBS = {}
 
@@ -262,6 +263,11 @@ class Context:
     def workspace_bytes(self, op, level, batch):
         n = C.c_size_t(0)
         self._call("ckksmi_workspace_bytes", self._h, op, level, batch, C.byref(n))
+        return n.value
+
+    def conv2d_workspace_bytes(self, Cin, O, kh, kw, level):
+        n = C.c_size_t(0)
+        self._call("ckksmi_conv2d_workspace_bytes", self._h, Cin, O, kh, kw, level, C.byref(n))
         return n.value
 
     def galois_key_register(self, rot, gk_dev):

@@ -70,7 +70,10 @@ def workspace_bytes(ctx, plans, max_items=64):
     for p in plans:
         n_out = int(np.prod(p.out_shape))
         if p.kind in ("conv", "fc"):
-            need = max(need, ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, p.level_in, p.w_int.size))
+            if p.kind == "conv":
+                need = max(need, ctx.conv2d_workspace_bytes(p.in_shape[0], p.out_shape[0], p.kernel, p.kernel, p.level_in))
+            else:
+                need = max(need, ctx.conv2d_workspace_bytes(int(np.prod(p.in_shape)), n_out, 1, 1, p.level_in))
             need = max(need, ctx.workspace_bytes(ckksmi.OP_RESCALE, p.level_in, min(n_out, max_items)))
         elif p.kind == "square":
             need = max(need, ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, p.level_in, min(n_out, max_items)))

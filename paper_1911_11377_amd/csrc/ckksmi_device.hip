@@ -14,6 +14,7 @@
 #include "kernels.h"
 #include "ntt_v2.h"
 #include "ks_fused.h"
+#include "mac_mfma.h"
 
 // Launch `kern`; when profiling is on, bracket it with two events on the same stream and
 // remember them under kernel class `kid` together with `units` of algorithmic work.
@@ -451,6 +452,12 @@ int dev_upload_tables(ckksmi_ctx *c) {
     const size_t N = c->N;
     const int T = c->T;
     c->d_mod = upload(c, c->h_modc, T, ok);
+    {
+        std::vector<WMul> p24(T);
+        for (int t = 0; t < T; t++) p24[t] = make_wmul(((u64)1 << 24) % c->mod[t], c->mod[t]);
+        c->d_pow24 = upload(c, p24.data(), p24.size(), ok);
+        if (const char *e = getenv("CKKSMI_MAC_MFMA")) c->mac_mfma = atoi(e) != 0;
+    }
     for (int t = 0; t < T; t++)
         if (c->mod[t] >= ((u64)1 << 50)) c->p51mask.w[t >> 6] |= 1ull << (t & 63);
     std::vector<WMul> fwd((size_t)T * N), inv((size_t)T * N), last(T);
@@ -825,6 +832,26 @@ extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, u
     return g.rc();
 }
 
+namespace {
+// Which multiply-accumulate kernel a layer shape can use, and the workspace the matrix-core one needs.
+struct MacShape {
+    bool mfma_ok;
+    int Kb, Mg;  // 64-tap steps, 32-channel groups
+    size_t afrag_bytes, mfma_bytes;
+};
+MacShape mac_shape(const ckksmi_ctx *c, int C, int O, int kh, int kw, int level) {
+    MacShape s;
+    const long long K = (long long)C * kh * kw;
+    s.Kb = (int)((K + 63) / 64);
+    s.Mg = (O + MM_CH - 1) / MM_CH;
+    s.afrag_bytes = (size_t)level * s.Kb * s.Mg * MM_MB * MM_DIG * 64 * 16;
+    s.mfma_bytes = s.afrag_bytes + (size_t)s.Kb * 64 * sizeof(TapEnt);
+    // below 8 output channels most of a 32-channel group would multiply zeros: the vector kernel is faster there
+    s.mfma_ok = c->mac_mfma && c->N >= MM_WORDS && O >= 8 && K <= MM_KMAX - 63;
+    return s;
+}
+}  // namespace
+
 extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw,
                                       int stride, int pad, int in_row0, int in_rows, int out_row0, int out_rows, uint64_t *out, int level,
                                       void *ws, size_t ws_bytes, void *stream) {
@@ -842,10 +869,28 @@ extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const i
     const long long last = std::min((long long)H - 1, (long long)(out_row0 + out_rows - 1) * stride - pad + kh - 1);
     if (first <= last && (first < in_row0 || last >= (long long)in_row0 + in_rows)) return CKKSMI_EINVAL;
     const size_t n_weights = (size_t)O * C * kh * kw;
+    Guard g(c);
+    MacShape ms = mac_shape(c, C, O, kh, kw, level);
+    if (ms.mfma_ok && ws_bytes >= ms.mfma_bytes && (size_t)C * in_rows * W < MM_TAP_DELTA_MAX && kh <= MM_TAP_KMAX && kw <= MM_TAP_KMAX) {
+        const size_t real = (size_t)out_rows * Wo * ms.Mg * (c->N / MM_WORDS) * 2 * level;
+        const size_t xdim = (real + 7) / 8 * 8;
+        if (xdim > 0x7fffffffu) return CKKSMI_EUNSUPPORTED;
+        v4i *afrag = (v4i *)ws;
+        TapEnt *taps = (TapEnt *)((char *)ws + ms.afrag_bytes);
+        const size_t prep = std::max(ms.afrag_bytes / 16, (size_t)ms.Kb * 64);
+        KL(c, CKKSMI_K_MACPREP_MFMA, 1, mac_prepare_mfma_kernel, dim3(ew_blocks(prep)), dim3(EW_THREADS), S(stream), (const long long *)w, afrag, taps,
+                      c->d_mod, level, O, C, kh, kw, in_rows, W, ms.Kb, ms.Mg);
+        MacMfmaArgs A;
+        A.in = (const u64d *)in; A.out = (u64d *)out; A.afrag = afrag; A.taps = taps; A.modc = c->d_mod; A.pow24 = c->d_pow24;
+        A.logN = c->logN; A.level = level; A.H = H; A.W = W; A.O = O; A.stride = stride; A.pad = pad; A.Wo = Wo;
+        A.in_row0 = in_row0; A.in_rows = in_rows; A.out_row0 = out_row0; A.out_rows = out_rows; A.Kb = ms.Kb; A.Mg = ms.Mg;
+        A.positions = (unsigned)(out_rows * Wo); A.total_wgs = xdim; A.real_wgs = real;
+        KL(c, CKKSMI_K_MAC_MFMA, (double)O * out_rows * Wo * 2 * level, conv_mac_mfma_kernel, dim3((unsigned)xdim), dim3(256), S(stream), A);
+        return g.rc();
+    }
     if (ws_bytes < n_weights * level * sizeof(WMul)) return CKKSMI_EWORKSPACE;
     const size_t zdim = (size_t)out_rows * Wo * ((O + MAC_OC - 1) / MAC_OC);
     if (zdim > 0x7fffffffu || ew_blocks(c->N) > 65535) return CKKSMI_EUNSUPPORTED;
-    Guard g(c);
     KL(c, CKKSMI_K_MACPREP, 1, mac_prepare_kernel, dim3(ew_blocks(n_weights * level)), dim3(EW_THREADS), S(stream), (const long long *)w, (WMul *)ws,
                   c->d_mod, level, n_weights);
     MacArgs A;
@@ -855,6 +900,15 @@ extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const i
     A.in_row0 = in_row0; A.in_rows = in_rows; A.out_row0 = out_row0; A.out_rows = out_rows;
     KL(c, CKKSMI_K_MAC, (double)O * out_rows * Wo * 2 * level, conv_mac_kernel, dim3((unsigned)zdim, ew_blocks(c->N), 2 * level), dim3(EW_THREADS), S(stream), A);
     return g.rc();
+}
+
+extern "C" int ckksmi_conv2d_workspace_bytes(const ckksmi_ctx *c, int C, int O, int kh, int kw, int level, size_t *bytes) {
+    if (!c || !bytes || C < 1 || O < 1 || kh < 1 || kw < 1) return CKKSMI_EINVAL;
+    if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
+    const MacShape ms = mac_shape(c, C, O, kh, kw, level);
+    const size_t valu = (size_t)O * C * kh * kw * level * sizeof(WMul);
+    *bytes = ms.mfma_ok ? std::max(valu, ms.mfma_bytes) : valu;
+    return CKKSMI_OK;
 }
 
 extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride,
@@ -919,7 +973,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
-                                                "rows_final_kernel", "conv_cols_kernel"};
+                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && c->logN >= 13 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",

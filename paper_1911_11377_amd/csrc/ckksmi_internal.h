@@ -87,6 +87,8 @@ struct ckksmi_ctx {
 
     // ---- device tables ----
     ModConst *d_mod = nullptr;   // [T]
+    WMul *d_pow24 = nullptr;     // [T] 2^24 mod p (matrix-core MAC: recombination of the digit diagonals)
+    int mac_mfma = 1;            // conv / FC MAC on the matrix cores where the shape allows (CKKSMI_MAC_MFMA=0: vector ALU only)
     WMul *d_tw_fwd = nullptr;    // [T][N]  psi^brev(x), x in [1,N)
     WMul *d_tw_inv = nullptr;    // [T][N]  psi^-brev(x); entry 0 holds N^-1
     WMul *d_tw_inv_last = nullptr;  // [T]   psi^-brev(1) * N^-1  (last inverse stage)

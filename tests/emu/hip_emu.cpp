@@ -93,5 +93,31 @@ void guarded_free(void *p) {
 
 }  // namespace emu
 
+// Matrix-core instruction v_mfma_i32_16x16x64_i8 for one wave of 64 fibers: lane l supplies 16 bytes of A (row l%16,
+// k-group l/16) and of B (column l%16, k-group l/16) and receives D[4*(l/16)+r][l%16].  Every thread of the block must
+// reach the call (the exchange uses the block barrier).
+typedef int emu_v4i __attribute__((vector_size(16)));
+emu_v4i emu_mfma_i32_16x16x64_i8(emu_v4i a, emu_v4i b, emu_v4i c) {
+    static emu_v4i sa[1024], sb[1024];
+    const unsigned tid = threadIdx.x + blockDim.x * (threadIdx.y + blockDim.y * threadIdx.z);
+    sa[tid] = a;
+    sb[tid] = b;
+    emu::sync();
+    const unsigned base = tid & ~63u, lane = tid & 63u, col = lane % 16, g = lane / 16;
+    for (int r = 0; r < 4; r++) {
+        const unsigned row = 4 * g + r;
+        int sum = 0;
+        for (unsigned kg = 0; kg < 4; kg++) {
+            signed char ab[16], bb[16];
+            memcpy(ab, &sa[base + kg * 16 + row], 16);
+            memcpy(bb, &sb[base + kg * 16 + col], 16);
+            for (int t = 0; t < 16; t++) sum += (int)ab[t] * (int)bb[t];
+        }
+        c[r] += sum;
+    }
+    emu::sync();
+    return c;
+}
+
 extern "C" void *emu_alloc(size_t bytes) { return emu::guarded_alloc(bytes); }
 extern "C" void emu_free(void *p) { emu::guarded_free(p); }

@@ -232,6 +232,11 @@ def case_rotate(be, shape, seed, rotations, batch=4, level=None):
     ctx.close()
 
 
+def mfma_enabled():
+    import os
+    return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"
+
+
 def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
     M = make_material(shape, seed)
     O = M.O
@@ -243,18 +248,28 @@ def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
     wi.flat[0] = -(1 << 62) + 7  # a weight far outside (-q/2, q/2)
     Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kh) // stride + 1
     dx, dw = be.to_dev(x), be.to_dev(wi, np.int64)
-    out = be.empty(Oc, Ho, Wo, 2, level, O.N)
-    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, level, wi.size))
-    ctx.conv2d_mac(dx, dw, Cin, H, W, Oc, kh, kh, stride, pad, out, level, ws, stream=be.stream)
-    got = be.to_host(out).reshape(Oc, Ho, Wo, 2, level, O.N)
-    assert np.array_equal(got, O.conv2d_mac(x, wi, stride, pad, level)), "conv MAC differs from the oracle"
+    want = O.conv2d_mac(x, wi, stride, pad, level)
+    # both multiply-accumulate kernels: the small workspace only fits the vector one, the layer's own query admits
+    # the matrix-core one where the shape allows it
+    mfma_shape = O.N >= 64 and Oc >= 8
+    for which, nbytes in (("vector", ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, level, wi.size)),
+                          ("auto", ctx.conv2d_workspace_bytes(Cin, Oc, kh, kh, level))):
+        out = be.empty(Oc, Ho, Wo, 2, level, O.N)
+        ws = be.ws(nbytes)
+        ctx.profile_enable(True)
+        ctx.conv2d_mac(dx, dw, Cin, H, W, Oc, kh, kh, stride, pad, out, level, ws, stream=be.stream)
+        got = be.to_host(out).reshape(Oc, Ho, Wo, 2, level, O.N)
+        ran = ctx.profile_read()
+        ctx.profile_enable(False)
+        assert ("conv_mac_mfma_kernel" in ran) == (which == "auto" and mfma_shape and mfma_enabled()), (which, list(ran))
+        assert np.array_equal(got, want), "conv MAC (%s) differs from the oracle" % which
     # FC: flat features
     F = Cin * H
     xf = x[:, :, 0].reshape(F, 2, level, O.N)
     wfc = np.rint(wl.weights_float((Oc, F), seed, "fc") * O.q[level - 1]).astype(np.int64)
     dxf, dwf = be.to_dev(xf), be.to_dev(wfc, np.int64)
     outf = be.empty(Oc, 2, level, O.N)
-    wsf = be.ws(ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, level, wfc.size))
+    wsf = be.ws(ctx.conv2d_workspace_bytes(F, Oc, 1, 1, level))
     ctx.fc_mac(dxf, dwf, F, Oc, outf, level, wsf, stream=be.stream)
     assert np.array_equal(be.to_host(outf).reshape(Oc, 2, level, O.N), O.fc_mac(xf, wfc, level)), "FC MAC differs"
     ctx.close()

@@ -57,6 +57,11 @@ def test_emulated_conv(be):
     pc.case_conv(be, TINY, seed=108, Cin=1, H=4, W=4, Oc=2, kh=3, stride=1, pad=1, level=2)
 
 
+def test_emulated_conv_matrix_cores(be):
+    """two 64-tap steps, two 32-channel groups (the second mostly empty), two 64-word blocks, zero padding, 51-bit prime"""
+    pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=115, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)
+
+
 def test_emulated_pool_and_network(be):
     pc.case_pool(be, TINY, seed=112, Cin=2, H=5, W=4, k=2)
     pc.case_pool(be, TINY, seed=113, Cin=1, H=3, W=3, k=3, level=2)

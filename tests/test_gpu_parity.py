@@ -97,6 +97,14 @@ def test_conv_and_fc_match_oracle(be):
     pc.case_conv(be, (8, 2, 50, 1, 51, 1), seed=308, Cin=2, H=4, W=5, Oc=3, kh=3, stride=1, pad=1)
 
 
+def test_conv_matrix_cores_shapes(be):
+    """multi-step / multi-group shapes of the matrix-core multiply-accumulate, with zero padding and a ragged channel group"""
+    announce("conv matrix cores 51-bit")
+    pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=312, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)
+    announce("conv matrix cores N=2^13")
+    pc.case_conv(be, (13, 3, 50, 0, 51, 1), seed=313, Cin=8, H=3, W=4, Oc=40, kh=3, stride=1, pad=1)
+
+
 def test_conv_at_layer_shape_slice(be):
     """N=2^15, 16x50-bit limbs, 3 input channels, 5x5 stride 2: one output position, three filters"""
     announce("conv N=2^15 level 16 slice")
