@@ -845,7 +845,7 @@ MacShape mac_shape(const ckksmi_ctx *c, int C, int O, int kh, int kw, int level)
     s.Kb = (int)((K + 63) / 64);
     s.Mg = (O + MM_CH - 1) / MM_CH;
     s.afrag_bytes = (size_t)level * s.Kb * s.Mg * MM_MB * MM_DIG * 64 * 16;
-    s.mfma_bytes = s.afrag_bytes + (size_t)s.Kb * 64 * sizeof(TapEnt);
+    s.mfma_bytes = s.afrag_bytes + 2 * (size_t)s.Kb * 64 * sizeof(TapEnt);
     // below 8 output channels most of a 32-channel group would multiply zeros: the vector kernel is faster there
     s.mfma_ok = c->mac_mfma && c->N >= MM_WORDS && O >= 8 && K <= MM_KMAX - 63;
     return s;
@@ -882,7 +882,7 @@ extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const i
                       c->d_mod, level, O, C, kh, kw, in_rows, W, ms.Kb, ms.Mg);
         MacMfmaArgs A;
         A.in = (const u64d *)in; A.out = (u64d *)out; A.afrag = afrag; A.taps = taps; A.modc = c->d_mod; A.pow24 = c->d_pow24;
-        A.logN = c->logN; A.level = level; A.H = H; A.W = W; A.O = O; A.stride = stride; A.pad = pad; A.Wo = Wo;
+        A.logN = c->logN; A.level = level; A.H = H; A.W = W; A.O = O; A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.Wo = Wo;
         A.in_row0 = in_row0; A.in_rows = in_rows; A.out_row0 = out_row0; A.out_rows = out_rows; A.Kb = ms.Kb; A.Mg = ms.Mg;
         A.positions = (unsigned)(out_rows * Wo); A.total_wgs = xdim; A.real_wgs = real;
         KL(c, CKKSMI_K_MAC_MFMA, (double)O * out_rows * Wo * 2 * level, conv_mac_mfma_kernel, dim3((unsigned)xdim), dim3(256), S(stream), A);

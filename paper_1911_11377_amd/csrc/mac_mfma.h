@@ -46,6 +46,8 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 // One tap packed in 32 bits: bits 0..21 (c*in_rows + u)*W + v = ciphertext index relative to the window origin,
 // bits 22..26 kernel row u, bits 27..31 kernel column v; u = 31 marks a padding entry beyond the last tap.
+// A second table holds delta * 2*level (the tap's limb-row offset) for windows that lie wholly inside the image, where
+// no tap needs a bounds check; entries beyond the last tap are 0 there: their weights are zero, any word will do.
 typedef unsigned TapEnt;
 #define MM_TAP_DELTA_MAX (1u << 22)
 #define MM_TAP_KMAX 30  // largest kernel height / width
@@ -54,11 +56,11 @@ struct MacMfmaArgs {
     const u64d *in;       // [C][in_rows][W] ciphertexts
     u64d *out;            // [O][out_rows][Wo]
     const v4i *afrag;     // [level][Kb][Mg][MM_MB][MM_DIG][64 lanes] 16-byte A fragments
-    const TapEnt *taps;   // [Kb*64]
+    const TapEnt *taps;   // [2][Kb*64]: packed entries, then premultiplied offsets
     const ModConst *modc;
     const WMul *pow24;    // 2^24 mod p per modulus
     int logN, level;
-    int H, W, O, stride, pad, Wo;
+    int H, W, O, kh, kw, stride, pad, Wo;
     int in_row0, in_rows, out_row0, out_rows;
     int Kb, Mg;
     unsigned positions;                  // out_rows * Wo
@@ -78,6 +80,7 @@ __global__ __launch_bounds__(EW_THREADS) void mac_prepare_mfma_kernel(const long
             e = ((c * in_rows + u) * W + v) | (u << 22) | (v << 27);
         }
         taps[k] = e;
+        taps[(size_t)Kb * 64 + k] = k < K ? (e & (MM_TAP_DELTA_MAX - 1)) * (unsigned)(2 * level) : 0u;
     }
     const size_t total = (size_t)level * Kb * Mg * MM_MB * MM_DIG * 64;
     if (idx >= total) return;
@@ -118,20 +121,28 @@ __device__ __forceinline__ void transpose4(const unsigned (&a)[4], unsigned (&o)
 }
 
 // Request the 16 words of one k-step (taps kb*64 + 16g + t of this lane's word) from their tap entries, and this
-// thread's share of the step's A fragments.  A tap on padding reads word 0 of the strip instead (always valid) and is
-// zeroed when the digits are formed: bit t of the returned mask says tap t is real.
+// thread's share of the step's A fragments.  INTERIOR: the window lies inside the image, the entries are limb-row
+// offsets and every load is valid.  Otherwise a tap on padding reads limb row 0 of the strip instead (always valid) and
+// is zeroed when the digits are formed: bit t of the returned mask says tap t is real.
 #define MM_ACHUNKS ((MM_MB * MM_DIG * 64 + 255) / 256)
-__device__ __forceinline__ unsigned mm_issue_loads(const MacMfmaArgs &A, const TapEnt (&ent)[16], int iy0, int ix0, int origin, size_t ctw,
-                                                   const u64d *inw, const v4i *asrc, unsigned tid, u64d (&x)[16], v4i (&ap)[MM_ACHUNKS]) {
+template <bool INTERIOR>
+__device__ __forceinline__ unsigned mm_issue_loads(const MacMfmaArgs &A, const TapEnt (&ent)[16], int iy0, int ix0, int origin, const u64d *inw,
+                                                   const v4i *asrc, unsigned tid, u64d (&x)[16], v4i (&ap)[MM_ACHUNKS]) {
     unsigned mask = 0;
+    const unsigned twoL = 2u * (unsigned)A.level;
 #pragma unroll
     for (int t = 0; t < 16; t++) {
         const unsigned e = ent[t];
-        const int iy = iy0 + (int)((e >> 22) & 31u), ix = ix0 + (int)(e >> 27);
-        const bool ok = (unsigned)iy < (unsigned)A.H && (unsigned)ix < (unsigned)A.W;
-        const unsigned idx = ok ? (unsigned)(origin + (int)(e & (MM_TAP_DELTA_MAX - 1))) : 0u;
-        x[t] = inw[(size_t)idx * ctw];
-        mask |= ok ? 1u << t : 0u;
+        unsigned row;  // limb row of the tap's ciphertext: ciphertext index * 2*level, below 2^30
+        if (INTERIOR) {
+            row = e + (unsigned)origin * twoL;
+        } else {
+            const int iy = iy0 + (int)((e >> 22) & 31u), ix = ix0 + (int)(e >> 27);
+            const bool ok = (unsigned)iy < (unsigned)A.H && (unsigned)ix < (unsigned)A.W;
+            row = ok ? __umul24((unsigned)(origin + (int)(e & (MM_TAP_DELTA_MAX - 1))), twoL) : 0u;
+            mask |= ok ? 1u << t : 0u;
+        }
+        x[t] = inw[(size_t)row << A.logN];
     }
 #pragma unroll
     for (int e = 0; e < MM_ACHUNKS; e++) {
@@ -146,17 +157,32 @@ __device__ __forceinline__ unsigned mm_issue_loads(const MacMfmaArgs &A, const T
 // contiguous range of v, in which the channel group is the fastest index, then the output position, then the word
 // block, then the limb -- consecutive workgroups of one XCD read the same input words (other channels, overlapping
 // windows) and find them in its L2.
+template <bool INTERIOR>
+__device__ __forceinline__ void conv_mac_mfma_body(const MacMfmaArgs &A, v4i *a_lds, unsigned mg, unsigned pos, unsigned wb, unsigned lc);
+
 __global__ __launch_bounds__(256, 2) void conv_mac_mfma_kernel(MacMfmaArgs A) {
     __shared__ v4i a_lds[MM_MB * MM_DIG * 64];
     const unsigned N = 1u << A.logN;
-    const unsigned tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t per_xcd = A.total_wgs / 8;
     size_t v = (size_t)(blockIdx.x % 8u) * per_xcd + blockIdx.x / 8u;
     if (v >= A.real_wgs) return;  // uniform for the workgroup
     const unsigned mg = (unsigned)(v % (unsigned)A.Mg); v /= (unsigned)A.Mg;
     const unsigned pos = (unsigned)(v % A.positions); v /= A.positions;
     const unsigned wb = (unsigned)(v % (N / MM_WORDS)); v /= (N / MM_WORDS);
-    const unsigned lc = (unsigned)v, i = lc % (unsigned)A.level;
+    const unsigned lc = (unsigned)v;
+    const int oyl = (int)(pos / (unsigned)A.Wo), ox = (int)(pos % (unsigned)A.Wo);
+    const int iy0 = (A.out_row0 + oyl) * A.stride - A.pad, ix0 = ox * A.stride - A.pad;
+    if (iy0 >= 0 && iy0 + A.kh <= A.H && ix0 >= 0 && ix0 + A.kw <= A.W)
+        conv_mac_mfma_body<true>(A, a_lds, mg, pos, wb, lc);
+    else
+        conv_mac_mfma_body<false>(A, a_lds, mg, pos, wb, lc);
+}
+
+template <bool INTERIOR>
+__device__ __forceinline__ void conv_mac_mfma_body(const MacMfmaArgs &A, v4i *a_lds, unsigned mg, unsigned pos, unsigned wb, unsigned lc) {
+    const unsigned N = 1u << A.logN;
+    const unsigned tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const unsigned i = lc % (unsigned)A.level;
     const int oyl = (int)(pos / (unsigned)A.Wo), ox = (int)(pos % (unsigned)A.Wo);
     const int iy0 = (A.out_row0 + oyl) * A.stride - A.pad, ix0 = ox * A.stride - A.pad;
     const int origin = (iy0 - A.in_row0) * A.W + ix0;
@@ -177,10 +203,10 @@ __global__ __launch_bounds__(256, 2) void conv_mac_mfma_kernel(MacMfmaArgs A) {
     u64d x[16];
     v4i ap[MM_ACHUNKS];
     TapEnt ent[16];
-    const TapEnt *tp = A.taps + 16 * g;
+    const TapEnt *tp = A.taps + (INTERIOR ? (size_t)A.Kb * 64 : 0) + 16 * g;
 #pragma unroll
     for (int t = 0; t < 16; t++) ent[t] = tp[t];
-    unsigned mask = mm_issue_loads(A, ent, iy0, ix0, origin, ctw, inw, asrc, tid, x, ap);
+    unsigned mask = mm_issue_loads<INTERIOR>(A, ent, iy0, ix0, origin, inw, asrc, tid, x, ap);
     if (A.Kb > 1) {
 #pragma unroll
         for (int t = 0; t < 16; t++) ent[t] = tp[64 + t];
@@ -197,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void conv_mac_mfma_kernel(MacMfmaArgs A) {
         unsigned lo[16], hi[16];
 #pragma unroll
         for (int t = 0; t < 16; t++) {
-            const u64d dg = ((mask >> t) & 1u) ? (x[t] + MM_BIAS) ^ MM_BIAS : 0ull;
+            const u64d dg = (INTERIOR || ((mask >> t) & 1u)) ? (x[t] + MM_BIAS) ^ MM_BIAS : 0ull;
             lo[t] = (unsigned)dg;
             hi[t] = (unsigned)(dg >> 32);
         }
@@ -218,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void conv_mac_mfma_kernel(MacMfmaArgs A) {
         }
         // the next step's operands are requested before this step's matrix work so that their latency hides behind it
         if (kb + 1 < A.Kb) {
-            mask = mm_issue_loads(A, ent, iy0, ix0, origin, ctw, inw, asrc + (size_t)(kb + 1) * astep, tid, x, ap);
+            mask = mm_issue_loads<INTERIOR>(A, ent, iy0, ix0, origin, inw, asrc + (size_t)(kb + 1) * astep, tid, x, ap);
             if (kb + 2 < A.Kb) {
 #pragma unroll
                 for (int t = 0; t < 16; t++) ent[t] = tp[(kb + 2) * 64 + t];

@@ -73,3 +73,4 @@ static inline unsigned __brev(unsigned x) {
 }
 
 #define CKKSMI_LAUNCH(kern, grid, block, stream, ...) emu::launch(grid, block, [&]() { kern(__VA_ARGS__); })
+static inline unsigned __umul24(unsigned a, unsigned b) { return (a & 0xffffffu) * (b & 0xffffffu); }
