@@ -47,6 +47,7 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "automorphism_kernel": 2 * w,
         # fused kernels: the converted limb is written once (column-pass output) plus its share of the source limbs
         "conv_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),   # ModUp
+        "modup_cols_kernel<4, %d>" % alpha: w * (1 + float(level) / (beta * E - level)),      # ModUp, targets looped in the workgroup
         "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
         "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
@@ -60,13 +61,16 @@ def laneops_per_unit(name, N, level, k, alpha):
     """FP64 vector instructions per unit of work (counted from the kernel source, per word: conversions u64<->f64 2 each,
     twiddle product 6, butterfly add/sub 2, reduction 3, canonical form 7) for the kernels where the ALU can bind"""
     beta = -(-level // alpha)
-    xform_pass = 2 + 8 * 4 + 3 + 9          # load conversion, 8 stages at 4 per word, one mid reduction, canonical store
+    # one pass of a transform between the reduced-double intermediate formats: 8 stages at 4 per word (twiddle product
+    # 5 + add + sub per butterfly, lazy reductions included), one mid reduction, one reduction at the store
+    xform_pass = 8 * 4 + 3 + 3
     table = {
-        "conv_cols_kernel<4, %d, 0>" % alpha: N * (9 * alpha + 3 + xform_pass - 2),
-        "conv_cols_kernel<4, %d, 1>" % k: N * (9 * k + 3 + xform_pass - 2),
-        "conv_cols_kernel<4, 1, 1>": N * (9 + 3 + xform_pass - 2),
+        "conv_cols_kernel<4, %d, 0>" % alpha: N * (7 * alpha + (alpha - 1) + 3 + xform_pass),
+        "modup_cols_kernel<4, %d>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),   # source words converted once per 24 targets
+        "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
+        "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         "rows_inner_kernel": N * beta * (xform_pass + 2 * (2 + 6 + 1 + 3)),
-        "rows_final_kernel": N * (xform_pass + 2 + 1 + 6 + 7 + 2 + 3),
+        "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),
     }
     return table.get(name)
 
@@ -76,6 +80,7 @@ def laneops_per_unit(name, N, level, k, alpha):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
     "conv_cols_kernel<4, 3, 0>": (2.0 * 398537 + 6291456) * 1024,
+    "modup_cols_kernel<4, 3>": (2.0 * 398537 + 6291456) * 1024,
     "rows_inner_kernel": (2.0 * 3760086 + 1824768) * 1024,
     "rows_final_kernel": (2.0 * 3968672 + 3080192) * 1024 / 2,
 }

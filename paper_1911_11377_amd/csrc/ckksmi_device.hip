@@ -203,6 +203,35 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
 #undef CONV_COLS_CASE
 }
 
+// ModUp conversion + column pass with the targets looped inside the workgroup (see modup_cols_kernel)
+void launch_modup_cols(ckksmi_ctx *c, const u64 *y, u64 *dst, size_t items, int level, double units, hipStream_t st) {
+    ModupColsArgs A;
+    memset(&A, 0, sizeof(A));
+    A.y = (const u64d *)y; A.dst = (u64d *)dst; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.cc = c->d_modup_c;
+    A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T;
+    A.beta = (level + c->alpha - 1) / c->alpha;
+    A.p51 = c->p51mask;
+    const unsigned tiles = (unsigned)(c->N / 4096);
+    // enough workgroups to fill the chip several times over, otherwise as many targets per workgroup as possible
+    const size_t base = (size_t)tiles * items * A.beta;
+    int chunks = (int)((size_t)c->ntt_target_wgs / (base ? base : 1));
+    if (chunks < 1) chunks = 1;
+    if (chunks > A.E) chunks = A.E;
+    A.targets_per_wg = c->modup_targets_per_wg > 0 ? c->modup_targets_per_wg : (A.E + chunks - 1) / chunks;
+    const unsigned z = (unsigned)((A.E + A.targets_per_wg - 1) / A.targets_per_wg);
+    const dim3 grid(tiles, (unsigned)(items * A.beta), z), block(V2_THREADS);
+#define MODUP_COLS_CASE(Q, NS)                                                                               \
+    case (Q) * 8 + (NS): KL(c, CKKSMI_K_CONV_COLS_MODUP, units, (modup_cols_kernel<Q, NS>), grid, block, st, A); break;
+    switch ((c->logN - 12) * 8 + c->alpha) {
+        MODUP_COLS_CASE(1, 1) MODUP_COLS_CASE(1, 2) MODUP_COLS_CASE(1, 3) MODUP_COLS_CASE(1, 4)
+        MODUP_COLS_CASE(2, 1) MODUP_COLS_CASE(2, 2) MODUP_COLS_CASE(2, 3) MODUP_COLS_CASE(2, 4)
+        MODUP_COLS_CASE(3, 1) MODUP_COLS_CASE(3, 2) MODUP_COLS_CASE(3, 3) MODUP_COLS_CASE(3, 4)
+        MODUP_COLS_CASE(4, 1) MODUP_COLS_CASE(4, 2) MODUP_COLS_CASE(4, 3) MODUP_COLS_CASE(4, 4)
+        default: break;
+    }
+#undef MODUP_COLS_CASE
+}
+
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
                        size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st) {
     RowsFinalArgs A;
@@ -278,8 +307,11 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         // y_i = d_i * qhat_i^-1 straight out of the inverse transform; conversion rides on the column pass
         launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
                    c->d_fin_modup + (size_t)level * c->n_q);
-        launch_conv_cols(c, 0, ycoef, (size_t)level * N, dtA, (size_t)beta * E * N, beta * E, items, level, nullptr,
-                         (double)items * (beta * E - level), st);
+        if (c->modup_loop)
+            launch_modup_cols(c, ycoef, dtA, items, level, (double)items * (beta * E - level), st);
+        else
+            launch_conv_cols(c, 0, ycoef, (size_t)level * N, dtA, (size_t)beta * E * N, beta * E, items, level, nullptr,
+                             (double)items * (beta * E - level), st);
     } else {
         launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st);
         launch_modup(c, ycoef, d_eval, d_stride, dtA, items, level, st);
@@ -457,6 +489,8 @@ int dev_upload_tables(ckksmi_ctx *c) {
         for (int t = 0; t < T; t++) p24[t] = make_wmul(((u64)1 << 24) % c->mod[t], c->mod[t]);
         c->d_pow24 = upload(c, p24.data(), p24.size(), ok);
         if (const char *e = getenv("CKKSMI_MAC_MFMA")) c->mac_mfma = atoi(e) != 0;
+        if (const char *e = getenv("CKKSMI_MODUP_LOOP")) c->modup_loop = atoi(e) != 0;
+        if (const char *e = getenv("CKKSMI_MODUP_TARGETS")) c->modup_targets_per_wg = atoi(e);
     }
     for (int t = 0; t < T; t++)
         if (c->mod[t] >= ((u64)1 << 50)) c->p51mask.w[t >> 6] |= 1ull << (t & 63);
@@ -982,7 +1016,11 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
         // the conversion kernels are instantiated per (size, source limbs, mode): report the symbol that runs
         static thread_local char buf[64];
         const int q = c->logN - 12;
-        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 0>", q, c->alpha); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) {
+            if (c->modup_loop) snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d>", q, c->alpha);
+            else snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 0>", q, c->alpha);
+            return buf;
+        }
         if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 1>", q, c->k); return buf; }
         if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, 1, 1>", q); return buf; }
     }

@@ -88,6 +88,8 @@ struct ckksmi_ctx {
     // ---- device tables ----
     ModConst *d_mod = nullptr;   // [T]
     WMul *d_pow24 = nullptr;     // [T] 2^24 mod p (matrix-core MAC: recombination of the digit diagonals)
+    int modup_loop = 1;          // ModUp column pass organised by source tile (CKKSMI_MODUP_LOOP=0: one workgroup per target limb)
+    int modup_targets_per_wg = 0;  // 0: chosen from the grid size (CKKSMI_MODUP_TARGETS)
     int mac_mfma = 1;            // conv / FC MAC on the matrix cores where the shape allows (CKKSMI_MAC_MFMA=0: vector ALU only)
     WMul *d_tw_fwd = nullptr;    // [T][N]  psi^brev(x), x in [1,N)
     WMul *d_tw_inv = nullptr;    // [T][N]  psi^-brev(x); entry 0 holds N^-1

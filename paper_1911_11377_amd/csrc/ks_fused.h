@@ -145,6 +145,124 @@ __global__ __launch_bounds__(V2_THREADS, 3) void conv_cols_kernel(ConvColsArgs A
         conv_cols_body<false, NSRC, Q>(A, lds, tw2_lds, t, slot, first_src, nsrc, W, hsub);
 }
 
+// ------------------------------------------------------------------ ModUp column pass, targets looped in the workgroup
+// The same conversion + column pass as conv_cols_kernel<Q, NSRC, 0>, organised around the SOURCE tile instead of the
+// target limb: a workgroup reads the digit's source words once, keeps them in registers as doubles and produces the
+// column-pass tile of every target limb of its chunk from them.  What remains per target is arithmetic and stores
+// (which do not stall a wave), so the loads no longer alternate with the butterflies.  Per target the 255 column-pass
+// twiddles of its modulus go through LDS (one coalesced 2 KB read per workgroup, fetched one target ahead).
+struct ModupColsArgs {
+    const u64d *y;                // [items][level][N] conversion inputs y_i, coefficient form, canonical
+    u64d *dst;                    // [items][beta][E][N]
+    const ModConst *modc;
+    const double *tw;             // forward twiddles [T][N]
+    const WMul *cc;               // ModUp constants [beta_top][alpha][alpha][T]
+    int logN, level, E, n_q, alpha, beta, T;
+    int targets_per_wg;
+    P51Mask p51;
+};
+
+template <bool P51, int NSRC, int Q>
+__device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], const WMul (&Wc)[NSRC], const double *twl, double *lds, u64d *dst,
+                                                  const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store) {
+    typedef ColsGeom<Q> Geo;
+    typedef ColsMasks<Q, P51> Mk;
+    double x[16];
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        double v = 0.0;
+#pragma unroll
+        for (int a = 0; a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
+        x[e] = reduce_balanced(v, p, pinv);  // |v| <= NSRC * 0.75p
+    }
+    {
+        double tw1[15];
+#pragma unroll
+        for (int i = 0; i < 15; i++) tw1[i] = twl[1 + i];
+        fwd_round<Mk::F1>(x, tw1, p, pinv);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e++) lds[geo.l1(e)] = x[e];
+    twl_next[threadIdx.x] = tw_store;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; i++) x[i] = lds[geo.l2(i)];
+    {
+        double tw2[15];
+#pragma unroll
+        for (int s = 0; s < 4; s++)
+#pragma unroll
+            for (int b = 0; b < (1 << s); b++) {
+                if (s >= 4 - Q) {
+                    const int u = s - (4 - Q);
+                    tw2[(1 << s) - 1 + b] = twl[(16u << u) + (geo.a << u) + (b & ((1 << u) - 1))];
+                } else {
+                    tw2[(1 << s) - 1 + b] = 0.0;
+                }
+            }
+        fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) dst[geo.g2(i)] = mid_store(x[i], p, pinv);
+}
+
+// grid: x = column tile (N/4096), y = item * beta + digit, z = chunk of targets_per_wg target limbs
+template <int Q, int NSRC>
+__global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs A) {
+    // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
+    // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
+    __shared__ double lds[2][16 * V2_GS];
+    __shared__ double twl[3][256];
+    const unsigned N = 1u << A.logN;
+    const unsigned item = blockIdx.y / (unsigned)A.beta, j = blockIdx.y % (unsigned)A.beta;
+    const int lo = (int)j * A.alpha;
+    const int nsrc = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
+    const int n_targets = A.E - nsrc;  // every limb of the extended basis outside the digit
+    const int k0 = (int)blockIdx.z * A.targets_per_wg;
+    const int k1 = k0 + A.targets_per_wg < n_targets ? k0 + A.targets_per_wg : n_targets;
+    if (k0 >= k1) return;
+    const ColsGeom<Q> geo(threadIdx.x, blockIdx.x);
+    // the digit's source words, once: a missing source (digit cut short by the level) re-reads limb lo, its constants are zero
+    double yd[NSRC][16];
+    {
+        const u64d *ysrc = A.y + ((size_t)item * A.level + lo) * N;
+        u64d raw[NSRC][16];
+#pragma unroll
+        for (int a = 0; a < NSRC; a++) {
+            const u64d *ya = ysrc + (size_t)(a < nsrc ? a : 0) * N;
+#pragma unroll
+            for (int e = 0; e < 16; e++) raw[a][e] = ya[geo.g1(e)];
+        }
+#pragma unroll
+        for (int a = 0; a < NSRC; a++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) yd[a][e] = u2d(raw[a][e]);
+    }
+    const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
+    // extended-basis index of target k (the digit's own limbs are skipped), and its modulus index
+    auto ext_of = [&](int k) { return k < lo ? k : k + nsrc; };
+    auto mod_of = [&](int x) { return x < A.level ? x : A.n_q + x - A.level; };
+    twl[0][threadIdx.x] = A.tw[(size_t)mod_of(ext_of(k0)) * N + threadIdx.x];
+    double tw_next = k0 + 1 < k1 ? A.tw[(size_t)mod_of(ext_of(k0 + 1)) * N + threadIdx.x] : 0.0;
+    __syncthreads();
+    for (int k = k0; k < k1; k++) {
+        const int x = ext_of(k), t = mod_of(x);
+        const double *tcur = twl[(k - k0) % 3];
+        double *tnext = twl[(k - k0 + 1) % 3];
+        const double tw_store = tw_next;  // twiddle of target k+1, written before this target's barrier
+        if (k + 2 < k1) tw_next = A.tw[(size_t)mod_of(ext_of(k + 2)) * N + threadIdx.x];
+        const double p = A.modc[t].p, pinv = A.modc[t].pinv;
+        WMul Wc[NSRC];
+#pragma unroll
+        for (int a = 0; a < NSRC; a++) Wc[a] = a < nsrc ? A.cc[(crow + a) * A.T + t] : WMul{0.0, 0.0};
+        u64d *dst = A.dst + (((size_t)item * A.beta + j) * A.E + x) * N;
+        if (is_p51(A.p51, t))
+            modup_cols_target<true, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store);
+        else
+            modup_cols_target<false, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store);
+    }
+}
+
 // ------------------------------------------------------------------ row pass helper
 // round-2 twiddles of a thread (registers) and the round-1 twiddles of the tile's 16 rows (LDS, [16][16])
 __device__ __forceinline__ void load_row_twiddles(const double *tw, unsigned N1, unsigned tile, unsigned hi4, unsigned lo4, double *tw1_lds,
@@ -252,44 +370,59 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
             a1[i] = reduce_balanced(mulmod(v, u2d(kr1[i]), p, pinv), p, pinv);
         }
     }
-    for (int j = 0; j < A.beta; j++) {
-        if (j == j_own) continue;
+    // The other digits, software-pipelined so that no memory latency sits in front of arithmetic: the limb words of a
+    // digit are requested while the previous digit is multiplied, its key words while the limb goes through the row
+    // pass.  xr holds the column-pass output of the converted limb in the register layout of the row pass.
+    int j = (j_own == 0) ? 1 : 0;
+    u64d xr[16];
+    if (j < A.beta) {
+        const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
+#pragma unroll
+        for (int i = 0; i < 16; i++) xr[i] = src[hi4 * 256 + lo4 + 16 * i];
+    }
+    while (j < A.beta) {
         const u64d *k0 = key + (((size_t)j * 2 + 0) * A.T + t) * N + tile0;
         const u64d *k1 = key + (((size_t)j * 2 + 1) * A.T + t) * N + tile0;
-        // every operand of this digit is requested up front: the key words (position layout i*256+tid) and the
-        // column-pass output of the converted limb in the register layout of the row pass
-        const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
-        u64d kr0[16], kr1[16], xr[16];
+        u64d kr0[16], kr1[16];
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            xr[i] = src[hi4 * 256 + lo4 + 16 * i];
             kr0[i] = k0[i * 256 + tid];
             kr1[i] = k1[i * 256 + tid];
         }
         SCHED_FENCE();
-        double xx[16];
-#pragma unroll
-        for (int e = 0; e < 16; e++) xx[e] = mid_load(xr[e]);
         {
-            double tw1[15];
+            double xx[16];
 #pragma unroll
-            for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
-            fwd_round<F1>(xx, tw1, p, pinv);
+            for (int e = 0; e < 16; e++) xx[e] = mid_load(xr[e]);
+            {
+                double tw1[15];
+#pragma unroll
+                for (int i = 0; i < 15; i++) tw1[i] = tw1_lds[hi4 * 16 + i];
+                fwd_round<F1>(xx, tw1, p, pinv);
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = xx[e];
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
+            {
+                double tw2[15];
+#pragma unroll
+                for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[i * 256 + tid];
+                fwd_round<F2>(xx, tw2, p, pinv);
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = reduce_balanced(xx[e], p, pinv);
         }
-#pragma unroll
-        for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = xx[e];
         __syncthreads();
+        int jn = j + 1;
+        if (jn == j_own) jn++;
+        if (jn < A.beta) {
+            const u64d *src = A.dtA + (((size_t)item * A.beta + jn) * A.E + x) * N + tile0;
 #pragma unroll
-        for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
-        {
-            double tw2[15];
-#pragma unroll
-            for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[i * 256 + tid];
-            fwd_round<F2>(xx, tw2, p, pinv);
+            for (int i = 0; i < 16; i++) xr[i] = src[hi4 * 256 + lo4 + 16 * i];
         }
-#pragma unroll
-        for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = reduce_balanced(xx[e], p, pinv);
-        __syncthreads();
+        SCHED_FENCE();
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             const double v = lds[i * V2_GS + hi4 * 17 + lo4];
@@ -297,6 +430,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
             a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(kr1[i]), p, pinv), p, pinv);
         }
         __syncthreads();
+        j = jn;
     }
     u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
