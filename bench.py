@@ -52,6 +52,7 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
         "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
         "rows_final_kernel": 4 * w,                                  # column-pass output, x, addend in; out
+        "rows_final2_kernel": 5 * w,                                 # two column-pass outputs, x, addend in; out
         "elementwise kernels": 3 * w,
     }
     return table.get(name)
@@ -71,6 +72,7 @@ def laneops_per_unit(name, N, level, k, alpha):
         "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         "rows_inner_kernel": N * beta * (xform_pass + 2 * (2 + 6 + 1 + 3)),
         "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),
+        "rows_final2_kernel": N * (2 * xform_pass + 2 + 1 + 5 + 3 + 1 + 5 + 7 + 2),
     }
     return table.get(name)
 

@@ -232,17 +232,38 @@ void launch_modup_cols(ckksmi_ctx *c, const u64 *y, u64 *dst, size_t items, int 
 #undef MODUP_COLS_CASE
 }
 
+// limb_count < 0: every limb, out laid out [rows][nc][N]; otherwise only limbs limb0 .. limb0+limb_count-1, written to
+// out + row*out_row_stride + (limb - limb0)*N
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
-                       size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st) {
+                       size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st, int limb0 = 0,
+                       int limb_count = -1, size_t out_row_stride = 0) {
     RowsFinalArgs A;
+    const int nz = limb_count < 0 ? nc : limb_count;
+    A.limb0 = limb_count < 0 ? 0 : limb0;
+    A.out_limb0 = A.limb0;
+    A.out_row_stride = limb_count < 0 ? (size_t)nc * c->N : out_row_stride;
     A.tmpA = (const u64d *)tmpA; A.x = (const u64d *)x; A.x_row_stride = x_row_stride;
     A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride; A.add_both = add_both;
     A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.Binv = Binv; A.logN = c->logN; A.nc = nc;
     A.rows = rows;
     A.p51 = c->p51mask;
     const unsigned tiles = (unsigned)(c->N / 4096);
-    const unsigned xch = zchunks_for(c, tiles * nc, rows, A.rows_per_x);
-    KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nc, rows_final_kernel, dim3(xch, tiles, nc), dim3(V2_THREADS), st, A);
+    const unsigned xch = zchunks_for(c, tiles * nz, rows, A.rows_per_x);
+    KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A);
+}
+
+void launch_rows_final2(ckksmi_ctx *c, const u64 *tmpA, const u64 *tmpB, const u64 *x, size_t x_row_stride, const u64 *addend,
+                        size_t add_item_stride, size_t add_comp_stride, u64 *out, const WMul *BinvA, const WMul *BinvB, int ncA, int rows,
+                        hipStream_t st) {
+    RowsFinal2Args A;
+    A.tmpA = (const u64d *)tmpA; A.tmpB = (const u64d *)tmpB; A.x = (const u64d *)x; A.x_row_stride = x_row_stride;
+    A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride;
+    A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.BinvA = BinvA; A.BinvB = BinvB;
+    A.logN = c->logN; A.ncA = ncA; A.ncB = ncA - 1; A.rows = rows;
+    A.p51 = c->p51mask;
+    const unsigned tiles = (unsigned)(c->N / 4096);
+    const unsigned xch = zchunks_for(c, tiles * A.ncB, rows, A.rows_per_x);
+    KL(c, CKKSMI_K_ROWS_FINAL2, (double)rows * A.ncB, rows_final2_kernel, dim3(xch, tiles, A.ncB), dim3(V2_THREADS), st, A);
 }
 
 // fusion switches (ckksmi_ctx::fuse): which limb-wise steps ride on a transform pass
@@ -289,8 +310,11 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
     }
 }
 
+// tail_scratch != nullptr: the key switch is followed by a rescale of (result + addend) and `out` receives the rescaled
+// ciphertexts [items][2][level-1][N]; tail_scratch holds 2*level*N words per item.  Needs both DivRound fusions.
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
-                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st) {
+                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
+                   u64 *tail_scratch = nullptr) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     u64 *ycoef = ws;
@@ -342,6 +366,25 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     }
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
+    if (tail_scratch) {
+        // ModDown and rescale share their last pass.  The rescale conversion needs the ModDown result of the dropped
+        // limb only, so that limb is finished first; every other limb then goes through both final steps at once.
+        const int rows = items * 2;
+        u64 *specials = acc + (size_t)level * N;
+        u64 *r_last = tail_scratch;                       // [rows][N]
+        u64 *tmpB = tail_scratch + (size_t)rows * N;      // [rows][level-1][N]
+        u64 *last_coef = ycoef;                           // [rows][N] (the conversion inputs of ModUp are no longer needed)
+        const DivRoundDev &DA = c->divround[0], &DB = c->divround[1 + (level - 1)];
+        int lidx[1] = {level - 1};
+        launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown);
+        launch_conv_cols(c, 1, specials, (size_t)E * N, tmp, (size_t)level * N, level, rows, 0, &DA, (double)rows * level, st);
+        launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, add_both, r_last, DA.Binv, level, rows, st,
+                          level - 1, 1, N);
+        launch_ntt(c, false, r_last, last_coef, table_map(lidx, 1, N, N), rows, st, c->d_fin_rescale + (level - 1));
+        launch_conv_cols(c, 1, last_coef, N, tmpB, (size_t)(level - 1) * N, level - 1, rows, 0, &DB, (double)rows * (level - 1), st);
+        launch_rows_final2(c, tmp, tmpB, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, out, DA.Binv, DB.Binv, level, rows, st);
+        return;
+    }
     divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
                   acc, (size_t)E * N, tmp, level, items * 2, addend, add_item_stride, add_comp_stride, add_both, out, st);
 }
@@ -490,6 +533,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
         c->d_pow24 = upload(c, p24.data(), p24.size(), ok);
         if (const char *e = getenv("CKKSMI_MAC_MFMA")) c->mac_mfma = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_LOOP")) c->modup_loop = atoi(e) != 0;
+        if (const char *e = getenv("CKKSMI_FUSE_TAIL")) c->fuse_tail = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_TARGETS")) c->modup_targets_per_wg = atoi(e);
     }
     for (int t = 0; t < T; t++)
@@ -802,6 +846,12 @@ extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const
         u64 *r = d + (size_t)items * 3 * level * N;      // [items][2][level][N]
         u64 *rest = r + (size_t)items * 2 * level * N;
         launch_tensor(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, level, items, S(stream));
+        if (c->fused && c->fuse_tail && (c->fuse & (FUSE_DIVCONV | FUSE_FINAL)) == (FUSE_DIVCONV | FUSE_FINAL)) {
+            // ModDown + add + rescale with a shared last pass: r is only scratch
+            ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
+                          out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), r);
+            continue;
+        }
         ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r, rest,
                 S(stream));
         rescale_core(c, r, out + (size_t)b0 * 2 * (level - 1) * N, items, level, rest, S(stream));
@@ -1007,7 +1057,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
-                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel"};
+                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && c->logN >= 13 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",

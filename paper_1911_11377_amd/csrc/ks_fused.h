@@ -365,15 +365,16 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         SCHED_FENCE();
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            const double v = u2d(xr[i]);
-            a0[i] = reduce_balanced(mulmod(v, u2d(kr0[i]), p, pinv), p, pinv);
-            a1[i] = reduce_balanced(mulmod(v, u2d(kr1[i]), p, pinv), p, pinv);
+            const double v = reduce_balanced(u2d(xr[i]), p, pinv), vp = v * pinv;
+            a0[i] = mulmod_w(u2d(kr0[i]), v, vp, p);
+            a1[i] = mulmod_w(u2d(kr1[i]), v, vp, p);
         }
     }
     // The other digits, software-pipelined so that no memory latency sits in front of arithmetic: the limb words of a
     // digit are requested while the previous digit is multiplied, its key words while the limb goes through the row
     // pass.  xr holds the column-pass output of the converted limb in the register layout of the row pass.
     int j = (j_own == 0) ? 1 : 0;
+    int pending = 1;  // terms in the accumulators since their last reduction (the own digit's term counts)
     u64d xr[16];
     if (j < A.beta) {
         const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
@@ -425,9 +426,19 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         SCHED_FENCE();
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            const double v = lds[i * V2_GS + hi4 * 17 + lo4];
-            a0[i] = reduce_balanced(a0[i] + mulmod(v, u2d(kr0[i]), p, pinv), p, pinv);
-            a1[i] = reduce_balanced(a1[i] + mulmod(v, u2d(kr1[i]), p, pinv), p, pinv);
+            // the transformed word is the prepared factor (|v| <= p/2 + 1, v/p computed once for both components), the
+            // key word the other one: each term is below 0.875p and the sum is reduced only when it could pass 2^53
+            const double v = lds[i * V2_GS + hi4 * 17 + lo4], vp = v * pinv;
+            a0[i] += mulmod_w(u2d(kr0[i]), v, vp, p);
+            a1[i] += mulmod_w(u2d(kr1[i]), v, vp, p);
+        }
+        if (++pending == (P51 ? 4 : 8)) {  // p < 2^51: 0.5p + 4 * 0.875p = 4p < 2^53; p < 2^50: 0.5p + 8 * 0.875p < 8p <= 2^53
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                a0[i] = reduce_balanced(a0[i], p, pinv);
+                a1[i] = reduce_balanced(a1[i], p, pinv);
+            }
+            pending = 0;
         }
         __syncthreads();
         j = jn;
@@ -436,8 +447,8 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
 #pragma unroll
     for (int i = 0; i < 16; i++) {
-        o0[i * 256 + tid] = d2u(canon_small(a0[i], p));
-        o1[i * 256 + tid] = d2u(canon_small(a1[i], p));
+        o0[i * 256 + tid] = d2u(canon(a0[i], p, pinv));
+        o1[i * 256 + tid] = d2u(canon(a1[i], p, pinv));
     }
 }
 
@@ -462,11 +473,14 @@ struct RowsFinalArgs {
     const u64d *addend;  // optional: row r limb i at addend + (r/2)*add_item_stride + (r%2)*add_comp_stride + i*N
     unsigned long long add_item_stride, add_comp_stride;
     int add_both;
-    u64d *out;           // [rows][nc][N]
+    u64d *out;           // row r, limb i at out + r*out_row_stride + (i - out_limb0)*N
+    unsigned long long out_row_stride;
+    int out_limb0;
     const ModConst *modc;
     const double *tw;
     const WMul *Binv;    // [T]
     int logN, nc;
+    int limb0;             // first limb handled (grid z counts from it)
     int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
     P51Mask p51;
 };
@@ -485,7 +499,7 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
     const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
     for (unsigned row = r0; row < r1; row++) {
         const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
-        u64d *out = A.out + ((size_t)row * A.nc + i) * N + tile0;
+        u64d *out = A.out + (size_t)row * A.out_row_stride + (size_t)(i - A.out_limb0) * N + tile0;
         const bool add = A.addend && (A.add_both || (row & 1u) == 0);
         const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
         // operands of the last step are requested before the transform so that their latency overlaps it
@@ -512,9 +526,80 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
 __global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A) {
     __shared__ double lds[16 * V2_GS];
     __shared__ double tw1_lds[16 * 16];
-    const int i = (int)blockIdx.z;
+    const int i = A.limb0 + (int)blockIdx.z;
     if (is_p51(A.p51, i))
         rows_final_body<true>(A, lds, tw1_lds, i);
     else
         rows_final_body<false>(A, lds, tw1_lds, i);
+}
+
+// ------------------------------------------------------------------ two DivRound final steps in one pass
+// ModDown followed by rescale, for the limbs that survive both: with rA, rB the row-pass results of the two conversions
+//     r_i   = (x_i - rA_i) * P^-1 + addend_i            (ModDown, then the add of the product's first two components)
+//     out_i = (r_i - rB_i) * q_last^-1                  (rescale)
+// r_i never leaves the registers.  rB comes from the ModDown result of the dropped limb q_last alone, which the caller
+// computes first with rows_final_kernel restricted to that limb.
+struct RowsFinal2Args {
+    const u64d *tmpA;    // [rows][ncA][N] column-pass output of the ModDown conversion
+    const u64d *tmpB;    // [rows][ncB][N] column-pass output of the rescale conversion, ncB = ncA - 1
+    const u64d *x;       // accumulators, evaluation form: row r, limb i at x + r*x_row_stride + i*N
+    unsigned long long x_row_stride;
+    const u64d *addend;  // row r limb i at addend + (r/2)*add_item_stride + (r%2)*add_comp_stride + i*N
+    unsigned long long add_item_stride, add_comp_stride;
+    u64d *out;           // [rows][ncB][N]
+    const ModConst *modc;
+    const double *tw;
+    const WMul *BinvA, *BinvB;  // [T]
+    int logN, ncA, ncB;
+    int rows, rows_per_x;
+    P51Mask p51;
+};
+
+template <bool P51>
+__device__ __forceinline__ void rows_final2_body(const RowsFinal2Args &A, double *lds, double *tw1_lds, int i) {
+    const unsigned N = 1u << A.logN, N1 = N >> 8;
+    const double p = A.modc[i].p, pinv = A.modc[i].pinv;
+    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
+    const unsigned tile = blockIdx.y;
+    double tw2[15];
+    load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
+    const size_t tile0 = (size_t)tile * 4096;
+    const WMul WA = A.BinvA[i], WB = A.BinvB[i];
+    const unsigned r0 = blockIdx.x * (unsigned)A.rows_per_x;
+    const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
+    for (unsigned row = r0; row < r1; row++) {
+        const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
+        const u64d *ad = A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0;
+        u64d *out = A.out + ((size_t)row * A.ncB + i) * N + tile0;
+        u64d xr[16], ar[16];
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            xr[q] = xin[q * 256 + tid];
+            ar[q] = ad[q * 256 + tid];
+        }
+        SCHED_FENCE();
+        rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.ncA + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+        double r[16];  // |r| < 2.5p
+#pragma unroll
+        for (int q = 0; q < 16; q++) r[q] = mulmod_w(u2d(xr[q]) - lds[q * V2_GS + hi4 * 17 + lo4], WA.w, WA.wp, p) + u2d(ar[q]);
+        __syncthreads();
+        rows_fwd_to_lds<P51>(A.tmpB + ((size_t)row * A.ncB + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            const double v = mulmod_w(r[q] - lds[q * V2_GS + hi4 * 17 + lo4], WB.w, WB.wp, p);  // |r - rB| < 3.1p < 2^53
+            out[q * 256 + tid] = d2u(canon(v, p, pinv));
+        }
+        __syncthreads();
+    }
+}
+
+// grid: x = chunk of rows (item, component), y = row tile (N/4096), z = limb (0 .. ncB-1)
+__global__ __launch_bounds__(V2_THREADS) void rows_final2_kernel(RowsFinal2Args A) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ double tw1_lds[16 * 16];
+    const int i = (int)blockIdx.z;
+    if (is_p51(A.p51, i))
+        rows_final2_body<true>(A, lds, tw1_lds, i);
+    else
+        rows_final2_body<false>(A, lds, tw1_lds, i);
 }

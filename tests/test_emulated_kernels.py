@@ -95,6 +95,14 @@ def test_emulated_partial_fusion(be, monkeypatch, fuse):
     pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=115, batch=1, levels=[4 if fuse % 2 else 3])
 
 
+@pytest.mark.parametrize("env", [{"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_MODUP_TARGETS": "3"}])
+def test_emulated_alternative_key_switch_paths(be, monkeypatch, env):
+    """one workgroup per target limb in ModUp, separate ModDown / rescale passes, several target chunks per source tile"""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=119, batch=1, levels=[4])
+
+
 @pytest.mark.parametrize("logN", [13, 14, 15])
 def test_emulated_fused_path_other_sizes(be, monkeypatch, logN):
     """2^13 <= N < 2^16: general column geometry (N1 = 32, 64, 128), fused and unfused, 50- and 51-bit primes"""
