@@ -81,10 +81,9 @@ def laneops_per_unit(name, N, level, k, alpha):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
-    "conv_cols_kernel<4, 3, 0>": (2.0 * 398537 + 6291456) * 1024,
-    "modup_cols_kernel<4, 3>": (2.0 * 398537 + 6291456) * 1024,
-    "rows_inner_kernel": (2.0 * 3760086 + 1824768) * 1024,
-    "rows_final_kernel": (2.0 * 3968672 + 3080192) * 1024 / 2,
+    "modup_cols_kernel<4, 3>": (2.0 * 644299 + 6406144) * 1024,
+    "rows_inner_kernel": (2.0 * 4045063 + 2313216) * 1024,
+    "rows_final2_kernel": (2.0 * 3065768 + 1507328) * 1024,
 }
 
 
