@@ -29,6 +29,11 @@
 #include "device_arith.h"
 
 #define V2_THREADS 256
+#ifdef CKKSMI_EMULATE
+#define NTT_SCHED_FENCE() ((void)0)
+#else
+#define NTT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
 #define V2_GS 272  // doubles per padded 16x17 group in LDS (row pass)
 
 struct NttV2Args {
@@ -252,8 +257,15 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
 #pragma unroll
             for (int i = 0; i < 16; i++) dst[tile0 + i * 256 + tid] = d2u(lds[i * V2_GS + hi4 * 17 + lo4]);
         } else {
+            {
+                // all 16 words requested before the first is used: one memory latency per item, not sixteen
+                u64d raw[16];
 #pragma unroll
-            for (int i = 0; i < 16; i++) lds[i * V2_GS + hi4 * 17 + lo4] = u2d(src[tile0 + i * 256 + tid]);
+                for (int i = 0; i < 16; i++) raw[i] = src[tile0 + i * 256 + tid];
+                NTT_SCHED_FENCE();
+#pragma unroll
+                for (int i = 0; i < 16; i++) lds[i * V2_GS + hi4 * 17 + lo4] = u2d(raw[i]);
+            }
             __syncthreads();
 #pragma unroll
             for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
