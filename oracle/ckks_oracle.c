@@ -696,21 +696,26 @@ void orc_fc_mac(const orc_params *P, const u64 *in, const i64 *w, int F, int O, 
 }
 
 /*
- * k x k pooling of per-pixel ciphertexts (the average-pooling rows of the
- * paper's Table 1) as a plain sum of ciphertexts: out[c,y,x] = sum_{u,v<k}
- * in[c, k*y+u, k*x+v]; the 1/k^2 of the average is a plaintext constant that the
- * caller folds into the next layer's weights.  in: [C][H][W] ciphertexts,
- * out: [C][H/k][W/k] (rows/columns beyond k*(H/k) are ignored).
+ * k x k pooling of per-pixel ciphertexts (the zero-padding and average-pooling
+ * rows of the paper's Table 1) as a plain sum of ciphertexts over windows of
+ * the image padded with `pad` rows / columns of zeros on every side:
+ * out[c,y,x] = sum_{u,v<k} in[c, k*y+u-pad, k*x+v-pad], positions outside the
+ * image contribute nothing; the 1/k^2 of the average is a plaintext constant
+ * that the caller folds into the next layer's weights.  in: [C][H][W]
+ * ciphertexts, out: [C][(H+2*pad)/k][(W+2*pad)/k] (rows/columns beyond the last
+ * full window are ignored).
  */
-void orc_sum_pool2d(const orc_params *P, const u64 *in, int C, int H, int W, int k, int level, u64 *out) {
+void orc_sum_pool2d(const orc_params *P, const u64 *in, int C, int H, int W, int k, int pad, int level, u64 *out) {
     u64 N = P->N;
     size_t ctw = (size_t)2 * level * N;
-    int Ho = H / k, Wo = W / k;
+    int Ho = (H + 2 * pad) / k, Wo = (W + 2 * pad) / k;
     for (int c = 0; c < C; c++) for (int y = 0; y < Ho; y++) for (int x = 0; x < Wo; x++) {
         u64 *dst = out + (((size_t)c * Ho + y) * Wo + x) * ctw;
         memset(dst, 0, ctw * 8);
         for (int u = 0; u < k; u++) for (int v = 0; v < k; v++) {
-            const u64 *src = in + (((size_t)c * H + (k * y + u)) * W + (k * x + v)) * ctw;
+            int iy = k * y + u - pad, ix = k * x + v - pad;
+            if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+            const u64 *src = in + (((size_t)c * H + iy) * W + ix) * ctw;
             for (int comp = 0; comp < 2; comp++) for (int i = 0; i < level; i++) {
                 u64 q = P->mod[i];
                 size_t off = ((size_t)comp * level + i) * N;

@@ -223,7 +223,7 @@ class Oracle:
             "orc_add_const": [V, u64p, C.c_int64, I, u64p],
             "orc_conv2d_mac": [V, u64p, i64p] + [I] * 8 + [I, u64p],
             "orc_fc_mac": [V, u64p, i64p, I, I, I, u64p],
-            "orc_sum_pool2d": [V, u64p, I, I, I, I, I, u64p],
+            "orc_sum_pool2d": [V, u64p, I, I, I, I, I, I, u64p],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -436,13 +436,13 @@ class Oracle:
         self._L.orc_fc_mac(self._h, _p64(x), _pi64(w), F, O, level, _p64(out))
         return out
 
-    def sum_pool2d(self, x, k, level):
-        """k x k pooling as a sum of ciphertexts (Table 1's average pooling without its 1/k^2)."""
+    def sum_pool2d(self, x, k, level, pad=0):
+        """k x k pooling as a sum of ciphertexts (Table 1's zero padding + average pooling without the 1/k^2)."""
         x = _u64(x)
         Cc, H, W = x.shape[:3]
         assert x.shape[3:] == (2, level, self.N)
-        out = np.empty((Cc, H // k, W // k, 2, level, self.N), dtype=np.uint64)
-        self._L.orc_sum_pool2d(self._h, _p64(x), Cc, H, W, k, level, _p64(out))
+        out = np.empty((Cc, (H + 2 * pad) // k, (W + 2 * pad) // k, 2, level, self.N), dtype=np.uint64)
+        self._L.orc_sum_pool2d(self._h, _p64(x), Cc, H, W, k, pad, level, _p64(out))
         return out
 
     def _map(self, fn, n, workers):
@@ -478,6 +478,17 @@ class Oracle:
         self._map(one, flat.shape[0], workers)
         return out.reshape(lead + (2, level - 1, self.N))
 
+    def poly2_each(self, cts, rlk, level, k2, k1, workers=1):
+        cts = _u64(cts)
+        lead = cts.shape[:-3]
+        flat = cts.reshape((-1, 2, level, self.N))
+        out = np.empty((flat.shape[0], 2, level - 2, self.N), dtype=np.uint64)
+
+        def one(b):
+            out[b] = self.poly2(flat[b], rlk, level, k2, k1)
+        self._map(one, flat.shape[0], workers)
+        return out.reshape(lead + (2, level - 2, self.N))
+
     def conv2d_mac_each(self, x, w, stride, pad, level, workers=1):
         """conv2d_mac, one output channel per call"""
         w = _i64(w)
@@ -495,7 +506,8 @@ class Oracle:
         x: [C][H][W][2][level][N].  layers: a list of
           ("conv", w_int [O][C][kh][kw], stride, pad)  convolution MAC, then rescale of every output   level -> level-1
           ("square",)                                  activation x^2 with relinearisation and rescale  level -> level-1
-          ("pool", k)                                  k x k sum pooling                                level unchanged
+          ("pool", k[, pad])                           k x k sum pooling of the zero-padded image       level unchanged
+          ("poly2", k2, k1)                            activation c2*x^2 + c1*x (integer constants)     level -> level-2
           ("fc", w_int [O][F])                         flatten [C][H][W] in that order, MAC, rescale    level -> level-1
         Integer weights are prepared by the caller (round(w * dropped modulus)).  Returns (cts, level).
         workers > 1 only spreads independent ciphertexts over threads.
@@ -511,7 +523,10 @@ class Oracle:
                 x = self.square_each(x, rlk, level, workers)
                 level -= 1
             elif kind == "pool":
-                x = self.sum_pool2d(x, layer[1], level)
+                x = self.sum_pool2d(x, layer[1], level, layer[2] if len(layer) > 2 else 0)
+            elif kind == "poly2":
+                x = self.poly2_each(x, rlk, level, layer[1], layer[2], workers)
+                level -= 2
             elif kind == "fc":
                 flat = x.reshape((-1, 2, level, self.N))
                 x = self.rescale_each(self.fc_mac(flat, layer[1], level), level, workers)
@@ -525,6 +540,20 @@ class Oracle:
     def square(self, x, rlk, level):
         """x^2 with relinearisation and rescale: level -> level-1."""
         return self.hmul_relin_rescale(x, x, rlk, level)
+
+    def poly2(self, x, rlk, level, k2, k1):
+        """c2*x^2 + c1*x (the degree-2 polynomial that replaces ReLU in section 3.1) on a ciphertext x at `level`
+        with scale s, ending at level-2 with scale s2 = s^2/q_{level-1}.  The caller prepares the integer constants so
+        that both addends carry that scale:
+          x2  = RS(Relin(x*x))                    level-1, scale s2
+          t2  = RS(x2 * k2)                       level-2   (k2 ~ c2 * q_{level-2})
+          t1  = RS(drop(x -> level-1) * k1)       level-2   (k1 ~ c1 * (s2/s) * q_{level-2})
+          out = t2 + t1
+        """
+        x2 = self.hmul_relin_rescale(x, x, rlk, level)
+        t2 = self.rescale(self.mul_scalar(x2, k2, level - 1), level - 1)
+        t1 = self.rescale(self.mul_scalar(self.mod_drop(x, level, level - 1), k1, level - 1), level - 1)
+        return self.add(t2, t1, level - 2)
 
     def poly3(self, y, rlk, level, c_m002, c_025, c_05):
         """0.5 + 0.25*y - 0.02*y^3 on a ciphertext y at `level`, ending at level-2.

@@ -107,7 +107,7 @@ def rotation_offsets(n_slots, count, seed):
 # ---------------------------------------------------------------------------
 # Network shapes (layer lists only: no arithmetic of the method lives here)
 # ---------------------------------------------------------------------------
-# ("conv", out_channels, kernel, stride, pad) | ("square",) | ("pool", k) | ("fc", out_features)
+# ("conv", out_channels, kernel, stride, pad) | ("square",) | ("poly2",) | ("pool", k[, pad]) | ("fc", out_features)
 CNN_TOPOLOGIES = {
     # the AlexNet-like network of the 2^16 workload: 3x64x64 -> 32x30x30 -> 64x14x14 -> 64x14x14 -> pool 64x7x7 -> 256 -> 2
     "cnn_2e16": {"input": (3, 64, 64),
@@ -117,6 +117,18 @@ CNN_TOPOLOGIES = {
     "cnn_reduced": {"input": (3, 16, 16),
                     "layers": [("conv", 6, 5, 2, 0), ("square",), ("conv", 8, 3, 2, 0), ("square",), ("conv", 8, 3, 1, 1),
                                ("pool", 2), ("fc", 16), ("square",), ("fc", 2)]},
+    # the layer list of the paper's Table 1 on 3x32x32 inputs: zero-padding rows merged into the layer that follows
+    # them, the degree-2 polynomial of section 3.1 after every conv / fc layer but the last (whose sigmoid is applied
+    # after decryption): 32 -> 22 -> 11 -> 7 -> 3 -> 3 -> 1 -> 1 -> 1 -> 4096 -> 4096 -> 1
+    "table1": {"input": (3, 32, 32),
+               "layers": [("conv", 96, 11, 1, 0), ("poly2",), ("pool", 2), ("conv", 256, 5, 1, 0), ("poly2",), ("pool", 2),
+                          ("conv", 384, 3, 1, 1), ("poly2",), ("pool", 2), ("conv", 384, 3, 1, 1), ("poly2",), ("pool", 2, 1),
+                          ("fc", 4096), ("poly2",), ("fc", 4096), ("poly2",), ("fc", 1)]},
+    # the same sequence at reduced width and input size (first kernel 5x5): 16 -> 12 -> 6 -> 4 -> 2 -> 2 -> 1 -> 1 -> 1
+    "table1_reduced": {"input": (3, 16, 16),
+                       "layers": [("conv", 2, 5, 1, 0), ("poly2",), ("pool", 2), ("conv", 9, 3, 1, 0), ("poly2",), ("pool", 2),
+                                  ("conv", 4, 3, 1, 1), ("poly2",), ("pool", 2), ("conv", 4, 3, 1, 1), ("poly2",), ("pool", 2, 1),
+                                  ("fc", 6), ("poly2",), ("fc", 6), ("poly2",), ("fc", 1)]},
     "cnn_tiny": {"input": (3, 16, 16),
                  "layers": [("conv", 4, 5, 2, 0), ("square",), ("conv", 4, 3, 2, 0), ("square",), ("conv", 4, 3, 1, 1),
                             ("pool", 2), ("fc", 6), ("square",), ("fc", 2)]},
@@ -134,7 +146,8 @@ def cnn_shapes(name):
             _, o, k, s, p = layer
             nxt = (o, (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1)
         elif kind == "pool":
-            nxt = (c, h // layer[1], w // layer[1])
+            pad = layer[2] if len(layer) > 2 else 0
+            nxt = (c, (h + 2 * pad) // layer[1], (w + 2 * pad) // layer[1])
         elif kind == "fc":
             nxt = (layer[1], 1, 1)
         else:

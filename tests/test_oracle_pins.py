@@ -586,8 +586,12 @@ def _float_network(imgs, layers_f):
             x = _conv_reference(x, layer[1], layer[2], layer[3])
         elif layer[0] == "square":
             x = x * x
+        elif layer[0] == "poly2":
+            x = layer[1] * x * x + layer[2] * x
         elif layer[0] == "pool":
             k = layer[1]
+            pad = layer[2] if len(layer) > 2 else 0
+            x = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))  # zero padding rows of Table 1
             Cc, H, W = x.shape[:3]
             x = x[:, : H // k * k, : W // k * k].reshape(Cc, H // k, k, W // k, k, -1).mean(axis=(2, 4))
         elif layer[0] == "fc":
@@ -640,4 +644,99 @@ def test_network_decrypts_to_float_network():
     for o in range(2):
         got = M.decrypt(out[o, 0, 0], s, out_level).real
         assert np.max(np.abs(got - want[o, 0, 0])) < 1e-6 * max(1.0, np.max(np.abs(want)))
+
+
+def test_padded_sum_pool_counts_only_the_image():
+    M = Material(4, 2, 30, 1, 31, 1, seed=27)
+    O = M.O
+    level = 2
+    Q = math.prod(O.q[:level])
+    x = wl.uniform_limbs(O.q[:level], O.N, 27, "x", lead=(1, 3, 3, 2))
+    out = O.sum_pool2d(x, 2, level, pad=1)  # padded 5x5 -> 2x2 windows starting at -1
+    assert out.shape[:3] == (1, 2, 2)
+    mx = [[M.decrypt_poly(x[0, y, xx], level) for xx in range(3)] for y in range(3)]
+    for y in range(2):
+        for xx in range(2):
+            want = [0] * O.N
+            for u in range(2):
+                for v in range(2):
+                    iy, ix = 2 * y + u - 1, 2 * xx + v - 1
+                    if 0 <= iy < 3 and 0 <= ix < 3:
+                        want = [a + b for a, b in zip(want, mx[iy][ix])]
+            got = M.decrypt_poly(out[0, y, xx], level)
+            assert all((g - w) % Q == 0 for g, w in zip(got, want))
+    # a 1x1 map padded by one and pooled 2x2 is the map itself (its one window holds three zeros)
+    one = O.sum_pool2d(x[:, :1, :1], 2, level, pad=1)
+    assert one.shape[:3] == (1, 1, 1) and np.array_equal(one[0, 0, 0], x[0, 0, 0])
+
+
+def test_table1_topology_matches_the_paper():
+    """the layer list used for the paper's network against Table 1 (rows with parameters, tests/golden)"""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "table1_layers.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    want = []
+    pad = 0
+    for _, kind, n, k, stride in rows:
+        if kind == "zeropad":
+            pad = int(k)
+        elif kind == "conv":
+            want.append(("conv", int(n), int(k), int(stride), pad)); pad = 0
+        elif kind == "avgpool":
+            want.append(("pool", int(k)) if pad == 0 else ("pool", int(k), pad)); pad = 0
+        elif kind == "fc":
+            want.append(("fc", int(n)))
+    got = [l for l in wl.CNN_TOPOLOGIES["table1"]["layers"] if l[0] != "poly2"]
+    assert got == want
+    # an activation after every conv / fc layer except the last one (section 3.1)
+    layers = wl.CNN_TOPOLOGIES["table1"]["layers"]
+    for i, l in enumerate(layers[:-1]):
+        if l[0] in ("conv", "fc"):
+            assert layers[i + 1] == ("poly2",)
+    assert layers[-1] == ("fc", 1)
+    assert wl.cnn_shapes("table1")[-1][2] == (1, 1, 1) and wl.cnn_shapes("table1")[12][1] == (384, 1, 1)
+
+
+def test_table1_like_network_with_degree2_activation_decrypts_to_float_network():
+    """Table 1's layer sequence (reduced widths) with the paper's degree-2 activation polynomial (tests/golden)
+    against the same network in floating point on the slot values"""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "activation_poly_deg2.txt")
+    c2, c1 = [float(l.split()[1]) for l in open(path) if l.strip() and not l.startswith("#")]
+    name = "table1_reduced"
+    M = Material(6, 20, 50, 3, 51, 3, seed=28)
+    O = M.O
+    level = 20
+    scale = 2.0**50
+    Cc, H, W = wl.CNN_TOPOLOGIES[name]["input"]
+    imgs = wl.rng(28, "img").uniform(0, 1, size=(Cc, H, W, O.N // 2))
+    x = np.array([[[M.encrypt(imgs[c, y, xx].astype(np.complex128), scale, level, (c, y, xx)) for xx in range(W)] for y in range(H)] for c in range(Cc)])
+    shapes = wl.cnn_shapes(name)
+    wf = wl.cnn_weights_float(name, 28, sigma=1.0)
+    layers_f, layers_i = [], []
+    lvl, s, fold = level, scale, 1.0
+    for (layer, (c, h, w), _), wt in zip(shapes, wf):
+        if layer[0] in ("conv", "fc"):
+            wt = wt * (3.0 / math.sqrt(wt[0].size))  # c1 = 0.5 halves the activations at every layer: keep them near 0.1 .. 1
+            wi = np.rint(wt * fold * O.q[lvl - 1]).astype(np.int64)
+            fold = 1.0
+            layers_f.append(("conv", wt, layer[3], layer[4]) if layer[0] == "conv" else ("fc", wt))
+            layers_i.append(("conv", wi, layer[3], layer[4]) if layer[0] == "conv" else ("fc", wi))
+            lvl -= 1
+        elif layer[0] == "poly2":
+            s2 = s * s / O.q[lvl - 1]
+            layers_f.append(("poly2", c2, c1))
+            layers_i.append(("poly2", round(c2 * O.q[lvl - 2]), round(c1 * (s2 / s) * O.q[lvl - 2])))
+            s = s2
+            lvl -= 2
+        else:
+            layers_f.append(layer)
+            layers_i.append(layer)
+            fold = fold / (layer[1] * layer[1])
+    out, out_level = O.cnn_forward(x, layers_i, M.rlk, level)
+    assert out_level == lvl == 1 and out.shape[:3] == (1, 1, 1)
+    want = _float_network(imgs, layers_f)
+    assert 1e-3 < np.max(np.abs(want)) < 0.4
+    got = M.decrypt(out[0, 0, 0], s, out_level).real
+    assert np.max(np.abs(got - want[0, 0, 0])) < 1e-6 * max(1.0, np.max(np.abs(want)))
 
