@@ -177,11 +177,13 @@ int ckksmi_conv2d_workspace_bytes(const ckksmi_ctx *ctx, int C, int O, int kh, i
 int ckksmi_conv2d_mac_rows(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int C, int H, int W, int O, int kh, int kw, int stride, int pad, int in_row0, int in_rows, int out_row0, int out_rows, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
 /* in: [F] ciphertexts, w: [O][F], out: [O] ciphertexts */
 int ckksmi_fc_mac(ckksmi_ctx *ctx, const uint64_t *in, const int64_t *w, int F, int O, uint64_t *out, int level, void *ws, size_t ws_bytes, void *stream);
-/* Pooling layers of the paper's network (Table 1: 2x2 average pooling) as a sum of ciphertexts:
- * out[c,y,x] = sum_{u,v<k} in[c, k*y+u, k*x+v]; the 1/k^2 of the average is left to the caller, who folds it into
- * the next layer's plaintext weights.  in: [C][H][W] ciphertexts, out: [C][H/k][W/k] at the same level; rows and
- * columns beyond k*(H/k), k*(W/k) are ignored; 1 <= k <= 16. */
-int ckksmi_sum_pool2d(ckksmi_ctx *ctx, const uint64_t *in, int C, int H, int W, int k, uint64_t *out, int level, void *stream);
+/* Pooling layers of the paper's network (Table 1: zero padding and 2x2 average pooling) as a sum of ciphertexts over
+ * windows of the image padded with `pad` zero rows / columns on every side (0 <= pad < k):
+ * out[c,y,x] = sum_{u,v<k} in[c, k*y+u-pad, k*x+v-pad], positions outside the image contribute nothing; the 1/k^2 of
+ * the average is left to the caller, who folds it into the next layer's plaintext weights.  in: [C][H][W]
+ * ciphertexts, out: [C][(H+2*pad)/k][(W+2*pad)/k] at the same level; rows and columns beyond the last full window are
+ * ignored; 1 <= k <= 16. */
+int ckksmi_sum_pool2d(ckksmi_ctx *ctx, const uint64_t *in, int C, int H, int W, int k, int pad, uint64_t *out, int level, void *stream);
 
 /* bytes of workspace that lets `op` process the whole batch in one sweep; with
  * less (but at least one item's worth, else CKKSMI_EWORKSPACE) the call splits

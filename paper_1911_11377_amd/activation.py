@@ -9,6 +9,11 @@ and the degree-2 polynomial of section 3.1).  Two schedules are provided:
              y3 = RS(Relin(y2*t))                      level l-2, scale s_3 = s_2*s_y/q_{l-2}
              u  = RS(drop(y -> l-1) * round(0.25*s_2)) level l-2, scale s_y*s_2/q_{l-2} = s_3
              out = y3 + u + round(0.5*s_3)
+  poly2  : c2*x^2 + c1*x (the degree-2 ReLU substitute of section 3.1) for x at level l, scale s   level l -> l-2
+             x2 = RS(Relin(x*x))                       level l-1, scale s_2 = s^2/q_{l-1}
+             t2 = RS(x2 * round(c2*q_{l-2}))           level l-2, scale s_2
+             t1 = RS(drop(x -> l-1) * round(c1*(s_2/s)*q_{l-2}))   level l-2, scale s_2
+             out = t2 + t1
 The integer constants depend only on the moduli and the tracked scale.
 """
 from dataclasses import dataclass
@@ -29,6 +34,23 @@ def poly3_constants(q, level, s_y):
     s_2 = s_y * s_y / q[level - 1]
     s_3 = s_2 * s_y / q[level - 2]
     return Poly3Constants(round(-0.02 * q[level - 1]), round(0.25 * s_2), round(0.5 * s_3), s_3)
+
+
+# coefficients printed in section 3.1 for the polynomial that replaces ReLU
+PAPER_POLY2 = (0.000469841857369822, 0.500000000000008)
+
+
+@dataclass(frozen=True)
+class Poly2Constants:
+    k2: int
+    k1: int
+    out_scale: float
+
+
+def poly2_constants(q, level, s, c2=PAPER_POLY2[0], c1=PAPER_POLY2[1]):
+    """q: list of ciphertext primes, level: level of x, s: its scale"""
+    s_2 = s * s / q[level - 1]
+    return Poly2Constants(round(c2 * q[level - 2]), round(c1 * (s_2 / s) * q[level - 2]), s_2)
 
 
 def workspace_bytes(ctx, level, batch):
@@ -62,3 +84,19 @@ def poly3(ctx, y, evk, out, level, batch, consts, ws, stream=None):
     ctx.rescale(yd, u, level - 1, batch, ws, stream=stream)
     ctx.add(y3, u, out, level - 2, batch, stream=stream)
     ctx.add_const(out, consts.c_05, out, level - 2, batch, stream=stream)
+
+
+def poly2(ctx, x, evk, out, level, batch, consts, ws, stream=None):
+    """out (level-2) = c2*x^2 + c1*x; ws as sized by workspace_bytes(ctx, level, batch)"""
+    ct = batch * 2 * ctx.N
+    x2, ws = _carve(ws, ct * (level - 1))
+    xd, ws = _carve(ws, ct * (level - 1))
+    t1, ws = _carve(ws, ct * (level - 2))
+    ctx.hmul_relin_rescale(x, x, evk, x2, level, batch, ws, stream=stream)
+    ctx.mul_scalar(x2, consts.k2, x2, level - 1, batch, stream=stream)
+    ctx.rescale(x2, out, level - 1, batch, ws, stream=stream)
+    ctx.mod_drop(x, level, level - 1, xd, batch, stream=stream)
+    ctx.mul_scalar(xd, consts.k1, xd, level - 1, batch, stream=stream)
+    ctx.rescale(xd, t1, level - 1, batch, ws, stream=stream)
+    ctx.add(out, t1, out, level - 2, batch, stream=stream)
+

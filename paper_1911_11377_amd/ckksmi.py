@@ -75,7 +75,7 @@ SIGNATURES = {
     "ckksmi_conv2d_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_conv2d_mac_rows": [VP, VP, VP] + [C.c_int] * 12 + [VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_fc_mac": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_int, VP, C.c_size_t, VP],
-    "ckksmi_sum_pool2d": [VP, VP, C.c_int, C.c_int, C.c_int, C.c_int, VP, C.c_int, VP],
+    "ckksmi_sum_pool2d": [VP, VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, VP, C.c_int, VP],
     "ckksmi_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_profile_enable": [VP, C.c_int],
     "ckksmi_profile_read": [VP, C.c_int, f64p, C.POINTER(C.c_longlong), f64p],
@@ -326,8 +326,8 @@ class Context:
         self._call("ckksmi_conv2d_mac_rows", self._h, _ptr(x), _ptr(w), Cin, H, W, O, kh, kw, stride, pad, in_row0, in_rows, out_row0, out_rows,
                    _ptr(out), level, _ptr(ws), _nbytes(ws), self._stream(stream))
 
-    def sum_pool2d(self, x, Cin, H, W, k, out, level, stream=None):
-        self._call("ckksmi_sum_pool2d", self._h, _ptr(x), Cin, H, W, k, _ptr(out), level, self._stream(stream))
+    def sum_pool2d(self, x, Cin, H, W, k, out, level, stream=None, pad=0):
+        self._call("ckksmi_sum_pool2d", self._h, _ptr(x), Cin, H, W, k, pad, _ptr(out), level, self._stream(stream))
 
     def fc_mac(self, x, w, F, O, out, level, ws, stream=None):
         self._call("ckksmi_fc_mac", self._h, _ptr(x), _ptr(w), F, O, _ptr(out), level, _ptr(ws), _nbytes(ws), self._stream(stream))

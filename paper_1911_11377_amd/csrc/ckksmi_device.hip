@@ -1002,18 +1002,19 @@ extern "C" int ckksmi_conv2d_mac(ckksmi_ctx *c, const uint64_t *in, const int64_
     return ckksmi_conv2d_mac_rows(c, in, w, C, H, W, O, kh, kw, stride, pad, 0, H, 0, Ho, out, level, ws, ws_bytes, stream);
 }
 
-extern "C" int ckksmi_sum_pool2d(ckksmi_ctx *c, const uint64_t *in, int C, int H, int W, int k, uint64_t *out, int level, void *stream) {
+extern "C" int ckksmi_sum_pool2d(ckksmi_ctx *c, const uint64_t *in, int C, int H, int W, int k, int pad, uint64_t *out, int level,
+                                 void *stream) {
     if (!c) return CKKSMI_EINVAL;
     if (!dev_ok(c)) return CKKSMI_EDEVICE;
     if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
     if (!in || !out || in == out) return CKKSMI_EINVAL;
-    if (C < 1 || H < 1 || W < 1 || k < 1 || k > 16 || H < k || W < k) return CKKSMI_EINVAL;
-    const int Ho = H / k, Wo = W / k;
+    if (C < 1 || H < 1 || W < 1 || k < 1 || k > 16 || pad < 0 || pad >= k || H + 2 * pad < k || W + 2 * pad < k) return CKKSMI_EINVAL;
+    const int Ho = (H + 2 * pad) / k, Wo = (W + 2 * pad) / k;
     const size_t total = (size_t)C * Ho * Wo * 2 * level * c->N;
     if (ew_blocks(total) > 0x7fffffffu) return CKKSMI_EUNSUPPORTED;
     Guard g(c);
     KL(c, CKKSMI_K_ELEMWISE, (double)C * Ho * Wo * 2 * level, sum_pool_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)in,
-                  (u64d *)out, c->d_mod, c->logN, level, H, W, k, Ho, Wo, total);
+                  (u64d *)out, c->d_mod, c->logN, level, H, W, k, pad, Ho, Wo, total);
     return g.rc();
 }
 

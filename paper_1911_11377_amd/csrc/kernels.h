@@ -609,10 +609,11 @@ __global__ __launch_bounds__(EW_THREADS) void conv_mac_kernel(MacArgs A) {
             A.out[((((size_t)(o0 + o) * A.out_rows + oyl) * A.Wo + ox) * ctw) + (size_t)lc * N + n] = d2u(canon(acc[o], mc.p, mc.pinv));
 }
 
-// k x k sum pooling of per-pixel ciphertexts: out[c][y][x] = sum_{u,v<k} in[c][k*y+u][k*x+v], word by word.
+// k x k sum pooling of per-pixel ciphertexts over the image padded with `pad` zero rows / columns on every side:
+// out[c][y][x] = sum_{u,v<k} in[c][k*y+u-pad][k*x+v-pad], word by word, positions outside the image skipped.
 // one thread per output word; idx runs over [C*Ho*Wo][2*level][N]
 __global__ __launch_bounds__(EW_THREADS) void sum_pool_kernel(const u64d *in, u64d *out, const ModConst *modc, int logN, int level, int H, int W,
-                                                              int k, int Ho, int Wo, size_t total) {
+                                                              int k, int pad, int Ho, int Wo, size_t total) {
     const size_t idx = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
     if (idx >= total) return;
     const size_t N = (size_t)1 << logN, ctw = (size_t)2 * level * N;
@@ -623,7 +624,9 @@ __global__ __launch_bounds__(EW_THREADS) void sum_pool_kernel(const u64d *in, u6
     u64d acc = 0;
     for (int u = 0; u < k; u++)
         for (int v = 0; v < k; v++) {
-            acc += in[((c * H + (k * y + u)) * W + (k * x + v)) * ctw + off];
+            const int iy = k * (int)y + u - pad, ix = k * (int)x + v - pad;
+            if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+            acc += in[((c * H + (size_t)iy) * W + (size_t)ix) * ctw + off];
             acc = acc >= p ? acc - p : acc;
         }
     out[idx] = acc;

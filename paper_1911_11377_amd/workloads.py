@@ -126,9 +126,12 @@ CNN_TOPOLOGIES = {
                           ("fc", 4096), ("poly2",), ("fc", 4096), ("poly2",), ("fc", 1)]},
     # the same sequence at reduced width and input size (first kernel 5x5): 16 -> 12 -> 6 -> 4 -> 2 -> 2 -> 1 -> 1 -> 1
     "table1_reduced": {"input": (3, 16, 16),
-                       "layers": [("conv", 2, 5, 1, 0), ("poly2",), ("pool", 2), ("conv", 9, 3, 1, 0), ("poly2",), ("pool", 2),
+                       "layers": [("conv", 1, 5, 1, 0), ("poly2",), ("pool", 2), ("conv", 9, 3, 1, 0), ("poly2",), ("pool", 2),
                                   ("conv", 4, 3, 1, 1), ("poly2",), ("pool", 2), ("conv", 4, 3, 1, 1), ("poly2",), ("pool", 2, 1),
                                   ("fc", 6), ("poly2",), ("fc", 6), ("poly2",), ("fc", 1)]},
+    # a few layers of the same kinds for slow (emulated) checks: 6 -> 4 -> 2 -> 2 -> 2 (padded pooling) -> 2
+    "table1_tiny": {"input": (2, 6, 6),
+                    "layers": [("conv", 8, 3, 1, 0), ("poly2",), ("pool", 2), ("conv", 3, 3, 1, 1), ("poly2",), ("pool", 2, 1), ("fc", 2)]},
     "cnn_tiny": {"input": (3, 16, 16),
                  "layers": [("conv", 4, 5, 2, 0), ("square",), ("conv", 4, 3, 2, 0), ("square",), ("conv", 4, 3, 1, 1),
                             ("pool", 2), ("fc", 6), ("square",), ("fc", 2)]},

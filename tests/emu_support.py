@@ -39,11 +39,42 @@ class EmuBuf:
     def is_contiguous(self):
         return True
 
+    def reshape(self, *shape):
+        """only the flat view (what the call-sequence modules use to carve buffers)"""
+        assert shape in ((-1,), ((-1,),))
+        return EmuView(self, 0, self.nbytes // 8)
+
+    def __getitem__(self, sl):
+        return self.reshape(-1)[sl]
+
     def __del__(self):
         try:
             self._lib.emu_free(self.addr)
         except Exception:
             pass
+
+
+class EmuView:
+    """a contiguous range of words of an EmuBuf (keeps its parent alive)"""
+
+    def __init__(self, parent, start, count):
+        self.parent, self.start, self.count = parent, start, count
+        self.nbytes = count * 8
+
+    def data_ptr(self):
+        return self.parent.addr + 8 * self.start
+
+    def is_contiguous(self):
+        return True
+
+    def reshape(self, *shape):
+        assert shape in ((-1,), ((-1,),))
+        return self
+
+    def __getitem__(self, sl):
+        assert isinstance(sl, slice) and sl.step in (None, 1)
+        a, b, _ = sl.indices(self.count)
+        return EmuView(self.parent, self.start + a, max(b - a, 0))
 
 
 def emu_context(*args, **kw):

@@ -290,7 +290,7 @@ def case_cnn(be, shape, seed, topology, workers=1):
     shapes = wl.cnn_shapes(topology)
     wf = wl.cnn_weights_float(topology, seed)
     # the test's own integer weights for the oracle: round(w * q_dropped), the pooling's 1/k^2 folded forward
-    layers_i, lvl, fold = [], level, 1.0
+    layers_i, lvl, fold, sc = [], level, 1.0, 2.0**50
     for (layer, _, _), wt in zip(shapes, wf):
         if layer[0] in ("conv", "fc"):
             wi = np.rint(wt * fold * float(O.q[lvl - 1])).astype(np.int64)
@@ -299,7 +299,14 @@ def case_cnn(be, shape, seed, topology, workers=1):
             lvl -= 1
         elif layer[0] == "square":
             layers_i.append(layer)
+            sc = sc * sc / O.q[lvl - 1]
             lvl -= 1
+        elif layer[0] == "poly2":
+            c2, c1 = 0.000469841857369822, 0.500000000000008  # section 3.1
+            s2 = sc * sc / O.q[lvl - 1]
+            layers_i.append(("poly2", round(c2 * O.q[lvl - 2]), round(c1 * (s2 / sc) * O.q[lvl - 2])))
+            sc = s2
+            lvl -= 2
         else:
             layers_i.append(layer)
             fold = 1.0 / (layer[1] * layer[1])
@@ -308,12 +315,15 @@ def case_cnn(be, shape, seed, topology, workers=1):
     for p, li in zip(plans, layers_i):
         if p.w_int is not None:
             assert np.array_equal(p.w_int, li[1]), "integer weights differ"
+        if p.kind == "poly2":
+            assert (p.consts.k2, p.consts.k1) == (li[1], li[2]), "activation constants differ"
     want, want_level = O.cnn_forward(x, layers_i, M.rlk, level, workers=workers)
     assert want_level == out_level
+    print("[parity] oracle network done, running the library", flush=True)
     ws = be.ws(cnn.workspace_bytes(ctx, plans, max_items=16))
     evk = be.to_dev(M.rlk)
     dx = be.to_dev(x)
-    out = cnn.forward(ctx, dx, plans, evk, be.empty, lambda a: be.to_dev(a, np.int64), ws, stream=be.stream)
+    out = cnn.forward(ctx, dx, plans, evk, be.empty, lambda a: be.to_dev(a, np.int64), ws, stream=be.stream, max_items=16)
     got = be.to_host(out).reshape(want.shape)
     assert np.array_equal(got, want), "network output differs from the oracle"
 
@@ -343,14 +353,20 @@ def case_cnn(be, shape, seed, topology, workers=1):
     ctx.close()
 
 
-def case_pool(be, shape, seed, Cin, H, W, k, level=None):
+def case_pool(be, shape, seed, Cin, H, W, k, level=None, pad=0):
     M = make_material(shape, seed)
     O = M.O
     ctx = be.context(*shape)
     level = level or O.n_q
     x = wl.uniform_limbs(O.q[:level], O.N, seed, "pool.x", lead=(Cin, H, W, 2))
-    out = be.empty(Cin, H // k, W // k, 2, level, O.N)
-    ctx.sum_pool2d(be.to_dev(x), Cin, H, W, k, out, level, stream=be.stream)
-    assert np.array_equal(be.to_host(out).reshape(Cin, H // k, W // k, 2, level, O.N), O.sum_pool2d(x, k, level)), "pooling differs"
+    Ho, Wo = (H + 2 * pad) // k, (W + 2 * pad) // k
+    out = be.empty(Cin, Ho, Wo, 2, level, O.N)
+    ctx.sum_pool2d(be.to_dev(x), Cin, H, W, k, out, level, stream=be.stream, pad=pad)
+    assert np.array_equal(be.to_host(out).reshape(Cin, Ho, Wo, 2, level, O.N), O.sum_pool2d(x, k, level, pad)), "pooling differs"
+    try:
+        ctx.sum_pool2d(be.to_dev(x), Cin, H, W, k, out, level, stream=be.stream, pad=k)
+        raise AssertionError("padding as wide as the window accepted")
+    except ckksmi.CkksmiError as e:
+        assert e.code == ckksmi.EINVAL
     ctx.close()
 

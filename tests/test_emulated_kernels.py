@@ -65,7 +65,13 @@ def test_emulated_conv_matrix_cores(be):
 def test_emulated_pool_and_network(be):
     pc.case_pool(be, TINY, seed=112, Cin=2, H=5, W=4, k=2)
     pc.case_pool(be, TINY, seed=113, Cin=1, H=3, W=3, k=3, level=2)
+    pc.case_pool(be, TINY, seed=120, Cin=2, H=3, W=2, k=2, pad=1)
     pc.case_cnn(be, (6, 10, 50, 3, 51, 3), seed=114, topology="cnn_tiny")
+
+
+def test_emulated_table1_like_network(be):
+    """the layer kinds of Table 1 with the degree-2 activation and a padded pooling (the full sequence runs on the GPU)"""
+    pc.case_cnn(be, (6, 8, 50, 2, 51, 2), seed=121, topology="table1_tiny")
 
 
 def test_emulated_item_loop_and_composite_at_2e16(be, monkeypatch):

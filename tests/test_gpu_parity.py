@@ -116,8 +116,15 @@ def test_pool_and_network_match_oracle(be):
     """the AlexNet-like layer sequence at reduced width, N=2^13 (fused key-switching kernels), 10 levels deep"""
     announce("pool")
     pc.case_pool(be, (10, 3, 40, 0, 41, 1), seed=310, Cin=3, H=6, W=7, k=2)
+    pc.case_pool(be, (10, 3, 40, 0, 41, 1), seed=314, Cin=2, H=3, W=3, k=2, pad=1)
     announce("network cnn_reduced N=2^13")
     pc.case_cnn(be, (13, 10, 50, 3, 51, 3), seed=311, topology="cnn_reduced", workers=16)
+
+
+def test_table1_like_network_matches_oracle(be):
+    """the layer sequence of the paper's Table 1 at reduced width with its degree-2 activation, N=2^13, 19 levels deep"""
+    announce("network table1_reduced N=2^13")
+    pc.case_cnn(be, (13, 20, 50, 3, 51, 3), seed=315, topology="table1_reduced", workers=16)
 
 
 def _encrypt_batch(M, zs, scale, level, tag):
