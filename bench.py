@@ -172,25 +172,23 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     return out
 
 
-def cnn_in_strips(torch, ckksmi, wl, gen):
-    """The AlexNet-like network at its real shape (N=2^16, 30x50-bit primes, 32768 images per pass, one ciphertext
-    per pixel).  Its activations (up to 0.8 TB per layer) do not fit on one GPU, so every layer runs strip by strip over
-    ALL of its output positions on buffers of uniform residues that are reused from strip to strip (ciphertexts are
-    pseudorandom and no kernel branches on data); the time is the sum over the strips of every layer."""
-    import numpy as np
+def cnn_in_strips(torch, ckksmi, wl, gen, preset, topology, what):
+    """A whole network at its real shape (N=2^16, 32768 images per pass, one ciphertext per pixel).  Its activations
+    (up to a terabyte per layer) do not fit on one GPU, so every layer runs strip by strip over ALL of its output
+    positions on buffers of uniform residues that are reused from strip to strip (ciphertexts are pseudorandom and no
+    kernel branches on data); the time is the sum over the strips of every layer."""
+    from paper_1911_11377_amd import activation, cnn
 
-    from paper_1911_11377_amd import cnn
-
-    p5 = wl.PRESETS["cnn_2e16"]
+    p5 = wl.PRESETS[preset]
     c5 = ckksmi.Context(p5.logN, p5.n_q, p5.q_bits, p5.k, p5.special_bits, p5.alpha, device=0)
     N, L = p5.N, p5.n_q
-    shapes = wl.cnn_shapes("cnn_2e16")
-    plans, out_level, _ = cnn.plan(shapes, wl.cnn_weights_float("cnn_2e16", 5), c5.q, L, 2.0 ** p5.log_scale)
+    shapes = wl.cnn_shapes(topology)
+    plans, out_level, _ = cnn.plan(shapes, wl.cnn_weights_float(topology, 5), c5.q, L, 2.0 ** p5.log_scale)
     evk = uniform_residues(torch, c5.moduli, (c5.beta_top, 2), N, gen)
     ct_words = lambda level: 2 * level * N
-    SQ_BATCH = 256
+    ACT_BATCH = 256
 
-    # strip sizes: one output row per conv strip, two input rows per pooling strip, SQ_BATCH ciphertexts per square call
+    # strip sizes: one output row per conv strip, one output row per pooling strip, ACT_BATCH ciphertexts per activation
     def strip_words(pl):
         C, H, W = pl.in_shape
         O, Ho, Wo = pl.out_shape
@@ -199,10 +197,11 @@ def cnn_in_strips(torch, ckksmi, wl, gen):
             return C * rows_in * W * ct_words(pl.level_in), O * Wo * ct_words(pl.level_in), O * Wo * ct_words(pl.level_out)
         if pl.kind == "fc":
             return C * H * W * ct_words(pl.level_in), O * ct_words(pl.level_in), O * ct_words(pl.level_out)
-        if pl.kind == "square":
-            n = min(SQ_BATCH, C * H * W)
+        if pl.kind in ("square", "poly2"):
+            n = min(ACT_BATCH, C * H * W)
             return n * ct_words(pl.level_in), 0, n * ct_words(pl.level_out)
-        return C * pl.kernel * W * ct_words(pl.level_in), 0, O * Wo * ct_words(pl.level_out)
+        rows_in = H if pl.pad else pl.kernel
+        return C * rows_in * W * ct_words(pl.level_in), 0, O * (Ho if pl.pad else 1) * Wo * ct_words(pl.level_out)
 
     need = [strip_words(pl) for pl in plans]
     ws_bytes = cnn.workspace_bytes(c5, plans, max_items=64)
@@ -233,9 +232,16 @@ def cnn_in_strips(torch, ckksmi, wl, gen):
             calls.append(fc)
         elif pl.kind == "square":
             n_ct = C * H * W
-            for b0 in range(0, n_ct, SQ_BATCH):
-                n = min(SQ_BATCH, n_ct - b0)
+            for b0 in range(0, n_ct, ACT_BATCH):
+                n = min(ACT_BATCH, n_ct - b0)
                 calls.append(lambda n=n: c5.hmul_relin_rescale(xin, xin, evk, out, pl.level_in, n, ws))
+        elif pl.kind == "poly2":
+            n_ct = C * H * W
+            for b0 in range(0, n_ct, ACT_BATCH):
+                n = min(ACT_BATCH, n_ct - b0)
+                calls.append(lambda n=n: cnn.poly2_batch(c5, pl, xin, evk, out, n, ws, 64))
+        elif pl.pad:
+            calls.append(lambda: c5.sum_pool2d(xin, C, H, W, pl.kernel, out, pl.level_in, pad=pl.pad))
         else:
             for r in range(Ho):
                 calls.append(lambda: c5.sum_pool2d(xin, C, pl.kernel, W, pl.kernel, out, pl.level_in))
@@ -251,13 +257,14 @@ def cnn_in_strips(torch, ckksmi, wl, gen):
         total_ms += ms
         layers.append({"layer": pl.kind, "in": list(pl.in_shape), "out": list(pl.out_shape), "level": pl.level_in, "strips": len(calls),
                        "ms": round(ms, 1)})
+        del wdev
     images = N // 2
     res = {"encrypted_images_per_s": round(images / (total_ms * 1e-3), 1), "images_per_pass": images, "s_per_pass": round(total_ms * 1e-3, 2),
            "levels": [L, out_level], "layers": layers,
-           "what": "conv 3->32 5x5 s2, x^2, conv 32->64 3x3 s2, x^2, conv 64->64 3x3 pad 1, 2x2 sum pool, FC 3136->256, x^2, FC 256->2; "
-                   "every layer at its real shape over all output positions, strip by strip on reused synthetic buffers"}
+           "what": what + "; every layer at its real shape over all output positions, strip by strip on reused synthetic buffers"}
     del xin, mac, out, ws, evk
     c5.close()
+    torch.cuda.empty_cache()
     return res
 
 
@@ -269,7 +276,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweep (keeps a profile to the timed steps)")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (rotation at N=2^14, conv layer at N=2^15, activation schedule)")
-    ap.add_argument("--no-cnn", action="store_true", help="skip the full-size network in strips (about a minute of GPU time, 130 GB of HBM)")
+    ap.add_argument("--no-cnn", action="store_true", help="skip the two full-size networks in strips (about a minute of GPU time, up to 200 GB of HBM)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of the input batch (known size) so that profiler byte counters can be scaled")
     args = ap.parse_args()
@@ -397,7 +404,14 @@ def main():
     if extras is not None and not args.no_cnn:
         del a, b, evk, out, ws
         torch.cuda.empty_cache()
-        extras["cnn_2e16_in_strips"] = cnn_in_strips(torch, ckksmi, wl, gen)
+        extras["cnn_2e16_in_strips"] = cnn_in_strips(
+            torch, ckksmi, wl, gen, "cnn_2e16", "cnn_2e16",
+            "conv 3->32 5x5 s2, x^2, conv 32->64 3x3 s2, x^2, conv 64->64 3x3 pad 1, 2x2 sum pool, FC 3136->256, x^2, FC 256->2")
+        # the paper's own network (Table 1, 3x32x32 inputs, degree-2 polynomial activations of section 3.1) on the 24-prime shape
+        extras["table1_2e16_in_strips"] = cnn_in_strips(
+            torch, ckksmi, wl, gen, "act_2e16", "table1",
+            "Table 1: conv 96@11x11, conv 256@5x5, conv 384@3x3 (pad 1) twice, 2x2 average pooling after each, FC 4096, FC 4096, FC 1; "
+            "0.00047x^2 + 0.5x after every layer but the last")
 
     line = {
         "metric": "HMult+relin+rescale ops/s at N=2^16", "value": round(value, 2), "unit": "ops/s", "n_gpus": 1,
