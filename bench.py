@@ -47,7 +47,10 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "automorphism_kernel": 2 * w,
         # fused kernels: the converted limb is written once (column-pass output) plus its share of the source limbs
         "conv_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),   # ModUp
-        "modup_cols_kernel<4, %d>" % alpha: w * (1 + float(level) / (beta * E - level)),      # ModUp, targets looped in the workgroup
+        # the same conversions organised by source tile (targets looped in the workgroup)
+        "modup_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),
+        "modup_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),
+        "modup_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),
         "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
         "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
@@ -67,7 +70,10 @@ def laneops_per_unit(name, N, level, k, alpha):
     xform_pass = 8 * 4 + 3 + 3
     table = {
         "conv_cols_kernel<4, %d, 0>" % alpha: N * (7 * alpha + (alpha - 1) + 3 + xform_pass),
-        "modup_cols_kernel<4, %d>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),   # source words converted once per 24 targets
+        # source words converted to doubles once per workgroup, not once per target
+        "modup_cols_kernel<4, %d, 0>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 1>" % k: N * (5 * k + k + 3 + xform_pass),
+        "modup_cols_kernel<4, 1, 1>": N * (5 + 1 + 3 + xform_pass),
         "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
         "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         "rows_inner_kernel": N * beta * (xform_pass + 2 * (2 + 6 + 1 + 3)),
@@ -81,7 +87,7 @@ def laneops_per_unit(name, N, level, k, alpha):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
-    "modup_cols_kernel<4, 3>": (2.0 * 644299 + 6406144) * 1024,
+    "modup_cols_kernel<4, 3, 0>": (2.0 * 644299 + 6406144) * 1024,
     "rows_inner_kernel": (2.0 * 4045063 + 2313216) * 1024,
     "rows_final2_kernel": (2.0 * 3065768 + 1507328) * 1024,
 }

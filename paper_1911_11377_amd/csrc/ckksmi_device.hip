@@ -203,26 +203,38 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
 #undef CONV_COLS_CASE
 }
 
-// ModUp conversion + column pass with the targets looped inside the workgroup (see modup_cols_kernel)
-void launch_modup_cols(ckksmi_ctx *c, const u64 *y, u64 *dst, size_t items, int level, double units, hipStream_t st) {
+// Conversion + column pass with the targets looped inside the workgroup (see modup_cols_kernel).
+// mode 0: ModUp of `items` polynomials (y: [items][level][N], dst: [items][beta][E][N]);
+// mode 1: DivRound conversion of `items` rows (y: row r at y + r*y_stride, dst: [rows][nc][N])
+void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t items, int level, int nc,
+                       const DivRoundDev *D, double units, hipStream_t st) {
     ModupColsArgs A;
     memset(&A, 0, sizeof(A));
-    A.y = (const u64d *)y; A.dst = (u64d *)dst; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.cc = c->d_modup_c;
-    A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T;
+    A.y = (const u64d *)y; A.y_row_stride = y_stride; A.dst = (u64d *)dst; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.cc = c->d_modup_c;
+    A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.nc = nc;
     A.beta = (level + c->alpha - 1) / c->alpha;
     A.p51 = c->p51mask;
+    if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
-    // enough workgroups to fill the chip several times over, otherwise as many targets per workgroup as possible
-    const size_t base = (size_t)tiles * items * A.beta;
-    int chunks = (int)((size_t)c->ntt_target_wgs / (base ? base : 1));
+    const int n_targets = mode == 0 ? A.E : nc;
+    const size_t ygrid = mode == 0 ? items * A.beta : items;
+    // enough workgroups to fill the chip (8 per CU), otherwise as many targets per workgroup as possible: the source
+    // tiles are read and converted once per workgroup (measured: 24 targets 0.65 ms, 6 targets 0.75 ms for ModDown)
+    const size_t base = (size_t)tiles * ygrid;
+    int chunks = (int)((size_t)2048 / (base ? base : 1));
     if (chunks < 1) chunks = 1;
-    if (chunks > A.E) chunks = A.E;
-    A.targets_per_wg = c->modup_targets_per_wg > 0 ? c->modup_targets_per_wg : (A.E + chunks - 1) / chunks;
-    const unsigned z = (unsigned)((A.E + A.targets_per_wg - 1) / A.targets_per_wg);
-    const dim3 grid(tiles, (unsigned)(items * A.beta), z), block(V2_THREADS);
+    if (chunks > n_targets) chunks = n_targets;
+    A.targets_per_wg = c->modup_targets_per_wg > 0 ? c->modup_targets_per_wg : (n_targets + chunks - 1) / chunks;
+    const unsigned z = (unsigned)((n_targets + A.targets_per_wg - 1) / A.targets_per_wg);
+    const dim3 grid(tiles, (unsigned)ygrid, z), block(V2_THREADS);
+    const int nsrc = mode == 0 ? c->alpha : D->nb;
+    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
 #define MODUP_COLS_CASE(Q, NS)                                                                               \
-    case (Q) * 8 + (NS): KL(c, CKKSMI_K_CONV_COLS_MODUP, units, (modup_cols_kernel<Q, NS>), grid, block, st, A); break;
-    switch ((c->logN - 12) * 8 + c->alpha) {
+    case (Q) * 8 + (NS):                                                                                     \
+        if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0>), grid, block, st, A);                 \
+        else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1>), grid, block, st, A);                           \
+        break;
+    switch ((c->logN - 12) * 8 + nsrc) {
         MODUP_COLS_CASE(1, 1) MODUP_COLS_CASE(1, 2) MODUP_COLS_CASE(1, 3) MODUP_COLS_CASE(1, 4)
         MODUP_COLS_CASE(2, 1) MODUP_COLS_CASE(2, 2) MODUP_COLS_CASE(2, 3) MODUP_COLS_CASE(2, 4)
         MODUP_COLS_CASE(3, 1) MODUP_COLS_CASE(3, 2) MODUP_COLS_CASE(3, 3) MODUP_COLS_CASE(3, 4)
@@ -250,6 +262,14 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
     const unsigned tiles = (unsigned)(c->N / 4096);
     const unsigned xch = zchunks_for(c, tiles * nz, rows, A.rows_per_x);
     KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A);
+}
+
+// DivRound conversion of `rows` rows + column pass of the nc results: tmp [rows][nc][N]
+void launch_div_cols(ckksmi_ctx *c, const u64 *b_scratch, size_t bs_stride, u64 *tmp, int nc, int rows, const DivRoundDev &D, hipStream_t st) {
+    if (c->modup_loop)
+        launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st);
+    else
+        launch_conv_cols(c, 1, b_scratch, bs_stride, tmp, (size_t)nc * c->N, nc, rows, 0, &D, (double)rows * nc, st);
 }
 
 void launch_rows_final2(ckksmi_ctx *c, const u64 *tmpA, const u64 *tmpB, const u64 *x, size_t x_row_stride, const u64 *addend,
@@ -290,7 +310,7 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
     for (int i = 0; i < nc; i++) idx[i] = i;
     launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fconv ? fin : nullptr);
     if (fconv) {
-        launch_conv_cols(c, 1, b_scratch, bs_stride, tmp, (size_t)nc * N, nc, rows, 0, &D, (double)rows * nc, st);
+        launch_div_cols(c, b_scratch, bs_stride, tmp, nc, rows, D, st);
     } else {
         DivConvArgs DC;
         DC.b_limbs = (const u64d *)b_scratch; DC.b_row_stride = bs_stride; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
@@ -332,7 +352,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
                    c->d_fin_modup + (size_t)level * c->n_q);
         if (c->modup_loop)
-            launch_modup_cols(c, ycoef, dtA, items, level, (double)items * (beta * E - level), st);
+            launch_modup_cols(c, 0, ycoef, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st);
         else
             launch_conv_cols(c, 0, ycoef, (size_t)level * N, dtA, (size_t)beta * E * N, beta * E, items, level, nullptr,
                              (double)items * (beta * E - level), st);
@@ -377,11 +397,11 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         const DivRoundDev &DA = c->divround[0], &DB = c->divround[1 + (level - 1)];
         int lidx[1] = {level - 1};
         launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown);
-        launch_conv_cols(c, 1, specials, (size_t)E * N, tmp, (size_t)level * N, level, rows, 0, &DA, (double)rows * level, st);
+        launch_div_cols(c, specials, (size_t)E * N, tmp, level, rows, DA, st);
         launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, add_both, r_last, DA.Binv, level, rows, st,
                           level - 1, 1, N);
         launch_ntt(c, false, r_last, last_coef, table_map(lidx, 1, N, N), rows, st, c->d_fin_rescale + (level - 1));
-        launch_conv_cols(c, 1, last_coef, N, tmpB, (size_t)(level - 1) * N, level - 1, rows, 0, &DB, (double)rows * (level - 1), st);
+        launch_div_cols(c, last_coef, N, tmpB, level - 1, rows, DB, st);
         launch_rows_final2(c, tmp, tmpB, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, out, DA.Binv, DB.Binv, level, rows, st);
         return;
     }
@@ -1067,13 +1087,10 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
         // the conversion kernels are instantiated per (size, source limbs, mode): report the symbol that runs
         static thread_local char buf[64];
         const int q = c->logN - 12;
-        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) {
-            if (c->modup_loop) snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d>", q, c->alpha);
-            else snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 0>", q, c->alpha);
-            return buf;
-        }
-        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, %d, 1>", q, c->k); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "conv_cols_kernel<%d, 1, 1>", q); return buf; }
+        const char *kn = c->modup_loop ? "modup_cols_kernel" : "conv_cols_kernel";
+        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "%s<%d, %d, 0>", kn, q, c->alpha); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "%s<%d, %d, 1>", kn, q, c->k); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "%s<%d, 1, 1>", kn, q); return buf; }
     }
     return names[kernel_class];
 }

@@ -151,29 +151,34 @@ __global__ __launch_bounds__(V2_THREADS, 3) void conv_cols_kernel(ConvColsArgs A
 // column-pass tile of every target limb of its chunk from them.  What remains per target is arithmetic and stores
 // (which do not stall a wave), so the loads no longer alternate with the butterflies.  Per target the 255 column-pass
 // twiddles of its modulus go through LDS (one coalesced 2 KB read per workgroup, fetched one target ahead).
+// MODE 0 (ModUp): grid y = item * beta + digit, sources = the digit's limbs of y, targets = the other limbs of the
+// extended basis.  MODE 1 (DivRound conversion, ModDown or rescale): grid y = row, sources = the D.nb dropped limbs
+// (row r at y + r*y_row_stride), targets = the nc kept limbs, h subtracted.
 struct ModupColsArgs {
-    const u64d *y;                // [items][level][N] conversion inputs y_i, coefficient form, canonical
-    u64d *dst;                    // [items][beta][E][N]
+    const u64d *y;                // MODE 0: [items][level][N] conversion inputs y_i, coefficient form, canonical
+    unsigned long long y_row_stride;  // MODE 1
+    u64d *dst;                    // MODE 0: [items][beta][E][N]; MODE 1: [rows][nc][N]
     const ModConst *modc;
     const double *tw;             // forward twiddles [T][N]
     const WMul *cc;               // ModUp constants [beta_top][alpha][alpha][T]
-    int logN, level, E, n_q, alpha, beta, T;
+    DivRoundDev D;                // MODE 1 constants
+    int logN, level, E, n_q, alpha, beta, T, nc;
     int targets_per_wg;
     P51Mask p51;
 };
 
 template <bool P51, int NSRC, int Q>
 __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], const WMul (&Wc)[NSRC], const double *twl, double *lds, u64d *dst,
-                                                  const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store) {
+                                                  const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store, double hsub) {
     typedef ColsGeom<Q> Geo;
     typedef ColsMasks<Q, P51> Mk;
     double x[16];
 #pragma unroll
     for (int e = 0; e < 16; e++) {
-        double v = 0.0;
+        double v = -hsub;
 #pragma unroll
         for (int a = 0; a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
-        x[e] = reduce_balanced(v, p, pinv);  // |v| <= NSRC * 0.75p
+        x[e] = reduce_balanced(v, p, pinv);  // |v| <= p + NSRC * 0.75p
     }
     {
         double tw1[15];
@@ -207,25 +212,35 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 }
 
 // grid: x = column tile (N/4096), y = item * beta + digit, z = chunk of targets_per_wg target limbs
-template <int Q, int NSRC>
+template <int Q, int NSRC, int MODE>
 __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs A) {
     // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
     // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
     __shared__ double lds[2][16 * V2_GS];
     __shared__ double twl[3][256];
     const unsigned N = 1u << A.logN;
-    const unsigned item = blockIdx.y / (unsigned)A.beta, j = blockIdx.y % (unsigned)A.beta;
-    const int lo = (int)j * A.alpha;
-    const int nsrc = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
-    const int n_targets = A.E - nsrc;  // every limb of the extended basis outside the digit
+    unsigned item = 0, j = 0;
+    int lo = 0, nsrc, n_targets;
+    const u64d *ysrc;
+    if (MODE == 0) {
+        item = blockIdx.y / (unsigned)A.beta;
+        j = blockIdx.y % (unsigned)A.beta;
+        lo = (int)j * A.alpha;
+        nsrc = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
+        n_targets = A.E - nsrc;  // every limb of the extended basis outside the digit
+        ysrc = A.y + ((size_t)item * A.level + lo) * N;
+    } else {
+        nsrc = A.D.nb;
+        n_targets = A.nc;
+        ysrc = A.y + (size_t)blockIdx.y * A.y_row_stride;
+    }
     const int k0 = (int)blockIdx.z * A.targets_per_wg;
     const int k1 = k0 + A.targets_per_wg < n_targets ? k0 + A.targets_per_wg : n_targets;
     if (k0 >= k1) return;
     const ColsGeom<Q> geo(threadIdx.x, blockIdx.x);
-    // the digit's source words, once: a missing source (digit cut short by the level) re-reads limb lo, its constants are zero
+    // the source words, once: a missing source (digit cut short by the level) re-reads the first limb, its constants are zero
     double yd[NSRC][16];
     {
-        const u64d *ysrc = A.y + ((size_t)item * A.level + lo) * N;
         u64d raw[NSRC][16];
 #pragma unroll
         for (int a = 0; a < NSRC; a++) {
@@ -239,9 +254,10 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
             for (int e = 0; e < 16; e++) yd[a][e] = u2d(raw[a][e]);
     }
     const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
-    // extended-basis index of target k (the digit's own limbs are skipped), and its modulus index
-    auto ext_of = [&](int k) { return k < lo ? k : k + nsrc; };
-    auto mod_of = [&](int x) { return x < A.level ? x : A.n_q + x - A.level; };
+    // MODE 0: extended-basis index of target k (the digit's own limbs are skipped) and its modulus index;
+    // MODE 1: target k is kept limb k
+    auto ext_of = [&](int k) { return MODE == 0 ? (k < lo ? k : k + nsrc) : k; };
+    auto mod_of = [&](int x) { return MODE == 0 ? (x < A.level ? x : A.n_q + x - A.level) : x; };
     twl[0][threadIdx.x] = A.tw[(size_t)mod_of(ext_of(k0)) * N + threadIdx.x];
     double tw_next = k0 + 1 < k1 ? A.tw[(size_t)mod_of(ext_of(k0 + 1)) * N + threadIdx.x] : 0.0;
     __syncthreads();
@@ -253,13 +269,22 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
         if (k + 2 < k1) tw_next = A.tw[(size_t)mod_of(ext_of(k + 2)) * N + threadIdx.x];
         const double p = A.modc[t].p, pinv = A.modc[t].pinv;
         WMul Wc[NSRC];
+        double hsub = 0.0;
+        u64d *dst;
+        if (MODE == 0) {
 #pragma unroll
-        for (int a = 0; a < NSRC; a++) Wc[a] = a < nsrc ? A.cc[(crow + a) * A.T + t] : WMul{0.0, 0.0};
-        u64d *dst = A.dst + (((size_t)item * A.beta + j) * A.E + x) * N;
+            for (int a = 0; a < NSRC; a++) Wc[a] = a < nsrc ? A.cc[(crow + a) * A.T + t] : WMul{0.0, 0.0};
+            dst = A.dst + (((size_t)item * A.beta + j) * A.E + x) * N;
+        } else {
+#pragma unroll
+            for (int a = 0; a < NSRC; a++) Wc[a] = a < nsrc ? A.D.conv[(size_t)a * A.T + t] : WMul{0.0, 0.0};
+            hsub = A.D.hc[t];
+            dst = A.dst + ((size_t)blockIdx.y * A.nc + t) * N;
+        }
         if (is_p51(A.p51, t))
-            modup_cols_target<true, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store);
+            modup_cols_target<true, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub);
         else
-            modup_cols_target<false, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store);
+            modup_cols_target<false, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub);
     }
 }
 
