@@ -219,6 +219,117 @@ def test_2e16_hybrid_shape_sampled(be):
         del ws, out
 
 
+def _device_residues(torch, q_list, lead, N, seed):
+    """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(wl.BASE_SEED + seed)
+    out = torch.empty(tuple(lead) + (len(q_list), N), dtype=torch.int64, device="cuda:0")
+    step = 1 << 27
+    flat = out.view(-1)
+    for o in range(0, flat.numel(), step):
+        flat[o:o + step].random_(0, 1 << 49, generator=g)
+    return out
+
+
+def _oracle_window(O, x_dev, wi, Cin, rows_in, W, in_row0, H, kh, stride, pad, level, o, oy, ox):
+    """one output ciphertext of a convolution from the oracle: the window's input ciphertexts are copied from the device
+    buffer x_dev ([Cin][rows_in][W] holding image rows in_row0..), taps on padding become all-zero ciphertexts"""
+    N = O.N
+    win = np.zeros((Cin, kh, kh, 2, level, N), dtype=np.uint64)
+    for u in range(kh):
+        for v in range(kh):
+            iy, ix = oy * stride + u - pad, ox * stride + v - pad
+            if 0 <= iy < H and 0 <= ix < W:
+                win[:, u, v] = x_dev[:, iy - in_row0, ix].cpu().numpy().view(np.uint64)
+    return O.conv2d_mac(win, wi[o:o + 1], 1, 0, level)[0, 0, 0]
+
+
+def test_conv_layer_full_size_sampled(be):
+    """the conv layer of the 2^15 workload in the benchmark's launch configuration (3x32x32 pixel ciphertexts, 16 primes,
+    3 -> 32 channels, 5x5 stride 2: matrix cores, 128 padded taps) followed by the rescale of all 6272 outputs; four
+    output ciphertexts compared word for word with the oracle"""
+    import torch
+    announce("conv layer N=2^15 full size, sampled parity")
+    p3 = wl.PRESETS["conv_2e15"]
+    shape = (p3.logN, p3.n_q, p3.q_bits, p3.k, p3.special_bits, p3.alpha)
+    O = orc.Oracle(*shape)
+    ctx = be.context(*shape)
+    assert ctx.moduli == O.moduli
+    L, N = p3.n_q, p3.N
+    Cin, H, W, Oc, kh, stride = 3, 32, 32, 32, 5, 2
+    Ho = (H - kh) // stride + 1
+    x = _device_residues(torch, O.q[:L], (Cin, H, W, 2), N, 31)
+    wi = np.rint(wl.weights_float((Oc, Cin, kh, kh), 31) * O.q[L - 1]).astype(np.int64)
+    dw = be.to_dev(wi, np.int64)
+    mac = be.empty(Oc, Ho, Ho, 2, L, N)
+    out = be.empty(Oc, Ho, Ho, 2, L - 1, N)
+    ws = be.ws(max(ctx.conv2d_workspace_bytes(Cin, Oc, kh, kh, L), ctx.workspace_bytes(ckksmi.OP_RESCALE, L, 256)))
+    ctx.profile_enable(True)
+    ctx.conv2d_mac(x, dw, Cin, H, W, Oc, kh, kh, stride, 0, mac, L, ws)
+    ctx.rescale(mac, out, L, Oc * Ho * Ho, ws)
+    torch.cuda.synchronize()
+    assert "conv_mac_mfma_kernel" in ctx.profile_read()
+    ctx.profile_enable(False)
+    for o, oy, ox in ((0, 0, 0), (31, 13, 13), (17, 6, 9), (8, 13, 0)):
+        announce("oracle for output (%d,%d,%d)" % (o, oy, ox))
+        want = _oracle_window(O, x, wi, Cin, H, W, 0, H, kh, stride, 0, L, o, oy, ox)
+        assert np.array_equal(mac[o, oy, ox].cpu().numpy().view(np.uint64), want), "MAC of output %r" % ((o, oy, ox),)
+        assert np.array_equal(out[o, oy, ox].cpu().numpy().view(np.uint64), O.rescale(want, L)), "rescaled output %r" % ((o, oy, ox),)
+    ctx.close()
+
+
+def test_network_layer_shapes_sampled(be):
+    """layers of the 2^16 network at their real width (two limbs): the 3136 -> 256 fully connected layer (49 tap steps,
+    8 channel groups) at N=2^14 and a strip of the zero-padded 64 -> 64 3x3 convolution at N=2^16, sampled outputs
+    against the oracle"""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    announce("FC 3136->256 at N=2^14, sampled parity")
+    shape = (14, 2, 50, 0, 51, 1)
+    O = orc.Oracle(*shape)
+    ctx = be.context(*shape)
+    L, N = 2, 1 << 14
+    F, Oc = 3136, 256
+    x = _device_residues(torch, O.q[:L], (F, 1, 1, 2), N, 32)
+    wi = np.rint(wl.weights_float((Oc, F), 32) * O.q[L - 1]).astype(np.int64)
+    out = be.empty(Oc, 2, L, N)
+    ws = be.ws(ctx.conv2d_workspace_bytes(F, Oc, 1, 1, L))
+    ctx.profile_enable(True)
+    ctx.fc_mac(x, be.to_dev(wi, np.int64), F, Oc, out, L, ws)
+    torch.cuda.synchronize()
+    assert "conv_mac_mfma_kernel" in ctx.profile_read()
+    ctx.profile_enable(False)
+    xh = x.cpu().numpy().view(np.uint64).reshape(F, 2, L, N)
+    picks = (0, 255, 100)
+    with ThreadPoolExecutor(len(picks)) as ex:  # the oracle's C calls release the GIL
+        wants = list(ex.map(lambda o: O.fc_mac(xh, wi[o:o + 1], L)[0], picks))
+    for o, want in zip(picks, wants):
+        assert np.array_equal(out[o].cpu().numpy().view(np.uint64), want), "FC output %d" % o
+    ctx.close()
+    del x, xh, out, ws
+
+    announce("padded conv strip 64->64 at N=2^16, sampled parity")
+    shape = (16, 2, 50, 0, 51, 1)
+    O = orc.Oracle(*shape)
+    ctx = be.context(*shape)
+    N = 1 << 16
+    # rows 12..13 of the 14x14 map from a strip holding image rows 11..13 (the last row touches the bottom padding)
+    Cin, H, W, Oc, kh = 64, 14, 14, 64, 3
+    in_row0, rows_in, out_row0, out_rows = 11, 3, 12, 2
+    xs = _device_residues(torch, O.q[:L], (Cin, rows_in, W, 2), N, 33)
+    wc = np.rint(wl.weights_float((Oc, Cin, kh, kh), 33) * O.q[L - 1]).astype(np.int64)
+    outs = be.empty(Oc, out_rows, W, 2, L, N)
+    ws = be.ws(ctx.conv2d_workspace_bytes(Cin, Oc, kh, kh, L))
+    ctx.conv2d_mac_rows(xs, be.to_dev(wc, np.int64), Cin, H, W, Oc, kh, kh, 1, 1, in_row0, rows_in, out_row0, out_rows, outs, L, ws)
+    torch.cuda.synchronize()
+    picks = ((0, 12, 0), (63, 13, 13), (33, 13, 5), (5, 12, 7))
+    with ThreadPoolExecutor(len(picks)) as ex:
+        wants = list(ex.map(lambda t: _oracle_window(O, xs, wc, Cin, rows_in, W, in_row0, H, kh, 1, 1, L, *t), picks))
+    for (o, oy, ox), want in zip(picks, wants):
+        assert np.array_equal(outs[o, oy - out_row0, ox].cpu().numpy().view(np.uint64), want), "strip output %r" % ((o, oy, ox),)
+    ctx.close()
+
+
 def test_activation_schedule_on_gpu(be):
     """x^2 then 0.5 + 0.25y - 0.02y^3 with relin + rescale at each level, against the oracle's
     composition (bit-exact) and the float polynomial"""
