@@ -48,9 +48,10 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         # fused kernels: the converted limb is written once (column-pass output) plus its share of the source limbs
         "conv_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),   # ModUp
         # the same conversions organised by source tile (targets looped in the workgroup)
-        "modup_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),
-        "modup_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),
-        "modup_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),
+        # (", true": the inverse column pass of the sources runs in the kernel too; same bytes)
+        "modup_cols_kernel<4, %d, 0, true>" % alpha: w * (1 + float(level) / (beta * E - level)),
+        "modup_cols_kernel<4, %d, 1, true>" % k: w * (1 + float(k) / level),
+        "modup_cols_kernel<4, 1, 1, true>": w * (1 + 1.0 / (level - 1)),
         "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
         "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
@@ -71,9 +72,10 @@ def laneops_per_unit(name, N, level, k, alpha):
     table = {
         "conv_cols_kernel<4, %d, 0>" % alpha: N * (7 * alpha + (alpha - 1) + 3 + xform_pass),
         # source words converted to doubles once per workgroup, not once per target
-        "modup_cols_kernel<4, %d, 0>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
-        "modup_cols_kernel<4, %d, 1>" % k: N * (5 * k + k + 3 + xform_pass),
-        "modup_cols_kernel<4, 1, 1>": N * (5 + 1 + 3 + xform_pass),
+        # (the inverse column pass of the source tiles, once per workgroup, adds about 5 %: not counted)
+        "modup_cols_kernel<4, %d, 0, true>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 1, true>" % k: N * (5 * k + k + 3 + xform_pass),
+        "modup_cols_kernel<4, 1, 1, true>": N * (5 + 1 + 3 + xform_pass),
         "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
         "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         "rows_inner_kernel": N * beta * (xform_pass + 2 * (2 + 6 + 1 + 3)),
@@ -87,7 +89,7 @@ def laneops_per_unit(name, N, level, k, alpha):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
-    "modup_cols_kernel<4, 3, 0>": (2.0 * 644299 + 6406144) * 1024,
+    "modup_cols_kernel<4, 3, 0, true>": (2.0 * 644299 + 6406144) * 1024,
     "rows_inner_kernel": (2.0 * 4045063 + 2313216) * 1024,
     "rows_final2_kernel": (2.0 * 3065768 + 1507328) * 1024,
 }

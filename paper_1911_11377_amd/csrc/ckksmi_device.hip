@@ -124,9 +124,10 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
             else KL(c, CKKSMI_K_NTT_FWD_ROW, limbs_work, ntt_fwd_kernel<false>, grow, dim3(NTT_THREADS), st, A);
         }
     } else {
+        // inverse: passes 2 = contiguous (row) pass only, leaving the reduced-double intermediate (register-tiled sizes)
         if (v2_rows) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, (ntt_v2_kernel<true, false>), gv2, dim3(V2_THREADS), st, V);
         else KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
-        if (A.LA) {
+        if (A.LA && (passes & 1)) {
             A.src = (const u64d *)dst;
             A.map.src_item_stride = A.map.dst_item_stride;
             V.src = A.src;
@@ -206,14 +207,16 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
 // Conversion + column pass with the targets looped inside the workgroup (see modup_cols_kernel).
 // mode 0: ModUp of `items` polynomials (y: [items][level][N], dst: [items][beta][E][N]);
 // mode 1: DivRound conversion of `items` rows (y: row r at y + r*y_stride, dst: [rows][nc][N])
+// fin != nullptr: y is the output of the inverse row pass and the kernel runs the inverse column pass itself
 void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t items, int level, int nc,
-                       const DivRoundDev *D, double units, hipStream_t st) {
+                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin = nullptr) {
     ModupColsArgs A;
     memset(&A, 0, sizeof(A));
     A.y = (const u64d *)y; A.y_row_stride = y_stride; A.dst = (u64d *)dst; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.cc = c->d_modup_c;
     A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.nc = nc;
     A.beta = (level + c->alpha - 1) / c->alpha;
     A.p51 = c->p51mask;
+    A.tw_inv = c->d_tww_inv; A.fin = fin;
     if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
     const int n_targets = mode == 0 ? A.E : nc;
@@ -231,8 +234,10 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
 #define MODUP_COLS_CASE(Q, NS)                                                                               \
     case (Q) * 8 + (NS):                                                                                     \
-        if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0>), grid, block, st, A);                 \
-        else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1>), grid, block, st, A);                           \
+        if (mode == 0 && fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, true>), grid, block, st, A);    \
+        else if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, false>), grid, block, st, A);     \
+        else if (fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, true>), grid, block, st, A);            \
+        else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, false>), grid, block, st, A);                    \
         break;
     switch ((c->logN - 12) * 8 + nsrc) {
         MODUP_COLS_CASE(1, 1) MODUP_COLS_CASE(1, 2) MODUP_COLS_CASE(1, 3) MODUP_COLS_CASE(1, 4)
@@ -265,9 +270,11 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
 }
 
 // DivRound conversion of `rows` rows + column pass of the nc results: tmp [rows][nc][N]
-void launch_div_cols(ckksmi_ctx *c, const u64 *b_scratch, size_t bs_stride, u64 *tmp, int nc, int rows, const DivRoundDev &D, hipStream_t st) {
+// fin != nullptr: b_scratch holds the output of the inverse row pass only (see launch_modup_cols)
+void launch_div_cols(ckksmi_ctx *c, const u64 *b_scratch, size_t bs_stride, u64 *tmp, int nc, int rows, const DivRoundDev &D, hipStream_t st,
+                     const FinConst *fin = nullptr) {
     if (c->modup_loop)
-        launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st);
+        launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
     else
         launch_conv_cols(c, 1, b_scratch, bs_stride, tmp, (size_t)nc * c->N, nc, rows, 0, &D, (double)rows * nc, st);
 }
@@ -308,9 +315,10 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
     const bool fconv = (c->fuse & FUSE_DIVCONV) != 0, ffinal = (c->fuse & FUSE_FINAL) != 0;
     int idx[CKKSMI_MAX_MODULI];
     for (int i = 0; i < nc; i++) idx[i] = i;
-    launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fconv ? fin : nullptr);
+    const bool finv = fconv && c->modup_loop && c->fuse_inv;  // the conversion kernel runs the inverse column pass itself
+    launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fconv ? fin : nullptr, finv ? 2 : 3);
     if (fconv) {
-        launch_div_cols(c, b_scratch, bs_stride, tmp, nc, rows, D, st);
+        launch_div_cols(c, b_scratch, bs_stride, tmp, nc, rows, D, st, finv ? fin : nullptr);
     } else {
         DivConvArgs DC;
         DC.b_limbs = (const u64d *)b_scratch; DC.b_row_stride = bs_stride; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
@@ -349,10 +357,12 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
     if (c->fuse & FUSE_MODUP) {
         // y_i = d_i * qhat_i^-1 straight out of the inverse transform; conversion rides on the column pass
+        const bool finv = c->modup_loop && c->fuse_inv;
         launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
-                   c->d_fin_modup + (size_t)level * c->n_q);
+                   c->d_fin_modup + (size_t)level * c->n_q, finv ? 2 : 3);
         if (c->modup_loop)
-            launch_modup_cols(c, 0, ycoef, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st);
+            launch_modup_cols(c, 0, ycoef, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st,
+                              finv ? c->d_fin_modup + (size_t)level * c->n_q : nullptr);
         else
             launch_conv_cols(c, 0, ycoef, (size_t)level * N, dtA, (size_t)beta * E * N, beta * E, items, level, nullptr,
                              (double)items * (beta * E - level), st);
@@ -396,12 +406,13 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         u64 *last_coef = ycoef;                           // [rows][N] (the conversion inputs of ModUp are no longer needed)
         const DivRoundDev &DA = c->divround[0], &DB = c->divround[1 + (level - 1)];
         int lidx[1] = {level - 1};
-        launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown);
-        launch_div_cols(c, specials, (size_t)E * N, tmp, level, rows, DA, st);
+        const bool finv = c->modup_loop && c->fuse_inv;
+        launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown, finv ? 2 : 3);
+        launch_div_cols(c, specials, (size_t)E * N, tmp, level, rows, DA, st, finv ? c->d_fin_moddown : nullptr);
         launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, add_both, r_last, DA.Binv, level, rows, st,
                           level - 1, 1, N);
-        launch_ntt(c, false, r_last, last_coef, table_map(lidx, 1, N, N), rows, st, c->d_fin_rescale + (level - 1));
-        launch_div_cols(c, last_coef, N, tmpB, level - 1, rows, DB, st);
+        launch_ntt(c, false, r_last, last_coef, table_map(lidx, 1, N, N), rows, st, c->d_fin_rescale + (level - 1), finv ? 2 : 3);
+        launch_div_cols(c, last_coef, N, tmpB, level - 1, rows, DB, st, finv ? c->d_fin_rescale + (level - 1) : nullptr);
         launch_rows_final2(c, tmp, tmpB, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, out, DA.Binv, DB.Binv, level, rows, st);
         return;
     }
@@ -554,6 +565,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
         if (const char *e = getenv("CKKSMI_MAC_MFMA")) c->mac_mfma = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_LOOP")) c->modup_loop = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_FUSE_TAIL")) c->fuse_tail = atoi(e) != 0;
+        if (const char *e = getenv("CKKSMI_FUSE_INV")) c->fuse_inv = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_TARGETS")) c->modup_targets_per_wg = atoi(e);
     }
     for (int t = 0; t < T; t++)
@@ -1088,9 +1100,10 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
         static thread_local char buf[64];
         const int q = c->logN - 12;
         const char *kn = c->modup_loop ? "modup_cols_kernel" : "conv_cols_kernel";
-        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "%s<%d, %d, 0>", kn, q, c->alpha); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "%s<%d, %d, 1>", kn, q, c->k); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "%s<%d, 1, 1>", kn, q); return buf; }
+        const char *tail = c->modup_loop ? (c->fuse_inv ? ", true>" : ", false>") : ">";
+        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "%s<%d, %d, 0%s", kn, q, c->alpha, tail); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "%s<%d, %d, 1%s", kn, q, c->k, tail); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "%s<%d, 1, 1%s", kn, q, tail); return buf; }
     }
     return names[kernel_class];
 }

@@ -165,7 +165,50 @@ struct ModupColsArgs {
     int logN, level, E, n_q, alpha, beta, T, nc;
     int targets_per_wg;
     P51Mask p51;
+    // INVSRC: y holds the output of the inverse ROW pass (reduced doubles); the inverse column pass with its folded
+    // constants runs in the workgroup's prologue and the conversion inputs never go through memory
+    const double *tw_inv;         // inverse twiddles [T][N]
+    const FinConst *fin;          // last-stage constants of source limb s (MODE 0: limb index; MODE 1: s-th dropped limb)
 };
+
+// Inverse column pass of one source tile in registers: x in the round-2 register layout on entry, the canonical
+// coefficient-form words (as doubles) in the round-1 layout on return.
+template <bool P51, int Q>
+__device__ __forceinline__ void inv_cols_in_regs(double (&x)[16], const double *twl, double *lds, const ColsGeom<Q> &geo, double p, double pinv,
+                                                 const FinConst &F) {
+    typedef ColsGeom<Q> Geo;
+    typedef ColsMasks<Q, P51> Mk;
+    const WMul unused = WMul{0.0, 0.0};
+    {
+        double tw2[15];
+#pragma unroll
+        for (int s = 0; s < 4; s++)
+#pragma unroll
+            for (int b = 0; b < (1 << s); b++) {
+                if (s >= 4 - Q) {
+                    const int u = s - (4 - Q);
+                    tw2[(1 << s) - 1 + b] = twl[(16u << u) + (geo.a << u) + (b & ((1 << u) - 1))];
+                } else {
+                    tw2[(1 << s) - 1 + b] = 0.0;
+                }
+            }
+        inv_stages<Geo::S0, Mk::I1, false>(x, tw2, p, pinv, unused, unused);
+    }
+    reduce16(x, p, pinv);
+#pragma unroll
+    for (int i = 0; i < 16; i++) lds[geo.l2(i)] = x[i];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = lds[geo.l1(e)];
+    {
+        double tw1[15];
+#pragma unroll
+        for (int i = 0; i < 15; i++) tw1[i] = twl[1 + i];
+        inv_round<Mk::I2, true>(x, tw1, p, pinv, F.ninv, F.wlast);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = canon(x[e] + F.cadd, p, pinv);
+}
 
 template <bool P51, int NSRC, int Q>
 __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], const WMul (&Wc)[NSRC], const double *twl, double *lds, u64d *dst,
@@ -212,7 +255,7 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 }
 
 // grid: x = column tile (N/4096), y = item * beta + digit, z = chunk of targets_per_wg target limbs
-template <int Q, int NSRC, int MODE>
+template <int Q, int NSRC, int MODE, bool INVSRC>
 __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs A) {
     // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
     // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
@@ -240,7 +283,7 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
     const ColsGeom<Q> geo(threadIdx.x, blockIdx.x);
     // the source words, once: a missing source (digit cut short by the level) re-reads the first limb, its constants are zero
     double yd[NSRC][16];
-    {
+    if (!INVSRC) {
         u64d raw[NSRC][16];
 #pragma unroll
         for (int a = 0; a < NSRC; a++) {
@@ -252,6 +295,40 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
         for (int a = 0; a < NSRC; a++)
 #pragma unroll
             for (int e = 0; e < 16; e++) yd[a][e] = u2d(raw[a][e]);
+    } else {
+        // every source tile is requested first, then taken through its inverse column pass one after the other
+        u64d raw[NSRC][16];
+#pragma unroll
+        for (int a = 0; a < NSRC; a++) {
+            const u64d *ya = ysrc + (size_t)(a < nsrc ? a : 0) * N;
+#pragma unroll
+            for (int i = 0; i < 16; i++) raw[a][i] = ya[geo.g2(i)];
+        }
+#pragma unroll
+        for (int a = 0; a < NSRC; a++) {
+            if (a < nsrc) {  // uniform
+                const int ls = MODE == 0 ? lo + a : a;                 // index of the source among the transformed limbs
+                const int ts = MODE == 0 ? lo + a : A.D.b_idx[a];      // its modulus
+                const double ps = A.modc[ts].p, psinv = A.modc[ts].pinv;
+                const FinConst F = A.fin[ls];
+                __syncthreads();  // the previous source is done with twl[2] and lds[0]
+                twl[2][threadIdx.x] = A.tw_inv[(size_t)ts * N + threadIdx.x];
+                __syncthreads();
+                double x[16];
+#pragma unroll
+                for (int i = 0; i < 16; i++) x[i] = mid_load(raw[a][i]);
+                if (is_p51(A.p51, ts))
+                    inv_cols_in_regs<true, Q>(x, twl[2], lds[0], geo, ps, psinv, F);
+                else
+                    inv_cols_in_regs<false, Q>(x, twl[2], lds[0], geo, ps, psinv, F);
+#pragma unroll
+                for (int e = 0; e < 16; e++) yd[a][e] = x[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) yd[a][e] = 0.0;
+            }
+        }
+        __syncthreads();  // lds[0] and twl are about to be reused by the targets
     }
     const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
     // MODE 0: extended-basis index of target k (the digit's own limbs are skipped) and its modulus index;
