@@ -27,6 +27,9 @@
  *     workspace memory: the caller passes device buffers and a hipStream_t (as
  *     void*; NULL = the default stream).  Device calls enqueue on that stream and
  *     return without synchronising.  The context owns only its constant tables.
+ *     Device buffers (ciphertexts, keys, workspace) must be 16-byte aligned: the
+ *     kernels move two words per lane and memory instruction; a misaligned
+ *     pointer is rejected with CKKSMI_EINVAL.
  *   - Scale is caller-side metadata; level and batch are explicit arguments.
  *   - A context created with device = -1 is host-only: the host functions work,
  *     every device function returns CKKSMI_EDEVICE.  There is no CPU fallback for

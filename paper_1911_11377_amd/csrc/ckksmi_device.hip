@@ -527,7 +527,7 @@ void rescale_core(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u
 }
 
 void launch_tensor(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, int level, int items, hipStream_t st) {
-    const size_t total = (size_t)items * level * c->N;
+    const size_t total = (size_t)items * level * c->N / 2;  // word pairs
     KL(c, CKKSMI_K_TENSOR, (double)items * level, tensor_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)a, (const u64d *)b, (u64d *)d, c->d_mod,
                   c->logN, level, total);
 }
@@ -675,8 +675,11 @@ void dev_free_tables(ckksmi_ctx *c) {
 }
 
 // ------------------------------------------------------------------ C ABI, device side
+// device buffers must be 16-byte aligned (two-word vector accesses)
+static inline bool al16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
 extern "C" int ckksmi_galois_key_register(ckksmi_ctx *c, int rot, const uint64_t *gk_dev) {
-    if (!c || !gk_dev) return CKKSMI_EINVAL;
+    if (!c || !gk_dev || !al16(gk_dev)) return CKKSMI_EINVAL;
     if (c->k == 0) return CKKSMI_EUNSUPPORTED;
     const int r = norm_rot(c, rot);
     for (auto &e : c->galois)
@@ -686,7 +689,7 @@ extern "C" int ckksmi_galois_key_register(ckksmi_ctx *c, int rot, const uint64_t
 }
 
 static int ntt_api(ckksmi_ctx *c, bool fwd, uint64_t *limbs, const int *index, int n_limbs, int batch, void *stream) {
-    if (!c || !limbs || !index || n_limbs < 1 || n_limbs > CKKSMI_MAX_MODULI || batch < 0) return CKKSMI_EINVAL;
+    if (!c || !limbs || !al16(limbs) || !index || n_limbs < 1 || n_limbs > CKKSMI_MAX_MODULI || batch < 0) return CKKSMI_EINVAL;
     if (!dev_ok(c)) return CKKSMI_EDEVICE;
     for (int i = 0; i < n_limbs; i++)
         if (index[i] < 0 || index[i] >= c->T) return CKKSMI_EINVAL;
@@ -782,7 +785,7 @@ extern "C" int ckksmi_mod_drop(ckksmi_ctx *c, const uint64_t *a, int level_in, i
 extern "C" int ckksmi_hmul(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, uint64_t *d, int level, int batch, void *stream) {
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
-    if (!a || !b || !d) return CKKSMI_EINVAL;
+    if (!a || !b || !d || !al16(a) || !al16(b) || !al16(d)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
     Guard g(c);
     launch_tensor(c, a, b, d, level, batch, S(stream));
@@ -820,7 +823,7 @@ extern "C" int ckksmi_relin(ckksmi_ctx *c, const uint64_t *d, const uint64_t *ev
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
     if (c->k == 0) return CKKSMI_EUNSUPPORTED;
-    if (!d || !evk || !out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (!d || !evk || !out || (!ws && batch) || !al16(d) || !al16(evk) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
     const size_t N = c->N, per = ks_words_per_item(c, level);
     const int chunk = sweep_items(ws_bytes, per, batch);
@@ -843,7 +846,7 @@ extern "C" int ckksmi_rescale(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, i
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
     if (level < 2) return CKKSMI_ELEVEL;
-    if (!a || !out || a == out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (!a || !out || a == out || (!ws && batch) || !al16(a) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
     const size_t N = c->N, per = rescale_words_per_item(c, level);
     const int chunk = sweep_items(ws_bytes, per, batch);
@@ -862,7 +865,7 @@ extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const
     if (rc) return rc;
     if (c->k == 0) return CKKSMI_EUNSUPPORTED;
     if (level < 2) return CKKSMI_ELEVEL;
-    if (!a || !b || !evk || !out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (!a || !b || !evk || !out || (!ws && batch) || !al16(a) || !al16(b) || !al16(evk) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
     const size_t N = c->N;
     const size_t per = 5 * (size_t)level * N + std::max(ks_words_per_item(c, level), rescale_words_per_item(c, level));
@@ -896,7 +899,7 @@ extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, u
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
     if (c->k == 0) return CKKSMI_EUNSUPPORTED;
-    if (!a || !rot || !out || a == out || (!ws && batch)) return CKKSMI_EINVAL;
+    if (!a || !rot || !out || a == out || (!ws && batch) || !al16(a) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
     // every rotation needs its key before anything is enqueued
     std::vector<int> key_of(batch);

@@ -272,23 +272,30 @@ __global__ __launch_bounds__(EW_THREADS) void mod_drop_kernel(const u64d *a, u64
     out[w] = a[(row * level_in + i) * N + (w & (N - 1))];
 }
 
-// d = (a0*b0, a0*b1 + a1*b0, a1*b1); a, b: [batch][2][level][N], d: [batch][3][level][N]
+// d = (a0*b0, a0*b1 + a1*b0, a1*b1); a, b: [batch][2][level][N], d: [batch][3][level][N].
+// One thread per pair of adjacent words (16 bytes per lane and memory instruction); total = batch*level*N/2 pairs.
+__device__ __forceinline__ void tensor_word(double a0, double a1, double b0, double b1, const ModConst &mc, u64d &d0, u64d &d1, u64d &d2) {
+    d0 = d2u(canon(mulmod(a0, b0, mc.p, mc.pinv), mc.p, mc.pinv));
+    d1 = d2u(canon(mulmod(a0, b1, mc.p, mc.pinv) + mulmod(a1, b0, mc.p, mc.pinv), mc.p, mc.pinv));
+    d2 = d2u(canon(mulmod(a1, b1, mc.p, mc.pinv), mc.p, mc.pinv));
+}
 __global__ __launch_bounds__(EW_THREADS) void tensor_kernel(const u64d *a, const u64d *b, u64d *d, const ModConst *modc, int logN,
-                                                            int level, size_t total /* batch*level*N */) {
-    size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
-    if (w >= total) return;
-    const size_t N = (size_t)1 << logN;
+                                                            int level, size_t total /* batch*level*N/2 */) {
+    const size_t pr = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (pr >= total) return;
+    const size_t N = (size_t)1 << logN, w = 2 * pr;
     const size_t limb = w >> logN, item = limb / level, i = limb % level, n = w & (N - 1);
     const ModConst mc = modc[i];
     const size_t ia = (item * 2 * level + i) * N + n, st = (size_t)level * N;
-    double a0 = u2d(a[ia]), a1 = u2d(a[ia + st]), b0 = u2d(b[ia]), b1 = u2d(b[ia + st]);
-    double d0 = mulmod(a0, b0, mc.p, mc.pinv);
-    double d1 = mulmod(a0, b1, mc.p, mc.pinv) + mulmod(a1, b0, mc.p, mc.pinv);
-    double d2 = mulmod(a1, b1, mc.p, mc.pinv);
+    const ulonglong2 A0 = *(const ulonglong2 *)(a + ia), A1 = *(const ulonglong2 *)(a + ia + st);
+    const ulonglong2 B0 = *(const ulonglong2 *)(b + ia), B1 = *(const ulonglong2 *)(b + ia + st);
+    ulonglong2 D0, D1, D2;
+    tensor_word(u2d(A0.x), u2d(A1.x), u2d(B0.x), u2d(B1.x), mc, D0.x, D1.x, D2.x);
+    tensor_word(u2d(A0.y), u2d(A1.y), u2d(B0.y), u2d(B1.y), mc, D0.y, D1.y, D2.y);
     const size_t id = (item * 3 * level + i) * N + n;
-    d[id] = d2u(canon(d0, mc.p, mc.pinv));
-    d[id + st] = d2u(canon(d1, mc.p, mc.pinv));
-    d[id + 2 * st] = d2u(canon(d2, mc.p, mc.pinv));
+    *(ulonglong2 *)(d + id) = D0;
+    *(ulonglong2 *)(d + id + st) = D1;
+    *(ulonglong2 *)(d + id + 2 * st) = D2;
 }
 
 // Evaluation-form automorphism X -> X^g: out[j] = in[pi(j)],

@@ -450,26 +450,31 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     double a0[16], a1[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) a0[i] = a1[i] = 0.0;
-    // The digit that contains this limb needs no transform: its operand is the source polynomial itself, read in
-    // position layout (word i*256+tid) like the key.
+    // Multiply-accumulate layout: a thread owns the word PAIRS (512*s + 2*tid, +1), s < 8, of the tile, so that key
+    // words, the own digit's words and the results move 16 bytes per lane (the load path handles 16 bytes per lane at the
+    // cost of 8); accumulator 2*s + b belongs to word 512*s + 2*tid + b = row 2*s + tid/128, column 2*(tid%128) + b.
+    // The digit that contains this limb needs no transform: its operand is the source polynomial itself.
     const int j_own = (int)x < A.level ? (int)x / A.alpha : -1;
     if (j_own >= 0) {
         const u64d *k0 = key + (((size_t)j_own * 2 + 0) * A.T + t) * N + tile0;
         const u64d *k1 = key + (((size_t)j_own * 2 + 1) * A.T + t) * N + tile0;
         const u64d *src = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0;
-        u64d kr0[16], kr1[16], xr[16];
+        ulonglong2 kr0[8], kr1[8], xo[8];
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            xr[i] = src[i * 256 + tid];
-            kr0[i] = k0[i * 256 + tid];
-            kr1[i] = k1[i * 256 + tid];
+        for (int s = 0; s < 8; s++) {
+            xo[s] = ((const ulonglong2 *)src)[256 * s + tid];
+            kr0[s] = ((const ulonglong2 *)k0)[256 * s + tid];
+            kr1[s] = ((const ulonglong2 *)k1)[256 * s + tid];
         }
         SCHED_FENCE();
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            const double v = reduce_balanced(u2d(xr[i]), p, pinv), vp = v * pinv;
-            a0[i] = mulmod_w(u2d(kr0[i]), v, vp, p);
-            a1[i] = mulmod_w(u2d(kr1[i]), v, vp, p);
+        for (int s = 0; s < 8; s++) {
+            const double v0 = reduce_balanced(u2d(xo[s].x), p, pinv), vp0 = v0 * pinv;
+            const double v1 = reduce_balanced(u2d(xo[s].y), p, pinv), vp1 = v1 * pinv;
+            a0[2 * s] = mulmod_w(u2d(kr0[s].x), v0, vp0, p);
+            a1[2 * s] = mulmod_w(u2d(kr1[s].x), v0, vp0, p);
+            a0[2 * s + 1] = mulmod_w(u2d(kr0[s].y), v1, vp1, p);
+            a1[2 * s + 1] = mulmod_w(u2d(kr1[s].y), v1, vp1, p);
         }
     }
     // The other digits, software-pipelined so that no memory latency sits in front of arithmetic: the limb words of a
@@ -486,11 +491,11 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     while (j < A.beta) {
         const u64d *k0 = key + (((size_t)j * 2 + 0) * A.T + t) * N + tile0;
         const u64d *k1 = key + (((size_t)j * 2 + 1) * A.T + t) * N + tile0;
-        u64d kr0[16], kr1[16];
+        ulonglong2 kr0[8], kr1[8];
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            kr0[i] = k0[i * 256 + tid];
-            kr1[i] = k1[i * 256 + tid];
+        for (int s = 0; s < 8; s++) {
+            kr0[s] = ((const ulonglong2 *)k0)[256 * s + tid];
+            kr1[s] = ((const ulonglong2 *)k1)[256 * s + tid];
         }
         SCHED_FENCE();
         {
@@ -527,12 +532,15 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         }
         SCHED_FENCE();
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
+        for (int s = 0; s < 8; s++) {
             // the transformed word is the prepared factor (|v| <= p/2 + 1, v/p computed once for both components), the
             // key word the other one: each term is below 0.875p and the sum is reduced only when it could pass 2^53
-            const double v = lds[i * V2_GS + hi4 * 17 + lo4], vp = v * pinv;
-            a0[i] += mulmod_w(u2d(kr0[i]), v, vp, p);
-            a1[i] += mulmod_w(u2d(kr1[i]), v, vp, p);
+            const double *vrow = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            const double v0 = vrow[0], vp0 = v0 * pinv, v1 = vrow[1], vp1 = v1 * pinv;
+            a0[2 * s] += mulmod_w(u2d(kr0[s].x), v0, vp0, p);
+            a1[2 * s] += mulmod_w(u2d(kr1[s].x), v0, vp0, p);
+            a0[2 * s + 1] += mulmod_w(u2d(kr0[s].y), v1, vp1, p);
+            a1[2 * s + 1] += mulmod_w(u2d(kr1[s].y), v1, vp1, p);
         }
         if (++pending == (P51 ? 4 : 8)) {  // p < 2^51: 0.5p + 4 * 0.875p = 4p < 2^53; p < 2^50: 0.5p + 8 * 0.875p < 8p <= 2^53
 #pragma unroll
@@ -548,9 +556,9 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        o0[i * 256 + tid] = d2u(canon(a0[i], p, pinv));
-        o1[i * 256 + tid] = d2u(canon(a1[i], p, pinv));
+    for (int s = 0; s < 8; s++) {
+        ((ulonglong2 *)o0)[256 * s + tid] = make_ulonglong2(d2u(canon(a0[2 * s], p, pinv)), d2u(canon(a0[2 * s + 1], p, pinv)));
+        ((ulonglong2 *)o1)[256 * s + tid] = make_ulonglong2(d2u(canon(a1[2 * s], p, pinv)), d2u(canon(a1[2 * s + 1], p, pinv)));
     }
 }
 
@@ -605,20 +613,25 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
         const bool add = A.addend && (A.add_both || (row & 1u) == 0);
         const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
         // operands of the last step are requested before the transform so that their latency overlaps it
-        u64d xr[16], ar[16];
+        // pointwise part in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
+        ulonglong2 xr[8], ar[8];
 #pragma unroll
-        for (int q = 0; q < 16; q++) {
-            xr[q] = xin[q * 256 + tid];
-            ar[q] = ad[q * 256 + tid];
+        for (int s = 0; s < 8; s++) {
+            xr[s] = ((const ulonglong2 *)xin)[256 * s + tid];
+            ar[s] = ((const ulonglong2 *)ad)[256 * s + tid];
         }
         SCHED_FENCE();
         rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.nc + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
 #pragma unroll
-        for (int q = 0; q < 16; q++) {
-            const double r = lds[q * V2_GS + hi4 * 17 + lo4];
-            double v = mulmod_w(u2d(xr[q]) - r, W.w, W.wp, p);
-            if (add) v += u2d(ar[q]);
-            out[q * 256 + tid] = d2u(canon(v, p, pinv));
+        for (int s = 0; s < 8; s++) {
+            const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            double v0 = mulmod_w(u2d(xr[s].x) - rr[0], W.w, W.wp, p);
+            double v1 = mulmod_w(u2d(xr[s].y) - rr[1], W.w, W.wp, p);
+            if (add) {
+                v0 += u2d(ar[s].x);
+                v1 += u2d(ar[s].y);
+            }
+            ((ulonglong2 *)out)[256 * s + tid] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
         }
         __syncthreads();
     }
@@ -673,23 +686,30 @@ __device__ __forceinline__ void rows_final2_body(const RowsFinal2Args &A, double
         const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
         const u64d *ad = A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0;
         u64d *out = A.out + ((size_t)row * A.ncB + i) * N + tile0;
-        u64d xr[16], ar[16];
+        // pointwise parts in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
+        ulonglong2 xr[8], ar[8];
 #pragma unroll
-        for (int q = 0; q < 16; q++) {
-            xr[q] = xin[q * 256 + tid];
-            ar[q] = ad[q * 256 + tid];
+        for (int s = 0; s < 8; s++) {
+            xr[s] = ((const ulonglong2 *)xin)[256 * s + tid];
+            ar[s] = ((const ulonglong2 *)ad)[256 * s + tid];
         }
         SCHED_FENCE();
         rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.ncA + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
         double r[16];  // |r| < 2.5p
 #pragma unroll
-        for (int q = 0; q < 16; q++) r[q] = mulmod_w(u2d(xr[q]) - lds[q * V2_GS + hi4 * 17 + lo4], WA.w, WA.wp, p) + u2d(ar[q]);
+        for (int s = 0; s < 8; s++) {
+            const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            r[2 * s] = mulmod_w(u2d(xr[s].x) - rr[0], WA.w, WA.wp, p) + u2d(ar[s].x);
+            r[2 * s + 1] = mulmod_w(u2d(xr[s].y) - rr[1], WA.w, WA.wp, p) + u2d(ar[s].y);
+        }
         __syncthreads();
         rows_fwd_to_lds<P51>(A.tmpB + ((size_t)row * A.ncB + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
 #pragma unroll
-        for (int q = 0; q < 16; q++) {
-            const double v = mulmod_w(r[q] - lds[q * V2_GS + hi4 * 17 + lo4], WB.w, WB.wp, p);  // |r - rB| < 3.1p < 2^53
-            out[q * 256 + tid] = d2u(canon(v, p, pinv));
+        for (int s = 0; s < 8; s++) {
+            const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            const double v0 = mulmod_w(r[2 * s] - rr[0], WB.w, WB.wp, p);  // |r - rB| < 3.1p < 2^53
+            const double v1 = mulmod_w(r[2 * s + 1] - rr[1], WB.w, WB.wp, p);
+            ((ulonglong2 *)out)[256 * s + tid] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
         }
         __syncthreads();
     }

@@ -254,17 +254,26 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(x[e], p, pinv);
             __syncthreads();
+            // canonical words out in pairs (512*s + 2*tid, +1): 16 bytes per lane and store
 #pragma unroll
-            for (int i = 0; i < 16; i++) dst[tile0 + i * 256 + tid] = d2u(lds[i * V2_GS + hi4 * 17 + lo4]);
+            for (int s = 0; s < 8; s++) {
+                const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+                ((ulonglong2 *)(dst + tile0))[256 * s + tid] = make_ulonglong2(d2u(rr[0]), d2u(rr[1]));
+            }
         } else {
             {
                 // all 16 words requested before the first is used: one memory latency per item, not sixteen
-                u64d raw[16];
+                // (in pairs 512*s + 2*tid, +1: 16 bytes per lane and load)
+                ulonglong2 raw[8];
 #pragma unroll
-                for (int i = 0; i < 16; i++) raw[i] = src[tile0 + i * 256 + tid];
+                for (int s = 0; s < 8; s++) raw[s] = ((const ulonglong2 *)(src + tile0))[256 * s + tid];
                 NTT_SCHED_FENCE();
 #pragma unroll
-                for (int i = 0; i < 16; i++) lds[i * V2_GS + hi4 * 17 + lo4] = u2d(raw[i]);
+                for (int s = 0; s < 8; s++) {
+                    double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+                    rr[0] = u2d(raw[s].x);
+                    rr[1] = u2d(raw[s].y);
+                }
             }
             __syncthreads();
 #pragma unroll

@@ -117,3 +117,19 @@ def test_emulated_fused_path_other_sizes(be, monkeypatch, logN):
     pc.case_relin_and_composite(be, (logN, 3, 50, 2, 51, 2), seed=117, batch=2, levels=[3, 2])
     monkeypatch.setenv("CKKSMI_FUSE", "0")
     pc.case_relin_and_composite(be, (logN, 2, 40, 1, 41, 1), seed=118, batch=1, levels=[2])
+
+
+def test_emulated_misaligned_device_pointer_is_rejected(be):
+    """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
+    from paper_1911_11377_amd import ckksmi
+    shape = TINY
+    ctx = be.context(*shape)
+    N, level = 1 << shape[0], shape[1]
+    a = be.empty(1 + 2 * level * N)
+    out = be.empty(2 * (level - 1) * N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_RESCALE, level, 1))
+    with pytest.raises(ckksmi.CkksmiError) as e:
+        ctx.rescale(a[1:], out, level, 1, ws, stream=be.stream)
+    assert e.value.code == ckksmi.EINVAL
+    ctx.close()
+
