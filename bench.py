@@ -40,6 +40,7 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "ntt_fwd_kernel<true>": w, "ntt_fwd_kernel<false>": w, "ntt_inv_kernel<false>": w, "ntt_inv_kernel<true>": w,
         "ntt_v2_kernel<false, true>": w, "ntt_v2_kernel<false, false>": w, "ntt_v2_kernel<true, false>": w, "ntt_v2_kernel<true, true>": w,
         "tensor_kernel": 7 * w,                       # 4 limbs in, 3 out
+        "tensor_rows_kernel": 8 * w,                  # + the inverse row pass of the third component out
         "modup_kernel": w * (1.0 / E * min(alpha, level) + 1),   # per output limb: its share of the digit's source limbs + itself
         "inner_product_kernel": w * (beta + 2 + 2.0 * beta / batch),  # beta inputs, 2 outputs, key read once per batch
         "divround_conv_kernel": w * (1 + float(k) / level),

@@ -221,7 +221,8 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_MAC_MFMA 18      /* conv / FC multiply-accumulate on the matrix cores */
 #define CKKSMI_K_MACPREP_MFMA 19  /* its weight digits and tap table */
 #define CKKSMI_K_ROWS_FINAL2 20   /* ModDown's and rescale's last steps in one contiguous pass */
-#define CKKSMI_K_COUNT 21
+#define CKKSMI_K_TENSOR_ROWS 21   /* tensor product fused with the inverse contiguous pass of its third component */
+#define CKKSMI_K_COUNT 22
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

@@ -342,7 +342,7 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
 // ciphertexts [items][2][level-1][N]; tail_scratch holds 2*level*N words per item.  Needs both DivRound fusions.
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
-                   u64 *tail_scratch = nullptr) {
+                   u64 *tail_scratch = nullptr, bool ymid_ready = false) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     u64 *ycoef = ws;
@@ -358,8 +358,10 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     if (c->fuse & FUSE_MODUP) {
         // y_i = d_i * qhat_i^-1 straight out of the inverse transform; conversion rides on the column pass
         const bool finv = c->modup_loop && c->fuse_inv;
-        launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
-                   c->d_fin_modup + (size_t)level * c->n_q, finv ? 2 : 3);
+        // ymid_ready: the tensor kernel already left the inverse row pass of d_eval at the start of the workspace
+        if (!(ymid_ready && finv))
+            launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
+                       c->d_fin_modup + (size_t)level * c->n_q, finv ? 2 : 3);
         if (c->modup_loop)
             launch_modup_cols(c, 0, ycoef, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st,
                               finv ? c->d_fin_modup + (size_t)level * c->n_q : nullptr);
@@ -532,6 +534,14 @@ void launch_tensor(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, int level,
                   c->logN, level, total);
 }
 
+// tensor product + inverse row pass of d2 into ymid (see tensor_rows_kernel); register-tiled sizes only
+void launch_tensor_rows(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, u64 *ymid, int level, int items, hipStream_t st) {
+    TensorRowsArgs A;
+    A.a = (const u64d *)a; A.b = (const u64d *)b; A.d = (u64d *)d; A.ymid = (u64d *)ymid; A.modc = c->d_mod; A.tw_inv = c->d_tww_inv;
+    A.logN = c->logN; A.level = level; A.p51 = c->p51mask;
+    KL(c, CKKSMI_K_TENSOR_ROWS, (double)items * level, tensor_rows_kernel, dim3((unsigned)(c->N / 4096), level, items), dim3(V2_THREADS), st, A);
+}
+
 int sweep_items(size_t ws_bytes, size_t words_per_item, int batch) {
     size_t fit = ws_bytes / 8 / words_per_item;
     if (fit > (size_t)batch) fit = batch;
@@ -566,6 +576,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
         if (const char *e = getenv("CKKSMI_MODUP_LOOP")) c->modup_loop = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_FUSE_TAIL")) c->fuse_tail = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_FUSE_INV")) c->fuse_inv = atoi(e) != 0;
+        if (const char *e = getenv("CKKSMI_FUSE_TENSOR")) c->fuse_tensor = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_TARGETS")) c->modup_targets_per_wg = atoi(e);
     }
     for (int t = 0; t < T; t++)
@@ -880,11 +891,24 @@ extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const
         u64 *d = (u64 *)ws;                              // [items][3][level][N]
         u64 *r = d + (size_t)items * 3 * level * N;      // [items][2][level][N]
         u64 *rest = r + (size_t)items * 2 * level * N;
-        launch_tensor(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, level, items, S(stream));
-        if (c->fused && c->fuse_tail && (c->fuse & (FUSE_DIVCONV | FUSE_FINAL)) == (FUSE_DIVCONV | FUSE_FINAL)) {
+        const bool tail = c->fused && c->fuse_tail && (c->fuse & (FUSE_DIVCONV | FUSE_FINAL)) == (FUSE_DIVCONV | FUSE_FINAL);
+        // the tensor kernel can take d2 through the inverse row pass on the way (its output lands where the key switch
+        // expects it: the start of its workspace)
+        const bool trows = c->fused && c->fuse_tensor && (c->fuse & FUSE_MODUP) && c->modup_loop && c->fuse_inv;
+        if (trows)
+            launch_tensor_rows(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, rest, level, items, S(stream));
+        else
+            launch_tensor(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, level, items, S(stream));
+        if (tail) {
             // ModDown + add + rescale with a shared last pass: r is only scratch
             ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
-                          out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), r);
+                          out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), r, trows);
+            continue;
+        }
+        if (trows) {
+            ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r,
+                          rest, S(stream), nullptr, true);
+            rescale_core(c, r, out + (size_t)b0 * 2 * (level - 1) * N, items, level, rest, S(stream));
             continue;
         }
         ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r, rest,
@@ -1093,7 +1117,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
-                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel"};
+                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && c->logN >= 13 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",

@@ -88,6 +88,7 @@ struct ckksmi_ctx {
     // ---- device tables ----
     ModConst *d_mod = nullptr;   // [T]
     WMul *d_pow24 = nullptr;     // [T] 2^24 mod p (matrix-core MAC: recombination of the digit diagonals)
+    int fuse_tensor = 1;         // hmul_relin_rescale: the tensor kernel runs the inverse row pass of d2 (CKKSMI_FUSE_TENSOR=0: separate pass)
     int fuse_inv = 1;            // conversion kernels run the inverse column pass of their sources themselves (CKKSMI_FUSE_INV=0: separate pass)
     int fuse_tail = 1;           // hmul_relin_rescale: ModDown and rescale share their last pass (CKKSMI_FUSE_TAIL=0: two passes)
     int modup_loop = 1;          // ModUp column pass organised by source tile (CKKSMI_MODUP_LOOP=0: one workgroup per target limb)

@@ -24,6 +24,85 @@
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #endif
 
+// ------------------------------------------------------------------ tensor + inverse row pass of its third component
+// The composite multiply feeds d2 = a1*b1 straight into key switching, whose first step is the inverse transform of
+// d2.  This kernel computes the tensor product of one 4096-word tile (all three components, written in evaluation form
+// as the plain tensor kernel does) and takes d2 through the inverse ROW pass while it is still on chip; the column
+// pass follows in the ModUp kernel.  Saves one read of d2 and a launch.
+struct TensorRowsArgs {
+    const u64d *a, *b;   // [items][2][level][N]
+    u64d *d;             // [items][3][level][N]
+    u64d *ymid;          // [items][level][N]: inverse row pass of d2 (reduced doubles)
+    const ModConst *modc;
+    const double *tw_inv;
+    int logN, level;
+    P51Mask p51;
+};
+
+template <bool P51>
+__device__ __forceinline__ void tensor_rows_body(const TensorRowsArgs &A, double *lds, unsigned item, int i) {
+    constexpr int I1 = P51 ? 0x2 : 0x4, I2 = P51 ? 0x1 : 0x4;
+    const unsigned N = 1u << A.logN, N1 = N >> 8;
+    const ModConst mc = A.modc[i];
+    const double p = mc.p, pinv = mc.pinv;
+    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
+    const size_t tile0 = (size_t)blockIdx.x * 4096, st = (size_t)A.level * N;
+    double tw1[15], tw2[15];
+    load_twiddles(A.tw_inv + (size_t)i * N, N1 + blockIdx.x * 16 + hi4, lo4, tw1, tw2);
+    const ulonglong2 *a0 = (const ulonglong2 *)(A.a + ((size_t)item * 2 * A.level + i) * N + tile0), *a1 = a0 + st / 2;
+    const ulonglong2 *b0 = (const ulonglong2 *)(A.b + ((size_t)item * 2 * A.level + i) * N + tile0), *b1 = b0 + st / 2;
+    ulonglong2 *d0 = (ulonglong2 *)(A.d + ((size_t)item * 3 * A.level + i) * N + tile0), *d1 = d0 + st / 2, *d2 = d1 + st / 2;
+    // word pairs (512*s + 2*tid, +1), four at a time to bound the registers in flight
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        ulonglong2 A0[4], A1[4], B0[4], B1[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            const unsigned e = 256u * (4 * h + s) + tid;
+            A0[s] = a0[e]; A1[s] = a1[e]; B0[s] = b0[e]; B1[s] = b1[e];
+        }
+        SCHED_FENCE();
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            const unsigned e = 256u * (4 * h + s) + tid;
+            ulonglong2 D0, D1, D2;
+            tensor_word(u2d(A0[s].x), u2d(A1[s].x), u2d(B0[s].x), u2d(B1[s].x), mc, D0.x, D1.x, D2.x);
+            tensor_word(u2d(A0[s].y), u2d(A1[s].y), u2d(B0[s].y), u2d(B1[s].y), mc, D0.y, D1.y, D2.y);
+            d0[e] = D0; d1[e] = D1; d2[e] = D2;
+            double *rr = lds + (2 * (4 * h + s) + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            rr[0] = u2d(D2.x);
+            rr[1] = u2d(D2.y);
+        }
+    }
+    __syncthreads();
+    // inverse row pass of d2 exactly as in ntt_v2_rows
+    double *grp = lds + hi4 * V2_GS;
+    const WMul unused = WMul{0.0, 0.0};
+    double x[16];
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
+    inv_round<I1, false>(x, tw2, p, pinv, unused, unused);
+#pragma unroll
+    for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = x[e];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 16; e++) x[e] = grp[e * 17 + lo4];
+    inv_round<I2, false>(x, tw1, p, pinv, unused, unused);
+    u64d *ym = A.ymid + ((size_t)item * A.level + i) * N + tile0;
+#pragma unroll
+    for (int e = 0; e < 16; e++) ym[hi4 * 256 + lo4 + 16 * e] = mid_store(x[e], p, pinv);
+}
+
+// grid: x = tile (N/4096), y = limb, z = item
+__global__ __launch_bounds__(V2_THREADS, 2) void tensor_rows_kernel(TensorRowsArgs A) {
+    __shared__ double lds[16 * V2_GS];
+    const int i = (int)blockIdx.y;
+    if (is_p51(A.p51, i))
+        tensor_rows_body<true>(A, lds, blockIdx.z, i);
+    else
+        tensor_rows_body<false>(A, lds, blockIdx.z, i);
+}
+
 // ------------------------------------------------------------------ column pass with conversion
 struct ConvColsArgs {
     const u64d *y;                // source limbs, coefficient form, canonical; item i at y + i*y_item_stride
