@@ -79,7 +79,10 @@ def laneops_per_unit(name, N, level, k, alpha):
         "modup_cols_kernel<4, 1, 1, true>": N * (5 + 1 + 3 + xform_pass),
         "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
         "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
-        "rows_inner_kernel": N * beta * (xform_pass + 2 * (2 + 6 + 1 + 3)),
+        # per word: a row pass for every digit except the limb's own one (level of the E limbs have one), two
+        # multiply-accumulates per digit (key word conversion 2 + exact product 5 + add 1, the prepared quotient and the
+        # lazy reductions shared: about 2 more per digit), canonical form of the two results
+        "rows_inner_kernel": N * ((beta - float(level) / (level + k)) * xform_pass + beta * (2 * 8 + 2) + 2 * 7),
         "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),
         "rows_final2_kernel": N * (2 * xform_pass + 2 + 1 + 5 + 3 + 1 + 5 + 7 + 2),
     }
@@ -90,9 +93,10 @@ def laneops_per_unit(name, N, level, k, alpha):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
-    "modup_cols_kernel<4, 3, 0, true>": (2.0 * 644299 + 6406144) * 1024,
-    "rows_inner_kernel": (2.0 * 4045063 + 2313216) * 1024,
-    "rows_final2_kernel": (2.0 * 3065768 + 1507328) * 1024,
+    "modup_cols_kernel<4, 3, 0, true>": (2.0 * 618083 + 6397952) * 1024,
+    "rows_inner_kernel": (2.0 * 3846468 + 1916928) * 1024,
+    "rows_final2_kernel": (2.0 * 3066124 + 1507328) * 1024,
+    "tensor_rows_kernel": (2.0 * 1963578 + 3145728) * 1024,
 }
 
 
