@@ -35,6 +35,7 @@
  * Modulus indices: 0..n_q-1 are the ciphertext primes q_i, n_q..n_q+k-1 the
  * special primes p_m.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -441,10 +442,19 @@ void orc_modup(const orc_params *P, const u64 *d_coef, int level, int j, u64 *ou
  * As integers: out = floor((x + h)/Bbar) - u, u = 0 when |B| = 1 (exact
  * round-to-nearest), 0 <= u <= |B|-1 otherwise.  h mod t is obtained from
  * 2*h = Bbar - 1, i.e. h = (Bbar mod t - 1) * 2^-1 mod t (t odd).
+ *
+ * exact != 0 removes u: sum_m y_m * bhat_m = ((x + h) mod Bbar) + u*Bbar, hence
+ * sum_m y_m / b_m = ((x + h) mod Bbar)/Bbar + u and u is the integer part of that
+ * sum.  It is taken in double precision, v = floor(((y_0*i_0 + y_1*i_1) + y_2*i_2) + ...)
+ * with i_m the double nearest to 1/b_m and every product and sum rounded to
+ * nearest, and r_i loses v * (Bbar mod c_i).  v = u unless (x + h) mod Bbar lies
+ * within about |B| * 2^-52 * Bbar of a multiple of Bbar; the order of the
+ * floating-point operations is part of the definition.
  */
-void orc_divround_coef(const orc_params *P, const u64 *x, const int *cidx, int nc, const int *bidx, int nb, u64 *out) {
+static void divround_coef(const orc_params *P, const u64 *x, const int *cidx, int nc, const int *bidx, int nb, int exact, u64 *out) {
     u64 N = P->N;
     u64 *y = (u64 *)malloc((size_t)nb * N * 8);
+    u64 *v = (u64 *)calloc(N, 8);
     for (int m = 0; m < nb; m++) {
         u64 bm = P->mod[bidx[m]];
         u64 bhat = 1;
@@ -454,6 +464,16 @@ void orc_divround_coef(const orc_params *P, const u64 *x, const int *cidx, int n
         const u64 *xm = x + (size_t)(nc + m) * N;
         for (u64 n = 0; n < N; n++) y[(size_t)m * N + n] = orc_mulmod(orc_addmod(xm[n] % bm, h, bm), inv, bm);
     }
+    if (exact)
+        for (u64 n = 0; n < N; n++) {
+            volatile double sum = 0.0; /* volatile: every operation rounded to double, none contracted */
+            for (int m = 0; m < nb; m++) {
+                volatile double inv_b = 1.0 / (double)P->mod[bidx[m]];
+                volatile double term = (double)y[(size_t)m * N + n] * inv_b;
+                sum = m == 0 ? term : sum + term;
+            }
+            v[n] = (u64)floor(sum);
+        }
     for (int i = 0; i < nc; i++) {
         u64 c = P->mod[cidx[i]];
         u64 Bbar = 1;
@@ -470,26 +490,35 @@ void orc_divround_coef(const orc_params *P, const u64 *x, const int *cidx, int n
         for (u64 n = 0; n < N; n++) {
             u64 r = 0;
             for (int m = 0; m < nb; m++) r = orc_addmod(r, orc_mulmod(y[(size_t)m * N + n] % c, bhat_c[m], c), c);
+            r = orc_submod(r, orc_mulmod(v[n] % c, Bbar, c), c);
             o[n] = orc_mulmod(orc_submod(orc_addmod(xi[n] % c, h, c), r, c), Binv, c);
         }
         free(bhat_c);
     }
-    free(y);
+    free(y); free(v);
+}
+
+void orc_divround_coef(const orc_params *P, const u64 *x, const int *cidx, int nc, const int *bidx, int nb, u64 *out) {
+    divround_coef(P, x, cidx, nc, bidx, nb, 0, out);
+}
+
+void orc_divround_exact_coef(const orc_params *P, const u64 *x, const int *cidx, int nc, const int *bidx, int nb, u64 *out) {
+    divround_coef(P, x, cidx, nc, bidx, nb, 1, out);
 }
 
 /*
- * Key switch of one polynomial d (evaluation form, [level][N]) with a switching
- * key [beta][2][n_q+k][N]:  inverse transform, ModUp each digit, transform,
- * inner product with the key over the extended basis, then DivRound_P of both
- * accumulators.  ks: [2][level][N] evaluation form.
+ * Inner-product stage of the key switch of one polynomial d (evaluation form,
+ * [level][N]) with a switching key [beta][2][n_q+k][N]: inverse transform, ModUp
+ * each digit, transform, multiply-accumulate with the key over the extended
+ * basis.  acc: [2][level+k][N], evaluation form, zeroed here.
  */
-void orc_keyswitch(const orc_params *P, const u64 *d_eval, const u64 *key, int level, u64 *ks) {
+static void ks_accumulate(const orc_params *P, const u64 *d_eval, const u64 *key, int level, u64 *acc) {
     u64 N = P->N;
     int E = level + P->k, T = P->n_q + P->k;
     int beta = (level + P->alpha - 1) / P->alpha;
     u64 *dc = (u64 *)malloc((size_t)level * N * 8);
     u64 *dt = (u64 *)malloc((size_t)E * N * 8);
-    u64 *acc = (u64 *)calloc((size_t)2 * E * N, 8);
+    memset(acc, 0, (size_t)2 * E * N * 8);
     memcpy(dc, d_eval, (size_t)level * N * 8);
     for (int i = 0; i < level; i++) orc_intt_limb(P, i, dc + (size_t)i * N);
     for (int j = 0; j < beta; j++) {
@@ -506,6 +535,18 @@ void orc_keyswitch(const orc_params *P, const u64 *d_eval, const u64 *key, int l
             }
         }
     }
+    free(dc); free(dt);
+}
+
+/*
+ * Key switch: the inner-product stage above, then DivRound_P of both
+ * accumulators.  ks: [2][level][N] evaluation form.
+ */
+void orc_keyswitch(const orc_params *P, const u64 *d_eval, const u64 *key, int level, u64 *ks) {
+    u64 N = P->N;
+    int E = level + P->k;
+    u64 *acc = (u64 *)malloc((size_t)2 * E * N * 8);
+    ks_accumulate(P, d_eval, key, level, acc);
     int *cidx = (int *)malloc(sizeof(int) * level), *bidx = (int *)malloc(sizeof(int) * (P->k ? P->k : 1));
     for (int i = 0; i < level; i++) cidx[i] = i;
     for (int m = 0; m < P->k; m++) bidx[m] = P->n_q + m;
@@ -516,7 +557,7 @@ void orc_keyswitch(const orc_params *P, const u64 *d_eval, const u64 *key, int l
         orc_divround_coef(P, ac, cidx, level, bidx, P->k, o);
         for (int i = 0; i < level; i++) orc_ntt_limb(P, i, o + (size_t)i * N);
     }
-    free(cidx); free(bidx); free(dc); free(dt); free(acc);
+    free(cidx); free(bidx); free(acc);
 }
 
 /* relinearise: (d0 + ks0, d1 + ks1), ks = KeySwitch(d2) with the key for s' = s^2 */
@@ -558,6 +599,50 @@ void orc_hmul_relin_rescale(const orc_params *P, const u64 *a, const u64 *b, con
     orc_relin(P, d, rlk, level, r);
     orc_rescale(P, r, level, out);
     free(d); free(r);
+}
+
+/*
+ * The same product with ONE division: the key-switch accumulators stay over the
+ * extended basis, P*(d0, d1) is added there (zero on the special limbs), and both
+ * components are divided by P*q_{level-1} in a single DivRound over
+ * B = {q_{level-1}, p_0 .. p_{k-1}}:
+ *     out_c = DivRound_B(acc_c + P*d_c),   c = 0, 1,
+ * with the exact form of DivRound: the conversion's overshoot u would otherwise
+ * sit at the scale of the output (in the strict sequence the rescale divides it
+ * by q_{level-1}) and, being one-sided, would add up over the coefficients.
+ * The integer divided is the one the strict sequence divides in two steps, so the
+ * two results differ only by the rounding of those steps (one unit per
+ * coefficient); the output bits are NOT those of orc_hmul_relin_rescale.
+ * out: [2][level-1][N] evaluation form.
+ */
+void orc_hmul_relin_rescale_merged(const orc_params *P, const u64 *a, const u64 *b, const u64 *rlk, int level, u64 *out) {
+    u64 N = P->N;
+    int E = level + P->k, nb = P->k + 1;
+    u64 *d = (u64 *)malloc((size_t)3 * level * N * 8);
+    u64 *acc = (u64 *)malloc((size_t)2 * E * N * 8);
+    orc_tensor(P, a, b, level, d);
+    ks_accumulate(P, d + (size_t)2 * level * N, rlk, level, acc);
+    int *cidx = (int *)malloc(sizeof(int) * level), *bidx = (int *)malloc(sizeof(int) * nb);
+    for (int i = 0; i < level - 1; i++) cidx[i] = i;
+    bidx[0] = level - 1;
+    for (int m = 0; m < P->k; m++) bidx[1 + m] = P->n_q + m;
+    for (int c = 0; c < 2; c++) {
+        u64 *ac = acc + (size_t)c * E * N;
+        for (int i = 0; i < level; i++) {
+            u64 q = P->mod[i];
+            u64 Pq = 1;
+            for (int m = 0; m < P->k; m++) Pq = orc_mulmod(Pq, P->mod[P->n_q + m] % q, q);
+            const u64 *dd = d + ((size_t)c * level + i) * N;
+            u64 *x = ac + (size_t)i * N;
+            for (u64 n = 0; n < N; n++) x[n] = orc_addmod(x[n], orc_mulmod(dd[n] % q, Pq, q), q);
+        }
+        /* extended layout [q_0 .. q_{level-1}, p_0 .. p_{k-1}] = kept limbs followed by the limbs of B */
+        for (int x = 0; x < E; x++) orc_intt_limb(P, ext_index(P, level, x), ac + (size_t)x * N);
+        u64 *o = out + (size_t)c * (level - 1) * N;
+        orc_divround_exact_coef(P, ac, cidx, level - 1, bidx, nb, o);
+        for (int i = 0; i < level - 1; i++) orc_ntt_limb(P, i, o + (size_t)i * N);
+    }
+    free(cidx); free(bidx); free(d); free(acc);
 }
 
 /* automorphism X -> X^g on signed coefficients (used for sigma_g(s)) */

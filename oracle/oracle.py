@@ -211,10 +211,12 @@ class Oracle:
             "orc_tensor": [V, u64p, u64p, I, u64p],
             "orc_modup": [V, u64p, I, I, u64p],
             "orc_divround_coef": [V, u64p, intp, I, intp, I, u64p],
+            "orc_divround_exact_coef": [V, u64p, intp, I, intp, I, u64p],
             "orc_keyswitch": [V, u64p, u64p, I, u64p],
             "orc_relin": [V, u64p, u64p, I, u64p],
             "orc_rescale": [V, u64p, I, u64p],
             "orc_hmul_relin_rescale": [V, u64p, u64p, u64p, I, u64p],
+            "orc_hmul_relin_rescale_merged": [V, u64p, u64p, u64p, I, u64p],
             "orc_rotate": [V, u64p, C.c_uint64, u64p, I, u64p],
             "orc_add": [V, u64p, u64p, I, u64p],
             "orc_sub": [V, u64p, u64p, I, u64p],
@@ -337,13 +339,14 @@ class Oracle:
         self._L.orc_modup(self._h, _p64(_u64(d_coef)), level, j, _p64(out))
         return out
 
-    def divround_coef(self, x, cidx, bidx):
+    def divround_coef(self, x, cidx, bidx, exact=False):
         ci = np.ascontiguousarray(cidx, dtype=np.int32)
         bi = np.ascontiguousarray(bidx, dtype=np.int32)
         x = _u64(x)
         assert x.shape == (len(ci) + len(bi), self.N)
         out = np.empty((len(ci), self.N), dtype=np.uint64)
-        self._L.orc_divround_coef(self._h, _p64(x), _pint(ci), len(ci), _pint(bi), len(bi), _p64(out))
+        fn = self._L.orc_divround_exact_coef if exact else self._L.orc_divround_coef
+        fn(self._h, _p64(x), _pint(ci), len(ci), _pint(bi), len(bi), _p64(out))
         return out
 
     def keyswitch(self, d_eval, key, level):
@@ -364,6 +367,12 @@ class Oracle:
     def hmul_relin_rescale(self, a, b, rlk, level):
         out = np.empty((2, level - 1, self.N), dtype=np.uint64)
         self._L.orc_hmul_relin_rescale(self._h, _p64(_u64(a)), _p64(_u64(b)), _p64(_u64(rlk)), level, _p64(out))
+        return out
+
+    def hmul_relin_rescale_merged(self, a, b, rlk, level):
+        """The product with one division by P*q_{level-1} (different output bits, same message)."""
+        out = np.empty((2, level - 1, self.N), dtype=np.uint64)
+        self._L.orc_hmul_relin_rescale_merged(self._h, _p64(_u64(a)), _p64(_u64(b)), _p64(_u64(rlk)), level, _p64(out))
         return out
 
     def automorphism_coef(self, a, g, t):

@@ -405,6 +405,107 @@ def test_hmul_at_scale_2e40_within_1e3():
     assert np.max(np.abs(got - za * zb)) < 1e-5  # expected size of the error at this N
 
 
+def test_divround_mixed_dropped_set():
+    """DivRound over B = {last q, every special prime}: floor((x + h)/B) - u with 0 <= u <= |B|-1, from Python integers."""
+    O = _small_oracle(alpha=2, k=2, n_q=4)
+    cidx, bidx = [0, 1, 2], [3, O.n_q, O.n_q + 1]
+    mods = [O.moduli[i] for i in cidx + bidx]
+    B = math.prod(O.moduli[i] for i in bidx)
+    x = wl.uniform_limbs(mods, O.N, 9, 33, 3)
+    xint = orc.crt_reconstruct(x, mods, centered=False)
+    out = O.divround_coef(x, cidx, bidx)
+    out_exact = O.divround_coef(x, cidx, bidx, exact=True)
+    us = set()
+    for n in range(O.N):
+        exact = (xint[n] + B // 2) // B
+        u = [u for u in range(len(bidx)) if all(int(out[i][n]) == (exact - u) % O.moduli[c] for i, c in enumerate(cidx))]
+        assert u
+        us.add(u[0])
+        assert all(int(out_exact[i][n]) == exact % O.moduli[c] for i, c in enumerate(cidx))
+    assert len(us) > 1  # the plain form does overshoot on this input, the exact form never
+
+
+@pytest.mark.parametrize("nb,bits", [(2, 20), (3, 20), (4, 20), (2, 50), (4, 50)])
+def test_divround_exact_is_round_to_nearest(nb, bits):
+    """the exact form of DivRound returns floor((x + h)/B) itself, |x/B - out| <= 1/2, for any number of dropped primes"""
+    O = orc.Oracle(5, 3, bits, nb, bits + 1, nb)
+    cidx, bidx = [0, 1, 2], [O.n_q + m for m in range(nb)]
+    mods = [O.moduli[i] for i in cidx + bidx]
+    B = math.prod(O.moduli[i] for i in bidx)
+    x = wl.uniform_limbs(mods, O.N, 10, nb, bits)
+    xint = orc.crt_reconstruct(x, mods, centered=False)
+    out = O.divround_coef(x, cidx, bidx, exact=True)
+    QC = math.prod(O.moduli[i] for i in cidx)
+    got = orc.crt_reconstruct(out, [O.moduli[c] for c in cidx], centered=False)
+    for n in range(O.N):
+        exact = (xint[n] + B // 2) // B
+        assert got[n] == exact % QC and abs(xint[n] - exact * B) <= B // 2
+
+
+def _coef_centered(O, ct, level):
+    """[2][level][N] evaluation form -> two lists of centered Python integers"""
+    idx = list(range(level))
+    return [orc.crt_reconstruct(O.intt_limbs(ct[c], idx), [O.q[i] for i in idx]) for c in range(2)]
+
+
+@pytest.mark.parametrize("alpha,k,n_q,level", [(1, 1, 3, 3), (2, 2, 5, 5), (2, 2, 5, 4), (3, 3, 7, 5)])
+def test_merged_division_with_zero_key_is_division_of_P_times_d(alpha, k, n_q, level):
+    """With an all-zero switching key the accumulators vanish and the merged result is DivRound_{q_last, P}(P*d_c):
+    floor((P*D + h)/(P*q_last)) exactly, with D the integer d_c in [0, Q_level) (Python integers)."""
+    O = _small_oracle(alpha, k, n_q)
+    a = np.stack([wl.uniform_limbs(O.q[:level], O.N, 40, c, level) for c in range(2)])
+    b = np.stack([wl.uniform_limbs(O.q[:level], O.N, 41, c, level) for c in range(2)])
+    zero_key = np.zeros((O.beta_top, 2, O.n_q + O.k, O.N), dtype=np.uint64)
+    out = O.hmul_relin_rescale_merged(a, b, zero_key, level)
+    d = O.tensor(a, b, level)
+    idx = list(range(level))
+    P = math.prod(O.p)
+    B = P * O.q[level - 1]
+    Qout = math.prod(O.q[: level - 1])
+    for c in range(2):
+        D = orc.crt_reconstruct(O.intt_limbs(d[c], idx), [O.q[i] for i in idx], centered=False)
+        got = orc.crt_reconstruct(O.intt_limbs(out[c], idx[:-1]), [O.q[i] for i in idx[:-1]], centered=False)
+        for n in range(O.N):
+            exact = (P * D[n] + B // 2) // B
+            assert got[n] == exact % Qout
+
+
+@pytest.mark.parametrize("alpha,k,n_q,level", [(1, 1, 3, 3), (2, 2, 5, 5), (2, 2, 5, 4), (3, 3, 7, 6)])
+def test_merged_division_differs_from_two_divisions_by_rounding_only(alpha, k, n_q, level):
+    """round(round(acc/P + d)/q) against one division of acc + P*d by P*q: the two rounding rules differ by at most
+    one unit per coefficient, and a wrong factor, basis or term would differ by about a whole modulus."""
+    M = Material(5, n_q, 20, k, 21, alpha, seed=42)
+    O = M.O
+    a = np.stack([wl.uniform_limbs(O.q[:level], O.N, 42, c, level) for c in range(2)])
+    b = np.stack([wl.uniform_limbs(O.q[:level], O.N, 43, c, level) for c in range(2)])
+    strict = _coef_centered(O, O.hmul_relin_rescale(a, b, M.rlk, level), level - 1)
+    merged = _coef_centered(O, O.hmul_relin_rescale_merged(a, b, M.rlk, level), level - 1)
+    Qout = math.prod(O.q[: level - 1])
+    worst = 0
+    for c in range(2):
+        for n in range(O.N):
+            diff = (merged[c][n] - strict[c][n]) % Qout
+            diff = diff - Qout if diff > Qout // 2 else diff
+            worst = max(worst, abs(diff))
+    assert worst <= 1
+
+
+def test_merged_division_decrypts_to_product():
+    M = Material(11, 4, 50, 1, 51, 1, seed=17)
+    scale = 2.0**40
+    za, zb = wl.slots_real(M.N // 2, 17, "a"), wl.slots_real(M.N // 2, 17, "b")
+    a, b = M.encrypt(za, scale, 4, "a"), M.encrypt(zb, scale, 4, "b")
+    got = M.decrypt(M.O.hmul_relin_rescale_merged(a, b, M.rlk, 4), scale * scale / M.O.q[3], 3)
+    assert np.max(np.abs(got - za * zb)) < 1e-5
+    M = Material(8, 6, 50, 3, 51, 3, seed=18)
+    scale = 2.0**50
+    za, zb = wl.slots_real(M.N // 2, 18, "a"), wl.slots_real(M.N // 2, 18, "b")
+    for level in (6, 5, 4):
+        a, b = M.encrypt(za, scale, level, "a"), M.encrypt(zb, scale, level, "b")
+        got = M.decrypt(M.O.hmul_relin_rescale_merged(a, b, M.rlk, level), scale * scale / M.O.q[level - 1], level - 1)
+        assert np.max(np.abs(got - za * zb)) < 1e-6
+
+
 def test_hybrid_keyswitch_alpha3_end_to_end():
     M = Material(8, 6, 50, 3, 51, 3, seed=18, rotations=(3,))
     scale = 2.0**50
