@@ -135,6 +135,14 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
                               "what": "square then degree-3 polynomial, 3 HMult+relin+rescale + 2 scalar rescales per ciphertext, level 24 -> 21"}
     del y, o3, wsa
 
+    # the same product with one division by P*q_last instead of ModDown followed by rescale (different output bits:
+    # a separate operation, not the headline one)
+    om = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: ctx.hmul_relin_rescale_merged(a, a, evk, om, L, B, ws), 5)
+    out["merged_division_2e16"] = {"ops_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 3),
+                                   "what": "HMult + key switch + ONE exact division by P*q_last, batch 64, level 24 -> 23"}
+    del om
+
     # N = 2^14, 8x50-bit + special prime: batch 256, HMult+relin+rescale and rotations by 8 random offsets
     p2 = wl.PRESETS["hmul_rot_2e14"]
     c2 = ckksmi.Context(p2.logN, p2.n_q, p2.q_bits, p2.k, p2.special_bits, p2.alpha, device=0)

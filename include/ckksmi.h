@@ -158,6 +158,17 @@ int ckksmi_relin(ckksmi_ctx *ctx, const uint64_t *d, const uint64_t *evk, uint64
 int ckksmi_rescale(ckksmi_ctx *ctx, const uint64_t *a, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* the strict sequence hmul -> relin -> rescale, bit-identical to the three calls */
 int ckksmi_hmul_relin_rescale(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out /*[2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* The same product with ONE division instead of ModDown followed by rescale (a fewer-transform variant of the
+ * multiplication of section 2.1; the paper fixes no order): the key-switch accumulators stay over the extended basis,
+ * P*(d0, d1) joins them there, and both components are divided by P*q_{level-1} at once,
+ *     out_c = DivRound_B(acc_c + P*d_c),  B = {q_{level-1}, p_0 .. p_{k-1}},
+ * in the exact form of DivRound: the overshoot of the basis conversion, v = floor(sum_m y_m * (1/b_m)) evaluated in
+ * double precision in the order of B (products and sums each rounded to nearest), is removed, so every coefficient is
+ * floor((x + h)/(P*q_{level-1})) itself.  The result encrypts the same product at the same scale and level as
+ * ckksmi_hmul_relin_rescale but differs from it by up to one unit per coefficient: the two are NOT bit-identical.
+ * Arguments, layouts, workspace (CKKSMI_OP_HMUL_RELIN_RESCALE) and errors as ckksmi_hmul_relin_rescale; additionally
+ * CKKSMI_EUNSUPPORTED when the context has more than 3 special primes. */
+int ckksmi_hmul_relin_rescale_merged(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out /*[2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* left rotation of item i by rot[i] slots (host array; each needs a registered
  * key): automorphism X -> X^g first, then key switch of the second component */
 int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [batch]*/, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
@@ -222,7 +233,9 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_MACPREP_MFMA 19  /* its weight digits and tap table */
 #define CKKSMI_K_ROWS_FINAL2 20   /* ModDown's and rescale's last steps in one contiguous pass */
 #define CKKSMI_K_TENSOR_ROWS 21   /* tensor product fused with the inverse contiguous pass of its third component */
-#define CKKSMI_K_COUNT 22
+#define CKKSMI_K_AXPY_LIMB 22     /* one limb of every row += constant * another limb (merged division: P*d on the dropped q) */
+#define CKKSMI_K_CONV_COLS_MERGED 23 /* the conversion kernel in the exact form of DivRound, sources {q_last, special primes} */
+#define CKKSMI_K_COUNT 24
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

@@ -70,6 +70,7 @@ SIGNATURES = {
     "ckksmi_relin": [VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rescale": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rotate": [VP, VP, intp, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_mac": [VP, VP, VP] + [C.c_int] * 8 + [VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
@@ -82,7 +83,7 @@ SIGNATURES = {
     "ckksmi_kernel_class_name": [VP, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
-K_COUNT = 22
+K_COUNT = 24
 
 _LIBS = {}
 
@@ -311,6 +312,10 @@ class Context:
 
     def hmul_relin_rescale(self, a, b, evk, out, level, batch, ws, stream=None):
         self._call("ckksmi_hmul_relin_rescale", self._h, _ptr(a), _ptr(b), _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
+                   self._stream(stream))
+
+    def hmul_relin_rescale_merged(self, a, b, evk, out, level, batch, ws, stream=None):
+        self._call("ckksmi_hmul_relin_rescale_merged", self._h, _ptr(a), _ptr(b), _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
                    self._stream(stream))
 
     def rotate(self, a, rot, out, level, batch, ws, stream=None):

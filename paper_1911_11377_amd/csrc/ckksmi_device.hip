@@ -187,7 +187,8 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
     A.items_per_z = c->conv_items_per_wg < (int)items ? c->conv_items_per_wg : (int)items;
     const unsigned z = (unsigned)((items + A.items_per_z - 1) / A.items_per_z);
     const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count, mode): registers sized for it
-    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
+    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP
+                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
     const dim3 grid(tiles, slots, z), block(V2_THREADS);
 #define CONV_COLS_CASE(Q, NS)                                                                                \
     case (Q) * 8 + (NS):                                                                                     \
@@ -219,7 +220,7 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     A.tw_inv = c->d_tww_inv; A.fin = fin;
     if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
-    const int n_targets = mode == 0 ? A.E : nc;
+    const int n_targets = mode == 0 ? A.E : nc;  // mode 2: mode 1 in the exact form of DivRound (needs fin)
     const size_t ygrid = mode == 0 ? items * A.beta : items;
     // enough workgroups to fill the chip (8 per CU), otherwise as many targets per workgroup as possible: the source
     // tiles are read and converted once per workgroup (measured: 24 targets 0.65 ms, 6 targets 0.75 ms for ModDown)
@@ -231,11 +232,13 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     const unsigned z = (unsigned)((n_targets + A.targets_per_wg - 1) / A.targets_per_wg);
     const dim3 grid(tiles, (unsigned)ygrid, z), block(V2_THREADS);
     const int nsrc = mode == 0 ? c->alpha : D->nb;
-    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
+    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP
+                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
 #define MODUP_COLS_CASE(Q, NS)                                                                               \
     case (Q) * 8 + (NS):                                                                                     \
         if (mode == 0 && fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, true>), grid, block, st, A);    \
         else if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, false>), grid, block, st, A);     \
+        else if (mode == 2) KL(c, kid, units, (modup_cols_kernel<Q, NS, 2, true>), grid, block, st, A);      \
         else if (fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, true>), grid, block, st, A);            \
         else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, false>), grid, block, st, A);                    \
         break;
@@ -253,8 +256,9 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
 // out + row*out_row_stride + (limb - limb0)*N
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
                        size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st, int limb0 = 0,
-                       int limb_count = -1, size_t out_row_stride = 0) {
+                       int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr) {
     RowsFinalArgs A;
+    A.pre = pre;
     const int nz = limb_count < 0 ? nc : limb_count;
     A.limb0 = limb_count < 0 ? 0 : limb0;
     A.out_limb0 = A.limb0;
@@ -322,7 +326,7 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
     } else {
         DivConvArgs DC;
         DC.b_limbs = (const u64d *)b_scratch; DC.b_row_stride = bs_stride; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
-        DC.logN = c->logN; DC.nc = nc; DC.T = c->T;
+        DC.logN = c->logN; DC.nc = nc; DC.T = c->T; DC.exact = 0;
         KL(c, CKKSMI_K_DIVCONV, (double)rows * nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
         launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 1);
     }
@@ -333,7 +337,49 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
         DivFinalArgs DF;
         DF.x = (const u64d *)x; DF.x_row_stride = x_stride; DF.tmp = (const u64d *)tmp;
         DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride; DF.add_both = add_both;
-        DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.logN = c->logN; DF.nc = nc;
+        DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.pre = nullptr; DF.logN = c->logN; DF.nc = nc;
+        KL(c, CKKSMI_K_DIVFINAL, (double)rows * nc, divround_final_kernel, dim3(ew_blocks(N), nc, rows), dim3(EW_THREADS), st, DF);
+    }
+}
+
+// The product's division in one step: acc [items][2][E][N] holds the key-switch accumulators over the extended basis
+// (evaluation form) and d0, d1 (the addend) join them multiplied by P before the division by P*q_{level-1}:
+//     out[items][2][level-1][N] = DivRound_B(acc + P*d),  B = {q_{level-1}, p_0 .. p_{k-1}},  exact form.
+// The limbs of B are contiguous in the extended layout (limbs level-1 .. E-1); they are overwritten.
+void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item_stride, size_t add_comp_stride, u64 *out, u64 *tmp, int items,
+                     int level, hipStream_t st) {
+    const size_t N = c->N;
+    const int E = level + c->k, rows = items * 2, nc = level - 1;
+    const DivRoundDev &D = c->divround_merged[level];
+    u64 *bl = acc + (size_t)(level - 1) * N;
+    // only the dropped limb q_{level-1} needs acc + P*d up front; the kept limbs receive P*d in the last step
+    KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
+       (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)(level - 1) * N), (unsigned long long)add_item_stride,
+       (unsigned long long)add_comp_stride, c->h_modc[level - 1], c->h_pmod[level - 1], c->logN);
+    const bool fast = c->fused && (c->fuse & FUSE_DIVCONV) && c->modup_loop && c->fuse_inv;
+    const bool ffinal = c->fused && (c->fuse & FUSE_FINAL);
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < nc; i++) idx[i] = i;
+    if (fast) {
+        const FinConst *fin = c->d_fin_merged + (size_t)level * CKKSMI_MAX_SPECIAL;
+        launch_ntt(c, false, bl, bl, table_map(D.b_idx, D.nb, (size_t)E * N, (size_t)E * N), rows, st, fin, 2);
+        launch_modup_cols(c, 2, bl, (size_t)E * N, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
+    } else {
+        launch_ntt(c, false, bl, bl, table_map(D.b_idx, D.nb, (size_t)E * N, (size_t)E * N), rows, st);
+        DivConvArgs DC;
+        DC.b_limbs = (const u64d *)bl; DC.b_row_stride = (size_t)E * N; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
+        DC.logN = c->logN; DC.nc = nc; DC.T = c->T; DC.exact = 1;
+        KL(c, CKKSMI_K_DIVCONV, (double)rows * nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
+        launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, ffinal ? 1 : 3);
+    }
+    if (ffinal) {
+        launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, D.Binv, nc, rows, st, 0, -1, 0, c->d_pmod);
+    } else {
+        if (fast) launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 2);
+        DivFinalArgs DF;
+        DF.x = (const u64d *)acc; DF.x_row_stride = (size_t)E * N; DF.tmp = (const u64d *)tmp;
+        DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride; DF.add_both = 1;
+        DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.pre = c->d_pmod; DF.logN = c->logN; DF.nc = nc;
         KL(c, CKKSMI_K_DIVFINAL, (double)rows * nc, divround_final_kernel, dim3(ew_blocks(N), nc, rows), dim3(EW_THREADS), st, DF);
     }
 }
@@ -342,7 +388,7 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
 // ciphertexts [items][2][level-1][N]; tail_scratch holds 2*level*N words per item.  Needs both DivRound fusions.
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
-                   u64 *tail_scratch = nullptr, bool ymid_ready = false) {
+                   u64 *tail_scratch = nullptr, bool ymid_ready = false, bool merged = false) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     u64 *ycoef = ws;
@@ -396,6 +442,10 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
         KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
     }
+    if (merged) {
+        merged_division(c, acc, addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
+        return;
+    }
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
     if (tail_scratch) {
@@ -434,9 +484,10 @@ void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int le
 // Key switch of `items` polynomials.  d_eval: item i's polynomial ([level][N], evaluation
 // form) at d_eval + i*d_stride.  out[i][c][l] = ks_c (+ addend).  ws: ks_words_per_item*items.
 void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
-             size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st) {
+             size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st, bool merged = false) {
     if (c->fused) {
-        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st);
+        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st, nullptr, false,
+                      merged);
         return;
     }
     const size_t N = c->N;
@@ -473,6 +524,10 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     IA.items = items;
     const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
     KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
+    if (merged) {
+        merged_division(c, acc, addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
+        return;
+    }
     // 5. ModDown: special limbs -> coefficient form, convert, back to evaluation form, combine
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
@@ -484,7 +539,7 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     DC.tmp = (u64d *)tmp;
     DC.modc = c->d_mod;
     DC.D = c->divround[0];
-    DC.logN = c->logN; DC.nc = level; DC.T = c->T;
+    DC.logN = c->logN; DC.nc = level; DC.T = c->T; DC.exact = 0;
     KL(c, CKKSMI_K_DIVCONV, (double)items * 2 * DC.nc, divround_conv_kernel, dim3(ew_blocks(N), items * 2), dim3(EW_THREADS), st, DC);
     launch_ntt(c, true, tmp, tmp, table_map(idx, level, (size_t)level * N, (size_t)level * N), (size_t)items * 2, st);
     DivFinalArgs DF;
@@ -493,7 +548,7 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride;
     DF.add_both = add_both;
     DF.out = (u64d *)out;
-    DF.modc = c->d_mod; DF.Binv = c->divround[0].Binv;
+    DF.modc = c->d_mod; DF.Binv = c->divround[0].Binv; DF.pre = nullptr;
     DF.logN = c->logN; DF.nc = level;
     KL(c, CKKSMI_K_DIVFINAL, (double)items * 2 * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level, items * 2), dim3(EW_THREADS), st, DF);
 }
@@ -513,7 +568,7 @@ void rescale_core(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u
     DC.b_limbs = (const u64d *)last; DC.b_row_stride = N;
     DC.tmp = (u64d *)tmp; DC.modc = c->d_mod;
     DC.D = c->divround[1 + (level - 1)];
-    DC.logN = c->logN; DC.nc = level - 1; DC.T = c->T;
+    DC.logN = c->logN; DC.nc = level - 1; DC.T = c->T; DC.exact = 0;
     KL(c, CKKSMI_K_DIVCONV, (double)items * 2 * DC.nc, divround_conv_kernel, dim3(ew_blocks(N), items * 2), dim3(EW_THREADS), st, DC);
     int idx[CKKSMI_MAX_MODULI];
     for (int i = 0; i < level - 1; i++) idx[i] = i;
@@ -523,7 +578,7 @@ void rescale_core(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u
     DF.tmp = (const u64d *)tmp;
     DF.addend = nullptr; DF.add_item_stride = DF.add_comp_stride = 0; DF.add_both = 0;
     DF.out = (u64d *)out;
-    DF.modc = c->d_mod; DF.Binv = c->divround[1 + (level - 1)].Binv;
+    DF.modc = c->d_mod; DF.Binv = c->divround[1 + (level - 1)].Binv; DF.pre = nullptr;
     DF.logN = c->logN; DF.nc = level - 1;
     KL(c, CKKSMI_K_DIVFINAL, (double)items * 2 * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level - 1, items * 2), dim3(EW_THREADS), st, DF);
 }
@@ -615,6 +670,21 @@ int dev_upload_tables(ckksmi_ctx *c) {
         c->d_modup_c = upload(c, mc.data(), mc.size(), ok);
     }
     // DivRound tables: 0 = ModDown over the special primes, 1+i = rescale dropping q_i
+    auto upload_divround = [&](const std::vector<int> &b) {
+        DivRoundHost h = make_divround(c, b);
+        DivRoundDev d;
+        memset(&d, 0, sizeof(d));
+        d.nb = h.nb;
+        for (int m = 0; m < h.nb; m++) {
+            d.b_idx[m] = h.b_idx[m]; d.hb[m] = h.hb[m]; d.invb[m] = h.invb[m];
+            d.invb_f[m] = 1.0 / (double)c->mod[h.b_idx[m]];
+        }
+        d.conv = upload(c, h.conv.data(), h.conv.size(), ok);
+        d.hc = upload(c, h.hc.data(), h.hc.size(), ok);
+        d.Binv = upload(c, h.Binv.data(), h.Binv.size(), ok);
+        d.Bmod = upload(c, h.Bmod.data(), h.Bmod.size(), ok);
+        return d;
+    };
     c->divround.assign(1 + c->n_q, DivRoundDev());
     for (int which = 0; which <= c->n_q; which++) {
         std::vector<int> b;
@@ -624,15 +694,23 @@ int dev_upload_tables(ckksmi_ctx *c) {
         } else {
             b.push_back(which - 1);
         }
-        DivRoundHost h = make_divround(c, b);
-        DivRoundDev d;
-        memset(&d, 0, sizeof(d));
-        d.nb = h.nb;
-        for (int m = 0; m < h.nb; m++) { d.b_idx[m] = h.b_idx[m]; d.hb[m] = h.hb[m]; d.invb[m] = h.invb[m]; }
-        d.conv = upload(c, h.conv.data(), h.conv.size(), ok);
-        d.hc = upload(c, h.hc.data(), h.hc.size(), ok);
-        d.Binv = upload(c, h.Binv.data(), h.Binv.size(), ok);
-        c->divround[which] = d;
+        c->divround[which] = upload_divround(b);
+    }
+    // merged division of the product (ModDown and rescale at once): level l drops {q_{l-1}, p_0 .. p_{k-1}}
+    c->divround_merged.assign(1 + c->n_q, DivRoundDev());
+    c->h_pmod.assign(T, WMul{0.0, 0.0});
+    if (c->k > 0 && c->k + 1 <= CKKSMI_MAX_SPECIAL) {
+        for (int level = 2; level <= c->n_q; level++) {
+            std::vector<int> b(1, level - 1);
+            for (int m = 0; m < c->k; m++) b.push_back(c->n_q + m);
+            c->divround_merged[level] = upload_divround(b);
+        }
+        for (int i = 0; i < c->n_q; i++) {
+            u64 P = 1;
+            for (int m = 0; m < c->k; m++) P = hm::mulmod(P, c->mod[c->n_q + m] % c->mod[i], c->mod[i]);
+            c->h_pmod[i] = make_wmul(P, c->mod[i]);
+        }
+        c->d_pmod = upload(c, c->h_pmod.data(), c->h_pmod.size(), ok);
     }
     // fused path: constants folded into the last stage of the inverse transforms
     c->fused = c->logN >= 13 && c->logN <= 16 && !getenv("CKKSMI_NO_FUSION");
@@ -673,6 +751,22 @@ int dev_upload_tables(ckksmi_ctx *c) {
         std::vector<FinConst> fr;
         for (int i = 0; i < c->n_q; i++) fr.push_back(fin(i, 1, (c->mod[i] - 1) / 2));
         c->d_fin_rescale = upload(c, fr.data(), fr.size(), ok);
+        if (c->d_pmod) {
+            std::vector<FinConst> fg((size_t)(c->n_q + 1) * CKKSMI_MAX_SPECIAL, fin(0, 1, 0));
+            for (int level = 2; level <= c->n_q; level++) {
+                const DivRoundDev &D = c->divround_merged[level];
+                for (int m = 0; m < D.nb; m++) {
+                    const int t = D.b_idx[m];
+                    const u64 bm = c->mod[t];
+                    u64 bhat = 1;
+                    for (int m2 = 0; m2 < D.nb; m2++)
+                        if (m2 != m) bhat = hm::mulmod(bhat, c->mod[D.b_idx[m2]] % bm, bm);
+                    const u64 inv = hm::invmod(bhat, bm);
+                    fg[(size_t)level * CKKSMI_MAX_SPECIAL + m] = fin(t, inv, hm::mulmod((bm - 1) / 2, inv, bm));
+                }
+            }
+            c->d_fin_merged = upload(c, fg.data(), fg.size(), ok);
+        }
     }
     if (!ok) { c->last_hip_error = (int)hipGetLastError(); return CKKSMI_EDEVICE; }
     return CKKSMI_OK;
@@ -870,11 +964,11 @@ extern "C" int ckksmi_rescale(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, i
     return g.rc();
 }
 
-extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level,
-                                         int batch, void *ws, size_t ws_bytes, void *stream) {
+static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level, int batch,
+                                  void *ws, size_t ws_bytes, void *stream, bool merged) {
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
-    if (c->k == 0) return CKKSMI_EUNSUPPORTED;
+    if (c->k == 0 || (merged && !c->d_pmod)) return CKKSMI_EUNSUPPORTED;
     if (level < 2) return CKKSMI_ELEVEL;
     if (!a || !b || !evk || !out || (!ws && batch) || !al16(a) || !al16(b) || !al16(evk) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
@@ -899,6 +993,16 @@ extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const
             launch_tensor_rows(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, rest, level, items, S(stream));
         else
             launch_tensor(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, level, items, S(stream));
+        if (merged) {
+            // one division by P*q_{level-1} of (accumulators + P*(d0, d1))
+            if (c->fused)
+                ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
+                              out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), nullptr, trows, true);
+            else
+                ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
+                        out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), true);
+            continue;
+        }
         if (tail) {
             // ModDown + add + rescale with a shared last pass: r is only scratch
             ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
@@ -916,6 +1020,16 @@ extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const
         rescale_core(c, r, out + (size_t)b0 * 2 * (level - 1) * N, items, level, rest, S(stream));
     }
     return g.rc();
+}
+
+extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level,
+                                         int batch, void *ws, size_t ws_bytes, void *stream) {
+    return hmul_relin_rescale_impl(c, a, b, evk, out, level, batch, ws, ws_bytes, stream, false);
+}
+
+extern "C" int ckksmi_hmul_relin_rescale_merged(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level,
+                                                int batch, void *ws, size_t ws_bytes, void *stream) {
+    return hmul_relin_rescale_impl(c, a, b, evk, out, level, batch, ws, ws_bytes, stream, true);
 }
 
 extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, uint64_t *out, int level, int batch, void *ws,
@@ -1117,7 +1231,8 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
-                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel"};
+                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel",
+                                                "axpy_limb_kernel", "modup_cols_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && c->logN >= 13 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
@@ -1131,6 +1246,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
         if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "%s<%d, %d, 0%s", kn, q, c->alpha, tail); return buf; }
         if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "%s<%d, %d, 1%s", kn, q, c->k, tail); return buf; }
         if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "%s<%d, 1, 1%s", kn, q, tail); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_MERGED) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 2, true>", q, c->k + 1); return buf; }
     }
     return names[kernel_class];
 }

@@ -47,6 +47,7 @@ struct DivRoundHost {
     std::vector<WMul> conv;     // [nb][T]   (Bbar/b_m) mod c
     std::vector<double> hc;     // [T]       floor(Bbar/2) mod c
     std::vector<WMul> Binv;     // [T]       Bbar^-1 mod c
+    std::vector<double> Bmod;   // [T]       Bbar mod c
 };
 
 struct DivRoundDev {
@@ -57,6 +58,9 @@ struct DivRoundDev {
     const WMul *conv;  // device [nb][T]
     const double *hc;  // device [T]
     const WMul *Binv;  // device [T]
+    // exact form (conversion overshoot removed): 1/b_m as a double, Bbar mod c
+    double invb_f[CKKSMI_MAX_SPECIAL];
+    const double *Bmod;  // device [T]
 };
 
 // Last-stage constants of an inverse transform that also multiplies by a constant c and adds a
@@ -111,6 +115,10 @@ struct ckksmi_ctx {
     FinConst *d_fin_modup = nullptr;    // [n_q + 1][n_q]  level, limb
     FinConst *d_fin_moddown = nullptr;  // [k]
     FinConst *d_fin_rescale = nullptr;  // [n_q]  dropped limb
+    FinConst *d_fin_merged = nullptr;   // [n_q + 1][CKKSMI_MAX_SPECIAL]  level, member of {q_{level-1}, p_0 ..}
+    std::vector<DivRoundDev> divround_merged;  // [n_q + 1] by level; nb == 0 where unavailable
+    std::vector<WMul> h_pmod;           // [T] P mod q_i (zero for the special primes)
+    WMul *d_pmod = nullptr;             // device copy; nullptr: merged division unavailable (k = 0 or k + 1 > CKKSMI_MAX_SPECIAL)
     P51Mask p51mask = {{0, 0}};
     bool fused = false;  // N = 2^16: register-tiled passes for everything, steps below optionally fused into them
     int fuse = 15;       // bit 0 ModUp, 1 inner product, 2 DivRound conversion, 3 DivRound final step

@@ -152,6 +152,7 @@ DivRoundHost make_divround(const ckksmi_ctx *c, const std::vector<int> &bidx) {
     d.conv.assign((size_t)d.nb * T, WMul{0, 0});
     d.hc.assign(T, 0.0);
     d.Binv.assign(T, WMul{0, 0});
+    d.Bmod.assign(T, 0.0);
     for (int m = 0; m < d.nb; m++) {
         d.b_idx[m] = bidx[m];
         const u64 bm = c->mod[bidx[m]];
@@ -170,6 +171,7 @@ DivRoundHost make_divround(const ckksmi_ctx *c, const std::vector<int> &bidx) {
         for (int m = 0; m < d.nb; m++) B = hm::mulmod(B, c->mod[bidx[m]] % q, q);
         d.hc[t] = (double)hm::mulmod(hm::submod(B, 1, q), hm::invmod(2, q), q);
         d.Binv[t] = make_wmul(hm::invmod(B, q), q);
+        d.Bmod[t] = (double)B;
         for (int m = 0; m < d.nb; m++) {
             u64 bhat = 1;
             for (int m2 = 0; m2 < d.nb; m2++)

@@ -487,6 +487,7 @@ struct DivConvArgs {
     const ModConst *modc;
     DivRoundDev D;
     int logN, nc, T;      // kept limbs are modulus indices 0 .. nc-1
+    int exact;            // 1: the conversion's overshoot v = floor(sum_m y_m * (1/b_m)) (doubles, in this order) is removed
 };
 
 __global__ __launch_bounds__(EW_THREADS) void divround_conv_kernel(DivConvArgs A) {
@@ -501,9 +502,16 @@ __global__ __launch_bounds__(EW_THREADS) void divround_conv_kernel(DivConvArgs A
         x = x >= mc.p ? x - mc.p : x;
         y[m] = canon(mulmod_w(x, A.D.invb[m].w, A.D.invb[m].wp, mc.p), mc.p, mc.pinv);
     }
+    double v = 0.0;
+    if (A.exact) {
+        double sum = y[0] * A.D.invb_f[0];
+        for (int m = 1; m < A.D.nb; m++) sum = sum + y[m] * A.D.invb_f[m];
+        v = floor(sum);
+    }
     for (int i = 0; i < A.nc; i++) {
         const ModConst mc = A.modc[i];
         double acc = -A.D.hc[i];
+        if (A.exact) acc = -reduce_balanced(A.D.hc[i] + v * A.D.Bmod[i], mc.p, mc.pinv);  // v <= nb - 1: exact product
         for (int m = 0; m < A.D.nb; m++) {
             const WMul W = A.D.conv[(size_t)m * A.T + i];
             acc += mulmod_w(y[m], W.w, W.wp, mc.p);
@@ -522,6 +530,7 @@ struct DivFinalArgs {
     u64d *out;           // [rows][nc][N]
     const ModConst *modc;
     const WMul *Binv;    // [T]
+    const WMul *pre;     // optional [T]: the addend enters BEFORE the division, out = (x + pre_i*addend - r) * Binv
     int logN, nc;
 };
 
@@ -534,12 +543,34 @@ __global__ __launch_bounds__(EW_THREADS) void divround_final_kernel(DivFinalArgs
     const WMul W = A.Binv[i];
     double x = u2d(A.x[(size_t)row * A.x_row_stride + (size_t)i * N + n]);
     double r = u2d(A.tmp[((size_t)row * A.nc + i) * N + n]);
+    if (A.pre) {
+        const WMul Pm = A.pre[i];
+        const double ad = u2d(A.addend[(size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + n]);
+        x += mulmod_w(ad, Pm.w, Pm.wp, mc.p);
+    }
     double v = canon(mulmod_w(x - r, W.w, W.wp, mc.p), mc.p, mc.pinv);
-    if (A.addend && (A.add_both || (row & 1u) == 0)) {
+    if (!A.pre && A.addend && (A.add_both || (row & 1u) == 0)) {
         v += u2d(A.addend[(size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + n]);
         v = v >= mc.p ? v - mc.p : v;
     }
     A.out[((size_t)row * A.nc + i) * N + n] = d2u(v);
+}
+
+// x[row][n] = (x[row][n] + w * a[row][n]) mod p on one limb of every row: row r of x at x + r*x_row_stride, of a at
+// a + (r/2)*a_item_stride + (r%2)*a_comp_stride.  Two words per thread.
+__global__ __launch_bounds__(EW_THREADS) void axpy_limb_kernel(u64d *x, unsigned long long x_row_stride, const u64d *a,
+                                                               unsigned long long a_item_stride, unsigned long long a_comp_stride, ModConst mc,
+                                                               WMul w, int logN) {
+    const unsigned pairs = 1u << (logN - 1);
+    const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (n >= pairs) return;
+    const unsigned row = blockIdx.y;
+    ulonglong2 *xp = (ulonglong2 *)(x + (size_t)row * x_row_stride) + n;
+    const ulonglong2 av = ((const ulonglong2 *)(a + (size_t)(row / 2) * a_item_stride + (size_t)(row % 2) * a_comp_stride))[n];
+    ulonglong2 xv = *xp;
+    xv.x = d2u(canon(u2d(xv.x) + mulmod_w(u2d(av.x), w.w, w.wp, mc.p), mc.p, mc.pinv));
+    xv.y = d2u(canon(u2d(xv.y) + mulmod_w(u2d(av.y), w.w, w.wp, mc.p), mc.p, mc.pinv));
+    *xp = xv;
 }
 
 // out[row][i] = a[row][i] + b[row][i] for rows of `level` limbs where only component 0

@@ -232,7 +232,9 @@ __global__ __launch_bounds__(V2_THREADS, 3) void conv_cols_kernel(ConvColsArgs A
 // twiddles of its modulus go through LDS (one coalesced 2 KB read per workgroup, fetched one target ahead).
 // MODE 0 (ModUp): grid y = item * beta + digit, sources = the digit's limbs of y, targets = the other limbs of the
 // extended basis.  MODE 1 (DivRound conversion, ModDown or rescale): grid y = row, sources = the D.nb dropped limbs
-// (row r at y + r*y_row_stride), targets = the nc kept limbs, h subtracted.
+// (row r at y + r*y_row_stride), targets = the nc kept limbs, h subtracted.  MODE 2: MODE 1 in the exact form of DivRound:
+// the overshoot v = floor(sum_m y_m * (1/b_m)) of every coefficient (double precision, products and sums in source
+// order, each rounded) is found once from the sources and v * (Bbar mod c) leaves every target.
 struct ModupColsArgs {
     const u64d *y;                // MODE 0: [items][level][N] conversion inputs y_i, coefficient form, canonical
     unsigned long long y_row_stride;  // MODE 1
@@ -289,15 +291,18 @@ __device__ __forceinline__ void inv_cols_in_regs(double (&x)[16], const double *
     for (int e = 0; e < 16; e++) x[e] = canon(x[e] + F.cadd, p, pinv);
 }
 
-template <bool P51, int NSRC, int Q>
+// EXACT: vpack holds the overshoot of the thread's 16 coefficients, 3 bits each; Bm = Bbar mod p
+template <bool P51, int NSRC, int Q, bool EXACT>
 __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], const WMul (&Wc)[NSRC], const double *twl, double *lds, u64d *dst,
-                                                  const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store, double hsub) {
+                                                  const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store, double hsub,
+                                                  unsigned long long vpack, double Bm) {
     typedef ColsGeom<Q> Geo;
     typedef ColsMasks<Q, P51> Mk;
     double x[16];
 #pragma unroll
     for (int e = 0; e < 16; e++) {
         double v = -hsub;
+        if (EXACT) v = -reduce_balanced(hsub + (double)(unsigned)((vpack >> (3 * e)) & 7u) * Bm, p, pinv);  // v <= 3: below 4p, exact
 #pragma unroll
         for (int a = 0; a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
         x[e] = reduce_balanced(v, p, pinv);  // |v| <= p + NSRC * 0.75p
@@ -334,8 +339,10 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 }
 
 // grid: x = column tile (N/4096), y = item * beta + digit, z = chunk of targets_per_wg target limbs
+// Four sources in the exact form need more than 256 registers a lane: that instantiation runs one wave per SIMD
+// (measured 0.97 ms against 1.37 ms with spills at two; the three-source ModUp is slower at one, 3.1 against 2.5 ms).
 template <int Q, int NSRC, int MODE, bool INVSRC>
-__global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs A) {
+__global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void modup_cols_kernel(ModupColsArgs A) {
     // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
     // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
     __shared__ double lds[2][16 * V2_GS];
@@ -344,6 +351,7 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
     unsigned item = 0, j = 0;
     int lo = 0, nsrc, n_targets;
     const u64d *ysrc;
+    static_assert(MODE != 2 || NSRC <= 4, "overshoot below 4: 3 bits each, h + v*Bbar below 4p");
     if (MODE == 0) {
         item = blockIdx.y / (unsigned)A.beta;
         j = blockIdx.y % (unsigned)A.beta;
@@ -409,6 +417,17 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
         }
         __syncthreads();  // lds[0] and twl are about to be reused by the targets
     }
+    unsigned long long vpack = 0;
+    if (MODE == 2) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            double sum = yd[0][e] * A.D.invb_f[0];
+#pragma unroll
+            for (int a = 1; a < NSRC; a++)
+                if (a < nsrc) sum = sum + yd[a][e] * A.D.invb_f[a];
+            vpack |= (unsigned long long)floor(sum) << (3 * e);
+        }
+    }
     const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
     // MODE 0: extended-basis index of target k (the digit's own limbs are skipped) and its modulus index;
     // MODE 1: target k is kept limb k
@@ -425,7 +444,7 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
         if (k + 2 < k1) tw_next = A.tw[(size_t)mod_of(ext_of(k + 2)) * N + threadIdx.x];
         const double p = A.modc[t].p, pinv = A.modc[t].pinv;
         WMul Wc[NSRC];
-        double hsub = 0.0;
+        double hsub = 0.0, Bm = 0.0;
         u64d *dst;
         if (MODE == 0) {
 #pragma unroll
@@ -435,12 +454,13 @@ __global__ __launch_bounds__(V2_THREADS, 2) void modup_cols_kernel(ModupColsArgs
 #pragma unroll
             for (int a = 0; a < NSRC; a++) Wc[a] = a < nsrc ? A.D.conv[(size_t)a * A.T + t] : WMul{0.0, 0.0};
             hsub = A.D.hc[t];
+            if (MODE == 2) Bm = A.D.Bmod[t];
             dst = A.dst + ((size_t)blockIdx.y * A.nc + t) * N;
         }
         if (is_p51(A.p51, t))
-            modup_cols_target<true, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub);
+            modup_cols_target<true, NSRC, Q, MODE == 2>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
         else
-            modup_cols_target<false, NSRC, Q>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub);
+            modup_cols_target<false, NSRC, Q, MODE == 2>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
     }
 }
 
@@ -668,6 +688,7 @@ struct RowsFinalArgs {
     const ModConst *modc;
     const double *tw;
     const WMul *Binv;    // [T]
+    const WMul *pre;     // optional [T]: the addend enters BEFORE the division, out = (x + pre_i*addend - r) * Binv
     int logN, nc;
     int limb0;             // first limb handled (grid z counts from it)
     int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
@@ -684,12 +705,14 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
     load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
     const size_t tile0 = (size_t)tile * 4096;
     const WMul W = A.Binv[i];
+    const bool pre = A.pre != nullptr;
+    const WMul Pm = pre ? A.pre[i] : WMul{0.0, 0.0};
     const unsigned r0 = blockIdx.x * (unsigned)A.rows_per_x;
     const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
     for (unsigned row = r0; row < r1; row++) {
         const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
         u64d *out = A.out + (size_t)row * A.out_row_stride + (size_t)(i - A.out_limb0) * N + tile0;
-        const bool add = A.addend && (A.add_both || (row & 1u) == 0);
+        const bool add = A.addend && (pre || A.add_both || (row & 1u) == 0);
         const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
         // operands of the last step are requested before the transform so that their latency overlaps it
         // pointwise part in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
@@ -704,9 +727,14 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
 #pragma unroll
         for (int s = 0; s < 8; s++) {
             const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
-            double v0 = mulmod_w(u2d(xr[s].x) - rr[0], W.w, W.wp, p);
-            double v1 = mulmod_w(u2d(xr[s].y) - rr[1], W.w, W.wp, p);
-            if (add) {
+            double x0 = u2d(xr[s].x), x1 = u2d(xr[s].y);
+            if (pre) {  // |x + pre*addend - r| < p + 1.5p + p/2 + 1
+                x0 += mulmod_w(u2d(ar[s].x), Pm.w, Pm.wp, p);
+                x1 += mulmod_w(u2d(ar[s].y), Pm.w, Pm.wp, p);
+            }
+            double v0 = mulmod_w(x0 - rr[0], W.w, W.wp, p);
+            double v1 = mulmod_w(x1 - rr[1], W.w, W.wp, p);
+            if (add && !pre) {
                 v0 += u2d(ar[s].x);
                 v1 += u2d(ar[s].y);
             }

@@ -206,6 +206,34 @@ def case_relin_and_composite(be, shape, seed, batch=2, levels=None, small_ws=Fal
     ctx.close()
 
 
+def case_merged_product(be, shape, seed, batch=2, levels=None, small_ws=False, expect_kernel=None):
+    """the product with one division by P*q_last, word for word against the oracle's definition of it"""
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    evk = be.to_dev(M.rlk)
+    for level in levels or [O.n_q]:
+        a, b = random_cts(M, level, batch, seed, ("ma", level)), random_cts(M, level, batch, seed, ("mb", level))
+        da, db = be.to_dev(a), be.to_dev(b)
+        out = be.empty(batch, 2, level - 1, O.N)
+        nbytes = ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch)
+        if small_ws and batch > 1:
+            nbytes = nbytes // batch + 8
+        ws = be.ws(nbytes)
+        if expect_kernel:
+            ctx.profile_enable(True)
+        ctx.hmul_relin_rescale_merged(da, db, evk, out, level, batch, ws, stream=be.stream)
+        got = be.to_host(out).reshape(batch, 2, level - 1, O.N)
+        if expect_kernel:
+            ran = ctx.profile_read()
+            ctx.profile_enable(False)
+            assert any(expect_kernel in n for n in ran), (expect_kernel, list(ran))
+        for i in range(batch):
+            assert np.array_equal(got[i], O.hmul_relin_rescale_merged(a[i], b[i], M.rlk, level)), "merged product differs at level %d item %d" % (level, i)
+    ctx.close()
+
+
 def case_rotate(be, shape, seed, rotations, batch=4, level=None):
     M = make_material(shape, seed, rotations=rotations)
     O = M.O

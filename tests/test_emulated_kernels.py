@@ -119,6 +119,34 @@ def test_emulated_fused_path_other_sizes(be, monkeypatch, logN):
     pc.case_relin_and_composite(be, (logN, 2, 40, 1, 41, 1), seed=118, batch=1, levels=[2])
 
 
+@pytest.mark.parametrize("shape,levels", [(TINY, [3, 2]), (HYBRID, [5, 4, 2]), (HYBRID3, [7, 5, 2])])
+def test_emulated_merged_product_small_sizes(be, shape, levels):
+    """one division by P*q_last, exact form: elementwise conversion with the double-precision overshoot"""
+    pc.case_merged_product(be, shape, seed=121, levels=levels)
+    if shape == HYBRID:
+        pc.case_merged_product(be, shape, seed=122, batch=3, levels=[5], small_ws=True)
+
+
+def test_emulated_merged_product_at_2e16(be, monkeypatch):
+    """the fused form: conversion kernel over {q_last, p_0, p_1, p_2} with the overshoot taken from the source registers"""
+    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "64")
+    pc.case_merged_product(be, (16, 4, 50, 3, 51, 3), seed=123, batch=2, levels=[4, 2], expect_kernel="modup_cols_kernel<4, 4, 2, true>")
+
+
+@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_FUSE": "7"}, {"CKKSMI_FUSE": "11"}, {"CKKSMI_MODUP_LOOP": "0"},
+                                 {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE_TENSOR": "0"}])
+def test_emulated_merged_product_alternative_paths(be, monkeypatch, env):
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    pc.case_merged_product(be, (16, 3, 50, 2, 51, 2), seed=124, batch=1, levels=[3])
+
+
+@pytest.mark.parametrize("logN", [13, 14, 15])
+def test_emulated_merged_product_other_sizes(be, monkeypatch, logN):
+    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "8")
+    pc.case_merged_product(be, (logN, 3, 50, 2, 51, 2), seed=125, batch=2, levels=[3, 2])
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

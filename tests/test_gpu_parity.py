@@ -219,6 +219,59 @@ def test_2e16_hybrid_shape_sampled(be):
         del ws, out
 
 
+@pytest.mark.parametrize("shape,levels,batch", [
+    (TINY, [3, 2], 2),
+    ((10, 5, 40, 2, 41, 2), [5, 4, 2], 3),
+    ((9, 7, 50, 3, 51, 3), [7, 5, 2], 2),
+    ((13, 3, 50, 1, 51, 1), [3], 2),
+    ((14, 3, 50, 2, 51, 2), [3, 2], 3),
+    ((15, 3, 50, 3, 51, 3), [3, 2], 1),
+    ((16, 4, 50, 3, 51, 3), [4, 2], 3),
+])
+def test_merged_product_matches_oracle(be, shape, levels, batch):
+    """the product with one division by P*q_last (exact DivRound): every word against the oracle's definition"""
+    announce("merged product %r levels %r" % (shape, levels))
+    pc.case_merged_product(be, shape, seed=320, batch=batch, levels=levels)
+
+
+@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "7"}, {"CKKSMI_FUSE": "11"},
+                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
+def test_merged_product_alternative_paths(be, monkeypatch, env):
+    announce("merged product, alternative paths %r" % (env,))
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    pc.case_merged_product(be, (16, 4, 50, 3, 51, 3), seed=321, batch=3, levels=[4])
+    pc.case_merged_product(be, (10, 5, 40, 2, 41, 2), seed=322, batch=5, levels=[5], small_ws=True)
+
+
+def test_merged_product_full_size_sampled_and_decrypts(be):
+    """N=2^16, 24 limbs, batch 64 in the benchmark's launch configuration: one item word for word against the oracle,
+    and an encrypted pair decrypts to the product within 1e-3 at scale 2^40"""
+    announce("merged product N=2^16 batch 64, sampled parity")
+    p = wl.PRESETS["act_2e16"]
+    M = pc.make_material(C4, 4)
+    ctx = be.context(*C4)
+    batch, level, pick = p.batch, 24, 41
+    evk = be.to_dev(M.rlk)
+    a = pc.random_cts(M, level, batch, 5, ("a", level))
+    b = pc.random_cts(M, level, batch, 5, ("b", level))
+    scale = 2.0 ** p.log_scale
+    za, zb = wl.slots_real(M.N // 2, 5, "za"), wl.slots_real(M.N // 2, 5, "zb")
+    a[0], b[0] = M.encrypt(za, scale, level, "a"), M.encrypt(zb, scale, level, "b")
+    out = be.empty(batch, 2, level - 1, M.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+    ctx.profile_enable(True)
+    ctx.hmul_relin_rescale_merged(be.to_dev(a), be.to_dev(b), evk, out, level, batch, ws)
+    got = be.to_host(out).reshape(batch, 2, level - 1, M.N)
+    ran = ctx.profile_read()
+    ctx.profile_enable(False)
+    assert "modup_cols_kernel<4, 4, 2, true>" in ran, list(ran)
+    announce("oracle for item %d" % pick)
+    assert np.array_equal(got[pick], M.O.hmul_relin_rescale_merged(a[pick], b[pick], M.rlk, level))
+    dec = M.decrypt(got[0], scale * scale / M.O.q[level - 1], level - 1)
+    assert np.max(np.abs(dec - za * zb)) < 1e-3
+
+
 def _device_residues(torch, q_list, lead, N, seed):
     """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
     g = torch.Generator(device="cuda:0")
