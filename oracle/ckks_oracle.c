@@ -708,6 +708,69 @@ void orc_rotate(const orc_params *P, const u64 *ct, u64 g, const u64 *gk, int le
     free(sg); free(tmp);
 }
 
+/*
+ * R rotations of ONE ciphertext with a shared ModUp ("hoisting"): the second
+ * component is decomposed and lifted once,
+ *     dt_j = NTT(ModUp_j(INTT(c1))),  j < beta,   over the extended basis,
+ * and every rotation applies its automorphism to those lifted digits (limb-wise,
+ * evaluation form) before the inner product with its own key:
+ *     acc_c = sum_j sigma_g(dt_j) * gk_g[j][c],   ks = DivRound_P(acc),
+ *     out_g = (sigma_g(c0) + ks0, ks1).
+ * sigma_g(ModUp_j(d)) = sigma_g(d) + sigma_g(u)*Q_j is as good a lift of
+ * sigma_g(d) as ModUp_j(sigma_g(d)) but not the same one, so out_g decrypts like
+ * orc_rotate's result and is NOT bit-identical to it.
+ * g: R Galois elements; gk: R keys [beta][2][n_q+k][N] back to back;
+ * out: [R][2][level][N].
+ */
+void orc_rotate_hoisted(const orc_params *P, const u64 *ct, int level, int R, const u64 *g, const u64 *gk, u64 *out) {
+    u64 N = P->N;
+    int E = level + P->k, T = P->n_q + P->k;
+    int beta = (level + P->alpha - 1) / P->alpha;
+    size_t key_words = (size_t)((P->n_q + P->alpha - 1) / P->alpha) * 2 * T * N; /* digits are fixed at the top level */
+    u64 *dc = (u64 *)malloc((size_t)level * N * 8);
+    u64 *dt = (u64 *)malloc((size_t)beta * E * N * 8);
+    u64 *acc = (u64 *)malloc((size_t)2 * E * N * 8);
+    u64 *v = (u64 *)malloc(N * 8);
+    int *cidx = (int *)malloc(sizeof(int) * level), *bidx = (int *)malloc(sizeof(int) * (P->k ? P->k : 1));
+    for (int i = 0; i < level; i++) cidx[i] = i;
+    for (int m = 0; m < P->k; m++) bidx[m] = P->n_q + m;
+    memcpy(dc, ct + (size_t)level * N, (size_t)level * N * 8);
+    for (int i = 0; i < level; i++) orc_intt_limb(P, i, dc + (size_t)i * N);
+    for (int j = 0; j < beta; j++) {
+        u64 *dj = dt + (size_t)j * E * N;
+        orc_modup(P, dc, level, j, dj);
+        for (int x = 0; x < E; x++) orc_ntt_limb(P, ext_index(P, level, x), dj + (size_t)x * N);
+    }
+    for (int r = 0; r < R; r++) {
+        const u64 *key = gk + (size_t)r * key_words;
+        u64 *o = out + (size_t)r * 2 * level * N;
+        memset(acc, 0, (size_t)2 * E * N * 8);
+        for (int j = 0; j < beta; j++)
+            for (int x = 0; x < E; x++) {
+                int t = ext_index(P, level, x);
+                u64 q = P->mod[t];
+                orc_automorphism_eval(dt + ((size_t)j * E + x) * N, P->logN, g[r], v);
+                for (int c = 0; c < 2; c++) {
+                    const u64 *kk = key + (((size_t)j * 2 + c) * T + t) * N;
+                    u64 *ac = acc + ((size_t)c * E + x) * N;
+                    for (u64 n = 0; n < N; n++) ac[n] = orc_addmod(ac[n], orc_mulmod(v[n] % q, kk[n] % q, q), q);
+                }
+            }
+        for (int c = 0; c < 2; c++) {
+            u64 *ac = acc + (size_t)c * E * N;
+            for (int x = 0; x < E; x++) orc_intt_limb(P, ext_index(P, level, x), ac + (size_t)x * N);
+            orc_divround_coef(P, ac, cidx, level, bidx, P->k, o + (size_t)c * level * N);
+            for (int i = 0; i < level; i++) orc_ntt_limb(P, i, o + ((size_t)c * level + i) * N);
+        }
+        for (int i = 0; i < level; i++) {
+            u64 q = P->mod[i];
+            orc_automorphism_eval(ct + (size_t)i * N, P->logN, g[r], v);
+            for (u64 n = 0; n < N; n++) o[(size_t)i * N + n] = orc_addmod(o[(size_t)i * N + n], v[n] % q, q);
+        }
+    }
+    free(cidx); free(bidx); free(dc); free(dt); free(acc); free(v);
+}
+
 /* ---- limb-wise operations ---- */
 void orc_add(const orc_params *P, const u64 *a, const u64 *b, int level, u64 *out) {
     for (int c = 0; c < 2; c++) for (int i = 0; i < level; i++) {

@@ -218,6 +218,7 @@ class Oracle:
             "orc_hmul_relin_rescale": [V, u64p, u64p, u64p, I, u64p],
             "orc_hmul_relin_rescale_merged": [V, u64p, u64p, u64p, I, u64p],
             "orc_rotate": [V, u64p, C.c_uint64, u64p, I, u64p],
+            "orc_rotate_hoisted": [V, u64p, I, I, u64p, u64p, u64p],
             "orc_add": [V, u64p, u64p, I, u64p],
             "orc_sub": [V, u64p, u64p, I, u64p],
             "orc_mul_plain": [V, u64p, u64p, I, u64p],
@@ -392,6 +393,14 @@ class Oracle:
         g = galois_element(self.logN, r)
         out = np.empty((2, level, self.N), dtype=np.uint64)
         self._L.orc_rotate(self._h, _p64(_u64(ct)), g, _p64(_u64(gk)), level, _p64(out))
+        return out
+
+    def rotate_hoisted(self, ct, rots, gks, level):
+        """Left rotations of one ciphertext by every r in rots with one shared ModUp; gks: their keys, in order."""
+        g = np.array([galois_element(self.logN, r) for r in rots], dtype=np.uint64)
+        keys = np.ascontiguousarray(np.stack([_u64(k) for k in gks]))
+        out = np.empty((len(rots), 2, level, self.N), dtype=np.uint64)
+        self._L.orc_rotate_hoisted(self._h, _p64(_u64(ct)), level, len(rots), _p64(g), _p64(keys), _p64(out))
         return out
 
     def add(self, a, b, level):

@@ -535,6 +535,39 @@ def test_rotation_permutation_formula_and_direction():
         assert np.max(np.abs(M.decrypt(out, 2.0**25, 3) - np.roll(z, -r))) < 1e-3
 
 
+@pytest.mark.parametrize("shape,level", [((6, 3, 30, 1, 31, 1), 3), ((6, 5, 30, 2, 31, 2), 5), ((6, 5, 30, 2, 31, 2), 4), ((5, 7, 30, 3, 31, 3), 5)])
+def test_hoisted_rotations_decrypt_to_rotated_slots_with_keyswitch_noise_only(shape, level):
+    """every rotation from the shared ModUp: the decrypted POLYNOMIAL is the automorphism of the input's (Python
+    integers) up to key-switch noise as small as the plain rotation's, and the slots are the rotated slots"""
+    rots = (1, 5, 7)
+    M = Material(*shape, seed=44, rotations=rots)
+    O = M.O
+    z = wl.slots_complex(O.N // 2, 44, level)
+    ct = M.encrypt(z, 2.0**25, level, "h")
+    outs = O.rotate_hoisted(ct, rots, [M.gk[r] for r in rots], level)
+    Q = math.prod(O.q[:level])
+    m_in = M.decrypt_poly(ct, level)
+    for idx, r in enumerate(rots):
+        g = orc.galois_element(O.logN, r)
+        want = [0] * O.N
+        for t in range(O.N):
+            i = (t * g) % (2 * O.N)
+            if i < O.N:
+                want[i] = m_in[t]
+            else:
+                want[i - O.N] = -m_in[t]
+        worst = {}
+        for name, out in (("hoisted", outs[idx]), ("plain", O.rotate(ct, r, M.gk[r], level))):
+            got = M.decrypt_poly(out, level)
+            noise = [((a - b + Q // 2) % Q) - Q // 2 for a, b in zip(got, want)]
+            worst[name] = max(abs(v) for v in noise)
+        assert worst["hoisted"] < 4 * max(worst["plain"], 64), worst
+        assert np.max(np.abs(M.decrypt(outs[idx], 2.0**25, level) - np.roll(z, -r))) < 1e-3
+        # a rotation does not depend on the others in the list
+        assert np.array_equal(outs[idx], O.rotate_hoisted(ct, [r], [M.gk[r]], level)[0])
+    assert not np.array_equal(outs[0], O.rotate(ct, rots[0], M.gk[rots[0]], level))  # a different lift: other bits
+
+
 def test_elementwise_ops_on_decrypted_polynomials():
     M = Material(5, 3, 30, 1, 31, 1, seed=20)
     O = M.O
