@@ -173,6 +173,18 @@ int ckksmi_hmul_relin_rescale_merged(ckksmi_ctx *ctx, const uint64_t *a, const u
  * key): automorphism X -> X^g first, then key switch of the second component */
 int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [batch]*/, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 
+/* n_rot rotations of EVERY item with one shared ModUp ("hoisting"; a fewer-transform variant of the rotation above, the
+ * paper fixes no algorithm): the second component is decomposed and lifted to the extended basis once per item,
+ * dt_j = NTT(ModUp_j(INTT(c1))), and rotation r applies its automorphism to the lifted digits before the inner product
+ * with its key: acc_c = sum_j sigma_r(dt_j) * gk_r[j][c], ks = DivRound_P(acc), out = (sigma_r(c0) + ks0, ks1).
+ * Decrypts like ckksmi_rotate's result but is NOT bit-identical to it (sigma(ModUp(d)) and ModUp(sigma(d)) are
+ * different lifts of the same polynomial).  rot: host array of n_rot offsets (1 <= n_rot <= 16), each with a
+ * registered key, CKKSMI_ENOKEY otherwise; out: device [batch][n_rot][2][level][N], must not alias a;
+ * ws: device workspace of ckksmi_rotate_hoisted_workspace_bytes(level, batch, n_rot) bytes (a smaller one makes
+ * several sweeps; CKKSMI_EWORKSPACE if not even one item fits). */
+int ckksmi_rotate_hoisted(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [n_rot]*/, int n_rot, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+int ckksmi_rotate_hoisted_workspace_bytes(const ckksmi_ctx *ctx, int level, int batch, int n_rot, size_t *bytes);
+
 /* Convolution / fully-connected layers of the paper's network (Table 1) over
  * per-pixel ciphertexts (slot s = image s), integer plaintext weights (device,
  * int64): out[o,y,x] = sum_{c,u,v} w[o,c,u,v] * in[c, y*stride+u-pad, x*stride+v-pad],
@@ -235,7 +247,9 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_TENSOR_ROWS 21   /* tensor product fused with the inverse contiguous pass of its third component */
 #define CKKSMI_K_AXPY_LIMB 22     /* one limb of every row += constant * another limb (merged division: P*d on the dropped q) */
 #define CKKSMI_K_CONV_COLS_MERGED 23 /* the conversion kernel in the exact form of DivRound, sources {q_last, special primes} */
-#define CKKSMI_K_COUNT 24
+#define CKKSMI_K_INNER_HOISTED 24 /* inner product of hoisted rotations (gathers the lifted digits through each automorphism) */
+#define CKKSMI_K_AUTOMORPH_BCAST 25 /* first component of every item through every rotation's automorphism */
+#define CKKSMI_K_COUNT 26
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

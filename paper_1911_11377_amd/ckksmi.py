@@ -71,6 +71,8 @@ SIGNATURES = {
     "ckksmi_rescale": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_rotate_hoisted": [VP, VP, intp, C.c_int, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_rotate_hoisted_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_rotate": [VP, VP, intp, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_mac": [VP, VP, VP] + [C.c_int] * 8 + [VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
@@ -83,7 +85,7 @@ SIGNATURES = {
     "ckksmi_kernel_class_name": [VP, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
-K_COUNT = 24
+K_COUNT = 26
 
 _LIBS = {}
 
@@ -312,6 +314,17 @@ class Context:
 
     def hmul_relin_rescale(self, a, b, evk, out, level, batch, ws, stream=None):
         self._call("ckksmi_hmul_relin_rescale", self._h, _ptr(a), _ptr(b), _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
+                   self._stream(stream))
+
+    def rotate_hoisted_workspace_bytes(self, level, batch, n_rot):
+        n = C.c_size_t(0)
+        self._call("ckksmi_rotate_hoisted_workspace_bytes", self._h, level, batch, n_rot, C.byref(n))
+        return n.value
+
+    def rotate_hoisted(self, a, rots, out, level, batch, ws, stream=None):
+        """every item rotated by every offset in rots with one shared ModUp; out [batch][len(rots)][2][level][N]"""
+        r = np.ascontiguousarray(rots, dtype=np.int32)
+        self._call("ckksmi_rotate_hoisted", self._h, _ptr(a), r.ctypes.data_as(intp), len(r), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
                    self._stream(stream))
 
     def hmul_relin_rescale_merged(self, a, b, evk, out, level, batch, ws, stream=None):

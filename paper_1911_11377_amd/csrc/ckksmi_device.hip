@@ -342,6 +342,33 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
     }
 }
 
+// Rotations with a shared ModUp: R rotations of every item of a key-switch sweep (see inner_product_hoisted_kernel)
+struct HoistPlan {
+    int R;
+    unsigned g[CKKSMI_MAX_KEYS], ginv[CKKSMI_MAX_KEYS];
+    const u64 *key[CKKSMI_MAX_KEYS];
+    const u64 *sig;  // sigma_r(c0) of every item: [items][R][level][N], the addend of the first component
+};
+
+void launch_hoisted_inner(ckksmi_ctx *c, const HoistPlan &H, const u64 *dt, const u64 *d_eval, size_t d_stride, u64 *acc, int items, int level,
+                          hipStream_t st) {
+    HoistArgs A;
+    memset(&A, 0, sizeof(A));
+    A.dt = (const u64d *)dt; A.d_eval = (const u64d *)d_eval; A.d_eval_item_stride = d_stride; A.acc = (u64d *)acc; A.modc = c->d_mod;
+    A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.beta = (level + c->alpha - 1) / c->alpha;
+    A.T = c->T; A.items = items; A.R = H.R;
+    for (int r = 0; r < H.R; r++) { A.g[r] = H.g[r]; A.ginv[r] = H.ginv[r]; A.key[r] = (const u64d *)H.key[r]; }
+    if (c->logN >= 8 && A.beta <= INNER_MAX_BETA && EW_THREADS == 256 && !getenv("CKKSMI_HOIST_GATHER")) {
+        // source rows staged in LDS once for all rotations
+        A.items_per_wg = std::max(1, std::min(items, HOIST_LDS_WORDS / 256 / A.beta));
+        const unsigned z = (unsigned)((items + A.items_per_wg - 1) / A.items_per_wg);
+        KL(c, CKKSMI_K_INNER_HOISTED, (double)items * H.R * A.E, inner_product_hoisted_tile_kernel, dim3((unsigned)(c->N / 256), A.E, z),
+           dim3(EW_THREADS), st, A);
+        return;
+    }
+    KL(c, CKKSMI_K_INNER_HOISTED, (double)items * H.R * A.E, inner_product_hoisted_kernel, dim3(ew_blocks(c->N), A.E, H.R), dim3(EW_THREADS), st, A);
+}
+
 // The product's division in one step: acc [items][2][E][N] holds the key-switch accumulators over the extended basis
 // (evaluation form) and d0, d1 (the addend) join them multiplied by P before the division by P*q_{level-1}:
 //     out[items][2][level-1][N] = DivRound_B(acc + P*d),  B = {q_{level-1}, p_0 .. p_{k-1}},  exact form.
@@ -388,13 +415,14 @@ void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item
 // ciphertexts [items][2][level-1][N]; tail_scratch holds 2*level*N words per item.  Needs both DivRound fusions.
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
-                   u64 *tail_scratch = nullptr, bool ymid_ready = false, bool merged = false) {
+                   u64 *tail_scratch = nullptr, bool ymid_ready = false, bool merged = false, const HoistPlan *hoist = nullptr) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    const int R = hoist ? hoist->R : 1;  // hoisted rotations: R accumulator pairs per item
     u64 *ycoef = ws;
     u64 *dtA = ycoef + (size_t)items * level * N;
     u64 *acc = dtA + (size_t)items * beta * E * N;
-    u64 *tmp = acc + (size_t)items * 2 * E * N;
+    u64 *tmp = acc + (size_t)items * R * 2 * E * N;
     int idx[CKKSMI_MAX_MODULI];
     for (int i = 0; i < level; i++) idx[i] = i;
     LimbMap M1;
@@ -418,6 +446,16 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st);
         launch_modup(c, ycoef, d_eval, d_stride, dtA, items, level, st);
         launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 1);
+    }
+    if (hoist) {
+        // the lifted digits in evaluation form once, then every rotation gathers from them
+        launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
+        launch_hoisted_inner(c, *hoist, dtA, (c->fuse & FUSE_MODUP) ? d_eval : nullptr, d_stride, acc, items, level, st);
+        int hidx[CKKSMI_MAX_SPECIAL];
+        for (int m = 0; m < c->k; m++) hidx[m] = c->n_q + m;
+        divround_rows(c, c->divround[0], c->d_fin_moddown, hidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
+                      acc, (size_t)E * N, tmp, level, items * R * 2, hoist->sig, (size_t)level * N, 0, 0, out, st);
+        return;
     }
     if (c->fuse & FUSE_INNER) {
         RowsInnerArgs RI;
@@ -484,18 +522,23 @@ void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int le
 // Key switch of `items` polynomials.  d_eval: item i's polynomial ([level][N], evaluation
 // form) at d_eval + i*d_stride.  out[i][c][l] = ks_c (+ addend).  ws: ks_words_per_item*items.
 void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
-             size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st, bool merged = false) {
+             size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st, bool merged = false,
+             const HoistPlan *hoist = nullptr) {
     if (c->fused) {
         ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st, nullptr, false,
-                      merged);
+                      merged, hoist);
         return;
     }
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    const int rows = items * 2 * (hoist ? hoist->R : 1);
     u64 *dcoef = ws;
     u64 *dt = dcoef + (size_t)items * level * N;
     u64 *acc = dt + (size_t)items * beta * E * N;
-    u64 *tmp = acc + (size_t)items * 2 * E * N;
+    u64 *tmp = acc + (size_t)rows * E * N;
+    if (hoist) {
+        addend = hoist->sig; add_item_stride = (size_t)level * N; add_comp_stride = 0; add_both = 0;
+    }
     int idx[CKKSMI_MAX_MODULI];
     for (int i = 0; i < level; i++) idx[i] = i;
     // 1. d -> coefficient form
@@ -517,13 +560,17 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     M1.per_item = beta * E; M1.mode = 1; M1.level = level; M1.E = E; M1.n_q = c->n_q; M1.alpha = c->alpha;
     M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
     launch_ntt(c, true, dt, dt, M1, items, st);
-    // 4. inner product with the key
-    InnerArgs IA;
-    IA.dt = (const u64d *)dt; IA.d_eval = nullptr; IA.d_eval_item_stride = 0; IA.alpha = c->alpha; IA.acc = (u64d *)acc; IA.modc = c->d_mod;
-    IA.logN = c->logN; IA.level = level; IA.E = E; IA.n_q = c->n_q; IA.beta = beta; IA.T = c->T;
-    IA.items = items;
-    const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
-    KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
+    // 4. inner product with the key (hoisted rotations: one per rotation, gathered through its automorphism)
+    if (hoist) {
+        launch_hoisted_inner(c, *hoist, dt, nullptr, 0, acc, items, level, st);
+    } else {
+        InnerArgs IA;
+        IA.dt = (const u64d *)dt; IA.d_eval = nullptr; IA.d_eval_item_stride = 0; IA.alpha = c->alpha; IA.acc = (u64d *)acc; IA.modc = c->d_mod;
+        IA.logN = c->logN; IA.level = level; IA.E = E; IA.n_q = c->n_q; IA.beta = beta; IA.T = c->T;
+        IA.items = items;
+        const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
+        KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
+    }
     if (merged) {
         merged_division(c, acc, addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
         return;
@@ -532,7 +579,7 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
     launch_ntt(c, false, acc + (size_t)level * N, acc + (size_t)level * N, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N),
-               (size_t)items * 2, st);
+               (size_t)rows, st);
     DivConvArgs DC;
     DC.b_limbs = (const u64d *)(acc + (size_t)level * N);
     DC.b_row_stride = (size_t)E * N;
@@ -540,8 +587,8 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     DC.modc = c->d_mod;
     DC.D = c->divround[0];
     DC.logN = c->logN; DC.nc = level; DC.T = c->T; DC.exact = 0;
-    KL(c, CKKSMI_K_DIVCONV, (double)items * 2 * DC.nc, divround_conv_kernel, dim3(ew_blocks(N), items * 2), dim3(EW_THREADS), st, DC);
-    launch_ntt(c, true, tmp, tmp, table_map(idx, level, (size_t)level * N, (size_t)level * N), (size_t)items * 2, st);
+    KL(c, CKKSMI_K_DIVCONV, (double)rows * DC.nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
+    launch_ntt(c, true, tmp, tmp, table_map(idx, level, (size_t)level * N, (size_t)level * N), (size_t)rows, st);
     DivFinalArgs DF;
     DF.x = (const u64d *)acc; DF.x_row_stride = (size_t)E * N;
     DF.tmp = (const u64d *)tmp;
@@ -550,7 +597,7 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
     DF.out = (u64d *)out;
     DF.modc = c->d_mod; DF.Binv = c->divround[0].Binv; DF.pre = nullptr;
     DF.logN = c->logN; DF.nc = level;
-    KL(c, CKKSMI_K_DIVFINAL, (double)items * 2 * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level, items * 2), dim3(EW_THREADS), st, DF);
+    KL(c, CKKSMI_K_DIVFINAL, (double)rows * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level, rows), dim3(EW_THREADS), st, DF);
 }
 
 // out[i] = DivRound_{q_{level-1}}(a[i]); ws: rescale_words_per_item*items
@@ -1089,6 +1136,65 @@ extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, u
     return g.rc();
 }
 
+static size_t hoisted_words_per_item(const ckksmi_ctx *c, int level, int R) {
+    const size_t N = c->N, E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
+    // sigma_r(c0) + lifted digits + R accumulator pairs + R conversion results
+    return N * ((size_t)R * level + (size_t)level + beta * E + (size_t)R * (2 * E + 2 * (size_t)level));
+}
+
+extern "C" int ckksmi_rotate_hoisted_workspace_bytes(const ckksmi_ctx *c, int level, int batch, int n_rot, size_t *bytes) {
+    if (!c || !bytes || level < 1 || level > c->n_q || batch < 0 || n_rot < 1 || n_rot > CKKSMI_MAX_KEYS) return CKKSMI_EINVAL;
+    const size_t items = (size_t)(batch < CKKSMI_MAX_ITEMS ? batch : CKKSMI_MAX_ITEMS);
+    *bytes = items * hoisted_words_per_item(c, level, n_rot) * 8;
+    return CKKSMI_OK;
+}
+
+extern "C" int ckksmi_rotate_hoisted(ckksmi_ctx *c, const uint64_t *a, const int *rot, int n_rot, uint64_t *out, int level, int batch, void *ws,
+                                     size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (c->k == 0) return CKKSMI_EUNSUPPORTED;
+    if (!a || !rot || !out || a == out || n_rot < 1 || n_rot > CKKSMI_MAX_KEYS || (!ws && batch) || !al16(a) || !al16(out) || !al16(ws))
+        return CKKSMI_EINVAL;
+    HoistPlan H;
+    memset(&H, 0, sizeof(H));
+    H.R = n_rot;
+    for (int r = 0; r < n_rot; r++) {
+        const int nr = norm_rot(c, rot[r]);
+        int found = -1;
+        for (size_t e = 0; e < c->galois.size(); e++)
+            if (c->galois[e].first == nr) found = (int)e;
+        if (found < 0) return CKKSMI_ENOKEY;
+        H.key[r] = c->galois[found].second;
+        H.g[r] = (unsigned)galois_element_of(c, rot[r]);
+        H.ginv[r] = (unsigned)hm::powmod(H.g[r], c->N - 1, 2 * c->N);  // the units mod 2N have order N
+    }
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N;
+    const int chunk = sweep_items(ws_bytes, hoisted_words_per_item(c, level, n_rot), batch);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    KeyTab K;
+    memset(&K, 0, sizeof(K));
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        const u64 *ain = a + (size_t)b0 * 2 * level * N;
+        u64 *sig = (u64 *)ws;  // [items][R][level][N]
+        u64 *rest = sig + (size_t)items * n_rot * level * N;
+        HoistArgs HA;
+        memset(&HA, 0, sizeof(HA));
+        HA.logN = c->logN; HA.level = level; HA.R = n_rot;
+        for (int r = 0; r < n_rot; r++) HA.g[r] = H.g[r];
+        const size_t total = (size_t)items * n_rot * level * N;
+        KL(c, CKKSMI_K_AUTOMORPH_BCAST, (double)items * n_rot * level, automorphism_bcast_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream),
+           (const u64d *)ain, (unsigned long long)((size_t)2 * level * N), (u64d *)sig, HA, total);
+        H.sig = sig;
+        ks_core(c, ain + (size_t)level * N, (size_t)2 * level * N, K, items, level, nullptr, 0, 0, 0, out + (size_t)b0 * n_rot * 2 * level * N, rest,
+                S(stream), false, &H);
+    }
+    return g.rc();
+}
+
 namespace {
 // Which multiply-accumulate kernel a layer shape can use, and the workspace the matrix-core one needs.
 struct MacShape {
@@ -1232,8 +1338,10 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
                                                 "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel",
-                                                "axpy_limb_kernel", "modup_cols_kernel"};
+                                                "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
+    if (c && kernel_class == CKKSMI_K_INNER_HOISTED && (c->logN < 8 || c->beta_top > INNER_MAX_BETA || getenv("CKKSMI_HOIST_GATHER")))
+        return "inner_product_hoisted_kernel";
     if (c && c->logN >= 13 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
                                     "ntt_v2_kernel<true, true>"};

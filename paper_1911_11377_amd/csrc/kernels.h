@@ -577,6 +577,177 @@ __global__ __launch_bounds__(EW_THREADS) void axpy_limb_kernel(u64d *x, unsigned
 // rows (even rows) receive the addend; used by rotation: (sigma(c0) + ks0, ks1)
 // is produced directly by divround_final's addend with add_comp_stride, so no kernel here.
 
+// ---------------------------------------------------------------- rotations with a shared ModUp
+// R rotations of each item from ONE lifted decomposition dt of its second component: rotation r applies its
+// automorphism to the lifted digits on the fly (a gather: out word m takes word pi_r(m)) and multiplies by its own key,
+//     acc[item][r][c][x][m] = sum_j dt[item][j][x][pi_r(m)] * key_r[j][c][x][m].
+// The permutation keeps the high bits of a word index among themselves (the low bits of brev), so the 256 outputs of
+// a workgroup gather from one 256-word run of the source: the gather is local to cache lines the workgroup uses up.
+struct HoistArgs {
+    const u64d *dt;      // [items][beta][E][N] evaluation form
+    const u64d *d_eval;  // optional: limbs that belong to a digit are read from here (item i at + i*stride, [level][N])
+    unsigned long long d_eval_item_stride;
+    u64d *acc;           // [items][R][2][E][N]
+    const ModConst *modc;
+    int logN, level, E, n_q, alpha, beta, T;
+    int items, R;
+    int items_per_wg;                  // tile kernel: items whose source rows share the workgroup's LDS
+    unsigned g[CKKSMI_MAX_KEYS];
+    unsigned ginv[CKKSMI_MAX_KEYS];    // g^-1 mod 2N
+    const u64d *key[CKKSMI_MAX_KEYS];
+};
+
+__device__ __forceinline__ unsigned automorphism_source(unsigned j, unsigned g, int logN) {
+    const unsigned N = 1u << logN;
+    const unsigned bj = __brev(j) >> (32 - logN);
+    const unsigned e = ((2u * bj + 1u) * g) & (2u * N - 1u);
+    return __brev((e - 1u) >> 1) >> (32 - logN);
+}
+
+// grid: x = word block, y = extended limb, z = rotation
+__global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_kernel(HoistArgs A) {
+    const unsigned N = 1u << A.logN;
+    const unsigned m = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (m >= N) return;
+    const unsigned x = blockIdx.y, r = blockIdx.z;
+    const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+    const ModConst mc = A.modc[t];
+    const unsigned src = automorphism_source(m, A.g[r], A.logN);
+    const u64d *key = A.key[r];
+    const int j_own = (A.d_eval && (int)x < A.level) ? (int)x / A.alpha : -1;
+    if (A.beta <= INNER_MAX_BETA) {
+        // the key words of this position stay in registers over the items
+        double k0[INNER_MAX_BETA], k1[INNER_MAX_BETA];
+#pragma unroll
+        for (int j = 0; j < INNER_MAX_BETA; j++)
+            if (j < A.beta) {
+                k0[j] = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + m]);
+                k1[j] = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + m]);
+            }
+        for (int item = 0; item < A.items; item++) {
+            double v[INNER_MAX_BETA];
+#pragma unroll
+            for (int j = 0; j < INNER_MAX_BETA; j++)
+                if (j < A.beta)
+                    v[j] = j == j_own ? u2d(A.d_eval[(size_t)item * A.d_eval_item_stride + (size_t)x * N + src])
+                                      : u2d(A.dt[(((size_t)item * A.beta + j) * A.E + x) * N + src]);
+            double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+            for (int j = 0; j < INNER_MAX_BETA; j++)
+                if (j < A.beta) {
+                    a0 = reduce_balanced(a0 + mulmod(v[j], k0[j], mc.p, mc.pinv), mc.p, mc.pinv);
+                    a1 = reduce_balanced(a1 + mulmod(v[j], k1[j], mc.p, mc.pinv), mc.p, mc.pinv);
+                }
+            const size_t row = ((size_t)item * A.R + r) * 2;
+            A.acc[((row + 0) * A.E + x) * N + m] = d2u(canon_small(a0, mc.p));
+            A.acc[((row + 1) * A.E + x) * N + m] = d2u(canon_small(a1, mc.p));
+        }
+        return;
+    }
+    for (int item = 0; item < A.items; item++) {
+        double a0 = 0.0, a1 = 0.0;
+        for (int j = 0; j < A.beta; j++) {
+            const double v = j == j_own ? u2d(A.d_eval[(size_t)item * A.d_eval_item_stride + (size_t)x * N + src])
+                                        : u2d(A.dt[(((size_t)item * A.beta + j) * A.E + x) * N + src]);
+            const double k0 = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + m]);
+            const double k1 = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + m]);
+            a0 = reduce_balanced(a0 + mulmod(v, k0, mc.p, mc.pinv), mc.p, mc.pinv);
+            a1 = reduce_balanced(a1 + mulmod(v, k1, mc.p, mc.pinv), mc.p, mc.pinv);
+        }
+        const size_t row = ((size_t)item * A.R + r) * 2;
+        A.acc[((row + 0) * A.E + x) * N + m] = d2u(canon_small(a0, mc.p));
+        A.acc[((row + 1) * A.E + x) * N + m] = d2u(canon_small(a1, mc.p));
+    }
+}
+
+// The same sums organised around the SOURCE: a workgroup stages one 256-word run of every lifted digit of a few items
+// in LDS (read from HBM once for all rotations), then walks the rotations: rotation r sends this run to exactly one
+// 256-word run of its output (found through the inverse automorphism), gathered out of LDS.
+#define HOIST_LDS_WORDS 8192  // 64 KiB: items_per_wg * beta * 256 words
+// grid: x = source run (N/256), y = extended limb, z = chunk of items_per_wg items
+__global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(HoistArgs A) {
+    __shared__ double tile[HOIST_LDS_WORDS];
+    const unsigned N = 1u << A.logN;
+    const unsigned tid = threadIdx.x, src0 = blockIdx.x * 256u, x = blockIdx.y;
+    const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+    const ModConst mc = A.modc[t];
+    const int j_own = (A.d_eval && (int)x < A.level) ? (int)x / A.alpha : -1;
+    const int item0 = (int)blockIdx.z * A.items_per_wg;
+    const int n_items = (item0 + A.items_per_wg < A.items ? item0 + A.items_per_wg : A.items) - item0;
+    for (int ii = 0; ii < n_items; ii++) {
+        // all digits of an item requested together (a load per iteration followed by its LDS write would serialise them)
+        const size_t item = (size_t)(item0 + ii);
+        u64d raw[INNER_MAX_BETA];
+#pragma unroll
+        for (int j = 0; j < INNER_MAX_BETA; j++)
+            if (j < A.beta) {
+                const u64d *row = j == j_own ? A.d_eval + item * A.d_eval_item_stride + (size_t)x * N : A.dt + ((item * A.beta + j) * A.E + x) * N;
+                raw[j] = row[src0 + tid];
+            }
+#pragma unroll
+        for (int j = 0; j < INNER_MAX_BETA; j++)
+            if (j < A.beta) tile[(ii * A.beta + j) * 256 + tid] = u2d(raw[j]);
+    }
+    __syncthreads();
+    // the key words of rotation r + 1 are requested before the sums of rotation r, so their latency is covered
+    double kn0[INNER_MAX_BETA], kn1[INNER_MAX_BETA];
+    unsigned m_next = (automorphism_source(src0, A.ginv[0], A.logN) & ~255u) + tid;  // this run's image under rotation 0
+#pragma unroll
+    for (int j = 0; j < INNER_MAX_BETA; j++)
+        if (j < A.beta) {
+            kn0[j] = u2d(A.key[0][(((size_t)j * 2 + 0) * A.T + t) * N + m_next]);
+            kn1[j] = u2d(A.key[0][(((size_t)j * 2 + 1) * A.T + t) * N + m_next]);
+        }
+    for (int r = 0; r < A.R; r++) {
+        const unsigned m = m_next;
+        const unsigned s = automorphism_source(m, A.g[r], A.logN) - src0;  // below 256
+        double k0[INNER_MAX_BETA], k1[INNER_MAX_BETA];
+#pragma unroll
+        for (int j = 0; j < INNER_MAX_BETA; j++) {
+            k0[j] = kn0[j];
+            k1[j] = kn1[j];
+        }
+        if (r + 1 < A.R) {
+            m_next = (automorphism_source(src0, A.ginv[r + 1], A.logN) & ~255u) + tid;
+            const u64d *key = A.key[r + 1];
+#pragma unroll
+            for (int j = 0; j < INNER_MAX_BETA; j++)
+                if (j < A.beta) {
+                    kn0[j] = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + m_next]);
+                    kn1[j] = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + m_next]);
+                }
+        }
+        for (int ii = 0; ii < n_items; ii++) {
+            double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+            for (int j = 0; j < INNER_MAX_BETA; j++)
+                if (j < A.beta) {
+                    const double v = tile[(ii * A.beta + j) * 256 + s];
+                    a0 = reduce_balanced(a0 + mulmod(v, k0[j], mc.p, mc.pinv), mc.p, mc.pinv);
+                    a1 = reduce_balanced(a1 + mulmod(v, k1[j], mc.p, mc.pinv), mc.p, mc.pinv);
+                }
+            const size_t row = ((size_t)(item0 + ii) * A.R + r) * 2;
+            A.acc[((row + 0) * A.E + x) * N + m] = d2u(canon_small(a0, mc.p));
+            A.acc[((row + 1) * A.E + x) * N + m] = d2u(canon_small(a1, mc.p));
+        }
+    }
+}
+
+// sigma_r of the first component of every item, for every rotation: out[item][r][i][m] = in[item][i][pi_r(m)]
+__global__ __launch_bounds__(EW_THREADS) void automorphism_bcast_kernel(const u64d *in, unsigned long long in_item_stride, u64d *out,
+                                                                        HoistArgs A, size_t total) {
+    const size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const unsigned N = 1u << A.logN;
+    const size_t row = w >> A.logN;
+    const unsigned m = (unsigned)(w & (N - 1));
+    const unsigned i = (unsigned)(row % (size_t)A.level);
+    const size_t ir = row / (size_t)A.level;
+    const unsigned r = (unsigned)(ir % (size_t)A.R);
+    const size_t item = ir / (size_t)A.R;
+    out[w] = in[item * in_item_stride + (size_t)i * N + automorphism_source(m, A.g[r], A.logN)];
+}
+
 // ---------------------------------------------------------------- conv / FC multiply-accumulate
 // Weights prepared per limb: wtab[i][widx] = (w mod q_i balanced, that / q_i)
 __global__ __launch_bounds__(EW_THREADS) void mac_prepare_kernel(const long long *w, WMul *wtab, const ModConst *modc, int level,

@@ -260,6 +260,39 @@ def case_rotate(be, shape, seed, rotations, batch=4, level=None):
     ctx.close()
 
 
+def case_rotate_hoisted(be, shape, seed, rotations, batch=3, level=None, small_ws=False):
+    """every item through every rotation with one shared ModUp, word for word against the oracle's definition of it"""
+    M = make_material(shape, seed, rotations=rotations)
+    O = M.O
+    ctx = be.context(*shape)
+    level = level or O.n_q
+    keys = {r: be.to_dev(M.gk[r]) for r in rotations}
+    for r in rotations:
+        ctx.galois_key_register(r, keys[r])
+    a = random_cts(M, level, batch, seed, "hoist")
+    da = be.to_dev(a)
+    R = len(rotations)
+    out = be.empty(batch, R, 2, level, O.N)
+    nbytes = ctx.rotate_hoisted_workspace_bytes(level, batch, R)
+    if small_ws and batch > 1:
+        nbytes = nbytes // batch + 8  # one item per sweep
+    ws = be.ws(nbytes)
+    ctx.rotate_hoisted(da, list(rotations), out, level, batch, ws, stream=be.stream)
+    got = be.to_host(out).reshape(batch, R, 2, level, O.N)
+    for i in range(batch):
+        want = O.rotate_hoisted(a[i], rotations, [M.gk[r] for r in rotations], level)
+        for k, r in enumerate(rotations):
+            assert np.array_equal(got[i, k], want[k]), "hoisted rotation of item %d by %d differs" % (i, r)
+    half = O.N // 2
+    missing = next(r for r in range(1, half) if all((q - r) % half for q in rotations))
+    try:
+        ctx.rotate_hoisted(da, [missing], out, level, batch, ws, stream=be.stream)
+        raise AssertionError("missing key not reported")
+    except ckksmi.CkksmiError as e:
+        assert e.code == ckksmi.ENOKEY
+    ctx.close()
+
+
 def mfma_enabled():
     import os
     return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"

@@ -147,6 +147,26 @@ def test_emulated_merged_product_other_sizes(be, monkeypatch, logN):
     pc.case_merged_product(be, (logN, 3, 50, 2, 51, 2), seed=125, batch=2, levels=[3, 2])
 
 
+@pytest.mark.parametrize("shape,level", [(TINY, 3), (HYBRID, 4), (HYBRID3, 5)])
+def test_emulated_hoisted_rotations_small_sizes(be, shape, level):
+    pc.case_rotate_hoisted(be, shape, seed=126, rotations=(1, 3, 6), level=level)
+    if shape == HYBRID:
+        pc.case_rotate_hoisted(be, shape, seed=127, rotations=(2, 5), level=5, small_ws=True)
+
+
+@pytest.mark.parametrize("env", [{}, {"CKKSMI_FUSE": "0"}, {"CKKSMI_FUSE": "14"}, {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_INV": "0"},
+                                 {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_HOIST_GATHER": "1"}])
+def test_emulated_hoisted_rotations_at_2e13(be, monkeypatch, env):
+    """register-tiled sizes: shared ModUp through the fused conversion kernels (or their alternatives), gathered inner product"""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    pc.case_rotate_hoisted(be, (13, 3, 50, 2, 51, 2), seed=128, rotations=(1, 100, 4095), batch=2, level=3)
+    if not env:
+        # more items than one workgroup stages (64 KiB of LDS: 32 digit rows), ragged last chunk; N = 256: a single run
+        pc.case_rotate_hoisted(be, (9, 9, 40, 1, 41, 1), seed=129, rotations=(1, 77), batch=5, level=9)
+        pc.case_rotate_hoisted(be, (8, 2, 40, 1, 41, 1), seed=130, rotations=(3,), batch=2, level=2)
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

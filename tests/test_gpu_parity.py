@@ -272,6 +272,51 @@ def test_merged_product_full_size_sampled_and_decrypts(be):
     assert np.max(np.abs(dec - za * zb)) < 1e-3
 
 
+@pytest.mark.parametrize("shape,level,rotations,batch", [
+    (TINY, 3, (1, 2, 100, 2047), 3),
+    ((9, 7, 50, 3, 51, 3), 5, (1, 3, 255), 2),
+    ((13, 3, 50, 1, 51, 1), 3, (5, 9), 3),
+    ((14, 8, 50, 1, 51, 1), 8, (1, 7, 300, 4000, 8191), 2),
+    ((16, 4, 50, 3, 51, 3), 4, (1, 2, 77), 2),
+    ((17, 2, 50, 1, 51, 1), 2, (3, 11), 1),
+])
+def test_hoisted_rotations_match_oracle(be, shape, level, rotations, batch):
+    """several rotations of each ciphertext from one shared ModUp: every word against the oracle's definition"""
+    announce("hoisted rotations %r level %d offsets %r" % (shape, level, rotations))
+    pc.case_rotate_hoisted(be, shape, seed=330, rotations=rotations, batch=batch, level=level)
+
+
+@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "14"}, {"CKKSMI_MODUP_LOOP": "0"},
+                                 {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_HOIST_GATHER": "1"}])
+def test_hoisted_rotations_alternative_paths(be, monkeypatch, env):
+    announce("hoisted rotations, alternative paths %r" % (env,))
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    pc.case_rotate_hoisted(be, (14, 3, 50, 2, 51, 2), seed=331, rotations=(1, 6, 1000), batch=3, level=3)
+    pc.case_rotate_hoisted(be, (10, 5, 40, 2, 41, 2), seed=332, rotations=(2, 5), batch=4, level=5, small_ws=True)
+
+
+def test_hoisted_rotations_decrypt_to_rotated_slots(be):
+    """N=2^14, 8 limbs: 8 rotations of encrypted vectors decrypt to the rotated vectors within 1e-3 at scale 2^40"""
+    announce("hoisted rotations N=2^14 decrypt")
+    p = wl.PRESETS["hmul_rot_2e14"]
+    rots = wl.rotation_offsets(p.N // 2, 8, 2)
+    M = pc.make_material(C2, 2, rotations=rots)
+    ctx = be.context(*C2)
+    keys = [be.to_dev(M.gk[r]) for r in rots]
+    for r, k in zip(rots, keys):
+        ctx.galois_key_register(r, k)
+    level, scale = 8, 2.0 ** p.log_scale
+    z = wl.slots_complex(M.N // 2, 2, "hz")
+    ct = M.encrypt(z, scale, level, "hz")
+    out = be.empty(1, len(rots), 2, level, M.N)
+    ws = be.ws(ctx.rotate_hoisted_workspace_bytes(level, 1, len(rots)))
+    ctx.rotate_hoisted(be.to_dev(ct[None]), rots, out, level, 1, ws)
+    got = be.to_host(out).reshape(len(rots), 2, level, M.N)
+    for k, r in enumerate(rots):
+        assert np.max(np.abs(M.decrypt(got[k], scale, level) - np.roll(z, -r))) < 1e-3
+
+
 def _device_residues(torch, q_list, lead, N, seed):
     """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
     g = torch.Generator(device="cuda:0")
