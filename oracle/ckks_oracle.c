@@ -602,6 +602,34 @@ void orc_hmul_relin_rescale(const orc_params *P, const u64 *a, const u64 *b, con
 }
 
 /*
+ * Lazy relinearisation: the sum of `terms` products is relinearised and rescaled
+ * ONCE, out = Rescale(Relin(sum_t Tensor(a_t, b_t))), the three-component tensors
+ * added limb-wise mod q_i.  a, b: [terms][2][level][N]; out: [2][level-1][N].
+ * Not the bits of summing separately relinearised products (one key-switch and one
+ * rounding error instead of `terms` of each); with terms = 1 it is
+ * orc_hmul_relin_rescale.
+ */
+void orc_hmul_sum_relin_rescale(const orc_params *P, const u64 *a, const u64 *b, int terms, const u64 *rlk, int level, u64 *out) {
+    u64 N = P->N;
+    size_t ct_words = (size_t)2 * level * N;
+    u64 *d = (u64 *)calloc((size_t)3 * level * N, 8);
+    u64 *dt = (u64 *)malloc((size_t)3 * level * N * 8);
+    u64 *r = (u64 *)malloc((size_t)2 * level * N * 8);
+    for (int t = 0; t < terms; t++) {
+        orc_tensor(P, a + (size_t)t * ct_words, b + (size_t)t * ct_words, level, dt);
+        for (int c = 0; c < 3; c++)
+            for (int i = 0; i < level; i++) {
+                u64 q = P->mod[i];
+                size_t o = ((size_t)c * level + i) * N;
+                for (u64 n = 0; n < N; n++) d[o + n] = orc_addmod(d[o + n], dt[o + n], q);
+            }
+    }
+    orc_relin(P, d, rlk, level, r);
+    orc_rescale(P, r, level, out);
+    free(d); free(dt); free(r);
+}
+
+/*
  * The same product with ONE division: the key-switch accumulators stay over the
  * extended basis, P*(d0, d1) is added there (zero on the special limbs), and both
  * components are divided by P*q_{level-1} in a single DivRound over

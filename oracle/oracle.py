@@ -217,6 +217,7 @@ class Oracle:
             "orc_rescale": [V, u64p, I, u64p],
             "orc_hmul_relin_rescale": [V, u64p, u64p, u64p, I, u64p],
             "orc_hmul_relin_rescale_merged": [V, u64p, u64p, u64p, I, u64p],
+            "orc_hmul_sum_relin_rescale": [V, u64p, u64p, I, u64p, I, u64p],
             "orc_rotate": [V, u64p, C.c_uint64, u64p, I, u64p],
             "orc_rotate_hoisted": [V, u64p, I, I, u64p, u64p, u64p],
             "orc_add": [V, u64p, u64p, I, u64p],
@@ -368,6 +369,14 @@ class Oracle:
     def hmul_relin_rescale(self, a, b, rlk, level):
         out = np.empty((2, level - 1, self.N), dtype=np.uint64)
         self._L.orc_hmul_relin_rescale(self._h, _p64(_u64(a)), _p64(_u64(b)), _p64(_u64(rlk)), level, _p64(out))
+        return out
+
+    def hmul_sum_relin_rescale(self, a, b, rlk, level):
+        """sum over the leading axis of a, b ([terms][2][level][N]) of the products, relinearised and rescaled once"""
+        a, b = np.ascontiguousarray(_u64(a)), np.ascontiguousarray(_u64(b))
+        assert a.shape == b.shape and a.shape[1:] == (2, level, self.N)
+        out = np.empty((2, level - 1, self.N), dtype=np.uint64)
+        self._L.orc_hmul_sum_relin_rescale(self._h, _p64(a), _p64(b), a.shape[0], _p64(_u64(rlk)), level, _p64(out))
         return out
 
     def hmul_relin_rescale_merged(self, a, b, rlk, level):

@@ -506,6 +506,38 @@ def test_merged_division_decrypts_to_product():
         assert np.max(np.abs(got - za * zb)) < 1e-6
 
 
+def test_lazy_relinearisation_decrypts_to_the_sum_of_products():
+    """one relinearisation and one rescale for a sum of products: decrypts to sum_t a_t*b_t, has the noise of ONE key
+    switch (not worse than the sum of separately relinearised products), and with one term is the plain product"""
+    M = Material(8, 6, 50, 3, 51, 3, seed=45)
+    O = M.O
+    scale, level, terms = 2.0**50, 5, 4
+    za = [wl.slots_real(M.N // 2, 45, ("a", t)) for t in range(terms)]
+    zb = [wl.slots_real(M.N // 2, 45, ("b", t)) for t in range(terms)]
+    a = np.stack([M.encrypt(za[t], scale, level, ("a", t)) for t in range(terms)])
+    b = np.stack([M.encrypt(zb[t], scale, level, ("b", t)) for t in range(terms)])
+    want = sum(x * y for x, y in zip(za, zb))
+    out = O.hmul_sum_relin_rescale(a, b, M.rlk, level)
+    s_out = scale * scale / O.q[level - 1]
+    err_lazy = np.max(np.abs(M.decrypt(out, s_out, level - 1) - want))
+    sep = O.hmul_relin_rescale(a[0], b[0], M.rlk, level)
+    for t in range(1, terms):
+        sep = O.add(sep, O.hmul_relin_rescale(a[t], b[t], M.rlk, level), level - 1)
+    err_sep = np.max(np.abs(M.decrypt(sep, s_out, level - 1) - want))
+    assert err_lazy < 1e-6 and err_lazy < 2 * err_sep + 1e-9
+    assert not np.array_equal(out, sep)
+    assert np.array_equal(O.hmul_sum_relin_rescale(a[:1], b[:1], M.rlk, level), O.hmul_relin_rescale(a[0], b[0], M.rlk, level))
+    # the tensors add limb-wise: the decrypted polynomial of the summed tensor is the sum of the products' (mod Q)
+    Q = math.prod(O.q[:level])
+    d_sum = [0] * O.N
+    for t in range(terms):
+        d_sum = [(x + y) % Q for x, y in zip(d_sum, M.decrypt_poly(O.tensor(a[t], b[t], level), level))]
+    lazy_unrescaled = O.relin(np.stack([O.tensor(a[t], b[t], level) for t in range(terms)]).astype(object).sum(axis=0) % np.array(O.q[:level], dtype=object)[None, :, None], M.rlk, level)
+    got = M.decrypt_poly(lazy_unrescaled, level)
+    worst = max(abs(((x - y + Q // 2) % Q) - Q // 2) for x, y in zip(got, d_sum))
+    assert worst < 2**40  # key-switch noise only (Q is 250 bits)
+
+
 def test_hybrid_keyswitch_alpha3_end_to_end():
     M = Material(8, 6, 50, 3, 51, 3, seed=18, rotations=(3,))
     scale = 2.0**50
