@@ -142,6 +142,14 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     out["merged_division_2e16"] = {"ops_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 3),
                                    "what": "HMult + key switch + ONE exact division by P*q_last, batch 64, level 24 -> 23"}
     del om
+    # a sum of 4 products relinearised and rescaled once (lazy relinearisation; the same ciphertexts serve as every term)
+    terms = 4
+    at = a.unsqueeze(1).expand(B, terms, 2, L, N).contiguous()
+    os_ = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: ctx.hmul_sum_relin_rescale(at, at, terms, evk, os_, L, B, ws), 3)
+    out["sum_of_4_products_2e16"] = {"sums_per_s": round(B / (ms * 1e-3), 1), "products_per_s": round(B * terms / (ms * 1e-3), 1), "ms": round(ms, 3),
+                                     "what": "sum of 4 HMult tensors, ONE key switch and rescale, batch 64, level 24 -> 23"}
+    del at, os_
 
     # N = 2^14, 8x50-bit + special prime: batch 256, HMult+relin+rescale and rotations by 8 random offsets
     p2 = wl.PRESETS["hmul_rot_2e14"]

@@ -158,6 +158,12 @@ int ckksmi_relin(ckksmi_ctx *ctx, const uint64_t *d, const uint64_t *evk, uint64
 int ckksmi_rescale(ckksmi_ctx *ctx, const uint64_t *a, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* the strict sequence hmul -> relin -> rescale, bit-identical to the three calls */
 int ckksmi_hmul_relin_rescale(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out /*[2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* Lazy relinearisation (a fewer-transform variant for sums of products; the paper fixes no order): item i holds `terms`
+ * pairs, a, b: device [batch][terms][2][level][N]; the three-component tensors of the pairs are added limb-wise and
+ * the sum is relinearised and rescaled ONCE, out_i = Rescale(Relin(sum_t Tensor(a_it, b_it))): one key switch instead of
+ * `terms`.  Not the bits of adding separately relinearised products; terms = 1 is ckksmi_hmul_relin_rescale.
+ * Workspace and errors as ckksmi_hmul_relin_rescale; CKKSMI_EINVAL for terms < 1. */
+int ckksmi_hmul_sum_relin_rescale(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, int terms, const uint64_t *evk, uint64_t *out /*[batch][2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* The same product with ONE division instead of ModDown followed by rescale (a fewer-transform variant of the
  * multiplication of section 2.1; the paper fixes no order): the key-switch accumulators stay over the extended basis,
  * P*(d0, d1) joins them there, and both components are divided by P*q_{level-1} at once,

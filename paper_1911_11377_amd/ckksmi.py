@@ -71,6 +71,7 @@ SIGNATURES = {
     "ckksmi_rescale": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_hmul_sum_relin_rescale": [VP, VP, VP, C.c_int, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rotate_hoisted": [VP, VP, intp, C.c_int, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rotate_hoisted_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_rotate": [VP, VP, intp, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
@@ -325,6 +326,11 @@ class Context:
         """every item rotated by every offset in rots with one shared ModUp; out [batch][len(rots)][2][level][N]"""
         r = np.ascontiguousarray(rots, dtype=np.int32)
         self._call("ckksmi_rotate_hoisted", self._h, _ptr(a), r.ctypes.data_as(intp), len(r), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
+                   self._stream(stream))
+
+    def hmul_sum_relin_rescale(self, a, b, terms, evk, out, level, batch, ws, stream=None):
+        """a, b: [batch][terms][2][level][N]; the sum of each item's products, relinearised and rescaled once"""
+        self._call("ckksmi_hmul_sum_relin_rescale", self._h, _ptr(a), _ptr(b), terms, _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
                    self._stream(stream))
 
     def hmul_relin_rescale_merged(self, a, b, evk, out, level, batch, ws, stream=None):

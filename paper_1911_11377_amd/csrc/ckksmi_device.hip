@@ -630,15 +630,17 @@ void rescale_core(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u
     KL(c, CKKSMI_K_DIVFINAL, (double)items * 2 * DF.nc, divround_final_kernel, dim3(ew_blocks(N), level - 1, items * 2), dim3(EW_THREADS), st, DF);
 }
 
-void launch_tensor(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, int level, int items, hipStream_t st) {
+// terms > 1: a, b hold [items][terms][2][level][N] and d receives the sum of the terms' tensors
+void launch_tensor(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, int level, int items, hipStream_t st, int terms = 1) {
     const size_t total = (size_t)items * level * c->N / 2;  // word pairs
-    KL(c, CKKSMI_K_TENSOR, (double)items * level, tensor_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)a, (const u64d *)b, (u64d *)d, c->d_mod,
-                  c->logN, level, total);
+    KL(c, CKKSMI_K_TENSOR, (double)items * level * terms, tensor_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)a, (const u64d *)b, (u64d *)d, c->d_mod,
+                  c->logN, level, total, terms);
 }
 
 // tensor product + inverse row pass of d2 into ymid (see tensor_rows_kernel); register-tiled sizes only
-void launch_tensor_rows(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, u64 *ymid, int level, int items, hipStream_t st) {
+void launch_tensor_rows(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, u64 *ymid, int level, int items, hipStream_t st, int terms = 1) {
     TensorRowsArgs A;
+    A.terms = terms;
     A.a = (const u64d *)a; A.b = (const u64d *)b; A.d = (u64d *)d; A.ymid = (u64d *)ymid; A.modc = c->d_mod; A.tw_inv = c->d_tww_inv;
     A.logN = c->logN; A.level = level; A.p51 = c->p51mask;
     KL(c, CKKSMI_K_TENSOR_ROWS, (double)items * level, tensor_rows_kernel, dim3((unsigned)(c->N / 4096), level, items), dim3(V2_THREADS), st, A);
@@ -1012,9 +1014,10 @@ extern "C" int ckksmi_rescale(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, i
 }
 
 static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level, int batch,
-                                  void *ws, size_t ws_bytes, void *stream, bool merged) {
+                                  void *ws, size_t ws_bytes, void *stream, bool merged, int terms = 1) {
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
+    if (terms < 1) return CKKSMI_EINVAL;
     if (c->k == 0 || (merged && !c->d_pmod)) return CKKSMI_EUNSUPPORTED;
     if (level < 2) return CKKSMI_ELEVEL;
     if (!a || !b || !evk || !out || (!ws && batch) || !al16(a) || !al16(b) || !al16(evk) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
@@ -1036,10 +1039,11 @@ static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint6
         // the tensor kernel can take d2 through the inverse row pass on the way (its output lands where the key switch
         // expects it: the start of its workspace)
         const bool trows = c->fused && c->fuse_tensor && (c->fuse & FUSE_MODUP) && c->modup_loop && c->fuse_inv;
+        const size_t in0 = (size_t)b0 * terms * 2 * level * N;
         if (trows)
-            launch_tensor_rows(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, rest, level, items, S(stream));
+            launch_tensor_rows(c, a + in0, b + in0, d, rest, level, items, S(stream), terms);
         else
-            launch_tensor(c, a + (size_t)b0 * 2 * level * N, b + (size_t)b0 * 2 * level * N, d, level, items, S(stream));
+            launch_tensor(c, a + in0, b + in0, d, level, items, S(stream), terms);
         if (merged) {
             // one division by P*q_{level-1} of (accumulators + P*(d0, d1))
             if (c->fused)
@@ -1072,6 +1076,11 @@ static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint6
 extern "C" int ckksmi_hmul_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level,
                                          int batch, void *ws, size_t ws_bytes, void *stream) {
     return hmul_relin_rescale_impl(c, a, b, evk, out, level, batch, ws, ws_bytes, stream, false);
+}
+
+extern "C" int ckksmi_hmul_sum_relin_rescale(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, int terms, const uint64_t *evk, uint64_t *out,
+                                             int level, int batch, void *ws, size_t ws_bytes, void *stream) {
+    return hmul_relin_rescale_impl(c, a, b, evk, out, level, batch, ws, ws_bytes, stream, false, terms);
 }
 
 extern "C" int ckksmi_hmul_relin_rescale_merged(ckksmi_ctx *c, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out, int level,

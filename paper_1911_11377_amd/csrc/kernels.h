@@ -279,19 +279,35 @@ __device__ __forceinline__ void tensor_word(double a0, double a1, double b0, dou
     d1 = d2u(canon(mulmod(a0, b1, mc.p, mc.pinv) + mulmod(a1, b0, mc.p, mc.pinv), mc.p, mc.pinv));
     d2 = d2u(canon(mulmod(a1, b1, mc.p, mc.pinv), mc.p, mc.pinv));
 }
+// terms > 1: d = sum over t of the tensors of (a_t, b_t), items laid out [batch][terms][2][level][N] (lazy relinearisation)
+__device__ __forceinline__ void tensor_accumulate(u64d &acc, u64d v, double p) {
+    const double s = u2d(acc) + u2d(v);
+    acc = d2u(s >= p ? s - p : s);
+}
 __global__ __launch_bounds__(EW_THREADS) void tensor_kernel(const u64d *a, const u64d *b, u64d *d, const ModConst *modc, int logN,
-                                                            int level, size_t total /* batch*level*N/2 */) {
+                                                            int level, size_t total /* batch*level*N/2 */, int terms) {
     const size_t pr = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
     if (pr >= total) return;
     const size_t N = (size_t)1 << logN, w = 2 * pr;
     const size_t limb = w >> logN, item = limb / level, i = limb % level, n = w & (N - 1);
     const ModConst mc = modc[i];
-    const size_t ia = (item * 2 * level + i) * N + n, st = (size_t)level * N;
-    const ulonglong2 A0 = *(const ulonglong2 *)(a + ia), A1 = *(const ulonglong2 *)(a + ia + st);
-    const ulonglong2 B0 = *(const ulonglong2 *)(b + ia), B1 = *(const ulonglong2 *)(b + ia + st);
+    const size_t st = (size_t)level * N;
     ulonglong2 D0, D1, D2;
-    tensor_word(u2d(A0.x), u2d(A1.x), u2d(B0.x), u2d(B1.x), mc, D0.x, D1.x, D2.x);
-    tensor_word(u2d(A0.y), u2d(A1.y), u2d(B0.y), u2d(B1.y), mc, D0.y, D1.y, D2.y);
+    for (int t = 0; t < terms; t++) {
+        const size_t ia = ((item * terms + t) * 2 * level + i) * N + n;
+        const ulonglong2 A0 = *(const ulonglong2 *)(a + ia), A1 = *(const ulonglong2 *)(a + ia + st);
+        const ulonglong2 B0 = *(const ulonglong2 *)(b + ia), B1 = *(const ulonglong2 *)(b + ia + st);
+        ulonglong2 T0, T1, T2;
+        tensor_word(u2d(A0.x), u2d(A1.x), u2d(B0.x), u2d(B1.x), mc, T0.x, T1.x, T2.x);
+        tensor_word(u2d(A0.y), u2d(A1.y), u2d(B0.y), u2d(B1.y), mc, T0.y, T1.y, T2.y);
+        if (t == 0) {
+            D0 = T0; D1 = T1; D2 = T2;
+        } else {
+            tensor_accumulate(D0.x, T0.x, mc.p); tensor_accumulate(D0.y, T0.y, mc.p);
+            tensor_accumulate(D1.x, T1.x, mc.p); tensor_accumulate(D1.y, T1.y, mc.p);
+            tensor_accumulate(D2.x, T2.x, mc.p); tensor_accumulate(D2.y, T2.y, mc.p);
+        }
+    }
     const size_t id = (item * 3 * level + i) * N + n;
     *(ulonglong2 *)(d + id) = D0;
     *(ulonglong2 *)(d + id + st) = D1;

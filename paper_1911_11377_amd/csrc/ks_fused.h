@@ -36,6 +36,7 @@ struct TensorRowsArgs {
     const ModConst *modc;
     const double *tw_inv;
     int logN, level;
+    int terms;           // > 1: a, b hold [items][terms][2][level][N] and d is the sum of the terms' tensors
     P51Mask p51;
 };
 
@@ -49,8 +50,8 @@ __device__ __forceinline__ void tensor_rows_body(const TensorRowsArgs &A, double
     const size_t tile0 = (size_t)blockIdx.x * 4096, st = (size_t)A.level * N;
     double tw1[15], tw2[15];
     load_twiddles(A.tw_inv + (size_t)i * N, N1 + blockIdx.x * 16 + hi4, lo4, tw1, tw2);
-    const ulonglong2 *a0 = (const ulonglong2 *)(A.a + ((size_t)item * 2 * A.level + i) * N + tile0), *a1 = a0 + st / 2;
-    const ulonglong2 *b0 = (const ulonglong2 *)(A.b + ((size_t)item * 2 * A.level + i) * N + tile0), *b1 = b0 + st / 2;
+    const ulonglong2 *a0 = (const ulonglong2 *)(A.a + ((size_t)item * A.terms * 2 * A.level + i) * N + tile0), *a1 = a0 + st / 2;
+    const ulonglong2 *b0 = (const ulonglong2 *)(A.b + ((size_t)item * A.terms * 2 * A.level + i) * N + tile0), *b1 = b0 + st / 2;
     ulonglong2 *d0 = (ulonglong2 *)(A.d + ((size_t)item * 3 * A.level + i) * N + tile0), *d1 = d0 + st / 2, *d2 = d1 + st / 2;
     // word pairs (512*s + 2*tid, +1), four at a time to bound the registers in flight
 #pragma unroll
@@ -62,16 +63,37 @@ __device__ __forceinline__ void tensor_rows_body(const TensorRowsArgs &A, double
             A0[s] = a0[e]; A1[s] = a1[e]; B0[s] = b0[e]; B1[s] = b1[e];
         }
         SCHED_FENCE();
+        ulonglong2 D0[4], D1[4], D2[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            tensor_word(u2d(A0[s].x), u2d(A1[s].x), u2d(B0[s].x), u2d(B1[s].x), mc, D0[s].x, D1[s].x, D2[s].x);
+            tensor_word(u2d(A0[s].y), u2d(A1[s].y), u2d(B0[s].y), u2d(B1[s].y), mc, D0[s].y, D1[s].y, D2[s].y);
+        }
+        for (int t = 1; t < A.terms; t++) {  // further terms of a sum of products
+            const size_t to = (size_t)t * st;  // 2*level*N words = st ulonglong2
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const unsigned e = 256u * (4 * h + s) + tid;
+                A0[s] = a0[to + e]; A1[s] = a1[to + e]; B0[s] = b0[to + e]; B1[s] = b1[to + e];
+            }
+            SCHED_FENCE();
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                ulonglong2 T0, T1, T2;
+                tensor_word(u2d(A0[s].x), u2d(A1[s].x), u2d(B0[s].x), u2d(B1[s].x), mc, T0.x, T1.x, T2.x);
+                tensor_word(u2d(A0[s].y), u2d(A1[s].y), u2d(B0[s].y), u2d(B1[s].y), mc, T0.y, T1.y, T2.y);
+                tensor_accumulate(D0[s].x, T0.x, p); tensor_accumulate(D0[s].y, T0.y, p);
+                tensor_accumulate(D1[s].x, T1.x, p); tensor_accumulate(D1[s].y, T1.y, p);
+                tensor_accumulate(D2[s].x, T2.x, p); tensor_accumulate(D2[s].y, T2.y, p);
+            }
+        }
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             const unsigned e = 256u * (4 * h + s) + tid;
-            ulonglong2 D0, D1, D2;
-            tensor_word(u2d(A0[s].x), u2d(A1[s].x), u2d(B0[s].x), u2d(B1[s].x), mc, D0.x, D1.x, D2.x);
-            tensor_word(u2d(A0[s].y), u2d(A1[s].y), u2d(B0[s].y), u2d(B1[s].y), mc, D0.y, D1.y, D2.y);
-            d0[e] = D0; d1[e] = D1; d2[e] = D2;
+            d0[e] = D0[s]; d1[e] = D1[s]; d2[e] = D2[s];
             double *rr = lds + (2 * (4 * h + s) + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
-            rr[0] = u2d(D2.x);
-            rr[1] = u2d(D2.y);
+            rr[0] = u2d(D2[s].x);
+            rr[1] = u2d(D2[s].y);
         }
     }
     __syncthreads();

@@ -260,6 +260,24 @@ def case_rotate(be, shape, seed, rotations, batch=4, level=None):
     ctx.close()
 
 
+def case_sum_of_products(be, shape, seed, terms, batch=2, levels=None):
+    """one relinearisation and rescale for a sum of products, word for word against the oracle"""
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    evk = be.to_dev(M.rlk)
+    for level in levels or [O.n_q]:
+        a = wl.uniform_limbs(O.q[:level], O.N, seed, ("sa", level), lead=(batch, terms, 2))
+        b = wl.uniform_limbs(O.q[:level], O.N, seed, ("sb", level), lead=(batch, terms, 2))
+        out = be.empty(batch, 2, level - 1, O.N)
+        ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+        ctx.hmul_sum_relin_rescale(be.to_dev(a), be.to_dev(b), terms, evk, out, level, batch, ws, stream=be.stream)
+        got = be.to_host(out).reshape(batch, 2, level - 1, O.N)
+        for i in range(batch):
+            assert np.array_equal(got[i], O.hmul_sum_relin_rescale(a[i], b[i], M.rlk, level)), "sum of products differs at level %d item %d" % (level, i)
+    ctx.close()
+
+
 def case_rotate_hoisted(be, shape, seed, rotations, batch=3, level=None, small_ws=False):
     """every item through every rotation with one shared ModUp, word for word against the oracle's definition of it"""
     M = make_material(shape, seed, rotations=rotations)

@@ -167,6 +167,14 @@ def test_emulated_hoisted_rotations_at_2e13(be, monkeypatch, env):
         pc.case_rotate_hoisted(be, (8, 2, 40, 1, 41, 1), seed=130, rotations=(3,), batch=2, level=2)
 
 
+def test_emulated_sum_of_products(be, monkeypatch):
+    """lazy relinearisation: the tensor kernels accumulate the terms (elementwise kernel, and the one fused with the row pass)"""
+    pc.case_sum_of_products(be, HYBRID, seed=131, terms=3, levels=[5, 2])
+    pc.case_sum_of_products(be, (13, 3, 50, 2, 51, 2), seed=132, terms=4, batch=2, levels=[3])
+    monkeypatch.setenv("CKKSMI_FUSE_TENSOR", "0")
+    pc.case_sum_of_products(be, (13, 3, 50, 2, 51, 2), seed=133, terms=2, batch=1, levels=[3])
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

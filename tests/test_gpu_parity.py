@@ -317,6 +317,19 @@ def test_hoisted_rotations_decrypt_to_rotated_slots(be):
         assert np.max(np.abs(M.decrypt(got[k], scale, level) - np.roll(z, -r))) < 1e-3
 
 
+@pytest.mark.parametrize("shape,levels,terms,batch", [
+    (TINY, [3, 2], 5, 2),
+    ((10, 5, 40, 2, 41, 2), [5, 3], 3, 3),
+    ((14, 3, 50, 2, 51, 2), [3], 4, 2),
+    ((16, 4, 50, 3, 51, 3), [4], 7, 2),
+    ((17, 2, 50, 1, 51, 1), [2], 2, 1),
+])
+def test_sum_of_products_matches_oracle(be, shape, levels, terms, batch):
+    """lazy relinearisation: sum of `terms` tensors, one key switch and one rescale"""
+    announce("sum of %d products %r levels %r" % (terms, shape, levels))
+    pc.case_sum_of_products(be, shape, seed=340, terms=terms, batch=batch, levels=levels)
+
+
 def _device_residues(torch, q_list, lead, N, seed):
     """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
     g = torch.Generator(device="cuda:0")
