@@ -412,6 +412,20 @@ class Oracle:
         self._L.orc_rotate_hoisted(self._h, _p64(_u64(ct)), level, len(rots), _p64(g), _p64(keys), _p64(out))
         return out
 
+    def linear_transform(self, x, diag_pts, gks, level):
+        """One ciphertext whose slots hold a vector z (the single-image, rotation-packed layout), times a matrix given by
+        its generalised diagonals: out = Rescale( sum_d pt_d * Rot_d(x) ), pt_d the encoded d-th diagonal ([level][N],
+        evaluation form) and Rot_d the rotation by d slots taken from ONE shared ModUp (rotate_hoisted); d = 0 needs no
+        rotation.  Decrypts to sum_d diag_d * roll(z, -d) = M z at scale s * s_pt / q_{level-1}.  level -> level-1."""
+        acc = None
+        rots = sorted(d for d in diag_pts if d != 0)
+        rotated = self.rotate_hoisted(x, rots, [gks[d] for d in rots], level) if rots else []
+        for d in sorted(diag_pts):
+            src = _u64(x) if d == 0 else rotated[rots.index(d)]
+            term = self.mul_plain(src, diag_pts[d], level)
+            acc = term if acc is None else self.add(acc, term, level)
+        return self.rescale(acc, level)
+
     def add(self, a, b, level):
         out = np.empty((2, level, self.N), dtype=np.uint64)
         self._L.orc_add(self._h, _p64(_u64(a)), _p64(_u64(b)), level, _p64(out))
@@ -649,6 +663,40 @@ def slot_exponents(logN):
         out.append(e)
         e = (e * 5) % (2 * N)
     return out
+
+
+def matrix_diagonals(M, n_slots):
+    """Generalised diagonals of a square matrix M (n x n, n dividing n_slots) for a slot vector that repeats z with
+    period n: diag_d[i] = M[i mod n][(i + d) mod n], so that M z = sum_d diag_d * roll(z, -d).  Zero diagonals are
+    left out.  Returns {d: vector of n_slots values}."""
+    M = np.asarray(M, dtype=np.float64)
+    n = M.shape[0]
+    assert M.shape == (n, n) and n_slots % n == 0
+    out = {}
+    for d in range(n):
+        diag = np.array([M[i][(i + d) % n] for i in range(n)])
+        if np.any(diag != 0.0):
+            out[d] = np.tile(diag, n_slots // n)
+    return out
+
+
+def conv_as_matrix(w, H, W, pad):
+    """The stride-1 convolution of a C x H x W image (flattened channel-major) with weights w [O][C][kh][kw] and zero
+    padding `pad`, output O x H' x W', written as a dense matrix [O*H'*W'][C*H*W] straight from the definition."""
+    w = np.asarray(w, dtype=np.float64)
+    O, C, kh, kw = w.shape
+    Ho, Wo = H + 2 * pad - kh + 1, W + 2 * pad - kw + 1
+    M = np.zeros((O * Ho * Wo, C * H * W))
+    for o in range(O):
+        for y in range(Ho):
+            for x in range(Wo):
+                for c in range(C):
+                    for u in range(kh):
+                        for v in range(kw):
+                            iy, ix = y + u - pad, x + v - pad
+                            if 0 <= iy < H and 0 <= ix < W:
+                                M[(o * Ho + y) * Wo + x][(c * H + iy) * W + ix] += w[o][c][u][v]
+    return M
 
 
 def encode_direct(z, scale, logN):

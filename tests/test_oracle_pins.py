@@ -600,6 +600,65 @@ def test_hoisted_rotations_decrypt_to_rotated_slots_with_keyswitch_noise_only(sh
     assert not np.array_equal(outs[0], O.rotate(ct, rots[0], M.gk[rots[0]], level))  # a different lift: other bits
 
 
+def _square_pad(M):
+    n = 1
+    while n < max(M.shape):
+        n *= 2
+    out = np.zeros((n, n))
+    out[: M.shape[0], : M.shape[1]] = M
+    return out
+
+
+def _packed_layer(M_, shape, seed, scale_bits=30):
+    """encrypt a vector replicated over the slots, apply the matrix through rotations, decrypt"""
+    Mt = Material(*shape, seed=seed)
+    O = Mt.O
+    level, n_slots = O.n_q, O.N // 2
+    Msq = _square_pad(np.asarray(M_, dtype=np.float64))
+    n = Msq.shape[0]
+    diags = orc.matrix_diagonals(Msq, n_slots)
+    Mt = Material(*shape, seed=seed, rotations=tuple(d for d in diags if d))
+    O = Mt.O
+    z = np.zeros(n)
+    z[: M_.shape[1]] = wl.slots_real(n, seed, "vec").real[: M_.shape[1]]
+    scale = 2.0**scale_bits
+    x = Mt.encrypt(np.tile(z, n_slots // n).astype(complex), scale, level, "vec")
+    pts = {d: Mt.encode(v.astype(complex), float(O.q[level - 1]), level) for d, v in diags.items()}
+    out = O.linear_transform(x, pts, Mt.gk, level)
+    got = Mt.decrypt(out, scale, level - 1)
+    return got.real[:n], Msq @ z, diags
+
+
+def test_packed_fully_connected_layer_decrypts_to_matrix_vector_product():
+    """single-image packing: a dense 16x16 layer on one ciphertext through 15 rotations from one shared ModUp"""
+    W = wl.weights_float((16, 16), 46, "fc")
+    got, want, diags = _packed_layer(W, (6, 4, 40, 2, 41, 2), 46)
+    assert sorted(diags) == list(range(16))
+    assert np.max(np.abs(got - want)) < 1e-4
+    # a rectangular layer (10 outputs from 13 inputs) is the same thing zero-padded
+    W2 = wl.weights_float((10, 13), 47, "fc")
+    got, want, _ = _packed_layer(W2, (6, 4, 40, 2, 41, 2), 47)
+    assert np.max(np.abs(got[:10] - want[:10])) < 1e-4 and np.max(np.abs(got[10:])) < 1e-4
+
+
+def test_packed_convolution_decrypts_to_the_convolution():
+    """single-image packing: 2 -> 2 channels, 3x3, zero padding 1 on a 4x4 image in 32 slots; the matrix is sparse, only
+    its non-zero diagonals cost a rotation; checked against a direct convolution, not against the matrix"""
+    w = wl.weights_float((2, 2, 3, 3), 48, "conv")
+    Mc = orc.conv_as_matrix(w, 4, 4, 1)
+    got, want, diags = _packed_layer(Mc, (7, 4, 40, 2, 41, 2), 48)
+    assert len(diags) < 32
+    z = np.zeros(32)
+    z[:32] = wl.slots_real(32, 48, "vec").real
+    img = z.reshape(2, 4, 4)
+    padded = np.zeros((2, 6, 6))
+    padded[:, 1:5, 1:5] = img
+    direct = np.array([[[sum(w[o, c, u, v] * padded[c, y + u, x + v] for c in range(2) for u in range(3) for v in range(3))
+                         for x in range(4)] for y in range(4)] for o in range(2)]).reshape(-1)
+    assert np.max(np.abs(want - direct)) < 1e-12
+    assert np.max(np.abs(got - direct)) < 1e-4
+
+
 def test_elementwise_ops_on_decrypted_polynomials():
     M = Material(5, 3, 30, 1, 31, 1, seed=20)
     O = M.O
