@@ -180,6 +180,22 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     ms = timed(torch, lambda: c2.rotate_hoisted(a2, rots, oh, L, Bh, wh), 3)
     out["rotate_hoisted_2e14"] = {"ops_per_s": round(Bh * len(rots) / (ms * 1e-3), 1), "ms": round(ms, 3),
                                   "what": "%d ciphertexts x %d rotations each, one ModUp per ciphertext" % (Bh, len(rots))}
+    # one image, rotation-packed: a dense 64x64 layer on ONE ciphertext (63 hoisted rotations, plaintext diagonals, rescale)
+    import numpy as np
+    from paper_1911_11377_amd import packed
+    Wd = wl.weights_float((64, 64), 2, "packed.fc")
+    lay_keys = {}
+    for d in range(1, 64):
+        if d not in rots:
+            lay_keys[d] = uniform_residues(torch, c2.moduli, (c2.beta_top, 2), N, gen)
+            c2.galois_key_register(d, lay_keys[d])
+    to_dev = lambda arr: torch.from_numpy(np.ascontiguousarray(arr).view(np.int64)).to("cuda:0")
+    plan = packed.plan_linear(c2, Wd, L, to_dev)
+    wp = torch.empty(packed.workspace_bytes(c2, plan) // 8, dtype=torch.int64, device="cuda:0")
+    op = torch.empty((2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: packed.linear_transform(c2, a2[0], plan, op, wp), 3)
+    out["packed_fc64_2e14"] = {"ms_per_layer": round(ms, 3), "what": "64x64 dense layer on one ciphertext: 63 rotations from one ModUp per 16, level 8 -> 7"}
+    del lay_keys, wp, op, plan
     del a2, b2, k2, gks, o2, or2, w2, oh, wh
     c2.close()
 

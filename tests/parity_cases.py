@@ -311,6 +311,51 @@ def case_rotate_hoisted(be, shape, seed, rotations, batch=3, level=None, small_w
     ctx.close()
 
 
+def case_packed_layer(be, shape, seed, M_float, level=None):
+    """a rotation-packed layer (matrix through hoisted rotations, plaintext diagonals, tree of adds, rescale) against the
+    oracle's schedule, word for word; the encoded diagonals are inputs of both sides"""
+    from paper_1911_11377_amd import packed
+    probe = be.context(*shape)
+    level = level or probe.n_q
+    n_slots = probe.N // 2
+    probe.close()
+    Msq = packed.square_pad(M_float)
+    diags_lib = packed.matrix_diagonals(Msq, n_slots)
+    diags = orc.matrix_diagonals(Msq, n_slots)
+    assert sorted(diags) == sorted(diags_lib) and all(np.array_equal(diags[d], diags_lib[d]) for d in diags)
+    rots = tuple(d for d in sorted(diags) if d)
+    M = make_material(shape, seed, rotations=rots)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    keys = {r: be.to_dev(M.gk[r]) for r in rots}
+    for r in rots:
+        ctx.galois_key_register(r, keys[r])
+    n = Msq.shape[0]
+    z = np.tile(wl.slots_real(n, seed, "packed").real, n_slots // n).astype(np.complex128)
+    scale = 2.0 ** 30
+    x = M.encrypt(z, scale, level, "packed")
+    pts = {}
+
+    def encode(values, s, l):
+        pt = M.encode(values, s, l)
+        pts[len(pts)] = pt
+        return pt
+
+    plan = packed.plan_linear(ctx, M_float, level, be.to_dev, encode=encode)
+    order = ([] if plan.pt0 is None else [0])
+    by_d = dict(zip(list(plan.rotations) + order, [pts[i] for i in range(len(pts))]))
+    out = be.empty(2, level - 1, O.N)
+    ws = be.ws(packed.workspace_bytes(ctx, plan))
+    packed.linear_transform(ctx, be.to_dev(x), plan, out, ws, stream=be.stream)
+    got = be.to_host(out).reshape(2, level - 1, O.N)
+    want = O.linear_transform(x, by_d, M.gk, level)
+    assert np.array_equal(got, want), "packed layer differs from the oracle"
+    dec = M.decrypt(got, scale, level - 1).real[:n]
+    assert np.max(np.abs(dec - Msq @ z.real[:n])) < 1e-3
+    ctx.close()
+
+
 def mfma_enabled():
     import os
     return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"

@@ -175,6 +175,14 @@ def test_emulated_sum_of_products(be, monkeypatch):
     pc.case_sum_of_products(be, (13, 3, 50, 2, 51, 2), seed=133, terms=2, batch=1, levels=[3])
 
 
+def test_emulated_rotation_packed_layers(be):
+    """single-image packing: a dense layer (every diagonal, two chunks of rotations) and a sparse convolution matrix"""
+    from paper_1911_11377_amd import packed, workloads as wl
+    pc.case_packed_layer(be, (6, 3, 40, 2, 41, 2), 134, wl.weights_float((32, 20), 134, "fc"))
+    w = wl.weights_float((2, 2, 3, 3), 135, "conv")
+    pc.case_packed_layer(be, (7, 3, 40, 1, 41, 1), 135, packed.conv_matrix(w, 4, 4, 1))
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

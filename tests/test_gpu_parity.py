@@ -330,6 +330,19 @@ def test_sum_of_products_matches_oracle(be, shape, levels, terms, batch):
     pc.case_sum_of_products(be, shape, seed=340, terms=terms, batch=batch, levels=levels)
 
 
+def test_rotation_packed_layers_match_oracle(be):
+    """single-image packing: a dense layer (63 rotations in four hoisted calls) and a sparse convolution matrix on one
+    ciphertext, word for word against the oracle's schedule, and decrypting to the matrix-vector product"""
+    from paper_1911_11377_amd import packed
+    announce("rotation-packed dense layer 64x48, N=2^13")
+    pc.case_packed_layer(be, (13, 3, 40, 2, 41, 2), 350, wl.weights_float((64, 48), 350, "fc"))
+    announce("rotation-packed convolution 4->4 channels 3x3 on 8x8, N=2^13")
+    w = wl.weights_float((4, 4, 3, 3), 351, "conv")
+    pc.case_packed_layer(be, (13, 3, 40, 1, 41, 1), 351, packed.conv_matrix(w, 8, 8, 1))
+    announce("rotation-packed dense layer 16x16 at a lower level, N=2^12")
+    pc.case_packed_layer(be, (12, 4, 40, 2, 41, 2), 352, wl.weights_float((16, 16), 352, "fc"), level=3)
+
+
 def _device_residues(torch, q_list, lead, N, seed):
     """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
     g = torch.Generator(device="cuda:0")
