@@ -179,6 +179,17 @@ int ckksmi_hmul_relin_rescale_merged(ckksmi_ctx *ctx, const uint64_t *a, const u
  * key): automorphism X -> X^g first, then key switch of the second component */
 int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [batch]*/, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 
+/* Encoding and encryption on the device (section 2.1), for feeding many fresh ciphertexts without the host in the way.
+ * ckksmi_encode_device: re, im: device doubles [batch][N/2] (im may be NULL: real slots); pt: device [batch][level][N],
+ * evaluation form, m = round(scale * phi^-1(z)) computed with a double-precision complex inverse transform: coefficients
+ * may differ from ckksmi_encode (long double) by a unit in the last place.  ws: device, batch*N*16 bytes.  Synchronises
+ * the stream before returning (a coefficient of 2^62 or more is reported as CKKSMI_EINVAL).
+ * ckksmi_encrypt_device: ct = (r*b + e0 + m, r*a + e1) exactly as ckksmi_encrypt; pk: device [2][n_q][N]; pt: device
+ * [batch][level][N]; r, e0, e1: device int64 [batch][N] (the caller draws them: ternary r, small errors); ct: device
+ * [batch][2][level][N]; ws: device, 3*level*N*8 bytes per item (a smaller one makes several sweeps). */
+int ckksmi_encode_device(ckksmi_ctx *ctx, const double *re, const double *im, double scale, int level, int batch, uint64_t *pt, void *ws, size_t ws_bytes, void *stream);
+int ckksmi_encrypt_device(ckksmi_ctx *ctx, const uint64_t *pk, const uint64_t *pt, const int64_t *r, const int64_t *e0, const int64_t *e1, int level, int batch, uint64_t *ct, void *ws, size_t ws_bytes, void *stream);
+
 /* n_rot rotations of EVERY item with one shared ModUp ("hoisting"; a fewer-transform variant of the rotation above, the
  * paper fixes no algorithm): the second component is decomposed and lifted to the extended basis once per item,
  * dt_j = NTT(ModUp_j(INTT(c1))), and rotation r applies its automorphism to the lifted digits before the inner product
@@ -255,7 +266,9 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_CONV_COLS_MERGED 23 /* the conversion kernel in the exact form of DivRound, sources {q_last, special primes} */
 #define CKKSMI_K_INNER_HOISTED 24 /* inner product of hoisted rotations (gathers the lifted digits through each automorphism) */
 #define CKKSMI_K_AUTOMORPH_BCAST 25 /* first component of every item through every rotation's automorphism */
-#define CKKSMI_K_COUNT 26
+#define CKKSMI_K_ENCODE 26          /* device-side encoding: scatter, complex inverse transform, rounding */
+#define CKKSMI_K_ENCRYPT 27         /* device-side encryption: residues of the small polynomials, combination with the key */
+#define CKKSMI_K_COUNT 28
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

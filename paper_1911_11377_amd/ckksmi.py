@@ -72,6 +72,8 @@ SIGNATURES = {
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_sum_relin_rescale": [VP, VP, VP, C.c_int, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_encode_device": [VP, VP, VP, C.c_double, C.c_int, C.c_int, VP, VP, C.c_size_t, VP],
+    "ckksmi_encrypt_device": [VP, VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, VP, C.c_size_t, VP],
     "ckksmi_rotate_hoisted": [VP, VP, intp, C.c_int, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rotate_hoisted_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
     "ckksmi_rotate": [VP, VP, intp, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
@@ -86,7 +88,7 @@ SIGNATURES = {
     "ckksmi_kernel_class_name": [VP, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
-K_COUNT = 26
+K_COUNT = 28
 
 _LIBS = {}
 
@@ -315,6 +317,16 @@ class Context:
 
     def hmul_relin_rescale(self, a, b, evk, out, level, batch, ws, stream=None):
         self._call("ckksmi_hmul_relin_rescale", self._h, _ptr(a), _ptr(b), _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
+                   self._stream(stream))
+
+    def encode_device(self, re, im, scale, level, batch, pt, ws, stream=None):
+        """re, im: device float64 [batch][N/2] (im may be None); pt: device [batch][level][N]; ws: batch*N*16 bytes"""
+        self._call("ckksmi_encode_device", self._h, _ptr(re), _ptr(im) if im is not None else None, float(scale), level, batch, _ptr(pt), _ptr(ws),
+                   _nbytes(ws), self._stream(stream))
+
+    def encrypt_device(self, pk, pt, r, e0, e1, level, batch, ct, ws, stream=None):
+        """pk [2][n_q][N], pt [batch][level][N], r/e0/e1 int64 [batch][N] (all device); ct [batch][2][level][N]"""
+        self._call("ckksmi_encrypt_device", self._h, _ptr(pk), _ptr(pt), _ptr(r), _ptr(e0), _ptr(e1), level, batch, _ptr(ct), _ptr(ws), _nbytes(ws),
                    self._stream(stream))
 
     def rotate_hoisted_workspace_bytes(self, level, batch, n_rot):

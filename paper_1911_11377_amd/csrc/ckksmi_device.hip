@@ -14,6 +14,7 @@
 #include "kernels.h"
 #include "ntt_v2.h"
 #include "ks_fused.h"
+#include "encode_device.h"
 #include "mac_mfma.h"
 
 // Launch `kern`; when profiling is on, bracket it with two events on the same stream and
@@ -817,6 +818,23 @@ int dev_upload_tables(ckksmi_ctx *c) {
             c->d_fin_merged = upload(c, fg.data(), fg.size(), ok);
         }
     }
+    {
+        // device-side encoding: slot exponents and the complex twiddles of the inverse transform
+        std::vector<unsigned> se(N / 2 ? N / 2 : 1);
+        u64 e = 1;
+        for (size_t k = 0; k < N / 2; k++) { se[k] = (unsigned)e; e = (e * 5) % (2 * N); }
+        c->d_slot_exp = upload(c, se.data(), se.size(), ok);
+        std::vector<double> ctw(2 * N);
+        const long double pi = acosl(-1.0L);
+        for (size_t x = 0; x < N; x++) {
+            const long double ang = pi * (long double)hm::brev(x, c->logN) / (long double)N;
+            ctw[2 * x] = (double)cosl(ang);
+            ctw[2 * x + 1] = (double)(-sinl(ang));
+        }
+        c->d_ctw = upload(c, ctw.data(), ctw.size(), ok);
+        const int zero = 0;
+        c->d_flag = upload(c, &zero, 1, ok);
+    }
     if (!ok) { c->last_hip_error = (int)hipGetLastError(); return CKKSMI_EDEVICE; }
     return CKKSMI_OK;
 }
@@ -1145,6 +1163,75 @@ extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, u
     return g.rc();
 }
 
+// ------------------------------------------------------------------ device-side encoding and encryption
+extern "C" int ckksmi_encode_device(ckksmi_ctx *c, const double *re, const double *im, double scale, int level, int batch, uint64_t *pt, void *ws,
+                                    size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!re || !pt || !(scale > 0) || (!ws && batch) || !al16(pt) || !al16(ws) || ((uintptr_t)re & 7u) || ((uintptr_t)im & 7u)) return CKKSMI_EINVAL;
+    if (c->logN < 1) return CKKSMI_EUNSUPPORTED;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N;
+    if (ws_bytes < (size_t)batch * N * 16) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    hipStream_t st = S(stream);
+    EncodeArgs A;
+    A.re = re; A.im = im; A.cbuf = (double2 *)ws; A.slot_exp = c->d_slot_exp; A.ctw = (const double2 *)c->d_ctw; A.logN = c->logN;
+    A.LA = la_for(c->logN);
+    const unsigned N1 = 1u << A.LA, N2 = (unsigned)(N >> A.LA);
+    const unsigned R = N2 >= CFFT_TILE ? 1u : CFFT_TILE / N2;
+    KL(c, CKKSMI_K_ENCODE, (double)batch, encode_scatter_kernel, dim3(ew_blocks(N / 2), batch), dim3(EW_THREADS), st, A);
+    KL(c, CKKSMI_K_ENCODE, (double)batch, cfft_inv_kernel<false>, dim3(batch, (N1 + R - 1) / R), dim3(NTT_THREADS), st, A);
+    if (A.LA) KL(c, CKKSMI_K_ENCODE, (double)batch, cfft_inv_kernel<true>, dim3(batch, N2 / NTT_TC), dim3(NTT_THREADS), st, A);
+    // the flag is only ever raised by the rounding kernel and read back after this call's kernels
+    if (hipMemsetAsync(c->d_flag, 0, sizeof(int), st) != hipSuccess) return CKKSMI_EDEVICE;
+    const size_t total = (size_t)batch * N;
+    KL(c, CKKSMI_K_ENCODE, (double)batch, encode_round_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const double2 *)ws, scale / (double)N,
+       (u64d *)pt, c->d_mod, c->logN, level, total, c->d_flag);
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < level; i++) idx[i] = i;
+    launch_ntt(c, true, pt, pt, table_map(idx, level, (size_t)level * N, (size_t)level * N), batch, st);
+    int flag = 0;
+    if (hipMemcpyAsync(&flag, c->d_flag, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess)
+        return CKKSMI_EDEVICE;
+    if (flag) return CKKSMI_EINVAL;
+    return g.rc();
+}
+
+extern "C" int ckksmi_encrypt_device(ckksmi_ctx *c, const uint64_t *pk, const uint64_t *pt, const int64_t *r, const int64_t *e0, const int64_t *e1,
+                                     int level, int batch, uint64_t *ct, void *ws, size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (!pk || !pt || !r || !e0 || !e1 || !ct || (!ws && batch) || !al16(pk) || !al16(pt) || !al16(ct) || !al16(ws) || ((uintptr_t)r & 7u) ||
+        ((uintptr_t)e0 & 7u) || ((uintptr_t)e1 & 7u))
+        return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N;
+    const size_t per = 3 * (size_t)level * N * 8;
+    const int chunk = (int)std::min<size_t>((size_t)batch, ws_bytes / per);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    hipStream_t st = S(stream);
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < level; i++) idx[i] = i;
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        u64 *small = (u64 *)ws;  // [items][3][level][N]: r, e0, e1
+        const int64_t *src[3] = {r, e0, e1};
+        const size_t rows_total = (size_t)items * N;
+        for (int which = 0; which < 3; which++)
+            KL(c, CKKSMI_K_ENCRYPT, (double)items * level, small_to_rns_kernel, dim3(ew_blocks(rows_total)), dim3(EW_THREADS), st,
+               (const long long *)(src[which] + (size_t)b0 * N), (u64d *)(small + (size_t)which * level * N),
+               (unsigned long long)((size_t)3 * level * N), c->d_mod, c->logN, level, rows_total);
+        launch_ntt(c, true, small, small, table_map(idx, level, (size_t)level * N, (size_t)level * N), (size_t)items * 3, st);
+        const size_t total = (size_t)items * level * N;
+        KL(c, CKKSMI_K_ENCRYPT, (double)items * level, encrypt_combine_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)small,
+           (const u64d *)pk, (const u64d *)(pt + (size_t)b0 * level * N), (u64d *)(ct + (size_t)b0 * 2 * level * N), c->d_mod, c->logN, level,
+           c->n_q, total);
+    }
+    return g.rc();
+}
+
 static size_t hoisted_words_per_item(const ckksmi_ctx *c, int level, int R) {
     const size_t N = c->N, E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     // sigma_r(c0) + lifted digits + R accumulator pairs + R conversion results
@@ -1347,7 +1434,8 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
                                                 "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel",
-                                                "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel"};
+                                                "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel",
+                                                "encoding kernels", "encryption kernels"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && kernel_class == CKKSMI_K_INNER_HOISTED && (c->logN < 8 || c->beta_top > INNER_MAX_BETA || getenv("CKKSMI_HOIST_GATHER")))
         return "inner_product_hoisted_kernel";

@@ -115,6 +115,9 @@ struct ckksmi_ctx {
     FinConst *d_fin_modup = nullptr;    // [n_q + 1][n_q]  level, limb
     FinConst *d_fin_moddown = nullptr;  // [k]
     FinConst *d_fin_rescale = nullptr;  // [n_q]  dropped limb
+    unsigned *d_slot_exp = nullptr;     // [N/2] 5^k mod 2N (device-side encoding)
+    void *d_ctw = nullptr;              // [N] complex doubles zeta^-brev(x), zeta = exp(i*pi/N)
+    int *d_flag = nullptr;              // one word: raised by a kernel that meets an unencodable value
     FinConst *d_fin_merged = nullptr;   // [n_q + 1][CKKSMI_MAX_SPECIAL]  level, member of {q_{level-1}, p_0 ..}
     std::vector<DivRoundDev> divround_merged;  // [n_q + 1] by level; nb == 0 where unavailable
     std::vector<WMul> h_pmod;           // [T] P mod q_i (zero for the special primes)

@@ -1,0 +1,157 @@
+// Device-side encoding and encryption (section 2.1: m = round(scale * phi^-1(z)), ct = (r*b + e0 + m, r*a + e1)).
+//
+// Encoding is the INVERSE of "evaluate the polynomial at the odd powers of zeta = exp(i*pi/N)", i.e. the inverse
+// negacyclic transform over the complex numbers: the same Gentleman-Sande butterfly network as the modular inverse
+// transform (kernels.h), with complex twiddles zeta^-brev(x) and complex double arithmetic.  Slot k belongs to the
+// exponent 5^k mod 2N and its conjugate to -5^k; in the transform's evaluation order, exponent 2u+1 sits at index
+// brev(u).  The real parts of the result, times scale/N, rounded to nearest, are the plaintext coefficients.
+// Encryption is exact integer work: the small polynomials r, e0, e1 go to residues and through the forward transform,
+// then one pointwise kernel combines them with the public key and the plaintext.
+#pragma once
+#include "kernels.h"
+
+#define CFFT_TILE 4096  // complex words staged in LDS per workgroup (64 KiB)
+
+struct EncodeArgs {
+    const double *re, *im;   // [batch][N/2], im may be null
+    double2 *cbuf;           // [batch][N]
+    const unsigned *slot_exp;  // [N/2]: 5^k mod 2N
+    const double2 *ctw;      // [N]: zeta^-brev(x)
+    int logN, LA;
+};
+
+__device__ __forceinline__ double2 cmul(double2 a, double2 b) { return make_double2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x); }
+
+// grid: x = block of slots, y = item
+__global__ __launch_bounds__(EW_THREADS) void encode_scatter_kernel(EncodeArgs A) {
+    const unsigned N = 1u << A.logN, half = N >> 1;
+    const unsigned k = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (k >= half) return;
+    const size_t item = blockIdx.y;
+    const double zr = A.re[item * half + k], zi = A.im ? A.im[item * half + k] : 0.0;
+    const unsigned e = A.slot_exp[k];
+    const unsigned j = __brev((e - 1u) >> 1) >> (32 - A.logN);
+    const unsigned jc = __brev((2u * N - e - 1u) >> 1) >> (32 - A.logN);
+    double2 *v = A.cbuf + item * N;
+    v[j] = make_double2(zr, zi);
+    v[jc] = make_double2(zr, -zi);
+}
+
+// Inverse complex negacyclic transform, the stage split of ntt_inv_kernel: COL = false first (stages logN-1 .. LA on
+// contiguous rows of N >> LA words), COL = true second (stages LA-1 .. 0 on strided tiles).  Unscaled (no 1/N).
+// grid: x = item, y = tile
+template <bool COL>
+__global__ __launch_bounds__(NTT_THREADS) void cfft_inv_kernel(EncodeArgs A) {
+    __shared__ double2 tile[CFFT_TILE];
+    const unsigned N = 1u << A.logN;
+    double2 *buf = A.cbuf + (size_t)blockIdx.x * N;
+    const double2 *tw = A.ctw;
+    const unsigned tid = threadIdx.x;
+    if (!COL) {
+        const unsigned N2 = N >> A.LA, N1 = 1u << A.LA;
+        const unsigned R = (N2 >= CFFT_TILE) ? 1u : CFFT_TILE / N2;
+        const unsigned rows_here = (N1 - blockIdx.y * R < R) ? N1 - blockIdx.y * R : R;
+        const unsigned row0 = blockIdx.y * R;
+        const unsigned cnt = rows_here * N2;
+        const size_t g0 = (size_t)row0 * N2;
+        for (unsigned e = tid; e < cnt; e += NTT_THREADS) tile[e] = buf[g0 + e];
+        __syncthreads();
+        const int LB = A.logN - A.LA;
+        for (int s = LB - 1; s >= 0; s--) {
+            const unsigned mp = 1u << s, tt = N2 >> (s + 1);
+            for (unsigned b = tid; b < cnt / 2; b += NTT_THREADS) {
+                const unsigned rr = b / (N2 / 2), bb = b % (N2 / 2);
+                const unsigned i = bb / tt, j = bb % tt;
+                const unsigned lo = rr * N2 + i * 2 * tt + j, hi = lo + tt;
+                const double2 x = tile[lo], y = tile[hi];
+                const double2 W = tw[mp * (N1 + row0 + rr) + i];
+                tile[lo] = make_double2(x.x + y.x, x.y + y.y);
+                tile[hi] = cmul(make_double2(x.x - y.x, x.y - y.y), W);
+            }
+            __syncthreads();
+        }
+        for (unsigned e = tid; e < cnt; e += NTT_THREADS) buf[g0 + e] = tile[e];
+    } else {
+        const unsigned N1 = 1u << A.LA, N2 = N >> A.LA;
+        const unsigned c0 = blockIdx.y * NTT_TC;
+        for (unsigned e = tid; e < N1 * NTT_TC; e += NTT_THREADS) {
+            const unsigned r = e / NTT_TC, c = e % NTT_TC;
+            tile[e] = buf[(size_t)r * N2 + c0 + c];
+        }
+        __syncthreads();
+        for (int s = A.LA - 1; s >= 0; s--) {
+            const unsigned m = 1u << s, tr = N1 >> (s + 1);
+            for (unsigned b = tid; b < (N1 / 2) * NTT_TC; b += NTT_THREADS) {
+                const unsigned c = b % NTT_TC, rb = b / NTT_TC;
+                const unsigned i = rb / tr, jr = rb % tr;
+                const unsigned lo = (i * 2 * tr + jr) * NTT_TC + c, hi = lo + tr * NTT_TC;
+                const double2 x = tile[lo], y = tile[hi];
+                const double2 W = tw[m + i];
+                tile[lo] = make_double2(x.x + y.x, x.y + y.y);
+                tile[hi] = cmul(make_double2(x.x - y.x, x.y - y.y), W);
+            }
+            __syncthreads();
+        }
+        for (unsigned e = tid; e < N1 * NTT_TC; e += NTT_THREADS) {
+            const unsigned r = e / NTT_TC, c = e % NTT_TC;
+            buf[(size_t)r * N2 + c0 + c] = tile[e];
+        }
+    }
+}
+
+// coefficients m_t = rint(Re(v_t) * factor) (factor = scale / N), then their residues: out [batch][level][N] in
+// coefficient form.  A coefficient of 2^62 or more in magnitude raises *overflow (the host reports CKKSMI_EINVAL).
+__global__ __launch_bounds__(EW_THREADS) void encode_round_kernel(const double2 *cbuf, double factor, u64d *out, const ModConst *modc, int logN,
+                                                                  int level, size_t total /* batch*N */, int *overflow) {
+    const size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const size_t N = (size_t)1 << logN, item = w >> logN, t = w & (N - 1);
+    const double m = rint(cbuf[w].x * factor);
+    if (!(fabs(m) < 4.0e18)) {
+        *overflow = 1;
+        return;
+    }
+    const long long mi = (long long)m;
+    for (int i = 0; i < level; i++) {
+        const long long q = (long long)modc[i].p;
+        long long r = mi % q;
+        if (r < 0) r += q;
+        out[(item * level + i) * N + t] = (u64d)r;
+    }
+}
+
+// residues of small signed polynomials: in [rows][N] (int64), row r written to out + r*out_row_stride as [level][N],
+// coefficient form
+__global__ __launch_bounds__(EW_THREADS) void small_to_rns_kernel(const long long *in, u64d *out, unsigned long long out_row_stride,
+                                                                  const ModConst *modc, int logN, int level, size_t total /* rows*N */) {
+    const size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const size_t N = (size_t)1 << logN, row = w >> logN, t = w & (N - 1);
+    const long long v = in[w];
+    for (int i = 0; i < level; i++) {
+        const long long q = (long long)modc[i].p;
+        long long r = v % q;
+        if (r < 0) r += q;
+        out[row * out_row_stride + (size_t)i * N + t] = (u64d)r;
+    }
+}
+
+// ct0 = r*b + e0 + m, ct1 = r*a + e1 (all in evaluation form); small: [batch][3][level][N] = (r, e0, e1) per item,
+// pk: [2][n_q][N], pt: [batch][level][N], ct: [batch][2][level][N]
+__global__ __launch_bounds__(EW_THREADS) void encrypt_combine_kernel(const u64d *small, const u64d *pk, const u64d *pt, u64d *ct,
+                                                                     const ModConst *modc, int logN, int level, int n_q, size_t total /* batch*level*N */) {
+    const size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (w >= total) return;
+    const size_t N = (size_t)1 << logN, limb = w >> logN, n = w & (N - 1);
+    const size_t item = limb / level, i = limb % level;
+    const ModConst mc = modc[i];
+    const size_t st = (size_t)level * N, so = (item * 3 * level + i) * N + n;
+    const double r = u2d(small[so]), e0 = u2d(small[so + st]), e1 = u2d(small[so + 2 * st]);
+    const double b = u2d(pk[i * N + n]), a = u2d(pk[((size_t)n_q + i) * N + n]);
+    const double m = u2d(pt[(item * level + i) * N + n]);
+    // mulmod: |result| <= 1.25p; plus two canonical words: below 4p
+    const double c0 = canon(mulmod(r, b, mc.p, mc.pinv) + e0 + m, mc.p, mc.pinv);
+    const double c1 = canon(mulmod(r, a, mc.p, mc.pinv) + e1, mc.p, mc.pinv);
+    ct[(item * 2 * level + i) * N + n] = d2u(c0);
+    ct[(item * 2 * level + level + i) * N + n] = d2u(c1);
+}

@@ -356,6 +356,51 @@ def case_packed_layer(be, shape, seed, M_float, level=None):
     ctx.close()
 
 
+def case_encode_encrypt_device(be, shape, seed, batch=3, level=None, log_scale=40, complex_slots=True, small_ws=False):
+    """device-side encoding (double-precision complex inverse transform: coefficients within one unit of the oracle's
+    encoder, slots back within 1e-9) and device-side encryption (integer work: bit-exact against the oracle)"""
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    level = level or O.n_q
+    scale = 2.0 ** log_scale
+    half = O.N // 2
+    zs = [wl.slots_complex(half, seed, ("enc", i)) if complex_slots else wl.slots_real(half, seed, ("enc", i)) for i in range(batch)]
+    re = np.stack([z.real for z in zs]).astype(np.float64)
+    im = np.stack([z.imag for z in zs]).astype(np.float64)
+    pt = be.empty(batch, level, O.N)
+    ws = be.ws(batch * O.N * 16)
+    ctx.encode_device(be.to_dev(re, np.float64), be.to_dev(im, np.float64) if complex_slots else None, scale, level, batch, pt, ws, stream=be.stream)
+    got = be.to_host(pt).reshape(batch, level, O.N)
+    idx = list(range(level))
+    worst = 0
+    for i in range(batch):
+        want = M.encode(zs[i], scale, level)
+        cg = orc.crt_reconstruct(O.intt_limbs(got[i], idx), O.q[:level])
+        cw = orc.crt_reconstruct(O.intt_limbs(want, idx), O.q[:level])
+        worst = max(worst, max(abs(a - b) for a, b in zip(cg, cw)))
+        back = orc.decode(cg, scale, O.logN)
+        assert np.max(np.abs(back - zs[i])) < max(1e-9, 4.0 * O.N / scale)
+    assert worst <= 1, "device encoder is %d units away from the oracle's" % worst
+    # encryption of the ORACLE's plaintexts with seeded randomness: every word
+    pts = np.stack([M.encode(z, scale, level) for z in zs])
+    r = np.stack([wl.ternary(O.N, seed, "dev.r", i) for i in range(batch)]).astype(np.int64)
+    e0 = np.stack([wl.gaussian_error(O.N, seed, "dev.e0", i) for i in range(batch)]).astype(np.int64)
+    e1 = np.stack([wl.gaussian_error(O.N, seed, "dev.e1", i) for i in range(batch)]).astype(np.int64)
+    ct = be.empty(batch, 2, level, O.N)
+    nbytes = batch * 3 * level * O.N * 8
+    if small_ws and batch > 1:
+        nbytes = nbytes // batch + 8
+    ws2 = be.ws(nbytes)
+    ctx.encrypt_device(be.to_dev(M.pk), be.to_dev(pts), be.to_dev(r, np.int64), be.to_dev(e0, np.int64), be.to_dev(e1, np.int64), level, batch, ct, ws2,
+                       stream=be.stream)
+    gct = be.to_host(ct).reshape(batch, 2, level, O.N)
+    for i in range(batch):
+        assert np.array_equal(gct[i], O.encrypt(M.pk, pts[i], r[i], e0[i], e1[i], level)), "device encryption of item %d differs" % i
+    ctx.close()
+
+
 def mfma_enabled():
     import os
     return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"

@@ -183,6 +183,14 @@ def test_emulated_rotation_packed_layers(be):
     pc.case_packed_layer(be, (7, 3, 40, 1, 41, 1), 135, packed.conv_matrix(w, 4, 4, 1))
 
 
+@pytest.mark.parametrize("shape,log_scale", [(TINY, 30), ((2, 2, 20, 1, 21, 1), 12), ((12, 2, 50, 1, 51, 1), 40), ((13, 2, 50, 1, 51, 1), 45)])
+def test_emulated_device_encode_and_encrypt(be, shape, log_scale):
+    """one-pass and two-pass complex inverse transform, rounding, residues; encryption with supplied randomness"""
+    pc.case_encode_encrypt_device(be, shape, seed=136, batch=2, log_scale=log_scale)
+    if shape == TINY:
+        pc.case_encode_encrypt_device(be, shape, seed=137, batch=3, level=2, log_scale=25, complex_slots=False, small_ws=True)
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

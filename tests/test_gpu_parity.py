@@ -343,6 +343,23 @@ def test_rotation_packed_layers_match_oracle(be):
     pc.case_packed_layer(be, (12, 4, 40, 2, 41, 2), 352, wl.weights_float((16, 16), 352, "fc"), level=3)
 
 
+@pytest.mark.parametrize("shape,log_scale,batch", [
+    ((4, 2, 20, 1, 21, 1), 12, 3),
+    (TINY, 30, 4),
+    ((13, 3, 50, 1, 51, 1), 45, 2),
+    (C2, 40, 3),
+    ((16, 4, 50, 3, 51, 3), 40, 2),
+    ((17, 2, 50, 1, 51, 1), 40, 1),
+])
+def test_device_encode_and_encrypt(be, shape, log_scale, batch):
+    """encoding on the device within one unit per coefficient of the oracle's encoder (and the slots back within 1e-9);
+    encryption on the device bit for bit"""
+    announce("device encode/encrypt %r scale 2^%d" % (shape, log_scale))
+    pc.case_encode_encrypt_device(be, shape, seed=360, batch=batch, log_scale=log_scale)
+    if shape == TINY:
+        pc.case_encode_encrypt_device(be, shape, seed=361, batch=5, level=2, log_scale=25, complex_slots=False, small_ws=True)
+
+
 def _device_residues(torch, q_list, lead, N, seed):
     """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
     g = torch.Generator(device="cuda:0")
