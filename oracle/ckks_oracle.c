@@ -799,6 +799,66 @@ void orc_rotate_hoisted(const orc_params *P, const u64 *ct, int level, int R, co
     free(cidx); free(bidx); free(dc); free(dt); free(acc); free(v);
 }
 
+/* ---- sampling (the distributions of section 2.1's key generation and encryption; the paper names none) ----
+ * Counter-based, so that any coefficient can be drawn anywhere: Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel
+ * random numbers: as easy as 1, 2, 3", 2011).  One round: with the 32x32->64 products p0 = M0*c0, p1 = M1*c2,
+ * (c0, c1, c2, c3) <- (hi(p1) ^ c1 ^ k0, lo(p1), hi(p0) ^ c3 ^ k1, lo(p0)); the key advances by (W0, W1) between
+ * rounds; ten rounds. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; r++) {
+        if (r) { k0 += W0; k1 += W1; }
+        uint64_t p0 = M0 * c0, p1 = M1 * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* thresholds of the rounded Gaussian's magnitude: T_k = floor(2^64 * P(|X| <= k)), P(|X| <= k) = erf((k + 1/2)/(sigma*sqrt 2)),
+ * taken from the complementary function so that the tail keeps its relative accuracy */
+#define ORC_GAUSS_K 40
+static void gauss_thresholds(double sigma, u64 T[ORC_GAUSS_K]) {
+    for (int k = 0; k < ORC_GAUSS_K; k++) {
+        long double tail = erfcl(((long double)k + 0.5L) / ((long double)sigma * sqrtl(2.0L))) * 18446744073709551616.0L; /* 2^64 */
+        T[k] = tail >= 1.0L ? (u64)0 - (u64)ceill(tail) : ~(u64)0;
+    }
+}
+
+/*
+ * rows polynomials of N coefficients.  Coefficient t of polynomial p = first_index + row uses the Philox block with
+ * counter (t, kind, lo32(p), hi32(p)) and key (lo32(seed), hi32(seed)); its words w0..w3 give
+ *   kind 0, ternary : ((w0 * 3) >> 32) - 1                    in {-1, 0, 1}
+ *   kind 1, Gaussian: magnitude = #{k : u >= T_k}, u = w1*2^32 + w0, negative when w2 is odd   (round(N(0, sigma^2)))
+ */
+void orc_sample(int kind, double sigma, u64 seed, u64 first_index, int rows, int logN, i64 *out) {
+    u64 N = (u64)1 << logN;
+    u64 T[ORC_GAUSS_K];
+    if (kind == 1) gauss_thresholds(sigma, T);
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (int row = 0; row < rows; row++) {
+        u64 p = first_index + (u64)row;
+        for (u64 t = 0; t < N; t++) {
+            uint32_t ctr[4] = {(uint32_t)t, (uint32_t)kind, (uint32_t)p, (uint32_t)(p >> 32)}, w[4];
+            orc_philox4x32_10(ctr, key, w);
+            i64 v;
+            if (kind == 0) {
+                v = (i64)(((u64)w[0] * 3) >> 32) - 1;
+            } else {
+                u64 u = ((u64)w[1] << 32) | w[0];
+                int mag = 0;
+                for (int k = 0; k < ORC_GAUSS_K; k++) mag += (u >= T[k]);
+                v = (w[2] & 1u) ? -(i64)mag : (i64)mag;
+            }
+            out[(size_t)row * N + t] = v;
+        }
+    }
+}
+
+void orc_gauss_thresholds(double sigma, u64 *T) { gauss_thresholds(sigma, T); }
+
 /* ---- limb-wise operations ---- */
 void orc_add(const orc_params *P, const u64 *a, const u64 *b, int level, u64 *out) {
     for (int c = 0; c < 2; c++) for (int i = 0; i < level; i++) {

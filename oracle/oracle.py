@@ -665,6 +665,33 @@ def slot_exponents(logN):
     return out
 
 
+def philox4x32_10(ctr, key):
+    c = (C.c_uint32 * 4)(*ctr)
+    k = (C.c_uint32 * 2)(*key)
+    o = (C.c_uint32 * 4)()
+    lib().orc_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def sample(kind, sigma, seed, first_index, rows, logN):
+    """rows x N small coefficients from the counter-based sampler: kind 0 ternary, kind 1 rounded Gaussian"""
+    out = np.empty((rows, 1 << logN), dtype=np.int64)
+    f = lib().orc_sample
+    f.argtypes = [C.c_int, C.c_double, C.c_uint64, C.c_uint64, C.c_int, C.c_int, C.POINTER(C.c_int64)]
+    f.restype = None
+    f(kind, float(sigma), seed, first_index, rows, logN, out.ctypes.data_as(C.POINTER(C.c_int64)))
+    return out
+
+
+def gauss_thresholds(sigma):
+    T = np.empty(40, dtype=np.uint64)
+    f = lib().orc_gauss_thresholds
+    f.argtypes = [C.c_double, C.POINTER(C.c_uint64)]
+    f.restype = None
+    f(float(sigma), T.ctypes.data_as(C.POINTER(C.c_uint64)))
+    return T
+
+
 def matrix_diagonals(M, n_slots):
     """Generalised diagonals of a square matrix M (n x n, n dividing n_slots) for a slot vector that repeats z with
     period n: diag_d[i] = M[i mod n][(i + d) mod n], so that M z = sum_d diag_d * roll(z, -d).  Zero diagonals are

@@ -659,6 +659,41 @@ def test_packed_convolution_decrypts_to_the_convolution():
     assert np.max(np.abs(got - direct)) < 1e-4
 
 
+def test_philox_known_answers():
+    """Philox4x32-10 known-answer vectors published with the generator (zeros, all ones, digits of pi)"""
+    assert orc.philox4x32_10([0] * 4, [0] * 2) == [0x6627E8D5, 0xE169C58D, 0xBC57AC4C, 0x9B00DBD8]
+    assert orc.philox4x32_10([0xFFFFFFFF] * 4, [0xFFFFFFFF] * 2) == [0x408F276D, 0x41C83B0E, 0xA20BC7C6, 0x6D5451FD]
+    assert orc.philox4x32_10([0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344], [0xA4093822, 0x299F31D0]) == [
+        0xD16CFE09, 0x94FDCCEB, 0x5001E420, 0x24126EA1]
+
+
+def test_sampler_distributions_and_counter_structure():
+    """ternary: each value a third of the time; Gaussian: the probabilities of round(N(0, sigma^2)) (chi-square against
+    the exact masses from erf), thresholds equal to 2^64*erf(.) ; a coefficient depends only on (seed, polynomial, t)"""
+    sigma, logN, rows = 3.2, 12, 64
+    tern = orc.sample(0, sigma, 7, 100, rows, logN)
+    n = tern.size
+    assert set(np.unique(tern)) == {-1, 0, 1}
+    for v in (-1, 0, 1):
+        assert abs(np.mean(tern == v) - 1 / 3) < 4 * math.sqrt(2 / 9 / n)
+    g = orc.sample(1, sigma, 7, 100, rows, logN)
+    assert abs(np.mean(g)) < 5 * sigma / math.sqrt(n)
+    assert abs(np.var(g) - (sigma**2 + 1 / 12)) < 0.1
+    chi = 0.0
+    for k in range(-12, 13):
+        pk = 0.5 * (math.erf((k + 0.5) / (sigma * math.sqrt(2))) - math.erf((k - 0.5) / (sigma * math.sqrt(2))))
+        chi += (np.sum(g == k) - n * pk) ** 2 / (n * pk)
+    assert chi < 60  # 24 degrees of freedom: 60 is beyond the 99.99 % point
+    T = orc.gauss_thresholds(sigma)
+    for k in range(12):
+        assert abs(int(T[k]) / 2.0**64 - math.erf((k + 0.5) / (sigma * math.sqrt(2)))) < 1e-14
+    assert all(int(T[k]) <= int(T[k + 1]) for k in range(39)) and int(T[39]) == 2**64 - 1
+    # counter structure: polynomial 103 drawn alone equals row 3 of the block; another seed gives other values
+    assert np.array_equal(orc.sample(1, sigma, 7, 103, 1, logN)[0], g[3])
+    assert np.array_equal(orc.sample(0, sigma, 7, 2**40 + 5, 2, 6)[1], orc.sample(0, sigma, 7, 2**40 + 6, 1, 6)[0])
+    assert not np.array_equal(orc.sample(1, sigma, 8, 100, 1, logN)[0], g[0])
+
+
 def test_elementwise_ops_on_decrypted_polynomials():
     M = Material(5, 3, 30, 1, 31, 1, seed=20)
     O = M.O
