@@ -144,18 +144,21 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     del om
     # fresh ciphertexts made on the device: encode (complex inverse transform) + encrypt with resident randomness
     z_re = torch.rand((B, N // 2), dtype=torch.float64, device="cuda:0", generator=gen) * 2 - 1
-    small = [torch.randint(-1, 2, (B, N), dtype=torch.int64, device="cuda:0", generator=gen) for _ in range(3)]
+    small = [torch.empty((B, N), dtype=torch.int64, device="cuda:0") for _ in range(3)]
     pk = uniform_residues(torch, ctx.q, (2,), N, gen)
     ptd = torch.empty((B, L, N), dtype=torch.int64, device="cuda:0")
     ctd = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda:0")
 
     def fresh():
+        ctx.sample_device(0, 3.2, 4, 0, B, small[0])
+        ctx.sample_device(1, 3.2, 4, B, B, small[1])
+        ctx.sample_device(1, 3.2, 4, 2 * B, B, small[2])
         ctx.encode_device(z_re, None, s, L, B, ptd, ws)
         ctx.encrypt_device(pk, ptd, small[0], small[1], small[2], L, B, ctd, ws)
 
     ms = timed(torch, fresh, 3)
     out["encode_encrypt_device_2e16"] = {"ciphertexts_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 3),
-                                         "what": "encode + encrypt on the device, batch 64, 24 limbs, randomness resident"}
+                                         "what": "sample (ternary r, Gaussian e0, e1) + encode + encrypt on the device, batch 64, 24 limbs"}
     del z_re, small, pk, ptd, ctd
     # a sum of 4 products relinearised and rescaled once (lazy relinearisation; the same ciphertexts serve as every term)
     terms = 4

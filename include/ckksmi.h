@@ -187,6 +187,15 @@ int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [bat
  * ckksmi_encrypt_device: ct = (r*b + e0 + m, r*a + e1) exactly as ckksmi_encrypt; pk: device [2][n_q][N]; pt: device
  * [batch][level][N]; r, e0, e1: device int64 [batch][N] (the caller draws them: ternary r, small errors); ct: device
  * [batch][2][level][N]; ws: device, 3*level*N*8 bytes per item (a smaller one makes several sweeps). */
+/* Small polynomials drawn on the device (the randomness of encryption and key generation, section 2.1; the paper names
+ * no distribution: ternary and rounded Gaussian are the usual ones).  Counter-based (Philox4x32-10, one block per
+ * coefficient: counter (t, kind, polynomial index), key = seed), so polynomial p = first_index + row is the same
+ * whenever and wherever it is drawn.  kind CKKSMI_SAMPLE_TERNARY: uniform on {-1, 0, 1}; CKKSMI_SAMPLE_GAUSSIAN:
+ * round(N(0, sigma^2)) by comparison of 64 random bits with the cumulative thresholds floor(2^64 * erf((k + 1/2)/(sigma sqrt 2))),
+ * k < 40, 0 < sigma < 64.  out: device int64 [rows][N], 8-byte aligned. */
+#define CKKSMI_SAMPLE_TERNARY 0
+#define CKKSMI_SAMPLE_GAUSSIAN 1
+int ckksmi_sample_device(ckksmi_ctx *ctx, int kind, double sigma, uint64_t seed, uint64_t first_index, int rows, int64_t *out, void *stream);
 int ckksmi_encode_device(ckksmi_ctx *ctx, const double *re, const double *im, double scale, int level, int batch, uint64_t *pt, void *ws, size_t ws_bytes, void *stream);
 int ckksmi_encrypt_device(ckksmi_ctx *ctx, const uint64_t *pk, const uint64_t *pt, const int64_t *r, const int64_t *e0, const int64_t *e1, int level, int batch, uint64_t *ct, void *ws, size_t ws_bytes, void *stream);
 

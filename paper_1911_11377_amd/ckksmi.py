@@ -72,6 +72,7 @@ SIGNATURES = {
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_sum_relin_rescale": [VP, VP, VP, C.c_int, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_sample_device": [VP, C.c_int, C.c_double, C.c_uint64, C.c_uint64, C.c_int, VP, VP],
     "ckksmi_encode_device": [VP, VP, VP, C.c_double, C.c_int, C.c_int, VP, VP, C.c_size_t, VP],
     "ckksmi_encrypt_device": [VP, VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, VP, C.c_size_t, VP],
     "ckksmi_rotate_hoisted": [VP, VP, intp, C.c_int, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
@@ -318,6 +319,10 @@ class Context:
     def hmul_relin_rescale(self, a, b, evk, out, level, batch, ws, stream=None):
         self._call("ckksmi_hmul_relin_rescale", self._h, _ptr(a), _ptr(b), _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),
                    self._stream(stream))
+
+    def sample_device(self, kind, sigma, seed, first_index, rows, out, stream=None):
+        """rows small polynomials (kind 0 ternary, 1 rounded Gaussian) into the device int64 buffer out [rows][N]"""
+        self._call("ckksmi_sample_device", self._h, kind, float(sigma), seed, first_index, rows, _ptr(out), self._stream(stream))
 
     def encode_device(self, re, im, scale, level, batch, pt, ws, stream=None):
         """re, im: device float64 [batch][N/2] (im may be None); pt: device [batch][level][N]; ws: batch*N*16 bytes"""

@@ -1232,6 +1232,26 @@ extern "C" int ckksmi_encrypt_device(ckksmi_ctx *c, const uint64_t *pk, const ui
     return g.rc();
 }
 
+extern "C" int ckksmi_sample_device(ckksmi_ctx *c, int kind, double sigma, uint64_t seed, uint64_t first_index, int rows, int64_t *out, void *stream) {
+    if (!dev_ok(c)) return CKKSMI_EDEVICE;
+    if ((kind != CKKSMI_SAMPLE_TERNARY && kind != CKKSMI_SAMPLE_GAUSSIAN) || rows < 0 || (!out && rows) || ((uintptr_t)out & 7u) ||
+        (kind == CKKSMI_SAMPLE_GAUSSIAN && !(sigma > 0.0 && sigma < 64.0)))
+        return CKKSMI_EINVAL;
+    if (rows == 0) return CKKSMI_OK;
+    Guard g(c);
+    SampleArgs A;
+    memset(&A, 0, sizeof(A));
+    A.out = (long long *)out; A.seed = seed; A.first_index = first_index; A.kind = kind; A.logN = c->logN; A.total = (size_t)rows * c->N;
+    if (kind == CKKSMI_SAMPLE_GAUSSIAN)
+        for (int k = 0; k < SAMPLE_K; k++) {
+            // P(|X| <= k) = erf((k + 1/2) / (sigma sqrt 2)) through the complementary function: the tail keeps its relative accuracy
+            const long double tail = erfcl(((long double)k + 0.5L) / ((long double)sigma * sqrtl(2.0L))) * 18446744073709551616.0L;
+            A.T[k] = tail >= 1.0L ? (unsigned long long)0 - (unsigned long long)ceill(tail) : ~0ull;
+        }
+    KL(c, CKKSMI_K_ENCRYPT, (double)rows, sample_kernel, dim3(ew_blocks(A.total)), dim3(EW_THREADS), S(stream), A);
+    return g.rc();
+}
+
 static size_t hoisted_words_per_item(const ckksmi_ctx *c, int level, int R) {
     const size_t N = c->N, E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     // sigma_r(c0) + lifted digits + R accumulator pairs + R conversion results

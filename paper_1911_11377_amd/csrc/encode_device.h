@@ -155,3 +155,48 @@ __global__ __launch_bounds__(EW_THREADS) void encrypt_combine_kernel(const u64d 
     ct[(item * 2 * level + i) * N + n] = d2u(c0);
     ct[(item * 2 * level + level + i) * N + n] = d2u(c1);
 }
+
+// ---------------------------------------------------------------- sampling
+// Counter-based (Philox4x32-10: Salmon, Moraes, Dror, Shaw 2011), one block per coefficient: counter
+// (t, kind, lo32(p), hi32(p)) for coefficient t of polynomial p, key = the two halves of the seed.
+//   kind 0, ternary : ((w0 * 3) >> 32) - 1
+//   kind 1, Gaussian: magnitude = number of thresholds T_k <= u, u = w1*2^32 + w0; negative when w2 is odd
+#define SAMPLE_K 40
+struct SampleArgs {
+    long long *out;  // [rows][N]
+    unsigned long long seed, first_index;
+    int kind, logN;
+    size_t total;    // rows * N
+    unsigned long long T[SAMPLE_K];  // floor(2^64 * P(|X| <= k)) of the rounded Gaussian
+};
+
+__device__ __forceinline__ void philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0, unsigned k1, unsigned (&w)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; r++) {
+        if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+        const unsigned long long p0 = 0xD2511F53ull * c0, p1 = 0xCD9E8D57ull * c2;
+        const unsigned n0 = (unsigned)(p1 >> 32) ^ c1 ^ k0, n1 = (unsigned)p1, n2 = (unsigned)(p0 >> 32) ^ c3 ^ k1, n3 = (unsigned)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void sample_kernel(SampleArgs A) {
+    const size_t idx = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    if (idx >= A.total) return;
+    const unsigned long long p = A.first_index + (idx >> A.logN);
+    const unsigned t = (unsigned)(idx & (((size_t)1 << A.logN) - 1));
+    unsigned w[4];
+    philox4x32_10(t, (unsigned)A.kind, (unsigned)p, (unsigned)(p >> 32), (unsigned)A.seed, (unsigned)(A.seed >> 32), w);
+    long long v;
+    if (A.kind == 0) {
+        v = (long long)(((unsigned long long)w[0] * 3ull) >> 32) - 1;
+    } else {
+        const unsigned long long u = ((unsigned long long)w[1] << 32) | w[0];
+        int mag = 0;
+#pragma unroll
+        for (int k = 0; k < SAMPLE_K; k++) mag += (u >= A.T[k]) ? 1 : 0;
+        v = (w[2] & 1u) ? -(long long)mag : (long long)mag;
+    }
+    A.out[idx] = v;
+}

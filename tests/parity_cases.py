@@ -401,6 +401,18 @@ def case_encode_encrypt_device(be, shape, seed, batch=3, level=None, log_scale=4
     ctx.close()
 
 
+def case_sample_device(be, shape, seed, rows=3, sigma=3.2, first_index=(1 << 33) + 5):
+    """the device sampler against the oracle's: integer work on counters, every coefficient"""
+    ctx = be.context(*shape)
+    logN = shape[0]
+    for kind in (0, 1):
+        out = be.empty(rows, 1 << logN)
+        ctx.sample_device(kind, sigma, seed, first_index, rows, out, stream=be.stream)
+        got = be.to_host(out).view(np.int64).reshape(rows, 1 << logN)
+        assert np.array_equal(got, orc.sample(kind, sigma, seed, first_index, rows, logN)), "sampler kind %d differs" % kind
+    ctx.close()
+
+
 def mfma_enabled():
     import os
     return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"

@@ -191,6 +191,11 @@ def test_emulated_device_encode_and_encrypt(be, shape, log_scale):
         pc.case_encode_encrypt_device(be, shape, seed=137, batch=3, level=2, log_scale=25, complex_slots=False, small_ws=True)
 
 
+def test_emulated_device_sampler(be):
+    pc.case_sample_device(be, TINY, seed=0x1234567890ABCDEF)
+    pc.case_sample_device(be, (9, 2, 50, 1, 51, 1), seed=3, rows=2, sigma=1.5, first_index=0)
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

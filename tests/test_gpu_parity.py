@@ -360,6 +360,14 @@ def test_device_encode_and_encrypt(be, shape, log_scale, batch):
         pc.case_encode_encrypt_device(be, shape, seed=361, batch=5, level=2, log_scale=25, complex_slots=False, small_ws=True)
 
 
+def test_device_sampler_matches_oracle(be):
+    """ternary and rounded-Gaussian polynomials drawn on the device: every coefficient equals the oracle's sampler"""
+    announce("device sampler")
+    pc.case_sample_device(be, TINY, seed=0x1234567890ABCDEF, rows=5)
+    pc.case_sample_device(be, (16, 2, 50, 1, 51, 1), seed=362, rows=3, sigma=3.2, first_index=(1 << 40) + 77)
+    pc.case_sample_device(be, (13, 2, 50, 1, 51, 1), seed=363, rows=2, sigma=8.0, first_index=0)
+
+
 def _device_residues(torch, q_list, lead, N, seed):
     """uniform residues below 2^49 (canonical for every 50/51-bit prime) drawn on the device from a seeded generator"""
     g = torch.Generator(device="cuda:0")
