@@ -413,6 +413,59 @@ def case_sample_device(be, shape, seed, rows=3, sigma=3.2, first_index=(1 << 33)
     ctx.close()
 
 
+def case_variant_errors(be, shape=(6, 3, 30, 1, 31, 1)):
+    """argument checks of the variant entry points: every refusal happens on the host, before anything is enqueued"""
+    ctx = be.context(*shape)
+    N, L = 1 << shape[0], shape[1]
+    a = be.empty(2, 2, L, N)
+    out = be.empty(2, 2, L, N)
+    ws = be.ws(1 << 22)
+    tiny_ws = be.ws(64)
+
+    def refused(code, fn, *args):
+        try:
+            fn(*args, stream=be.stream)
+        except ckksmi.CkksmiError as e:
+            assert e.code == code, (fn.__name__, e.code, code)
+            return
+        raise AssertionError("%s accepted bad arguments" % fn.__name__)
+
+    # empty batches are fine and enqueue nothing
+    ctx.hmul_relin_rescale_merged(a, a, a, out, L, 0, ws, stream=be.stream)
+    ctx.hmul_sum_relin_rescale(a, a, 3, a, out, L, 0, ws, stream=be.stream)
+    ctx.sample_device(0, 3.2, 1, 0, 0, out, stream=be.stream)
+    ctx.encode_device(a, None, 2.0**20, L, 0, out, ws, stream=be.stream)
+    ctx.encrypt_device(a, a, a, a, a, L, 0, out, ws, stream=be.stream)
+    refused(ckksmi.ELEVEL, ctx.hmul_relin_rescale_merged, a, a, a, out, 1, 1, ws)
+    refused(ckksmi.ELEVEL, ctx.hmul_relin_rescale_merged, a, a, a, out, L + 1, 1, ws)
+    refused(ckksmi.EWORKSPACE, ctx.hmul_relin_rescale_merged, a, a, a, out, L, 1, tiny_ws)
+    refused(ckksmi.EINVAL, ctx.hmul_sum_relin_rescale, a, a, 0, a, out, L, 1, ws)
+    refused(ckksmi.EWORKSPACE, ctx.hmul_sum_relin_rescale, a, a, 2, a, out, L, 1, tiny_ws)
+    refused(ckksmi.EINVAL, ctx.rotate_hoisted, a, [], out, L, 1, ws)
+    refused(ckksmi.EINVAL, ctx.rotate_hoisted, a, list(range(1, 18)), out, L, 1, ws)
+    refused(ckksmi.ENOKEY, ctx.rotate_hoisted, a, [1], out, L, 1, ws)
+    ctx.galois_key_register(1, be.empty(ctx.beta_top, 2, L + shape[3], N))
+    refused(ckksmi.EWORKSPACE, ctx.rotate_hoisted, a, [1], out, L, 1, tiny_ws)
+    refused(ckksmi.EINVAL, ctx.rotate_hoisted, a, [1], a, L, 1, ws)  # out must not alias the input
+    refused(ckksmi.EINVAL, ctx.sample_device, 2, 3.2, 1, 0, 1, out)
+    refused(ckksmi.EINVAL, ctx.sample_device, 1, 0.0, 1, 0, 1, out)
+    refused(ckksmi.EINVAL, ctx.sample_device, 1, 100.0, 1, 0, 1, out)
+    refused(ckksmi.EINVAL, ctx.encode_device, a, None, -1.0, L, 1, out, ws)
+    refused(ckksmi.EWORKSPACE, ctx.encode_device, a, None, 2.0**20, L, 1, out, tiny_ws)
+    refused(ckksmi.EWORKSPACE, ctx.encrypt_device, a, a, a, a, a, L, 1, out, tiny_ws)
+    refused(ckksmi.ELEVEL, ctx.encrypt_device, a, a, a, a, a, L + 1, 1, out, ws)
+    ctx.close()
+    # the merged division needs room for q_last beside the special primes: four special primes are too many
+    ctx4 = be.context(6, 5, 30, 4, 31, 4)
+    refused(ckksmi.EUNSUPPORTED, ctx4.hmul_relin_rescale_merged, a, a, a, out, 2, 1, ws)
+    ctx4.close()
+    # a value too large to encode is reported, not wrapped
+    ctx = be.context(*shape)
+    big = be.to_dev(np.full((1, N // 2), 1.0), np.float64)
+    refused(ckksmi.EINVAL, ctx.encode_device, big, None, 2.0**70, L, 1, out, ws)
+    ctx.close()
+
+
 def mfma_enabled():
     import os
     return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"

@@ -196,6 +196,10 @@ def test_emulated_device_sampler(be):
     pc.case_sample_device(be, (9, 2, 50, 1, 51, 1), seed=3, rows=2, sigma=1.5, first_index=0)
 
 
+def test_emulated_variant_entry_points_refuse_bad_arguments(be):
+    pc.case_variant_errors(be)
+
+
 def test_emulated_misaligned_device_pointer_is_rejected(be):
     """device buffers must be 16-byte aligned (vector accesses of two words): an odd word offset is refused on the host"""
     from paper_1911_11377_amd import ckksmi

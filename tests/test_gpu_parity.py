@@ -524,3 +524,8 @@ def test_edge_cases(be):
     with pytest.raises(ckksmi.CkksmiError) as e:
         ctx.add(buf, buf, buf, 4, 1)
     assert e.value.code == ckksmi.ELEVEL
+
+
+def test_variant_entry_points_refuse_bad_arguments(be):
+    announce("argument checks of the variant entry points")
+    pc.case_variant_errors(be)
