@@ -53,6 +53,10 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "modup_cols_kernel<4, %d, 0, true>" % alpha: w * (1 + float(level) / (beta * E - level)),
         "modup_cols_kernel<4, %d, 1, true>" % k: w * (1 + float(k) / level),
         "modup_cols_kernel<4, 1, 1, true>": w * (1 + 1.0 / (level - 1)),
+        # ModDown + rescale as one conversion / the merged division: k + 1 source limbs for level - 1 targets
+        "modup_cols_kernel<4, %d, 3, true>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
+        "modup_cols_kernel<4, %d, 2, true>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
+        "axpy_limb_kernel": 3 * w,
         "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
         "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
@@ -77,13 +81,15 @@ def laneops_per_unit(name, N, level, k, alpha):
         "modup_cols_kernel<4, %d, 0, true>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
         "modup_cols_kernel<4, %d, 1, true>" % k: N * (5 * k + k + 3 + xform_pass),
         "modup_cols_kernel<4, 1, 1, true>": N * (5 + 1 + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 3, true>" % (k + 1): N * (5 * k + k + 3 + 5 + 2 + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 2, true>" % (k + 1): N * (5 * (k + 1) + (k + 1) + 6 + 3 + xform_pass),
         "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
         "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         # per word: a row pass for every digit except the limb's own one (level of the E limbs have one), two
         # multiply-accumulates per digit (key word conversion 2 + exact product 5 + add 1, the prepared quotient and the
         # lazy reductions shared: about 2 more per digit), canonical form of the two results
         "rows_inner_kernel": N * ((beta - float(level) / (level + k)) * xform_pass + beta * (2 * 8 + 2) + 2 * 7),
-        "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),
+        "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),   # (+5 when the kept limb is scaled before the subtraction)
         "rows_final2_kernel": N * (2 * xform_pass + 2 + 1 + 5 + 3 + 1 + 5 + 7 + 2),
     }
     return table.get(name)

@@ -277,7 +277,8 @@ int ckksmi_workspace_bytes(const ckksmi_ctx *ctx, int op, int level, int batch, 
 #define CKKSMI_K_AUTOMORPH_BCAST 25 /* first component of every item through every rotation's automorphism */
 #define CKKSMI_K_ENCODE 26          /* device-side encoding: scatter, complex inverse transform, rounding */
 #define CKKSMI_K_ENCRYPT 27         /* device-side encryption: residues of the small polynomials, combination with the key */
-#define CKKSMI_K_COUNT 28
+#define CKKSMI_K_CONV_COLS_TAIL 28  /* ModDown followed by rescale as one conversion (the strict sequence's bits) */
+#define CKKSMI_K_COUNT 29
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */

@@ -89,7 +89,7 @@ SIGNATURES = {
     "ckksmi_kernel_class_name": [VP, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
-K_COUNT = 28
+K_COUNT = 29
 
 _LIBS = {}
 

@@ -189,7 +189,8 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
     const unsigned z = (unsigned)((items + A.items_per_z - 1) / A.items_per_z);
     const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count, mode): registers sized for it
     const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP
-                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
+                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED
+                               : mode == 3 ? CKKSMI_K_CONV_COLS_TAIL : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
     const dim3 grid(tiles, slots, z), block(V2_THREADS);
 #define CONV_COLS_CASE(Q, NS)                                                                                \
     case (Q) * 8 + (NS):                                                                                     \
@@ -211,9 +212,10 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
 // mode 1: DivRound conversion of `items` rows (y: row r at y + r*y_stride, dst: [rows][nc][N])
 // fin != nullptr: y is the output of the inverse row pass and the kernel runs the inverse column pass itself
 void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t items, int level, int nc,
-                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin = nullptr) {
+                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin = nullptr, const DivRoundDev *D2 = nullptr) {
     ModupColsArgs A;
     memset(&A, 0, sizeof(A));
+    if (D2) { A.hc2 = D2->hc; A.hb2 = D2->hb[0]; }
     A.y = (const u64d *)y; A.y_row_stride = y_stride; A.dst = (u64d *)dst; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.cc = c->d_modup_c;
     A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.nc = nc;
     A.beta = (level + c->alpha - 1) / c->alpha;
@@ -221,7 +223,7 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     A.tw_inv = c->d_tww_inv; A.fin = fin;
     if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
-    const int n_targets = mode == 0 ? A.E : nc;  // mode 2: mode 1 in the exact form of DivRound (needs fin)
+    const int n_targets = mode == 0 ? A.E : nc;  // mode 2: mode 1 in the exact form of DivRound; mode 3: ModDown + rescale (both need fin)
     const size_t ygrid = mode == 0 ? items * A.beta : items;
     // enough workgroups to fill the chip (8 per CU), otherwise as many targets per workgroup as possible: the source
     // tiles are read and converted once per workgroup (measured: 24 targets 0.65 ms, 6 targets 0.75 ms for ModDown)
@@ -234,12 +236,14 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     const dim3 grid(tiles, (unsigned)ygrid, z), block(V2_THREADS);
     const int nsrc = mode == 0 ? c->alpha : D->nb;
     const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP
-                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
+                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED
+                               : mode == 3 ? CKKSMI_K_CONV_COLS_TAIL : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
 #define MODUP_COLS_CASE(Q, NS)                                                                               \
     case (Q) * 8 + (NS):                                                                                     \
         if (mode == 0 && fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, true>), grid, block, st, A);    \
         else if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, false>), grid, block, st, A);     \
         else if (mode == 2) KL(c, kid, units, (modup_cols_kernel<Q, NS, 2, true>), grid, block, st, A);      \
+        else if (mode == 3) KL(c, kid, units, (modup_cols_kernel<Q, NS, 3, true>), grid, block, st, A);      \
         else if (fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, true>), grid, block, st, A);            \
         else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, false>), grid, block, st, A);                    \
         break;
@@ -257,9 +261,10 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
 // out + row*out_row_stride + (limb - limb0)*N
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
                        size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st, int limb0 = 0,
-                       int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr) {
+                       int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr, const WMul *xmul = nullptr) {
     RowsFinalArgs A;
     A.pre = pre;
+    A.xmul = xmul;
     const int nz = limb_count < 0 ? nc : limb_count;
     A.limb0 = limb_count < 0 ? 0 : limb0;
     A.out_limb0 = A.limb0;
@@ -383,7 +388,7 @@ void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item
     // only the dropped limb q_{level-1} needs acc + P*d up front; the kept limbs receive P*d in the last step
     KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
        (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)(level - 1) * N), (unsigned long long)add_item_stride,
-       (unsigned long long)add_comp_stride, c->h_modc[level - 1], c->h_pmod[level - 1], c->logN);
+       (unsigned long long)add_comp_stride, c->h_modc[level - 1], make_wmul(1, c->mod[level - 1]), c->h_pmod[level - 1], c->logN);
     const bool fast = c->fused && (c->fuse & FUSE_DIVCONV) && c->modup_loop && c->fuse_inv;
     const bool ffinal = c->fused && (c->fuse & FUSE_FINAL);
     int idx[CKKSMI_MAX_MODULI];
@@ -498,6 +503,25 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         const DivRoundDev &DA = c->divround[0], &DB = c->divround[1 + (level - 1)];
         int lidx[1] = {level - 1};
         const bool finv = c->modup_loop && c->fuse_inv;
+        if (c->fuse_tail >= 2 && finv && c->d_fin_tail && add_both) {
+            // ONE conversion and ONE last pass for ModDown + add + rescale (same bits; see modup_cols_kernel MODE 3):
+            // u = x_last * P^-1 + d_last replaces the dropped limb, its inverse transform rides with the special limbs'
+            const int last = level - 1;
+            u64 *bl = acc + (size_t)last * N;  // limbs last, p_0 .. p_{k-1} of every row: contiguous in the extended layout
+            KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
+               (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)last * N), (unsigned long long)add_item_stride,
+               (unsigned long long)add_comp_stride, c->h_modc[last], c->h_Pinv[last], make_wmul(1, c->mod[last]), c->logN);
+            DivRoundDev D3 = DA;
+            D3.nb = c->k + 1;
+            D3.b_idx[0] = last;
+            for (int m = 0; m < c->k; m++) D3.b_idx[1 + m] = c->n_q + m;
+            const FinConst *ft = c->d_fin_tail + (size_t)level * CKKSMI_MAX_SPECIAL;
+            launch_ntt(c, false, bl, bl, table_map(D3.b_idx, D3.nb, (size_t)E * N, (size_t)E * N), rows, st, ft, 2);
+            launch_modup_cols(c, 3, bl, (size_t)E * N, tmp, rows, 0, last, &D3, (double)rows * last, st, ft, &DB);
+            launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, DB.Binv, last, rows, st, 0, -1, 0, nullptr,
+                              DA.Binv);
+            return;
+        }
         launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown, finv ? 2 : 3);
         launch_div_cols(c, specials, (size_t)E * N, tmp, level, rows, DA, st, finv ? c->d_fin_moddown : nullptr);
         launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, add_both, r_last, DA.Binv, level, rows, st,
@@ -679,7 +703,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
         c->d_pow24 = upload(c, p24.data(), p24.size(), ok);
         if (const char *e = getenv("CKKSMI_MAC_MFMA")) c->mac_mfma = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_LOOP")) c->modup_loop = atoi(e) != 0;
-        if (const char *e = getenv("CKKSMI_FUSE_TAIL")) c->fuse_tail = atoi(e) != 0;
+        if (const char *e = getenv("CKKSMI_FUSE_TAIL")) c->fuse_tail = atoi(e);  // 0 separate, 1 shared last pass, 2 one conversion
         if (const char *e = getenv("CKKSMI_FUSE_INV")) c->fuse_inv = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_FUSE_TENSOR")) c->fuse_tensor = atoi(e) != 0;
         if (const char *e = getenv("CKKSMI_MODUP_TARGETS")) c->modup_targets_per_wg = atoi(e);
@@ -749,6 +773,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
     // merged division of the product (ModDown and rescale at once): level l drops {q_{l-1}, p_0 .. p_{k-1}}
     c->divround_merged.assign(1 + c->n_q, DivRoundDev());
     c->h_pmod.assign(T, WMul{0.0, 0.0});
+    c->h_Pinv.assign(T, WMul{0.0, 0.0});
     if (c->k > 0 && c->k + 1 <= CKKSMI_MAX_SPECIAL) {
         for (int level = 2; level <= c->n_q; level++) {
             std::vector<int> b(1, level - 1);
@@ -759,6 +784,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
             u64 P = 1;
             for (int m = 0; m < c->k; m++) P = hm::mulmod(P, c->mod[c->n_q + m] % c->mod[i], c->mod[i]);
             c->h_pmod[i] = make_wmul(P, c->mod[i]);
+            c->h_Pinv[i] = make_wmul(hm::invmod(P, c->mod[i]), c->mod[i]);
         }
         c->d_pmod = upload(c, c->h_pmod.data(), c->h_pmod.size(), ok);
     }
@@ -801,6 +827,14 @@ int dev_upload_tables(ckksmi_ctx *c) {
         std::vector<FinConst> fr;
         for (int i = 0; i < c->n_q; i++) fr.push_back(fin(i, 1, (c->mod[i] - 1) / 2));
         c->d_fin_rescale = upload(c, fr.data(), fr.size(), ok);
+        if (c->k > 0 && c->k + 1 <= CKKSMI_MAX_SPECIAL) {
+            std::vector<FinConst> ft((size_t)(c->n_q + 1) * CKKSMI_MAX_SPECIAL, fin(0, 1, 0));
+            for (int level = 1; level <= c->n_q; level++) {
+                ft[(size_t)level * CKKSMI_MAX_SPECIAL] = fin(level - 1, 1, 0);
+                for (int m = 0; m < c->k; m++) ft[(size_t)level * CKKSMI_MAX_SPECIAL + 1 + m] = fd[m];
+            }
+            c->d_fin_tail = upload(c, ft.data(), ft.size(), ok);
+        }
         if (c->d_pmod) {
             std::vector<FinConst> fg((size_t)(c->n_q + 1) * CKKSMI_MAX_SPECIAL, fin(0, 1, 0));
             for (int level = 2; level <= c->n_q; level++) {
@@ -1455,7 +1489,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
                                                 "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel",
                                                 "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel",
-                                                "encoding kernels", "encryption kernels"};
+                                                "encoding kernels", "encryption kernels", "modup_cols_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && kernel_class == CKKSMI_K_INNER_HOISTED && (c->logN < 8 || c->beta_top > INNER_MAX_BETA || getenv("CKKSMI_HOIST_GATHER")))
         return "inner_product_hoisted_kernel";
@@ -1471,6 +1505,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
         if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "%s<%d, %d, 0%s", kn, q, c->alpha, tail); return buf; }
         if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "%s<%d, %d, 1%s", kn, q, c->k, tail); return buf; }
         if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "%s<%d, 1, 1%s", kn, q, tail); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_TAIL) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 3, true>", q, c->k + 1); return buf; }
         if (kernel_class == CKKSMI_K_CONV_COLS_MERGED) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 2, true>", q, c->k + 1); return buf; }
     }
     return names[kernel_class];

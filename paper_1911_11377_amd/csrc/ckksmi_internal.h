@@ -94,7 +94,8 @@ struct ckksmi_ctx {
     WMul *d_pow24 = nullptr;     // [T] 2^24 mod p (matrix-core MAC: recombination of the digit diagonals)
     int fuse_tensor = 1;         // hmul_relin_rescale: the tensor kernel runs the inverse row pass of d2 (CKKSMI_FUSE_TENSOR=0: separate pass)
     int fuse_inv = 1;            // conversion kernels run the inverse column pass of their sources themselves (CKKSMI_FUSE_INV=0: separate pass)
-    int fuse_tail = 1;           // hmul_relin_rescale: ModDown and rescale share their last pass (CKKSMI_FUSE_TAIL=0: two passes)
+    int fuse_tail = 2;           // hmul_relin_rescale: 2 = ModDown and rescale as one conversion and one last pass, 1 = they share
+                                 // their last pass, 0 = two separate DivRounds (CKKSMI_FUSE_TAIL)
     int modup_loop = 1;          // ModUp column pass organised by source tile (CKKSMI_MODUP_LOOP=0: one workgroup per target limb)
     int modup_targets_per_wg = 0;  // 0: chosen from the grid size (CKKSMI_MODUP_TARGETS)
     int mac_mfma = 1;            // conv / FC MAC on the matrix cores where the shape allows (CKKSMI_MAC_MFMA=0: vector ALU only)
@@ -118,9 +119,11 @@ struct ckksmi_ctx {
     unsigned *d_slot_exp = nullptr;     // [N/2] 5^k mod 2N (device-side encoding)
     void *d_ctw = nullptr;              // [N] complex doubles zeta^-brev(x), zeta = exp(i*pi/N)
     int *d_flag = nullptr;              // one word: raised by a kernel that meets an unencodable value
+    FinConst *d_fin_tail = nullptr;     // [n_q + 1][CKKSMI_MAX_SPECIAL]  level, {plain inverse of q_{level-1}, ModDown's constants}
     FinConst *d_fin_merged = nullptr;   // [n_q + 1][CKKSMI_MAX_SPECIAL]  level, member of {q_{level-1}, p_0 ..}
     std::vector<DivRoundDev> divround_merged;  // [n_q + 1] by level; nb == 0 where unavailable
     std::vector<WMul> h_pmod;           // [T] P mod q_i (zero for the special primes)
+    std::vector<WMul> h_Pinv;           // [T] P^-1 mod q_i
     WMul *d_pmod = nullptr;             // device copy; nullptr: merged division unavailable (k = 0 or k + 1 > CKKSMI_MAX_SPECIAL)
     P51Mask p51mask = {{0, 0}};
     bool fused = false;  // N = 2^16: register-tiled passes for everything, steps below optionally fused into them

@@ -572,11 +572,11 @@ __global__ __launch_bounds__(EW_THREADS) void divround_final_kernel(DivFinalArgs
     A.out[((size_t)row * A.nc + i) * N + n] = d2u(v);
 }
 
-// x[row][n] = (x[row][n] + w * a[row][n]) mod p on one limb of every row: row r of x at x + r*x_row_stride, of a at
+// x[row][n] = (wx * x[row][n] + w * a[row][n]) mod p on one limb of every row: row r of x at x + r*x_row_stride, of a at
 // a + (r/2)*a_item_stride + (r%2)*a_comp_stride.  Two words per thread.
 __global__ __launch_bounds__(EW_THREADS) void axpy_limb_kernel(u64d *x, unsigned long long x_row_stride, const u64d *a,
                                                                unsigned long long a_item_stride, unsigned long long a_comp_stride, ModConst mc,
-                                                               WMul w, int logN) {
+                                                               WMul wx, WMul w, int logN) {
     const unsigned pairs = 1u << (logN - 1);
     const unsigned n = blockIdx.x * EW_THREADS + threadIdx.x;
     if (n >= pairs) return;
@@ -584,8 +584,8 @@ __global__ __launch_bounds__(EW_THREADS) void axpy_limb_kernel(u64d *x, unsigned
     ulonglong2 *xp = (ulonglong2 *)(x + (size_t)row * x_row_stride) + n;
     const ulonglong2 av = ((const ulonglong2 *)(a + (size_t)(row / 2) * a_item_stride + (size_t)(row % 2) * a_comp_stride))[n];
     ulonglong2 xv = *xp;
-    xv.x = d2u(canon(u2d(xv.x) + mulmod_w(u2d(av.x), w.w, w.wp, mc.p), mc.p, mc.pinv));
-    xv.y = d2u(canon(u2d(xv.y) + mulmod_w(u2d(av.y), w.w, w.wp, mc.p), mc.p, mc.pinv));
+    xv.x = d2u(canon(mulmod_w(u2d(xv.x), wx.w, wx.wp, mc.p) + mulmod_w(u2d(av.x), w.w, w.wp, mc.p), mc.p, mc.pinv));
+    xv.y = d2u(canon(mulmod_w(u2d(xv.y), wx.w, wx.wp, mc.p) + mulmod_w(u2d(av.y), w.w, w.wp, mc.p), mc.p, mc.pinv));
     *xp = xv;
 }
 

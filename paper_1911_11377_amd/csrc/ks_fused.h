@@ -257,6 +257,11 @@ __global__ __launch_bounds__(V2_THREADS, 3) void conv_cols_kernel(ConvColsArgs A
 // (row r at y + r*y_row_stride), targets = the nc kept limbs, h subtracted.  MODE 2: MODE 1 in the exact form of DivRound:
 // the overshoot v = floor(sum_m y_m * (1/b_m)) of every coefficient (double precision, products and sums in source
 // order, each rounded) is found once from the sources and v * (Bbar mod c) leaves every target.
+// MODE 3: ModDown FOLLOWED BY rescale, in the strict sequence's own bits, as one conversion.  Source 0 is the limb
+// u = x_last * P^-1 + d_last (last = nc, the limb the rescale drops) and sources 1.. are the special limbs (D describes the
+// ModDown over them, with b_idx[0] = last put in front).  Per coefficient the workgroup first forms the ModDown result of
+// the dropped limb in coefficient form, s = u - (ModDown's conversion to limb `last`) * P^-1, and from it the rescale's
+// conversion input y_B = (s + h_B) mod q_last; every target then receives the combination given at modup_cols_target.
 struct ModupColsArgs {
     const u64d *y;                // MODE 0: [items][level][N] conversion inputs y_i, coefficient form, canonical
     unsigned long long y_row_stride;  // MODE 1
@@ -272,6 +277,9 @@ struct ModupColsArgs {
     // constants runs in the workgroup's prologue and the conversion inputs never go through memory
     const double *tw_inv;         // inverse twiddles [T][N]
     const FinConst *fin;          // last-stage constants of source limb s (MODE 0: limb index; MODE 1: s-th dropped limb)
+    // MODE 3: constants of the rescale that follows the ModDown described by D
+    const double *hc2;            // [T] the rescale's h mod c
+    double hb2;                   // the rescale's h mod q_last
 };
 
 // Inverse column pass of one source tile in registers: x in the round-2 register layout on entry, the canonical
@@ -313,8 +321,12 @@ __device__ __forceinline__ void inv_cols_in_regs(double (&x)[16], const double *
     for (int e = 0; e < 16; e++) x[e] = canon(x[e] + F.cadd, p, pinv);
 }
 
-// EXACT: vpack holds the overshoot of the thread's 16 coefficients, 3 bits each; Bm = Bbar mod p
-template <bool P51, int NSRC, int Q, bool EXACT>
+// VARIANT 1 (exact DivRound): vpack holds the overshoot of the thread's 16 coefficients, 3 bits each; Bm = Bbar mod p.
+// VARIANT 2 (ModDown and rescale in one conversion): source 0 is the rescale's conversion input y_B, sources 1.. are
+// ModDown's; Wc[0] = P^-1 mod p, hsub = ModDown's h mod p, Bm = the rescale's h mod p:
+//     value = (sum_a y_a*conv_a - hA) * P^-1 + y_B - hB     (the two conversion results the last pass would subtract,
+//                                                            brought to one: the transforms are linear)
+template <bool P51, int NSRC, int Q, int VARIANT>
 __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], const WMul (&Wc)[NSRC], const double *twl, double *lds, u64d *dst,
                                                   const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store, double hsub,
                                                   unsigned long long vpack, double Bm) {
@@ -324,10 +336,12 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 #pragma unroll
     for (int e = 0; e < 16; e++) {
         double v = -hsub;
-        if (EXACT) v = -reduce_balanced(hsub + (double)(unsigned)((vpack >> (3 * e)) & 7u) * Bm, p, pinv);  // v <= 3: below 4p, exact
+        if (VARIANT == 1) v = -reduce_balanced(hsub + (double)(unsigned)((vpack >> (3 * e)) & 7u) * Bm, p, pinv);  // v <= 3: below 4p, exact
 #pragma unroll
-        for (int a = 0; a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
+        for (int a = (VARIANT == 2 ? 1 : 0); a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
         x[e] = reduce_balanced(v, p, pinv);  // |v| <= p + NSRC * 0.75p
+        if (VARIANT == 2)  // 0.75p + (y_B < 2^51) + p: below 2^53
+            x[e] = reduce_balanced(mulmod_w(x[e], Wc[0].w, Wc[0].wp, p) + yd[0][e] - Bm, p, pinv);
     }
     {
         double tw1[15];
@@ -364,7 +378,7 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 // Four sources in the exact form need more than 256 registers a lane: that instantiation runs one wave per SIMD
 // (measured 0.97 ms against 1.37 ms with spills at two; the three-source ModUp is slower at one, 3.1 against 2.5 ms).
 template <int Q, int NSRC, int MODE, bool INVSRC>
-__global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void modup_cols_kernel(ModupColsArgs A) {
+__global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE >= 2) ? 1 : 2) void modup_cols_kernel(ModupColsArgs A) {
     // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
     // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
     __shared__ double lds[2][16 * V2_GS];
@@ -450,6 +464,25 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void 
             vpack |= (unsigned long long)floor(sum) << (3 * e);
         }
     }
+    if (MODE == 3) {
+        // the dropped limb's ModDown result in coefficient form, then the rescale's conversion input, in place of source 0
+        const int tl = A.nc;
+        const double pl = A.modc[tl].p, plinv = A.modc[tl].pinv;
+        const WMul Pinv = A.D.Binv[tl];
+        const double hA = A.D.hc[tl];
+        WMul Wl[NSRC];
+#pragma unroll
+        for (int a = 1; a < NSRC; a++) Wl[a] = a < nsrc ? A.D.conv[(size_t)(a - 1) * A.T + tl] : WMul{0.0, 0.0};
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            double v = -hA;
+#pragma unroll
+            for (int a = 1; a < NSRC; a++) v += mulmod_w(yd[a][e], Wl[a].w, Wl[a].wp, pl);
+            v = reduce_balanced(v, pl, plinv);
+            const double sl = yd[0][e] - mulmod_w(v, Pinv.w, Pinv.wp, pl);  // (-0.75p, 1.75p)
+            yd[0][e] = canon(sl + A.hb2, pl, plinv);
+        }
+    }
     const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
     // MODE 0: extended-basis index of target k (the digit's own limbs are skipped) and its modulus index;
     // MODE 1: target k is kept limb k
@@ -474,15 +507,20 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void 
             dst = A.dst + (((size_t)item * A.beta + j) * A.E + x) * N;
         } else {
 #pragma unroll
-            for (int a = 0; a < NSRC; a++) Wc[a] = a < nsrc ? A.D.conv[(size_t)a * A.T + t] : WMul{0.0, 0.0};
+            for (int a = 0; a < NSRC; a++)
+                Wc[a] = a < nsrc ? A.D.conv[(size_t)(MODE == 3 ? (a ? a - 1 : 0) : a) * A.T + t] : WMul{0.0, 0.0};
             hsub = A.D.hc[t];
             if (MODE == 2) Bm = A.D.Bmod[t];
+            if (MODE == 3) {
+                Wc[0] = A.D.Binv[t];
+                Bm = A.hc2[t];
+            }
             dst = A.dst + ((size_t)blockIdx.y * A.nc + t) * N;
         }
         if (is_p51(A.p51, t))
-            modup_cols_target<true, NSRC, Q, MODE == 2>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
+            modup_cols_target<true, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
         else
-            modup_cols_target<false, NSRC, Q, MODE == 2>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
+            modup_cols_target<false, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
     }
 }
 
@@ -711,6 +749,7 @@ struct RowsFinalArgs {
     const double *tw;
     const WMul *Binv;    // [T]
     const WMul *pre;     // optional [T]: the addend enters BEFORE the division, out = (x + pre_i*addend - r) * Binv
+    const WMul *xmul;    // optional [T] (without pre): out = (x*xmul_i + addend - r) * Binv
     int logN, nc;
     int limb0;             // first limb handled (grid z counts from it)
     int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
@@ -727,14 +766,14 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
     load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
     const size_t tile0 = (size_t)tile * 4096;
     const WMul W = A.Binv[i];
-    const bool pre = A.pre != nullptr;
-    const WMul Pm = pre ? A.pre[i] : WMul{0.0, 0.0};
+    const bool pre = A.pre != nullptr, xm = A.xmul != nullptr;
+    const WMul Pm = pre ? A.pre[i] : (xm ? A.xmul[i] : WMul{0.0, 0.0});
     const unsigned r0 = blockIdx.x * (unsigned)A.rows_per_x;
     const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
     for (unsigned row = r0; row < r1; row++) {
         const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
         u64d *out = A.out + (size_t)row * A.out_row_stride + (size_t)(i - A.out_limb0) * N + tile0;
-        const bool add = A.addend && (pre || A.add_both || (row & 1u) == 0);
+        const bool add = A.addend && (pre || xm || A.add_both || (row & 1u) == 0);
         const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
         // operands of the last step are requested before the transform so that their latency overlaps it
         // pointwise part in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
@@ -754,9 +793,13 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
                 x0 += mulmod_w(u2d(ar[s].x), Pm.w, Pm.wp, p);
                 x1 += mulmod_w(u2d(ar[s].y), Pm.w, Pm.wp, p);
             }
+            if (xm) {  // |x*xmul + addend - r| < 0.75p + p + p/2 + 1
+                x0 = mulmod_w(x0, Pm.w, Pm.wp, p) + u2d(ar[s].x);
+                x1 = mulmod_w(x1, Pm.w, Pm.wp, p) + u2d(ar[s].y);
+            }
             double v0 = mulmod_w(x0 - rr[0], W.w, W.wp, p);
             double v1 = mulmod_w(x1 - rr[1], W.w, W.wp, p);
-            if (add && !pre) {
+            if (add && !pre && !xm) {
                 v0 += u2d(ar[s].x);
                 v1 += u2d(ar[s].y);
             }

@@ -65,7 +65,7 @@ def test_relin_and_composite_levels_and_digits(be, shape, levels, batch):
 
 
 @pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "6"}, {"CKKSMI_NTT_TARGET_WGS": "64"},
-                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_MODUP_TARGETS": "2"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
+                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_MODUP_TARGETS": "2"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
 def test_alternative_kernel_paths_give_the_same_bits(be, monkeypatch, env):
     """the unfused kernels, partial fusion and long per-workgroup item loops must all match the oracle too"""
     announce("alternative paths %r" % (env,))
@@ -212,8 +212,13 @@ def test_2e16_hybrid_shape_sampled(be):
         b = pc.random_cts(M, level, batch, 4, ("b", level))
         out = be.empty(batch, 2, level - 1, M.N)
         ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+        ctx.profile_enable(True)
         ctx.hmul_relin_rescale(be.to_dev(a), be.to_dev(b), evk, out, level, batch, ws)
         got = be.to_host(out).reshape(batch, 2, level - 1, M.N)
+        ran = ctx.profile_read()
+        ctx.profile_enable(False)
+        # the launch configuration bench.py times: ModDown and rescale as one conversion
+        assert "modup_cols_kernel<4, 4, 3, true>" in ran and "tensor_rows_kernel" in ran, list(ran)
         announce("oracle for item %d at level %d" % (pick, level))
         assert np.array_equal(got[pick], M.O.hmul_relin_rescale(a[pick], b[pick], M.rlk, level))
         del ws, out
