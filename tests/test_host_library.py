@@ -31,6 +31,20 @@ def test_library_exports_every_declared_symbol():
     assert sorted(ckksmi.SIGNATURES) == names, "binding and header disagree on the set of entry points"
 
 
+def test_binding_constants_match_the_header():
+    """kernel classes, sampler kinds and workspace operations: the binding's numbers are the header's, and every class has a name"""
+    text = open(os.path.join(ROOT, "include", "ckksmi.h")).read()
+    defines = {m.group(1): int(m.group(2)) for m in re.finditer(r"#define\s+(CKKSMI_[A-Z0-9_]+)\s+(-?\d+)\b", text)}
+    assert defines["CKKSMI_K_COUNT"] == ckksmi.K_COUNT
+    classes = sorted(v for k, v in defines.items() if k.startswith("CKKSMI_K_") and k != "CKKSMI_K_COUNT")
+    assert classes == list(range(ckksmi.K_COUNT))
+    L = ckksmi.load()
+    for kid in range(ckksmi.K_COUNT):
+        assert L.ckksmi_kernel_class_name(None, kid), "kernel class %d has no name" % kid
+    for name in ("OP_RELIN", "OP_RESCALE", "OP_HMUL_RELIN_RESCALE", "OP_ROTATE", "OP_CONV2D_MAC"):
+        assert getattr(ckksmi, name) == defines["CKKSMI_" + name]
+
+
 def host_ctx(logN, n_q, q_bits, k, special_bits, alpha):
     return ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=-1)
 
