@@ -73,6 +73,7 @@ typedef struct {
 #define CKKSMI_OP_HMUL_RELIN_RESCALE 3
 #define CKKSMI_OP_ROTATE 4
 #define CKKSMI_OP_CONV2D_MAC 5 /* `batch` = number of weights O*C*kh*kw (or O*F) */
+#define CKKSMI_OP_MUL_SCALAR_RESCALE 6
 
 /* ------------------------------------------------------------------ context */
 /* Primes: the n_q largest q_bits-bit primes = 1 mod 2N in descending order, then
@@ -156,6 +157,13 @@ int ckksmi_relin(ckksmi_ctx *ctx, const uint64_t *d, const uint64_t *evk, uint64
 /* divide by q_{level-1} with rounding to nearest: level -> level-1.  out may alias a
  * only when batch == 1 */
 int ckksmi_rescale(ckksmi_ctx *ctx, const uint64_t *a, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* Rescale(c * Drop(a -> level)) + addend, bit-identical to ckksmi_mod_drop, ckksmi_mul_scalar, ckksmi_rescale and
+ * ckksmi_add in a row (the scalar steps of the polynomial activation schedules, section 2.2), without writing the
+ * intermediate ciphertexts: the input is read at its own level level_in >= level (only its first `level` limbs are used),
+ * the scalar rides in the constants of the dropped limb's inverse transform and in the last pass, which also adds the
+ * addend.  a: [batch][2][level_in][N]; addend: NULL or [batch][2][level-1][N] (may be `out` itself);
+ * out: [batch][2][level-1][N], must not alias a; workspace CKKSMI_OP_MUL_SCALAR_RESCALE (for `level`). */
+int ckksmi_mul_scalar_rescale(ckksmi_ctx *ctx, const uint64_t *a, int64_t c, const uint64_t *addend, uint64_t *out, int level_in, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* the strict sequence hmul -> relin -> rescale, bit-identical to the three calls */
 int ckksmi_hmul_relin_rescale(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out /*[2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* Lazy relinearisation (a fewer-transform variant for sums of products; the paper fixes no order): item i holds `terms`

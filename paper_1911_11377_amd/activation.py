@@ -5,9 +5,9 @@ and the degree-2 polynomial of section 3.1).  Two schedules are provided:
   square : y = RS(Relin(x*x))                                          level l -> l-1
   poly3  : 0.5 + 0.25*y - 0.02*y^3 for y at level l, scale s_y          level l -> l-2
              y2 = RS(Relin(y*y))                       level l-1, scale s_2 = s_y^2/q_{l-1}
-             t  = RS(y * round(-0.02*q_{l-1}))         level l-1, scale s_y
+             t  = RS(y * round(-0.02*q_{l-1}))         level l-1, scale s_y   (scalar product and rescale in one call)
              y3 = RS(Relin(y2*t))                      level l-2, scale s_3 = s_2*s_y/q_{l-2}
-             u  = RS(drop(y -> l-1) * round(0.25*s_2)) level l-2, scale s_y*s_2/q_{l-2} = s_3
+             u  = RS(drop(y -> l-1) * round(0.25*s_2)) level l-2, scale s_y*s_2/q_{l-2} = s_3   (drop, product, rescale in one call)
              out = y3 + u + round(0.5*s_3)
   poly2  : c2*x^2 + c1*x (the degree-2 ReLU substitute of section 3.1) for x at level l, scale s   level l -> l-2
              x2 = RS(Relin(x*x))                       level l-1, scale s_2 = s^2/q_{l-1}
@@ -70,19 +70,13 @@ def square(ctx, x, evk, y, level, batch, ws, stream=None):
 def poly3(ctx, y, evk, out, level, batch, consts, ws, stream=None):
     ct = batch * 2 * ctx.N
     y2, ws = _carve(ws, ct * (level - 1))
-    t_full, ws = _carve(ws, ct * level)
     t, ws = _carve(ws, ct * (level - 1))
     y3 = out
     ctx.hmul_relin_rescale(y, y, evk, y2, level, batch, ws, stream=stream)
-    ctx.mul_scalar(y, consts.c_m002, t_full, level, batch, stream=stream)
-    ctx.rescale(t_full, t, level, batch, ws, stream=stream)
+    ctx.mul_scalar_rescale(y, consts.c_m002, t, level, batch, ws, stream=stream)
     ctx.hmul_relin_rescale(y2, t, evk, y3, level - 1, batch, ws, stream=stream)
-    yd, rest = _carve(t_full, ct * (level - 1))  # t_full is free again
-    ctx.mod_drop(y, level, level - 1, yd, batch, stream=stream)
-    ctx.mul_scalar(yd, consts.c_025, yd, level - 1, batch, stream=stream)
-    u = y2[: ct * (level - 2)]                   # y2 is free again
-    ctx.rescale(yd, u, level - 1, batch, ws, stream=stream)
-    ctx.add(y3, u, out, level - 2, batch, stream=stream)
+    # u = RS(drop(y) * c) lands on y3 (= out) in the same pass: drop, product, rescale and sum in one call
+    ctx.mul_scalar_rescale(y, consts.c_025, out, level - 1, batch, ws, stream=stream, level_in=level, addend=y3)
     ctx.add_const(out, consts.c_05, out, level - 2, batch, stream=stream)
 
 
@@ -90,13 +84,8 @@ def poly2(ctx, x, evk, out, level, batch, consts, ws, stream=None):
     """out (level-2) = c2*x^2 + c1*x; ws as sized by workspace_bytes(ctx, level, batch)"""
     ct = batch * 2 * ctx.N
     x2, ws = _carve(ws, ct * (level - 1))
-    xd, ws = _carve(ws, ct * (level - 1))
-    t1, ws = _carve(ws, ct * (level - 2))
     ctx.hmul_relin_rescale(x, x, evk, x2, level, batch, ws, stream=stream)
-    ctx.mul_scalar(x2, consts.k2, x2, level - 1, batch, stream=stream)
-    ctx.rescale(x2, out, level - 1, batch, ws, stream=stream)
-    ctx.mod_drop(x, level, level - 1, xd, batch, stream=stream)
-    ctx.mul_scalar(xd, consts.k1, xd, level - 1, batch, stream=stream)
-    ctx.rescale(xd, t1, level - 1, batch, ws, stream=stream)
-    ctx.add(out, t1, out, level - 2, batch, stream=stream)
+    ctx.mul_scalar_rescale(x2, consts.k2, out, level - 1, batch, ws, stream=stream)
+    # t1 = RS(drop(x) * k1) is added to t2 (in out) by the same pass
+    ctx.mul_scalar_rescale(x, consts.k1, out, level - 1, batch, ws, stream=stream, level_in=level, addend=out)
 

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 DEFAULT_LIB = os.path.join(_HERE, "libckksmi.so")
 
 OK, EINVAL, ELEVEL, ENOKEY, EWORKSPACE, EDEVICE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
-OP_RELIN, OP_RESCALE, OP_HMUL_RELIN_RESCALE, OP_ROTATE, OP_CONV2D_MAC = 1, 2, 3, 4, 5
+OP_RELIN, OP_RESCALE, OP_HMUL_RELIN_RESCALE, OP_ROTATE, OP_CONV2D_MAC, OP_MUL_SCALAR_RESCALE = 1, 2, 3, 4, 5, 6
 
 u64p = C.POINTER(C.c_uint64)
 i64p = C.POINTER(C.c_int64)
@@ -70,6 +70,7 @@ SIGNATURES = {
     "ckksmi_relin": [VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rescale": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_mul_scalar_rescale": [VP, VP, C.c_int64, VP, VP, C.c_int, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_sum_relin_rescale": [VP, VP, VP, C.c_int, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_sample_device": [VP, C.c_int, C.c_double, C.c_uint64, C.c_uint64, C.c_int, VP, VP],
@@ -315,6 +316,12 @@ class Context:
 
     def rescale(self, a, out, level, batch, ws, stream=None):
         self._call("ckksmi_rescale", self._h, _ptr(a), _ptr(out), level, batch, _ptr(ws), _nbytes(ws), self._stream(stream))
+
+    def mul_scalar_rescale(self, a, c, out, level, batch, ws, stream=None, level_in=None, addend=None):
+        """out = Rescale(c * a) at `level` (+ addend, which may be out); level_in > level: a is stored with level_in limbs and
+        dropped to `level` on the way"""
+        self._call("ckksmi_mul_scalar_rescale", self._h, _ptr(a), int(c), _ptr(addend) if addend is not None else None, _ptr(out),
+                   level_in or level, level, batch, _ptr(ws), _nbytes(ws), self._stream(stream))
 
     def hmul_relin_rescale(self, a, b, evk, out, level, batch, ws, stream=None):
         self._call("ckksmi_hmul_relin_rescale", self._h, _ptr(a), _ptr(b), _ptr(evk), _ptr(out), level, batch, _ptr(ws), _nbytes(ws),

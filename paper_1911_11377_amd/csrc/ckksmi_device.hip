@@ -212,9 +212,11 @@ void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u6
 // mode 1: DivRound conversion of `items` rows (y: row r at y + r*y_stride, dst: [rows][nc][N])
 // fin != nullptr: y is the output of the inverse row pass and the kernel runs the inverse column pass itself
 void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t items, int level, int nc,
-                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin = nullptr, const DivRoundDev *D2 = nullptr) {
+                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin = nullptr, const DivRoundDev *D2 = nullptr,
+                       const FinConst *fin_val = nullptr) {
     ModupColsArgs A;
     memset(&A, 0, sizeof(A));
+    if (fin_val) { A.use_fin_val = 1; A.fin_val = *fin_val; }
     if (D2) { A.hc2 = D2->hc; A.hb2 = D2->hb[0]; }
     A.y = (const u64d *)y; A.y_row_stride = y_stride; A.dst = (u64d *)dst; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.cc = c->d_modup_c;
     A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.nc = nc;
@@ -261,7 +263,8 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
 // out + row*out_row_stride + (limb - limb0)*N
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
                        size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st, int limb0 = 0,
-                       int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr, const WMul *xmul = nullptr) {
+                       int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr, const WMul *xmul = nullptr,
+                       const ScalarTab *stab = nullptr) {
     RowsFinalArgs A;
     A.pre = pre;
     A.xmul = xmul;
@@ -276,15 +279,18 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
     A.p51 = c->p51mask;
     const unsigned tiles = (unsigned)(c->N / 4096);
     const unsigned xch = zchunks_for(c, tiles * nz, rows, A.rows_per_x);
-    KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A);
+    if (stab)
+        KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_scalar_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A, *stab);
+    else
+        KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A);
 }
 
 // DivRound conversion of `rows` rows + column pass of the nc results: tmp [rows][nc][N]
 // fin != nullptr: b_scratch holds the output of the inverse row pass only (see launch_modup_cols)
 void launch_div_cols(ckksmi_ctx *c, const u64 *b_scratch, size_t bs_stride, u64 *tmp, int nc, int rows, const DivRoundDev &D, hipStream_t st,
-                     const FinConst *fin = nullptr) {
+                     const FinConst *fin = nullptr, const FinConst *fin_val = nullptr) {
     if (c->modup_loop)
-        launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
+        launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin, nullptr, fin_val);
     else
         launch_conv_cols(c, 1, b_scratch, bs_stride, tmp, (size_t)nc * c->N, nc, rows, 0, &D, (double)rows * nc, st);
 }
@@ -542,6 +548,35 @@ void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int le
     int lidx[1] = {level - 1};
     divround_rows(c, c->divround[1 + (level - 1)], c->d_fin_rescale + (level - 1), lidx, a + (size_t)(level - 1) * N, (size_t)level * N, last,
                   N, a, (size_t)level * N, tmp, level - 1, items * 2, nullptr, 0, 0, 0, out, st);
+}
+
+// Can the rescale of v*a run with the scalar folded into its kernels (inverse transform constants and last pass)?
+bool scalar_rescale_fused_ok(const ckksmi_ctx *c) {
+    return c->fused && (c->fuse & (FUSE_DIVCONV | FUSE_FINAL)) == (FUSE_DIVCONV | FUSE_FINAL) && c->modup_loop && c->fuse_inv;
+}
+
+// out = DivRound_{q_{level-1}}(v * a) without materialising v*a: the dropped limb's inverse transform multiplies by v in its
+// last stage (per-call constants), the last pass multiplies the kept limb by v before the subtraction
+void scalar_rescale_fused(ckksmi_ctx *c, const u64 *a, int64_t v, const u64 *addend, u64 *out, int items, int level_in, int level, u64 *ws,
+                          hipStream_t st) {
+    const size_t N = c->N;
+    const size_t in_stride = (size_t)level_in * N;  // the input rows hold level_in limbs, of which the first `level` are used
+    const int last = level - 1, rows = items * 2;
+    u64 *lastbuf = ws;
+    u64 *tmp = lastbuf + (size_t)rows * N;
+    int lidx[1] = {last};
+    const DivRoundDev &D = c->divround[1 + last];
+    const u64 q = c->mod[last], vm = hm::signed_mod(v, q);
+    FinConst F;
+    F.ninv = make_wmul(hm::mulmod(c->h_ninv[last], vm, q), q);
+    F.wlast = make_wmul(hm::mulmod(hm::mulmod(c->h_inv[last][1], c->h_ninv[last], q), vm, q), q);
+    F.cadd = (double)((q - 1) / 2);
+    F.pad = 0.0;
+    const ScalarTab St = scalar_tab(c, v, level);
+    launch_ntt(c, false, a + (size_t)last * N, lastbuf, table_map(lidx, 1, in_stride, N), rows, st, c->d_fin_rescale + last, 2);
+    launch_div_cols(c, lastbuf, N, tmp, last, rows, D, st, c->d_fin_rescale + last, &F);
+    launch_rows_final(c, tmp, a, in_stride, addend, (size_t)2 * last * N, (size_t)last * N, 1, out, D.Binv, last, rows, st, 0, -1, 0, nullptr, nullptr,
+                      &St);
 }
 
 // Key switch of `items` polynomials.  d_eval: item i's polynomial ([level][N], evaluation
@@ -1009,6 +1044,10 @@ extern "C" int ckksmi_workspace_bytes(const ckksmi_ctx *c, int op, int level, in
             if (level < 2) return CKKSMI_ELEVEL;
             per = rescale_words_per_item(c, level);
             break;
+        case CKKSMI_OP_MUL_SCALAR_RESCALE:
+            if (level < 2) return CKKSMI_ELEVEL;
+            per = rescale_words_per_item(c, level) + 4 * (size_t)level * N;
+            break;
         case CKKSMI_OP_HMUL_RELIN_RESCALE:
             if (level < 2) return CKKSMI_ELEVEL;
             per = 5 * (size_t)level * N + std::max(ks_words_per_item(c, level), rescale_words_per_item(c, level));
@@ -1061,6 +1100,52 @@ extern "C" int ckksmi_rescale(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, i
     for (int b0 = 0; b0 < batch; b0 += chunk) {
         const int items = std::min(chunk, batch - b0);
         rescale_core(c, a + (size_t)b0 * 2 * level * N, out + (size_t)b0 * 2 * (level - 1) * N, items, level, (u64 *)ws, S(stream));
+    }
+    return g.rc();
+}
+
+extern "C" int ckksmi_mul_scalar_rescale(ckksmi_ctx *c, const uint64_t *a, int64_t v, const uint64_t *addend, uint64_t *out, int level_in,
+                                         int level, int batch, void *ws, size_t ws_bytes, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (level < 2 || level_in < level || level_in > c->n_q) return CKKSMI_ELEVEL;
+    if (!a || !out || a == out || (!ws && batch) || !al16(a) || !al16(out) || !al16(ws) || !al16(addend)) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N, per = rescale_words_per_item(c, level) + 4 * (size_t)level * N;
+    const int chunk = sweep_items(ws_bytes, per, batch);
+    if (chunk < 1) return CKKSMI_EWORKSPACE;
+    Guard g(c);
+    hipStream_t st = S(stream);
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        const u64 *ain = a + (size_t)b0 * 2 * level_in * N;
+        u64 *o = out + (size_t)b0 * 2 * (level - 1) * N;
+        const u64 *add = addend ? addend + (size_t)b0 * 2 * (level - 1) * N : nullptr;
+        if (scalar_rescale_fused_ok(c)) {
+            scalar_rescale_fused(c, ain, v, add, o, items, level_in, level, (u64 *)ws, st);
+        } else {
+            // the steps as they are (modulus drop, scalar product, rescale): the product goes through the workspace
+            u64 *prod = (u64 *)ws;
+            const size_t total = (size_t)items * 2 * level * N;
+            const u64 *src = ain;
+            if (level_in != level) {
+                KL(c, CKKSMI_K_ELEMWISE, (double)items * 2 * level, mod_drop_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)ain,
+                   (u64d *)prod, c->logN, level_in, level, total);
+                src = prod;
+            }
+            KL(c, CKKSMI_K_ELEMWISE, (double)items * 2 * level, mul_scalar_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const u64d *)src,
+               (u64d *)prod, c->d_mod, scalar_tab(c, v, level), c->logN, level, total);
+            if (add) {
+                // the addend may be the output buffer itself: the quotient goes through the workspace
+                u64 *res = prod + total + (size_t)items * rescale_words_per_item(c, level);
+                const size_t tout = (size_t)items * 2 * (level - 1) * N;
+                rescale_core(c, prod, res, items, level, prod + total, st);
+                KL(c, CKKSMI_K_ELEMWISE, (double)items * 2 * (level - 1), addsub_kernel, dim3(ew_blocks(tout)), dim3(EW_THREADS), st, (const u64d *)res,
+                   (const u64d *)add, (u64d *)o, c->d_mod, c->logN, level - 1, tout, 0);
+            } else {
+                rescale_core(c, prod, o, items, level, prod + total, st);
+            }
+        }
     }
     return g.rc();
 }

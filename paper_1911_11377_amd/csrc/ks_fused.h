@@ -280,6 +280,9 @@ struct ModupColsArgs {
     // MODE 3: constants of the rescale that follows the ModDown described by D
     const double *hc2;            // [T] the rescale's h mod c
     double hb2;                   // the rescale's h mod q_last
+    // per-call constants of the single source of a rescale whose input is multiplied by a scalar on the way
+    int use_fin_val;
+    FinConst fin_val;
 };
 
 // Inverse column pass of one source tile in registers: x in the round-2 register layout on entry, the canonical
@@ -433,7 +436,7 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE >= 2) ? 1 : 2) void 
                 const int ls = MODE == 0 ? lo + a : a;                 // index of the source among the transformed limbs
                 const int ts = MODE == 0 ? lo + a : A.D.b_idx[a];      // its modulus
                 const double ps = A.modc[ts].p, psinv = A.modc[ts].pinv;
-                const FinConst F = A.fin[ls];
+                const FinConst F = A.use_fin_val ? A.fin_val : A.fin[ls];
                 __syncthreads();  // the previous source is done with twl[2] and lds[0]
                 twl[2][threadIdx.x] = A.tw_inv[(size_t)ts * N + threadIdx.x];
                 __syncthreads();
@@ -757,7 +760,8 @@ struct RowsFinalArgs {
 };
 
 template <bool P51>
-__device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *lds, double *tw1_lds, int i) {
+__device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *lds, double *tw1_lds, int i, bool xm_val = false,
+                                                WMul xmv = WMul{0.0, 0.0}) {
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[i].p, pinv = A.modc[i].pinv;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
@@ -766,14 +770,15 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
     load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
     const size_t tile0 = (size_t)tile * 4096;
     const WMul W = A.Binv[i];
-    const bool pre = A.pre != nullptr, xm = A.xmul != nullptr;
-    const WMul Pm = pre ? A.pre[i] : (xm ? A.xmul[i] : WMul{0.0, 0.0});
+    const bool pre = A.pre != nullptr, xm = xm_val || A.xmul != nullptr;
+    const WMul Pm = pre ? A.pre[i] : (xm_val ? xmv : (xm ? A.xmul[i] : WMul{0.0, 0.0}));
     const unsigned r0 = blockIdx.x * (unsigned)A.rows_per_x;
     const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
     for (unsigned row = r0; row < r1; row++) {
         const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
         u64d *out = A.out + (size_t)row * A.out_row_stride + (size_t)(i - A.out_limb0) * N + tile0;
         const bool add = A.addend && (pre || xm || A.add_both || (row & 1u) == 0);
+        const double has_add = add ? 1.0 : 0.0;
         const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
         // operands of the last step are requested before the transform so that their latency overlaps it
         // pointwise part in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
@@ -793,13 +798,15 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
                 x0 += mulmod_w(u2d(ar[s].x), Pm.w, Pm.wp, p);
                 x1 += mulmod_w(u2d(ar[s].y), Pm.w, Pm.wp, p);
             }
-            if (xm) {  // |x*xmul + addend - r| < 0.75p + p + p/2 + 1
-                x0 = mulmod_w(x0, Pm.w, Pm.wp, p) + u2d(ar[s].x);
-                x1 = mulmod_w(x1, Pm.w, Pm.wp, p) + u2d(ar[s].y);
+            if (xm) {  // |x*xmul + addend - r| < 0.75p + p + p/2 + 1 (without an addend `ar` is a copy of x: not used)
+                // the hmul tail's addend enters before the division; the scalar rescale's one is added to the result
+                const double before = xm_val ? 0.0 : has_add;
+                x0 = mulmod_w(x0, Pm.w, Pm.wp, p) + before * u2d(ar[s].x);
+                x1 = mulmod_w(x1, Pm.w, Pm.wp, p) + before * u2d(ar[s].y);
             }
             double v0 = mulmod_w(x0 - rr[0], W.w, W.wp, p);
             double v1 = mulmod_w(x1 - rr[1], W.w, W.wp, p);
-            if (add && !pre && !xm) {
+            if (add && !pre && (!xm || xm_val)) {
                 v0 += u2d(ar[s].x);
                 v1 += u2d(ar[s].y);
             }
@@ -818,6 +825,18 @@ __global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A)
         rows_final_body<true>(A, lds, tw1_lds, i);
     else
         rows_final_body<false>(A, lds, tw1_lds, i);
+}
+
+// the same with the kept limb multiplied by a per-call scalar first: out = (c*x - r) * Binv (+ addend): rescale of c*x
+__global__ __launch_bounds__(V2_THREADS) void rows_final_scalar_kernel(RowsFinalArgs A, ScalarTab S) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ double tw1_lds[16 * 16];
+    const int i = A.limb0 + (int)blockIdx.z;
+    const WMul xmv = S.c[i];
+    if (is_p51(A.p51, i))
+        rows_final_body<true>(A, lds, tw1_lds, i, true, xmv);
+    else
+        rows_final_body<false>(A, lds, tw1_lds, i, true, xmv);
 }
 
 // ------------------------------------------------------------------ two DivRound final steps in one pass

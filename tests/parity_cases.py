@@ -167,6 +167,33 @@ def case_rescale(be, shape, seed, batch=2, levels=None):
         for i in range(batch):
             assert np.array_equal(got[i], O.rescale(a[i], level)), "rescale differs at level %d" % level
         assert np.array_equal(be.to_host(da).reshape(a.shape), a), "rescale modified its input"
+        # the same division of a scalar multiple, in one call: the bits of the two calls
+        for cst in (-(1 << 38) + 12345, 7, (1 << 52) + 3):
+            out2 = be.empty(batch, 2, level - 1, O.N)
+            nb = ctx.workspace_bytes(ckksmi.OP_MUL_SCALAR_RESCALE, level, batch)
+            ws2 = be.ws(nb // batch + 8 if (batch > 1 and cst == 7) else nb)  # once with room for one item only
+            ctx.mul_scalar_rescale(da, cst, out2, level, batch, ws2, stream=be.stream)
+            got2 = be.to_host(out2).reshape(batch, 2, level - 1, O.N)
+            for i in range(batch):
+                assert np.array_equal(got2[i], O.rescale(O.mul_scalar(a[i], cst, level), level)), "scalar rescale differs at level %d" % level
+        assert np.array_equal(be.to_host(da).reshape(a.shape), a), "scalar rescale modified its input"
+        if level >= 3:  # input stored one level higher: the drop rides along
+            out3 = be.empty(batch, 2, level - 2, O.N)
+            ctx.mul_scalar_rescale(da, -99991, out3, level - 1, batch, be.ws(ctx.workspace_bytes(ckksmi.OP_MUL_SCALAR_RESCALE, level - 1, batch)),
+                                   stream=be.stream, level_in=level)
+            got3 = be.to_host(out3).reshape(batch, 2, level - 2, O.N)
+            for i in range(batch):
+                want = O.rescale(O.mul_scalar(a[i][:, : level - 1], -99991, level - 1), level - 1)
+                assert np.array_equal(got3[i], want), "scalar rescale with a drop differs at level %d" % level
+            # ... and added onto a ciphertext already in the output buffer
+            base = random_cts(M, level - 2, batch, seed, ("rs.add", level))
+            out4 = be.to_dev(base)
+            ctx.mul_scalar_rescale(da, -99991, out4, level - 1, batch, be.ws(ctx.workspace_bytes(ckksmi.OP_MUL_SCALAR_RESCALE, level - 1, batch)),
+                                   stream=be.stream, level_in=level, addend=out4)
+            got4 = be.to_host(out4).reshape(batch, 2, level - 2, O.N)
+            for i in range(batch):
+                want = O.add(O.rescale(O.mul_scalar(a[i][:, : level - 1], -99991, level - 1), level - 1), base[i], level - 2)
+                assert np.array_equal(got4[i], want), "scalar rescale with an addend differs at level %d" % level
     ctx.close()
 
 

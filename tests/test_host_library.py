@@ -41,7 +41,7 @@ def test_binding_constants_match_the_header():
     L = ckksmi.load()
     for kid in range(ckksmi.K_COUNT):
         assert L.ckksmi_kernel_class_name(None, kid), "kernel class %d has no name" % kid
-    for name in ("OP_RELIN", "OP_RESCALE", "OP_HMUL_RELIN_RESCALE", "OP_ROTATE", "OP_CONV2D_MAC"):
+    for name in ("OP_RELIN", "OP_RESCALE", "OP_HMUL_RELIN_RESCALE", "OP_ROTATE", "OP_CONV2D_MAC", "OP_MUL_SCALAR_RESCALE"):
         assert getattr(ckksmi, name) == defines["CKKSMI_" + name]
 
 
