@@ -220,7 +220,7 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     wp = torch.empty(packed.workspace_bytes(c2, plan) // 8, dtype=torch.int64, device="cuda:0")
     op = torch.empty((2, L - 1, N), dtype=torch.int64, device="cuda:0")
     ms = timed(torch, lambda: packed.linear_transform(c2, a2[0], plan, op, wp), 3)
-    out["packed_fc64_2e14"] = {"ms_per_layer": round(ms, 3), "what": "64x64 dense layer on one ciphertext: 63 rotations from one ModUp per 16, level 8 -> 7"}
+    out["packed_fc64_2e14"] = {"ms_per_layer": round(ms, 3), "what": "64x64 dense layer on one ciphertext: 63 rotations from one ModUp, level 8 -> 7"}
     del lay_keys, wp, op, plan
     del a2, b2, k2, gks, o2, or2, w2, oh, wh
     c2.close()

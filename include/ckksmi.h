@@ -212,7 +212,7 @@ int ckksmi_encrypt_device(ckksmi_ctx *ctx, const uint64_t *pk, const uint64_t *p
  * dt_j = NTT(ModUp_j(INTT(c1))), and rotation r applies its automorphism to the lifted digits before the inner product
  * with its key: acc_c = sum_j sigma_r(dt_j) * gk_r[j][c], ks = DivRound_P(acc), out = (sigma_r(c0) + ks0, ks1).
  * Decrypts like ckksmi_rotate's result but is NOT bit-identical to it (sigma(ModUp(d)) and ModUp(sigma(d)) are
- * different lifts of the same polynomial).  rot: host array of n_rot offsets (1 <= n_rot <= 16), each with a
+ * different lifts of the same polynomial).  rot: host array of n_rot offsets (1 <= n_rot <= 64), each with a
  * registered key, CKKSMI_ENOKEY otherwise; out: device [batch][n_rot][2][level][N], must not alias a;
  * ws: device workspace of ckksmi_rotate_hoisted_workspace_bytes(level, batch, n_rot) bytes (a smaller one makes
  * several sweeps; CKKSMI_EWORKSPACE if not even one item fits). */

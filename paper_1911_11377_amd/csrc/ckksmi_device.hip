@@ -373,7 +373,14 @@ void launch_hoisted_inner(ckksmi_ctx *c, const HoistPlan &H, const u64 *dt, cons
     if (c->logN >= 8 && A.beta <= INNER_MAX_BETA && EW_THREADS == 256 && !getenv("CKKSMI_HOIST_GATHER")) {
         // source rows staged in LDS once for all rotations
         A.items_per_wg = std::max(1, std::min(items, HOIST_LDS_WORDS / 256 / A.beta));
-        const unsigned z = (unsigned)((items + A.items_per_wg - 1) / A.items_per_wg);
+        A.item_chunks = (items + A.items_per_wg - 1) / A.items_per_wg;
+        // few items: the rotations are spread over workgroups as well, until the chip is filled (each rotation chunk stages
+        // the source runs again)
+        const size_t base = (size_t)(c->N / 256) * A.E * A.item_chunks;
+        int rot_chunks = (int)std::min<size_t>((size_t)H.R, (2048 + base - 1) / base);
+        A.rots_per_wg = (H.R + rot_chunks - 1) / rot_chunks;
+        rot_chunks = (H.R + A.rots_per_wg - 1) / A.rots_per_wg;
+        const unsigned z = (unsigned)(A.item_chunks * rot_chunks);
         KL(c, CKKSMI_K_INNER_HOISTED, (double)items * H.R * A.E, inner_product_hoisted_tile_kernel, dim3((unsigned)(c->N / 256), A.E, z),
            dim3(EW_THREADS), st, A);
         return;

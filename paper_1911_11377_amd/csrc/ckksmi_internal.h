@@ -14,7 +14,7 @@ typedef unsigned __int128 u128;
 #define CKKSMI_MAX_SPECIAL 4
 #define CKKSMI_MAX_ALPHA 4
 #define CKKSMI_MAX_MODULI 72
-#define CKKSMI_MAX_KEYS 16     // distinct switching keys one launch can address
+#define CKKSMI_MAX_KEYS 64     // distinct switching keys one launch can address (tables of pointers travel as kernel arguments)
 #define CKKSMI_MAX_ITEMS 256   // items per key-switch sweep (per-item tables travel as kernel arguments)
 
 // ---- host integer helpers (host_math.cpp) ----

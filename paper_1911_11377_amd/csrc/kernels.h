@@ -608,6 +608,7 @@ struct HoistArgs {
     int logN, level, E, n_q, alpha, beta, T;
     int items, R;
     int items_per_wg;                  // tile kernel: items whose source rows share the workgroup's LDS
+    int rots_per_wg, item_chunks;      // tile kernel: grid z = item chunk + item_chunks * rotation chunk
     unsigned g[CKKSMI_MAX_KEYS];
     unsigned ginv[CKKSMI_MAX_KEYS];    // g^-1 mod 2N
     const u64d *key[CKKSMI_MAX_KEYS];
@@ -680,7 +681,7 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_kernel(Hoist
 // in LDS (read from HBM once for all rotations), then walks the rotations: rotation r sends this run to exactly one
 // 256-word run of its output (found through the inverse automorphism), gathered out of LDS.
 #define HOIST_LDS_WORDS 8192  // 64 KiB: items_per_wg * beta * 256 words
-// grid: x = source run (N/256), y = extended limb, z = chunk of items_per_wg items
+// grid: x = source run (N/256), y = extended limb, z = (chunk of items_per_wg items, chunk of rots_per_wg rotations)
 __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(HoistArgs A) {
     __shared__ double tile[HOIST_LDS_WORDS];
     const unsigned N = 1u << A.logN;
@@ -688,7 +689,9 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
     const ModConst mc = A.modc[t];
     const int j_own = (A.d_eval && (int)x < A.level) ? (int)x / A.alpha : -1;
-    const int item0 = (int)blockIdx.z * A.items_per_wg;
+    const int item0 = (int)(blockIdx.z % (unsigned)A.item_chunks) * A.items_per_wg;
+    const int r_begin = (int)(blockIdx.z / (unsigned)A.item_chunks) * A.rots_per_wg;
+    const int r_end = r_begin + A.rots_per_wg < A.R ? r_begin + A.rots_per_wg : A.R;
     const int n_items = (item0 + A.items_per_wg < A.items ? item0 + A.items_per_wg : A.items) - item0;
     for (int ii = 0; ii < n_items; ii++) {
         // all digits of an item requested together (a load per iteration followed by its LDS write would serialise them)
@@ -707,14 +710,14 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
     __syncthreads();
     // the key words of rotation r + 1 are requested before the sums of rotation r, so their latency is covered
     double kn0[INNER_MAX_BETA], kn1[INNER_MAX_BETA];
-    unsigned m_next = (automorphism_source(src0, A.ginv[0], A.logN) & ~255u) + tid;  // this run's image under rotation 0
+    unsigned m_next = (automorphism_source(src0, A.ginv[r_begin], A.logN) & ~255u) + tid;  // this run's image under the first rotation
 #pragma unroll
     for (int j = 0; j < INNER_MAX_BETA; j++)
         if (j < A.beta) {
-            kn0[j] = u2d(A.key[0][(((size_t)j * 2 + 0) * A.T + t) * N + m_next]);
-            kn1[j] = u2d(A.key[0][(((size_t)j * 2 + 1) * A.T + t) * N + m_next]);
+            kn0[j] = u2d(A.key[r_begin][(((size_t)j * 2 + 0) * A.T + t) * N + m_next]);
+            kn1[j] = u2d(A.key[r_begin][(((size_t)j * 2 + 1) * A.T + t) * N + m_next]);
         }
-    for (int r = 0; r < A.R; r++) {
+    for (int r = r_begin; r < r_end; r++) {
         const unsigned m = m_next;
         const unsigned s = automorphism_source(m, A.g[r], A.logN) - src0;  // below 256
         double k0[INNER_MAX_BETA], k1[INNER_MAX_BETA];
@@ -723,7 +726,7 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
             k0[j] = kn0[j];
             k1[j] = kn1[j];
         }
-        if (r + 1 < A.R) {
+        if (r + 1 < r_end) {
             m_next = (automorphism_source(src0, A.ginv[r + 1], A.logN) & ~255u) + tid;
             const u64d *key = A.key[r + 1];
 #pragma unroll

@@ -21,7 +21,7 @@ import numpy as np
 
 from . import ckksmi
 
-MAX_ROTATIONS_PER_CALL = 16  # distinct keys one ckksmi_rotate_hoisted call can address
+MAX_ROTATIONS_PER_CALL = 64  # distinct keys one ckksmi_rotate_hoisted call can address
 
 
 def square_pad(M):
@@ -92,22 +92,25 @@ def plan_linear(ctx, M, level, to_dev, encode=None):
     return LinearPlan(level, Msq.shape[0], rots, pts, pt0)
 
 
-def workspace_bytes(ctx, plan):
+def workspace_bytes(ctx, plan, max_rotations=MAX_ROTATIONS_PER_CALL):
     """bytes for the `ws` argument of linear_transform (device scratch for the rotated copies, the rotations' own
     workspace, the running sum and the rescale)"""
     L, N = plan.level, ctx.N
-    R = min(len(plan.rotations), MAX_ROTATIONS_PER_CALL)
+    R = min(len(plan.rotations), max_rotations)
     ct = 2 * L * N * 8
     rot_ws = ctx.rotate_hoisted_workspace_bytes(L, 1, R) if R else 0
     return (R + 1) * ct + max(rot_ws, ctx.workspace_bytes(ckksmi.OP_RESCALE, L, 1))
 
 
-def linear_transform(ctx, x, plan, out, ws, stream=None):
+def linear_transform(ctx, x, plan, out, ws, stream=None, max_rotations=MAX_ROTATIONS_PER_CALL):
     """out [2][level-1][N] = RS(sum_d pt_d * Rot_d(x)) for one ciphertext x [2][level][N] (device, torch-like buffers that
-    support flat slicing).  The Galois keys of plan.rotations must be registered.  ws: workspace_bytes(ctx, plan)."""
+    support flat slicing).  The Galois keys of plan.rotations must be registered.  ws: workspace_bytes(ctx, plan).
+    max_rotations: rotations per ckksmi_rotate_hoisted call (less workspace for a smaller value, more calls)."""
+    if not 1 <= max_rotations <= MAX_ROTATIONS_PER_CALL:
+        raise ValueError("max_rotations out of range")
     L, N = plan.level, ctx.N
     ct = 2 * L * N
-    R_max = min(len(plan.rotations), MAX_ROTATIONS_PER_CALL)
+    R_max = min(len(plan.rotations), max_rotations)
     flat = ws.reshape(-1) if hasattr(ws, "reshape") else ws
     rotated = flat[: R_max * ct]
     acc = flat[R_max * ct: (R_max + 1) * ct]
@@ -116,8 +119,8 @@ def linear_transform(ctx, x, plan, out, ws, stream=None):
     if plan.pt0 is not None:
         ctx.mul_plain(x, plan.pt0, 0, acc, L, 1, stream=stream)
         have_acc = True
-    for c0 in range(0, len(plan.rotations), MAX_ROTATIONS_PER_CALL):
-        rots = plan.rotations[c0: c0 + MAX_ROTATIONS_PER_CALL]
+    for c0 in range(0, len(plan.rotations), max_rotations):
+        rots = plan.rotations[c0: c0 + max_rotations]
         R = len(rots)
         ctx.rotate_hoisted(x, rots, rotated, L, 1, rest, stream=stream)
         # every rotated copy times its diagonal: R items, plaintext r for item r

@@ -338,7 +338,7 @@ def case_rotate_hoisted(be, shape, seed, rotations, batch=3, level=None, small_w
     ctx.close()
 
 
-def case_packed_layer(be, shape, seed, M_float, level=None):
+def case_packed_layer(be, shape, seed, M_float, level=None, max_rotations=None):
     """a rotation-packed layer (matrix through hoisted rotations, plaintext diagonals, tree of adds, rescale) against the
     oracle's schedule, word for word; the encoded diagonals are inputs of both sides"""
     from paper_1911_11377_amd import packed
@@ -373,8 +373,9 @@ def case_packed_layer(be, shape, seed, M_float, level=None):
     order = ([] if plan.pt0 is None else [0])
     by_d = dict(zip(list(plan.rotations) + order, [pts[i] for i in range(len(pts))]))
     out = be.empty(2, level - 1, O.N)
-    ws = be.ws(packed.workspace_bytes(ctx, plan))
-    packed.linear_transform(ctx, be.to_dev(x), plan, out, ws, stream=be.stream)
+    mr = max_rotations or packed.MAX_ROTATIONS_PER_CALL
+    ws = be.ws(packed.workspace_bytes(ctx, plan, mr))
+    packed.linear_transform(ctx, be.to_dev(x), plan, out, ws, stream=be.stream, max_rotations=mr)
     got = be.to_host(out).reshape(2, level - 1, O.N)
     want = O.linear_transform(x, by_d, M.gk, level)
     assert np.array_equal(got, want), "packed layer differs from the oracle"
@@ -469,7 +470,7 @@ def case_variant_errors(be, shape=(6, 3, 30, 1, 31, 1)):
     refused(ckksmi.EINVAL, ctx.hmul_sum_relin_rescale, a, a, 0, a, out, L, 1, ws)
     refused(ckksmi.EWORKSPACE, ctx.hmul_sum_relin_rescale, a, a, 2, a, out, L, 1, tiny_ws)
     refused(ckksmi.EINVAL, ctx.rotate_hoisted, a, [], out, L, 1, ws)
-    refused(ckksmi.EINVAL, ctx.rotate_hoisted, a, list(range(1, 18)), out, L, 1, ws)
+    refused(ckksmi.EINVAL, ctx.rotate_hoisted, a, list(range(1, 66)), out, L, 1, ws)
     refused(ckksmi.ENOKEY, ctx.rotate_hoisted, a, [1], out, L, 1, ws)
     ctx.galois_key_register(1, be.empty(ctx.beta_top, 2, L + shape[3], N))
     refused(ckksmi.EWORKSPACE, ctx.rotate_hoisted, a, [1], out, L, 1, tiny_ws)

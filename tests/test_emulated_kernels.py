@@ -179,6 +179,7 @@ def test_emulated_rotation_packed_layers(be):
     """single-image packing: a dense layer (every diagonal, two chunks of rotations) and a sparse convolution matrix"""
     from paper_1911_11377_amd import packed, workloads as wl
     pc.case_packed_layer(be, (6, 3, 40, 2, 41, 2), 134, wl.weights_float((32, 20), 134, "fc"))
+    pc.case_packed_layer(be, (6, 3, 40, 2, 41, 2), 134, wl.weights_float((32, 20), 134, "fc"), max_rotations=7)  # five calls, ragged last
     w = wl.weights_float((2, 2, 3, 3), 135, "conv")
     pc.case_packed_layer(be, (7, 3, 40, 1, 41, 1), 135, packed.conv_matrix(w, 4, 4, 1))
 

@@ -336,11 +336,12 @@ def test_sum_of_products_matches_oracle(be, shape, levels, terms, batch):
 
 
 def test_rotation_packed_layers_match_oracle(be):
-    """single-image packing: a dense layer (63 rotations in four hoisted calls) and a sparse convolution matrix on one
+    """single-image packing: a dense layer (63 rotations from one ModUp, then again in calls of 16) and a sparse convolution matrix on one
     ciphertext, word for word against the oracle's schedule, and decrypting to the matrix-vector product"""
     from paper_1911_11377_amd import packed
     announce("rotation-packed dense layer 64x48, N=2^13")
     pc.case_packed_layer(be, (13, 3, 40, 2, 41, 2), 350, wl.weights_float((64, 48), 350, "fc"))
+    pc.case_packed_layer(be, (13, 3, 40, 2, 41, 2), 350, wl.weights_float((64, 48), 350, "fc"), max_rotations=16)
     announce("rotation-packed convolution 4->4 channels 3x3 on 8x8, N=2^13")
     w = wl.weights_float((4, 4, 3, 3), 351, "conv")
     pc.case_packed_layer(be, (13, 3, 40, 1, 41, 1), 351, packed.conv_matrix(w, 8, 8, 1))
