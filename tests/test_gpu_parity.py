@@ -58,6 +58,8 @@ def test_tiny_shape_full_batch(be):
     ((9, 7, 50, 3, 51, 3), [7, 6, 5, 2], 2),
     ((13, 3, 50, 1, 51, 1), [3], 2),
     ((15, 3, 50, 3, 51, 3), [3, 2], 1),
+    ((13, 7, 50, 3, 51, 3), [7, 6, 5, 3], 2),   # register-tiled size, last digit of 1, 3 and 2 limbs
+    ((14, 5, 51, 2, 51, 2), [5, 4, 2], 2),      # 51-bit primes throughout: the tighter reduction schedule everywhere
 ])
 def test_relin_and_composite_levels_and_digits(be, shape, levels, batch):
     announce("relin/composite %r levels %r" % (shape, levels))
@@ -232,6 +234,7 @@ def test_2e16_hybrid_shape_sampled(be):
     ((14, 3, 50, 2, 51, 2), [3, 2], 3),
     ((15, 3, 50, 3, 51, 3), [3, 2], 1),
     ((16, 4, 50, 3, 51, 3), [4, 2], 3),
+    ((13, 7, 50, 3, 51, 3), [7, 6, 5, 3], 2),
 ])
 def test_merged_product_matches_oracle(be, shape, levels, batch):
     """the product with one division by P*q_last (exact DivRound): every word against the oracle's definition"""
