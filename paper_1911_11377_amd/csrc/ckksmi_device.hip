@@ -476,6 +476,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
                       acc, (size_t)E * N, tmp, level, items * R * 2, hoist->sig, (size_t)level * N, 0, 0, out, st);
         return;
     }
+    bool tail_folded = false;
     if (c->fuse & FUSE_INNER) {
         RowsInnerArgs RI;
         RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
@@ -484,6 +485,10 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         const unsigned tiles = (unsigned)(N / 4096);
         RI.kt = tiles < 8 ? tiles : 8;
         RI.p51 = c->p51mask;
+        RI.fold_tail = (tail_scratch && c->fuse_tail >= 3 && c->modup_loop && c->fuse_inv && c->d_fin_tail && add_both) ? 1 : 0;
+        RI.Pinv = c->divround[0].Binv;
+        RI.addend = (const u64d *)addend; RI.add_item_stride = add_item_stride; RI.add_comp_stride = add_comp_stride;
+        tail_folded = RI.fold_tail != 0;
         KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
     } else {
         launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
@@ -521,6 +526,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
             // u = x_last * P^-1 + d_last replaces the dropped limb, its inverse transform rides with the special limbs'
             const int last = level - 1;
             u64 *bl = acc + (size_t)last * N;  // limbs last, p_0 .. p_{k-1} of every row: contiguous in the extended layout
+            if (!tail_folded)
             KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
                (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)last * N), (unsigned long long)add_item_stride,
                (unsigned long long)add_comp_stride, c->h_modc[last], c->h_Pinv[last], make_wmul(1, c->mod[last]), c->logN);
@@ -531,8 +537,11 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
             const FinConst *ft = c->d_fin_tail + (size_t)level * CKKSMI_MAX_SPECIAL;
             launch_ntt(c, false, bl, bl, table_map(D3.b_idx, D3.nb, (size_t)E * N, (size_t)E * N), rows, st, ft, 2);
             launch_modup_cols(c, 3, bl, (size_t)E * N, tmp, rows, 0, last, &D3, (double)rows * last, st, ft, &DB);
-            launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, DB.Binv, last, rows, st, 0, -1, 0, nullptr,
-                              DA.Binv);
+            if (tail_folded)  // the kept limbs already hold x * P^-1 + d
+                launch_rows_final(c, tmp, acc, (size_t)E * N, nullptr, 0, 0, 0, out, DB.Binv, last, rows, st);
+            else
+                launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, DB.Binv, last, rows, st, 0, -1, 0,
+                                  nullptr, DA.Binv);
             return;
         }
         launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown, finv ? 2 : 3);

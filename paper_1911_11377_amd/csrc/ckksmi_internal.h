@@ -94,7 +94,8 @@ struct ckksmi_ctx {
     WMul *d_pow24 = nullptr;     // [T] 2^24 mod p (matrix-core MAC: recombination of the digit diagonals)
     int fuse_tensor = 1;         // hmul_relin_rescale: the tensor kernel runs the inverse row pass of d2 (CKKSMI_FUSE_TENSOR=0: separate pass)
     int fuse_inv = 1;            // conversion kernels run the inverse column pass of their sources themselves (CKKSMI_FUSE_INV=0: separate pass)
-    int fuse_tail = 2;           // hmul_relin_rescale: 2 = ModDown and rescale as one conversion and one last pass, 1 = they share
+    int fuse_tail = 3;           // hmul_relin_rescale: 3 = as 2, and the fused inner product already writes x*P^-1 + d for the ciphertext
+                                 // limbs; 2 = ModDown and rescale as one conversion and one last pass, 1 = they share
                                  // their last pass, 0 = two separate DivRounds (CKKSMI_FUSE_TAIL)
     int modup_loop = 1;          // ModUp column pass organised by source tile (CKKSMI_MODUP_LOOP=0: one workgroup per target limb)
     int modup_targets_per_wg = 0;  // 0: chosen from the grid size (CKKSMI_MODUP_TARGETS)

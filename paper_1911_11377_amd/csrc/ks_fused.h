@@ -584,6 +584,12 @@ struct RowsInnerArgs {
     int logN, level, E, n_q, alpha, beta, T;
     unsigned kt;         // min(N/4096, 8): see the grid mapping in rows_inner_body
     P51Mask p51;
+    // fold_tail: the product's ModDown + rescale follows as one conversion and one last pass; the ciphertext limbs then
+    // leave this kernel as z = acc * P^-1 + d (d = the product's component of the same row), which is what both of them read
+    int fold_tail;
+    const WMul *Pinv;    // [T] P^-1 mod q_i
+    const u64d *addend;  // item i, component c, limb l at addend + i*add_item_stride + c*add_comp_stride + l*N
+    unsigned long long add_item_stride, add_comp_stride;
 };
 
 template <bool P51>
@@ -717,6 +723,26 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     }
     u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
+    if (A.fold_tail && (int)x < A.level) {
+        const WMul Pi = A.Pinv[t];
+        const u64d *d0 = A.addend + (size_t)item * A.add_item_stride + (size_t)x * N + tile0;
+        const u64d *d1 = d0 + A.add_comp_stride;
+        ulonglong2 dw0[8], dw1[8];
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            dw0[s] = ((const ulonglong2 *)d0)[256 * s + tid];
+            dw1[s] = ((const ulonglong2 *)d1)[256 * s + tid];
+        }
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            // accumulators are below 2^53: the prepared product is exact for them as they are
+            const double z00 = mulmod_w(a0[2 * s], Pi.w, Pi.wp, p) + u2d(dw0[s].x), z01 = mulmod_w(a0[2 * s + 1], Pi.w, Pi.wp, p) + u2d(dw0[s].y);
+            const double z10 = mulmod_w(a1[2 * s], Pi.w, Pi.wp, p) + u2d(dw1[s].x), z11 = mulmod_w(a1[2 * s + 1], Pi.w, Pi.wp, p) + u2d(dw1[s].y);
+            ((ulonglong2 *)o0)[256 * s + tid] = make_ulonglong2(d2u(canon(z00, p, pinv)), d2u(canon(z01, p, pinv)));
+            ((ulonglong2 *)o1)[256 * s + tid] = make_ulonglong2(d2u(canon(z10, p, pinv)), d2u(canon(z11, p, pinv)));
+        }
+        return;
+    }
 #pragma unroll
     for (int s = 0; s < 8; s++) {
         ((ulonglong2 *)o0)[256 * s + tid] = make_ulonglong2(d2u(canon(a0[2 * s], p, pinv)), d2u(canon(a0[2 * s + 1], p, pinv)));
