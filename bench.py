@@ -59,8 +59,10 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "axpy_limb_kernel": 3 * w,
         "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
-        "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch),   # beta limbs in, 2 out, key once per batch
-        "rows_final_kernel": 4 * w,                                  # column-pass output, x, addend in; out
+        # beta limbs in, 2 out, key once per batch; the ciphertext limbs also read the product's two components (the
+        # z = x*P^-1 + d that the tail of HMult+relin+rescale consumes is formed here)
+        "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch + 2.0 * level / E),
+        "rows_final_kernel": 3 * w,                                  # column-pass output and z in; out (4 with a separate addend)
         "rows_final2_kernel": 5 * w,                                 # two column-pass outputs, x, addend in; out
         "elementwise kernels": 3 * w,
     }
@@ -88,7 +90,8 @@ def laneops_per_unit(name, N, level, k, alpha):
         # per word: a row pass for every digit except the limb's own one (level of the E limbs have one), two
         # multiply-accumulates per digit (key word conversion 2 + exact product 5 + add 1, the prepared quotient and the
         # lazy reductions shared: about 2 more per digit), canonical form of the two results
-        "rows_inner_kernel": N * ((beta - float(level) / (level + k)) * xform_pass + beta * (2 * 8 + 2) + 2 * 7),
+        "rows_inner_kernel": N * ((beta - float(level) / (level + k)) * xform_pass + beta * (2 * 8 + 2) + 2 * 7
+                                  + 2 * (5 + 3) * float(level) / (level + k)),
         "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),   # (+5 when the kept limb is scaled before the subtraction)
         "rows_final2_kernel": N * (2 * xform_pass + 2 + 1 + 5 + 3 + 1 + 5 + 7 + 2),
     }
@@ -100,10 +103,10 @@ def laneops_per_unit(name, N, level, k, alpha):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
     "modup_cols_kernel<4, 3, 0, true>": (2.0 * 618083 + 6397952) * 1024,
-    "rows_inner_kernel": (2.0 * 3846468 + 1916928) * 1024,
+    "rows_inner_kernel": (2.0 * 4582582 + 1824768) * 1024,
     "rows_final2_kernel": (2.0 * 3066124 + 1507328) * 1024,
     "tensor_rows_kernel": (2.0 * 1963578 + 3145728) * 1024,
-    "rows_final_kernel": (2.0 * 2311265 + 1507328) * 1024,
+    "rows_final_kernel": (2.0 * 1556772 + 1507328) * 1024,
     "modup_cols_kernel<4, 4, 3, true>": (2.0 * 133455 + 1507328) * 1024,
 }
 
