@@ -101,7 +101,7 @@ def test_emulated_partial_fusion(be, monkeypatch, fuse):
     pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=115, batch=1, levels=[4 if fuse % 2 else 3])
 
 
-@pytest.mark.parametrize("env", [{"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_FUSE_TAIL": "2"}, {"CKKSMI_MODUP_TARGETS": "3"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}, {"CKKSMI_FUSE_TAIL": "0", "CKKSMI_FUSE_TENSOR": "1"}])
+@pytest.mark.parametrize("env", [{"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_FUSE_TAIL": "2"}, {"CKKSMI_FUSE": "13"}, {"CKKSMI_MODUP_TARGETS": "3"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}, {"CKKSMI_FUSE_TAIL": "0", "CKKSMI_FUSE_TENSOR": "1"}])
 def test_emulated_alternative_key_switch_paths(be, monkeypatch, env):
     """one workgroup per target limb in ModUp, separate ModDown / rescale passes, several target chunks per source tile"""
     for k, v in env.items():

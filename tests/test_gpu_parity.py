@@ -67,7 +67,7 @@ def test_relin_and_composite_levels_and_digits(be, shape, levels, batch):
 
 
 @pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "6"}, {"CKKSMI_NTT_TARGET_WGS": "64"},
-                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_FUSE_TAIL": "2"}, {"CKKSMI_MODUP_TARGETS": "2"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
+                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_FUSE_TAIL": "2"}, {"CKKSMI_FUSE": "13"}, {"CKKSMI_MODUP_TARGETS": "2"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
 def test_alternative_kernel_paths_give_the_same_bits(be, monkeypatch, env):
     """the unfused kernels, partial fusion and long per-workgroup item loops must all match the oracle too"""
     announce("alternative paths %r" % (env,))
