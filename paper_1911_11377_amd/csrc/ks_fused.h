@@ -332,7 +332,7 @@ __device__ __forceinline__ void inv_cols_in_regs(double (&x)[16], const double *
 template <bool P51, int NSRC, int Q, int VARIANT>
 __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], const WMul (&Wc)[NSRC], const double *twl, double *lds, u64d *dst,
                                                   const ColsGeom<Q> &geo, double p, double pinv, double *twl_next, double tw_store, double hsub,
-                                                  unsigned long long vpack, double Bm) {
+                                                  unsigned long long vpack, double Bm, const double *ybl = nullptr) {
     typedef ColsGeom<Q> Geo;
     typedef ColsMasks<Q, P51> Mk;
     double x[16];
@@ -344,7 +344,7 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
         for (int a = (VARIANT == 2 ? 1 : 0); a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
         x[e] = reduce_balanced(v, p, pinv);  // |v| <= p + NSRC * 0.75p
         if (VARIANT == 2)  // 0.75p + (y_B < 2^51) + p: below 2^53
-            x[e] = reduce_balanced(mulmod_w(x[e], Wc[0].w, Wc[0].wp, p) + yd[0][e] - Bm, p, pinv);
+            x[e] = reduce_balanced(mulmod_w(x[e], Wc[0].w, Wc[0].wp, p) + ybl[e * 256 + threadIdx.x] - Bm, p, pinv);
     }
     {
         double tw1[15];
@@ -378,10 +378,12 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 }
 
 // grid: x = column tile (N/4096), y = item * beta + digit, z = chunk of targets_per_wg target limbs
-// Four sources in the exact form need more than 256 registers a lane: that instantiation runs one wave per SIMD
-// (measured 0.97 ms against 1.37 ms with spills at two; the three-source ModUp is slower at one, 3.1 against 2.5 ms).
+// Four source tiles do not fit the registers of two waves per SIMD.  MODE 3 keeps y_B, which enters every target as a plain
+// addend, in the second exchange buffer and pays a second barrier per target (0.80 ms; all four in registers at one wave
+// per SIMD: 1.0 ms).  MODE 2 multiplies all four sources per target: it runs one wave per SIMD with all of them in
+// registers (0.97 ms; one of them in LDS at two waves: 1.21 ms; with spills at two: 1.4 ms).
 template <int Q, int NSRC, int MODE, bool INVSRC>
-__global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE >= 2) ? 1 : 2) void modup_cols_kernel(ModupColsArgs A) {
+__global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void modup_cols_kernel(ModupColsArgs A) {
     // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
     // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
     __shared__ double lds[2][16 * V2_GS];
@@ -483,7 +485,9 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE >= 2) ? 1 : 2) void 
             for (int a = 1; a < NSRC; a++) v += mulmod_w(yd[a][e], Wl[a].w, Wl[a].wp, pl);
             v = reduce_balanced(v, pl, plinv);
             const double sl = yd[0][e] - mulmod_w(v, Pinv.w, Pinv.wp, pl);  // (-0.75p, 1.75p)
-            yd[0][e] = canon(sl + A.hb2, pl, plinv);
+            // y_B lives in the second exchange buffer from here on (this mode uses one buffer and two barriers per target):
+            // four source tiles do not fit the registers of two waves per SIMD
+            lds[1][e * 256 + threadIdx.x] = canon(sl + A.hb2, pl, plinv);
         }
     }
     const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
@@ -520,10 +524,13 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE >= 2) ? 1 : 2) void 
             }
             dst = A.dst + ((size_t)blockIdx.y * A.nc + t) * N;
         }
+        constexpr bool ONE_BUF = MODE == 3;  // the second buffer holds y_B
+        double *xbuf = ONE_BUF ? lds[0] : lds[(k - k0) & 1];
         if (is_p51(A.p51, t))
-            modup_cols_target<true, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
+            modup_cols_target<true, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, xbuf, dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm, lds[1]);
         else
-            modup_cols_target<false, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, lds[(k - k0) & 1], dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm);
+            modup_cols_target<false, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, xbuf, dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm, lds[1]);
+        if (ONE_BUF) __syncthreads();  // single exchange buffer: everybody has read it before the next target writes
     }
 }
 
