@@ -107,7 +107,7 @@ MEASURED_TRAFFIC = {
     "rows_final2_kernel": (2.0 * 3066124 + 1507328) * 1024,
     "tensor_rows_kernel": (2.0 * 1963578 + 3145728) * 1024,
     "rows_final_kernel": (2.0 * 1556772 + 1507328) * 1024,
-    "modup_cols_kernel<4, 4, 3, true>": (2.0 * 133455 + 1507328) * 1024,
+    "modup_cols_kernel<4, 4, 3, true>": (2.0 * 171453 + 1537870) * 1024,
 }
 
 
