@@ -341,7 +341,10 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
         double v = -hsub;
         if (VARIANT == 1) v = -reduce_balanced(hsub + (double)(unsigned)((vpack >> (3 * e)) & 7u) * Bm, p, pinv);  // v <= 3: below 4p, exact
 #pragma unroll
-        for (int a = (VARIANT == 2 ? 1 : 0); a < NSRC; a++) v += mulmod_w(yd[a][e], Wc[a].w, Wc[a].wp, p);
+        for (int a = (VARIANT == 2 ? 1 : 0); a < NSRC; a++) {
+            const double ya = (VARIANT == 0 && NSRC == 3 && a == 0 && ybl) ? ybl[e * 256 + threadIdx.x] : yd[a][e];
+            v += mulmod_w(ya, Wc[a].w, Wc[a].wp, p);
+        }
         x[e] = reduce_balanced(v, p, pinv);  // |v| <= p + NSRC * 0.75p
         if (VARIANT == 2)  // 0.75p + (y_B < 2^51) + p: below 2^53
             x[e] = reduce_balanced(mulmod_w(x[e], Wc[0].w, Wc[0].wp, p) + ybl[e * 256 + threadIdx.x] - Bm, p, pinv);
@@ -490,6 +493,13 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void 
             lds[1][e * 256 + threadIdx.x] = canon(sl + A.hb2, pl, plinv);
         }
     }
+    // three source tiles: the first one lives in the second exchange buffer (one buffer, two barriers per target): without
+    // it the kernel spills at two waves per SIMD (ModUp at the benchmark shape: 2.35 against 2.58 ms)
+    constexpr bool SRC0_LDS = (MODE <= 1 && NSRC == 3 && INVSRC);
+    if (SRC0_LDS) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) lds[1][e * 256 + threadIdx.x] = yd[0][e];
+    }
     const size_t crow = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
     // MODE 0: extended-basis index of target k (the digit's own limbs are skipped) and its modulus index;
     // MODE 1: target k is kept limb k
@@ -524,12 +534,12 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void 
             }
             dst = A.dst + ((size_t)blockIdx.y * A.nc + t) * N;
         }
-        constexpr bool ONE_BUF = MODE == 3;  // the second buffer holds y_B
+        constexpr bool ONE_BUF = MODE == 3 || SRC0_LDS;  // the second buffer holds y_B / the first source tile
         double *xbuf = ONE_BUF ? lds[0] : lds[(k - k0) & 1];
         if (is_p51(A.p51, t))
-            modup_cols_target<true, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, xbuf, dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm, lds[1]);
+            modup_cols_target<true, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, xbuf, dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm, (MODE == 3 || SRC0_LDS) ? lds[1] : nullptr);
         else
-            modup_cols_target<false, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, xbuf, dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm, lds[1]);
+            modup_cols_target<false, NSRC, Q, (MODE >= 2 ? MODE - 1 : 0)>(yd, Wc, tcur, xbuf, dst, geo, p, pinv, tnext, tw_store, hsub, vpack, Bm, (MODE == 3 || SRC0_LDS) ? lds[1] : nullptr);
         if (ONE_BUF) __syncthreads();  // single exchange buffer: everybody has read it before the next target writes
     }
 }
