@@ -102,7 +102,7 @@ def laneops_per_unit(name, N, level, k, alpha):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
-    "modup_cols_kernel<4, 3, 0, true>": (2.0 * 618083 + 6397952) * 1024,
+    "modup_cols_kernel<4, 3, 0, true>": (2.0 * 409785 + 6291456) * 1024,
     "rows_inner_kernel": (2.0 * 4582582 + 1824768) * 1024,
     "rows_final2_kernel": (2.0 * 3066124 + 1507328) * 1024,
     "tensor_rows_kernel": (2.0 * 1963578 + 3145728) * 1024,
