@@ -264,8 +264,9 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
                        size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st, int limb0 = 0,
                        int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr, const WMul *xmul = nullptr,
-                       const ScalarTab *stab = nullptr) {
+                       const ScalarTab *stab = nullptr, bool zsub = false) {
     RowsFinalArgs A;
+    A.zsub = zsub ? 1 : 0;
     A.pre = pre;
     A.xmul = xmul;
     const int nz = limb_count < 0 ? nc : limb_count;
@@ -326,7 +327,7 @@ void launch_modup(ckksmi_ctx *c, const u64 *dcoef, const u64 *d_eval, size_t d_s
 // b_scratch == b_limbs), kept limbs at x + r*x_stride; out[r][i] = (x_i - NTT(r_i - h)) * Bbar^-1 (+ addend).
 void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, const int *bidx, const u64 *b_limbs, size_t b_stride,
                    u64 *b_scratch, size_t bs_stride, const u64 *x, size_t x_stride, u64 *tmp, int nc, int rows, const u64 *addend,
-                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, hipStream_t st) {
+                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, hipStream_t st, bool zsub = false) {
     const size_t N = c->N;
     const bool fconv = (c->fuse & FUSE_DIVCONV) != 0, ffinal = (c->fuse & FUSE_FINAL) != 0;
     int idx[CKKSMI_MAX_MODULI];
@@ -343,7 +344,8 @@ void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, con
         launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 1);
     }
     if (ffinal) {
-        launch_rows_final(c, tmp, x, x_stride, addend, add_item_stride, add_comp_stride, add_both, out, D.Binv, nc, rows, st);
+        launch_rows_final(c, tmp, x, x_stride, addend, add_item_stride, add_comp_stride, add_both, out, D.Binv, nc, rows, st, 0, -1, 0, nullptr, nullptr,
+                          nullptr, zsub);
     } else {
         launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 2);
         DivFinalArgs DF;
@@ -486,6 +488,8 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         RI.kt = tiles < 8 ? tiles : 8;
         RI.p51 = c->p51mask;
         RI.fold_tail = (tail_scratch && c->fuse_tail >= 3 && c->modup_loop && c->fuse_inv && c->d_fin_tail && add_both) ? 1 : 0;
+        // a plain ModDown with an addend (relinearisation, rotation) reads z the same way in its last pass
+        if (!tail_scratch && !merged && !hoist && addend && c->fuse_tail >= 3 && (c->fuse & FUSE_FINAL)) RI.fold_tail = add_both ? 1 : 2;
         RI.Pinv = c->divround[0].Binv;
         RI.addend = (const u64d *)addend; RI.add_item_stride = add_item_stride; RI.add_comp_stride = add_comp_stride;
         tail_folded = RI.fold_tail != 0;
@@ -553,8 +557,12 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         launch_rows_final2(c, tmp, tmpB, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, out, DA.Binv, DB.Binv, level, rows, st);
         return;
     }
-    divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
-                  acc, (size_t)E * N, tmp, level, items * 2, addend, add_item_stride, add_comp_stride, add_both, out, st);
+    if (tail_folded)  // the ciphertext limbs already hold x * P^-1 + addend
+        divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
+                      acc, (size_t)E * N, tmp, level, items * 2, nullptr, 0, 0, 0, out, st, true);
+    else
+        divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
+                      acc, (size_t)E * N, tmp, level, items * 2, addend, add_item_stride, add_comp_stride, add_both, out, st);
 }
 
 void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u64 *ws, hipStream_t st) {

@@ -601,8 +601,9 @@ struct RowsInnerArgs {
     int logN, level, E, n_q, alpha, beta, T;
     unsigned kt;         // min(N/4096, 8): see the grid mapping in rows_inner_body
     P51Mask p51;
-    // fold_tail: the product's ModDown + rescale follows as one conversion and one last pass; the ciphertext limbs then
-    // leave this kernel as z = acc * P^-1 + d (d = the product's component of the same row), which is what both of them read
+    // fold_tail: the ciphertext limbs leave this kernel as z = acc * P^-1 + d (d = the addend of the same row: the product's
+    // component, or sigma(c0) for the first row of a rotation), which is what the ModDown (and rescale) that follows reads.
+    // 1: both components have an addend, 2: the first one only
     int fold_tail;
     const WMul *Pinv;    // [T] P^-1 mod q_i
     const u64d *addend;  // item i, component c, limb l at addend + i*add_item_stride + c*add_comp_stride + l*N
@@ -743,7 +744,9 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     if (A.fold_tail && (int)x < A.level) {
         const WMul Pi = A.Pinv[t];
         const u64d *d0 = A.addend + (size_t)item * A.add_item_stride + (size_t)x * N + tile0;
-        const u64d *d1 = d0 + A.add_comp_stride;
+        const bool both = A.fold_tail == 1;  // 2: only the first component has an addend (rotation)
+        const u64d *d1 = both ? d0 + A.add_comp_stride : d0;
+        const double has1 = both ? 1.0 : 0.0;
         ulonglong2 dw0[8], dw1[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
@@ -754,7 +757,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         for (int s = 0; s < 8; s++) {
             // accumulators are below 2^53: the prepared product is exact for them as they are
             const double z00 = mulmod_w(a0[2 * s], Pi.w, Pi.wp, p) + u2d(dw0[s].x), z01 = mulmod_w(a0[2 * s + 1], Pi.w, Pi.wp, p) + u2d(dw0[s].y);
-            const double z10 = mulmod_w(a1[2 * s], Pi.w, Pi.wp, p) + u2d(dw1[s].x), z11 = mulmod_w(a1[2 * s + 1], Pi.w, Pi.wp, p) + u2d(dw1[s].y);
+            const double z10 = mulmod_w(a1[2 * s], Pi.w, Pi.wp, p) + has1 * u2d(dw1[s].x), z11 = mulmod_w(a1[2 * s + 1], Pi.w, Pi.wp, p) + has1 * u2d(dw1[s].y);
             ((ulonglong2 *)o0)[256 * s + tid] = make_ulonglong2(d2u(canon(z00, p, pinv)), d2u(canon(z01, p, pinv)));
             ((ulonglong2 *)o1)[256 * s + tid] = make_ulonglong2(d2u(canon(z10, p, pinv)), d2u(canon(z11, p, pinv)));
         }
@@ -796,6 +799,7 @@ struct RowsFinalArgs {
     const WMul *Binv;    // [T]
     const WMul *pre;     // optional [T]: the addend enters BEFORE the division, out = (x + pre_i*addend - r) * Binv
     const WMul *xmul;    // optional [T] (without pre): out = (x*xmul_i + addend - r) * Binv
+    int zsub;            // 1: x already holds x*Binv + addend: out = x - r * Binv
     int logN, nc;
     int limb0;             // first limb handled (grid z counts from it)
     int rows, rows_per_x;  // a workgroup loops over rows_per_x rows (same limb, same tile: twiddles reused)
@@ -847,8 +851,14 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
                 x0 = mulmod_w(x0, Pm.w, Pm.wp, p) + before * u2d(ar[s].x);
                 x1 = mulmod_w(x1, Pm.w, Pm.wp, p) + before * u2d(ar[s].y);
             }
-            double v0 = mulmod_w(x0 - rr[0], W.w, W.wp, p);
-            double v1 = mulmod_w(x1 - rr[1], W.w, W.wp, p);
+            double v0, v1;
+            if (A.zsub) {
+                v0 = x0 - mulmod_w(rr[0], W.w, W.wp, p);
+                v1 = x1 - mulmod_w(rr[1], W.w, W.wp, p);
+            } else {
+                v0 = mulmod_w(x0 - rr[0], W.w, W.wp, p);
+                v1 = mulmod_w(x1 - rr[1], W.w, W.wp, p);
+            }
             if (add && !pre && (!xm || xm_val)) {
                 v0 += u2d(ar[s].x);
                 v1 += u2d(ar[s].y);
