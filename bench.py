@@ -50,12 +50,12 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "conv_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),   # ModUp
         # the same conversions organised by source tile (targets looped in the workgroup)
         # (", true": the inverse column pass of the sources runs in the kernel too; same bytes)
-        "modup_cols_kernel<4, %d, 0, true>" % alpha: w * (1 + float(level) / (beta * E - level)),
-        "modup_cols_kernel<4, %d, 1, true>" % k: w * (1 + float(k) / level),
-        "modup_cols_kernel<4, 1, 1, true>": w * (1 + 1.0 / (level - 1)),
+        "modup_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),
+        "modup_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),
+        "modup_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),
         # ModDown + rescale as one conversion / the merged division: k + 1 source limbs for level - 1 targets
-        "modup_cols_kernel<4, %d, 3, true>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
-        "modup_cols_kernel<4, %d, 2, true>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
+        "modup_cols_kernel<4, %d, 3>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
+        "modup_cols_kernel<4, %d, 2>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
         "axpy_limb_kernel": 3 * w,
         "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
         "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
@@ -80,11 +80,11 @@ def laneops_per_unit(name, N, level, k, alpha):
         "conv_cols_kernel<4, %d, 0>" % alpha: N * (7 * alpha + (alpha - 1) + 3 + xform_pass),
         # source words converted to doubles once per workgroup, not once per target
         # (the inverse column pass of the source tiles, once per workgroup, adds about 5 %: not counted)
-        "modup_cols_kernel<4, %d, 0, true>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
-        "modup_cols_kernel<4, %d, 1, true>" % k: N * (5 * k + k + 3 + xform_pass),
-        "modup_cols_kernel<4, 1, 1, true>": N * (5 + 1 + 3 + xform_pass),
-        "modup_cols_kernel<4, %d, 3, true>" % (k + 1): N * (5 * k + k + 3 + 5 + 2 + 3 + xform_pass),
-        "modup_cols_kernel<4, %d, 2, true>" % (k + 1): N * (5 * (k + 1) + (k + 1) + 6 + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 0>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 1>" % k: N * (5 * k + k + 3 + xform_pass),
+        "modup_cols_kernel<4, 1, 1>": N * (5 + 1 + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 3>" % (k + 1): N * (5 * k + k + 3 + 5 + 2 + 3 + xform_pass),
+        "modup_cols_kernel<4, %d, 2>" % (k + 1): N * (5 * (k + 1) + (k + 1) + 6 + 3 + xform_pass),
         "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
         "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         # per word: a row pass for every digit except the limb's own one (level of the E limbs have one), two
@@ -102,12 +102,12 @@ def laneops_per_unit(name, N, level, k, alpha):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
 # 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
 MEASURED_TRAFFIC = {
-    "modup_cols_kernel<4, 3, 0, true>": (2.0 * 409785 + 6291456) * 1024,
+    "modup_cols_kernel<4, 3, 0>": (2.0 * 409785 + 6291456) * 1024,
     "rows_inner_kernel": (2.0 * 4582582 + 1824768) * 1024,
     "rows_final2_kernel": (2.0 * 3066124 + 1507328) * 1024,
     "tensor_rows_kernel": (2.0 * 1963578 + 3145728) * 1024,
     "rows_final_kernel": (2.0 * 1556772 + 1507328) * 1024,
-    "modup_cols_kernel<4, 4, 3, true>": (2.0 * 171453 + 1537870) * 1024,
+    "modup_cols_kernel<4, 4, 3>": (2.0 * 171453 + 1537870) * 1024,
 }
 
 

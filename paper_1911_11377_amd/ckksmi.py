@@ -88,6 +88,7 @@ SIGNATURES = {
     "ckksmi_profile_enable": [VP, C.c_int],
     "ckksmi_profile_read": [VP, C.c_int, f64p, C.POINTER(C.c_longlong), f64p],
     "ckksmi_kernel_class_name": [VP, C.c_int],
+    "ckksmi_tune": [VP, C.c_int, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
 K_COUNT = 29
@@ -381,6 +382,10 @@ class Context:
         self._call("ckksmi_fc_mac", self._h, _ptr(x), _ptr(w), F, O, _ptr(out), level, _ptr(ws), _nbytes(ws), self._stream(stream))
 
     # ------------------------------------------------------------ measurement
+    def tune_target_wgs(self, value):
+        """workgroups a transform launch aims for before its workgroups loop over items (ckksmi_tune)"""
+        self._call("ckksmi_tune", self._h, 0, int(value))
+
     def profile_enable(self, on=True):
         self._call("ckksmi_profile_enable", self._h, 1 if on else 0)
 

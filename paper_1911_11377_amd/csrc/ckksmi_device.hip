@@ -169,50 +169,14 @@ unsigned zchunks_for(const ckksmi_ctx *c, unsigned wgs_per_item, size_t items, i
     return (unsigned)((items + items_per_z - 1) / items_per_z);
 }
 
-void launch_conv_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t dst_stride, int slots, size_t items,
-                      int level, const DivRoundDev *D, double units, hipStream_t st) {
-    ConvColsArgs A;
-    memset(&A, 0, sizeof(A));
-    A.y = (const u64d *)y; A.y_item_stride = y_stride;
-    A.dst = (u64d *)dst; A.dst_item_stride = dst_stride;
-    A.modc = c->d_mod; A.tw = c->d_tww_fwd;
-    A.logN = c->logN; A.items = (int)items;
-    A.mode = mode;
-    A.p51 = c->p51mask;
-    A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.T = c->T; A.cc = c->d_modup_c;
-    if (D) A.D = *D;
-    const unsigned tiles = (unsigned)(c->N / 4096);
-    // the column pass needs only the first N1 table entries per modulus (cache-resident), so nothing is gained by
-    // looping over items; with the item as the slowest grid index all targets of a digit run together and share
-    // their source tiles in L2
-    A.items_per_z = c->conv_items_per_wg < (int)items ? c->conv_items_per_wg : (int)items;
-    const unsigned z = (unsigned)((items + A.items_per_z - 1) / A.items_per_z);
-    const int nsrc = mode == 0 ? c->alpha : D->nb;  // one kernel instance per (size, source count, mode): registers sized for it
-    const int kid = mode == 0 ? CKKSMI_K_CONV_COLS_MODUP
-                               : mode == 2 ? CKKSMI_K_CONV_COLS_MERGED
-                               : mode == 3 ? CKKSMI_K_CONV_COLS_TAIL : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
-    const dim3 grid(tiles, slots, z), block(V2_THREADS);
-#define CONV_COLS_CASE(Q, NS)                                                                                \
-    case (Q) * 8 + (NS):                                                                                     \
-        if (mode == 0) KL(c, kid, units, (conv_cols_kernel<Q, NS, 0>), grid, block, st, A);                  \
-        else KL(c, kid, units, (conv_cols_kernel<Q, NS, 1>), grid, block, st, A);                            \
-        break;
-    switch ((c->logN - 12) * 8 + nsrc) {
-        CONV_COLS_CASE(1, 1) CONV_COLS_CASE(1, 2) CONV_COLS_CASE(1, 3) CONV_COLS_CASE(1, 4)
-        CONV_COLS_CASE(2, 1) CONV_COLS_CASE(2, 2) CONV_COLS_CASE(2, 3) CONV_COLS_CASE(2, 4)
-        CONV_COLS_CASE(3, 1) CONV_COLS_CASE(3, 2) CONV_COLS_CASE(3, 3) CONV_COLS_CASE(3, 4)
-        CONV_COLS_CASE(4, 1) CONV_COLS_CASE(4, 2) CONV_COLS_CASE(4, 3) CONV_COLS_CASE(4, 4)
-        default: break;
-    }
-#undef CONV_COLS_CASE
-}
-
 // Conversion + column pass with the targets looped inside the workgroup (see modup_cols_kernel).
 // mode 0: ModUp of `items` polynomials (y: [items][level][N], dst: [items][beta][E][N]);
 // mode 1: DivRound conversion of `items` rows (y: row r at y + r*y_stride, dst: [rows][nc][N])
-// fin != nullptr: y is the output of the inverse row pass and the kernel runs the inverse column pass itself
+// mode 2: mode 1 in the exact form of DivRound; mode 3: ModDown followed by rescale as one conversion (D2 = the rescale).
+// y is the output of the inverse row pass; the kernel runs the inverse column pass itself with the last-stage constants fin
+// (fin_val: one set of constants passed by value for the single source of a rescale)
 void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u64 *dst, size_t items, int level, int nc,
-                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin = nullptr, const DivRoundDev *D2 = nullptr,
+                       const DivRoundDev *D, double units, hipStream_t st, const FinConst *fin, const DivRoundDev *D2 = nullptr,
                        const FinConst *fin_val = nullptr) {
     ModupColsArgs A;
     memset(&A, 0, sizeof(A));
@@ -225,7 +189,7 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     A.tw_inv = c->d_tww_inv; A.fin = fin;
     if (D) A.D = *D;
     const unsigned tiles = (unsigned)(c->N / 4096);
-    const int n_targets = mode == 0 ? A.E : nc;  // mode 2: mode 1 in the exact form of DivRound; mode 3: ModDown + rescale (both need fin)
+    const int n_targets = mode == 0 ? A.E : nc;
     const size_t ygrid = mode == 0 ? items * A.beta : items;
     // enough workgroups to fill the chip (8 per CU), otherwise as many targets per workgroup as possible: the source
     // tiles are read and converted once per workgroup (measured: 24 targets 0.65 ms, 6 targets 0.75 ms for ModDown)
@@ -233,7 +197,7 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
     int chunks = (int)((size_t)2048 / (base ? base : 1));
     if (chunks < 1) chunks = 1;
     if (chunks > n_targets) chunks = n_targets;
-    A.targets_per_wg = c->modup_targets_per_wg > 0 ? c->modup_targets_per_wg : (n_targets + chunks - 1) / chunks;
+    A.targets_per_wg = (n_targets + chunks - 1) / chunks;
     const unsigned z = (unsigned)((n_targets + A.targets_per_wg - 1) / A.targets_per_wg);
     const dim3 grid(tiles, (unsigned)ygrid, z), block(V2_THREADS);
     const int nsrc = mode == 0 ? c->alpha : D->nb;
@@ -242,12 +206,10 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
                                : mode == 3 ? CKKSMI_K_CONV_COLS_TAIL : (nsrc == 1 ? CKKSMI_K_CONV_COLS_RESCALE : CKKSMI_K_CONV_COLS_DIV);
 #define MODUP_COLS_CASE(Q, NS)                                                                               \
     case (Q) * 8 + (NS):                                                                                     \
-        if (mode == 0 && fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, true>), grid, block, st, A);    \
-        else if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0, false>), grid, block, st, A);     \
-        else if (mode == 2) KL(c, kid, units, (modup_cols_kernel<Q, NS, 2, true>), grid, block, st, A);      \
-        else if (mode == 3) KL(c, kid, units, (modup_cols_kernel<Q, NS, 3, true>), grid, block, st, A);      \
-        else if (fin) KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, true>), grid, block, st, A);            \
-        else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1, false>), grid, block, st, A);                    \
+        if (mode == 0) KL(c, kid, units, (modup_cols_kernel<Q, NS, 0>), grid, block, st, A);                 \
+        else if (mode == 2) KL(c, kid, units, (modup_cols_kernel<Q, NS, 2>), grid, block, st, A);            \
+        else if (mode == 3) KL(c, kid, units, (modup_cols_kernel<Q, NS, 3>), grid, block, st, A);            \
+        else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1>), grid, block, st, A);                           \
         break;
     switch ((c->logN - 12) * 8 + nsrc) {
         MODUP_COLS_CASE(1, 1) MODUP_COLS_CASE(1, 2) MODUP_COLS_CASE(1, 3) MODUP_COLS_CASE(1, 4)
@@ -286,74 +248,17 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
         KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A);
 }
 
-// DivRound conversion of `rows` rows + column pass of the nc results: tmp [rows][nc][N]
-// fin != nullptr: b_scratch holds the output of the inverse row pass only (see launch_modup_cols)
-void launch_div_cols(ckksmi_ctx *c, const u64 *b_scratch, size_t bs_stride, u64 *tmp, int nc, int rows, const DivRoundDev &D, hipStream_t st,
-                     const FinConst *fin = nullptr, const FinConst *fin_val = nullptr) {
-    if (c->modup_loop)
-        launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin, nullptr, fin_val);
-    else
-        launch_conv_cols(c, 1, b_scratch, bs_stride, tmp, (size_t)nc * c->N, nc, rows, 0, &D, (double)rows * nc, st);
-}
-
-void launch_rows_final2(ckksmi_ctx *c, const u64 *tmpA, const u64 *tmpB, const u64 *x, size_t x_row_stride, const u64 *addend,
-                        size_t add_item_stride, size_t add_comp_stride, u64 *out, const WMul *BinvA, const WMul *BinvB, int ncA, int rows,
-                        hipStream_t st) {
-    RowsFinal2Args A;
-    A.tmpA = (const u64d *)tmpA; A.tmpB = (const u64d *)tmpB; A.x = (const u64d *)x; A.x_row_stride = x_row_stride;
-    A.addend = (const u64d *)addend; A.add_item_stride = add_item_stride; A.add_comp_stride = add_comp_stride;
-    A.out = (u64d *)out; A.modc = c->d_mod; A.tw = c->d_tww_fwd; A.BinvA = BinvA; A.BinvB = BinvB;
-    A.logN = c->logN; A.ncA = ncA; A.ncB = ncA - 1; A.rows = rows;
-    A.p51 = c->p51mask;
-    const unsigned tiles = (unsigned)(c->N / 4096);
-    const unsigned xch = zchunks_for(c, tiles * A.ncB, rows, A.rows_per_x);
-    KL(c, CKKSMI_K_ROWS_FINAL2, (double)rows * A.ncB, rows_final2_kernel, dim3(xch, tiles, A.ncB), dim3(V2_THREADS), st, A);
-}
-
-// fusion switches (ckksmi_ctx::fuse): which limb-wise steps ride on a transform pass
-enum { FUSE_MODUP = 1, FUSE_INNER = 2, FUSE_DIVCONV = 4, FUSE_FINAL = 8 };
-
-void launch_modup(ckksmi_ctx *c, const u64 *dcoef, const u64 *d_eval, size_t d_stride, u64 *dt, int items, int level, hipStream_t st) {
-    const size_t N = c->N;
-    const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
-    ModUpArgs MU;
-    MU.d_coef = (const u64d *)dcoef; MU.d_eval = (const u64d *)d_eval; MU.d_eval_item_stride = d_stride; MU.out = (u64d *)dt;
-    MU.modc = c->d_mod; MU.inv = c->d_modup_inv; MU.cc = c->d_modup_c;
-    MU.logN = c->logN; MU.level = level; MU.E = E; MU.n_q = c->n_q; MU.alpha = c->alpha; MU.beta = beta; MU.T = c->T;
-    KL(c, CKKSMI_K_MODUP, (double)items * beta * E, modup_kernel, dim3(ew_blocks(N), beta, items), dim3(EW_THREADS), st, MU);
-}
-
-// DivRound of `rows` rows: dropped limbs (evaluation form) at b_limbs + r*b_stride (nb limbs, in place scratch allowed when
-// b_scratch == b_limbs), kept limbs at x + r*x_stride; out[r][i] = (x_i - NTT(r_i - h)) * Bbar^-1 (+ addend).
+// DivRound of `rows` rows on the register-tiled kernels: dropped limbs (evaluation form) at b_limbs + r*b_stride (nb limbs;
+// b_scratch == b_limbs works in place), kept limbs at x + r*x_stride; out[r][i] = (x_i - NTT(r_i - h)) * Bbar^-1 (+ addend).
+// zsub: the kept limbs already hold x * Bbar^-1 + addend, out = x - NTT(r - h) * Bbar^-1.
 void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, const int *bidx, const u64 *b_limbs, size_t b_stride,
                    u64 *b_scratch, size_t bs_stride, const u64 *x, size_t x_stride, u64 *tmp, int nc, int rows, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, hipStream_t st, bool zsub = false) {
-    const size_t N = c->N;
-    const bool fconv = (c->fuse & FUSE_DIVCONV) != 0, ffinal = (c->fuse & FUSE_FINAL) != 0;
-    int idx[CKKSMI_MAX_MODULI];
-    for (int i = 0; i < nc; i++) idx[i] = i;
-    const bool finv = fconv && c->modup_loop && c->fuse_inv;  // the conversion kernel runs the inverse column pass itself
-    launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fconv ? fin : nullptr, finv ? 2 : 3);
-    if (fconv) {
-        launch_div_cols(c, b_scratch, bs_stride, tmp, nc, rows, D, st, finv ? fin : nullptr);
-    } else {
-        DivConvArgs DC;
-        DC.b_limbs = (const u64d *)b_scratch; DC.b_row_stride = bs_stride; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
-        DC.logN = c->logN; DC.nc = nc; DC.T = c->T; DC.exact = 0;
-        KL(c, CKKSMI_K_DIVCONV, (double)rows * nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
-        launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 1);
-    }
-    if (ffinal) {
-        launch_rows_final(c, tmp, x, x_stride, addend, add_item_stride, add_comp_stride, add_both, out, D.Binv, nc, rows, st, 0, -1, 0, nullptr, nullptr,
-                          nullptr, zsub);
-    } else {
-        launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 2);
-        DivFinalArgs DF;
-        DF.x = (const u64d *)x; DF.x_row_stride = x_stride; DF.tmp = (const u64d *)tmp;
-        DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride; DF.add_both = add_both;
-        DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.pre = nullptr; DF.logN = c->logN; DF.nc = nc;
-        KL(c, CKKSMI_K_DIVFINAL, (double)rows * nc, divround_final_kernel, dim3(ew_blocks(N), nc, rows), dim3(EW_THREADS), st, DF);
-    }
+    // inverse row pass of the dropped limbs; the conversion kernel runs their inverse column pass itself
+    launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fin, 2);
+    launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
+    launch_rows_final(c, tmp, x, x_stride, addend, add_item_stride, add_comp_stride, add_both, out, D.Binv, nc, rows, st, 0, -1, 0, nullptr, nullptr,
+                      nullptr, zsub);
 }
 
 // Rotations with a shared ModUp: R rotations of every item of a key-switch sweep (see inner_product_hoisted_kernel)
@@ -364,6 +269,9 @@ struct HoistPlan {
     const u64 *sig;  // sigma_r(c0) of every item: [items][R][level][N], the addend of the first component
 };
 
+// the gather through LDS needs runs of 256 words and at most INNER_MAX_BETA digits; otherwise the plain gather kernel
+inline bool hoisted_tile_ok(const ckksmi_ctx *c, int beta) { return c->logN >= 8 && beta <= INNER_MAX_BETA && EW_THREADS == 256; }
+
 void launch_hoisted_inner(ckksmi_ctx *c, const HoistPlan &H, const u64 *dt, const u64 *d_eval, size_t d_stride, u64 *acc, int items, int level,
                           hipStream_t st) {
     HoistArgs A;
@@ -372,7 +280,7 @@ void launch_hoisted_inner(ckksmi_ctx *c, const HoistPlan &H, const u64 *dt, cons
     A.logN = c->logN; A.level = level; A.E = level + c->k; A.n_q = c->n_q; A.alpha = c->alpha; A.beta = (level + c->alpha - 1) / c->alpha;
     A.T = c->T; A.items = items; A.R = H.R;
     for (int r = 0; r < H.R; r++) { A.g[r] = H.g[r]; A.ginv[r] = H.ginv[r]; A.key[r] = (const u64d *)H.key[r]; }
-    if (c->logN >= 8 && A.beta <= INNER_MAX_BETA && EW_THREADS == 256 && !getenv("CKKSMI_HOIST_GATHER")) {
+    if (hoisted_tile_ok(c, A.beta)) {
         // source rows staged in LDS once for all rotations
         A.items_per_wg = std::max(1, std::min(items, HOIST_LDS_WORDS / 256 / A.beta));
         A.item_chunks = (items + A.items_per_wg - 1) / A.items_per_wg;
@@ -404,165 +312,106 @@ void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item
     KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
        (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)(level - 1) * N), (unsigned long long)add_item_stride,
        (unsigned long long)add_comp_stride, c->h_modc[level - 1], make_wmul(1, c->mod[level - 1]), c->h_pmod[level - 1], c->logN);
-    const bool fast = c->fused && (c->fuse & FUSE_DIVCONV) && c->modup_loop && c->fuse_inv;
-    const bool ffinal = c->fused && (c->fuse & FUSE_FINAL);
-    int idx[CKKSMI_MAX_MODULI];
-    for (int i = 0; i < nc; i++) idx[i] = i;
-    if (fast) {
+    if (c->fused) {
         const FinConst *fin = c->d_fin_merged + (size_t)level * CKKSMI_MAX_SPECIAL;
         launch_ntt(c, false, bl, bl, table_map(D.b_idx, D.nb, (size_t)E * N, (size_t)E * N), rows, st, fin, 2);
         launch_modup_cols(c, 2, bl, (size_t)E * N, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
-    } else {
-        launch_ntt(c, false, bl, bl, table_map(D.b_idx, D.nb, (size_t)E * N, (size_t)E * N), rows, st);
-        DivConvArgs DC;
-        DC.b_limbs = (const u64d *)bl; DC.b_row_stride = (size_t)E * N; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
-        DC.logN = c->logN; DC.nc = nc; DC.T = c->T; DC.exact = 1;
-        KL(c, CKKSMI_K_DIVCONV, (double)rows * nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
-        launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, ffinal ? 1 : 3);
-    }
-    if (ffinal) {
         launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, D.Binv, nc, rows, st, 0, -1, 0, c->d_pmod);
-    } else {
-        if (fast) launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st, nullptr, 2);
-        DivFinalArgs DF;
-        DF.x = (const u64d *)acc; DF.x_row_stride = (size_t)E * N; DF.tmp = (const u64d *)tmp;
-        DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride; DF.add_both = 1;
-        DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.pre = c->d_pmod; DF.logN = c->logN; DF.nc = nc;
-        KL(c, CKKSMI_K_DIVFINAL, (double)rows * nc, divround_final_kernel, dim3(ew_blocks(N), nc, rows), dim3(EW_THREADS), st, DF);
+        return;
     }
+    int idx[CKKSMI_MAX_MODULI];
+    for (int i = 0; i < nc; i++) idx[i] = i;
+    launch_ntt(c, false, bl, bl, table_map(D.b_idx, D.nb, (size_t)E * N, (size_t)E * N), rows, st);
+    DivConvArgs DC;
+    DC.b_limbs = (const u64d *)bl; DC.b_row_stride = (size_t)E * N; DC.tmp = (u64d *)tmp; DC.modc = c->d_mod; DC.D = D;
+    DC.logN = c->logN; DC.nc = nc; DC.T = c->T; DC.exact = 1;
+    KL(c, CKKSMI_K_DIVCONV, (double)rows * nc, divround_conv_kernel, dim3(ew_blocks(N), rows), dim3(EW_THREADS), st, DC);
+    launch_ntt(c, true, tmp, tmp, table_map(idx, nc, (size_t)nc * N, (size_t)nc * N), rows, st);
+    DivFinalArgs DF;
+    DF.x = (const u64d *)acc; DF.x_row_stride = (size_t)E * N; DF.tmp = (const u64d *)tmp;
+    DF.addend = (const u64d *)addend; DF.add_item_stride = add_item_stride; DF.add_comp_stride = add_comp_stride; DF.add_both = 1;
+    DF.out = (u64d *)out; DF.modc = c->d_mod; DF.Binv = D.Binv; DF.pre = c->d_pmod; DF.logN = c->logN; DF.nc = nc;
+    KL(c, CKKSMI_K_DIVFINAL, (double)rows * nc, divround_final_kernel, dim3(ew_blocks(N), nc, rows), dim3(EW_THREADS), st, DF);
 }
 
-// tail_scratch != nullptr: the key switch is followed by a rescale of (result + addend) and `out` receives the rescaled
-// ciphertexts [items][2][level-1][N]; tail_scratch holds 2*level*N words per item.  Needs both DivRound fusions.
+// Can ModDown + add + rescale of a product run as one conversion and one last pass (modup_cols_kernel MODE 3)?  The dropped
+// limb joins the special limbs as a conversion source, so one more than k sources must fit.
+inline bool one_conversion_tail_ok(const ckksmi_ctx *c) { return c->fused && c->d_fin_tail != nullptr; }
+
+// Key switch on the register-tiled kernels (2^13 <= N <= 2^16).
+// tail: the key switch is followed by a rescale of (result + addend), both components have an addend, and `out` receives
+// the rescaled ciphertexts [items][2][level-1][N] (needs one_conversion_tail_ok).
+// ymid_ready: the tensor kernel already left the inverse row pass of d_eval at the start of the workspace.
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
-                   u64 *tail_scratch = nullptr, bool ymid_ready = false, bool merged = false, const HoistPlan *hoist = nullptr) {
+                   bool tail = false, bool ymid_ready = false, bool merged = false, const HoistPlan *hoist = nullptr) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     const int R = hoist ? hoist->R : 1;  // hoisted rotations: R accumulator pairs per item
-    u64 *ycoef = ws;
-    u64 *dtA = ycoef + (size_t)items * level * N;
+    u64 *ymid = ws;
+    u64 *dtA = ymid + (size_t)items * level * N;
     u64 *acc = dtA + (size_t)items * beta * E * N;
     u64 *tmp = acc + (size_t)items * R * 2 * E * N;
     int idx[CKKSMI_MAX_MODULI];
     for (int i = 0; i < level; i++) idx[i] = i;
-    LimbMap M1;
-    memset(&M1, 0, sizeof(M1));
-    M1.per_item = beta * E; M1.mode = 1; M1.level = level; M1.E = E; M1.n_q = c->n_q; M1.alpha = c->alpha;
-    M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
-    if (c->fuse & FUSE_MODUP) {
-        // y_i = d_i * qhat_i^-1 straight out of the inverse transform; conversion rides on the column pass
-        const bool finv = c->modup_loop && c->fuse_inv;
-        // ymid_ready: the tensor kernel already left the inverse row pass of d_eval at the start of the workspace
-        if (!(ymid_ready && finv))
-            launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st,
-                       c->d_fin_modup + (size_t)level * c->n_q, finv ? 2 : 3);
-        if (c->modup_loop)
-            launch_modup_cols(c, 0, ycoef, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st,
-                              finv ? c->d_fin_modup + (size_t)level * c->n_q : nullptr);
-        else
-            launch_conv_cols(c, 0, ycoef, (size_t)level * N, dtA, (size_t)beta * E * N, beta * E, items, level, nullptr,
-                             (double)items * (beta * E - level), st);
-    } else {
-        launch_ntt(c, false, d_eval, ycoef, table_map(idx, level, d_stride, (size_t)level * N), items, st);
-        launch_modup(c, ycoef, d_eval, d_stride, dtA, items, level, st);
-        launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 1);
-    }
+    // y_i = d_i * qhat_i^-1 comes straight out of the inverse transform (row pass here, column pass inside the conversion
+    // kernel); the conversion rides on the column pass of the forward transform of its results
+    const FinConst *fin_up = c->d_fin_modup + (size_t)level * c->n_q;
+    if (!ymid_ready) launch_ntt(c, false, d_eval, ymid, table_map(idx, level, d_stride, (size_t)level * N), items, st, fin_up, 2);
+    launch_modup_cols(c, 0, ymid, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st, fin_up);
+    int sidx[CKKSMI_MAX_SPECIAL];
+    for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
+    u64 *specials = acc + (size_t)level * N;
     if (hoist) {
         // the lifted digits in evaluation form once, then every rotation gathers from them
+        LimbMap M1;
+        memset(&M1, 0, sizeof(M1));
+        M1.per_item = beta * E; M1.mode = 1; M1.level = level; M1.E = E; M1.n_q = c->n_q; M1.alpha = c->alpha;
+        M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
         launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
-        launch_hoisted_inner(c, *hoist, dtA, (c->fuse & FUSE_MODUP) ? d_eval : nullptr, d_stride, acc, items, level, st);
-        int hidx[CKKSMI_MAX_SPECIAL];
-        for (int m = 0; m < c->k; m++) hidx[m] = c->n_q + m;
-        divround_rows(c, c->divround[0], c->d_fin_moddown, hidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
-                      acc, (size_t)E * N, tmp, level, items * R * 2, hoist->sig, (size_t)level * N, 0, 0, out, st);
+        launch_hoisted_inner(c, *hoist, dtA, d_eval, d_stride, acc, items, level, st);
+        divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, specials, (size_t)E * N, specials, (size_t)E * N, acc, (size_t)E * N, tmp, level,
+                      items * R * 2, hoist->sig, (size_t)level * N, 0, 0, out, st);
         return;
     }
-    bool tail_folded = false;
-    if (c->fuse & FUSE_INNER) {
-        RowsInnerArgs RI;
-        RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
-        RI.modc = c->d_mod; RI.tw = c->d_tww_fwd;
-        RI.logN = c->logN; RI.level = level; RI.E = E; RI.n_q = c->n_q; RI.alpha = c->alpha; RI.beta = beta; RI.T = c->T;
-        const unsigned tiles = (unsigned)(N / 4096);
-        RI.kt = tiles < 8 ? tiles : 8;
-        RI.p51 = c->p51mask;
-        RI.fold_tail = (tail_scratch && c->fuse_tail >= 3 && c->modup_loop && c->fuse_inv && c->d_fin_tail && add_both) ? 1 : 0;
-        // a plain ModDown with an addend (relinearisation, rotation) reads z the same way in its last pass
-        if (!tail_scratch && !merged && !hoist && addend && c->fuse_tail >= 3 && (c->fuse & FUSE_FINAL)) RI.fold_tail = add_both ? 1 : 2;
-        RI.Pinv = c->divround[0].Binv;
-        RI.addend = (const u64d *)addend; RI.add_item_stride = add_item_stride; RI.add_comp_stride = add_comp_stride;
-        tail_folded = RI.fold_tail != 0;
-        KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
-    } else {
-        launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
-        if (c->fuse & FUSE_MODUP) {
-            // the digit's own limbs were not copied by a ModUp kernel: the inner product reads them from d_eval
-        }
-        InnerArgs IA;
-        IA.dt = (const u64d *)dtA; IA.d_eval = (c->fuse & FUSE_MODUP) ? (const u64d *)d_eval : nullptr; IA.d_eval_item_stride = d_stride;
-        IA.alpha = c->alpha;
-        IA.acc = (u64d *)acc; IA.modc = c->d_mod;
-        IA.logN = c->logN; IA.level = level; IA.E = E; IA.n_q = c->n_q; IA.beta = beta; IA.T = c->T;
-        IA.items = items;
-        const unsigned zin = zchunks_for(c, ew_blocks(N) * E, items, IA.items_per_z);
-        KL(c, CKKSMI_K_INNER, (double)items * E, inner_product_kernel, dim3(ew_blocks(N), E, zin), dim3(EW_THREADS), st, IA, K);
-    }
+    RowsInnerArgs RI;
+    RI.dtA = (const u64d *)dtA; RI.d_eval = (const u64d *)d_eval; RI.d_eval_item_stride = d_stride; RI.acc = (u64d *)acc;
+    RI.modc = c->d_mod; RI.tw = c->d_tww_fwd;
+    RI.logN = c->logN; RI.level = level; RI.E = E; RI.n_q = c->n_q; RI.alpha = c->alpha; RI.beta = beta; RI.T = c->T;
+    const unsigned tiles = (unsigned)(N / 4096);
+    RI.kt = tiles < 8 ? tiles : 8;
+    RI.p51 = c->p51mask;
+    // the ciphertext limbs leave the inner product as z = x * P^-1 + addend, which is what ModDown's last pass (and the
+    // one-conversion tail) read; the merged division wants the accumulators themselves
+    RI.fold_tail = (merged || !addend) ? 0 : (add_both ? 1 : 2);
+    RI.Pinv = c->divround[0].Binv;
+    RI.addend = (const u64d *)addend; RI.add_item_stride = add_item_stride; RI.add_comp_stride = add_comp_stride;
+    KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
     if (merged) {
         merged_division(c, acc, addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
         return;
     }
-    int sidx[CKKSMI_MAX_SPECIAL];
-    for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
-    if (tail_scratch) {
-        // ModDown and rescale share their last pass.  The rescale conversion needs the ModDown result of the dropped
-        // limb only, so that limb is finished first; every other limb then goes through both final steps at once.
-        const int rows = items * 2;
-        u64 *specials = acc + (size_t)level * N;
-        u64 *r_last = tail_scratch;                       // [rows][N]
-        u64 *tmpB = tail_scratch + (size_t)rows * N;      // [rows][level-1][N]
-        u64 *last_coef = ycoef;                           // [rows][N] (the conversion inputs of ModUp are no longer needed)
-        const DivRoundDev &DA = c->divround[0], &DB = c->divround[1 + (level - 1)];
-        int lidx[1] = {level - 1};
-        const bool finv = c->modup_loop && c->fuse_inv;
-        if (c->fuse_tail >= 2 && finv && c->d_fin_tail && add_both) {
-            // ONE conversion and ONE last pass for ModDown + add + rescale (same bits; see modup_cols_kernel MODE 3):
-            // u = x_last * P^-1 + d_last replaces the dropped limb, its inverse transform rides with the special limbs'
-            const int last = level - 1;
-            u64 *bl = acc + (size_t)last * N;  // limbs last, p_0 .. p_{k-1} of every row: contiguous in the extended layout
-            if (!tail_folded)
-            KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
-               (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)last * N), (unsigned long long)add_item_stride,
-               (unsigned long long)add_comp_stride, c->h_modc[last], c->h_Pinv[last], make_wmul(1, c->mod[last]), c->logN);
-            DivRoundDev D3 = DA;
-            D3.nb = c->k + 1;
-            D3.b_idx[0] = last;
-            for (int m = 0; m < c->k; m++) D3.b_idx[1 + m] = c->n_q + m;
-            const FinConst *ft = c->d_fin_tail + (size_t)level * CKKSMI_MAX_SPECIAL;
-            launch_ntt(c, false, bl, bl, table_map(D3.b_idx, D3.nb, (size_t)E * N, (size_t)E * N), rows, st, ft, 2);
-            launch_modup_cols(c, 3, bl, (size_t)E * N, tmp, rows, 0, last, &D3, (double)rows * last, st, ft, &DB);
-            if (tail_folded)  // the kept limbs already hold x * P^-1 + d
-                launch_rows_final(c, tmp, acc, (size_t)E * N, nullptr, 0, 0, 0, out, DB.Binv, last, rows, st);
-            else
-                launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, DB.Binv, last, rows, st, 0, -1, 0,
-                                  nullptr, DA.Binv);
-            return;
-        }
-        launch_ntt(c, false, specials, specials, table_map(sidx, c->k, (size_t)E * N, (size_t)E * N), rows, st, c->d_fin_moddown, finv ? 2 : 3);
-        launch_div_cols(c, specials, (size_t)E * N, tmp, level, rows, DA, st, finv ? c->d_fin_moddown : nullptr);
-        launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, add_both, r_last, DA.Binv, level, rows, st,
-                          level - 1, 1, N);
-        launch_ntt(c, false, r_last, last_coef, table_map(lidx, 1, N, N), rows, st, c->d_fin_rescale + (level - 1), finv ? 2 : 3);
-        launch_div_cols(c, last_coef, N, tmpB, level - 1, rows, DB, st, finv ? c->d_fin_rescale + (level - 1) : nullptr);
-        launch_rows_final2(c, tmp, tmpB, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, out, DA.Binv, DB.Binv, level, rows, st);
+    const int rows = items * 2;
+    if (tail) {
+        // ONE conversion and ONE last pass for ModDown + add + rescale (same bits; see modup_cols_kernel MODE 3):
+        // u = x_last * P^-1 + d_last (written by the inner product) stands in place of the dropped limb, its inverse
+        // transform rides with the special limbs' (limbs last, p_0 .. p_{k-1} of every row are neighbours)
+        const int last = level - 1;
+        u64 *bl = acc + (size_t)last * N;
+        const DivRoundDev &DB = c->divround[1 + last];
+        DivRoundDev D3 = c->divround[0];
+        D3.nb = c->k + 1;
+        D3.b_idx[0] = last;
+        for (int m = 0; m < c->k; m++) D3.b_idx[1 + m] = c->n_q + m;
+        const FinConst *ft = c->d_fin_tail + (size_t)level * CKKSMI_MAX_SPECIAL;
+        launch_ntt(c, false, bl, bl, table_map(D3.b_idx, D3.nb, (size_t)E * N, (size_t)E * N), rows, st, ft, 2);
+        launch_modup_cols(c, 3, bl, (size_t)E * N, tmp, rows, 0, last, &D3, (double)rows * last, st, ft, &DB);
+        launch_rows_final(c, tmp, acc, (size_t)E * N, nullptr, 0, 0, 0, out, DB.Binv, last, rows, st);
         return;
     }
-    if (tail_folded)  // the ciphertext limbs already hold x * P^-1 + addend
-        divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
-                      acc, (size_t)E * N, tmp, level, items * 2, nullptr, 0, 0, 0, out, st, true);
-    else
-        divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, acc + (size_t)level * N, (size_t)E * N, acc + (size_t)level * N, (size_t)E * N,
-                      acc, (size_t)E * N, tmp, level, items * 2, addend, add_item_stride, add_comp_stride, add_both, out, st);
+    // plain ModDown; with an addend the kept limbs already hold x * P^-1 + addend
+    divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, specials, (size_t)E * N, specials, (size_t)E * N, acc, (size_t)E * N, tmp, level, rows,
+                  nullptr, 0, 0, 0, out, st, addend != nullptr);
 }
 
 void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u64 *ws, hipStream_t st) {
@@ -572,11 +421,6 @@ void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int le
     int lidx[1] = {level - 1};
     divround_rows(c, c->divround[1 + (level - 1)], c->d_fin_rescale + (level - 1), lidx, a + (size_t)(level - 1) * N, (size_t)level * N, last,
                   N, a, (size_t)level * N, tmp, level - 1, items * 2, nullptr, 0, 0, 0, out, st);
-}
-
-// Can the rescale of v*a run with the scalar folded into its kernels (inverse transform constants and last pass)?
-bool scalar_rescale_fused_ok(const ckksmi_ctx *c) {
-    return c->fused && (c->fuse & (FUSE_DIVCONV | FUSE_FINAL)) == (FUSE_DIVCONV | FUSE_FINAL) && c->modup_loop && c->fuse_inv;
 }
 
 // out = DivRound_{q_{level-1}}(v * a) without materialising v*a: the dropped limb's inverse transform multiplies by v in its
@@ -598,7 +442,7 @@ void scalar_rescale_fused(ckksmi_ctx *c, const u64 *a, int64_t v, const u64 *add
     F.pad = 0.0;
     const ScalarTab St = scalar_tab(c, v, level);
     launch_ntt(c, false, a + (size_t)last * N, lastbuf, table_map(lidx, 1, in_stride, N), rows, st, c->d_fin_rescale + last, 2);
-    launch_div_cols(c, lastbuf, N, tmp, last, rows, D, st, c->d_fin_rescale + last, &F);
+    launch_modup_cols(c, 1, lastbuf, N, tmp, rows, 0, last, &D, (double)rows * last, st, c->d_fin_rescale + last, nullptr, &F);
     launch_rows_final(c, tmp, a, in_stride, addend, (size_t)2 * last * N, (size_t)last * N, 1, out, D.Binv, last, rows, st, 0, -1, 0, nullptr, nullptr,
                       &St);
 }
@@ -609,10 +453,11 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
              size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st, bool merged = false,
              const HoistPlan *hoist = nullptr) {
     if (c->fused) {
-        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st, nullptr, false,
+        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st, false, false,
                       merged, hoist);
         return;
     }
+    // other ring sizes: the generic kernels, one step after the other
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     const int rows = items * 2 * (hoist ? hoist->R : 1);
@@ -760,12 +605,6 @@ int dev_upload_tables(ckksmi_ctx *c) {
         std::vector<WMul> p24(T);
         for (int t = 0; t < T; t++) p24[t] = make_wmul(((u64)1 << 24) % c->mod[t], c->mod[t]);
         c->d_pow24 = upload(c, p24.data(), p24.size(), ok);
-        if (const char *e = getenv("CKKSMI_MAC_MFMA")) c->mac_mfma = atoi(e) != 0;
-        if (const char *e = getenv("CKKSMI_MODUP_LOOP")) c->modup_loop = atoi(e) != 0;
-        if (const char *e = getenv("CKKSMI_FUSE_TAIL")) c->fuse_tail = atoi(e);  // 0 separate, 1 shared last pass, 2 one conversion
-        if (const char *e = getenv("CKKSMI_FUSE_INV")) c->fuse_inv = atoi(e) != 0;
-        if (const char *e = getenv("CKKSMI_FUSE_TENSOR")) c->fuse_tensor = atoi(e) != 0;
-        if (const char *e = getenv("CKKSMI_MODUP_TARGETS")) c->modup_targets_per_wg = atoi(e);
     }
     for (int t = 0; t < T; t++)
         if (c->mod[t] >= ((u64)1 << 50)) c->p51mask.w[t >> 6] |= 1ull << (t & 63);
@@ -847,9 +686,8 @@ int dev_upload_tables(ckksmi_ctx *c) {
         }
         c->d_pmod = upload(c, c->h_pmod.data(), c->h_pmod.size(), ok);
     }
-    // fused path: constants folded into the last stage of the inverse transforms
-    c->fused = c->logN >= 13 && c->logN <= 16 && !getenv("CKKSMI_NO_FUSION");
-    if (const char *e = getenv("CKKSMI_FUSE")) c->fuse = atoi(e) & 15;  // tuning / test knob
+    // register-tiled sizes: constants folded into the last stage of the inverse transforms
+    c->fused = c->logN >= 13 && c->logN <= 16;
     if (c->fused) {
         auto fin = [&](int t, u64 mult, u64 add) {
             const u64 q = c->mod[t];
@@ -1145,7 +983,7 @@ extern "C" int ckksmi_mul_scalar_rescale(ckksmi_ctx *c, const uint64_t *a, int64
         const u64 *ain = a + (size_t)b0 * 2 * level_in * N;
         u64 *o = out + (size_t)b0 * 2 * (level - 1) * N;
         const u64 *add = addend ? addend + (size_t)b0 * 2 * (level - 1) * N : nullptr;
-        if (scalar_rescale_fused_ok(c)) {
+        if (c->fused) {
             scalar_rescale_fused(c, ain, v, add, o, items, level_in, level, (u64 *)ws, st);
         } else {
             // the steps as they are (modulus drop, scalar product, rescale): the product goes through the workspace
@@ -1196,40 +1034,32 @@ static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint6
         u64 *d = (u64 *)ws;                              // [items][3][level][N]
         u64 *r = d + (size_t)items * 3 * level * N;      // [items][2][level][N]
         u64 *rest = r + (size_t)items * 2 * level * N;
-        const bool tail = c->fused && c->fuse_tail && (c->fuse & (FUSE_DIVCONV | FUSE_FINAL)) == (FUSE_DIVCONV | FUSE_FINAL);
-        // the tensor kernel can take d2 through the inverse row pass on the way (its output lands where the key switch
-        // expects it: the start of its workspace)
-        const bool trows = c->fused && c->fuse_tensor && (c->fuse & FUSE_MODUP) && c->modup_loop && c->fuse_inv;
+        // register-tiled sizes: the tensor kernel takes d2 through the inverse row pass on the way (its output lands where
+        // the key switch expects it: the start of its workspace)
         const size_t in0 = (size_t)b0 * terms * 2 * level * N;
-        if (trows)
-            launch_tensor_rows(c, a + in0, b + in0, d, rest, level, items, S(stream), terms);
-        else
+        u64 *o = out + (size_t)b0 * 2 * (level - 1) * N;
+        if (!c->fused) {
             launch_tensor(c, a + in0, b + in0, d, level, items, S(stream), terms);
-        if (merged) {
-            // one division by P*q_{level-1} of (accumulators + P*(d0, d1))
-            if (c->fused)
-                ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
-                              out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), nullptr, trows, true);
-            else
-                ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
-                        out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), true);
+            if (merged) {
+                ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, o, rest,
+                        S(stream), true);
+            } else {
+                ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r, rest,
+                        S(stream));
+                rescale_core(c, r, o, items, level, rest, S(stream));
+            }
             continue;
         }
-        if (tail) {
-            // ModDown + add + rescale with a shared last pass: r is only scratch
-            ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1,
-                          out + (size_t)b0 * 2 * (level - 1) * N, rest, S(stream), r, trows);
-            continue;
-        }
-        if (trows) {
+        launch_tensor_rows(c, a + in0, b + in0, d, rest, level, items, S(stream), terms);
+        if (merged || one_conversion_tail_ok(c)) {
+            // one division by P*q_{level-1} of (accumulators + P*(d0, d1)), or ModDown + add + rescale as one conversion
+            ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, o,
+                          rest, S(stream), !merged, true, merged);
+        } else {
             ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r,
-                          rest, S(stream), nullptr, true);
-            rescale_core(c, r, out + (size_t)b0 * 2 * (level - 1) * N, items, level, rest, S(stream));
-            continue;
+                          rest, S(stream), false, true);
+            rescale_core(c, r, o, items, level, rest, S(stream));
         }
-        ks_core(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r, rest,
-                S(stream));
-        rescale_core(c, r, out + (size_t)b0 * 2 * (level - 1) * N, items, level, rest, S(stream));
     }
     return g.rc();
 }
@@ -1469,7 +1299,7 @@ MacShape mac_shape(const ckksmi_ctx *c, int C, int O, int kh, int kw, int level)
     s.afrag_bytes = (size_t)level * s.Kb * s.Mg * MM_MB * MM_DIG * 64 * 16;
     s.mfma_bytes = s.afrag_bytes + 2 * (size_t)s.Kb * 64 * sizeof(TapEnt);
     // below 8 output channels most of a 32-channel group would multiply zeros: the vector kernel is faster there
-    s.mfma_ok = c->mac_mfma && c->N >= MM_WORDS && O >= 8 && K <= MM_KMAX - 63;
+    s.mfma_ok = c->N >= MM_WORDS && O >= 8 && K <= MM_KMAX - 63;
     return s;
 }
 }  // namespace
@@ -1591,17 +1421,22 @@ extern "C" int ckksmi_profile_read(ckksmi_ctx *c, int kernel_class, double *tota
     return CKKSMI_OK;
 }
 
+extern "C" int ckksmi_tune(ckksmi_ctx *c, int knob, int value) {
+    if (!c || knob != CKKSMI_TUNE_TARGET_WGS || value < 1) return CKKSMI_EINVAL;
+    c->ntt_target_wgs = value;
+    return CKKSMI_OK;
+}
+
 extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_class) {
     static const char *names[CKKSMI_K_COUNT] = {"ntt_fwd_kernel<true>", "ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_inv_kernel<true>",
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
-                                                "elementwise kernels", "conv_cols_kernel", "conv_cols_kernel", "rows_inner_kernel",
-                                                "rows_final_kernel", "conv_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "rows_final2_kernel", "tensor_rows_kernel",
+                                                "elementwise kernels", "modup_cols_kernel", "modup_cols_kernel", "rows_inner_kernel",
+                                                "rows_final_kernel", "modup_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "ntt_lds_kernel", "tensor_rows_kernel",
                                                 "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel",
                                                 "encoding kernels", "encryption kernels", "modup_cols_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
-    if (c && kernel_class == CKKSMI_K_INNER_HOISTED && (c->logN < 8 || c->beta_top > INNER_MAX_BETA || getenv("CKKSMI_HOIST_GATHER")))
-        return "inner_product_hoisted_kernel";
+    if (c && kernel_class == CKKSMI_K_INNER_HOISTED && !hoisted_tile_ok(c, c->beta_top)) return "inner_product_hoisted_kernel";
     if (c && c->logN >= 13 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
                                     "ntt_v2_kernel<true, true>"};
@@ -1609,13 +1444,11 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
         // the conversion kernels are instantiated per (size, source limbs, mode): report the symbol that runs
         static thread_local char buf[64];
         const int q = c->logN - 12;
-        const char *kn = c->modup_loop ? "modup_cols_kernel" : "conv_cols_kernel";
-        const char *tail = c->modup_loop ? (c->fuse_inv ? ", true>" : ", false>") : ">";
-        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "%s<%d, %d, 0%s", kn, q, c->alpha, tail); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "%s<%d, %d, 1%s", kn, q, c->k, tail); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "%s<%d, 1, 1%s", kn, q, tail); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_TAIL) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 3, true>", q, c->k + 1); return buf; }
-        if (kernel_class == CKKSMI_K_CONV_COLS_MERGED) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 2, true>", q, c->k + 1); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_MODUP) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 0>", q, c->alpha); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_DIV) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 1>", q, c->k); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_RESCALE) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, 1, 1>", q); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_TAIL) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 3>", q, c->k + 1); return buf; }
+        if (kernel_class == CKKSMI_K_CONV_COLS_MERGED) { snprintf(buf, sizeof(buf), "modup_cols_kernel<%d, %d, 2>", q, c->k + 1); return buf; }
     }
     return names[kernel_class];
 }

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "../../include/ckksmi.h"
+#include "../../include/ckksmi_profile.h"
 
 typedef uint64_t u64;
 typedef int64_t i64;
@@ -75,8 +76,7 @@ struct ProfRec { int kid; double units; void *start, *stop; };
 
 struct ckksmi_ctx {
     bool prof_on = false;
-    int ntt_target_wgs = 8192;
-    int conv_items_per_wg = 1;  // items a conversion workgroup loops over (1: item-major dispatch keeps a digit's source tiles shared in L2)  // workgroups a transform launch aims for before it starts looping over items
+    int ntt_target_wgs = 8192;  // workgroups a transform launch aims for before it starts looping over items (ckksmi_tune)
     std::vector<ProfRec> prof;
 
     int logN = 0, n_q = 0, k = 0, alpha = 1, T = 0, beta_top = 0;
@@ -92,14 +92,6 @@ struct ckksmi_ctx {
     // ---- device tables ----
     ModConst *d_mod = nullptr;   // [T]
     WMul *d_pow24 = nullptr;     // [T] 2^24 mod p (matrix-core MAC: recombination of the digit diagonals)
-    int fuse_tensor = 1;         // hmul_relin_rescale: the tensor kernel runs the inverse row pass of d2 (CKKSMI_FUSE_TENSOR=0: separate pass)
-    int fuse_inv = 1;            // conversion kernels run the inverse column pass of their sources themselves (CKKSMI_FUSE_INV=0: separate pass)
-    int fuse_tail = 3;           // hmul_relin_rescale: 3 = as 2, and the fused inner product already writes x*P^-1 + d for the ciphertext
-                                 // limbs; 2 = ModDown and rescale as one conversion and one last pass, 1 = they share
-                                 // their last pass, 0 = two separate DivRounds (CKKSMI_FUSE_TAIL)
-    int modup_loop = 1;          // ModUp column pass organised by source tile (CKKSMI_MODUP_LOOP=0: one workgroup per target limb)
-    int modup_targets_per_wg = 0;  // 0: chosen from the grid size (CKKSMI_MODUP_TARGETS)
-    int mac_mfma = 1;            // conv / FC MAC on the matrix cores where the shape allows (CKKSMI_MAC_MFMA=0: vector ALU only)
     WMul *d_tw_fwd = nullptr;    // [T][N]  psi^brev(x), x in [1,N)
     WMul *d_tw_inv = nullptr;    // [T][N]  psi^-brev(x); entry 0 holds N^-1
     WMul *d_tw_inv_last = nullptr;  // [T]   psi^-brev(1) * N^-1  (last inverse stage)
@@ -127,8 +119,7 @@ struct ckksmi_ctx {
     std::vector<WMul> h_Pinv;           // [T] P^-1 mod q_i
     WMul *d_pmod = nullptr;             // device copy; nullptr: merged division unavailable (k = 0 or k + 1 > CKKSMI_MAX_SPECIAL)
     P51Mask p51mask = {{0, 0}};
-    bool fused = false;  // N = 2^16: register-tiled passes for everything, steps below optionally fused into them
-    int fuse = 15;       // bit 0 ModUp, 1 inner product, 2 DivRound conversion, 3 DivRound final step
+    bool fused = false;  // 2^13 <= N <= 2^16: register-tiled passes with the limb-wise steps fused into them
 
     // registered Galois keys
     std::vector<std::pair<int, const u64 *>> galois;

@@ -48,14 +48,6 @@ extern "C" int ckksmi_ctx_create(const ckksmi_params *p, ckksmi_ctx **out) {
     c->T = c->n_q + c->k;
     c->beta_top = (c->n_q + alpha - 1) / alpha;
     c->device = p->device;
-    if (const char *e = getenv("CKKSMI_CONV_ITEMS")) {  // tuning / test knob
-        int v = atoi(e);
-        if (v >= 1) c->conv_items_per_wg = v;
-    }
-    if (const char *e = getenv("CKKSMI_NTT_TARGET_WGS")) {  // tuning / test knob
-        int v = atoi(e);
-        if (v >= 1) c->ntt_target_wgs = v;
-    }
     if (p->moduli_override) {
         for (int t = 0; t < c->T; t++) {
             u64 m = p->moduli_override[t];

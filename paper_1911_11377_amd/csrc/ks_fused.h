@@ -2,19 +2,20 @@
 // transform passes of ntt_v2.h.  They remove the HBM round trips between a transform and the
 // limb-wise step next to it:
 //
-//   conv_cols_kernel   : fast basis conversion (ModUp of a digit, or the conversion step of
-//                        DivRound) computed while loading the column pass of the forward
-//                        transform of its result -- the converted limb is never stored in
-//                        coefficient form;
+//   tensor_rows_kernel : tensor product of a tile + the inverse row pass of its third component;
+//   modup_cols_kernel  : inverse column pass of the source tiles, fast basis conversion (ModUp of
+//                        a digit, or the conversion step of DivRound) and the column pass of the
+//                        forward transform of every converted limb -- neither the conversion
+//                        inputs nor the converted limbs are ever stored in coefficient form;
 //   rows_inner_kernel  : row pass of the forward transform of every digit's extended limb,
 //                        multiplied by the switching key and accumulated over the digits in
 //                        registers -- the transformed limbs are never stored;
 //   rows_final_kernel  : row pass fused with DivRound's last step
 //                        out = (x - NTT(r - h)) * Bbar^-1 (+ addend).
 //
-// The conversion inputs y (y_i = d_i * qhat_i^-1 mod q_i, canonical) are produced by the inverse
+// The conversion inputs y (y_i = d_i * qhat_i^-1 mod q_i, canonical) come out of the inverse
 // transform itself: its last stage multiplies by 1/N anyway, so the extra constant rides along
-// (NttV2Args::fin).
+// (FinConst).
 #pragma once
 #include "ntt_v2.h"
 
@@ -125,130 +126,10 @@ __global__ __launch_bounds__(V2_THREADS, 2) void tensor_rows_kernel(TensorRowsAr
         tensor_rows_body<false>(A, lds, blockIdx.z, i);
 }
 
-// ------------------------------------------------------------------ column pass with conversion
-struct ConvColsArgs {
-    const u64d *y;                // source limbs, coefficient form, canonical; item i at y + i*y_item_stride
-    unsigned long long y_item_stride;
-    u64d *dst;                    // [items][slots][N] (column pass output, to be finished by a row pass)
-    unsigned long long dst_item_stride;
-    const ModConst *modc;
-    const double *tw;             // forward twiddles [T][N]
-    int logN, items, items_per_z;
-    int mode;                     // 0: ModUp (slot = j*E + x), 1: DivRound (slot = kept limb i)
-    int level, E, n_q, alpha, T;  // ModUp
-    const WMul *cc;               // ModUp constants [beta_top][alpha][alpha][T]
-    DivRoundDev D;                // DivRound constants; its nb source limbs are y's limbs 0..nb-1
-    P51Mask p51;
-};
-
-template <bool P51, int NSRC, int Q>
-__device__ __forceinline__ void conv_cols_body(const ConvColsArgs &A, double *lds, double *tw2_lds, int t, unsigned slot, unsigned first_src,
-                                               int nsrc, const WMul *W, double hsub) {
-    typedef ColsGeom<Q> Geo;
-    typedef ColsMasks<Q, P51> Mk;
-    const unsigned N = 1u << A.logN;
-    const double p = A.modc[t].p, pinv = A.modc[t].pinv;
-    const double *tw = A.tw + (size_t)t * N;
-    const Geo geo(threadIdx.x, blockIdx.x);
-    double tw1[15];
-    {
-        // round-2 twiddles depend only on a = tid / 16: kept in LDS ([16][16] doubles) to free registers
-        double tw2[15];
-        load_cols_twiddles<Q>(tw, geo.a, tw1, tw2);
-#pragma unroll
-        for (int i = 0; i < 15; i++)
-            if (geo.l16 == (unsigned)i) tw2_lds[geo.a * 16 + i] = tw2[i];
-        __syncthreads();
-    }
-    WMul Wc[NSRC];
-#pragma unroll
-    for (int a = 0; a < NSRC; a++) Wc[a] = W[a];
-    const unsigned i0 = blockIdx.z * (unsigned)A.items_per_z;
-    const unsigned i1 = (i0 + A.items_per_z < (unsigned)A.items) ? i0 + A.items_per_z : (unsigned)A.items;
-    for (unsigned it = i0; it < i1; it++) {
-        const u64d *ysrc = A.y + (size_t)it * A.y_item_stride + (size_t)first_src * N;
-        u64d *dst = A.dst + (size_t)it * A.dst_item_stride + (size_t)slot * N;
-        // all source words first (one memory latency instead of one per source limb), then the arithmetic;
-        // a digit cut short by the level has nsrc < NSRC sources (its missing constants are zero).
-        // (Requesting the next item's words before this item's butterflies was tried: the extra live registers
-        // spill and the kernel gets slower.)
-        u64d raw[NSRC][16];
-#pragma unroll
-        for (int a = 0; a < NSRC; a++) {
-            const u64d *ya = ysrc + (size_t)(a < nsrc ? a : 0) * N;  // a missing source re-reads limb 0; its constant is zero
-#pragma unroll
-            for (int e = 0; e < 16; e++) raw[a][e] = ya[geo.g1(e)];
-        }
-        SCHED_FENCE();  // keep every load above the arithmetic
-        double x[16];
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-            double v = -hsub;
-#pragma unroll
-            for (int a = 0; a < NSRC; a++) v += mulmod_w(u2d(raw[a][e]), Wc[a].w, Wc[a].wp, p);
-            // |v| <= p + NSRC*0.75p < 2^53: bring into the balanced range the round schedule assumes
-            x[e] = reduce_balanced(v, p, pinv);
-        }
-        fwd_round<Mk::F1>(x, tw1, p, pinv);
-#pragma unroll
-        for (int e = 0; e < 16; e++) lds[geo.l1(e)] = x[e];
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 16; i++) x[i] = lds[geo.l2(i)];
-        {
-            double tw2[15];
-#pragma unroll
-            for (int i = 0; i < 15; i++) tw2[i] = tw2_lds[geo.a * 16 + i];
-            fwd_stages<Geo::S0, Mk::F2>(x, tw2, p, pinv);
-        }
-#pragma unroll
-        for (int i = 0; i < 16; i++) dst[geo.g2(i)] = mid_store(x[i], p, pinv);
-        __syncthreads();
-    }
-}
-
-// grid: x = column tile (N/4096), y = slot, z = chunk of items.  Q = logN - 12; NSRC = most source limbs any slot has;
-// MODE 0: ModUp, 1: DivRound conversion
-template <int Q, int NSRC, int MODE>
-__global__ __launch_bounds__(V2_THREADS, 3) void conv_cols_kernel(ConvColsArgs A) {
-    __shared__ double lds[16 * V2_GS];
-    __shared__ double tw2_lds[16 * 16];
-    const unsigned slot = blockIdx.y;
-    int t, nsrc;
-    unsigned first_src;
-    double hsub = 0.0;
-    WMul W[NSRC];
-#pragma unroll
-    for (int a = 0; a < NSRC; a++) W[a] = WMul{0.0, 0.0};
-    if (MODE == 0) {
-        const unsigned j = slot / (unsigned)A.E, x = slot % (unsigned)A.E;
-        const int lo = (int)j * A.alpha;
-        nsrc = (A.level - lo < A.alpha) ? A.level - lo : A.alpha;
-        if ((int)x >= lo && (int)x < lo + nsrc) return;  // limb of the digit itself: already in evaluation form
-        t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
-        first_src = (unsigned)lo;
-        const size_t row = ((size_t)j * A.alpha + (nsrc - 1)) * A.alpha;
-#pragma unroll
-        for (int a = 0; a < NSRC; a++)
-            if (a < nsrc) W[a] = A.cc[(row + a) * A.T + t];
-    } else {
-        t = (int)slot;
-        nsrc = A.D.nb;
-        first_src = 0;
-#pragma unroll
-        for (int a = 0; a < NSRC; a++)
-            if (a < nsrc) W[a] = A.D.conv[(size_t)a * A.T + t];
-        hsub = A.D.hc[t];
-    }
-    if (is_p51(A.p51, t))
-        conv_cols_body<true, NSRC, Q>(A, lds, tw2_lds, t, slot, first_src, nsrc, W, hsub);
-    else
-        conv_cols_body<false, NSRC, Q>(A, lds, tw2_lds, t, slot, first_src, nsrc, W, hsub);
-}
-
-// ------------------------------------------------------------------ ModUp column pass, targets looped in the workgroup
-// The same conversion + column pass as conv_cols_kernel<Q, NSRC, 0>, organised around the SOURCE tile instead of the
-// target limb: a workgroup reads the digit's source words once, keeps them in registers as doubles and produces the
+// ------------------------------------------------------------------ conversion + column pass, targets looped in the workgroup
+// Fast basis conversion and the column pass of the forward transform of its results, organised around the SOURCE tile:
+// a workgroup reads the source tiles once (as the output of the inverse row pass, and runs their inverse column pass
+// itself), keeps them in registers as doubles and produces the
 // column-pass tile of every target limb of its chunk from them.  What remains per target is arithmetic and stores
 // (which do not stall a wave), so the loads no longer alternate with the butterflies.  Per target the 255 column-pass
 // twiddles of its modulus go through LDS (one coalesced 2 KB read per workgroup, fetched one target ahead).
@@ -273,7 +154,7 @@ struct ModupColsArgs {
     int logN, level, E, n_q, alpha, beta, T, nc;
     int targets_per_wg;
     P51Mask p51;
-    // INVSRC: y holds the output of the inverse ROW pass (reduced doubles); the inverse column pass with its folded
+    // y holds the output of the inverse ROW pass (reduced doubles); the inverse column pass with its folded
     // constants runs in the workgroup's prologue and the conversion inputs never go through memory
     const double *tw_inv;         // inverse twiddles [T][N]
     const FinConst *fin;          // last-stage constants of source limb s (MODE 0: limb index; MODE 1: s-th dropped limb)
@@ -385,7 +266,7 @@ __device__ __forceinline__ void modup_cols_target(const double (&yd)[NSRC][16], 
 // addend, in the second exchange buffer and pays a second barrier per target (0.80 ms; all four in registers at one wave
 // per SIMD: 1.0 ms).  MODE 2 multiplies all four sources per target: it runs one wave per SIMD with all of them in
 // registers (0.97 ms; one of them in LDS at two waves: 1.21 ms; with spills at two: 1.4 ms).
-template <int Q, int NSRC, int MODE, bool INVSRC>
+template <int Q, int NSRC, int MODE>
 __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void modup_cols_kernel(ModupColsArgs A) {
     // one barrier per target: the exchange buffer alternates between two copies, the twiddles rotate through three
     // (target k's set is written during target k-1, while slower waves may still read the set of target k-2... k-1)
@@ -414,19 +295,7 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void 
     const ColsGeom<Q> geo(threadIdx.x, blockIdx.x);
     // the source words, once: a missing source (digit cut short by the level) re-reads the first limb, its constants are zero
     double yd[NSRC][16];
-    if (!INVSRC) {
-        u64d raw[NSRC][16];
-#pragma unroll
-        for (int a = 0; a < NSRC; a++) {
-            const u64d *ya = ysrc + (size_t)(a < nsrc ? a : 0) * N;
-#pragma unroll
-            for (int e = 0; e < 16; e++) raw[a][e] = ya[geo.g1(e)];
-        }
-#pragma unroll
-        for (int a = 0; a < NSRC; a++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) yd[a][e] = u2d(raw[a][e]);
-    } else {
+    {
         // every source tile is requested first, then taken through its inverse column pass one after the other
         u64d raw[NSRC][16];
 #pragma unroll
@@ -495,7 +364,7 @@ __global__ __launch_bounds__(V2_THREADS, (NSRC >= 4 && MODE == 2) ? 1 : 2) void 
     }
     // three source tiles: the first one lives in the second exchange buffer (one buffer, two barriers per target): without
     // it the kernel spills at two waves per SIMD (ModUp at the benchmark shape: 2.35 against 2.58 ms)
-    constexpr bool SRC0_LDS = (MODE <= 1 && NSRC == 3 && INVSRC);
+    constexpr bool SRC0_LDS = (MODE <= 1 && NSRC == 3);
     if (SRC0_LDS) {
 #pragma unroll
         for (int e = 0; e < 16; e++) lds[1][e * 256 + threadIdx.x] = yd[0][e];
@@ -890,82 +759,4 @@ __global__ __launch_bounds__(V2_THREADS) void rows_final_scalar_kernel(RowsFinal
         rows_final_body<true>(A, lds, tw1_lds, i, true, xmv);
     else
         rows_final_body<false>(A, lds, tw1_lds, i, true, xmv);
-}
-
-// ------------------------------------------------------------------ two DivRound final steps in one pass
-// ModDown followed by rescale, for the limbs that survive both: with rA, rB the row-pass results of the two conversions
-//     r_i   = (x_i - rA_i) * P^-1 + addend_i            (ModDown, then the add of the product's first two components)
-//     out_i = (r_i - rB_i) * q_last^-1                  (rescale)
-// r_i never leaves the registers.  rB comes from the ModDown result of the dropped limb q_last alone, which the caller
-// computes first with rows_final_kernel restricted to that limb.
-struct RowsFinal2Args {
-    const u64d *tmpA;    // [rows][ncA][N] column-pass output of the ModDown conversion
-    const u64d *tmpB;    // [rows][ncB][N] column-pass output of the rescale conversion, ncB = ncA - 1
-    const u64d *x;       // accumulators, evaluation form: row r, limb i at x + r*x_row_stride + i*N
-    unsigned long long x_row_stride;
-    const u64d *addend;  // row r limb i at addend + (r/2)*add_item_stride + (r%2)*add_comp_stride + i*N
-    unsigned long long add_item_stride, add_comp_stride;
-    u64d *out;           // [rows][ncB][N]
-    const ModConst *modc;
-    const double *tw;
-    const WMul *BinvA, *BinvB;  // [T]
-    int logN, ncA, ncB;
-    int rows, rows_per_x;
-    P51Mask p51;
-};
-
-template <bool P51>
-__device__ __forceinline__ void rows_final2_body(const RowsFinal2Args &A, double *lds, double *tw1_lds, int i) {
-    const unsigned N = 1u << A.logN, N1 = N >> 8;
-    const double p = A.modc[i].p, pinv = A.modc[i].pinv;
-    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
-    const unsigned tile = blockIdx.y;
-    double tw2[15];
-    load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
-    const size_t tile0 = (size_t)tile * 4096;
-    const WMul WA = A.BinvA[i], WB = A.BinvB[i];
-    const unsigned r0 = blockIdx.x * (unsigned)A.rows_per_x;
-    const unsigned r1 = (r0 + A.rows_per_x < (unsigned)A.rows) ? r0 + A.rows_per_x : (unsigned)A.rows;
-    for (unsigned row = r0; row < r1; row++) {
-        const u64d *xin = A.x + (size_t)row * A.x_row_stride + (size_t)i * N + tile0;
-        const u64d *ad = A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0;
-        u64d *out = A.out + ((size_t)row * A.ncB + i) * N + tile0;
-        // pointwise parts in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
-        ulonglong2 xr[8], ar[8];
-#pragma unroll
-        for (int s = 0; s < 8; s++) {
-            xr[s] = ((const ulonglong2 *)xin)[256 * s + tid];
-            ar[s] = ((const ulonglong2 *)ad)[256 * s + tid];
-        }
-        SCHED_FENCE();
-        rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.ncA + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
-        double r[16];  // |r| < 2.5p
-#pragma unroll
-        for (int s = 0; s < 8; s++) {
-            const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
-            r[2 * s] = mulmod_w(u2d(xr[s].x) - rr[0], WA.w, WA.wp, p) + u2d(ar[s].x);
-            r[2 * s + 1] = mulmod_w(u2d(xr[s].y) - rr[1], WA.w, WA.wp, p) + u2d(ar[s].y);
-        }
-        __syncthreads();
-        rows_fwd_to_lds<P51>(A.tmpB + ((size_t)row * A.ncB + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
-#pragma unroll
-        for (int s = 0; s < 8; s++) {
-            const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
-            const double v0 = mulmod_w(r[2 * s] - rr[0], WB.w, WB.wp, p);  // |r - rB| < 3.1p < 2^53
-            const double v1 = mulmod_w(r[2 * s + 1] - rr[1], WB.w, WB.wp, p);
-            ((ulonglong2 *)out)[256 * s + tid] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
-        }
-        __syncthreads();
-    }
-}
-
-// grid: x = chunk of rows (item, component), y = row tile (N/4096), z = limb (0 .. ncB-1)
-__global__ __launch_bounds__(V2_THREADS) void rows_final2_kernel(RowsFinal2Args A) {
-    __shared__ double lds[16 * V2_GS];
-    __shared__ double tw1_lds[16 * 16];
-    const int i = (int)blockIdx.z;
-    if (is_p51(A.p51, i))
-        rows_final2_body<true>(A, lds, tw1_lds, i);
-    else
-        rows_final2_body<false>(A, lds, tw1_lds, i);
 }

@@ -2,6 +2,8 @@
 function runs one operation of the library through its C ABI on buffers supplied by a
 backend and compares the result word for word with the CPU oracle on the same seeded
 inputs.  Bit-exact is the bar: all ciphertext arithmetic is integer mod q_i."""
+import contextlib
+
 import numpy as np
 
 from oracle import oracle as orc
@@ -10,7 +12,26 @@ from paper_1911_11377_amd import workloads as wl
 from helpers import Material
 
 
-class GpuBackend:
+class _Tunable:
+    """contexts made inside `with be.tuned(n):` aim for n workgroups per transform launch, so that a small batch
+    still makes the workgroups loop over items"""
+    target_wgs = None
+
+    @contextlib.contextmanager
+    def tuned(self, target_wgs):
+        old, self.target_wgs = self.target_wgs, target_wgs
+        try:
+            yield self
+        finally:
+            self.target_wgs = old
+
+    def _tune(self, ctx):
+        if self.target_wgs:
+            ctx.tune_target_wgs(self.target_wgs)
+        return ctx
+
+
+class GpuBackend(_Tunable):
     """device buffers are torch tensors on cuda:0"""
 
     def __init__(self):
@@ -21,7 +42,7 @@ class GpuBackend:
         self.lib_path = None
 
     def context(self, logN, n_q, q_bits, k, special_bits, alpha):
-        return ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=0)
+        return self._tune(ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=0))
 
     def to_dev(self, arr, dtype=np.uint64):
         a = np.ascontiguousarray(arr, dtype=dtype)
@@ -40,7 +61,7 @@ class GpuBackend:
     stream = None
 
 
-class EmuBackend:
+class EmuBackend(_Tunable):
     """'device' buffers are guard-paged host memory; kernels run as CPU fibers"""
 
     def __init__(self):
@@ -51,7 +72,7 @@ class EmuBackend:
         self.lib = ckksmi.load(self.lib_path)
 
     def context(self, logN, n_q, q_bits, k, special_bits, alpha):
-        return ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=0, lib=self.lib_path)
+        return self._tune(ckksmi.Context(logN, n_q, q_bits, k, special_bits, alpha, device=0, lib=self.lib_path))
 
     def to_dev(self, arr, dtype=np.uint64):
         return self.es.to_emu(self.lib, arr, dtype)
@@ -494,9 +515,200 @@ def case_variant_errors(be, shape=(6, 3, 30, 1, 31, 1)):
     ctx.close()
 
 
-def mfma_enabled():
-    import os
-    return os.environ.get("CKKSMI_MAC_MFMA", "1") != "0"
+def edge_limbs(moduli, N, pattern):
+    """[len(moduli)][N] residues at the ends and the middle of [0, q): the values where a lazy range, a canonical form or an
+    integer <-> floating-point conversion would first go wrong"""
+    out = np.zeros((len(moduli), N), dtype=np.uint64)
+    for i, q in enumerate(moduli):
+        q = int(q)
+        if pattern == "zero":
+            pass
+        elif pattern == "qm1":
+            out[i] = q - 1
+        elif pattern == "half_lo":
+            out[i] = (q - 1) // 2
+        elif pattern == "half_hi":
+            out[i] = (q + 1) // 2
+        elif pattern == "alt":
+            out[i, 1::2] = q - 1
+        elif pattern == "alt_halves":
+            out[i, 0::2] = (q - 1) // 2
+            out[i, 1::2] = (q + 1) // 2
+        elif pattern == "onehot":
+            out[i, (7 * i + 3) % N] = q - 1
+        elif pattern == "one":
+            out[i] = 1
+        else:
+            raise ValueError(pattern)
+    return out
+
+
+EDGE_PATTERNS = ("zero", "qm1", "half_lo", "half_hi", "alt", "alt_halves", "onehot", "one")
+# pairs of operands for the products: extreme times extreme, extreme times middle, sparse times dense
+EDGE_PAIRS = (("qm1", "qm1"), ("zero", "qm1"), ("half_lo", "half_hi"), ("half_hi", "half_hi"), ("alt", "qm1"), ("onehot", "alt_halves"),
+              ("alt_halves", "alt"), ("one", "qm1"))
+
+
+def edge_ct(M, level, pattern, comps=2):
+    return np.stack([edge_limbs(M.O.q[:level], M.N, pattern) for _ in range(comps)])
+
+
+def case_edge_values(be, shape, seed, level=None, rotation=5, extreme_key=True, seeded_key=True, conv=True, pairs=EDGE_PAIRS):
+    """residues at the ends and the middle of [0, q) (all 0, all q-1, (q-1)/2, (q+1)/2, alternating, one-hot) through the
+    transforms, the tensor, relinearisation, the composite product, rescale, the scalar rescale, rotation and the
+    multiply-accumulate, with the seeded switching key and with a key whose every word is q-1: word for word against the
+    oracle.  Uniform inputs almost never reach these values."""
+    M = make_material(shape, seed, rotations=(rotation,) if shape[3] else ())
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    level = level or O.n_q
+    N = O.N
+    # transforms of every pattern, every modulus of the chain
+    idx = list(range(O.n_q + O.k))
+    x = np.stack([edge_limbs(O.moduli, N, pat) for pat in EDGE_PATTERNS])
+    d = be.to_dev(x)
+    ctx.ntt(d, idx, len(EDGE_PATTERNS), stream=be.stream)
+    got = be.to_host(d).reshape(x.shape)
+    for b, pat in enumerate(EDGE_PATTERNS):
+        assert np.array_equal(got[b], O.ntt_limbs(x[b], idx)), "forward transform of pattern %s" % pat
+    d = be.to_dev(x)
+    ctx.intt(d, idx, len(EDGE_PATTERNS), stream=be.stream)
+    got = be.to_host(d).reshape(x.shape)
+    for b, pat in enumerate(EDGE_PATTERNS):
+        assert np.array_equal(got[b], O.intt_limbs(x[b], idx)), "inverse transform of pattern %s" % pat
+    EDGE_PAIRS = pairs
+    batch = len(EDGE_PAIRS)
+    a = np.stack([edge_ct(M, level, pa) for pa, _ in EDGE_PAIRS])
+    b = np.stack([edge_ct(M, level, pb) for _, pb in EDGE_PAIRS])
+    da, db = be.to_dev(a), be.to_dev(b)
+    # tensor
+    d3 = be.empty(batch, 3, level, N)
+    ctx.hmul(da, db, d3, level, batch, stream=be.stream)
+    hd = be.to_host(d3).reshape(batch, 3, level, N)
+    for i in range(batch):
+        assert np.array_equal(hd[i], O.tensor(a[i], b[i], level)), "tensor of %r" % (EDGE_PAIRS[i],)
+    # rescale and the scalar rescale (scalars that reduce to q-1, to the middle, and far outside (-q/2, q/2))
+    if level >= 2:
+        ws = be.ws(ctx.workspace_bytes(ckksmi.OP_MUL_SCALAR_RESCALE, level, batch))
+        out = be.empty(batch, 2, level - 1, N)
+        ctx.rescale(da, out, level, batch, ws, stream=be.stream)
+        got = be.to_host(out).reshape(batch, 2, level - 1, N)
+        for i in range(batch):
+            assert np.array_equal(got[i], O.rescale(a[i], level)), "rescale of %s" % EDGE_PAIRS[i][0]
+        for cst in (-1, int(O.q[level - 1]) // 2, (1 << 62) - 1, -(1 << 62) + 1):
+            ctx.mul_scalar_rescale(db, cst, out, level, batch, ws, stream=be.stream)
+            got = be.to_host(out).reshape(batch, 2, level - 1, N)
+            for i in range(batch):
+                assert np.array_equal(got[i], O.rescale(O.mul_scalar(b[i], cst, level), level)), "scalar rescale of %s by %d" % (EDGE_PAIRS[i][1], cst)
+    if O.k:
+        keys = [("seeded", M.rlk, M.gk[rotation])] if seeded_key else []
+        if extreme_key:
+            kq = np.empty_like(M.rlk)
+            for t, q in enumerate(O.moduli):
+                kq[:, :, t, :] = np.uint64(int(q) - 1)
+            keys.append(("all q-1", kq, kq))
+        for name, rlk, gk in keys:
+            evk = be.to_dev(rlk)
+            # relinearisation of the tensors above, and the composite product
+            r = be.empty(batch, 2, level, N)
+            ctx.relin(d3, evk, r, level, batch, be.ws(ctx.workspace_bytes(ckksmi.OP_RELIN, level, batch)), stream=be.stream)
+            got = be.to_host(r).reshape(batch, 2, level, N)
+            for i in range(batch):
+                assert np.array_equal(got[i], O.relin(hd[i], rlk, level)), "relin of %r, key %s" % (EDGE_PAIRS[i], name)
+            if level >= 2:
+                out = be.empty(batch, 2, level - 1, N)
+                ctx.hmul_relin_rescale(da, db, evk, out, level, batch, be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch)), stream=be.stream)
+                got = be.to_host(out).reshape(batch, 2, level - 1, N)
+                for i in range(batch):
+                    assert np.array_equal(got[i], O.hmul_relin_rescale(a[i], b[i], rlk, level)), "product of %r, key %s" % (EDGE_PAIRS[i], name)
+            # rotation
+            dgk = be.to_dev(gk)
+            ctx.galois_key_register(rotation, dgk)
+            outr = be.empty(batch, 2, level, N)
+            ctx.rotate(da, [rotation] * batch, outr, level, batch, be.ws(ctx.workspace_bytes(ckksmi.OP_ROTATE, level, batch)), stream=be.stream)
+            got = be.to_host(outr).reshape(batch, 2, level, N)
+            for i in range(batch):
+                assert np.array_equal(got[i], O.rotate(a[i], rotation, gk, level)), "rotation of %s, key %s" % (EDGE_PAIRS[i][0], name)
+    if conv:
+        # multiply-accumulate: every input word q-1 (and the other patterns), weights at the ends of int64's usable range
+        Cin, H, W, Oc, kh = 2, 3, 4, 9, 3
+        pats = [EDGE_PATTERNS[(c * H * W + y * W + xx) % len(EDGE_PATTERNS)] if (c + y + xx) % 3 else "qm1" for c in range(Cin) for y in range(H) for xx in range(W)]
+        xin = np.stack([edge_ct(M, level, pat) for pat in pats]).reshape(Cin, H, W, 2, level, N)
+        wi = np.rint(wl.weights_float((Oc, Cin, kh, kh), seed, "edge.w") * float(O.q[level - 1])).astype(np.int64)
+        wi.flat[0], wi.flat[1], wi.flat[2], wi.flat[3] = (1 << 62) - 1, -(1 << 62) + 1, -1, int(O.q[level - 1]) - 1
+        want = O.conv2d_mac(xin, wi, 1, 1, level)
+        for nbytes in (ctx.workspace_bytes(ckksmi.OP_CONV2D_MAC, level, wi.size), ctx.conv2d_workspace_bytes(Cin, Oc, kh, kh, level)):
+            outc = be.empty(Oc, H, W, 2, level, N)
+            ctx.conv2d_mac(be.to_dev(xin), be.to_dev(wi, np.int64), Cin, H, W, Oc, kh, kh, 1, 1, outc, level, be.ws(nbytes), stream=be.stream)
+            assert np.array_equal(be.to_host(outc).reshape(want.shape), want), "multiply-accumulate on edge values"
+    ctx.close()
+
+
+def own_poly3_constants(q, level_y, s_y):
+    """the three integer constants of 0.5 + 0.25 y - 0.02 y^3 for y at level_y, scale s_y, written out from the schedule:
+    t = RS(y * c1) must keep y's scale, so c1 = round(-0.02 * q_dropped); u = RS(y * c2) must reach the scale of y^3
+    (s_2 * s_y / q_dropped'), so c2 = round(0.25 * s_2); the constant term enters at the output scale"""
+    q_a, q_b = float(q[level_y - 1]), float(q[level_y - 2])
+    s_2 = s_y * s_y / q_a
+    s_3 = s_2 * s_y / q_b
+    return int(round(-0.02 * q_a)), int(round(0.25 * s_2)), int(round(0.5 * s_3)), s_3
+
+
+def case_activation(be, shape, seed, level, batch, sample, log_scale=50, decrypt=True, workers=1, expect_kernels=()):
+    """x^2, then 0.5 + 0.25 y - 0.02 y^3 (three products and two scalar steps, one level each) through the library's call
+    sequence, against the oracle's composition: y and the result word for word for the items in `sample`; those items are
+    real encryptions and decrypt to the float polynomial, the rest are uniform residues"""
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_1911_11377_amd import activation
+
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    N, s = O.N, 2.0 ** log_scale
+    x = random_cts(M, level, batch, seed, "act.x")
+    zs = {}
+    for i in sample:
+        zs[i] = wl.slots_real(N // 2, seed, "act.z", i)
+        if decrypt:
+            x[i] = M.encrypt(zs[i], s, level, ("act", i))
+    s_y = s * s / float(O.q[level - 1])
+    c1, c2, c3, s_out = own_poly3_constants(O.q, level - 1, s_y)
+    consts = activation.poly3_constants(O.q, level - 1, s_y)
+    assert (consts.c_m002, consts.c_025, consts.c_05) == (c1, c2, c3), "the call sequence's constants differ from the schedule's"
+    assert consts.out_scale == s_out
+    dx, evk = be.to_dev(x), be.to_dev(M.rlk)
+    y = be.empty(batch, 2, level - 1, N)
+    out = be.empty(batch, 2, level - 3, N)
+    ws = be.ws(activation.workspace_bytes(ctx, level, batch))
+    if expect_kernels:
+        ctx.profile_enable(True)
+    activation.square(ctx, dx, evk, y, level, batch, ws, stream=be.stream)
+    activation.poly3(ctx, y, evk, out, level - 1, batch, consts, ws, stream=be.stream)
+    gy = be.to_host(y).reshape(batch, 2, level - 1, N)
+    go = be.to_host(out).reshape(batch, 2, level - 3, N)
+    if expect_kernels:
+        ran = ctx.profile_read()
+        ctx.profile_enable(False)
+        for k in expect_kernels:
+            assert k in ran, (k, sorted(ran))
+
+    def oracle_item(i):
+        oy = O.square(x[i], M.rlk, level)
+        return oy, O.poly3(oy, M.rlk, level - 1, c1, c2, c3)
+
+    with ThreadPoolExecutor(max(1, min(workers, len(sample)))) as ex:  # the oracle's C calls release the GIL
+        wants = list(ex.map(oracle_item, sample))
+    for i, (oy, oo) in zip(sample, wants):
+        assert np.array_equal(gy[i], oy), "x^2 of item %d differs from the oracle" % i
+        assert np.array_equal(go[i], oo), "activation of item %d differs from the oracle" % i
+        if decrypt:
+            yv = zs[i].real ** 2
+            dec = M.decrypt(go[i], s_out, level - 3)
+            assert np.max(np.abs(dec.real - (0.5 + 0.25 * yv - 0.02 * yv ** 3))) < 1e-3
+    assert np.array_equal(be.to_host(dx).reshape(x.shape), x), "the schedule modified its input"
+    ctx.close()
 
 
 def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
@@ -523,7 +735,7 @@ def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
         got = be.to_host(out).reshape(Oc, Ho, Wo, 2, level, O.N)
         ran = ctx.profile_read()
         ctx.profile_enable(False)
-        assert ("conv_mac_mfma_kernel" in ran) == (which == "auto" and mfma_shape and mfma_enabled()), (which, list(ran))
+        assert ("conv_mac_mfma_kernel" in ran) == (which == "auto" and mfma_shape), (which, list(ran))
         assert np.array_equal(got, want), "conv MAC (%s) differs from the oracle" % which
     # FC: flat features
     F = Cin * H

@@ -74,49 +74,28 @@ def test_emulated_table1_like_network(be):
     pc.case_cnn(be, (6, 8, 50, 2, 51, 2), seed=121, topology="table1_tiny")
 
 
-def test_emulated_item_loop_and_composite_at_2e16(be, monkeypatch):
+def test_emulated_item_loop_and_composite_at_2e16(be):
     """N = 2^16: both register-tiled passes, with workgroups looping over several items"""
-    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "16")
-    pc.case_ntt(be, (16, 1, 50, 1, 51, 1), seed=109, batch=3)
-    pc.case_ntt(be, (13, 2, 50, 1, 51, 1), seed=110, batch=3)
-    pc.case_relin_and_composite(be, (16, 2, 50, 1, 51, 1), seed=111, batch=2, levels=[2])
+    with be.tuned(16):
+        pc.case_ntt(be, (16, 1, 50, 1, 51, 1), seed=109, batch=3)
+        pc.case_ntt(be, (13, 2, 50, 1, 51, 1), seed=110, batch=3)
+        pc.case_relin_and_composite(be, (16, 2, 50, 1, 51, 1), seed=111, batch=2, levels=[2])
 
 
-def test_emulated_fused_hybrid_at_2e16(be, monkeypatch):
+def test_emulated_fused_hybrid_at_2e16(be):
     """N = 2^16 with 3-prime digits: fused ModUp / inner product / ModDown / rescale kernels, partial last digit"""
-    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "64")
-    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=112, batch=2, levels=[4, 2])
-    pc.case_rescale(be, (16, 3, 50, 0, 51, 1), seed=113, batch=2, levels=[3])
-
-
-def test_emulated_unfused_path_at_2e16(be, monkeypatch):
-    monkeypatch.setenv("CKKSMI_NO_FUSION", "1")
-    pc.case_relin_and_composite(be, (16, 2, 50, 2, 51, 2), seed=114, batch=1, levels=[2])
-
-
-@pytest.mark.parametrize("fuse", [0, 1, 2, 4, 8, 5, 10])
-def test_emulated_partial_fusion(be, monkeypatch, fuse):
-    """every fusion switch on its own and in pairs gives the oracle's bits"""
-    monkeypatch.setenv("CKKSMI_FUSE", str(fuse))
-    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=115, batch=1, levels=[4 if fuse % 2 else 3])
-
-
-@pytest.mark.parametrize("env", [{"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_FUSE_TAIL": "2"}, {"CKKSMI_FUSE": "13"}, {"CKKSMI_MODUP_TARGETS": "3"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}, {"CKKSMI_FUSE_TAIL": "0", "CKKSMI_FUSE_TENSOR": "1"}])
-def test_emulated_alternative_key_switch_paths(be, monkeypatch, env):
-    """one workgroup per target limb in ModUp, separate ModDown / rescale passes, several target chunks per source tile"""
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
-    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=119, batch=1, levels=[4])
+    with be.tuned(64):
+        pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=112, batch=2, levels=[4, 2])
+        pc.case_rescale(be, (16, 3, 50, 0, 51, 1), seed=113, batch=2, levels=[3])
 
 
 @pytest.mark.parametrize("logN", [13, 14, 15])
-def test_emulated_fused_path_other_sizes(be, monkeypatch, logN):
-    """2^13 <= N < 2^16: general column geometry (N1 = 32, 64, 128), fused and unfused, 50- and 51-bit primes"""
-    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "8")
-    pc.case_ntt(be, (logN, 2, 50, 1, 51, 1), seed=116, batch=3)
-    pc.case_relin_and_composite(be, (logN, 3, 50, 2, 51, 2), seed=117, batch=2, levels=[3, 2])
-    monkeypatch.setenv("CKKSMI_FUSE", "0")
-    pc.case_relin_and_composite(be, (logN, 2, 40, 1, 41, 1), seed=118, batch=1, levels=[2])
+def test_emulated_fused_path_other_sizes(be, logN):
+    """2^13 <= N < 2^16: general column geometry (N1 = 32, 64, 128), 40-, 50- and 51-bit primes"""
+    with be.tuned(8):
+        pc.case_ntt(be, (logN, 2, 50, 1, 51, 1), seed=116, batch=3)
+        pc.case_relin_and_composite(be, (logN, 3, 50, 2, 51, 2), seed=117, batch=2, levels=[3, 2])
+        pc.case_relin_and_composite(be, (logN, 2, 40, 1, 41, 1), seed=118, batch=1, levels=[2])
 
 
 @pytest.mark.parametrize("shape,levels", [(TINY, [3, 2]), (HYBRID, [5, 4, 2]), (HYBRID3, [7, 5, 2])])
@@ -127,24 +106,16 @@ def test_emulated_merged_product_small_sizes(be, shape, levels):
         pc.case_merged_product(be, shape, seed=122, batch=3, levels=[5], small_ws=True)
 
 
-def test_emulated_merged_product_at_2e16(be, monkeypatch):
+def test_emulated_merged_product_at_2e16(be):
     """the fused form: conversion kernel over {q_last, p_0, p_1, p_2} with the overshoot taken from the source registers"""
-    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "64")
-    pc.case_merged_product(be, (16, 4, 50, 3, 51, 3), seed=123, batch=2, levels=[4, 2], expect_kernel="modup_cols_kernel<4, 4, 2, true>")
-
-
-@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_FUSE": "7"}, {"CKKSMI_FUSE": "11"}, {"CKKSMI_MODUP_LOOP": "0"},
-                                 {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE_TENSOR": "0"}])
-def test_emulated_merged_product_alternative_paths(be, monkeypatch, env):
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
-    pc.case_merged_product(be, (16, 3, 50, 2, 51, 2), seed=124, batch=1, levels=[3])
+    with be.tuned(64):
+        pc.case_merged_product(be, (16, 4, 50, 3, 51, 3), seed=123, batch=2, levels=[4, 2], expect_kernel="modup_cols_kernel<4, 4, 2>")
 
 
 @pytest.mark.parametrize("logN", [13, 14, 15])
-def test_emulated_merged_product_other_sizes(be, monkeypatch, logN):
-    monkeypatch.setenv("CKKSMI_NTT_TARGET_WGS", "8")
-    pc.case_merged_product(be, (logN, 3, 50, 2, 51, 2), seed=125, batch=2, levels=[3, 2])
+def test_emulated_merged_product_other_sizes(be, logN):
+    with be.tuned(8):
+        pc.case_merged_product(be, (logN, 3, 50, 2, 51, 2), seed=125, batch=2, levels=[3, 2])
 
 
 @pytest.mark.parametrize("shape,level", [(TINY, 3), (HYBRID, 4), (HYBRID3, 5)])
@@ -154,25 +125,20 @@ def test_emulated_hoisted_rotations_small_sizes(be, shape, level):
         pc.case_rotate_hoisted(be, shape, seed=127, rotations=(2, 5), level=5, small_ws=True)
 
 
-@pytest.mark.parametrize("env", [{}, {"CKKSMI_FUSE": "0"}, {"CKKSMI_FUSE": "14"}, {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_INV": "0"},
-                                 {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_HOIST_GATHER": "1"}])
-def test_emulated_hoisted_rotations_at_2e13(be, monkeypatch, env):
-    """register-tiled sizes: shared ModUp through the fused conversion kernels (or their alternatives), gathered inner product"""
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
+def test_emulated_hoisted_rotations_at_2e13(be):
+    """register-tiled sizes: shared ModUp through the fused conversion kernels, gathered inner product"""
     pc.case_rotate_hoisted(be, (13, 3, 50, 2, 51, 2), seed=128, rotations=(1, 100, 4095), batch=2, level=3)
-    if not env:
-        # more items than one workgroup stages (64 KiB of LDS: 32 digit rows), ragged last chunk; N = 256: a single run
-        pc.case_rotate_hoisted(be, (9, 9, 40, 1, 41, 1), seed=129, rotations=(1, 77), batch=5, level=9)
-        pc.case_rotate_hoisted(be, (8, 2, 40, 1, 41, 1), seed=130, rotations=(3,), batch=2, level=2)
+    # more items than one workgroup stages (64 KiB of LDS: 32 digit rows), ragged last chunk; N = 256: a single run
+    pc.case_rotate_hoisted(be, (9, 9, 40, 1, 41, 1), seed=129, rotations=(1, 77), batch=5, level=9)
+    pc.case_rotate_hoisted(be, (8, 2, 40, 1, 41, 1), seed=130, rotations=(3,), batch=2, level=2)
+    # more digits than the LDS-staged gather takes: the plain gather kernel; and a ring below 256 words
+    pc.case_rotate_hoisted(be, (8, 17, 40, 1, 41, 1), seed=138, rotations=(2,), batch=1, level=17)
 
 
-def test_emulated_sum_of_products(be, monkeypatch):
+def test_emulated_sum_of_products(be):
     """lazy relinearisation: the tensor kernels accumulate the terms (elementwise kernel, and the one fused with the row pass)"""
     pc.case_sum_of_products(be, HYBRID, seed=131, terms=3, levels=[5, 2])
     pc.case_sum_of_products(be, (13, 3, 50, 2, 51, 2), seed=132, terms=4, batch=2, levels=[3])
-    monkeypatch.setenv("CKKSMI_FUSE_TENSOR", "0")
-    pc.case_sum_of_products(be, (13, 3, 50, 2, 51, 2), seed=133, terms=2, batch=1, levels=[3])
 
 
 def test_emulated_rotation_packed_layers(be):
@@ -215,3 +181,31 @@ def test_emulated_misaligned_device_pointer_is_rejected(be):
     assert e.value.code == ckksmi.EINVAL
     ctx.close()
 
+
+
+FEW_PAIRS = (("qm1", "qm1"), ("half_lo", "half_hi"), ("alt", "qm1"), ("onehot", "alt_halves"))
+
+
+@pytest.mark.parametrize("shape", [TINY, HYBRID, HYBRID3, (5, 9, 51, 2, 51, 2)])
+def test_emulated_edge_values_generic_kernels(be, shape):
+    """all-0, all-(q-1), (q-1)/2, (q+1)/2, alternating and one-hot residues, seeded key and all-(q-1) key, through every
+    operation (generic kernels)"""
+    pc.case_edge_values(be, shape, seed=140)
+
+
+@pytest.mark.parametrize("shape,level", [((13, 24, 50, 3, 51, 3), 24), ((13, 15, 51, 3, 51, 3), 15)])
+def test_emulated_edge_values_register_tiled_kernels(be, shape, level):
+    """the same at a register-tiled size with 3-prime digits: 8 digits of 50-bit primes (eight terms meet in the fused inner
+    product's accumulators before their one reduction) and 5 digits of 51-bit primes (reduced every four terms)"""
+    pc.case_edge_values(be, shape, seed=142, level=level, conv=False, pairs=FEW_PAIRS)
+
+
+def test_emulated_edge_values_matrix_core_mac(be):
+    pc.case_edge_values(be, (7, 2, 51, 0, 52, 1), seed=143)
+    pc.case_edge_values(be, (7, 3, 50, 1, 51, 1), seed=144)
+
+
+def test_emulated_activation_schedule_register_tiled(be):
+    """x^2 then the degree-3 polynomial at N = 2^13 with 3-prime digits: the scalar rescale reads its input one level up and
+    adds onto the output buffer; workspace carved by the call sequence; every item compared"""
+    pc.case_activation(be, (13, 6, 50, 3, 51, 3), seed=145, level=6, batch=3, sample=[0, 1, 2])

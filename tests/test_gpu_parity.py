@@ -66,18 +66,6 @@ def test_relin_and_composite_levels_and_digits(be, shape, levels, batch):
     pc.case_relin_and_composite(be, shape, seed=303, batch=batch, levels=levels)
 
 
-@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "6"}, {"CKKSMI_NTT_TARGET_WGS": "64"},
-                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_TAIL": "0"}, {"CKKSMI_FUSE_TAIL": "1"}, {"CKKSMI_FUSE_TAIL": "2"}, {"CKKSMI_FUSE": "13"}, {"CKKSMI_MODUP_TARGETS": "2"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
-def test_alternative_kernel_paths_give_the_same_bits(be, monkeypatch, env):
-    """the unfused kernels, partial fusion and long per-workgroup item loops must all match the oracle too"""
-    announce("alternative paths %r" % (env,))
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
-    pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=310, batch=3, levels=[4, 2])
-    pc.case_relin_and_composite(be, (14, 3, 50, 2, 51, 2), seed=311, batch=5, levels=[3])
-    pc.case_rotate(be, (13, 3, 50, 1, 51, 1), seed=312, rotations=[5, 9], batch=3)
-
-
 def test_largest_ring_uses_generic_kernels(be):
     announce("N=2^17 generic path")
     pc.case_relin_and_composite(be, (17, 2, 50, 1, 51, 1), seed=313, batch=1, levels=[2])
@@ -202,14 +190,16 @@ def test_2e14_shape_hmul_and_rotations(be):
 
 def test_2e16_hybrid_shape_sampled(be):
     """N=2^16, 24x50-bit + 3 special primes (8 digits of 3): batch 64 in the benchmark's launch
-    configuration, one item compared word for word with the oracle at levels 24 and 23"""
+    configuration; the first, a middle and the last item compared word for word with the oracle at
+    levels 24, 23 and 22 (the levels the activation schedule multiplies at)"""
+    from concurrent.futures import ThreadPoolExecutor
     announce("N=2^16 hybrid batch 64, sampled parity")
     p = wl.PRESETS["act_2e16"]
     M = pc.make_material(C4, 4)
     ctx = be.context(*C4)
     batch = p.batch
     evk = be.to_dev(M.rlk)
-    for level, pick in ((24, 17), (23, 63)):
+    for level, picks in ((24, (0, 17, 63)), (23, (0, 31, 63)), (22, (0, 40, 63))):
         a = pc.random_cts(M, level, batch, 4, ("a", level))
         b = pc.random_cts(M, level, batch, 4, ("b", level))
         out = be.empty(batch, 2, level - 1, M.N)
@@ -220,10 +210,70 @@ def test_2e16_hybrid_shape_sampled(be):
         ran = ctx.profile_read()
         ctx.profile_enable(False)
         # the launch configuration bench.py times: ModDown and rescale as one conversion
-        assert "modup_cols_kernel<4, 4, 3, true>" in ran and "tensor_rows_kernel" in ran, list(ran)
-        announce("oracle for item %d at level %d" % (pick, level))
-        assert np.array_equal(got[pick], M.O.hmul_relin_rescale(a[pick], b[pick], M.rlk, level))
+        assert "modup_cols_kernel<4, 4, 3>" in ran and "tensor_rows_kernel" in ran, list(ran)
+        announce("oracle for items %r at level %d" % (picks, level))
+        with ThreadPoolExecutor(len(picks)) as ex:  # the oracle's C calls release the GIL
+            wants = list(ex.map(lambda i: M.O.hmul_relin_rescale(a[i], b[i], M.rlk, level), picks))
+        for i, want in zip(picks, wants):
+            assert np.array_equal(got[i], want), "item %d at level %d" % (i, level)
         del ws, out
+
+
+def test_2e16_rotation_sampled(be):
+    """ckksmi_rotate at N=2^16, 24 primes, 3-prime digits, batch 64 over two Galois keys: three items word for word"""
+    from concurrent.futures import ThreadPoolExecutor
+    announce("N=2^16 rotations batch 64, sampled parity")
+    rots = (1, 12345)
+    M = pc.make_material(C4, 6, rotations=rots)
+    ctx = be.context(*C4)
+    level, batch = 24, 64
+    keys = [be.to_dev(M.gk[r]) for r in rots]
+    for r, k in zip(rots, keys):
+        ctx.galois_key_register(r, k)
+    a = pc.random_cts(M, level, batch, 6, "rot16")
+    rot = [rots[(i * 7 // 3) % 2] for i in range(batch)]
+    out = be.empty(batch, 2, level, M.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_ROTATE, level, batch))
+    ctx.rotate(be.to_dev(a), rot, out, level, batch, ws)
+    got = be.to_host(out).reshape(batch, 2, level, M.N)
+    picks = (0, 29, 63)
+    assert len({rot[i] for i in picks}) == 2
+    announce("oracle for items %r" % (picks,))
+    with ThreadPoolExecutor(len(picks)) as ex:
+        wants = list(ex.map(lambda i: M.O.rotate(a[i], rot[i], M.gk[rot[i]], level), picks))
+    for i, want in zip(picks, wants):
+        assert np.array_equal(got[i], want), "rotation of item %d by %d" % (i, rot[i])
+    ctx.close()
+
+
+def test_item_loops_on_gpu(be):
+    """few workgroups per launch, so that every register-tiled kernel loops over several items"""
+    announce("item loops")
+    with be.tuned(64):
+        pc.case_relin_and_composite(be, (16, 4, 50, 3, 51, 3), seed=310, batch=3, levels=[4, 2])
+        pc.case_relin_and_composite(be, (14, 3, 50, 2, 51, 2), seed=311, batch=5, levels=[3])
+        pc.case_rotate(be, (13, 3, 50, 1, 51, 1), seed=312, rotations=[5, 9], batch=3)
+        pc.case_ntt(be, (15, 2, 50, 1, 51, 1), seed=313, batch=7)
+
+
+FEW_PAIRS = (("qm1", "qm1"), ("half_lo", "half_hi"), ("alt", "qm1"), ("onehot", "alt_halves"))
+
+
+@pytest.mark.parametrize("shape,level,kw", [
+    ((5, 5, 40, 2, 41, 2), 5, {}),
+    ((9, 9, 51, 2, 51, 2), 9, {}),
+    ((13, 24, 50, 3, 51, 3), 24, {"conv": False}),                        # 8 digits of 50-bit primes: eight terms per reduction
+    ((14, 15, 51, 3, 51, 3), 15, {"conv": False, "pairs": FEW_PAIRS}),    # 51-bit primes: reduced every four terms
+    ((15, 4, 50, 1, 51, 1), 4, {"pairs": FEW_PAIRS}),
+    ((16, 24, 50, 3, 51, 3), 24, {"conv": False, "pairs": FEW_PAIRS[:3], "seeded_key": False}),  # the benchmark's shape, all-(q-1) key
+    ((13, 2, 51, 0, 52, 1), 2, {}),                                       # matrix-core multiply-accumulate, 51-bit prime
+])
+def test_edge_values_match_oracle(be, shape, level, kw):
+    """residues at the ends and the middle of [0, q) (all 0, all q-1, (q-1)/2, (q+1)/2, alternating, one-hot), scalars and
+    weights at the ends of their ranges, and a switching key of all q-1, through the transforms, tensor, relinearisation,
+    the composite product, rescale, scalar rescale, rotation and the multiply-accumulate: every word against the oracle"""
+    announce("edge values %r" % (shape,))
+    pc.case_edge_values(be, shape, seed=370, level=level, **kw)
 
 
 @pytest.mark.parametrize("shape,levels,batch", [
@@ -240,16 +290,6 @@ def test_merged_product_matches_oracle(be, shape, levels, batch):
     """the product with one division by P*q_last (exact DivRound): every word against the oracle's definition"""
     announce("merged product %r levels %r" % (shape, levels))
     pc.case_merged_product(be, shape, seed=320, batch=batch, levels=levels)
-
-
-@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "7"}, {"CKKSMI_FUSE": "11"},
-                                 {"CKKSMI_MODUP_LOOP": "0"}, {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_FUSE_TENSOR": "0"}])
-def test_merged_product_alternative_paths(be, monkeypatch, env):
-    announce("merged product, alternative paths %r" % (env,))
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
-    pc.case_merged_product(be, (16, 4, 50, 3, 51, 3), seed=321, batch=3, levels=[4])
-    pc.case_merged_product(be, (10, 5, 40, 2, 41, 2), seed=322, batch=5, levels=[5], small_ws=True)
 
 
 def test_merged_product_full_size_sampled_and_decrypts(be):
@@ -273,7 +313,7 @@ def test_merged_product_full_size_sampled_and_decrypts(be):
     got = be.to_host(out).reshape(batch, 2, level - 1, M.N)
     ran = ctx.profile_read()
     ctx.profile_enable(False)
-    assert "modup_cols_kernel<4, 4, 2, true>" in ran, list(ran)
+    assert "modup_cols_kernel<4, 4, 2>" in ran, list(ran)
     announce("oracle for item %d" % pick)
     assert np.array_equal(got[pick], M.O.hmul_relin_rescale_merged(a[pick], b[pick], M.rlk, level))
     dec = M.decrypt(got[0], scale * scale / M.O.q[level - 1], level - 1)
@@ -292,16 +332,6 @@ def test_hoisted_rotations_match_oracle(be, shape, level, rotations, batch):
     """several rotations of each ciphertext from one shared ModUp: every word against the oracle's definition"""
     announce("hoisted rotations %r level %d offsets %r" % (shape, level, rotations))
     pc.case_rotate_hoisted(be, shape, seed=330, rotations=rotations, batch=batch, level=level)
-
-
-@pytest.mark.parametrize("env", [{"CKKSMI_FUSE": "0"}, {"CKKSMI_NO_FUSION": "1"}, {"CKKSMI_FUSE": "14"}, {"CKKSMI_MODUP_LOOP": "0"},
-                                 {"CKKSMI_FUSE_INV": "0"}, {"CKKSMI_HOIST_GATHER": "1"}])
-def test_hoisted_rotations_alternative_paths(be, monkeypatch, env):
-    announce("hoisted rotations, alternative paths %r" % (env,))
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
-    pc.case_rotate_hoisted(be, (14, 3, 50, 2, 51, 2), seed=331, rotations=(1, 6, 1000), batch=3, level=3)
-    pc.case_rotate_hoisted(be, (10, 5, 40, 2, 41, 2), seed=332, rotations=(2, 5), batch=4, level=5, small_ws=True)
 
 
 def test_hoisted_rotations_decrypt_to_rotated_slots(be):
@@ -488,35 +518,26 @@ def test_network_layer_shapes_sampled(be):
     ctx.close()
 
 
-def test_activation_schedule_on_gpu(be):
+@pytest.mark.parametrize("shape,level,batch,sample", [
+    ((10, 6, 50, 3, 51, 3), 6, 3, [0, 1, 2]),          # generic kernels
+    ((13, 6, 50, 3, 51, 3), 6, 5, [0, 1, 2, 3, 4]),    # register-tiled kernels, every item
+    ((14, 8, 51, 3, 51, 3), 7, 4, [0, 3]),             # 51-bit primes, input below the top level
+])
+def test_activation_schedule_on_gpu(be, shape, level, batch, sample):
     """x^2 then 0.5 + 0.25y - 0.02y^3 with relin + rescale at each level, against the oracle's
-    composition (bit-exact) and the float polynomial"""
-    announce("activation schedule")
-    from paper_1911_11377_amd import activation
+    composition (bit-exact, both the square and the result) and the float polynomial; the integer constants are
+    the test's own and must equal the call sequence's"""
+    announce("activation schedule %r" % (shape,))
+    pc.case_activation(be, shape, seed=5, level=level, batch=batch, sample=sample, workers=len(sample))
 
-    shape = (10, 6, 50, 3, 51, 3)
-    M = pc.make_material(shape, 5)
-    O = M.O
-    ctx = be.context(*shape)
-    level, s, batch = 6, 2.0**50, 3
-    zs = [wl.slots_real(O.N // 2, 5, i) for i in range(batch)]
-    x = _encrypt_batch(M, zs, s, level, "x")
-    consts = activation.poly3_constants(O.q, level - 1, s * s / O.q[level - 1])
-    dx, evk = be.to_dev(x), be.to_dev(M.rlk)
-    y = be.empty(batch, 2, level - 1, O.N)
-    out = be.empty(batch, 2, level - 3, O.N)
-    ws = be.ws(activation.workspace_bytes(ctx, level, batch))
-    activation.square(ctx, dx, evk, y, level, batch, ws)
-    activation.poly3(ctx, y, evk, out, level - 1, batch, consts, ws)
-    gy = be.to_host(y).reshape(batch, 2, level - 1, O.N)
-    go = be.to_host(out).reshape(batch, 2, level - 3, O.N)
-    for i in range(batch):
-        oy = O.square(x[i], M.rlk, level)
-        assert np.array_equal(gy[i], oy)
-        assert np.array_equal(go[i], O.poly3(oy, M.rlk, level - 1, consts.c_m002, consts.c_025, consts.c_05))
-        yv = zs[i].real ** 2
-        dec = ctx.decode(ctx.decrypt(M.s, go[i], level - 3), level - 3, consts.out_scale)
-        assert np.max(np.abs(dec.real - (0.5 + 0.25 * yv - 0.02 * yv**3))) < 1e-3
+
+def test_activation_schedule_full_size_sampled(be):
+    """the schedule at the benchmark's shape: N=2^16, 24 primes, level 24 -> 21, batch 64, workspace carved by the call
+    sequence; the first, a middle and the last item are real encryptions, compared word for word after x^2 and at the end,
+    and decrypt to the float polynomial within 1e-3"""
+    announce("activation schedule N=2^16 level 24 batch 64, sampled parity")
+    pc.case_activation(be, C4, seed=7, level=24, batch=64, sample=[0, 33, 63], workers=3,
+                       expect_kernels=("modup_cols_kernel<4, 4, 3>", "modup_cols_kernel<4, 1, 1>", "tensor_rows_kernel"))
 
 
 def test_edge_cases(be):

@@ -16,8 +16,13 @@ from helpers import Material
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def header_text():
+    inc = os.path.join(ROOT, "include")
+    return "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
+
+
 def header_symbols():
-    text = open(os.path.join(ROOT, "include", "ckksmi.h")).read()
+    text = header_text()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ckksmi_[a-z0-9_]+)\s*\(", text)))
 
@@ -33,7 +38,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_binding_constants_match_the_header():
     """kernel classes, sampler kinds and workspace operations: the binding's numbers are the header's, and every class has a name"""
-    text = open(os.path.join(ROOT, "include", "ckksmi.h")).read()
+    text = header_text()
     defines = {m.group(1): int(m.group(2)) for m in re.finditer(r"#define\s+(CKKSMI_[A-Z0-9_]+)\s+(-?\d+)\b", text)}
     assert defines["CKKSMI_K_COUNT"] == ckksmi.K_COUNT
     classes = sorted(v for k, v in defines.items() if k.startswith("CKKSMI_K_") and k != "CKKSMI_K_COUNT")
