@@ -157,6 +157,17 @@ int ckksmi_relin(ckksmi_ctx *ctx, const uint64_t *d, const uint64_t *evk, uint64
 /* divide by q_{level-1} with rounding to nearest: level -> level-1.  out may alias a
  * only when batch == 1 */
 int ckksmi_rescale(ckksmi_ctx *ctx, const uint64_t *a, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
+/* ckksmi_rescale for callers that cannot allocate or hold a workspace (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels and the same bits, with the intermediates (the dropped limb in
+ * coefficient form and the converted limbs, (2 + 2*(level-1)) * N words per ciphertext) in a static device array of
+ * CKKSMI_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.  The call allocates nothing
+ * (no device or host memory, no events: it records no profiling data) and enqueues on `stream` like every device call.
+ * a, out as ckksmi_rescale.  A batch whose intermediates exceed the array is swept in chunks; CKKSMI_EWORKSPACE if one
+ * ciphertext's intermediates alone exceed it (e.g. N = 2^16 above level 64, N = 2^17 above level 32);
+ * CKKSMI_EUNSUPPORTED on a device ordinal of 64 or more.  All calls on one GPU share the one array, whatever their context
+ * or stream: calls that overlap in time on the same GPU race on it (calls on one stream are ordered and safe). */
+#define CKKSMI_STATIC_SCRATCH_BYTES (64u << 20)
+int ckksmi_rescale_static(ckksmi_ctx *ctx, const uint64_t *a, uint64_t *out, int level, int batch, void *stream);
 /* Rescale(c * Drop(a -> level)) + addend, bit-identical to ckksmi_mod_drop, ckksmi_mul_scalar, ckksmi_rescale and
  * ckksmi_add in a row (the scalar steps of the polynomial activation schedules, section 2.2), without writing the
  * intermediate ciphertexts: the input is read at its own level level_in >= level (only its first `level` limbs are used),

@@ -69,6 +69,7 @@ SIGNATURES = {
     "ckksmi_hmul": [VP, VP, VP, VP, C.c_int, C.c_int, VP],
     "ckksmi_relin": [VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_rescale": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
+    "ckksmi_rescale_static": [VP, VP, VP, C.c_int, C.c_int, VP],
     "ckksmi_hmul_relin_rescale": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_mul_scalar_rescale": [VP, VP, C.c_int64, VP, VP, C.c_int, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_hmul_relin_rescale_merged": [VP, VP, VP, VP, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
@@ -317,6 +318,10 @@ class Context:
 
     def rescale(self, a, out, level, batch, ws, stream=None):
         self._call("ckksmi_rescale", self._h, _ptr(a), _ptr(out), level, batch, _ptr(ws), _nbytes(ws), self._stream(stream))
+
+    def rescale_static(self, a, out, level, batch, stream=None):
+        """ckksmi_rescale over the library's static scratch array: no workspace argument, allocates nothing"""
+        self._call("ckksmi_rescale_static", self._h, _ptr(a), _ptr(out), level, batch, self._stream(stream))
 
     def mul_scalar_rescale(self, a, c, out, level, batch, ws, stream=None, level_in=None, addend=None):
         """out = Rescale(c * a) at `level` (+ addend, which may be out); level_in > level: a is stored with level_in limbs and

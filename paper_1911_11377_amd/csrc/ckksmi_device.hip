@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "ckksmi_internal.h"
 #include "kernels.h"
@@ -26,7 +27,27 @@
         if (pr_) (void)hipEventRecord((hipEvent_t)pr_->stop, (st));                     \
     } while (0)
 
+// Scratch memory of ckksmi_rescale_static, the one entry point that takes no workspace: a file-scope device array, one copy
+// per GPU, held until the process ends.  Host code never uses the array's name as an address: every device's copy is
+// looked up once (hipGetSymbolAddress, with that device current) when the first context on that device is created.
+static __device__ __align__(256) unsigned long long scratch[CKKSMI_STATIC_SCRATCH_BYTES / 8];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, nullptr until looked up
+
+// with `device` current
+bool lookup_static_scratch(int device) {
+    if (device < 0 || device >= kMaxDevices) return true;  // no static scratch there: ckksmi_rescale_static reports it
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return true;
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return false;
+    g_scratch_ptr[device] = p;
+    return true;
+}
 
 ProfRec *prof_begin(ckksmi_ctx *c, int kid, double units, hipStream_t st) {
     hipEvent_t a, b;
@@ -597,6 +618,7 @@ int norm_rot(const ckksmi_ctx *c, int rot) {
 // ------------------------------------------------------------------ tables
 int dev_upload_tables(ckksmi_ctx *c) {
     if (hipSetDevice(c->device) != hipSuccess) return CKKSMI_EDEVICE;
+    if (!lookup_static_scratch(c->device)) { c->last_hip_error = (int)hipGetLastError(); return CKKSMI_EDEVICE; }
     bool ok = true;
     const size_t N = c->N;
     const int T = c->T;
@@ -963,6 +985,31 @@ extern "C" int ckksmi_rescale(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, i
         const int items = std::min(chunk, batch - b0);
         rescale_core(c, a + (size_t)b0 * 2 * level * N, out + (size_t)b0 * 2 * (level - 1) * N, items, level, (u64 *)ws, S(stream));
     }
+    return g.rc();
+}
+
+// The same sweeps as ckksmi_rescale over the GPU's static scratch array instead of a caller's workspace.  Nothing on this
+// path allocates: no hipMalloc / hipFree, no events (profiling records none here), no containers.
+extern "C" int ckksmi_rescale_static(ckksmi_ctx *c, const uint64_t *a, uint64_t *out, int level, int batch, void *stream) {
+    int rc = ct_args_ok(c, level, batch);
+    if (rc) return rc;
+    if (level < 2) return CKKSMI_ELEVEL;
+    if (!a || !out || a == out || !al16(a) || !al16(out)) return CKKSMI_EINVAL;
+    if (batch == 0) return CKKSMI_OK;
+    const size_t N = c->N, per = rescale_words_per_item(c, level);
+    // the static array must hold one item's intermediates; more items than fit are swept in chunks
+    if (per * 8 > (size_t)CKKSMI_STATIC_SCRATCH_BYTES) return CKKSMI_EWORKSPACE;
+    u64 *ws = c->device < kMaxDevices ? (u64 *)g_scratch_ptr[c->device] : nullptr;
+    if (!ws) return CKKSMI_EUNSUPPORTED;
+    const int chunk = sweep_items((size_t)CKKSMI_STATIC_SCRATCH_BYTES, per, batch);
+    const bool was_profiling = c->prof_on;
+    c->prof_on = false;  // timing events are allocations
+    Guard g(c);
+    for (int b0 = 0; b0 < batch; b0 += chunk) {
+        const int items = std::min(chunk, batch - b0);
+        rescale_core(c, a + (size_t)b0 * 2 * level * N, out + (size_t)b0 * 2 * (level - 1) * N, items, level, ws, S(stream));
+    }
+    c->prof_on = was_profiling;
     return g.rc();
 }
 

@@ -19,6 +19,8 @@
 #define __shared__ static
 #define __forceinline__ inline __attribute__((always_inline))
 #define __launch_bounds__(...)
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) x
 
 struct dim3 {
     unsigned x, y, z;
@@ -51,6 +53,8 @@ static inline hipError_t hipFree(void *p) { emu::guarded_free(p); return 0; }
 static inline hipError_t hipMemcpy(void *d, const void *s, size_t n, int) { memcpy(d, s, n); return 0; }
 static inline hipError_t hipMemcpyAsync(void *d, const void *s, size_t n, int, hipStream_t) { memcpy(d, s, n); return 0; }
 static inline hipError_t hipMemsetAsync(void *d, int v, size_t n, hipStream_t) { memset(d, v, n); return 0; }
+template <class Sym>
+static inline hipError_t hipGetSymbolAddress(void **p, Sym &symbol) { *p = (void *)&symbol; return 0; }
 static inline hipError_t hipSetDevice(int) { return 0; }
 static inline hipError_t hipGetDevice(int *d) { *d = 0; return 0; }
 static inline hipError_t hipGetLastError() { return 0; }
