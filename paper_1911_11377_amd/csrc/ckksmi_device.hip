@@ -323,6 +323,7 @@ void launch_hoisted_inner(ckksmi_ctx *c, const HoistPlan &H, const u64 *dt, cons
 // (evaluation form) and d0, d1 (the addend) join them multiplied by P before the division by P*q_{level-1}:
 //     out[items][2][level-1][N] = DivRound_B(acc + P*d),  B = {q_{level-1}, p_0 .. p_{k-1}},  exact form.
 // The limbs of B are contiguous in the extended layout (limbs level-1 .. E-1); they are overwritten.
+// addend == nullptr: acc already holds acc + P*d on the ciphertext limbs (the fused inner product's tensor mode).
 void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item_stride, size_t add_comp_stride, u64 *out, u64 *tmp, int items,
                      int level, hipStream_t st) {
     const size_t N = c->N;
@@ -330,6 +331,7 @@ void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item
     const DivRoundDev &D = c->divround_merged[level];
     u64 *bl = acc + (size_t)(level - 1) * N;
     // only the dropped limb q_{level-1} needs acc + P*d up front; the kept limbs receive P*d in the last step
+    if (addend)
     KL(c, CKKSMI_K_AXPY_LIMB, (double)rows, axpy_limb_kernel, dim3(ew_blocks(N / 2), rows), dim3(EW_THREADS), st, (u64d *)bl,
        (unsigned long long)((size_t)E * N), (const u64d *)(addend + (size_t)(level - 1) * N), (unsigned long long)add_item_stride,
        (unsigned long long)add_comp_stride, c->h_modc[level - 1], make_wmul(1, c->mod[level - 1]), c->h_pmod[level - 1], c->logN);
@@ -337,7 +339,8 @@ void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item
         const FinConst *fin = c->d_fin_merged + (size_t)level * CKKSMI_MAX_SPECIAL;
         launch_ntt(c, false, bl, bl, table_map(D.b_idx, D.nb, (size_t)E * N, (size_t)E * N), rows, st, fin, 2);
         launch_modup_cols(c, 2, bl, (size_t)E * N, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
-        launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, D.Binv, nc, rows, st, 0, -1, 0, c->d_pmod);
+        launch_rows_final(c, tmp, acc, (size_t)E * N, addend, add_item_stride, add_comp_stride, 1, out, D.Binv, nc, rows, st, 0, -1, 0,
+                          addend ? c->d_pmod : nullptr);
         return;
     }
     int idx[CKKSMI_MAX_MODULI];
@@ -362,10 +365,13 @@ inline bool one_conversion_tail_ok(const ckksmi_ctx *c) { return c->fused && c->
 // Key switch on the register-tiled kernels (2^13 <= N <= 2^16).
 // tail: the key switch is followed by a rescale of (result + addend), both components have an addend, and `out` receives
 // the rescaled ciphertexts [items][2][level-1][N] (needs one_conversion_tail_ok).
-// ymid_ready: the tensor kernel already left the inverse row pass of d_eval at the start of the workspace.
+// ta != nullptr (the composite multiply; d_eval and addend unused): the polynomial switched is the third tensor component
+// of the operands ta, tb ([items][terms][2][level][N]), whose inverse row pass the tensor kernel already left at the start of
+// the workspace, and the other two components are the addends; the fused inner product forms all three from the operands.
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
-                   bool tail = false, bool ymid_ready = false, bool merged = false, const HoistPlan *hoist = nullptr) {
+                   bool tail = false, bool merged = false, const HoistPlan *hoist = nullptr, const u64 *ta = nullptr, const u64 *tb = nullptr,
+                   int terms = 1) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     const int R = hoist ? hoist->R : 1;  // hoisted rotations: R accumulator pairs per item
@@ -378,7 +384,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     // y_i = d_i * qhat_i^-1 comes straight out of the inverse transform (row pass here, column pass inside the conversion
     // kernel); the conversion rides on the column pass of the forward transform of its results
     const FinConst *fin_up = c->d_fin_modup + (size_t)level * c->n_q;
-    if (!ymid_ready) launch_ntt(c, false, d_eval, ymid, table_map(idx, level, d_stride, (size_t)level * N), items, st, fin_up, 2);
+    if (!ta) launch_ntt(c, false, d_eval, ymid, table_map(idx, level, d_stride, (size_t)level * N), items, st, fin_up, 2);
     launch_modup_cols(c, 0, ymid, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st, fin_up);
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
@@ -404,12 +410,13 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     RI.p51 = c->p51mask;
     // the ciphertext limbs leave the inner product as z = x * P^-1 + addend, which is what ModDown's last pass (and the
     // one-conversion tail) read; the merged division wants the accumulators themselves
-    RI.fold_tail = (merged || !addend) ? 0 : (add_both ? 1 : 2);
+    RI.fold_tail = (merged || !addend || ta) ? 0 : (add_both ? 1 : 2);
     RI.Pinv = c->divround[0].Binv;
     RI.addend = (const u64d *)addend; RI.add_item_stride = add_item_stride; RI.add_comp_stride = add_comp_stride;
+    RI.ta = (const u64d *)ta; RI.tb = (const u64d *)tb; RI.terms = terms; RI.keep_acc = merged ? 1 : 0; RI.Pmod = c->d_pmod;
     KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
     if (merged) {
-        merged_division(c, acc, addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
+        merged_division(c, acc, ta ? nullptr : addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
         return;
     }
     const int rows = items * 2;
@@ -432,7 +439,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     }
     // plain ModDown; with an addend the kept limbs already hold x * P^-1 + addend
     divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, specials, (size_t)E * N, specials, (size_t)E * N, acc, (size_t)E * N, tmp, level, rows,
-                  nullptr, 0, 0, 0, out, st, addend != nullptr);
+                  nullptr, 0, 0, 0, out, st, addend != nullptr || ta != nullptr);
 }
 
 void rescale_core_fused(ckksmi_ctx *c, const u64 *a, u64 *out, int items, int level, u64 *ws, hipStream_t st) {
@@ -474,8 +481,7 @@ void ks_core(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K,
              size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st, bool merged = false,
              const HoistPlan *hoist = nullptr) {
     if (c->fused) {
-        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st, false, false,
-                      merged, hoist);
+        ks_core_fused(c, d_eval, d_stride, K, items, level, addend, add_item_stride, add_comp_stride, add_both, out, ws, st, false, merged, hoist);
         return;
     }
     // other ring sizes: the generic kernels, one step after the other
@@ -587,11 +593,11 @@ void launch_tensor(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, int level,
                   c->logN, level, total, terms);
 }
 
-// tensor product + inverse row pass of d2 into ymid (see tensor_rows_kernel); register-tiled sizes only
-void launch_tensor_rows(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *d, u64 *ymid, int level, int items, hipStream_t st, int terms = 1) {
+// third tensor component + its inverse row pass into ymid (see tensor_rows_kernel); register-tiled sizes only
+void launch_tensor_rows(ckksmi_ctx *c, const u64 *a, const u64 *b, u64 *ymid, int level, int items, hipStream_t st, int terms = 1) {
     TensorRowsArgs A;
     A.terms = terms;
-    A.a = (const u64d *)a; A.b = (const u64d *)b; A.d = (u64d *)d; A.ymid = (u64d *)ymid; A.modc = c->d_mod; A.tw_inv = c->d_tww_inv;
+    A.a = (const u64d *)a; A.b = (const u64d *)b; A.ymid = (u64d *)ymid; A.modc = c->d_mod; A.tw_inv = c->d_tww_inv;
     A.logN = c->logN; A.level = level; A.p51 = c->p51mask;
     KL(c, CKKSMI_K_TENSOR_ROWS, (double)items * level, tensor_rows_kernel, dim3((unsigned)(c->N / 4096), level, items), dim3(V2_THREADS), st, A);
 }
@@ -694,12 +700,14 @@ int dev_upload_tables(ckksmi_ctx *c) {
     c->divround_merged.assign(1 + c->n_q, DivRoundDev());
     c->h_pmod.assign(T, WMul{0.0, 0.0});
     c->h_Pinv.assign(T, WMul{0.0, 0.0});
-    if (c->k > 0 && c->k + 1 <= CKKSMI_MAX_SPECIAL) {
+    c->merged_ok = c->k > 0 && c->k + 1 <= CKKSMI_MAX_SPECIAL;
+    if (c->merged_ok)
         for (int level = 2; level <= c->n_q; level++) {
             std::vector<int> b(1, level - 1);
             for (int m = 0; m < c->k; m++) b.push_back(c->n_q + m);
             c->divround_merged[level] = upload_divround(b);
         }
+    if (c->k > 0) {
         for (int i = 0; i < c->n_q; i++) {
             u64 P = 1;
             for (int m = 0; m < c->k; m++) P = hm::mulmod(P, c->mod[c->n_q + m] % c->mod[i], c->mod[i]);
@@ -754,7 +762,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
             }
             c->d_fin_tail = upload(c, ft.data(), ft.size(), ok);
         }
-        if (c->d_pmod) {
+        if (c->merged_ok) {
             std::vector<FinConst> fg((size_t)(c->n_q + 1) * CKKSMI_MAX_SPECIAL, fin(0, 1, 0));
             for (int level = 2; level <= c->n_q; level++) {
                 const DivRoundDev &D = c->divround_merged[level];
@@ -1064,7 +1072,7 @@ static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint6
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;
     if (terms < 1) return CKKSMI_EINVAL;
-    if (c->k == 0 || (merged && !c->d_pmod)) return CKKSMI_EUNSUPPORTED;
+    if (c->k == 0 || (merged && !c->merged_ok)) return CKKSMI_EUNSUPPORTED;
     if (level < 2) return CKKSMI_ELEVEL;
     if (!a || !b || !evk || !out || (!ws && batch) || !al16(a) || !al16(b) || !al16(evk) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (batch == 0) return CKKSMI_OK;
@@ -1097,14 +1105,14 @@ static int hmul_relin_rescale_impl(ckksmi_ctx *c, const uint64_t *a, const uint6
             }
             continue;
         }
-        launch_tensor_rows(c, a + in0, b + in0, d, rest, level, items, S(stream), terms);
+        // the tensor is never written: its third component goes through the inverse row pass on the way, the inner product forms
+        // what it needs of all three from the operands
+        launch_tensor_rows(c, a + in0, b + in0, rest, level, items, S(stream), terms);
         if (merged || one_conversion_tail_ok(c)) {
             // one division by P*q_{level-1} of (accumulators + P*(d0, d1)), or ModDown + add + rescale as one conversion
-            ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, o,
-                          rest, S(stream), !merged, true, merged);
+            ks_core_fused(c, nullptr, 0, K, items, level, nullptr, 0, 0, 1, o, rest, S(stream), !merged, merged, nullptr, a + in0, b + in0, terms);
         } else {
-            ks_core_fused(c, d + (size_t)2 * level * N, (size_t)3 * level * N, K, items, level, d, (size_t)3 * level * N, (size_t)level * N, 1, r,
-                          rest, S(stream), false, true);
+            ks_core_fused(c, nullptr, 0, K, items, level, nullptr, 0, 0, 1, r, rest, S(stream), false, false, nullptr, a + in0, b + in0, terms);
             rescale_core(c, r, o, items, level, rest, S(stream));
         }
     }

@@ -117,7 +117,8 @@ struct ckksmi_ctx {
     std::vector<DivRoundDev> divround_merged;  // [n_q + 1] by level; nb == 0 where unavailable
     std::vector<WMul> h_pmod;           // [T] P mod q_i (zero for the special primes)
     std::vector<WMul> h_Pinv;           // [T] P^-1 mod q_i
-    WMul *d_pmod = nullptr;             // device copy; nullptr: merged division unavailable (k = 0 or k + 1 > CKKSMI_MAX_SPECIAL)
+    WMul *d_pmod = nullptr;             // device copy (k > 0)
+    bool merged_ok = false;             // merged division available: k > 0 and k + 1 <= CKKSMI_MAX_SPECIAL
     P51Mask p51mask = {{0, 0}};
     bool fused = false;  // 2^13 <= N <= 2^16: register-tiled passes with the limb-wise steps fused into them
 

@@ -25,19 +25,19 @@
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #endif
 
-// ------------------------------------------------------------------ tensor + inverse row pass of its third component
+// ------------------------------------------------------------------ third tensor component + its inverse row pass
 // The composite multiply feeds d2 = a1*b1 straight into key switching, whose first step is the inverse transform of
-// d2.  This kernel computes the tensor product of one 4096-word tile (all three components, written in evaluation form
-// as the plain tensor kernel does) and takes d2 through the inverse ROW pass while it is still on chip; the column
-// pass follows in the ModUp kernel.  Saves one read of d2 and a launch.
+// d2.  This kernel forms d2 of one 4096-word tile (summed over the terms of a sum of products) and takes it through the
+// inverse ROW pass while it is on chip; the column pass follows in the ModUp kernel.  Nothing else of the tensor is
+// written anywhere: the fused inner product forms d0, d1 and d2 again from the operands where it needs them
+// (rows_inner_kernel, tensor mode), which costs it one more limb read and saves this kernel six limb transfers.
 struct TensorRowsArgs {
-    const u64d *a, *b;   // [items][2][level][N]
-    u64d *d;             // [items][3][level][N]
+    const u64d *a, *b;   // [items][terms][2][level][N]
     u64d *ymid;          // [items][level][N]: inverse row pass of d2 (reduced doubles)
     const ModConst *modc;
     const double *tw_inv;
     int logN, level;
-    int terms;           // > 1: a, b hold [items][terms][2][level][N] and d is the sum of the terms' tensors
+    int terms;
     P51Mask p51;
 };
 
@@ -51,55 +51,47 @@ __device__ __forceinline__ void tensor_rows_body(const TensorRowsArgs &A, double
     const size_t tile0 = (size_t)blockIdx.x * 4096, st = (size_t)A.level * N;
     double tw1[15], tw2[15];
     load_twiddles(A.tw_inv + (size_t)i * N, N1 + blockIdx.x * 16 + hi4, lo4, tw1, tw2);
-    const ulonglong2 *a0 = (const ulonglong2 *)(A.a + ((size_t)item * A.terms * 2 * A.level + i) * N + tile0), *a1 = a0 + st / 2;
-    const ulonglong2 *b0 = (const ulonglong2 *)(A.b + ((size_t)item * A.terms * 2 * A.level + i) * N + tile0), *b1 = b0 + st / 2;
-    ulonglong2 *d0 = (ulonglong2 *)(A.d + ((size_t)item * 3 * A.level + i) * N + tile0), *d1 = d0 + st / 2, *d2 = d1 + st / 2;
-    // word pairs (512*s + 2*tid, +1), four at a time to bound the registers in flight
+    // second components of the operands
+    const ulonglong2 *a1 = (const ulonglong2 *)(A.a + ((size_t)item * A.terms * 2 * A.level + A.level + i) * N + tile0);
+    const ulonglong2 *b1 = (const ulonglong2 *)(A.b + ((size_t)item * A.terms * 2 * A.level + A.level + i) * N + tile0);
+    double *grp = lds + hi4 * V2_GS;
+    // word pairs in the row-pair layout (every row stays with its 16 lanes: no workgroup barrier)
+    ulonglong2 A1[8], B1[8];
 #pragma unroll
-    for (int h = 0; h < 2; h++) {
-        ulonglong2 A0[4], A1[4], B0[4], B1[4];
+    for (int s = 0; s < 8; s++) {
+        A1[s] = a1[row_pair_index(hi4, lo4, s)];
+        B1[s] = b1[row_pair_index(hi4, lo4, s)];
+    }
+    SCHED_FENCE();
+    double d2[16];
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-            const unsigned e = 256u * (4 * h + s) + tid;
-            A0[s] = a0[e]; A1[s] = a1[e]; B0[s] = b0[e]; B1[s] = b1[e];
+    for (int s = 0; s < 8; s++) {
+        d2[2 * s] = mulmod(u2d(A1[s].x), u2d(B1[s].x), p, pinv);
+        d2[2 * s + 1] = mulmod(u2d(A1[s].y), u2d(B1[s].y), p, pinv);
+    }
+    for (int t = 1; t < A.terms; t++) {  // further terms of a sum of products
+        const size_t to = (size_t)t * st;  // 2*level*N words = st pairs
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            A1[s] = a1[to + row_pair_index(hi4, lo4, s)];
+            B1[s] = b1[to + row_pair_index(hi4, lo4, s)];
         }
         SCHED_FENCE();
-        ulonglong2 D0[4], D1[4], D2[4];
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-            tensor_word(u2d(A0[s].x), u2d(A1[s].x), u2d(B0[s].x), u2d(B1[s].x), mc, D0[s].x, D1[s].x, D2[s].x);
-            tensor_word(u2d(A0[s].y), u2d(A1[s].y), u2d(B0[s].y), u2d(B1[s].y), mc, D0[s].y, D1[s].y, D2[s].y);
-        }
-        for (int t = 1; t < A.terms; t++) {  // further terms of a sum of products
-            const size_t to = (size_t)t * st;  // 2*level*N words = st ulonglong2
-#pragma unroll
-            for (int s = 0; s < 4; s++) {
-                const unsigned e = 256u * (4 * h + s) + tid;
-                A0[s] = a0[to + e]; A1[s] = a1[to + e]; B0[s] = b0[to + e]; B1[s] = b1[to + e];
-            }
-            SCHED_FENCE();
-#pragma unroll
-            for (int s = 0; s < 4; s++) {
-                ulonglong2 T0, T1, T2;
-                tensor_word(u2d(A0[s].x), u2d(A1[s].x), u2d(B0[s].x), u2d(B1[s].x), mc, T0.x, T1.x, T2.x);
-                tensor_word(u2d(A0[s].y), u2d(A1[s].y), u2d(B0[s].y), u2d(B1[s].y), mc, T0.y, T1.y, T2.y);
-                tensor_accumulate(D0[s].x, T0.x, p); tensor_accumulate(D0[s].y, T0.y, p);
-                tensor_accumulate(D1[s].x, T1.x, p); tensor_accumulate(D1[s].y, T1.y, p);
-                tensor_accumulate(D2[s].x, T2.x, p); tensor_accumulate(D2[s].y, T2.y, p);
-            }
-        }
-#pragma unroll
-        for (int s = 0; s < 4; s++) {
-            const unsigned e = 256u * (4 * h + s) + tid;
-            d0[e] = D0[s]; d1[e] = D1[s]; d2[e] = D2[s];
-            double *rr = lds + (2 * (4 * h + s) + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
-            rr[0] = u2d(D2[s].x);
-            rr[1] = u2d(D2[s].y);
+        for (int s = 0; s < 8; s++) {  // |sum| <= p/2 + 1 + 1.25p
+            d2[2 * s] = reduce_balanced(d2[2 * s] + mulmod(u2d(A1[s].x), u2d(B1[s].x), p, pinv), p, pinv);
+            d2[2 * s + 1] = reduce_balanced(d2[2 * s + 1] + mulmod(u2d(A1[s].y), u2d(B1[s].y), p, pinv), p, pinv);
         }
     }
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 8; s++) {
+        // the inverse row pass starts from the canonical representative, as it does when d2 comes from memory
+        double *rr = grp + row_pair_lds(lo4, s);
+        rr[0] = canon(d2[2 * s], p, pinv);
+        rr[1] = canon(d2[2 * s + 1], p, pinv);
+    }
+    ROW_GROUP_SYNC();
     // inverse row pass of d2 exactly as in ntt_v2_rows
-    double *grp = lds + hi4 * V2_GS;
     const WMul unused = WMul{0.0, 0.0};
     double x[16];
 #pragma unroll
@@ -107,7 +99,7 @@ __device__ __forceinline__ void tensor_rows_body(const TensorRowsArgs &A, double
     inv_round<I1, false>(x, tw2, p, pinv, unused, unused);
 #pragma unroll
     for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = x[e];
-    __syncthreads();
+    ROW_GROUP_SYNC();
 #pragma unroll
     for (int e = 0; e < 16; e++) x[e] = grp[e * 17 + lo4];
     inv_round<I2, false>(x, tw1, p, pinv, unused, unused);
@@ -432,7 +424,7 @@ __device__ __forceinline__ void load_row_twiddles(const double *tw, unsigned N1,
 
 // Finish the forward transform of one 16-row tile (column pass already done) and leave the
 // balanced-reduced results in LDS in the padded layout: word (row g, position q) at g*V2_GS + (q/16)*17 + q%16.
-// Ends with a barrier; the caller must put a barrier before the next call.
+// Every row is handled by its own 16 lanes: ends with a row-group sync, and the caller puts one before the next call.
 template <bool P51>
 __device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, const double *tw1_lds, const double (&tw2)[15], double p,
                                                 double pinv, unsigned hi4, unsigned lo4) {
@@ -450,13 +442,13 @@ __device__ __forceinline__ void rows_fwd_to_lds(const u64d *tile, double *lds, c
     }
 #pragma unroll
     for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = x[e];
-    __syncthreads();
+    ROW_GROUP_SYNC();
 #pragma unroll
     for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
     fwd_round<F2>(x, tw2, p, pinv);
 #pragma unroll
     for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = reduce_balanced(x[e], p, pinv);
-    __syncthreads();
+    ROW_GROUP_SYNC();
 }
 
 // ------------------------------------------------------------------ row pass + inner product
@@ -477,6 +469,13 @@ struct RowsInnerArgs {
     const WMul *Pinv;    // [T] P^-1 mod q_i
     const u64d *addend;  // item i, component c, limb l at addend + i*add_item_stride + c*add_comp_stride + l*N
     unsigned long long add_item_stride, add_comp_stride;
+    // Tensor mode (ta != nullptr; the composite multiply): the source polynomial is d2 = sum_t a1_t*b1_t of the operands
+    // ta, tb: [items][terms][2][level][N], formed here for the limb's own digit, and the accumulators of the ciphertext limbs
+    // start at P*d0 and P*d1 (d0 = sum a0*b0, d1 = sum a0*b1 + a1*b0), so that they leave as
+    // z = (acc + P*d) * P^-1 = acc * P^-1 + d, or as acc + P*d itself (keep_acc: what the merged division divides).
+    const u64d *ta, *tb;
+    int terms, keep_acc;
+    const WMul *Pmod;    // [T] P mod q_i
 };
 
 template <bool P51>
@@ -505,21 +504,76 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     double a0[16], a1[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) a0[i] = a1[i] = 0.0;
-    // Multiply-accumulate layout: a thread owns the word PAIRS (512*s + 2*tid, +1), s < 8, of the tile, so that key
-    // words, the own digit's words and the results move 16 bytes per lane (the load path handles 16 bytes per lane at the
-    // cost of 8); accumulator 2*s + b belongs to word 512*s + 2*tid + b = row 2*s + tid/128, column 2*(tid%128) + b.
+    // Multiply-accumulate layout (row_pair_index): a thread owns 8 word pairs of the row its 16 lanes transform, so that key
+    // words, the own digit's words and the results move 16 bytes per lane and the whole digit loop needs no workgroup barrier;
+    // accumulator 2*s + b belongs to the word at column 32*s + 2*lo4 + b of row hi4.
     // The digit that contains this limb needs no transform: its operand is the source polynomial itself.
     const int j_own = (int)x < A.level ? (int)x / A.alpha : -1;
-    if (j_own >= 0) {
+    const bool tensor_mode = A.ta != nullptr && j_own >= 0;
+    int pending = 1;  // terms in the accumulators since their last reduction (the own digit's term counts)
+    if (tensor_mode) {
+        // d0, d1, d2 of the thread's 16 words from the operands (summed over the terms, balanced-reduced)
+        const size_t st = (size_t)A.level * N / 2;  // pairs between the two components of a ciphertext
+        const ulonglong2 *pa = (const ulonglong2 *)(A.ta + ((size_t)item * A.terms * 2 * A.level + x) * N + tile0);
+        const ulonglong2 *pb = (const ulonglong2 *)(A.tb + ((size_t)item * A.terms * 2 * A.level + x) * N + tile0);
+        const ulonglong2 *k0 = (const ulonglong2 *)(key + (((size_t)j_own * 2 + 0) * A.T + t) * N + tile0);
+        const ulonglong2 *k1 = (const ulonglong2 *)(key + (((size_t)j_own * 2 + 1) * A.T + t) * N + tile0);
+        const WMul Pm = A.Pmod[t];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {  // four pairs at a time: bounds the registers in flight
+            // the own digit's key words travel with the first term's operands
+            ulonglong2 kr0[4], kr1[4];
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                kr0[s] = k0[row_pair_index(hi4, lo4, 4 * h + s)];
+                kr1[s] = k1[row_pair_index(hi4, lo4, 4 * h + s)];
+            }
+            double l0[8], l1[8], l2[8];
+            for (int tm = 0; tm < A.terms; tm++) {
+                const size_t to = (size_t)tm * 2 * st;
+                ulonglong2 A0[4], A1[4], B0[4], B1[4];
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const unsigned e = row_pair_index(hi4, lo4, 4 * h + s);
+                    A0[s] = pa[to + e]; A1[s] = pa[to + st + e]; B0[s] = pb[to + e]; B1[s] = pb[to + st + e];
+                }
+                SCHED_FENCE();
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+#pragma unroll
+                    for (int b = 0; b < 2; b++) {
+                        const int i = 2 * s + b;
+                        const double x0 = u2d(b ? A0[s].y : A0[s].x), x1 = u2d(b ? A1[s].y : A1[s].x);
+                        const double y0 = u2d(b ? B0[s].y : B0[s].x), y1 = u2d(b ? B1[s].y : B1[s].x);
+                        const double t0 = mulmod(x0, y0, p, pinv), t1 = mulmod(x0, y1, p, pinv) + mulmod(x1, y0, p, pinv), t2 = mulmod(x1, y1, p, pinv);
+                        // |t| <= 2.5p on top of a reduced sum: below 2^53
+                        l0[i] = reduce_balanced((tm ? l0[i] : 0.0) + t0, p, pinv);
+                        l1[i] = reduce_balanced((tm ? l1[i] : 0.0) + t1, p, pinv);
+                        l2[i] = reduce_balanced((tm ? l2[i] : 0.0) + t2, p, pinv);
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const double v0 = l2[2 * s], vp0 = v0 * pinv, v1 = l2[2 * s + 1], vp1 = v1 * pinv;
+                // two terms below 0.875p each: the own digit's product and P*d
+                a0[8 * h + 2 * s] = mulmod_w(u2d(kr0[s].x), v0, vp0, p) + mulmod_w(l0[2 * s], Pm.w, Pm.wp, p);
+                a1[8 * h + 2 * s] = mulmod_w(u2d(kr1[s].x), v0, vp0, p) + mulmod_w(l1[2 * s], Pm.w, Pm.wp, p);
+                a0[8 * h + 2 * s + 1] = mulmod_w(u2d(kr0[s].y), v1, vp1, p) + mulmod_w(l0[2 * s + 1], Pm.w, Pm.wp, p);
+                a1[8 * h + 2 * s + 1] = mulmod_w(u2d(kr1[s].y), v1, vp1, p) + mulmod_w(l1[2 * s + 1], Pm.w, Pm.wp, p);
+            }
+        }
+        pending = 2;
+    } else if (j_own >= 0) {
         const u64d *k0 = key + (((size_t)j_own * 2 + 0) * A.T + t) * N + tile0;
         const u64d *k1 = key + (((size_t)j_own * 2 + 1) * A.T + t) * N + tile0;
         const u64d *src = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0;
         ulonglong2 kr0[8], kr1[8], xo[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            xo[s] = ((const ulonglong2 *)src)[256 * s + tid];
-            kr0[s] = ((const ulonglong2 *)k0)[256 * s + tid];
-            kr1[s] = ((const ulonglong2 *)k1)[256 * s + tid];
+            xo[s] = ((const ulonglong2 *)src)[row_pair_index(hi4, lo4, s)];
+            kr0[s] = ((const ulonglong2 *)k0)[row_pair_index(hi4, lo4, s)];
+            kr1[s] = ((const ulonglong2 *)k1)[row_pair_index(hi4, lo4, s)];
         }
         SCHED_FENCE();
 #pragma unroll
@@ -536,7 +590,6 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     // digit are requested while the previous digit is multiplied, its key words while the limb goes through the row
     // pass.  xr holds the column-pass output of the converted limb in the register layout of the row pass.
     int j = (j_own == 0) ? 1 : 0;
-    int pending = 1;  // terms in the accumulators since their last reduction (the own digit's term counts)
     u64d xr[16];
     if (j < A.beta) {
         const u64d *src = A.dtA + (((size_t)item * A.beta + j) * A.E + x) * N + tile0;
@@ -549,8 +602,8 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         ulonglong2 kr0[8], kr1[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            kr0[s] = ((const ulonglong2 *)k0)[256 * s + tid];
-            kr1[s] = ((const ulonglong2 *)k1)[256 * s + tid];
+            kr0[s] = ((const ulonglong2 *)k0)[row_pair_index(hi4, lo4, s)];
+            kr1[s] = ((const ulonglong2 *)k1)[row_pair_index(hi4, lo4, s)];
         }
         SCHED_FENCE();
         {
@@ -565,7 +618,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
             }
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = xx[e];
-            __syncthreads();
+            ROW_GROUP_SYNC();
 #pragma unroll
             for (int e = 0; e < 16; e++) xx[e] = grp[lo4 * 17 + e];
             {
@@ -577,7 +630,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = reduce_balanced(xx[e], p, pinv);
         }
-        __syncthreads();
+        ROW_GROUP_SYNC();
         int jn = j + 1;
         if (jn == j_own) jn++;
         if (jn < A.beta) {
@@ -590,7 +643,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         for (int s = 0; s < 8; s++) {
             // the transformed word is the prepared factor (|v| <= p/2 + 1, v/p computed once for both components), the
             // key word the other one: each term is below 0.875p and the sum is reduced only when it could pass 2^53
-            const double *vrow = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            const double *vrow = grp + row_pair_lds(lo4, s);
             const double v0 = vrow[0], vp0 = v0 * pinv, v1 = vrow[1], vp1 = v1 * pinv;
             a0[2 * s] += mulmod_w(u2d(kr0[s].x), v0, vp0, p);
             a1[2 * s] += mulmod_w(u2d(kr1[s].x), v0, vp0, p);
@@ -605,12 +658,24 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
             }
             pending = 0;
         }
-        __syncthreads();
+        ROW_GROUP_SYNC();  // the row's lanes have read its words before the next digit overwrites them
         j = jn;
     }
     u64d *o0 = A.acc + (((size_t)item * 2 + 0) * A.E + x) * N + tile0;
     u64d *o1 = A.acc + (((size_t)item * 2 + 1) * A.E + x) * N + tile0;
-    if (A.fold_tail && (int)x < A.level) {
+    if (tensor_mode && !A.keep_acc) {
+        // z = (acc + P*d) * P^-1; accumulators are below 2^53: the prepared product is exact for them as they are
+        const WMul Pi = A.Pinv[t];
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const double z00 = mulmod_w(a0[2 * s], Pi.w, Pi.wp, p), z01 = mulmod_w(a0[2 * s + 1], Pi.w, Pi.wp, p);
+            const double z10 = mulmod_w(a1[2 * s], Pi.w, Pi.wp, p), z11 = mulmod_w(a1[2 * s + 1], Pi.w, Pi.wp, p);
+            ((ulonglong2 *)o0)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(z00, p, pinv)), d2u(canon(z01, p, pinv)));
+            ((ulonglong2 *)o1)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(z10, p, pinv)), d2u(canon(z11, p, pinv)));
+        }
+        return;
+    }
+    if (!tensor_mode && A.fold_tail && (int)x < A.level) {
         const WMul Pi = A.Pinv[t];
         const u64d *d0 = A.addend + (size_t)item * A.add_item_stride + (size_t)x * N + tile0;
         const bool both = A.fold_tail == 1;  // 2: only the first component has an addend (rotation)
@@ -619,23 +684,23 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
         ulonglong2 dw0[8], dw1[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            dw0[s] = ((const ulonglong2 *)d0)[256 * s + tid];
-            dw1[s] = ((const ulonglong2 *)d1)[256 * s + tid];
+            dw0[s] = ((const ulonglong2 *)d0)[row_pair_index(hi4, lo4, s)];
+            dw1[s] = ((const ulonglong2 *)d1)[row_pair_index(hi4, lo4, s)];
         }
 #pragma unroll
         for (int s = 0; s < 8; s++) {
             // accumulators are below 2^53: the prepared product is exact for them as they are
             const double z00 = mulmod_w(a0[2 * s], Pi.w, Pi.wp, p) + u2d(dw0[s].x), z01 = mulmod_w(a0[2 * s + 1], Pi.w, Pi.wp, p) + u2d(dw0[s].y);
             const double z10 = mulmod_w(a1[2 * s], Pi.w, Pi.wp, p) + has1 * u2d(dw1[s].x), z11 = mulmod_w(a1[2 * s + 1], Pi.w, Pi.wp, p) + has1 * u2d(dw1[s].y);
-            ((ulonglong2 *)o0)[256 * s + tid] = make_ulonglong2(d2u(canon(z00, p, pinv)), d2u(canon(z01, p, pinv)));
-            ((ulonglong2 *)o1)[256 * s + tid] = make_ulonglong2(d2u(canon(z10, p, pinv)), d2u(canon(z11, p, pinv)));
+            ((ulonglong2 *)o0)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(z00, p, pinv)), d2u(canon(z01, p, pinv)));
+            ((ulonglong2 *)o1)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(z10, p, pinv)), d2u(canon(z11, p, pinv)));
         }
         return;
     }
 #pragma unroll
     for (int s = 0; s < 8; s++) {
-        ((ulonglong2 *)o0)[256 * s + tid] = make_ulonglong2(d2u(canon(a0[2 * s], p, pinv)), d2u(canon(a0[2 * s + 1], p, pinv)));
-        ((ulonglong2 *)o1)[256 * s + tid] = make_ulonglong2(d2u(canon(a1[2 * s], p, pinv)), d2u(canon(a1[2 * s + 1], p, pinv)));
+        ((ulonglong2 *)o0)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(a0[2 * s], p, pinv)), d2u(canon(a0[2 * s + 1], p, pinv)));
+        ((ulonglong2 *)o1)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(a1[2 * s], p, pinv)), d2u(canon(a1[2 * s + 1], p, pinv)));
     }
 }
 
@@ -697,18 +762,18 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
         const double has_add = add ? 1.0 : 0.0;
         const u64d *ad = add ? A.addend + (size_t)(row / 2) * A.add_item_stride + (size_t)(row % 2) * A.add_comp_stride + (size_t)i * N + tile0 : xin;
         // operands of the last step are requested before the transform so that their latency overlaps it
-        // pointwise part in word pairs (512*s + 2*tid, +1): 16 bytes per lane and memory instruction
+        // pointwise part in the row-pair layout: 16 bytes per lane and memory instruction, no workgroup barrier
         ulonglong2 xr[8], ar[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            xr[s] = ((const ulonglong2 *)xin)[256 * s + tid];
-            ar[s] = ((const ulonglong2 *)ad)[256 * s + tid];
+            xr[s] = ((const ulonglong2 *)xin)[row_pair_index(hi4, lo4, s)];
+            ar[s] = ((const ulonglong2 *)ad)[row_pair_index(hi4, lo4, s)];
         }
         SCHED_FENCE();
         rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.nc + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+            const double *rr = lds + hi4 * V2_GS + row_pair_lds(lo4, s);
             double x0 = u2d(xr[s].x), x1 = u2d(xr[s].y);
             if (pre) {  // |x + pre*addend - r| < p + 1.5p + p/2 + 1
                 x0 += mulmod_w(u2d(ar[s].x), Pm.w, Pm.wp, p);
@@ -732,9 +797,9 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
                 v0 += u2d(ar[s].x);
                 v1 += u2d(ar[s].y);
             }
-            ((ulonglong2 *)out)[256 * s + tid] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
+            ((ulonglong2 *)out)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
         }
-        __syncthreads();
+        ROW_GROUP_SYNC();
     }
 }
 

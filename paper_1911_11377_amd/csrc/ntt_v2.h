@@ -36,6 +36,28 @@
 #endif
 #define V2_GS 272  // doubles per padded 16x17 group in LDS (row pass)
 
+// Row pass: the 16 lanes that work on one row of 256 words exchange their words through that row's own LDS group and
+// nothing else, and 16 consecutive lanes always sit in one wavefront.  A wavefront's LDS instructions execute in program
+// order, so these exchanges need no workgroup barrier: the fences only keep the compiler from moving LDS accesses across
+// the exchange point.  (The CPU stand-in runs one thread at a time and needs a real barrier there.)
+#ifdef CKKSMI_EMULATE
+#define ROW_GROUP_SYNC() __syncthreads()
+#else
+#define ROW_GROUP_SYNC()                                        \
+    do {                                                        \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  \
+        __builtin_amdgcn_wave_barrier();                        \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  \
+    } while (0)
+#endif
+
+// Pointwise layout of the row-pass kernels: thread (hi4 = tid / 16, lo4 = tid % 16) owns the word pairs at columns
+// 32*s + 2*lo4, +1 (s < 8) of row hi4 of the tile: 16 bytes per lane and memory instruction, 256 contiguous bytes per
+// row and instruction, and every word of a row stays with the 16 lanes that transform that row.
+__device__ __forceinline__ unsigned row_pair_index(unsigned hi4, unsigned lo4, int s) { return hi4 * 128u + 16u * s + lo4; }  // in 16-byte units from the tile
+// the same pair in the row's LDS group (padded 16 x 17 doubles; word q of the row at (q / 16) * 17 + q % 16)
+__device__ __forceinline__ unsigned row_pair_lds(unsigned lo4, int s) { return (2u * s + (lo4 >> 3)) * 17u + 2u * (lo4 & 7u); }
+
 struct NttV2Args {
     const u64d *src;
     u64d *dst;
@@ -247,48 +269,48 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
             fwd_round<F1>(x, tw1, p, pinv);
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[e * 17 + lo4] = x[e];
-            __syncthreads();
+            ROW_GROUP_SYNC();
 #pragma unroll
             for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
             fwd_round<F2>(x, tw2, p, pinv);
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = canon(x[e], p, pinv);
-            __syncthreads();
-            // canonical words out in pairs (512*s + 2*tid, +1): 16 bytes per lane and store
+            ROW_GROUP_SYNC();
+            // canonical words out in the row-pair layout: 16 bytes per lane and store
 #pragma unroll
             for (int s = 0; s < 8; s++) {
-                const double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
-                ((ulonglong2 *)(dst + tile0))[256 * s + tid] = make_ulonglong2(d2u(rr[0]), d2u(rr[1]));
+                const double *rr = grp + row_pair_lds(lo4, s);
+                ((ulonglong2 *)(dst + tile0))[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(rr[0]), d2u(rr[1]));
             }
         } else {
             {
                 // all 16 words requested before the first is used: one memory latency per item, not sixteen
-                // (in pairs 512*s + 2*tid, +1: 16 bytes per lane and load)
+                // (row-pair layout: 16 bytes per lane and load)
                 ulonglong2 raw[8];
 #pragma unroll
-                for (int s = 0; s < 8; s++) raw[s] = ((const ulonglong2 *)(src + tile0))[256 * s + tid];
+                for (int s = 0; s < 8; s++) raw[s] = ((const ulonglong2 *)(src + tile0))[row_pair_index(hi4, lo4, s)];
                 NTT_SCHED_FENCE();
 #pragma unroll
                 for (int s = 0; s < 8; s++) {
-                    double *rr = lds + (2 * s + (tid >> 7)) * V2_GS + ((tid & 127u) >> 3) * 17 + 2 * (tid & 7u);
+                    double *rr = grp + row_pair_lds(lo4, s);
                     rr[0] = u2d(raw[s].x);
                     rr[1] = u2d(raw[s].y);
                 }
             }
-            __syncthreads();
+            ROW_GROUP_SYNC();
 #pragma unroll
             for (int e = 0; e < 16; e++) x[e] = grp[lo4 * 17 + e];
             inv_round<I1, false>(x, tw2, p, pinv, unused, unused);
 #pragma unroll
             for (int e = 0; e < 16; e++) grp[lo4 * 17 + e] = x[e];
-            __syncthreads();
+            ROW_GROUP_SYNC();
 #pragma unroll
             for (int e = 0; e < 16; e++) x[e] = grp[e * 17 + lo4];
             inv_round<I2, false>(x, tw1, p, pinv, unused, unused);
 #pragma unroll
             for (int e = 0; e < 16; e++) dst[tile0 + hi4 * 256 + lo4 + 16 * e] = mid_store(x[e], p, pinv);
         }
-        __syncthreads();
+        ROW_GROUP_SYNC();
     }
 }
 
