@@ -20,6 +20,41 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
 INT8_PEAK_OPS = 5.0e15        # dense int8 MFMA
 FP64_PEAK_LANEOPS = 39.3e12   # 256 CU x 64 lanes x 2.4 GHz, one FP64 instruction per lane per clock
+COUNTERS_FILE = os.path.join(ROOT, "profiles", "counters_act_2e16.json")
+
+
+def load_counters():
+    """per-kernel hardware counters of the default workload (one launch each, batch 64, level 24), collected with
+    rocprofv3 --pmc on this build and summarised in profiles/; None when the file is missing"""
+    try:
+        with open(COUNTERS_FILE) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return None
+
+
+def counter_figures(C, name):
+    """HBM traffic per launch (FETCH_SIZE and WRITE_SIZE in KiB, each scaled by what the same counter reads for a plain
+    device copy of known size in the same profile), counted vector instructions per launch and the fraction of issue
+    cycles the vector ALU was busy, for one kernel of the counters file"""
+    if not C or name not in C.get("kernels", {}):
+        return None
+    k, probe = C["kernels"][name], C["copy_probe"]
+    out = {}
+    if "FETCH_SIZE" in k and "WRITE_SIZE" in k:
+        ff = probe["bytes"] / (probe["FETCH_SIZE"] * 1024.0)
+        wf = probe["bytes"] / (probe["WRITE_SIZE"] * 1024.0)
+        out["traffic"] = ff * k["FETCH_SIZE"] * 1024.0 + wf * k["WRITE_SIZE"] * 1024.0
+    if "SQ_INSTS_VALU" in k:
+        out["valu_wave_instr"] = k["SQ_INSTS_VALU"]
+    if "SQ_ACTIVE_INST_VALU" in k and "SQ_BUSY_CYCLES" in k:
+        # SQ_ACTIVE_INST_VALU counts 4-cycle slots over all 1024 SIMDs, SQ_BUSY_CYCLES cycles summed over the 32 shader engines
+        out["valu_busy"] = k["SQ_ACTIVE_INST_VALU"] * 4.0 / (k["SQ_BUSY_CYCLES"] / 32.0 * 1024.0)
+    if "SQ_LDS_BANK_CONFLICT" in k and "SQ_ACTIVE_INST_LDS" in k:
+        out["lds_conflict_frac"] = k["SQ_LDS_BANK_CONFLICT"] / max(k["SQ_ACTIVE_INST_LDS"], 1.0)
+    if "TCC_HIT_sum" in k and "TCC_MISS_sum" in k:
+        out["l2_hit_rate"] = k["TCC_HIT_sum"] / max(k["TCC_HIT_sum"] + k["TCC_MISS_sum"], 1.0)
+    return out
 
 
 def uniform_residues(torch, moduli, lead, N, gen):
@@ -40,16 +75,15 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "ntt_fwd_kernel<true>": w, "ntt_fwd_kernel<false>": w, "ntt_inv_kernel<false>": w, "ntt_inv_kernel<true>": w,
         "ntt_v2_kernel<false, true>": w, "ntt_v2_kernel<false, false>": w, "ntt_v2_kernel<true, false>": w, "ntt_v2_kernel<true, true>": w,
         "tensor_kernel": 7 * w,                       # 4 limbs in, 3 out
-        "tensor_rows_kernel": 8 * w,                  # + the inverse row pass of the third component out
+        "tensor_rows_kernel": 3 * w,                  # the operands' second components in, the inverse row pass of a1*b1 out
         "modup_kernel": w * (1.0 / E * min(alpha, level) + 1),   # per output limb: its share of the digit's source limbs + itself
         "inner_product_kernel": w * (beta + 2 + 2.0 * beta / batch),  # beta inputs, 2 outputs, key read once per batch
         "divround_conv_kernel": w * (1 + float(k) / level),
         "divround_final_kernel": 4 * w,               # x, tmp, addend in; out
         "automorphism_kernel": 2 * w,
         # fused kernels: the converted limb is written once (column-pass output) plus its share of the source limbs
-        "conv_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),   # ModUp
         # the same conversions organised by source tile (targets looped in the workgroup)
-        # (", true": the inverse column pass of the sources runs in the kernel too; same bytes)
+        # (the inverse column pass of the sources runs in the kernel too; same bytes)
         "modup_cols_kernel<4, %d, 0>" % alpha: w * (1 + float(level) / (beta * E - level)),
         "modup_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),
         "modup_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),
@@ -57,13 +91,10 @@ def bytes_per_unit(name, N, level, k, alpha, batch):
         "modup_cols_kernel<4, %d, 3>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
         "modup_cols_kernel<4, %d, 2>" % (k + 1): w * (1 + float(k + 1) / max(level - 1, 1)),
         "axpy_limb_kernel": 3 * w,
-        "conv_cols_kernel<4, %d, 1>" % k: w * (1 + float(k) / level),                         # ModDown conversion
-        "conv_cols_kernel<4, 1, 1>": w * (1 + 1.0 / (level - 1)),                             # rescale conversion
-        # beta limbs in, 2 out, key once per batch; the ciphertext limbs also read the product's two components (the
-        # z = x*P^-1 + d that the tail of HMult+relin+rescale consumes is formed here)
-        "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch + 2.0 * level / E),
+        # beta limbs in, 2 out, key read once per batch; in the composite multiply a ciphertext limb reads the four operand
+        # limbs instead of its own digit's word (d0, d1, d2 are formed here, and with them z = x*P^-1 + d)
+        "rows_inner_kernel": w * (beta + 2 + 2.0 * beta / batch + 3.0 * level / E),
         "rows_final_kernel": 3 * w,                                  # column-pass output and z in; out (4 with a separate addend)
-        "rows_final2_kernel": 5 * w,                                 # two column-pass outputs, x, addend in; out
         "elementwise kernels": 3 * w,
     }
     return table.get(name)
@@ -77,7 +108,6 @@ def laneops_per_unit(name, N, level, k, alpha):
     # 5 + add + sub per butterfly, lazy reductions included), one mid reduction, one reduction at the store
     xform_pass = 8 * 4 + 3 + 3
     table = {
-        "conv_cols_kernel<4, %d, 0>" % alpha: N * (7 * alpha + (alpha - 1) + 3 + xform_pass),
         # source words converted to doubles once per workgroup, not once per target
         # (the inverse column pass of the source tiles, once per workgroup, adds about 5 %: not counted)
         "modup_cols_kernel<4, %d, 0>" % alpha: N * (5 * alpha + (alpha - 1) + 3 + xform_pass),
@@ -85,30 +115,14 @@ def laneops_per_unit(name, N, level, k, alpha):
         "modup_cols_kernel<4, 1, 1>": N * (5 + 1 + 3 + xform_pass),
         "modup_cols_kernel<4, %d, 3>" % (k + 1): N * (5 * k + k + 3 + 5 + 2 + 3 + xform_pass),
         "modup_cols_kernel<4, %d, 2>" % (k + 1): N * (5 * (k + 1) + (k + 1) + 6 + 3 + xform_pass),
-        "conv_cols_kernel<4, %d, 1>" % k: N * (7 * k + k + 3 + xform_pass),
-        "conv_cols_kernel<4, 1, 1>": N * (7 + 1 + 3 + xform_pass),
         # per word: a row pass for every digit except the limb's own one (level of the E limbs have one), two
         # multiply-accumulates per digit (key word conversion 2 + exact product 5 + add 1, the prepared quotient and the
         # lazy reductions shared: about 2 more per digit), canonical form of the two results
         "rows_inner_kernel": N * ((beta - float(level) / (level + k)) * xform_pass + beta * (2 * 8 + 2) + 2 * 7
                                   + 2 * (5 + 3) * float(level) / (level + k)),
         "rows_final_kernel": N * (xform_pass + 2 + 1 + 5 + 3 + 7 + 2),   # (+5 when the kept limb is scaled before the subtraction)
-        "rows_final2_kernel": N * (2 * xform_pass + 2 + 1 + 5 + 3 + 1 + 5 + 7 + 2),
     }
     return table.get(name)
-
-
-# HBM bytes per launch of the kernels that dominate the default workload (act_2e16, batch 64, level 24), measured with
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the copy probe (profiles/hmul_relin_rescale_act_2e16.md):
-# 2.0 * FETCH_SIZE + WRITE_SIZE, in bytes
-MEASURED_TRAFFIC = {
-    "modup_cols_kernel<4, 3, 0>": (2.0 * 409785 + 6291456) * 1024,
-    "rows_inner_kernel": (2.0 * 4582582 + 1824768) * 1024,
-    "rows_final2_kernel": (2.0 * 3066124 + 1507328) * 1024,
-    "tensor_rows_kernel": (2.0 * 1963578 + 3145728) * 1024,
-    "rows_final_kernel": (2.0 * 1556772 + 1507328) * 1024,
-    "modup_cols_kernel<4, 4, 3>": (2.0 * 171453 + 1537870) * 1024,
-}
 
 
 def timed(torch, fn, reps):
@@ -350,13 +364,106 @@ def cnn_in_strips(torch, ckksmi, wl, gen, preset, topology, what):
     return res
 
 
+def op_byte_models(N, level, k, alpha, batch):
+    """bytes of one HMult + relinearise + rescale under the two models of the survey's measurement plan (limb = 8N bytes):
+    compulsory = read two ciphertexts, write one, the key once per batch; stage-wise = every stage reads its inputs once and
+    writes its outputs once, nothing fused (tensor, inverse transform of d2, ModUp, forward transforms, inner product,
+    ModDown, rescale; transforms counted once per limb)"""
+    E, beta = level + k, -(-level // alpha)
+    w = 8.0 * N
+    compulsory = w * (4 * level + 2 * (level - 1) + 2.0 * beta * E / batch)
+    tensor = w * (4 * level + 3 * level)
+    intt_d2 = w * 2 * level
+    modup = w * (level + beta * E - level)
+    ntt_up = w * 2 * (beta * E - level)
+    inner = w * (beta * E + 2 * E + 2.0 * beta * E / batch)
+    moddown = w * (2 * (2 * k) + (2 * k + 2 * level) + 2 * (2 * level) + 4 * (2 * level))
+    rescale = w * (2 * 2 + (2 + 2 * (level - 1)) + 2 * 2 * (level - 1) + 3 * 2 * (level - 1))
+    return compulsory, tensor + intt_d2 + modup + ntt_up + inner + moddown + rescale
+
+
+def copy_bandwidth(torch, nbytes=3 << 29):
+    """a plain device-to-device copy (reads and writes nbytes each): what the memory system sustains for streaming"""
+    src = torch.empty(nbytes // 8, dtype=torch.int64, device="cuda:0")
+    dst = torch.empty_like(src)
+    ms = timed(torch, lambda: dst.copy_(src), 5)
+    del src, dst
+    return 2.0 * nbytes / (ms * 1e-3) / 1e9
+
+
+def transform_sweeps(torch, ckksmi, wl, gen, ctx4):
+    """plain forward and inverse limb transforms, in place, for the shape of every workload: batch x 2 x (level + k) limbs
+    (the conv workload's 3072 ciphertexts are capped at 256 per launch); GB/s on 16N bytes per limb transform"""
+    out = {}
+    for name, preset, cap in (("tiny_2e12", "tiny", None), ("hmul_rot_2e14", "hmul_rot_2e14", None), ("conv_2e15", "conv_2e15", 256),
+                              ("act_2e16", "act_2e16", None)):
+        p = wl.PRESETS[preset]
+        c = ctx4 if preset == "act_2e16" else ckksmi.Context(p.logN, p.n_q, p.q_bits, p.k, p.special_bits, p.alpha, device=0)
+        cts = p.batch if cap is None else min(p.batch, cap)
+        idx = list(range(p.n_q)) + [p.n_q + m for m in range(p.k)]
+        limbs = uniform_residues(torch, [c.moduli[t] for t in idx], (cts * 2,), p.N, gen)
+        reps = 3 if p.logN >= 15 else 20
+        row = {"limbs": cts * 2 * len(idx)}
+        for d, fn in (("fwd", c.ntt), ("inv", c.intt)):
+            ms = timed(torch, lambda: fn(limbs, idx, cts * 2), reps)
+            gbps = 16.0 * p.N * len(idx) * cts * 2 / (ms * 1e-3) / 1e9
+            row[d] = {"GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+        out[name] = row
+        del limbs
+        if c is not ctx4:
+            c.close()
+    return out
+
+
+def oracle_legs(np, torch, wl, ckksmi, cores):
+    """the oracle timed on the host cores, one unit of work per workload shape: a limb transform, HMult + relinearise +
+    rescale, a rotation, one conv output ciphertext (multiply-accumulate over its window + rescale); single thread, and the
+    same unit once per thread on `cores` threads (independent ciphertexts; the C calls release the GIL).  Inputs are uniform
+    residues from the neutral input module: the oracle's time does not depend on the data."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import oracle as orc
+
+    def both(fn):
+        t0 = time.perf_counter()
+        fn(0)
+        t1 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(fn, range(cores)))
+        t2 = time.perf_counter()
+        return {"single_thread_s": round(t1 - t0, 4), "per_s_single": round(1.0 / (t1 - t0), 3), "per_s_all_cores": round(cores / (t2 - t1), 3)}
+
+    legs = {}
+    for name, preset, ops in (("tiny_2e12", "tiny", ("ntt", "hmul")), ("hmul_rot_2e14", "hmul_rot_2e14", ("ntt", "hmul", "rotate")),
+                              ("conv_2e15", "conv_2e15", ("ntt", "conv_out")), ("act_2e16", "act_2e16", ("ntt", "rotate"))):
+        p = wl.PRESETS[preset]
+        O = orc.Oracle(p.logN, p.n_q, p.q_bits, p.k, p.special_bits, p.alpha)
+        L, N = p.n_q, p.N
+        row = {}
+        ct = wl.uniform_limbs(O.q[:L], N, 9, "oracle.leg", preset, lead=(2,))
+        if "ntt" in ops:
+            limb = ct[0, :1].copy()
+            row["limb_transform"] = both(lambda i: O.ntt_limbs(limb, [0]))
+        key = wl.uniform_limbs(O.moduli, N, 9, "oracle.key", preset, lead=(O.beta_top, 2)) if p.k else None
+        if "hmul" in ops:
+            row["hmul_relin_rescale"] = both(lambda i: O.hmul_relin_rescale(ct, ct, key, L))
+        if "rotate" in ops:
+            row["rotate"] = both(lambda i: O.rotate(ct, 1, key, L))
+        if "conv_out" in ops:
+            win = wl.uniform_limbs(O.q[:L], N, 9, "oracle.win", lead=(3, 5, 5, 2))
+            wi = np.rint(wl.weights_float((1, 3, 5, 5), 9, "oracle.w") * float(O.q[L - 1])).astype(np.int64)
+            row["conv_output_ciphertext"] = both(lambda i: O.rescale(O.conv2d_mac(win, wi, 1, 0, L)[0, 0, 0], L))
+        legs[name] = row
+    return legs
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweep (keeps a profile to the timed steps)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweeps (keeps a profile to the timed steps)")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (rotation at N=2^14, conv layer at N=2^15, activation schedule)")
     ap.add_argument("--no-cnn", action="store_true", help="skip the two full-size networks in strips (about a minute of GPU time, up to 200 GB of HBM)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -389,49 +496,97 @@ def main():
     def step():
         ctx.hmul_relin_rescale(a, b, evk, out, level, batch, ws)
 
+    # ---- the timed region: K steps, nothing else on the stream (no timing events inside)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = ctx.profile_read()
-    ctx.profile_enable(False)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = batch * args.steps / (t1 - t0)
 
+    # ---- the same K steps again with two HIP events around every kernel launch (recorded by the library on the launch
+    # stream): per-kernel average durations for the roofline; the events cost a little, so this loop is not the headline
+    ctx.profile_enable(True)
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_per_step_profiled = (t3 - t2) * 1e3 / args.steps
+
     # ---- roofline of the dominant kernel (largest share of the timed region)
+    counters = load_counters() if (level, batch, p.logN) == (24, 64, 16) else None
     kernels = {}
     for name, (ms, launches, units) in prof.items():
         bpu = bytes_per_unit(name, N, level, p.k, p.alpha, batch)
-        kernels[name] = {"ms_total": round(ms, 3), "launches": launches, "avg_ms": round(ms / launches, 4),
-                         "GBps": round(bpu * units / (ms * 1e-3) / 1e9, 1) if bpu else None}
+        row = {"ms_total": round(ms, 3), "launches": launches, "avg_ms": round(ms / launches, 4),
+               "GBps": round(bpu * units / (ms * 1e-3) / 1e9, 1) if bpu else None}
+        cf = counter_figures(counters, name)
+        if cf:
+            if "traffic" in cf:
+                row["traffic_over_algorithmic"] = round(cf["traffic"] / (bpu * units / launches), 3) if bpu else None
+            if "valu_wave_instr" in cf:
+                row["alu_frac_counted"] = round(cf["valu_wave_instr"] * 64.0 / (ms / launches * 1e-3) / FP64_PEAK_LANEOPS, 4)
+            for kname in ("valu_busy", "lds_conflict_frac", "l2_hit_rate"):
+                if kname in cf:
+                    row[kname] = round(cf[kname], 4)
+        kernels[name] = row
     dom = max(prof, key=lambda n: prof[n][0])
     ms, launches, units = prof[dom]
     bpu = bytes_per_unit(dom, N, level, p.k, p.alpha, batch)
     achieved = bpu * units / (ms * 1e-3) / 1e9
-    lpu = laneops_per_unit(dom, N, level, p.k, p.alpha)
-    alu_rate = lpu * units / (ms * 1e-3) if lpu else None
     hbm_frac = achieved / HBM_PEAK_GBPS
+    # vector-ALU rate of the dominant kernel: vector instructions counted by the hardware (SQ_INSTS_VALU of one launch,
+    # from the counters file) x 64 lanes / this run's average launch duration; the count made by hand from the source
+    # stays beside it
+    lpu = laneops_per_unit(dom, N, level, p.k, p.alpha)
+    alu_frac_hand = lpu * units / (ms * 1e-3) / FP64_PEAK_LANEOPS if lpu else None
+    cf = counter_figures(counters, dom) or {}
+    alu_rate = cf["valu_wave_instr"] * 64.0 / (ms / launches * 1e-3) if "valu_wave_instr" in cf else (lpu * units / (ms * 1e-3) if lpu else None)
     alu_frac = alu_rate / FP64_PEAK_LANEOPS if alu_rate else 0.0
     ntt_ms = sum(prof[n][0] for n in prof if n.startswith("ntt_"))
     ntt_limbs = sum(prof[n][2] for n in prof if n in ("ntt_fwd_kernel<false>", "ntt_inv_kernel<false>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>"))
-    traffic = MEASURED_TRAFFIC.get(dom) if (level, batch, p.logN) == (24, 64, 16) else None
     if alu_frac > hbm_frac:
-        # the kernel does more FP64 work per byte than the machine balance: the vector ALU binds.  Peak = 256 CUs x 64
-        # lanes x 2.4 GHz = 39.3 T FP64 instructions/s (half the 78.6 TFLOP/s FMA figure); unit: T instructions/s
+        # the kernel does more vector work per byte than the machine balance: the vector ALU binds.  Peak = 256 CUs x 64
+        # lanes x 2.4 GHz = 39.3 T vector instructions/s (half the 78.6 TFLOP/s FP64 FMA figure); unit: T instructions/s
         roofline = {"kernel": dom, "bound": "alu", "achieved": round(alu_rate / 1e12, 2), "peak": FP64_PEAK_LANEOPS / 1e12,
-                    "unit": "T FP64 lane-instr/s", "frac": round(alu_frac, 4)}
+                    "unit": "T lane-instr/s", "frac": round(alu_frac, 4)}
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(hbm_frac, 4)}
-    roofline.update({"traffic": traffic, "hbm_GBps": round(achieved, 1), "hbm_frac": round(hbm_frac, 4), "alu_frac": round(alu_frac, 4),
+    roofline.update({"traffic": cf.get("traffic"), "hbm_GBps": round(achieved, 1), "hbm_frac": round(hbm_frac, 4), "alu_frac": round(alu_frac, 4),
+                     "alu_frac_source": "SQ_INSTS_VALU (profiles/counters_act_2e16.json)" if "valu_wave_instr" in cf else "hand count",
+                     "alu_frac_hand_count": round(alu_frac_hand, 4) if alu_frac_hand else None,
+                     "valu_busy": round(cf["valu_busy"], 4) if "valu_busy" in cf else None,
                      "avg_launch_ms": round(ms / launches, 4), "bytes_per_launch": bpu * units / launches,
                      "all_transforms_GBps": round(16 * N * ntt_limbs / (ntt_ms * 1e-3) / 1e9, 1) if ntt_ms else None,
                      "kernels": kernels})
+
+    # ---- the whole step against the byte models and the streaming bandwidth the memory system sustains
+    copy_gbps = copy_bandwidth(torch)
+    compulsory, stagewise = op_byte_models(N, level, p.k, p.alpha, batch)
+    step_s = ms_per_step * 1e-3
+    traffic_step = None
+    if counters:
+        per = [counter_figures(counters, n) for n in prof]
+        if all(x and "traffic" in x for x in per):
+            traffic_step = sum(x["traffic"] * prof[n][1] / args.steps for x, n in zip(per, prof))
+    step_fracs = {
+        "ms_per_step": round(ms_per_step, 3), "ms_per_step_with_timing_events": round(ms_per_step_profiled, 3),
+        "stagewise_bytes_per_op": stagewise, "compulsory_bytes_per_op": compulsory,
+        "frac_of_hbm_peak_on_stagewise_bytes": round(stagewise * batch / step_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "frac_of_hbm_peak_on_compulsory_bytes": round(compulsory * batch / step_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "copy_GBps": round(copy_gbps, 1),
+        "measured_traffic_bytes_per_step": traffic_step,
+        "frac_of_hbm_peak_on_measured_traffic": round(traffic_step / step_s / 1e9 / HBM_PEAK_GBPS, 4) if traffic_step else None,
+        "frac_of_copy_bandwidth_on_measured_traffic": round(traffic_step / step_s / 1e9 / copy_gbps, 4) if traffic_step else None,
+    }
 
     if args.copy_probe:
         probe = torch.empty_like(a)
@@ -439,22 +594,9 @@ def main():
         torch.cuda.synchronize()
         del probe
 
-    # ---- plain transform sweep: batch x 2 x (level + k) limbs, forward then inverse, in place
-    idx = list(range(level)) + [p.n_q + m for m in range(p.k)]
-    limbs = uniform_residues(torch, [ctx.moduli[t] for t in idx], (batch * 2,), N, gen)
-    ntt = {}
-    for name, fn in (() if args.no_sweep else (("fwd", ctx.ntt), ("inv", ctx.intt))):
-        fn(limbs, idx, batch * 2)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
-            fn(limbs, idx, batch * 2)
-        e1.record()
-        torch.cuda.synchronize()
-        gbps = 16.0 * N * len(idx) * batch * 2 * 3 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        ntt[name] = {"GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
-    del limbs
+    # ---- plain transform sweeps, one per workload shape
+    sweeps = {} if args.no_sweep else transform_sweeps(torch, ckksmi, wl, gen, ctx)
+    ntt = sweeps.get("act_2e16", {})
 
     extras = None
     if not (args.no_extras or args.no_sweep):
@@ -474,14 +616,17 @@ def main():
         hb = b[:cores].cpu().numpy().view(np.uint64)
         hk = evk.cpu().numpy().view(np.uint64)
         c0 = time.perf_counter()
+        O.hmul_relin_rescale(ha[0], hb[0], hk, level)
+        c1 = time.perf_counter()
         with ThreadPoolExecutor(cores) as ex:  # the C calls release the GIL
             res = list(ex.map(lambda i: O.hmul_relin_rescale(ha[i], hb[i], hk, level), range(cores)))
-        c1 = time.perf_counter()
+        c2 = time.perf_counter()
         got = out[:cores].cpu().numpy().view(np.uint64)
         match = all(np.array_equal(res[i], got[i]) for i in range(cores))
-        cpu = {"value": round(cores / (c1 - c0), 4), "unit": "ops/s", "cores": cores, "kind": "oracle",
+        cpu = {"value": round(cores / (c2 - c1), 4), "unit": "ops/s", "cores": cores, "kind": "oracle",
                "sample": "%d of the %d HMult+relin+rescale of one step, one per thread, same inputs" % (cores, batch),
-               "matches_gpu_bits": bool(match)}
+               "single_thread_ops_per_s": round(1.0 / (c1 - c0), 4), "matches_gpu_bits": bool(match),
+               "per_workload": oracle_legs(np, torch, wl, ckksmi, cores)}
 
     if extras is not None and not args.no_cnn:
         del a, b, evk, out, ws
@@ -501,7 +646,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "act_2e16: N=2^16, 24x50-bit primes + 3x51-bit special primes, 8 digits of 3, batch 64, level 24",
                    "op": "tensor -> key switch (ModUp, inner product, ModDown) -> add -> rescale"},
-        "roofline": roofline, "ntt_sweep": ntt, "cpu_baseline": cpu, "extras": extras,
+        "roofline": roofline, "step": step_fracs, "ntt_sweep": ntt, "ntt_sweeps": sweeps, "cpu_baseline": cpu, "extras": extras,
     }
     print(json.dumps(line))
 
