@@ -15,6 +15,7 @@
 #include "kernels.h"
 #include "ntt_v2.h"
 #include "ks_fused.h"
+#include "ntt_wg.h"
 #include "encode_device.h"
 #include "mac_mfma.h"
 
@@ -131,6 +132,23 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     V.items_per_z = (int)((items + zchunks - 1) / zchunks);
     zchunks = (unsigned)((items + V.items_per_z - 1) / V.items_per_z);
     dim3 gv2(tiles, M.per_item, zchunks);
+    if (passes == 3 && (c->logN == 13 || c->logN == 14)) {
+        // the whole limb in one workgroup: one trip through HBM (see ntt_wg.h); a workgroup loops over items of its limb slot
+        unsigned zc = ((unsigned)c->ntt_target_wgs / 4 + M.per_item - 1) / M.per_item;
+        if (zc > items) zc = (unsigned)items;
+        if (zc < 1) zc = 1;
+        V.items_per_z = (int)((items + zc - 1) / zc);
+        zc = (unsigned)((items + V.items_per_z - 1) / V.items_per_z);
+        const dim3 gw(M.per_item, zc), bw((unsigned)(N / 16));
+        if (c->logN == 13) {
+            if (forward) KL(c, CKKSMI_K_NTT_LDS, limbs_work, (ntt_wg_kernel<false, 13>), gw, bw, st, V);
+            else KL(c, CKKSMI_K_NTT_LDS, limbs_work, (ntt_wg_kernel<true, 13>), gw, bw, st, V);
+        } else {
+            if (forward) KL(c, CKKSMI_K_NTT_LDS, limbs_work, (ntt_wg_kernel<false, 14>), gw, bw, st, V);
+            else KL(c, CKKSMI_K_NTT_LDS, limbs_work, (ntt_wg_kernel<true, 14>), gw, bw, st, V);
+        }
+        return;
+    }
     if (forward) {
         if (A.LA && (passes & 1)) {
             if (v2_cols) KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, (ntt_v2_kernel<false, true>), gv2, dim3(V2_THREADS), st, V);
@@ -1487,7 +1505,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "tensor_kernel", "modup_kernel", "inner_product_kernel", "divround_conv_kernel",
                                                 "divround_final_kernel", "automorphism_kernel", "mac_prepare_kernel", "conv_mac_kernel",
                                                 "elementwise kernels", "modup_cols_kernel", "modup_cols_kernel", "rows_inner_kernel",
-                                                "rows_final_kernel", "modup_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "ntt_lds_kernel", "tensor_rows_kernel",
+                                                "rows_final_kernel", "modup_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "ntt_wg_kernel", "tensor_rows_kernel",
                                                 "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel",
                                                 "encoding kernels", "encryption kernels", "modup_cols_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
