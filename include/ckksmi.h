@@ -26,7 +26,8 @@
  *     memory on the context's GPU.  The library never allocates ciphertext or
  *     workspace memory: the caller passes device buffers and a hipStream_t (as
  *     void*; NULL = the default stream).  Device calls enqueue on that stream and
- *     return without synchronising.  The context owns only its constant tables.
+ *     return without synchronising (one exception: ckksmi_encode_device reads an overflow word back and therefore
+ *     waits for its stream).  The context owns only its constant tables.
  *     Device buffers (ciphertexts, keys, workspace) must be 16-byte aligned: the
  *     kernels move two words per lane and memory instruction; a misaligned
  *     pointer is rejected with CKKSMI_EINVAL.

@@ -811,8 +811,8 @@ int dev_upload_tables(ckksmi_ctx *c) {
             ctw[2 * x + 1] = (double)(-sinl(ang));
         }
         c->d_ctw = upload(c, ctw.data(), ctw.size(), ok);
-        const int zero = 0;
-        c->d_flag = upload(c, &zero, 1, ok);
+        const int zeros[CKKSMI_FLAG_SLOTS] = {0};
+        c->d_flag = upload(c, zeros, CKKSMI_FLAG_SLOTS, ok);
     }
     if (!ok) { c->last_hip_error = (int)hipGetLastError(); return CKKSMI_EDEVICE; }
     return CKKSMI_OK;
@@ -1223,22 +1223,24 @@ extern "C" int ckksmi_encode_device(ckksmi_ctx *c, const double *re, const doubl
     hipStream_t st = S(stream);
     EncodeArgs A;
     A.re = re; A.im = im; A.cbuf = (double2 *)ws; A.slot_exp = c->d_slot_exp; A.ctw = (const double2 *)c->d_ctw; A.logN = c->logN;
+    // every call takes its own overflow word (round-robin over CKKSMI_FLAG_SLOTS), so calls in flight on different streams
+    // of one context do not share one
+    int *flag_word = c->d_flag + (c->flag_next.fetch_add(1) % CKKSMI_FLAG_SLOTS);
+    A.flag = flag_word;
     A.LA = la_for(c->logN);
     const unsigned N1 = 1u << A.LA, N2 = (unsigned)(N >> A.LA);
     const unsigned R = N2 >= CFFT_TILE ? 1u : CFFT_TILE / N2;
     KL(c, CKKSMI_K_ENCODE, (double)batch, encode_scatter_kernel, dim3(ew_blocks(N / 2), batch), dim3(EW_THREADS), st, A);
     KL(c, CKKSMI_K_ENCODE, (double)batch, cfft_inv_kernel<false>, dim3(batch, (N1 + R - 1) / R), dim3(NTT_THREADS), st, A);
     if (A.LA) KL(c, CKKSMI_K_ENCODE, (double)batch, cfft_inv_kernel<true>, dim3(batch, N2 / NTT_TC), dim3(NTT_THREADS), st, A);
-    // the flag is only ever raised by the rounding kernel and read back after this call's kernels
-    if (hipMemsetAsync(c->d_flag, 0, sizeof(int), st) != hipSuccess) return CKKSMI_EDEVICE;
     const size_t total = (size_t)batch * N;
     KL(c, CKKSMI_K_ENCODE, (double)batch, encode_round_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), st, (const double2 *)ws, scale / (double)N,
-       (u64d *)pt, c->d_mod, c->logN, level, total, c->d_flag);
+       (u64d *)pt, c->d_mod, c->logN, level, total, flag_word);
     int idx[CKKSMI_MAX_MODULI];
     for (int i = 0; i < level; i++) idx[i] = i;
     launch_ntt(c, true, pt, pt, table_map(idx, level, (size_t)level * N, (size_t)level * N), batch, st);
     int flag = 0;
-    if (hipMemcpyAsync(&flag, c->d_flag, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess)
+    if (hipMemcpyAsync(&flag, flag_word, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess)
         return CKKSMI_EDEVICE;
     if (flag) return CKKSMI_EINVAL;
     return g.rc();

@@ -1,5 +1,6 @@
 // Internal declarations shared by the host code and the kernel launchers.
 #pragma once
+#include <atomic>
 #include <cstddef>
 #include <cstdint>
 #include <string>
@@ -16,6 +17,7 @@ typedef unsigned __int128 u128;
 #define CKKSMI_MAX_ALPHA 4
 #define CKKSMI_MAX_MODULI 72
 #define CKKSMI_MAX_KEYS 64     // distinct switching keys one launch can address (tables of pointers travel as kernel arguments)
+#define CKKSMI_FLAG_SLOTS 64    // overflow words of the device encoder: calls in flight at once on one context
 #define CKKSMI_MAX_ITEMS 256   // items per key-switch sweep (per-item tables travel as kernel arguments)
 
 // ---- host integer helpers (host_math.cpp) ----
@@ -111,7 +113,8 @@ struct ckksmi_ctx {
     FinConst *d_fin_rescale = nullptr;  // [n_q]  dropped limb
     unsigned *d_slot_exp = nullptr;     // [N/2] 5^k mod 2N (device-side encoding)
     void *d_ctw = nullptr;              // [N] complex doubles zeta^-brev(x), zeta = exp(i*pi/N)
-    int *d_flag = nullptr;              // one word: raised by a kernel that meets an unencodable value
+    int *d_flag = nullptr;              // CKKSMI_FLAG_SLOTS words: one is raised by a kernel that meets an unencodable value
+    std::atomic<unsigned> flag_next{0}; // the next call's word
     FinConst *d_fin_tail = nullptr;     // [n_q + 1][CKKSMI_MAX_SPECIAL]  level, {plain inverse of q_{level-1}, ModDown's constants}
     FinConst *d_fin_merged = nullptr;   // [n_q + 1][CKKSMI_MAX_SPECIAL]  level, member of {q_{level-1}, p_0 ..}
     std::vector<DivRoundDev> divround_merged;  // [n_q + 1] by level; nb == 0 where unavailable

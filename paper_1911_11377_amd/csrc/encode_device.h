@@ -18,6 +18,7 @@ struct EncodeArgs {
     const unsigned *slot_exp;  // [N/2]: 5^k mod 2N
     const double2 *ctw;      // [N]: zeta^-brev(x)
     int logN, LA;
+    int *flag;               // this call's overflow word: cleared here by the first kernel of the sequence, raised by the last
 };
 
 __device__ __forceinline__ double2 cmul(double2 a, double2 b) { return make_double2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x); }
@@ -26,6 +27,7 @@ __device__ __forceinline__ double2 cmul(double2 a, double2 b) { return make_doub
 __global__ __launch_bounds__(EW_THREADS) void encode_scatter_kernel(EncodeArgs A) {
     const unsigned N = 1u << A.logN, half = N >> 1;
     const unsigned k = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (k == 0 && blockIdx.y == 0) *A.flag = 0;  // the rounding kernel that may raise it runs later on the same stream
     if (k >= half) return;
     const size_t item = blockIdx.y;
     const double zr = A.re[item * half + k], zi = A.im ? A.im[item * half + k] : 0.0;

@@ -193,11 +193,12 @@ def test_emulated_edge_values_generic_kernels(be, shape):
     pc.case_edge_values(be, shape, seed=140)
 
 
-@pytest.mark.parametrize("shape,level", [((13, 24, 50, 3, 51, 3), 24), ((13, 15, 51, 3, 51, 3), 15)])
-def test_emulated_edge_values_register_tiled_kernels(be, shape, level):
+@pytest.mark.parametrize("shape,level,seeded", [((13, 24, 50, 3, 51, 3), 24, False), ((13, 15, 51, 3, 51, 3), 15, True)])
+def test_emulated_edge_values_register_tiled_kernels(be, shape, level, seeded):
     """the same at a register-tiled size with 3-prime digits: 8 digits of 50-bit primes (eight terms meet in the fused inner
-    product's accumulators before their one reduction) and 5 digits of 51-bit primes (reduced every four terms)"""
-    pc.case_edge_values(be, shape, seed=142, level=level, conv=False, pairs=FEW_PAIRS)
+    product's accumulators before their one reduction; key of all q-1) and 5 digits of 51-bit primes (reduced every four
+    terms; both keys).  Two operand pairs each: the GPU suite runs the full set."""
+    pc.case_edge_values(be, shape, seed=142, level=level, conv=False, pairs=FEW_PAIRS[:2], seeded_key=seeded)
 
 
 def test_emulated_edge_values_matrix_core_mac(be):
