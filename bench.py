@@ -242,6 +242,29 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     del a2, b2, k2, gks, o2, or2, w2, oh, wh
     c2.close()
 
+    # ONE image through a whole network in the rotation-packed layout (the latency figure: the paper reports minutes per
+    # image, section 3.2): the layer kinds and order of Table 1 at reduced width (3x16x16 -> conv 4@5x5 -> x -> 2x2 pool ->
+    # conv 6@3x3 -> x -> pool -> FC 16 -> x -> FC 2, x = the degree-2 polynomial of section 3.1), every pooling merged into the
+    # matrix of the layer after it, N = 2^14, 11 primes; keys and input are uniform residues
+    cs = ckksmi.Context(14, 11, 50, 3, 51, 3, device=0)
+    topo = "single_image_reduced"
+    plans, n_per, lvl_out, _ = packed.plan_network(cs, wl.cnn_shapes(topo), wl.cnn_weights_float(topo, 7, sigma=0.25), 11, 2.0 ** 50, to_dev)
+    all_rots = sorted({d for pl in plans if isinstance(pl, packed.BlockPlan) for r in pl.rotations.values() for d in r})
+    net_keys = []
+    for d in all_rots:
+        net_keys.append(uniform_residues(torch, cs.moduli, (cs.beta_top, 2), 1 << 14, gen))
+        cs.galois_key_register(d, net_keys[-1])
+    evk_s = uniform_residues(torch, cs.moduli, (cs.beta_top, 2), 1 << 14, gen)
+    xin_s = uniform_residues(torch, cs.q, (1, 2), 1 << 14, gen)
+    wsn = torch.empty(packed.network_workspace_bytes(cs, plans, 11) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: packed.run_network(cs, xin_s, plans, evk_s, 11, wsn), 2)
+    n_mul = sum(len(o) for pl in plans if isinstance(pl, packed.BlockPlan) for o in pl.offsets.values())
+    out["single_image_network_2e14"] = {"ms_per_image": round(ms, 2), "rotations": sum(len(r) for pl in plans if isinstance(pl, packed.BlockPlan) for r in pl.rotations.values()),
+                                        "plaintext_products": n_mul, "distinct_keys": len(all_rots), "levels": [11, lvl_out], "period": n_per,
+                                        "what": "one image, rotation-packed: 3x16x16 -> conv 4@5x5, poly2, pool+conv 6@3x3, poly2, pool+FC 16, poly2, FC 2"}
+    del net_keys, evk_s, xin_s, wsn, plans
+    cs.close()
+
     # conv layer, slots-as-batch: N = 2^15, 16x50-bit, 3x32x32 pixel ciphertexts (16384 images), 3 -> 32 channels 5x5 stride 2, then rescale
     p3 = wl.PRESETS["conv_2e15"]
     c3 = ckksmi.Context(p3.logN, p3.n_q, p3.q_bits, p3.k, p3.special_bits, p3.alpha, device=0)

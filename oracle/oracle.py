@@ -426,6 +426,45 @@ class Oracle:
             acc = term if acc is None else self.add(acc, term, level)
         return self.rescale(acc, level)
 
+    def linear_transform_blocks(self, xs, diag_pts, gks, level):
+        """A matrix-vector product whose vectors span several ciphertexts (single-image packing of a layer wider than the
+        slot count): xs[j] holds block j of the input vector, diag_pts[(i, j)] = {d: encoded diagonal d of block (i, j)},
+        and output block i is  Rescale( sum_j sum_d pt_(i,j),d * Rot_d(xs[j]) ).  Every input block is rotated once for
+        all the output blocks that need it, by all its offsets from ONE shared ModUp (rotate_hoisted); d = 0 needs no
+        rotation.  Returns the list of output ciphertexts (level-1), blocks 0 .. max i; an output block that no input
+        reaches would be an encryption of zero and is not allowed here."""
+        n_out = 1 + max(i for i, _ in diag_pts)
+        acc = [None] * n_out
+        for j, x in enumerate(xs):
+            rots = sorted({d for (i, jj), dg in diag_pts.items() if jj == j for d in dg if d != 0})
+            rotated = self.rotate_hoisted(x, rots, [gks[d] for d in rots], level) if rots else []
+            for (i, jj), dg in sorted(diag_pts.items()):
+                if jj != j:
+                    continue
+                for d in sorted(dg):
+                    src = _u64(x) if d == 0 else rotated[rots.index(d)]
+                    term = self.mul_plain(src, dg[d], level)
+                    acc[i] = term if acc[i] is None else self.add(acc[i], term, level)
+        assert all(a is not None for a in acc), "an output block receives nothing"
+        return [self.rescale(a, level) for a in acc]
+
+    def packed_network(self, xs, stages, rlk, gks, level):
+        """One image through a network in the single-image packing: xs = the ciphertexts holding the input vector's
+        blocks; stages = [("linear", diag_pts) | ("poly2", k2, k1)], a linear stage being any product of the network's
+        linear layers between two activations (convolution, pooling and fully connected layers are all matrices, and a
+        pooling layer is merged with the layer after it), poly2 the degree-2 activation of section 3.1 applied to every
+        block.  Returns (list of output ciphertexts, their level)."""
+        for st in stages:
+            if st[0] == "linear":
+                xs = self.linear_transform_blocks(xs, st[1], gks, level)
+                level -= 1
+            elif st[0] == "poly2":
+                xs = [self.poly2(x, rlk, level, st[1], st[2]) for x in xs]
+                level -= 2
+            else:
+                raise ValueError(st[0])
+        return xs, level
+
     def add(self, a, b, level):
         out = np.empty((2, level, self.N), dtype=np.uint64)
         self._L.orc_add(self._h, _p64(_u64(a)), _p64(_u64(b)), level, _p64(out))
@@ -707,12 +746,13 @@ def matrix_diagonals(M, n_slots):
     return out
 
 
-def conv_as_matrix(w, H, W, pad):
-    """The stride-1 convolution of a C x H x W image (flattened channel-major) with weights w [O][C][kh][kw] and zero
-    padding `pad`, output O x H' x W', written as a dense matrix [O*H'*W'][C*H*W] straight from the definition."""
+def conv_as_matrix(w, H, W, pad, stride=1):
+    """The convolution of a C x H x W image (flattened channel-major) with weights w [O][C][kh][kw], zero padding `pad`
+    and stride `stride`, output O x H' x W' with H' = (H + 2 pad - kh) / stride + 1, written as a dense matrix
+    [O*H'*W'][C*H*W] straight from the definition (Table 1's convolution rows)."""
     w = np.asarray(w, dtype=np.float64)
     O, C, kh, kw = w.shape
-    Ho, Wo = H + 2 * pad - kh + 1, W + 2 * pad - kw + 1
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
     M = np.zeros((O * Ho * Wo, C * H * W))
     for o in range(O):
         for y in range(Ho):
@@ -720,10 +760,45 @@ def conv_as_matrix(w, H, W, pad):
                 for c in range(C):
                     for u in range(kh):
                         for v in range(kw):
-                            iy, ix = y + u - pad, x + v - pad
+                            iy, ix = y * stride + u - pad, x * stride + v - pad
                             if 0 <= iy < H and 0 <= ix < W:
                                 M[(o * Ho + y) * Wo + x][(c * H + iy) * W + ix] += w[o][c][u][v]
     return M
+
+
+def pool_as_matrix(C, H, W, k, pad=0):
+    """k x k average pooling (Table 1's pooling rows) of a C x H x W image padded with `pad` zero rows / columns on every
+    side, windows at multiples of k, output C x floor((H + 2 pad)/k) x floor((W + 2 pad)/k), as a matrix [C*H'*W'][C*H*W]
+    with entries 1/k^2 (positions on the padding contribute nothing)."""
+    Ho, Wo = (H + 2 * pad) // k, (W + 2 * pad) // k
+    M = np.zeros((C * Ho * Wo, C * H * W))
+    for c in range(C):
+        for y in range(Ho):
+            for x in range(Wo):
+                for u in range(k):
+                    for v in range(k):
+                        iy, ix = k * y + u - pad, k * x + v - pad
+                        if 0 <= iy < H and 0 <= ix < W:
+                            M[(c * Ho + y) * Wo + x][(c * H + iy) * W + ix] = 1.0 / (k * k)
+    return M
+
+
+def block_diagonals(M, n, n_slots):
+    """A matrix of any shape cut into n x n blocks (zero-padded to multiples of n; n divides n_slots, and n = n_slots as
+    soon as there is more than one block in a direction): {(i, j): {d: diagonal d of block (i, j) tiled over n_slots}},
+    empty diagonals and empty blocks left out.  Output block i of M z is sum_j sum_d diag_(i,j),d * roll(z_j, -d)."""
+    M = np.asarray(M, dtype=np.float64)
+    bo, bi = -(-M.shape[0] // n), -(-M.shape[1] // n)
+    assert n_slots % n == 0 and (n == n_slots or (bo == 1 and bi == 1))
+    P = np.zeros((bo * n, bi * n))
+    P[: M.shape[0], : M.shape[1]] = M
+    out = {}
+    for i in range(bo):
+        for j in range(bi):
+            dg = matrix_diagonals(P[i * n:(i + 1) * n, j * n:(j + 1) * n], n_slots)
+            if dg:
+                out[(i, j)] = dg
+    return out
 
 
 def encode_direct(z, scale, logN):

@@ -50,18 +50,18 @@ def matrix_diagonals(M, n_slots):
     return out
 
 
-def conv_matrix(w, H, W, pad):
-    """stride-1 convolution of a channel-major C x H x W vector as a matrix [O*Ho*Wo][C*H*W]"""
+def conv_matrix(w, H, W, pad, stride=1):
+    """convolution (zero padding `pad`, stride `stride`) of a channel-major C x H x W vector as a matrix [O*Ho*Wo][C*H*W]"""
     w = np.asarray(w, dtype=np.float64)
     O, C, kh, kw = w.shape
-    Ho, Wo = H + 2 * pad - kh + 1, W + 2 * pad - kw + 1
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
     M = np.zeros((O, Ho, Wo, C, H, W))
     ys, xs = np.arange(Ho), np.arange(Wo)
     for u in range(kh):
-        iy = ys + u - pad
+        iy = ys * stride + u - pad
         vy = (iy >= 0) & (iy < H)
         for v in range(kw):
-            ix = xs + v - pad
+            ix = xs * stride + v - pad
             vx = (ix >= 0) & (ix < W)
             for o in range(O):
                 for c in range(C):
@@ -140,3 +140,226 @@ def linear_transform(ctx, x, plan, out, ws, stream=None, max_rotations=MAX_ROTAT
     if not have_acc:
         raise ValueError("the matrix has no non-zero diagonal")
     ctx.rescale(acc, out, L, 1, rest, stream=stream)
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# whole networks on one image: vectors that may span several ciphertexts, pooling and strided layers as matrices
+# ---------------------------------------------------------------------------------------------------------------------
+def pool_matrix(C, H, W, k, pad=0):
+    """k x k average pooling of a channel-major C x H x W vector padded with `pad` zero rows / columns on every side, as a
+    matrix [C*Ho*Wo][C*H*W] with entries 1/k^2, Ho = (H + 2 pad) // k"""
+    Ho, Wo = (H + 2 * pad) // k, (W + 2 * pad) // k
+    M = np.zeros((C, Ho, Wo, C, H, W))
+    for u in range(k):
+        iy = np.arange(Ho) * k + u - pad
+        vy = (iy >= 0) & (iy < H)
+        for v in range(k):
+            ix = np.arange(Wo) * k + v - pad
+            vx = (ix >= 0) & (ix < W)
+            for c in range(C):
+                M[c, np.arange(Ho)[vy][:, None], np.arange(Wo)[vx][None, :], c, iy[vy][:, None], ix[vx][None, :]] = 1.0 / (k * k)
+    return M.reshape(C * Ho * Wo, C * H * W)
+
+
+def stage_matrices(layer_shapes, weights):
+    """[("linear", M) | ("poly2",)] for a layer list as workloads.cnn_shapes gives it: the linear layers between two
+    activations (convolutions, poolings, fully connected layers) multiplied into one matrix each"""
+    stages, pending = [], None
+    for (layer, (c, h, w), _), wt in zip(layer_shapes, weights):
+        kind = layer[0]
+        if kind == "poly2":
+            stages += [("linear", pending), ("poly2",)]
+            pending = None
+            continue
+        if kind == "conv":
+            M = conv_matrix(wt, h, w, layer[4], layer[3])
+        elif kind == "pool":
+            M = pool_matrix(c, h, w, layer[1], layer[2] if len(layer) > 2 else 0)
+        elif kind == "fc":
+            M = np.asarray(wt, dtype=np.float64)
+        else:
+            raise ValueError("layer kind %r has no matrix" % (kind,))
+        pending = M if pending is None else M @ pending
+    if pending is not None:
+        stages.append(("linear", pending))
+    return stages
+
+
+def block_diagonals(M, n, n_slots):
+    """{(i, j): {d: diagonal d of the n x n block (i, j) of M, tiled over the slots}}; M zero-padded to multiples of n"""
+    M = np.asarray(M, dtype=np.float64)
+    bo, bi = -(-M.shape[0] // n), -(-M.shape[1] // n)
+    if n_slots % n or not (n == n_slots or (bo == 1 and bi == 1)):
+        raise ValueError("several blocks need a block size equal to the slot count")
+    P = np.zeros((bo * n, bi * n))
+    P[: M.shape[0], : M.shape[1]] = M
+    out = {}
+    for i in range(bo):
+        for j in range(bi):
+            dg = matrix_diagonals(P[i * n:(i + 1) * n, j * n:(j + 1) * n], n_slots)
+            if dg:
+                out[(i, j)] = dg
+    return out
+
+
+@dataclass
+class BlockPlan:
+    """a matrix cut into blocks, prepared for one level"""
+    level: int
+    n_in: int
+    n_out: int
+    rotations: dict     # input block j -> ascending non-zero offsets any output block needs of it
+    offsets: dict       # (i, j) -> ascending offsets (0 included) of that block
+    pts: dict           # (i, j) -> device [len(offsets)][level][N] in that order
+
+
+def plan_blocks(ctx, M, n, level, to_dev, encode=None):
+    """encode the diagonals of every block of M at scale q_{level-1}"""
+    dg = block_diagonals(M, n, ctx.N // 2)
+    enc = encode or (lambda v, s, l: ctx.encode(v, s, l))
+    scale = float(ctx.q[level - 1])
+    n_out, n_in = 1 + max(i for i, _ in dg), -(-np.asarray(M).shape[1] // n)
+    if sorted({i for i, _ in dg}) != list(range(n_out)):
+        raise ValueError("an output block receives nothing")
+    rots = {j: sorted({d for (_, jj), dd in dg.items() if jj == j for d in dd if d}) for j in range(n_in)}
+    offsets = {ij: sorted(dd) for ij, dd in dg.items()}
+    pts = {ij: to_dev(np.stack([enc(dg[ij][d].astype(np.complex128), scale, level) for d in offsets[ij]])) for ij in dg}
+    return BlockPlan(level, n_in, n_out, rots, offsets, pts)
+
+
+def blocks_workspace_bytes(ctx, plan, max_rotations=MAX_ROTATIONS_PER_CALL):
+    L, N = plan.level, ctx.N
+    R = max([min(len(r), max_rotations) for r in plan.rotations.values()] + [1])
+    ct = 2 * L * N * 8
+    rot_ws = ctx.rotate_hoisted_workspace_bytes(L, 1, R)
+    return (2 * R + plan.n_out) * ct + max(rot_ws, ctx.workspace_bytes(ckksmi.OP_RESCALE, L, plan.n_out))
+
+
+def linear_transform_blocks(ctx, xs, plan, out, ws, stream=None, max_rotations=MAX_ROTATIONS_PER_CALL):
+    """out [n_out][2][level-1][N] = RS(sum_j sum_d pt_(i,j),d * Rot_d(xs[j])) for the input blocks xs [n_in][2][level][N].
+    Every input block is rotated once (in calls of at most max_rotations offsets) for all output blocks."""
+    L, N = plan.level, ctx.N
+    ct = 2 * L * N
+    flat = ws.reshape(-1) if hasattr(ws, "reshape") else ws
+    xflat = xs.reshape(-1) if hasattr(xs, "reshape") else xs
+    R_max = max([min(len(r), max_rotations) for r in plan.rotations.values()] + [1])
+    rotated = flat[: R_max * ct]
+    prod = flat[R_max * ct: 2 * R_max * ct]
+    acc = flat[2 * R_max * ct: (2 * R_max + plan.n_out) * ct]
+    rest = flat[(2 * R_max + plan.n_out) * ct:]
+    started = [False] * plan.n_out
+
+    def accumulate(i, src):
+        a = acc[i * ct:(i + 1) * ct]
+        if started[i]:
+            ctx.add(a, src, a, L, 1, stream=stream)
+        else:
+            ctx.mul_scalar(src, 1, a, L, 1, stream=stream)  # start of the running sum (a copy)
+            started[i] = True
+
+    for j in range(plan.n_in):
+        x = xflat[j * ct:(j + 1) * ct]
+        for (i, jj), offs in sorted(plan.offsets.items()):
+            if jj == j and offs and offs[0] == 0:
+                ctx.mul_plain(x, plan.pts[(i, j)].reshape(-1)[: L * N], 0, prod[:ct], L, 1, stream=stream)
+                accumulate(i, prod[:ct])
+        rots_j = plan.rotations[j]
+        for c0 in range(0, len(rots_j), max_rotations):
+            chunk = rots_j[c0: c0 + max_rotations]
+            ctx.rotate_hoisted(x, chunk, rotated, L, 1, rest, stream=stream)
+            for (i, jj), offs in sorted(plan.offsets.items()):
+                if jj != j:
+                    continue
+                # runs of consecutive rotated copies whose offsets this block has: one batched product per run
+                m, k = 0, 0
+                while k < len(chunk):
+                    if chunk[k] not in offs:
+                        k += 1
+                        continue
+                    k1 = k
+                    p0 = offs.index(chunk[k])
+                    while k1 + 1 < len(chunk) and p0 + (k1 + 1 - k) < len(offs) and offs[p0 + (k1 + 1 - k)] == chunk[k1 + 1]:
+                        k1 += 1
+                    run = k1 - k + 1
+                    ctx.mul_plain(rotated[k * ct:(k1 + 1) * ct], plan.pts[(i, j)].reshape(-1)[p0 * L * N:(p0 + run) * L * N], L * N,
+                                  prod[m * ct:(m + run) * ct], L, run, stream=stream)
+                    m += run
+                    k = k1 + 1
+                if m == 0:
+                    continue
+                while m > 1:  # pairwise tree (modular addition: any order gives the same words)
+                    h = m // 2
+                    ctx.add(prod[: h * ct], prod[(m - h) * ct: m * ct], prod[: h * ct], L, h, stream=stream)
+                    m -= h
+                accumulate(i, prod[:ct])
+    ctx.rescale(acc, out, L, plan.n_out, rest, stream=stream)
+
+
+def network_period(stages, n_slots):
+    longest = max(max(st[1].shape) for st in stages if st[0] == "linear")
+    n = 1
+    while n < longest:
+        n *= 2
+    return min(n, n_slots)
+
+
+def plan_network(ctx, layer_shapes, weights, level, scale, to_dev, encode=None):
+    """plans of every stage of a network on one image (BlockPlan or activation.Poly2Constants), the packing period, the
+    output level and scale"""
+    from . import activation
+    stages = stage_matrices(layer_shapes, weights)
+    n = network_period(stages, ctx.N // 2)
+    plans = []
+    for st in stages:
+        if st[0] == "linear":
+            plans.append(plan_blocks(ctx, st[1], n, level, to_dev, encode))
+            level -= 1
+        else:
+            k = activation.poly2_constants(ctx.q, level, scale)
+            plans.append(k)
+            scale = k.out_scale
+            level -= 2
+    return plans, n, level, scale
+
+
+def network_workspace_bytes(ctx, plans, level, max_rotations=MAX_ROTATIONS_PER_CALL):
+    from . import activation
+    need, blocks, N = 0, 1, ctx.N
+    for pl in plans:
+        if isinstance(pl, BlockPlan):
+            need = max(need, blocks_workspace_bytes(ctx, pl, max_rotations))
+            blocks = pl.n_out
+            level -= 1
+        else:
+            need = max(need, activation.workspace_bytes(ctx, level, blocks))
+            level -= 2
+    # two ping-pong buffers for the activations between stages
+    widest = max([pl.n_in for pl in plans if isinstance(pl, BlockPlan)] + [pl.n_out for pl in plans if isinstance(pl, BlockPlan)])
+    return need + 2 * widest * 2 * ctx.n_q * N * 8
+
+
+def run_network(ctx, xs, plans, evk, level, ws, stream=None, max_rotations=MAX_ROTATIONS_PER_CALL):
+    """one image through the planned stages; xs [n_in][2][level][N]; returns (flat device view of the output blocks
+    [n_out][2][level_out][N] inside ws, n_out, level_out)"""
+    from . import activation
+    N = ctx.N
+    flat = ws.reshape(-1) if hasattr(ws, "reshape") else ws
+    widest = max([pl.n_in for pl in plans if isinstance(pl, BlockPlan)] + [pl.n_out for pl in plans if isinstance(pl, BlockPlan)])
+    half = widest * 2 * ctx.n_q * N
+    bufs = [flat[:half], flat[half: 2 * half]]
+    rest = flat[2 * half:]
+    cur, which = xs, 0
+    blocks = None
+    for pl in plans:
+        dst = bufs[which]
+        if isinstance(pl, BlockPlan):
+            linear_transform_blocks(ctx, cur, pl, dst[: pl.n_out * 2 * (level - 1) * N], rest, stream=stream, max_rotations=max_rotations)
+            blocks = pl.n_out
+            level -= 1
+            cur = dst[: blocks * 2 * level * N]
+        else:
+            activation.poly2(ctx, cur, evk, dst[: blocks * 2 * (level - 2) * N], level, blocks, pl, rest, stream=stream)
+            level -= 2
+            cur = dst[: blocks * 2 * level * N]
+        which ^= 1
+    return cur, blocks, level

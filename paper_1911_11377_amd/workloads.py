@@ -132,6 +132,13 @@ CNN_TOPOLOGIES = {
     # a few layers of the same kinds for slow (emulated) checks: 6 -> 4 -> 2 -> 2 -> 2 (padded pooling) -> 2
     "table1_tiny": {"input": (2, 6, 6),
                     "layers": [("conv", 8, 3, 1, 0), ("poly2",), ("pool", 2), ("conv", 3, 3, 1, 1), ("poly2",), ("pool", 2, 1), ("fc", 2)]},
+    # one image in the rotation-packed layout: strided convolution, activation, pooling merged into the layer after it
+    "single_image_tiny": {"input": (2, 8, 8),
+                          "layers": [("conv", 3, 3, 2, 1), ("poly2",), ("pool", 2), ("fc", 4), ("poly2",), ("fc", 2)]},
+    # the same with the layer kinds and order of Table 1 at reduced width: 3x16x16 -> 4x12x12 -> 4x6x6 -> 6x4x4 -> 6x2x2 -> 16 -> 2
+    "single_image_reduced": {"input": (3, 16, 16),
+                             "layers": [("conv", 4, 5, 1, 0), ("poly2",), ("pool", 2), ("conv", 6, 3, 1, 0), ("poly2",), ("pool", 2),
+                                        ("fc", 16), ("poly2",), ("fc", 2)]},
     "cnn_tiny": {"input": (3, 16, 16),
                  "layers": [("conv", 4, 5, 2, 0), ("square",), ("conv", 4, 3, 2, 0), ("square",), ("conv", 4, 3, 1, 1),
                             ("pool", 2), ("fc", 6), ("square",), ("fc", 2)]},

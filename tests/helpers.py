@@ -65,3 +65,68 @@ def poly_mul_negacyclic_int(a, b):
             else:
                 out[k - n] -= a[i] * b[j]
     return out
+
+
+# ---------------------------------------------------------------------------
+# single-image (rotation-packed) networks: test-side planning from the oracle's definitions
+# ---------------------------------------------------------------------------
+PAPER_C2, PAPER_C1 = 0.000469841857369822, 0.500000000000008  # section 3.1, tests/golden/activation_poly_deg2.txt
+
+
+def network_stage_matrices(topology, weights):
+    """[("linear", M) | ("poly2",)]: the linear layers between two activations multiplied into one matrix (convolution and
+    pooling matrices from the oracle's definitions, fully connected layers as they are)"""
+    stages, pending = [], None
+    for (layer, (c, h, w), _), wt in zip(wl.cnn_shapes(topology), weights):
+        kind = layer[0]
+        if kind == "poly2":
+            stages += [("linear", pending), ("poly2",)]
+            pending = None
+            continue
+        if kind == "conv":
+            M = orc.conv_as_matrix(wt, h, w, layer[4], layer[3])
+        elif kind == "pool":
+            M = orc.pool_as_matrix(c, h, w, layer[1], layer[2] if len(layer) > 2 else 0)
+        elif kind == "fc":
+            M = np.asarray(wt, dtype=np.float64)
+        else:
+            raise ValueError(kind)
+        pending = M if pending is None else M @ pending
+    if pending is not None:
+        stages.append(("linear", pending))
+    return stages
+
+
+def network_float(stages, z):
+    """the same stages on a plain float vector"""
+    for st in stages:
+        z = st[1] @ z if st[0] == "linear" else PAPER_C2 * z * z + PAPER_C1 * z
+    return z
+
+
+def network_period(stages, n_slots):
+    """the slot period of the packing: the next power of two above every vector length, at most the slot count"""
+    longest = max(max(st[1].shape) for st in stages if st[0] == "linear")
+    n = 1
+    while n < longest:
+        n *= 2
+    return min(n, n_slots)
+
+
+def network_integer_stages(stages, q, level, scale, n, n_slots, encode):
+    """the stages as the oracle's packed_network takes them: encoded diagonals (scale q_{level-1}, so that the rescale
+    restores the scale) and the integer constants of the degree-2 activation from the tracked scale.  Returns
+    (stages, rotation offsets used, output level, output scale)."""
+    out, rots = [], set()
+    for st in stages:
+        if st[0] == "linear":
+            dg = orc.block_diagonals(st[1], n, n_slots)
+            out.append(("linear", {ij: {d: encode(v.astype(np.complex128), float(q[level - 1]), level) for d, v in dd.items()} for ij, dd in dg.items()}))
+            rots |= {d for dd in dg.values() for d in dd if d}
+            level -= 1
+        else:
+            s2 = scale * scale / float(q[level - 1])
+            out.append(("poly2", round(PAPER_C2 * float(q[level - 2])), round(PAPER_C1 * (s2 / scale) * float(q[level - 2]))))
+            scale = s2
+            level -= 2
+    return out, sorted(rots), level, scale

@@ -405,6 +405,64 @@ def case_packed_layer(be, shape, seed, M_float, level=None, max_rotations=None):
     ctx.close()
 
 
+def case_packed_network(be, shape, seed, topology, sigma=0.25, max_rotations=None):
+    """one image through a network in the rotation-packed layout (strided convolution and pooling as matrices, vectors that
+    may span several ciphertexts, degree-2 activations) against the oracle's schedule: every output ciphertext word for
+    word, and decrypted against the float network.  The stage matrices, the activation constants and the encoded diagonals
+    are the test's own (from the oracle's definitions) and must equal the library's plan."""
+    import helpers
+    from paper_1911_11377_amd import packed
+    probe = orc.Oracle(*shape)
+    n_slots, level, s = probe.N // 2, probe.n_q, 2.0 ** 50
+    weights = wl.cnn_weights_float(topology, seed, sigma=sigma)
+    stages = helpers.network_stage_matrices(topology, weights)
+    lib_stages = packed.stage_matrices(wl.cnn_shapes(topology), weights)
+    assert len(stages) == len(lib_stages)
+    for a, b in zip(stages, lib_stages):
+        assert a[0] == b[0] and (a[0] != "linear" or np.allclose(a[1], b[1], rtol=0, atol=1e-15)), "stage matrices differ"
+    n = helpers.network_period(stages, n_slots)
+    rots = sorted({d for st in stages if st[0] == "linear" for dd in orc.block_diagonals(st[1], n, n_slots).values() for d in dd if d})
+    M = make_material(shape, seed, rotations=tuple(rots))
+    O = M.O
+    # both sides plan from the LIBRARY's stage matrices here (they agree with the test's to rounding, and the encoder must
+    # see identical inputs for identical plaintexts)
+    ist, rots2, out_level, out_scale = helpers.network_integer_stages(lib_stages, O.q, level, s, n, n_slots, M.encode)
+    assert rots2 == rots
+    ctx = be.context(*shape)
+    check_moduli(ctx, M)
+    keys = {r: be.to_dev(M.gk[r]) for r in rots}
+    for r in rots:
+        ctx.galois_key_register(r, keys[r])
+    plans, n_lib, lvl_lib, scale_lib = packed.plan_network(ctx, wl.cnn_shapes(topology), weights, level, s, be.to_dev, encode=M.encode)
+    assert (n_lib, lvl_lib) == (n, out_level) and scale_lib == out_scale
+    for pl, st in zip(plans, ist):
+        if st[0] == "poly2":
+            assert (pl.k2, pl.k1) == (st[1], st[2]), "activation constants differ"
+        else:
+            assert {ij: sorted(dd) for ij, dd in st[1].items()} == pl.offsets, "diagonals differ"
+    C, H, W = wl.CNN_TOPOLOGIES[topology]["input"]
+    img = wl.slots_real(C * H * W, seed, "image", lo=0.0, hi=1.0).real
+    blocks = -(-img.size // n)
+    zin = np.zeros(blocks * n)
+    zin[: img.size] = img
+    xs = np.stack([M.encrypt(np.tile(zin[j * n:(j + 1) * n], n_slots // n).astype(complex), s, level, ("img", j)) for j in range(blocks)])
+    want, wl_level = O.packed_network(list(xs), ist, M.rlk, M.gk, level)
+    mr = max_rotations or packed.MAX_ROTATIONS_PER_CALL
+    ws = be.ws(packed.network_workspace_bytes(ctx, plans, level, mr))
+    res, n_out, got_level = packed.run_network(ctx, be.to_dev(xs), plans, be.to_dev(M.rlk), level, ws, stream=be.stream, max_rotations=mr)
+    assert (n_out, got_level) == (len(want), wl_level)
+    got = be.to_host(ws).reshape(-1)
+    # the result sits at a known place of the workspace: read it through the same flat view
+    off = (res.data_ptr() - ws.data_ptr()) // 8
+    got = got[off: off + n_out * 2 * got_level * O.N].reshape(n_out, 2, got_level, O.N)
+    for i in range(n_out):
+        assert np.array_equal(got[i], want[i]), "output block %d of the packed network differs from the oracle" % i
+    dec = np.concatenate([M.decrypt(got[i], out_scale, got_level).real[:n] for i in range(n_out)])
+    ref = helpers.network_float(stages, img)
+    assert np.max(np.abs(dec[: ref.size] - ref)) < 1e-3
+    ctx.close()
+
+
 def case_encode_encrypt_device(be, shape, seed, batch=3, level=None, log_scale=40, complex_slots=True, small_ws=False):
     """device-side encoding (double-precision complex inverse transform: coefficients within one unit of the oracle's
     encoder, slots back within 1e-9) and device-side encryption (integer work: bit-exact against the oracle)"""

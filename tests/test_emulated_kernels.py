@@ -210,3 +210,10 @@ def test_emulated_activation_schedule_register_tiled(be):
     """x^2 then the degree-3 polynomial at N = 2^13 with 3-prime digits: the scalar rescale reads its input one level up and
     adds onto the output buffer; workspace carved by the call sequence; every item compared"""
     pc.case_activation(be, (13, 6, 50, 3, 51, 3), seed=145, level=6, batch=3, sample=[0, 1, 2])
+
+
+def test_emulated_single_image_network(be):
+    """one image in the rotation-packed layout: strided convolution, activation, pooling merged into the next layer; with 64
+    slots the input spans two ciphertexts (block matrix), with 128 one; rotations in calls of at most 5 in the first run"""
+    pc.case_packed_network(be, (7, 8, 50, 2, 51, 2), seed=150, topology="single_image_tiny", max_rotations=5)
+    pc.case_packed_network(be, (8, 8, 50, 2, 51, 2), seed=151, topology="single_image_tiny")

@@ -382,6 +382,18 @@ def test_rotation_packed_layers_match_oracle(be):
     pc.case_packed_layer(be, (12, 4, 40, 2, 41, 2), 352, wl.weights_float((16, 16), 352, "fc"), level=3)
 
 
+@pytest.mark.parametrize("shape,topology", [
+    ((7, 8, 50, 2, 51, 2), "single_image_tiny"),     # 64 slots: the input vector spans two ciphertexts, generic kernels
+    ((13, 8, 50, 3, 51, 3), "single_image_tiny"),    # register-tiled kernels, 3-prime digits
+])
+def test_single_image_network_matches_oracle(be, shape, topology):
+    """one image through a network in the rotation-packed layout (strided convolution, degree-2 activations, pooling merged
+    into the next layer as a matrix product, vectors that may span several ciphertexts): every output word against the
+    oracle's schedule, decrypted output against the float network"""
+    announce("single-image network %s %r" % (topology, shape))
+    pc.case_packed_network(be, shape, seed=380, topology=topology)
+
+
 @pytest.mark.parametrize("shape,log_scale,batch", [
     ((4, 2, 20, 1, 21, 1), 12, 3),
     (TINY, 30, 4),

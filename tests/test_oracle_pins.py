@@ -659,6 +659,104 @@ def test_packed_convolution_decrypts_to_the_convolution():
     assert np.max(np.abs(got - direct)) < 1e-4
 
 
+def test_strided_convolution_and_pooling_matrices_match_the_layer_definitions():
+    """the matrices of the single-image packing against direct loops over the layer definitions: a stride-2 convolution
+    with zero padding, and 2x2 average pooling (plain and with a padded border)"""
+    g = wl.rng(60, "mat")
+    C, H, W, O, k, stride, pad = 2, 7, 6, 3, 3, 2, 1
+    w = g.normal(size=(O, C, k, k))
+    img = g.normal(size=(C, H, W))
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    padded = np.zeros((C, H + 2 * pad, W + 2 * pad))
+    padded[:, pad:pad + H, pad:pad + W] = img
+    direct = np.array([[[sum(w[o, c, u, v] * padded[c, y * stride + u, x * stride + v] for c in range(C) for u in range(k) for v in range(k))
+                         for x in range(Wo)] for y in range(Ho)] for o in range(O)])
+    assert np.allclose(orc.conv_as_matrix(w, H, W, pad, stride) @ img.reshape(-1), direct.reshape(-1), atol=1e-12)
+    # stride 1 is what the earlier single-layer pins use
+    assert np.array_equal(orc.conv_as_matrix(w, H, W, pad, 1), orc.conv_as_matrix(w, H, W, pad))
+    for pp in (0, 1):
+        Hp, Wp = (H + 2 * pp) // 2, (W + 2 * pp) // 2
+        padded = np.zeros((C, H + 2 * pp + 2, W + 2 * pp + 2))
+        padded[:, pp:pp + H, pp:pp + W] = img
+        pooled = np.array([[[padded[c, 2 * y:2 * y + 2, 2 * x:2 * x + 2].mean() for x in range(Wp)] for y in range(Hp)] for c in range(C)])
+        assert np.allclose(orc.pool_as_matrix(C, H, W, 2, pp) @ img.reshape(-1), pooled.reshape(-1), atol=1e-12)
+
+
+def _run_single_image(topology, shape, seed, sigma=0.25):
+    import helpers
+    probe = orc.Oracle(*shape)
+    n_slots, level, s = probe.N // 2, probe.n_q, 2.0 ** 50
+    weights = wl.cnn_weights_float(topology, seed, sigma=sigma)
+    stages = helpers.network_stage_matrices(topology, weights)
+    n = helpers.network_period(stages, n_slots)
+    # the rotation offsets are known from the matrices alone: keys first, then the encodings
+    rots = sorted({d for st in stages if st[0] == "linear" for dd in orc.block_diagonals(st[1], n, n_slots).values() for d in dd if d})
+    M = Material(*shape, seed=seed, rotations=tuple(rots))
+    O = M.O
+    ist, rots2, out_level, out_scale = helpers.network_integer_stages(stages, O.q, level, s, n, n_slots, M.encode)
+    assert rots2 == rots
+    C, H, W = wl.CNN_TOPOLOGIES[topology]["input"]
+    img = wl.slots_real(C * H * W, seed, "image", lo=0.0, hi=1.0).real
+    blocks = -(-img.size // n)
+    zin = np.zeros(blocks * n)
+    zin[: img.size] = img
+    xs = [M.encrypt(np.tile(zin[j * n:(j + 1) * n], n_slots // n).astype(complex), s, level, ("img", j)) for j in range(blocks)]
+    outs, lvl = O.packed_network(xs, ist, M.rlk, M.gk, level)
+    assert lvl == out_level
+    want = helpers.network_float(stages, img)
+    got = np.concatenate([M.decrypt(o, out_scale, lvl).real[:n] for o in outs])
+    return got, want, blocks, len(outs), len(rots)
+
+
+def test_single_image_network_decrypts_to_the_float_network():
+    """strided convolution, degree-2 activation, pooling merged into the fully connected layer after it, activation, fully
+    connected: one image in ONE ciphertext (128 slots), against the float network"""
+    got, want, n_in, n_out, n_rot = _run_single_image("single_image_tiny", (8, 8, 50, 2, 51, 2), 61)
+    assert (n_in, n_out) == (1, 1) and n_rot > 20
+    assert np.max(np.abs(want)) > 1e-3
+    assert np.max(np.abs(got[: want.size] - want)) < 1e-4 and np.max(np.abs(got[want.size:])) < 1e-4
+
+
+def test_single_image_network_with_a_vector_that_spans_two_ciphertexts():
+    """the same network with 64 slots per ciphertext: the 128 input values take two ciphertexts, the first layer is a
+    1 x 2 block matrix, every input block rotated once for the output block"""
+    got, want, n_in, n_out, _ = _run_single_image("single_image_tiny", (7, 8, 50, 2, 51, 2), 61)
+    assert (n_in, n_out) == (2, 1)
+    assert np.max(np.abs(got[: want.size] - want)) < 1e-4
+
+
+def test_block_linear_transform_with_several_output_ciphertexts():
+    """a 70 x 50 dense matrix with 32 slots per ciphertext: 2 input blocks, 3 output blocks"""
+    import helpers
+    shape = (6, 3, 50, 2, 51, 2)
+    probe = orc.Oracle(*shape)
+    n = probe.N // 2
+    Wm = wl.weights_float((70, 50), 62, "blk", sigma=0.3)
+    dg = orc.block_diagonals(Wm, n, n)
+    assert sorted(dg) == [(i, j) for i in range(3) for j in range(2)]
+    rots = sorted({d for dd in dg.values() for d in dd if d})
+    M = Material(*shape, seed=62, rotations=tuple(rots))
+    O = M.O
+    z = np.zeros(2 * n)
+    z[:50] = wl.slots_real(50, 62, "z").real
+    s = 2.0 ** 40
+    xs = [M.encrypt(z[j * n:(j + 1) * n].astype(complex), s, 3, ("z", j)) for j in range(2)]
+    pts = {ij: {d: M.encode(v.astype(complex), float(O.q[2]), 3) for d, v in dd.items()} for ij, dd in dg.items()}
+    outs = O.linear_transform_blocks(xs, pts, M.gk, 3)
+    got = np.concatenate([M.decrypt(o, s, 2).real for o in outs])
+    want = np.zeros(3 * n)
+    want[:70] = Wm @ z[:50]
+    assert np.max(np.abs(got - want)) < 1e-4
+    # one block in each direction is the single-ciphertext transform, bit for bit
+    W1 = wl.weights_float((20, 30), 63, "one", sigma=0.3)
+    d1 = orc.block_diagonals(W1, n, n)
+    assert list(d1) == [(0, 0)]
+    M1 = Material(*shape, seed=63, rotations=tuple(d for d in d1[(0, 0)] if d))
+    x = M1.encrypt(wl.slots_real(n, 63, "x"), s, 3, "x")
+    p1 = {d: M1.encode(v.astype(complex), float(M1.O.q[2]), 3) for d, v in d1[(0, 0)].items()}
+    assert np.array_equal(M1.O.linear_transform_blocks([x], {(0, 0): p1}, M1.gk, 3)[0], M1.O.linear_transform(x, p1, M1.gk, 3))
+
+
 def test_philox_known_answers():
     """Philox4x32-10 known-answer vectors published with the generator (zeros, all ones, digits of pi)"""
     assert orc.philox4x32_10([0] * 4, [0] * 2) == [0x6627E8D5, 0xE169C58D, 0xBC57AC4C, 0x9B00DBD8]
