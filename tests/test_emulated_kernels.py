@@ -60,6 +60,7 @@ def test_emulated_conv(be):
 def test_emulated_conv_matrix_cores(be):
     """two 64-tap steps, two 32-channel groups (the second mostly empty), two 64-word blocks, zero padding, 51-bit prime"""
     pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=115, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)
+    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=116, Cin=4, H=5, W=5, Oc=8, kh=5, stride=1, pad=0)    # 100 taps
 
 
 def test_emulated_pool_and_network(be):

@@ -94,6 +94,9 @@ def test_conv_matrix_cores_shapes(be):
     pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=312, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)
     announce("conv matrix cores N=2^13")
     pc.case_conv(be, (13, 3, 50, 0, 51, 1), seed=313, Cin=8, H=3, W=4, Oc=40, kh=3, stride=1, pad=1)
+    announce("conv matrix cores, 100 taps and 27 taps")
+    pc.case_conv(be, (8, 2, 50, 0, 51, 1), seed=314, Cin=4, H=6, W=5, Oc=17, kh=5, stride=1, pad=0)
+    pc.case_conv(be, (8, 2, 50, 0, 51, 1), seed=315, Cin=3, H=4, W=4, Oc=9, kh=3, stride=1, pad=1)
 
 
 def test_conv_at_layer_shape_slice(be):
