@@ -49,7 +49,9 @@ extern "C" {
 #define CKKSMI_K_ENCODE 26          /* device-side encoding: scatter, complex inverse transform, rounding */
 #define CKKSMI_K_ENCRYPT 27         /* device-side encryption: residues of the small polynomials, combination with the key */
 #define CKKSMI_K_CONV_COLS_TAIL 28  /* ModDown followed by rescale as one conversion (the strict sequence's bits) */
-#define CKKSMI_K_COUNT 29
+#define CKKSMI_K_MAC_MFMA_RES 29    /* the same for layers of few taps: weight digits resident in LDS, several positions per workgroup */
+#define CKKSMI_K_MAC_MFMA_STRIP 30  /* ... and a narrow window: four neighbouring positions share a strip of the image staged in LDS */
+#define CKKSMI_K_COUNT 31
 int ckksmi_profile_enable(ckksmi_ctx *ctx, int on);
 int ckksmi_profile_read(ckksmi_ctx *ctx, int kernel_class, double *total_ms, long long *launches, double *units);
 /* name of the kernel that class runs as in this context (the transforms have size-specific kernels) */
@@ -58,7 +60,8 @@ const char *ckksmi_kernel_class_name(const ckksmi_ctx *ctx, int kernel_class);
 
 /* Launch-shape knobs (benchmarks and tests; the defaults suit a full GPU).
  * CKKSMI_TUNE_TARGET_WGS: number of workgroups a transform launch aims for before its workgroups start looping over
- * the items of the batch (default 8192; a small value makes even a small batch exercise the item loops). */
+ * the items of the batch (default 8192; a small value makes even a small batch exercise the item loops).  The
+ * matrix-core multiply-accumulate aims for half of it before a workgroup walks several output positions. */
 #define CKKSMI_TUNE_TARGET_WGS 0
 int ckksmi_tune(ckksmi_ctx *ctx, int knob, int value);
 

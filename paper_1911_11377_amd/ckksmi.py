@@ -92,7 +92,7 @@ SIGNATURES = {
     "ckksmi_tune": [VP, C.c_int, C.c_int],
 }
 _RESTYPES = {"ckksmi_ctx_destroy": None, "ckksmi_strerror": C.c_char_p, "ckksmi_kernel_class_name": C.c_char_p}
-K_COUNT = 29
+K_COUNT = 31
 
 _LIBS = {}
 

@@ -1360,19 +1360,43 @@ extern "C" int ckksmi_rotate_hoisted(ckksmi_ctx *c, const uint64_t *a, const int
 }
 
 namespace {
-// Which multiply-accumulate kernel a layer shape can use, and the workspace the matrix-core one needs.
+// Which multiply-accumulate kernel a layer shape can use, and the workspace the matrix-core ones need.
 struct MacShape {
     bool mfma_ok;
-    int Kb, Mg;  // 64-tap steps, 32-channel groups
-    size_t afrag_bytes, mfma_bytes;
+    bool resident;  // few taps: the kernel that keeps the weight digits in LDS
+    bool strip;     // ... and a narrow window: four positions (TY x TX) share a strip of the image staged in LDS
+    int TY, TX, SR, SC;  // strip rows per channel, pixels per strip row
+    int quad;       // its last step covers at most 16 taps, as a quad step
+    int Kb, Mg;     // steps (64 taps, or the quad step), 32-channel groups
+    size_t afrag_bytes, taps_bytes, off_bytes, tapoff_bytes, wsum_bytes, mfma_bytes;
 };
-MacShape mac_shape(const ckksmi_ctx *c, int C, int O, int kh, int kw, int level) {
+MacShape mac_shape(const ckksmi_ctx *c, int C, int O, int kh, int kw, int stride, int out_rows, int Wo, int level) {
     MacShape s;
     const long long K = (long long)C * kh * kw;
     s.Kb = (int)((K + 63) / 64);
+    s.resident = s.Kb <= MM_RES_STEPS;
+    s.quad = (s.resident && K % 64 != 0 && K % 64 <= 16) ? 1 : 0;
+    // the four waves' positions: 2 x 2 or 1 x 4, whichever leaves fewer waves without a position (then the smaller strip)
+    s.strip = false;
+    s.TY = 1; s.TX = MM_STRIP_POS; s.SR = kh; s.SC = kw + (MM_STRIP_POS - 1) * stride;
+    if (s.Kb <= MM_STRIP_STEPS && c->N >= 16 && kh + stride < 256 && kw + 3LL * stride < 65536) {
+        long long best = -1;
+        for (int ty = 1; ty <= 2; ty++) {
+            const int tx = MM_STRIP_POS / ty;
+            const long long sr = kh + (ty - 1) * stride, sc = kw + (tx - 1) * stride, ln = (long long)C * sr * sc;
+            if (ln > MM_STRIP_LINES) continue;
+            const long long slots = (long long)((out_rows + ty - 1) / ty) * ((Wo + tx - 1) / tx);
+            const long long cost = slots * 1024 + ln;
+            if (best < 0 || cost < best) { best = cost; s.strip = true; s.TY = ty; s.TX = tx; s.SR = (int)sr; s.SC = (int)sc; }
+        }
+    }
     s.Mg = (O + MM_CH - 1) / MM_CH;
-    s.afrag_bytes = (size_t)level * s.Kb * s.Mg * MM_MB * MM_DIG * 64 * 16;
-    s.mfma_bytes = s.afrag_bytes + 2 * (size_t)s.Kb * 64 * sizeof(TapEnt);
+    s.afrag_bytes = (size_t)level * s.Kb * s.Mg * MM_FRAG * 16;
+    s.taps_bytes = 2 * (size_t)s.Kb * 64 * sizeof(TapEnt);
+    s.off_bytes = (size_t)s.Kb * 64 * sizeof(unsigned long long);
+    s.tapoff_bytes = (size_t)s.Kb * 64 * sizeof(unsigned);
+    s.wsum_bytes = (size_t)level * s.Mg * MM_CH * sizeof(double);
+    s.mfma_bytes = s.afrag_bytes + s.taps_bytes + s.off_bytes + s.tapoff_bytes + s.wsum_bytes;
     // below 8 output channels most of a 32-channel group would multiply zeros: the vector kernel is faster there
     s.mfma_ok = c->N >= MM_WORDS && O >= 8 && K <= MM_KMAX - 63;
     return s;
@@ -1397,22 +1421,71 @@ extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const i
     if (first <= last && (first < in_row0 || last >= (long long)in_row0 + in_rows)) return CKKSMI_EINVAL;
     const size_t n_weights = (size_t)O * C * kh * kw;
     Guard g(c);
-    MacShape ms = mac_shape(c, C, O, kh, kw, level);
+    MacShape ms = mac_shape(c, C, O, kh, kw, stride, out_rows, Wo, level);
     if (ms.mfma_ok && ws_bytes >= ms.mfma_bytes && (size_t)C * in_rows * W < MM_TAP_DELTA_MAX && kh <= MM_TAP_KMAX && kw <= MM_TAP_KMAX) {
-        const size_t real = (size_t)out_rows * Wo * ms.Mg * (c->N / MM_WORDS) * 2 * level;
+        const unsigned positions = (unsigned)(out_rows * Wo);
+        // resident kernel: each workgroup takes `run` positions of a 64-word block, nrun workgroups share the block;
+        // strip kernel: `run` tiles (four positions of a row) of a 16-word block
+        const int spr = (Wo + ms.TX - 1) / ms.TX;
+        const unsigned units_per_block = ms.strip ? (unsigned)(((out_rows + ms.TY - 1) / ms.TY) * spr) : positions;
+        // long runs amortise the weight digits and keep the staging pipeline full (64 tiles, or 8 positions where every
+        // wave loads its own words); short ones where the layer would otherwise give the chip too few workgroups
+        const size_t blocks = (size_t)(c->N / (ms.strip ? 16 : MM_WORDS)) * 2 * level;
+        const size_t target = (size_t)std::max(1, c->ntt_target_wgs / 2);
+        const unsigned want_nrun = (unsigned)std::min<size_t>(units_per_block, (target + blocks - 1) / blocks);
+        const unsigned run = std::max(1u, std::min(ms.strip ? 64u : 8u, units_per_block / std::max(1u, want_nrun)));
+        const unsigned nrun = (units_per_block + run - 1) / run;
+        const size_t real = ms.strip      ? (size_t)nrun * (c->N / 16) * 2 * level
+                            : ms.resident ? (size_t)nrun * (c->N / MM_WORDS) * 2 * level
+                                          : (size_t)positions * ms.Mg * (c->N / MM_WORDS) * 2 * level;
         const size_t xdim = (real + 7) / 8 * 8;
         if (xdim > 0x7fffffffu) return CKKSMI_EUNSUPPORTED;
-        v4i *afrag = (v4i *)ws;
-        TapEnt *taps = (TapEnt *)((char *)ws + ms.afrag_bytes);
-        const size_t prep = std::max(ms.afrag_bytes / 16, (size_t)ms.Kb * 64);
+        char *wp = (char *)ws;  // every part is a multiple of 16 bytes
+        v4i *afrag = (v4i *)wp; wp += ms.afrag_bytes;
+        TapEnt *taps = (TapEnt *)wp; wp += ms.taps_bytes;
+        unsigned long long *off64 = (unsigned long long *)wp; wp += ms.off_bytes;
+        unsigned *tapoff = (unsigned *)wp; wp += ms.tapoff_bytes;
+        double *wsum = (double *)wp;
+        const size_t prep = std::max(std::max(ms.afrag_bytes / 16, (size_t)ms.Kb * 64), (size_t)level * ms.Mg * MM_CH);
         KL(c, CKKSMI_K_MACPREP_MFMA, 1, mac_prepare_mfma_kernel, dim3(ew_blocks(prep)), dim3(EW_THREADS), S(stream), (const long long *)w, afrag, taps,
-                      c->d_mod, level, O, C, kh, kw, in_rows, W, ms.Kb, ms.Mg);
+                      off64, tapoff, ms.SR, ms.SC, wsum, c->d_mod, level, c->logN, O, C, kh, kw, in_rows, W, ms.Kb, ms.Mg, ms.quad);
         MacMfmaArgs A;
-        A.in = (const u64d *)in; A.out = (u64d *)out; A.afrag = afrag; A.taps = taps; A.modc = c->d_mod; A.pow24 = c->d_pow24;
-        A.logN = c->logN; A.level = level; A.H = H; A.W = W; A.O = O; A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.Wo = Wo;
-        A.in_row0 = in_row0; A.in_rows = in_rows; A.out_row0 = out_row0; A.out_rows = out_rows; A.Kb = ms.Kb; A.Mg = ms.Mg;
-        A.positions = (unsigned)(out_rows * Wo); A.total_wgs = xdim; A.real_wgs = real;
-        KL(c, CKKSMI_K_MAC_MFMA, (double)O * out_rows * Wo * 2 * level, conv_mac_mfma_kernel, dim3((unsigned)xdim), dim3(256), S(stream), A);
+        A.in = (const u64d *)in; A.out = (u64d *)out; A.afrag = afrag; A.taps = taps; A.off64 = off64; A.tapoff = tapoff; A.wsum = wsum; A.modc = c->d_mod;
+        A.pow24 = c->d_pow24;
+        A.logN = c->logN; A.level = level; A.C = C; A.H = H; A.W = W; A.O = O; A.kh = kh; A.kw = kw; A.stride = stride; A.pad = pad; A.Wo = Wo;
+        A.in_row0 = in_row0; A.in_rows = in_rows; A.out_row0 = out_row0; A.out_rows = out_rows; A.Kb = ms.Kb; A.Mg = ms.Mg; A.quad = ms.quad;
+        A.positions = positions; A.nrun = nrun; A.run = run; A.TY = ms.TY; A.TX = ms.TX; A.SR = ms.SR; A.SC = ms.SC; A.spr = spr; A.total_wgs = xdim; A.real_wgs = real;
+        const double units = (double)O * out_rows * Wo * 2 * level;
+        if (ms.strip) {
+            const dim3 grid((unsigned)xdim), block(256);
+#define MAC_STRIP(KB, Q)                                                                                                            \
+    do {                                                                                                                            \
+        if (ms.TY == 1) KL(c, CKKSMI_K_MAC_MFMA_STRIP, units, (conv_mac_mfma_strip_kernel<KB, Q, 1>), grid, block, S(stream), A);   \
+        else KL(c, CKKSMI_K_MAC_MFMA_STRIP, units, (conv_mac_mfma_strip_kernel<KB, Q, 2>), grid, block, S(stream), A);              \
+    } while (0)
+            switch (ms.Kb * 2 + ms.quad) {
+                case 2: MAC_STRIP(1, false); break;
+                case 3: MAC_STRIP(1, true); break;
+                case 4: MAC_STRIP(2, false); break;
+                default: MAC_STRIP(2, true); break;
+            }
+#undef MAC_STRIP
+        } else if (ms.resident) {
+            const dim3 grid((unsigned)xdim), block(256);
+#define MAC_RES(KB, Q) KL(c, CKKSMI_K_MAC_MFMA_RES, units, (conv_mac_mfma_resident_kernel<KB, Q>), grid, block, S(stream), A)
+            switch (ms.Kb * 2 + ms.quad) {
+                case 2: MAC_RES(1, false); break;
+                case 3: MAC_RES(1, true); break;
+                case 4: MAC_RES(2, false); break;
+                case 5: MAC_RES(2, true); break;
+                case 6: MAC_RES(3, false); break;
+                case 7: MAC_RES(3, true); break;
+                case 8: MAC_RES(4, false); break;
+                default: MAC_RES(4, true); break;
+            }
+#undef MAC_RES
+        } else
+            KL(c, CKKSMI_K_MAC_MFMA, units, conv_mac_mfma_kernel, dim3((unsigned)xdim), dim3(256), S(stream), A);
         return g.rc();
     }
     if (ws_bytes < n_weights * level * sizeof(WMul)) return CKKSMI_EWORKSPACE;
@@ -1432,7 +1505,7 @@ extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const i
 extern "C" int ckksmi_conv2d_workspace_bytes(const ckksmi_ctx *c, int C, int O, int kh, int kw, int level, size_t *bytes) {
     if (!c || !bytes || C < 1 || O < 1 || kh < 1 || kw < 1) return CKKSMI_EINVAL;
     if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
-    const MacShape ms = mac_shape(c, C, O, kh, kw, level);
+    const MacShape ms = mac_shape(c, C, O, kh, kw, 1, 1, 1, level);
     const size_t valu = (size_t)O * C * kh * kw * level * sizeof(WMul);
     *bytes = ms.mfma_ok ? std::max(valu, ms.mfma_bytes) : valu;
     return CKKSMI_OK;
@@ -1509,7 +1582,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "elementwise kernels", "modup_cols_kernel", "modup_cols_kernel", "rows_inner_kernel",
                                                 "rows_final_kernel", "modup_cols_kernel", "conv_mac_mfma_kernel", "mac_prepare_mfma_kernel", "ntt_wg_kernel", "tensor_rows_kernel",
                                                 "axpy_limb_kernel", "modup_cols_kernel", "inner_product_hoisted_tile_kernel", "automorphism_bcast_kernel",
-                                                "encoding kernels", "encryption kernels", "modup_cols_kernel"};
+                                                "encoding kernels", "encryption kernels", "modup_cols_kernel", "conv_mac_mfma_resident_kernel", "conv_mac_mfma_strip_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && kernel_class == CKKSMI_K_INNER_HOISTED && !hoisted_tile_ok(c, c->beta_top)) return "inner_product_hoisted_kernel";
     if (c && c->logN >= 13 && c->logN <= 16) {

@@ -769,6 +769,15 @@ def case_activation(be, shape, seed, level, batch, sample, log_scale=50, decrypt
     ctx.close()
 
 
+def mfma_kernel_name(Cin, kh, kw, stride):
+    """which matrix-core kernel a layer runs on.  At most 128 taps and a window block (2 x 2 or 1 x 4 positions) of at most
+    192 lines: four positions share a staged strip; at most 256 taps: weight digits resident in LDS; otherwise they stream"""
+    taps = Cin * kh * kw
+    if taps <= 128 and min(Cin * (kh + stride) * (kw + stride), Cin * kh * (kw + 3 * stride)) <= 192:
+        return "conv_mac_mfma_strip_kernel"
+    return "conv_mac_mfma_resident_kernel" if taps <= 256 else "conv_mac_mfma_kernel"
+
+
 def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
     M = make_material(shape, seed)
     O = M.O
@@ -793,7 +802,8 @@ def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
         got = be.to_host(out).reshape(Oc, Ho, Wo, 2, level, O.N)
         ran = ctx.profile_read()
         ctx.profile_enable(False)
-        assert ("conv_mac_mfma_kernel" in ran) == (which == "auto" and mfma_shape), (which, list(ran))
+        mfma_name = mfma_kernel_name(Cin, kh, kh, stride)
+        assert (mfma_name in ran) == (which == "auto" and mfma_shape), (which, list(ran))
         assert np.array_equal(got, want), "conv MAC (%s) differs from the oracle" % which
     # FC: flat features
     F = Cin * H

@@ -97,6 +97,12 @@ def test_conv_matrix_cores_shapes(be):
     announce("conv matrix cores, 100 taps and 27 taps")
     pc.case_conv(be, (8, 2, 50, 0, 51, 1), seed=314, Cin=4, H=6, W=5, Oc=17, kh=5, stride=1, pad=0)
     pc.case_conv(be, (8, 2, 50, 0, 51, 1), seed=315, Cin=3, H=4, W=4, Oc=9, kh=3, stride=1, pad=1)
+    announce("conv matrix cores, workgroups that walk several tiles / positions")
+    with be.tuned(2):
+        pc.case_conv(be, (7, 2, 50, 0, 51, 1), seed=316, Cin=3, H=9, W=8, Oc=33, kh=5, stride=1, pad=1)    # 2 x 2 blocks, 35 positions
+        pc.case_conv(be, (7, 2, 50, 0, 51, 1), seed=317, Cin=2, H=3, W=13, Oc=8, kh=3, stride=1, pad=0)    # 1 x 4 blocks, three tiles
+        pc.case_conv(be, (7, 2, 50, 0, 51, 1), seed=318, Cin=7, H=4, W=16, Oc=9, kh=3, stride=3, pad=1)    # weight digits resident, six positions
+        pc.case_conv(be, (7, 2, 50, 0, 51, 1), seed=319, Cin=29, H=3, W=3, Oc=8, kh=3, stride=1, pad=1)    # 261 taps: streaming kernel
 
 
 def test_conv_at_layer_shape_slice(be):
@@ -471,7 +477,7 @@ def test_conv_layer_full_size_sampled(be):
     ctx.conv2d_mac(x, dw, Cin, H, W, Oc, kh, kh, stride, 0, mac, L, ws)
     ctx.rescale(mac, out, L, Oc * Ho * Ho, ws)
     torch.cuda.synchronize()
-    assert "conv_mac_mfma_kernel" in ctx.profile_read()
+    assert "conv_mac_mfma_strip_kernel" in ctx.profile_read()  # 75 taps: one full step and a quad step, windows shared through LDS
     ctx.profile_enable(False)
     for o, oy, ox in ((0, 0, 0), (31, 13, 13), (17, 6, 9), (8, 13, 0)):
         announce("oracle for output (%d,%d,%d)" % (o, oy, ox))
