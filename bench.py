@@ -160,6 +160,16 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
                               "what": "square then degree-3 polynomial, 3 HMult+relin+rescale + 2 scalar rescales per ciphertext, level 24 -> 21"}
     del y, o3, wsa
 
+    # rotation on the main shape: automorphism + key switch with one Galois key (the evaluation key's buffer stands in:
+    # uniform residues of the same shape), batch 64 at level 24
+    ctx.galois_key_register(1, evk)
+    orot = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda:0")
+    wrot = torch.empty(ctx.workspace_bytes(ckksmi.OP_ROTATE, L, B) // 8, dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: ctx.rotate(a, [1] * B, orot, L, B, wrot), 5)
+    out["rotate_2e16"] = {"ops_per_s": round(B / (ms * 1e-3), 1), "ms": round(ms, 3),
+                          "what": "HRot by one slot, batch 64, level 24 (ModUp, inner product, ModDown: no tensor, no rescale)"}
+    del orot, wrot
+
     # the same product with one division by P*q_last instead of ModDown followed by rescale (different output bits:
     # a separate operation, not the headline one)
     om = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
@@ -193,6 +203,31 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     out["sum_of_4_products_2e16"] = {"sums_per_s": round(B / (ms * 1e-3), 1), "products_per_s": round(B * terms / (ms * 1e-3), 1), "ms": round(ms, 3),
                                      "what": "sum of 4 HMult tensors, ONE key switch and rescale, batch 64, level 24 -> 23"}
     del at, os_
+
+    # the tiny shape (N = 2^12, 3x40-bit + special prime, batch 16): launch-bound, so also as one captured graph
+    p1 = wl.PRESETS["tiny"]
+    c1 = ckksmi.Context(p1.logN, p1.n_q, p1.q_bits, p1.k, p1.special_bits, p1.alpha, device=0)
+    a1 = uniform_residues(torch, c1.q, (p1.batch, 2), p1.N, gen)
+    k1 = uniform_residues(torch, c1.moduli, (c1.beta_top, 2), p1.N, gen)
+    o1 = torch.empty((p1.batch, 2, p1.n_q - 1, p1.N), dtype=torch.int64, device="cuda:0")
+    w1 = torch.empty(c1.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, p1.n_q, p1.batch) // 8, dtype=torch.int64, device="cuda:0")
+    step1 = lambda: c1.hmul_relin_rescale(a1, a1, k1, o1, p1.n_q, p1.batch, w1)
+    ms_eager = timed(torch, step1, 50)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step1()
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(10):
+            step1()
+    ms_graph = timed(torch, graph.replay, 5) / 10
+    out["hmul_relin_rescale_2e12"] = {"ops_per_s": round(p1.batch / (ms_eager * 1e-3), 1), "ms": round(ms_eager, 4),
+                                      "ops_per_s_graph": round(p1.batch / (ms_graph * 1e-3), 1), "ms_graph": round(ms_graph, 4),
+                                      "what": "tiny shape, batch 16, level 3; the second figure replays ten steps captured in one graph"}
+    del a1, k1, o1, w1, graph
+    c1.close()
 
     # N = 2^14, 8x50-bit + special prime: batch 256, HMult+relin+rescale and rotations by 8 random offsets
     p2 = wl.PRESETS["hmul_rot_2e14"]

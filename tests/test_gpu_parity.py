@@ -561,6 +561,47 @@ def test_activation_schedule_full_size_sampled(be):
                        expect_kernels=("modup_cols_kernel<4, 4, 3>", "modup_cols_kernel<4, 1, 1>", "tensor_rows_kernel"))
 
 
+def test_step_replays_from_a_captured_graph(be):
+    """HMult + relinearise + rescale enqueues kernels only (no allocation, no memset, no synchronisation): captured into a
+    graph on a side stream and replayed with fresh inputs in the same buffers, every replay gives the eager call's words,
+    and the first the oracle's"""
+    import torch
+
+    announce("graph capture and replay")
+    shape, level, batch = (13, 7, 50, 3, 51, 3), 7, 2
+    M = pc.make_material(shape, 330)
+    O = M.O
+    ctx = be.context(*shape)
+    evk = be.to_dev(M.rlk)
+    xs = [wl.uniform_limbs(O.q[:level], O.N, 330 + r, "graph.x", lead=(batch, 2)) for r in range(3)]
+    ys = [wl.uniform_limbs(O.q[:level], O.N, 330 + r, "graph.y", lead=(batch, 2)) for r in range(3)]
+    da, db = be.to_dev(xs[0]), be.to_dev(ys[0])
+    out, ref = be.empty(batch, 2, level - 1, O.N), be.empty(batch, 2, level - 1, O.N)
+    ws = be.ws(ctx.workspace_bytes(ckksmi.OP_HMUL_RELIN_RESCALE, level, batch))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx.hmul_relin_rescale(da, db, evk, out, level, batch, ws)  # warm-up outside the capture
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        ctx.hmul_relin_rescale(da, db, evk, out, level, batch, ws)
+    for r in range(3):
+        da.copy_(be.to_dev(xs[r]))
+        db.copy_(be.to_dev(ys[r]))
+        out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ctx.hmul_relin_rescale(da, db, evk, ref, level, batch, ws)  # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), "replay %d differs from the eager call" % r
+        if r == 0:
+            want = np.stack([O.hmul_relin_rescale(xs[0][i], ys[0][i], M.rlk, level) for i in range(batch)])
+            assert np.array_equal(be.to_host(out).reshape(want.shape), want), "replayed step differs from the oracle"
+    ctx.close()
+
+
 def test_edge_cases(be):
     announce("edge cases")
     ctx = be.context(*TINY)
