@@ -137,6 +137,35 @@ def timed(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
+def conv_layer_workload(torch, ckksmi, wl, gen):
+    """conv layer, slots-as-batch: N = 2^15, 16x50-bit, 3x32x32 pixel ciphertexts (16384 images), 3 -> 32 channels 5x5
+    stride 2 (multiply-accumulate on the matrix cores), then the rescale of the 6272 output ciphertexts"""
+    out = {}
+    p3 = wl.PRESETS["conv_2e15"]
+    c3 = ckksmi.Context(p3.logN, p3.n_q, p3.q_bits, p3.k, p3.special_bits, p3.alpha, device=0)
+    L, N = p3.n_q, p3.N
+    Cin, H, W, O, kh, stride = 3, 32, 32, 32, 5, 2
+    Ho = (H - kh) // stride + 1
+    xin = uniform_residues(torch, c3.q, (Cin * H * W, 2), N, gen)
+    wts = torch.from_numpy(__import__("numpy").rint(wl.weights_float((O, Cin, kh, kh), 3) * c3.q[L - 1]).astype("int64")).to("cuda:0")
+    co = torch.empty((O * Ho * Ho, 2, L, N), dtype=torch.int64, device="cuda:0")
+    cr = torch.empty((O * Ho * Ho, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
+    wm = torch.empty(c3.conv2d_workspace_bytes(Cin, O, kh, kh, L) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    wr = torch.empty(c3.workspace_bytes(ckksmi.OP_RESCALE, L, 256) // 8, dtype=torch.int64, device="cuda:0")
+    ms_mac = timed(torch, lambda: c3.conv2d_mac(xin, wts, Cin, H, W, O, kh, kh, stride, 0, co, L, wm), 1)
+    ms_rs = timed(torch, lambda: c3.rescale(co, cr, L, O * Ho * Ho, wr), 1)
+    mac_count = float(O) * Ho * Ho * Cin * kh * kh * 2 * L * N
+    out["conv_layer_2e15"] = {"encrypted_images_per_s": round((N // 2) / ((ms_mac + ms_rs) * 1e-3), 1), "ms_mac": round(ms_mac, 2),
+                              "ms_rescale": round(ms_rs, 2), "word_macs_per_s": round(mac_count / (ms_mac * 1e-3), 0),
+                              # matrix cores: 49 int8 multiply-accumulates (7 x 7 base-256 digits) per word MAC, 2 ops each, against
+                              # the 5.0 POP/s dense int8 peak; only the layer's real taps are counted, not the padding to 64
+                              "mfma_frac": round(mac_count * 49 * 2 / (ms_mac * 1e-3) / INT8_PEAK_OPS, 4),
+                              "what": "3x32x32 pixel ciphertexts -> 32x14x14, 5x5 stride 2, ptxt x ct MAC + rescale, 16384 images per pass"}
+    del xin, co, cr, wm, wr
+    c3.close()
+    return out
+
+
 def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     """the other rows of the hot path, each timed on its own workload shape (uniform residues, resident in HBM)"""
     from paper_1911_11377_amd import activation
@@ -300,29 +329,7 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     del net_keys, evk_s, xin_s, wsn, plans
     cs.close()
 
-    # conv layer, slots-as-batch: N = 2^15, 16x50-bit, 3x32x32 pixel ciphertexts (16384 images), 3 -> 32 channels 5x5 stride 2, then rescale
-    p3 = wl.PRESETS["conv_2e15"]
-    c3 = ckksmi.Context(p3.logN, p3.n_q, p3.q_bits, p3.k, p3.special_bits, p3.alpha, device=0)
-    L, N = p3.n_q, p3.N
-    Cin, H, W, O, kh, stride = 3, 32, 32, 32, 5, 2
-    Ho = (H - kh) // stride + 1
-    xin = uniform_residues(torch, c3.q, (Cin * H * W, 2), N, gen)
-    wts = torch.from_numpy(__import__("numpy").rint(wl.weights_float((O, Cin, kh, kh), 3) * c3.q[L - 1]).astype("int64")).to("cuda:0")
-    co = torch.empty((O * Ho * Ho, 2, L, N), dtype=torch.int64, device="cuda:0")
-    cr = torch.empty((O * Ho * Ho, 2, L - 1, N), dtype=torch.int64, device="cuda:0")
-    wm = torch.empty(c3.conv2d_workspace_bytes(Cin, O, kh, kh, L) // 8 + 1, dtype=torch.int64, device="cuda:0")
-    wr = torch.empty(c3.workspace_bytes(ckksmi.OP_RESCALE, L, 256) // 8, dtype=torch.int64, device="cuda:0")
-    ms_mac = timed(torch, lambda: c3.conv2d_mac(xin, wts, Cin, H, W, O, kh, kh, stride, 0, co, L, wm), 1)
-    ms_rs = timed(torch, lambda: c3.rescale(co, cr, L, O * Ho * Ho, wr), 1)
-    mac_count = float(O) * Ho * Ho * Cin * kh * kh * 2 * L * N
-    out["conv_layer_2e15"] = {"encrypted_images_per_s": round((N // 2) / ((ms_mac + ms_rs) * 1e-3), 1), "ms_mac": round(ms_mac, 2),
-                              "ms_rescale": round(ms_rs, 2), "word_macs_per_s": round(mac_count / (ms_mac * 1e-3), 0),
-                              # matrix cores: 49 int8 multiply-accumulates (7 x 7 base-256 digits) per word MAC, 2 ops each, against
-                              # the 5.0 POP/s dense int8 peak; only the layer's real taps are counted, not the padding to 64
-                              "mfma_frac": round(mac_count * 49 * 2 / (ms_mac * 1e-3) / INT8_PEAK_OPS, 4),
-                              "what": "3x32x32 pixel ciphertexts -> 32x14x14, 5x5 stride 2, ptxt x ct MAC + rescale, 16384 images per pass"}
-    del xin, co, cr, wm, wr
-    c3.close()
+    out.update(conv_layer_workload(torch, ckksmi, wl, gen))
     return out
 
 
@@ -522,6 +529,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the plain transform sweeps (keeps a profile to the timed steps)")
+    ap.add_argument("--conv-only", action="store_true", help="run the conv layer workload (N=2^15) alone and print its figures: for profiles of its kernels")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (rotation at N=2^14, conv layer at N=2^15, activation schedule)")
     ap.add_argument("--no-cnn", action="store_true", help="skip the two full-size networks in strips (about a minute of GPU time, up to 200 GB of HBM)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -539,6 +547,11 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.conv_only:
+        g3 = torch.Generator(device="cuda:0")
+        g3.manual_seed(wl.BASE_SEED + 3)
+        print(json.dumps({"extras": conv_layer_workload(torch, ckksmi, wl, g3)}))
+        return
     p = wl.PRESETS["act_2e16"]
     level, batch, N = p.n_q, p.batch, p.N
     ctx = ckksmi.Context(p.logN, p.n_q, p.q_bits, p.k, p.special_bits, p.alpha, device=0)
