@@ -1410,6 +1410,7 @@ extern "C" int ckksmi_conv2d_mac_rows(ckksmi_ctx *c, const uint64_t *in, const i
     if (!dev_ok(c)) return CKKSMI_EDEVICE;
     if (level < 1 || level > c->n_q) return CKKSMI_ELEVEL;
     if (!in || !w || !out || !ws || in == out) return CKKSMI_EINVAL;
+    if (!al16(in) || !al16(out) || !al16(ws)) return CKKSMI_EINVAL;
     if (C < 1 || H < 1 || W < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0) return CKKSMI_EINVAL;
     if (H + 2 * pad < kh || W + 2 * pad < kw) return CKKSMI_EINVAL;
     const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;

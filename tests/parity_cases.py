@@ -778,7 +778,7 @@ def mfma_kernel_name(Cin, kh, kw, stride):
     return "conv_mac_mfma_resident_kernel" if taps <= 256 else "conv_mac_mfma_kernel"
 
 
-def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
+def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None, rows_check=True, fc_check=True):
     M = make_material(shape, seed)
     O = M.O
     ctx = be.context(*shape)
@@ -805,6 +805,22 @@ def case_conv(be, shape, seed, Cin, H, W, Oc, kh, stride, pad, level=None):
         mfma_name = mfma_kernel_name(Cin, kh, kh, stride)
         assert (mfma_name in ran) == (which == "auto" and mfma_shape), (which, list(ran))
         assert np.array_equal(got, want), "conv MAC (%s) differs from the oracle" % which
+    # the same layer in strips of output rows, each strip handed only the input rows its windows touch
+    ws = be.ws(ctx.conv2d_workspace_bytes(Cin, Oc, kh, kh, level))
+    cut = max(1, Ho // 2)
+    for r0, r1 in ((0, cut), (cut, Ho)):
+        if r0 >= r1 or not rows_check:
+            continue
+        i0 = max(0, r0 * stride - pad)
+        i1 = min(H, (r1 - 1) * stride - pad + kh)
+        strip = be.to_dev(np.ascontiguousarray(x[:, i0:i1]))
+        outs = be.empty(Oc, r1 - r0, Wo, 2, level, O.N)
+        ctx.conv2d_mac_rows(strip, dw, Cin, H, W, Oc, kh, kh, stride, pad, i0, i1 - i0, r0, r1 - r0, outs, level, ws, stream=be.stream)
+        got = be.to_host(outs).reshape(Oc, r1 - r0, Wo, 2, level, O.N)
+        assert np.array_equal(got, want[:, r0:r1]), "conv MAC in strips of rows differs from the oracle (rows %d..%d)" % (r0, r1)
+    if not fc_check:
+        ctx.close()
+        return
     # FC: flat features
     F = Cin * H
     xf = x[:, :, 0].reshape(F, 2, level, O.N)

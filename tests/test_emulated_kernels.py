@@ -58,21 +58,20 @@ def test_emulated_conv(be):
 
 
 def test_emulated_conv_matrix_cores(be):
-    """two 64-tap steps, two 32-channel groups (the second mostly empty), two 64-word blocks, zero padding, 51-bit prime"""
-    pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=115, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)
-    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=116, Cin=4, H=5, W=5, Oc=8, kh=5, stride=1, pad=0)    # 100 taps
+    """the three matrix-core kernels: strips shared by 2 x 2 and 1 x 4 positions, weight digits resident, weight digits
+    streaming; full and quad steps, two channel groups (the second mostly empty), zero padding, a 51-bit prime, strips of rows"""
+    pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=115, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)     # 75 taps: full + quad step
+    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=116, Cin=4, H=5, W=5, Oc=8, kh=5, stride=1, pad=0, rows_check=False)    # 100 taps
+    # 261 taps: more steps than stay in LDS, the streaming kernel; its FC part has 87 taps (two full steps)
+    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=117, Cin=29, H=3, W=3, Oc=8, kh=3, stride=1, pad=1, rows_check=False)
     # one output row of five positions: the four waves take 1 x 4 positions (two tiles, three waves without a position)
-    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=119, Cin=2, H=3, W=7, Oc=8, kh=3, stride=1, pad=0)
+    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=119, Cin=2, H=3, W=7, Oc=8, kh=3, stride=1, pad=0, fc_check=False)
     # a workgroup walks several tiles / positions: the double-buffered strip, the request for the next position's words
     with be.tuned(2):
-        pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=120, Cin=3, H=9, W=8, Oc=33, kh=5, stride=1, pad=1)    # 2 x 2 blocks, 35 positions
-        pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=121, Cin=2, H=3, W=13, Oc=8, kh=3, stride=1, pad=0)    # 1 x 4 blocks, three tiles
-        pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=122, Cin=7, H=4, W=16, Oc=9, kh=3, stride=3, pad=1)    # resident, six positions
-    # 7 x 3 x 3 = 63 taps at stride 3: the strip (7*3*12 lines) is too wide to stage, weight digits resident; six output
-    # columns: two positions per workgroup run
-    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=118, Cin=7, H=4, W=16, Oc=9, kh=3, stride=3, pad=1)
-    # 261 taps: more steps than stay in LDS, the streaming kernel; its FC part has 87 taps (two full steps)
-    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=117, Cin=29, H=3, W=3, Oc=8, kh=3, stride=1, pad=1)
+        pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=120, Cin=3, H=7, W=6, Oc=8, kh=5, stride=1, pad=1, fc_check=False)    # 2 x 2 blocks, 20 positions
+        pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=121, Cin=2, H=3, W=13, Oc=8, kh=3, stride=1, pad=0, rows_check=False, fc_check=False)    # 1 x 4 blocks, three tiles
+        # 7 x 3 x 3 = 63 taps at stride 3: the window block (7*3*12 lines) is too wide to stage, weight digits resident, six positions
+        pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=122, Cin=7, H=4, W=16, Oc=9, kh=3, stride=3, pad=1, fc_check=False)
 
 
 def test_emulated_pool_and_network(be):
