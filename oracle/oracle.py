@@ -448,15 +448,56 @@ class Oracle:
         assert all(a is not None for a in acc), "an output block receives nothing"
         return [self.rescale(a, level) for a in acc]
 
+    def linear_transform_bsgs(self, xs, bsgs_pts, gks, level, baby):
+        """The block matrix-vector product of linear_transform_blocks with the rotations split into baby and giant steps
+        (the standard way to apply an n-diagonal matrix with about 2 sqrt(n) rotation keys instead of n): offset
+        d = g * baby + b, and
+            sum_d diag_d * Rot_d(x) = sum_g Rot_(g*baby)( sum_b roll(diag_(g*baby+b), +g*baby) * Rot_b(x) ).
+        bsgs_pts[(i, j)] = {(g, b): the encoded, pre-rotated diagonal roll(diag_(g*baby+b), g*baby)} (see bsgs_diagonals).
+        Steps: every input block x_j is rotated by its baby offsets b != 0 from ONE shared ModUp (rotate_hoisted); for
+        every output block i and giant index g the inner sum over j and b (plaintext products and additions); each inner
+        sum with g != 0 is rotated by g*baby with an ordinary rotation (its own ModUp); the sum over g is rescaled.
+        Returns the list of output ciphertexts at level-1.  Other bits than linear_transform_blocks (other rotations, other
+        key-switching noise), the same decrypted product."""
+        n_out = 1 + max(i for i, _ in bsgs_pts)
+        rotated = []
+        for j, x in enumerate(xs):
+            babies = sorted({b for (i, jj), dg in bsgs_pts.items() if jj == j for (_, b) in dg if b != 0})
+            rot = self.rotate_hoisted(x, babies, [gks[b] for b in babies], level) if babies else []
+            rotated.append({0: _u64(x), **{b: rot[k] for k, b in enumerate(babies)}})
+        outs = []
+        for i in range(n_out):
+            giants = sorted({g for (ii, _), dg in bsgs_pts.items() if ii == i for (g, _) in dg})
+            assert giants, "an output block receives nothing"
+            total = None
+            for g in giants:
+                inner = None
+                for (ii, j), dg in sorted(bsgs_pts.items()):
+                    if ii != i:
+                        continue
+                    for (gg, b) in sorted(dg):
+                        if gg != g:
+                            continue
+                        term = self.mul_plain(rotated[j][b], dg[(gg, b)], level)
+                        inner = term if inner is None else self.add(inner, term, level)
+                if g != 0:
+                    inner = self.rotate(inner, g * baby, gks[g * baby], level)
+                total = inner if total is None else self.add(total, inner, level)
+            outs.append(self.rescale(total, level))
+        return outs
+
     def packed_network(self, xs, stages, rlk, gks, level):
         """One image through a network in the single-image packing: xs = the ciphertexts holding the input vector's
-        blocks; stages = [("linear", diag_pts) | ("poly2", k2, k1)], a linear stage being any product of the network's
+        blocks; stages = [("linear", diag_pts) | ("linear_bsgs", bsgs_pts, baby) | ("poly2", k2, k1)], a linear stage being any product of the network's
         linear layers between two activations (convolution, pooling and fully connected layers are all matrices, and a
         pooling layer is merged with the layer after it), poly2 the degree-2 activation of section 3.1 applied to every
         block.  Returns (list of output ciphertexts, their level)."""
         for st in stages:
             if st[0] == "linear":
                 xs = self.linear_transform_blocks(xs, st[1], gks, level)
+                level -= 1
+            elif st[0] == "linear_bsgs":
+                xs = self.linear_transform_bsgs(xs, st[1], gks, level, st[2])
                 level -= 1
             elif st[0] == "poly2":
                 xs = [self.poly2(x, rlk, level, st[1], st[2]) for x in xs]
@@ -798,6 +839,15 @@ def block_diagonals(M, n, n_slots):
             dg = matrix_diagonals(P[i * n:(i + 1) * n, j * n:(j + 1) * n], n_slots)
             if dg:
                 out[(i, j)] = dg
+    return out
+
+
+def bsgs_diagonals(diags, baby):
+    """Baby-step / giant-step form of block diagonals {(i, j): {d: vector}} (block_diagonals): {(i, j): {(g, b): roll(vector,
+    +g*baby)}} with d = g*baby + b, 0 <= b < baby.  Rotating a product left by g*baby slots rotates the diagonal back."""
+    out = {}
+    for key, dg in diags.items():
+        out[key] = {(d // baby, d % baby): np.roll(v, (d // baby) * baby) for d, v in dg.items()}
     return out
 
 

@@ -113,16 +113,28 @@ def network_period(stages, n_slots):
     return min(n, n_slots)
 
 
-def network_integer_stages(stages, q, level, scale, n, n_slots, encode):
+def bsgs_baby(n):
+    """baby-step count for a matrix of period n: the power of two next to sqrt(n) from above"""
+    return 1 << ((int(n - 1).bit_length() + 1) // 2)
+
+
+def network_integer_stages(stages, q, level, scale, n, n_slots, encode, bsgs=False):
     """the stages as the oracle's packed_network takes them: encoded diagonals (scale q_{level-1}, so that the rescale
-    restores the scale) and the integer constants of the degree-2 activation from the tracked scale.  Returns
+    restores the scale) and the integer constants of the degree-2 activation from the tracked scale; bsgs: the linear
+    stages in baby-step / giant-step form (pre-rotated diagonals, baby = bsgs_baby(n)).  Returns
     (stages, rotation offsets used, output level, output scale)."""
     out, rots = [], set()
     for st in stages:
         if st[0] == "linear":
             dg = orc.block_diagonals(st[1], n, n_slots)
-            out.append(("linear", {ij: {d: encode(v.astype(np.complex128), float(q[level - 1]), level) for d, v in dd.items()} for ij, dd in dg.items()}))
-            rots |= {d for dd in dg.values() for d in dd if d}
+            if bsgs:
+                baby = bsgs_baby(n)
+                bs = orc.bsgs_diagonals(dg, baby)
+                out.append(("linear_bsgs", {ij: {gb: encode(v.astype(np.complex128), float(q[level - 1]), level) for gb, v in dd.items()} for ij, dd in bs.items()}, baby))
+                rots |= {b for dd in bs.values() for (_, b) in dd if b} | {g * baby for dd in bs.values() for (g, _) in dd if g}
+            else:
+                out.append(("linear", {ij: {d: encode(v.astype(np.complex128), float(q[level - 1]), level) for d, v in dd.items()} for ij, dd in dg.items()}))
+                rots |= {d for dd in dg.values() for d in dd if d}
             level -= 1
         else:
             s2 = scale * scale / float(q[level - 1])

@@ -682,7 +682,7 @@ def test_strided_convolution_and_pooling_matrices_match_the_layer_definitions():
         assert np.allclose(orc.pool_as_matrix(C, H, W, 2, pp) @ img.reshape(-1), pooled.reshape(-1), atol=1e-12)
 
 
-def _run_single_image(topology, shape, seed, sigma=0.25):
+def _run_single_image(topology, shape, seed, sigma=0.25, bsgs=False):
     import helpers
     probe = orc.Oracle(*shape)
     n_slots, level, s = probe.N // 2, probe.n_q, 2.0 ** 50
@@ -691,9 +691,12 @@ def _run_single_image(topology, shape, seed, sigma=0.25):
     n = helpers.network_period(stages, n_slots)
     # the rotation offsets are known from the matrices alone: keys first, then the encodings
     rots = sorted({d for st in stages if st[0] == "linear" for dd in orc.block_diagonals(st[1], n, n_slots).values() for d in dd if d})
+    if bsgs:  # every offset d = g*baby + b needs the keys of b and of g*baby only
+        baby = helpers.bsgs_baby(n)
+        rots = sorted({d % baby for d in rots if d % baby} | {d - d % baby for d in rots if d >= baby})
     M = Material(*shape, seed=seed, rotations=tuple(rots))
     O = M.O
-    ist, rots2, out_level, out_scale = helpers.network_integer_stages(stages, O.q, level, s, n, n_slots, M.encode)
+    ist, rots2, out_level, out_scale = helpers.network_integer_stages(stages, O.q, level, s, n, n_slots, M.encode, bsgs=bsgs)
     assert rots2 == rots
     C, H, W = wl.CNN_TOPOLOGIES[topology]["input"]
     img = wl.slots_real(C * H * W, seed, "image", lo=0.0, hi=1.0).real
@@ -714,6 +717,15 @@ def test_single_image_network_decrypts_to_the_float_network():
     got, want, n_in, n_out, n_rot = _run_single_image("single_image_tiny", (8, 8, 50, 2, 51, 2), 61)
     assert (n_in, n_out) == (1, 1) and n_rot > 20
     assert np.max(np.abs(want)) > 1e-3
+    assert np.max(np.abs(got[: want.size] - want)) < 1e-4 and np.max(np.abs(got[want.size:])) < 1e-4
+
+
+def test_single_image_network_with_baby_and_giant_steps():
+    """the same network with every linear stage in baby-step / giant-step form: the same decrypted result from a third of
+    the rotation keys (period 128: baby = 16, at most 15 + 7 offsets)"""
+    got, want, n_in, n_out, n_rot = _run_single_image("single_image_tiny", (8, 8, 50, 2, 51, 2), 61, bsgs=True)
+    _, _, _, _, n_rot_plain = _run_single_image("single_image_tiny", (8, 8, 50, 2, 51, 2), 61)
+    assert (n_in, n_out) == (1, 1) and n_rot <= 22 and n_rot_plain > 3 * n_rot // 2
     assert np.max(np.abs(got[: want.size] - want)) < 1e-4 and np.max(np.abs(got[want.size:])) < 1e-4
 
 
@@ -755,6 +767,48 @@ def test_block_linear_transform_with_several_output_ciphertexts():
     x = M1.encrypt(wl.slots_real(n, 63, "x"), s, 3, "x")
     p1 = {d: M1.encode(v.astype(complex), float(M1.O.q[2]), 3) for d, v in d1[(0, 0)].items()}
     assert np.array_equal(M1.O.linear_transform_blocks([x], {(0, 0): p1}, M1.gk, 3)[0], M1.O.linear_transform(x, p1, M1.gk, 3))
+
+
+def test_baby_step_giant_step_transform_decrypts_to_the_same_product_with_fewer_keys():
+    """the 70 x 50 matrix again (2 input blocks, 3 output blocks, 32 slots): with baby = 8 every offset d = 8 g + b needs
+    only the keys of b = 1..7 and of 8, 16, 24 instead of all 31; the decrypted result is M z as before; one giant
+    group only (baby >= every offset) rotates nothing after the sums and is linear_transform_blocks bit for bit; the
+    pre-rotated diagonals are what the identity  diag_d * roll(z, -d) = roll(roll(diag_d, g*baby) * roll(z, -b), -g*baby)  asks"""
+    shape = (6, 3, 50, 2, 51, 2)
+    probe = orc.Oracle(*shape)
+    n = probe.N // 2
+    Wm = wl.weights_float((70, 50), 62, "blk", sigma=0.3)
+    dg = orc.block_diagonals(Wm, n, n)
+    baby = 8
+    bs = orc.bsgs_diagonals(dg, baby)
+    zt = wl.slots_real(n, 64, "zt").real
+    for key in dg:  # the identity on plain vectors, every diagonal
+        for d, v in dg[key].items():
+            g, b = divmod(d, baby)
+            assert np.allclose(v * np.roll(zt, -d), np.roll(bs[key][(g, b)] * np.roll(zt, -b), -g * baby))
+    needed = sorted({b for dd in bs.values() for (_, b) in dd if b} | {g * baby for dd in bs.values() for (g, _) in dd if g})
+    assert needed == [1, 2, 3, 4, 5, 6, 7, 8, 16, 24]
+    M = Material(*shape, seed=62, rotations=tuple(needed))
+    O = M.O
+    z = np.zeros(2 * n)
+    z[:50] = wl.slots_real(50, 62, "z").real
+    s = 2.0 ** 40
+    xs = [M.encrypt(z[j * n:(j + 1) * n].astype(complex), s, 3, ("z", j)) for j in range(2)]
+    pts = {ij: {gb: M.encode(v.astype(complex), float(O.q[2]), 3) for gb, v in dd.items()} for ij, dd in bs.items()}
+    outs = O.linear_transform_bsgs(xs, pts, M.gk, 3, baby)
+    assert len(outs) == 3 and all(o.shape == (2, 2, O.N) for o in outs)
+    got = np.concatenate([M.decrypt(o, s, 2).real for o in outs])
+    want = np.zeros(3 * n)
+    want[:70] = Wm @ z[:50]
+    assert np.max(np.abs(got - want)) < 1e-4
+    # a baby step that covers every offset: no giant rotation, the same sums in the same order as the plain block transform
+    M2 = Material(*shape, seed=62, rotations=tuple(range(1, n)))
+    pts_plain = {ij: {d: M2.encode(v.astype(complex), float(O.q[2]), 3) for d, v in dd.items()} for ij, dd in dg.items()}
+    pts_one = {ij: {(0, d): pt for d, pt in dd.items()} for ij, dd in pts_plain.items()}
+    xs2 = [M2.encrypt(z[j * n:(j + 1) * n].astype(complex), s, 3, ("z", j)) for j in range(2)]
+    a = M2.O.linear_transform_bsgs(xs2, pts_one, M2.gk, 3, n)
+    b_ = M2.O.linear_transform_blocks(xs2, pts_plain, M2.gk, 3)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b_))
 
 
 def test_philox_known_answers():
