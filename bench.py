@@ -334,7 +334,24 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     out["single_image_network_2e14"] = {"ms_per_image": round(ms, 2), "ms_per_image_graph": round(ms_graph, 2), "rotations": sum(len(r) for pl in plans if isinstance(pl, packed.BlockPlan) for r in pl.rotations.values()),
                                         "plaintext_products": n_mul, "distinct_keys": len(all_rots), "levels": [11, lvl_out], "period": n_per,
                                         "what": "one image, rotation-packed: 3x16x16 -> conv 4@5x5, poly2, pool+conv 6@3x3, poly2, pool+FC 16, poly2, FC 2"}
-    del net_keys, evk_s, xin_s, wsn, plans
+    del net_keys, wsn, plans
+    # the same network with baby steps and giant steps: offset d = g*32 + b costs a rotation by b (hoisted) and one by 32 g
+    # of a whole sum, so every layer reads about 60 rotation keys instead of up to 961
+    plans_b, _, lvl_b, _ = packed.plan_network(cs, wl.cnn_shapes(topo), wl.cnn_weights_float(topo, 7, sigma=0.25), 11, 2.0 ** 50, to_dev, bsgs=True)
+    rots_b = sorted({d for pl in plans_b if isinstance(pl, packed.BsgsPlan) for d in pl.rotation_offsets()})
+    keys_b = []
+    for d in rots_b:
+        keys_b.append(uniform_residues(torch, cs.moduli, (cs.beta_top, 2), 1 << 14, gen))
+        cs.galois_key_register(d, keys_b[-1])
+    wsb = torch.empty(packed.network_workspace_bytes(cs, plans_b, 11) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    ms_b = timed(torch, lambda: packed.run_network(cs, xin_s, plans_b, evk_s, 11, wsb), 3)
+    bs = [pl for pl in plans_b if isinstance(pl, packed.BsgsPlan)]
+    out["single_image_network_bsgs_2e14"] = {"ms_per_image": round(ms_b, 2), "baby": bs[0].baby, "distinct_keys": len(rots_b),
+                                             "baby_rotations": sum(len(b) for pl in bs for b in pl.babies.values()),
+                                             "giant_rotations": sum(len(pl.groups) - pl.n_plain for pl in bs),
+                                             "plaintext_products": sum(len(pl.terms) for pl in bs), "levels": [11, lvl_b],
+                                             "what": "the same network, every matrix in baby-step / giant-step form (other bits, same decrypted result)"}
+    del keys_b, evk_s, xin_s, wsb, plans_b
     cs.close()
 
     out.update(conv_layer_workload(torch, ckksmi, wl, gen))

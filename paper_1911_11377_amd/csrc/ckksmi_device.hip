@@ -896,6 +896,22 @@ extern "C" int ckksmi_mul_plain(ckksmi_ctx *c, const uint64_t *a, const uint64_t
     return g.rc();
 }
 
+extern "C" int ckksmi_plain_mac(ckksmi_ctx *c, const uint64_t *cts, int n_ct, const uint64_t *pts, const int32_t *src, const int32_t *group_start,
+                                int n_terms, int n_groups, uint64_t *out, int level, void *stream) {
+    int rc = ct_args_ok(c, level, n_groups);
+    if (rc) return rc;
+    if (n_ct < 1 || n_terms < 0) return CKKSMI_EINVAL;
+    if (!cts || !out || !group_start || (n_terms && (!pts || !src)) || !al16(cts) || !al16(pts) || !al16(out)) return CKKSMI_EINVAL;
+    if (n_groups == 0) return CKKSMI_OK;
+    if (n_groups > 65535 || level > 65535) return CKKSMI_EUNSUPPORTED;
+    const size_t ct_words = 2 * (size_t)level * c->N;
+    if (out < cts + (size_t)n_ct * ct_words && cts < out + (size_t)n_groups * ct_words) return CKKSMI_EINVAL;  // the sums read every input
+    Guard g(c);
+    KL(c, CKKSMI_K_ELEMWISE, (double)n_terms * 2 * level, plain_mac_kernel, dim3(ew_blocks(c->N), level, n_groups), dim3(EW_THREADS), S(stream),
+       (const u64d *)cts, n_ct, (const u64d *)pts, (const int *)src, (const int *)group_start, n_terms, (u64d *)out, c->d_mod, c->logN, level);
+    return g.rc();
+}
+
 extern "C" int ckksmi_mul_scalar(ckksmi_ctx *c, const uint64_t *a, int64_t v, uint64_t *out, int level, int batch, void *stream) {
     int rc = ct_args_ok(c, level, batch);
     if (rc) return rc;

@@ -12,6 +12,12 @@ d at once from ONE shared ModUp (ckksmi_rotate_hoisted), the products by ckksmi_
 a pairwise tree, then ckksmi_rescale.  Only non-zero diagonals cost a rotation: a k x k convolution on a C x H x W
 image has far fewer of them than a dense layer.
 
+Baby steps and giant steps (plan_bsgs, linear_transform_bsgs): with d = g*B + b,
+    sum_d diag_d * Rot_d(x) = sum_g Rot_(g*B)( sum_b roll(diag_(g*B+b), +g*B) * Rot_b(x) ),
+so a layer needs the keys of the baby offsets b < B (hoisted from one ModUp) and of the giant offsets g*B (one ordinary
+rotation per inner sum, all in one batched call) -- about 2 sqrt(n) keys read per layer instead of n -- and its inner
+sums are one launch of ckksmi_plain_mac over tables the plan uploads once.
+
 This module only plans (host side: matrices, diagonals, encodings) and marshals arguments; every step on
 ciphertexts runs in the library's kernels.
 """
@@ -295,6 +301,126 @@ def linear_transform_blocks(ctx, xs, plan, out, ws, stream=None, max_rotations=M
     ctx.rescale(acc, out, L, plan.n_out, rest, stream=stream)
 
 
+# ---------------------------------------------------------------- baby steps and giant steps
+def bsgs_baby(n):
+    """baby-step count for a matrix of period n: the power of two next to sqrt(n) from above"""
+    return 1 << ((int(n - 1).bit_length() + 1) // 2)
+
+
+@dataclass
+class BsgsPlan:
+    """a matrix cut into blocks, its offsets split as d = g*baby + b: every input block is rotated by its baby offsets
+    from one shared ModUp, the products are summed per (output block, g), each such sum with g != 0 is rotated by g*baby,
+    and the sums over g are rescaled.  About 2 sqrt(n) rotation keys (and key reads per image) instead of n."""
+    level: int
+    n_in: int
+    n_out: int
+    baby: int
+    babies: dict        # input block j -> ascending non-zero baby offsets
+    slot: dict          # (j, b) -> position of Rot_b(x_j) among the rotated copies (b = 0: the block itself)
+    n_ct: int           # rotated copies in all
+    groups: list        # [(i, g)] in table order: the groups with g = 0 first, then those that are rotated
+    n_plain: int        # number of groups with g = 0
+    terms: list         # [(i, j, g, b)] in table order
+    pts: object         # device [len(terms)][level][N]: the encoded diagonals, rolled by g*baby slots
+    src: object         # device int32 [len(terms)]
+    group_start: object  # device int32 [len(groups) + 1]
+
+    def rotation_offsets(self):
+        return sorted({b for bb in self.babies.values() for b in bb} | {g * self.baby for _, g in self.groups if g})
+
+
+def _i32_table(values, to_dev):
+    """an int32 table as a device buffer (carried in whole 64-bit words)"""
+    a = np.zeros((len(values) + 1) // 2 * 2 + 2, dtype=np.int32)
+    a[: len(values)] = values
+    return to_dev(a.view(np.uint64))
+
+
+def plan_bsgs(ctx, M, n, level, to_dev, encode=None, baby=None):
+    """encode the diagonals of every block of M at scale q_{level-1} in baby-step / giant-step form"""
+    dg = block_diagonals(M, n, ctx.N // 2)
+    baby = baby or bsgs_baby(n)
+    enc = encode or (lambda v, s, l: ctx.encode(v, s, l))
+    scale = float(ctx.q[level - 1])
+    n_out, n_in = 1 + max(i for i, _ in dg), -(-np.asarray(M).shape[1] // n)
+    if sorted({i for i, _ in dg}) != list(range(n_out)):
+        raise ValueError("an output block receives nothing")
+    babies = {j: sorted({d % baby for (_, jj), dd in dg.items() if jj == j for d in dd if d % baby}) for j in range(n_in)}
+    slot, n_ct = {}, 0
+    for j in range(n_in):
+        for b in [0] + babies[j]:
+            slot[(j, b)] = n_ct
+            n_ct += 1
+    keys = sorted({(i, d // baby) for (i, _), dd in dg.items() for d in dd})
+    groups = [k for k in keys if k[1] == 0] + [k for k in keys if k[1] != 0]
+    terms, src, start, vecs = [], [], [0], []
+    for (i, g) in groups:
+        for (ii, j), dd in sorted(dg.items()):
+            if ii != i:
+                continue
+            for d in sorted(dd):
+                if d // baby != g:
+                    continue
+                terms.append((i, j, g, d % baby))
+                src.append(slot[(j, d % baby)])
+                vecs.append(enc(np.roll(dd[d], g * baby).astype(np.complex128), scale, level))
+        start.append(len(terms))
+    return BsgsPlan(level, n_in, n_out, baby, babies, slot, n_ct, groups, sum(1 for _, g in groups if g == 0), terms,
+                    to_dev(np.stack(vecs)), _i32_table(src, to_dev), _i32_table(start, to_dev))
+
+
+def bsgs_workspace_bytes(ctx, plan, max_rotations=MAX_ROTATIONS_PER_CALL):
+    L, N = plan.level, ctx.N
+    ct = 2 * L * N * 8
+    n_giant = len(plan.groups) - plan.n_plain
+    R = max([min(len(b), max_rotations) for b in plan.babies.values()] + [1])
+    aux = max(ctx.rotate_hoisted_workspace_bytes(L, 1, R), ctx.workspace_bytes(ckksmi.OP_ROTATE, L, max(n_giant, 1)),
+              ctx.workspace_bytes(ckksmi.OP_RESCALE, L, plan.n_out))
+    return (plan.n_ct + len(plan.groups) + n_giant + plan.n_out) * ct + aux
+
+
+def linear_transform_bsgs(ctx, xs, plan, out, ws, stream=None, max_rotations=MAX_ROTATIONS_PER_CALL):
+    """out [n_out][2][level-1][N] = RS(sum_g Rot_(g*baby)(sum_j sum_b pt * Rot_b(xs[j]))) for the input blocks
+    xs [n_in][2][level][N]"""
+    L, N = plan.level, ctx.N
+    ct = 2 * L * N
+    flat = ws.reshape(-1) if hasattr(ws, "reshape") else ws
+    xflat = xs.reshape(-1) if hasattr(xs, "reshape") else xs
+    n_groups, n_giant = len(plan.groups), len(plan.groups) - plan.n_plain
+    rotated = flat[: plan.n_ct * ct]
+    inner = flat[plan.n_ct * ct: (plan.n_ct + n_groups) * ct]
+    turned = flat[(plan.n_ct + n_groups) * ct: (plan.n_ct + n_groups + n_giant) * ct]
+    acc = flat[(plan.n_ct + n_groups + n_giant) * ct: (plan.n_ct + n_groups + n_giant + plan.n_out) * ct]
+    rest = flat[(plan.n_ct + n_groups + n_giant + plan.n_out) * ct:]
+    # 1. the rotated copies of every input block: the block itself, then its baby offsets from one shared ModUp
+    for j in range(plan.n_in):
+        x = xflat[j * ct:(j + 1) * ct]
+        s0 = plan.slot[(j, 0)]
+        ctx.mul_scalar(x, 1, rotated[s0 * ct:(s0 + 1) * ct], L, 1, stream=stream)  # a copy
+        bb = plan.babies[j]
+        for c0 in range(0, len(bb), max_rotations):
+            chunk = bb[c0: c0 + max_rotations]
+            s1 = plan.slot[(j, chunk[0])]
+            ctx.rotate_hoisted(x, chunk, rotated[s1 * ct:(s1 + len(chunk)) * ct], L, 1, rest, stream=stream)
+    # 2. every inner sum in one launch
+    ctx.plain_mac(rotated, plan.n_ct, plan.pts, plan.src, plan.group_start, len(plan.terms), n_groups, inner, L, stream=stream)
+    # 3. the sums with g != 0, each rotated by g*baby (one batch of ordinary rotations)
+    if n_giant:
+        ctx.rotate(inner[plan.n_plain * ct:], [g * plan.baby for _, g in plan.groups[plan.n_plain:]], turned, L, n_giant, rest, stream=stream)
+    # 4. per output block the sum over g (modular additions: any order gives the same words), then the rescale
+    started = [False] * plan.n_out
+    for k, (i, g) in enumerate(plan.groups):
+        srcbuf = inner[k * ct:(k + 1) * ct] if g == 0 else turned[(k - plan.n_plain) * ct:(k - plan.n_plain + 1) * ct]
+        a = acc[i * ct:(i + 1) * ct]
+        if started[i]:
+            ctx.add(a, srcbuf, a, L, 1, stream=stream)
+        else:
+            ctx.mul_scalar(srcbuf, 1, a, L, 1, stream=stream)
+            started[i] = True
+    ctx.rescale(acc, out, L, plan.n_out, rest, stream=stream)
+
+
 def network_period(stages, n_slots):
     longest = max(max(st[1].shape) for st in stages if st[0] == "linear")
     n = 1
@@ -303,16 +429,16 @@ def network_period(stages, n_slots):
     return min(n, n_slots)
 
 
-def plan_network(ctx, layer_shapes, weights, level, scale, to_dev, encode=None):
-    """plans of every stage of a network on one image (BlockPlan or activation.Poly2Constants), the packing period, the
-    output level and scale"""
+def plan_network(ctx, layer_shapes, weights, level, scale, to_dev, encode=None, bsgs=False):
+    """plans of every stage of a network on one image (BlockPlan, or BsgsPlan with bsgs=True, or
+    activation.Poly2Constants), the packing period, the output level and scale"""
     from . import activation
     stages = stage_matrices(layer_shapes, weights)
     n = network_period(stages, ctx.N // 2)
     plans = []
     for st in stages:
         if st[0] == "linear":
-            plans.append(plan_blocks(ctx, st[1], n, level, to_dev, encode))
+            plans.append(plan_bsgs(ctx, st[1], n, level, to_dev, encode) if bsgs else plan_blocks(ctx, st[1], n, level, to_dev, encode))
             level -= 1
         else:
             k = activation.poly2_constants(ctx.q, level, scale)
@@ -326,15 +452,15 @@ def network_workspace_bytes(ctx, plans, level, max_rotations=MAX_ROTATIONS_PER_C
     from . import activation
     need, blocks, N = 0, 1, ctx.N
     for pl in plans:
-        if isinstance(pl, BlockPlan):
-            need = max(need, blocks_workspace_bytes(ctx, pl, max_rotations))
+        if isinstance(pl, (BlockPlan, BsgsPlan)):
+            need = max(need, bsgs_workspace_bytes(ctx, pl, max_rotations) if isinstance(pl, BsgsPlan) else blocks_workspace_bytes(ctx, pl, max_rotations))
             blocks = pl.n_out
             level -= 1
         else:
             need = max(need, activation.workspace_bytes(ctx, level, blocks))
             level -= 2
     # two ping-pong buffers for the activations between stages
-    widest = max([pl.n_in for pl in plans if isinstance(pl, BlockPlan)] + [pl.n_out for pl in plans if isinstance(pl, BlockPlan)])
+    widest = max([pl.n_in for pl in plans if isinstance(pl, (BlockPlan, BsgsPlan))] + [pl.n_out for pl in plans if isinstance(pl, (BlockPlan, BsgsPlan))])
     return need + 2 * widest * 2 * ctx.n_q * N * 8
 
 
@@ -344,7 +470,7 @@ def run_network(ctx, xs, plans, evk, level, ws, stream=None, max_rotations=MAX_R
     from . import activation
     N = ctx.N
     flat = ws.reshape(-1) if hasattr(ws, "reshape") else ws
-    widest = max([pl.n_in for pl in plans if isinstance(pl, BlockPlan)] + [pl.n_out for pl in plans if isinstance(pl, BlockPlan)])
+    widest = max([pl.n_in for pl in plans if isinstance(pl, (BlockPlan, BsgsPlan))] + [pl.n_out for pl in plans if isinstance(pl, (BlockPlan, BsgsPlan))])
     half = widest * 2 * ctx.n_q * N
     bufs = [flat[:half], flat[half: 2 * half]]
     rest = flat[2 * half:]
@@ -352,8 +478,9 @@ def run_network(ctx, xs, plans, evk, level, ws, stream=None, max_rotations=MAX_R
     blocks = None
     for pl in plans:
         dst = bufs[which]
-        if isinstance(pl, BlockPlan):
-            linear_transform_blocks(ctx, cur, pl, dst[: pl.n_out * 2 * (level - 1) * N], rest, stream=stream, max_rotations=max_rotations)
+        if isinstance(pl, (BlockPlan, BsgsPlan)):
+            fn = linear_transform_bsgs if isinstance(pl, BsgsPlan) else linear_transform_blocks
+            fn(ctx, cur, pl, dst[: pl.n_out * 2 * (level - 1) * N], rest, stream=stream, max_rotations=max_rotations)
             blocks = pl.n_out
             level -= 1
             cur = dst[: blocks * 2 * level * N]

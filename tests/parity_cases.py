@@ -172,6 +172,49 @@ def case_elementwise(be, shape, seed, batch=3):
     ctx.close()
 
 
+def case_plain_mac(be, shape, seed, n_ct=5, level=None):
+    """grouped sums of plaintext x ciphertext products against the oracle's products and additions term by term; an empty
+    group gives zeros; an index outside the table's range is read as the nearest valid one (documented: no access outside
+    the buffers)"""
+    M = make_material(shape, seed)
+    O = M.O
+    ctx = be.context(*shape)
+    level = level or O.n_q
+    cts = random_cts(M, level, n_ct, seed, "mac.ct")
+    groups = [[0, 1, 2, 3, 4, 0, 2], [], [4], [1, 1, 3, n_ct + 7, -2]]  # the last two entries are clamped to n_ct-1 and 0
+    src = [t for g in groups for t in g]
+    start = np.cumsum([0] + [len(g) for g in groups])
+    pts = wl.uniform_limbs(O.q[:level], O.N, seed, "mac.pt", lead=(len(src),))
+    def i32(v):
+        a = np.zeros((len(v) + 1) // 2 * 2 + 2, dtype=np.int32)
+        a[: len(v)] = v
+        return be.to_dev(a.view(np.uint64))
+    out = be.empty(len(groups), 2, level, O.N)
+    ctx.plain_mac(be.to_dev(cts), n_ct, be.to_dev(pts), i32(src), i32(start), len(src), len(groups), out, level, stream=be.stream)
+    got = be.to_host(out).reshape(len(groups), 2, level, O.N)
+    t = 0
+    for gi, g in enumerate(groups):
+        want = np.zeros((2, level, O.N), dtype=np.uint64)
+        for sidx in g:
+            want = O.add(want, O.mul_plain(cts[min(max(sidx, 0), n_ct - 1)], pts[t], level), level)
+            t += 1
+        assert np.array_equal(got[gi], want), "grouped plaintext products differ from the oracle (group %d)" % gi
+    # refusals: overlapping output, no ciphertexts
+    dc = be.to_dev(cts)
+    with_rc = lambda fn, *a: _rc(fn, *a, stream=be.stream)
+    assert with_rc(ctx.plain_mac, dc, n_ct, be.to_dev(pts), i32(src), i32(start), len(src), len(groups), dc, level) == ckksmi.EINVAL
+    assert with_rc(ctx.plain_mac, dc, 0, be.to_dev(pts), i32(src), i32(start), len(src), len(groups), out, level) == ckksmi.EINVAL
+    ctx.close()
+
+
+def _rc(fn, *args, **kw):
+    try:
+        fn(*args, **kw)
+    except ckksmi.CkksmiError as e:
+        return e.code
+    return 0
+
+
 def case_rescale(be, shape, seed, batch=2, levels=None):
     M = make_material(shape, seed)
     O = M.O
@@ -405,7 +448,7 @@ def case_packed_layer(be, shape, seed, M_float, level=None, max_rotations=None):
     ctx.close()
 
 
-def case_packed_network(be, shape, seed, topology, sigma=0.25, max_rotations=None):
+def case_packed_network(be, shape, seed, topology, sigma=0.25, max_rotations=None, bsgs=False):
     """one image through a network in the rotation-packed layout (strided convolution and pooling as matrices, vectors that
     may span several ciphertexts, degree-2 activations) against the oracle's schedule: every output ciphertext word for
     word, and decrypted against the float network.  The stage matrices, the activation constants and the encoded diagonals
@@ -422,22 +465,29 @@ def case_packed_network(be, shape, seed, topology, sigma=0.25, max_rotations=Non
         assert a[0] == b[0] and (a[0] != "linear" or np.allclose(a[1], b[1], rtol=0, atol=1e-15)), "stage matrices differ"
     n = helpers.network_period(stages, n_slots)
     rots = sorted({d for st in stages if st[0] == "linear" for dd in orc.block_diagonals(st[1], n, n_slots).values() for d in dd if d})
+    if bsgs:  # baby steps and giant steps: offset d = g*baby + b needs the keys of b and of g*baby only
+        baby = helpers.bsgs_baby(n)
+        rots = sorted({d % baby for d in rots if d % baby} | {d - d % baby for d in rots if d >= baby})
     M = make_material(shape, seed, rotations=tuple(rots))
     O = M.O
     # both sides plan from the LIBRARY's stage matrices here (they agree with the test's to rounding, and the encoder must
     # see identical inputs for identical plaintexts)
-    ist, rots2, out_level, out_scale = helpers.network_integer_stages(lib_stages, O.q, level, s, n, n_slots, M.encode)
+    ist, rots2, out_level, out_scale = helpers.network_integer_stages(lib_stages, O.q, level, s, n, n_slots, M.encode, bsgs=bsgs)
     assert rots2 == rots
     ctx = be.context(*shape)
     check_moduli(ctx, M)
     keys = {r: be.to_dev(M.gk[r]) for r in rots}
     for r in rots:
         ctx.galois_key_register(r, keys[r])
-    plans, n_lib, lvl_lib, scale_lib = packed.plan_network(ctx, wl.cnn_shapes(topology), weights, level, s, be.to_dev, encode=M.encode)
+    plans, n_lib, lvl_lib, scale_lib = packed.plan_network(ctx, wl.cnn_shapes(topology), weights, level, s, be.to_dev, encode=M.encode, bsgs=bsgs)
     assert (n_lib, lvl_lib) == (n, out_level) and scale_lib == out_scale
     for pl, st in zip(plans, ist):
         if st[0] == "poly2":
             assert (pl.k2, pl.k1) == (st[1], st[2]), "activation constants differ"
+        elif st[0] == "linear_bsgs":
+            assert pl.baby == st[2] == helpers.bsgs_baby(n)
+            assert sorted((i, j, g, b) for (i, j), dd in st[1].items() for (g, b) in dd) == sorted(pl.terms), "diagonals differ"
+            assert set(pl.rotation_offsets()) <= set(rots)
         else:
             assert {ij: sorted(dd) for ij, dd in st[1].items()} == pl.offsets, "diagonals differ"
     C, H, W = wl.CNN_TOPOLOGIES[topology]["input"]

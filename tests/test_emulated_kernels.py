@@ -224,6 +224,17 @@ def test_emulated_activation_schedule_register_tiled(be):
     pc.case_activation(be, (13, 6, 50, 3, 51, 3), seed=145, level=6, batch=3, sample=[0, 1, 2])
 
 
+def test_emulated_grouped_plaintext_products(be):
+    pc.case_plain_mac(be, TINY, seed=160)
+    pc.case_plain_mac(be, (5, 4, 50, 1, 51, 1), seed=161, n_ct=3, level=3)
+
+
+def test_emulated_single_image_network_baby_and_giant_steps(be):
+    """the same network with baby and giant steps: period 64 with two input ciphertexts (baby 8), period 128 with one"""
+    pc.case_packed_network(be, (7, 8, 50, 2, 51, 2), seed=152, topology="single_image_tiny", max_rotations=5, bsgs=True)
+    pc.case_packed_network(be, (8, 8, 50, 2, 51, 2), seed=153, topology="single_image_tiny", bsgs=True)
+
+
 def test_emulated_single_image_network(be):
     """one image in the rotation-packed layout: strided convolution, activation, pooling merged into the next layer; with 64
     slots the input spans two ciphertexts (block matrix), with 128 one; rotations in calls of at most 5 in the first run"""

@@ -401,6 +401,14 @@ def test_single_image_network_matches_oracle(be, shape, topology):
     oracle's schedule, decrypted output against the float network"""
     announce("single-image network %s %r" % (topology, shape))
     pc.case_packed_network(be, shape, seed=380, topology=topology)
+    announce("single-image network %s %r, baby and giant steps" % (topology, shape))
+    pc.case_packed_network(be, shape, seed=381, topology=topology, bsgs=True)
+
+
+def test_grouped_plaintext_products(be):
+    announce("grouped plaintext products")
+    pc.case_plain_mac(be, TINY, seed=382)
+    pc.case_plain_mac(be, (13, 5, 50, 1, 51, 1), seed=383, n_ct=4, level=4)
 
 
 @pytest.mark.parametrize("shape,log_scale,batch", [
