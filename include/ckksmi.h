@@ -145,15 +145,15 @@ int ckksmi_sub(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, uint64_t *
 int ckksmi_mul_plain(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *pt, size_t pt_stride, uint64_t *out, int level, int batch, void *stream);
 /* Sums of plaintext x ciphertext products, the inner sums of a matrix-vector product in the rotation-packed
  * (single-image) layout, where section 2.1's plaintext multiplications and additions come in hundreds per layer:
- *     out[g] = sum over the terms t = group_start[g] .. group_start[g+1]-1 of  pts[t] (*) cts[src[t]]
+ *     out[g] = sum over the ciphertexts s with term[g][s] >= 0 of  pts[term[g][s]] (*) cts[s]
  * (slot-wise, both components, mod every q_i: the same words as ckksmi_mul_plain and ckksmi_add term by term).
- * cts: device [n_ct][2][level][N]; pts: device [n_terms][level][N], evaluation form; src: device int32 [n_terms],
- * values in [0, n_ct); group_start: device int32 [n_groups+1], non-decreasing, group_start[n_groups] <= n_terms;
- * out: device [n_groups][2][level][N], must not overlap cts (CKKSMI_EINVAL).  The tables live on the device (a plan
- * uploads them once) and are not read by the host: an index outside its range is clamped by the kernel, it gives a
- * wrong sum but no access outside the buffers.  An empty group gives zeros. */
-int ckksmi_plain_mac(ckksmi_ctx *ctx, const uint64_t *cts, int n_ct, const uint64_t *pts, const int32_t *src, const int32_t *group_start,
-                     int n_terms, int n_groups, uint64_t *out, int level, void *stream);
+ * cts: device [n_ct][2][level][N]; pts: device [n_pts][level][N], evaluation form; term: device int32
+ * [n_groups][n_ct], the plaintext that multiplies ciphertext s in sum g, negative = none; out: device
+ * [n_groups][2][level][N], must not overlap cts (CKKSMI_EINVAL).  The table lives on the device (a plan uploads it
+ * once) and is not read by the host: an entry >= n_pts is treated as "none" by the kernel, it gives a wrong sum but
+ * no access outside the buffers.  A sum without terms gives zeros. */
+int ckksmi_plain_mac(ckksmi_ctx *ctx, const uint64_t *cts, int n_ct, const uint64_t *pts, int n_pts, const int32_t *term, int n_groups,
+                     uint64_t *out, int level, void *stream);
 /* every word times the signed constant c (reduced mod each q_i) */
 int ckksmi_mul_scalar(ckksmi_ctx *ctx, const uint64_t *a, int64_t c, uint64_t *out, int level, int batch, void *stream);
 /* add the constant polynomial c to component 0 (every slot += c/scale) */

@@ -82,7 +82,7 @@ SIGNATURES = {
     "ckksmi_rotate": [VP, VP, intp, VP, C.c_int, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_mac": [VP, VP, VP] + [C.c_int] * 8 + [VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_conv2d_workspace_bytes": [VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)],
-    "ckksmi_plain_mac": [VP, VP, C.c_int, VP, VP, VP, C.c_int, C.c_int, VP, C.c_int, VP],
+    "ckksmi_plain_mac": [VP, VP, C.c_int, VP, C.c_int, VP, C.c_int, VP, C.c_int, VP],
     "ckksmi_conv2d_mac_rows": [VP, VP, VP] + [C.c_int] * 12 + [VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_fc_mac": [VP, VP, VP, C.c_int, C.c_int, VP, C.c_int, VP, C.c_size_t, VP],
     "ckksmi_sum_pool2d": [VP, VP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, VP, C.c_int, VP],
@@ -373,10 +373,9 @@ class Context:
         assert r.shape == (batch,)
         self._call("ckksmi_rotate", self._h, _ptr(a), r.ctypes.data_as(intp), _ptr(out), level, batch, _ptr(ws), _nbytes(ws), self._stream(stream))
 
-    def plain_mac(self, cts, n_ct, pts, src, group_start, n_terms, n_groups, out, level, stream=None):
-        """out[g] = sum of pts[t] * cts[src[t]] over the terms of group g; src, group_start: device int32 tables"""
-        self._call("ckksmi_plain_mac", self._h, _ptr(cts), n_ct, _ptr(pts), _ptr(src), _ptr(group_start), n_terms, n_groups, _ptr(out), level,
-                   self._stream(stream))
+    def plain_mac(self, cts, n_ct, pts, n_pts, term, n_groups, out, level, stream=None):
+        """out[g] = sum over s of pts[term[g][s]] * cts[s] where term[g][s] >= 0; term: device int32 [n_groups][n_ct]"""
+        self._call("ckksmi_plain_mac", self._h, _ptr(cts), n_ct, _ptr(pts), n_pts, _ptr(term), n_groups, _ptr(out), level, self._stream(stream))
 
     def conv2d_mac(self, x, w, Cin, H, W, O, kh, kw, stride, pad, out, level, ws, stream=None):
         self._call("ckksmi_conv2d_mac", self._h, _ptr(x), _ptr(w), Cin, H, W, O, kh, kw, stride, pad, _ptr(out), level, _ptr(ws), _nbytes(ws),

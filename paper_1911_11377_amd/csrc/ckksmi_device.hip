@@ -896,19 +896,19 @@ extern "C" int ckksmi_mul_plain(ckksmi_ctx *c, const uint64_t *a, const uint64_t
     return g.rc();
 }
 
-extern "C" int ckksmi_plain_mac(ckksmi_ctx *c, const uint64_t *cts, int n_ct, const uint64_t *pts, const int32_t *src, const int32_t *group_start,
-                                int n_terms, int n_groups, uint64_t *out, int level, void *stream) {
+extern "C" int ckksmi_plain_mac(ckksmi_ctx *c, const uint64_t *cts, int n_ct, const uint64_t *pts, int n_pts, const int32_t *term, int n_groups,
+                                uint64_t *out, int level, void *stream) {
     int rc = ct_args_ok(c, level, n_groups);
     if (rc) return rc;
-    if (n_ct < 1 || n_terms < 0) return CKKSMI_EINVAL;
-    if (!cts || !out || !group_start || (n_terms && (!pts || !src)) || !al16(cts) || !al16(pts) || !al16(out)) return CKKSMI_EINVAL;
+    if (n_ct < 1 || n_pts < 0) return CKKSMI_EINVAL;
+    if (!cts || !out || !term || (n_pts && !pts) || !al16(cts) || !al16(pts) || !al16(out)) return CKKSMI_EINVAL;
     if (n_groups == 0) return CKKSMI_OK;
-    if (n_groups > 65535 || level > 65535) return CKKSMI_EUNSUPPORTED;
+    if ((n_groups + PM_GROUPS - 1) / PM_GROUPS > 65535 || level > 65535) return CKKSMI_EUNSUPPORTED;
     const size_t ct_words = 2 * (size_t)level * c->N;
     if (out < cts + (size_t)n_ct * ct_words && cts < out + (size_t)n_groups * ct_words) return CKKSMI_EINVAL;  // the sums read every input
     Guard g(c);
-    KL(c, CKKSMI_K_ELEMWISE, (double)n_terms * 2 * level, plain_mac_kernel, dim3(ew_blocks(c->N), level, n_groups), dim3(EW_THREADS), S(stream),
-       (const u64d *)cts, n_ct, (const u64d *)pts, (const int *)src, (const int *)group_start, n_terms, (u64d *)out, c->d_mod, c->logN, level);
+    KL(c, CKKSMI_K_ELEMWISE, (double)n_pts * 2 * level, plain_mac_kernel, dim3(ew_blocks(c->N), level, (n_groups + PM_GROUPS - 1) / PM_GROUPS),
+       dim3(EW_THREADS), S(stream), (const u64d *)cts, n_ct, (const u64d *)pts, n_pts, (const int *)term, n_groups, (u64d *)out, c->d_mod, c->logN, level);
     return g.rc();
 }
 

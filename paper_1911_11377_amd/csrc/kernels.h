@@ -238,32 +238,43 @@ __global__ __launch_bounds__(EW_THREADS) void mul_plain_kernel(const u64d *a, co
     out[w] = d2u(canon(mulmod(x, y, mc.p, mc.pinv), mc.p, mc.pinv));
 }
 
-// out[g] = sum over the terms t of group g of pt[t] * ct[src[t]] (both components).  grid: x = word blocks, y = limb,
-// z = group.  Every index read from the tables is clamped, so a wrong table gives wrong sums, never an access outside
-// the buffers.  The running sums stay balanced-reduced: |sum| <= p/2 + 1 before a product (|.| <= p) is added.
-__global__ __launch_bounds__(EW_THREADS) void plain_mac_kernel(const u64d *cts, int n_ct, const u64d *pts, const int *src, const int *group_start,
-                                                               int n_terms, u64d *out, const ModConst *modc, int logN, int level) {
+// out[g] = sum over the ciphertexts s with term[g][s] >= 0 of pts[term[g][s]] * cts[s] (both components).
+// grid: x = word blocks, y = limb, z = chunks of PM_GROUPS groups: a thread loads the word of ciphertext s once for the
+// chunk's groups (the ciphertexts are re-read once per chunk, the plaintexts once in all).  A table entry beyond the
+// plaintexts counts as "none", so a wrong table gives wrong sums, never an access outside the buffers.  The running
+// sums stay balanced-reduced: |sum| <= p/2 + 1 before a product (|.| <= p) is added.
+#define PM_GROUPS 8
+__global__ __launch_bounds__(EW_THREADS) void plain_mac_kernel(const u64d *cts, int n_ct, const u64d *pts, int n_pts, const int *term, int n_groups,
+                                                               u64d *out, const ModConst *modc, int logN, int level) {
     const size_t N = (size_t)1 << logN;
     const size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
     if (w >= N) return;
-    const int i = (int)blockIdx.y, g = (int)blockIdx.z;
+    const int i = (int)blockIdx.y, g0 = (int)blockIdx.z * PM_GROUPS;
     const ModConst mc = modc[i];
-    int t0 = group_start[g], t1 = group_start[g + 1];
-    t0 = t0 < 0 ? 0 : (t0 > n_terms ? n_terms : t0);
-    t1 = t1 < t0 ? t0 : (t1 > n_terms ? n_terms : t1);
     const size_t ct_words = 2 * (size_t)level * N, pt_words = (size_t)level * N, off = (size_t)i * N + w;
-    double a0 = 0.0, a1 = 0.0;
-    for (int t = t0; t < t1; t++) {
-        int sct = src[t];
-        sct = sct < 0 ? 0 : (sct >= n_ct ? n_ct - 1 : sct);
-        const double y = u2d(pts[(size_t)t * pt_words + off]);
+    double a0[PM_GROUPS], a1[PM_GROUPS];
+#pragma unroll
+    for (int k = 0; k < PM_GROUPS; k++) a0[k] = a1[k] = 0.0;
+    for (int sct = 0; sct < n_ct; sct++) {
         const u64d *x = cts + (size_t)sct * ct_words + off;
-        a0 = reduce_balanced(a0 + mulmod(u2d(x[0]), y, mc.p, mc.pinv), mc.p, mc.pinv);
-        a1 = reduce_balanced(a1 + mulmod(u2d(x[pt_words]), y, mc.p, mc.pinv), mc.p, mc.pinv);
+        const double x0 = u2d(x[0]), x1 = u2d(x[pt_words]);
+#pragma unroll
+        for (int k = 0; k < PM_GROUPS; k++) {
+            if (g0 + k >= n_groups) continue;                      // uniform
+            const int t = term[(size_t)(g0 + k) * n_ct + sct];     // the same for every thread
+            if (t < 0 || t >= n_pts) continue;
+            const double y = u2d(pts[(size_t)t * pt_words + off]);
+            a0[k] = reduce_balanced(a0[k] + mulmod(x0, y, mc.p, mc.pinv), mc.p, mc.pinv);
+            a1[k] = reduce_balanced(a1[k] + mulmod(x1, y, mc.p, mc.pinv), mc.p, mc.pinv);
+        }
     }
-    u64d *o = out + (size_t)g * ct_words + off;
-    o[0] = d2u(canon(a0, mc.p, mc.pinv));
-    o[pt_words] = d2u(canon(a1, mc.p, mc.pinv));
+#pragma unroll
+    for (int k = 0; k < PM_GROUPS; k++) {
+        if (g0 + k >= n_groups) continue;
+        u64d *o = out + (size_t)(g0 + k) * ct_words + off;
+        o[0] = d2u(canon(a0[k], mc.p, mc.pinv));
+        o[pt_words] = d2u(canon(a1[k], mc.p, mc.pinv));
+    }
 }
 
 __global__ __launch_bounds__(EW_THREADS) void mul_scalar_kernel(const u64d *a, u64d *out, const ModConst *modc, ScalarTab S,

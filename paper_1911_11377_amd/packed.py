@@ -323,8 +323,7 @@ class BsgsPlan:
     n_plain: int        # number of groups with g = 0
     terms: list         # [(i, j, g, b)] in table order
     pts: object         # device [len(terms)][level][N]: the encoded diagonals, rolled by g*baby slots
-    src: object         # device int32 [len(terms)]
-    group_start: object  # device int32 [len(groups) + 1]
+    term: object        # device int32 [len(groups)][n_ct]: the plaintext that multiplies rotated copy s in group k, -1 = none
 
     def rotation_offsets(self):
         return sorted({b for bb in self.babies.values() for b in bb} | {g * self.baby for _, g in self.groups if g})
@@ -354,20 +353,20 @@ def plan_bsgs(ctx, M, n, level, to_dev, encode=None, baby=None):
             n_ct += 1
     keys = sorted({(i, d // baby) for (i, _), dd in dg.items() for d in dd})
     groups = [k for k in keys if k[1] == 0] + [k for k in keys if k[1] != 0]
-    terms, src, start, vecs = [], [], [0], []
-    for (i, g) in groups:
+    terms, vecs = [], []
+    table = np.full((len(groups), n_ct), -1, dtype=np.int32)
+    for k, (i, g) in enumerate(groups):
         for (ii, j), dd in sorted(dg.items()):
             if ii != i:
                 continue
             for d in sorted(dd):
                 if d // baby != g:
                     continue
+                table[k, slot[(j, d % baby)]] = len(terms)
                 terms.append((i, j, g, d % baby))
-                src.append(slot[(j, d % baby)])
                 vecs.append(enc(np.roll(dd[d], g * baby).astype(np.complex128), scale, level))
-        start.append(len(terms))
     return BsgsPlan(level, n_in, n_out, baby, babies, slot, n_ct, groups, sum(1 for _, g in groups if g == 0), terms,
-                    to_dev(np.stack(vecs)), _i32_table(src, to_dev), _i32_table(start, to_dev))
+                    to_dev(np.stack(vecs)), _i32_table(table.reshape(-1), to_dev))
 
 
 def bsgs_workspace_bytes(ctx, plan, max_rotations=MAX_ROTATIONS_PER_CALL):
@@ -404,7 +403,7 @@ def linear_transform_bsgs(ctx, xs, plan, out, ws, stream=None, max_rotations=MAX
             s1 = plan.slot[(j, chunk[0])]
             ctx.rotate_hoisted(x, chunk, rotated[s1 * ct:(s1 + len(chunk)) * ct], L, 1, rest, stream=stream)
     # 2. every inner sum in one launch
-    ctx.plain_mac(rotated, plan.n_ct, plan.pts, plan.src, plan.group_start, len(plan.terms), n_groups, inner, L, stream=stream)
+    ctx.plain_mac(rotated, plan.n_ct, plan.pts, len(plan.terms), plan.term, n_groups, inner, L, stream=stream)
     # 3. the sums with g != 0, each rotated by g*baby (one batch of ordinary rotations)
     if n_giant:
         ctx.rotate(inner[plan.n_plain * ct:], [g * plan.baby for _, g in plan.groups[plan.n_plain:]], turned, L, n_giant, rest, stream=stream)

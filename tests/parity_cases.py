@@ -173,37 +173,45 @@ def case_elementwise(be, shape, seed, batch=3):
 
 
 def case_plain_mac(be, shape, seed, n_ct=5, level=None):
-    """grouped sums of plaintext x ciphertext products against the oracle's products and additions term by term; an empty
-    group gives zeros; an index outside the table's range is read as the nearest valid one (documented: no access outside
-    the buffers)"""
+    """grouped sums of plaintext x ciphertext products against the oracle's products and additions term by term: eleven
+    sums (two chunks of groups), one of them empty; a table entry beyond the plaintexts counts as none (documented: no
+    access outside the buffers)"""
     M = make_material(shape, seed)
     O = M.O
     ctx = be.context(*shape)
     level = level or O.n_q
     cts = random_cts(M, level, n_ct, seed, "mac.ct")
-    groups = [[0, 1, 2, 3, 4, 0, 2], [], [4], [1, 1, 3, n_ct + 7, -2]]  # the last two entries are clamped to n_ct-1 and 0
-    src = [t for g in groups for t in g]
-    start = np.cumsum([0] + [len(g) for g in groups])
-    pts = wl.uniform_limbs(O.q[:level], O.N, seed, "mac.pt", lead=(len(src),))
+    n_groups = 11
+    r = wl.rng(seed, "mac.table")
+    table = np.full((n_groups, n_ct), -1, dtype=np.int32)
+    n_pts = 0
+    for g in range(n_groups):
+        for sct in range(n_ct):
+            if g != 3 and r.random() < 0.6:
+                table[g, sct] = n_pts
+                n_pts += 1
+    pts = wl.uniform_limbs(O.q[:level], O.N, seed, "mac.pt", lead=(n_pts,))
+    bad = table.copy()
+    bad[3, 0] = n_pts + 5  # beyond the plaintexts: none
     def i32(v):
         a = np.zeros((len(v) + 1) // 2 * 2 + 2, dtype=np.int32)
         a[: len(v)] = v
         return be.to_dev(a.view(np.uint64))
-    out = be.empty(len(groups), 2, level, O.N)
-    ctx.plain_mac(be.to_dev(cts), n_ct, be.to_dev(pts), i32(src), i32(start), len(src), len(groups), out, level, stream=be.stream)
-    got = be.to_host(out).reshape(len(groups), 2, level, O.N)
-    t = 0
-    for gi, g in enumerate(groups):
+    out = be.empty(n_groups, 2, level, O.N)
+    dc, dp = be.to_dev(cts), be.to_dev(pts)
+    ctx.plain_mac(dc, n_ct, dp, n_pts, i32(bad.reshape(-1)), n_groups, out, level, stream=be.stream)
+    got = be.to_host(out).reshape(n_groups, 2, level, O.N)
+    for g in range(n_groups):
         want = np.zeros((2, level, O.N), dtype=np.uint64)
-        for sidx in g:
-            want = O.add(want, O.mul_plain(cts[min(max(sidx, 0), n_ct - 1)], pts[t], level), level)
-            t += 1
-        assert np.array_equal(got[gi], want), "grouped plaintext products differ from the oracle (group %d)" % gi
+        for sct in range(n_ct):
+            if table[g, sct] >= 0:
+                want = O.add(want, O.mul_plain(cts[sct], pts[table[g, sct]], level), level)
+        assert np.array_equal(got[g], want), "grouped plaintext products differ from the oracle (group %d)" % g
+    assert not got[3].any()
     # refusals: overlapping output, no ciphertexts
-    dc = be.to_dev(cts)
     with_rc = lambda fn, *a: _rc(fn, *a, stream=be.stream)
-    assert with_rc(ctx.plain_mac, dc, n_ct, be.to_dev(pts), i32(src), i32(start), len(src), len(groups), dc, level) == ckksmi.EINVAL
-    assert with_rc(ctx.plain_mac, dc, 0, be.to_dev(pts), i32(src), i32(start), len(src), len(groups), out, level) == ckksmi.EINVAL
+    assert with_rc(ctx.plain_mac, dc, n_ct, dp, n_pts, i32(table.reshape(-1)), n_groups, dc, level) == ckksmi.EINVAL
+    assert with_rc(ctx.plain_mac, dc, 0, dp, n_pts, i32(table.reshape(-1)), n_groups, out, level) == ckksmi.EINVAL
     ctx.close()
 
 
