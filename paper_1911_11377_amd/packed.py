@@ -324,6 +324,8 @@ class BsgsPlan:
     terms: list         # [(i, j, g, b)] in table order
     pts: object         # device [len(terms)][level][N]: the encoded diagonals, rolled by g*baby slots
     term: object        # device int32 [len(groups)][n_ct]: the plaintext that multiplies rotated copy s in group k, -1 = none
+    ones: object        # device [level][N] of ones: the plaintext 1 in evaluation form (summing groups = products with it)
+    member: object      # device int32 [n_out][len(groups)]: 0 where group k belongs to output block i, -1 elsewhere
 
     def rotation_offsets(self):
         return sorted({b for bb in self.babies.values() for b in bb} | {g * self.baby for _, g in self.groups if g})
@@ -365,8 +367,12 @@ def plan_bsgs(ctx, M, n, level, to_dev, encode=None, baby=None):
                 table[k, slot[(j, d % baby)]] = len(terms)
                 terms.append((i, j, g, d % baby))
                 vecs.append(enc(np.roll(dd[d], g * baby).astype(np.complex128), scale, level))
+    member = np.full((n_out, len(groups)), -1, dtype=np.int32)
+    for k, (i, g) in enumerate(groups):
+        member[i, k] = 0
     return BsgsPlan(level, n_in, n_out, baby, babies, slot, n_ct, groups, sum(1 for _, g in groups if g == 0), terms,
-                    to_dev(np.stack(vecs)), _i32_table(table.reshape(-1), to_dev))
+                    to_dev(np.stack(vecs)), _i32_table(table.reshape(-1), to_dev), to_dev(np.ones((level, ctx.N), dtype=np.uint64)),
+                    _i32_table(member.reshape(-1), to_dev))
 
 
 def bsgs_workspace_bytes(ctx, plan, max_rotations=MAX_ROTATIONS_PER_CALL):
@@ -376,7 +382,7 @@ def bsgs_workspace_bytes(ctx, plan, max_rotations=MAX_ROTATIONS_PER_CALL):
     R = max([min(len(b), max_rotations) for b in plan.babies.values()] + [1])
     aux = max(ctx.rotate_hoisted_workspace_bytes(L, 1, R), ctx.workspace_bytes(ckksmi.OP_ROTATE, L, max(n_giant, 1)),
               ctx.workspace_bytes(ckksmi.OP_RESCALE, L, plan.n_out))
-    return (plan.n_ct + len(plan.groups) + n_giant + plan.n_out) * ct + aux
+    return (plan.n_ct + 2 * len(plan.groups) + plan.n_out) * ct + aux
 
 
 def linear_transform_bsgs(ctx, xs, plan, out, ws, stream=None, max_rotations=MAX_ROTATIONS_PER_CALL):
@@ -389,9 +395,9 @@ def linear_transform_bsgs(ctx, xs, plan, out, ws, stream=None, max_rotations=MAX
     n_groups, n_giant = len(plan.groups), len(plan.groups) - plan.n_plain
     rotated = flat[: plan.n_ct * ct]
     inner = flat[plan.n_ct * ct: (plan.n_ct + n_groups) * ct]
-    turned = flat[(plan.n_ct + n_groups) * ct: (plan.n_ct + n_groups + n_giant) * ct]
-    acc = flat[(plan.n_ct + n_groups + n_giant) * ct: (plan.n_ct + n_groups + n_giant + plan.n_out) * ct]
-    rest = flat[(plan.n_ct + n_groups + n_giant + plan.n_out) * ct:]
+    turned = flat[(plan.n_ct + n_groups) * ct: (plan.n_ct + 2 * n_groups) * ct]
+    acc = flat[(plan.n_ct + 2 * n_groups) * ct: (plan.n_ct + 2 * n_groups + plan.n_out) * ct]
+    rest = flat[(plan.n_ct + 2 * n_groups + plan.n_out) * ct:]
     # 1. the rotated copies of every input block: the block itself, then its baby offsets from one shared ModUp
     for j in range(plan.n_in):
         x = xflat[j * ct:(j + 1) * ct]
@@ -404,19 +410,15 @@ def linear_transform_bsgs(ctx, xs, plan, out, ws, stream=None, max_rotations=MAX
             ctx.rotate_hoisted(x, chunk, rotated[s1 * ct:(s1 + len(chunk)) * ct], L, 1, rest, stream=stream)
     # 2. every inner sum in one launch
     ctx.plain_mac(rotated, plan.n_ct, plan.pts, len(plan.terms), plan.term, n_groups, inner, L, stream=stream)
-    # 3. the sums with g != 0, each rotated by g*baby (one batch of ordinary rotations)
+    # 3. the sums with g = 0 as they are, those with g != 0 rotated by g*baby (one batch of ordinary rotations)
+    if plan.n_plain:
+        ctx.mul_scalar(inner[: plan.n_plain * ct], 1, turned[: plan.n_plain * ct], L, plan.n_plain, stream=stream)
     if n_giant:
-        ctx.rotate(inner[plan.n_plain * ct:], [g * plan.baby for _, g in plan.groups[plan.n_plain:]], turned, L, n_giant, rest, stream=stream)
-    # 4. per output block the sum over g (modular additions: any order gives the same words), then the rescale
-    started = [False] * plan.n_out
-    for k, (i, g) in enumerate(plan.groups):
-        srcbuf = inner[k * ct:(k + 1) * ct] if g == 0 else turned[(k - plan.n_plain) * ct:(k - plan.n_plain + 1) * ct]
-        a = acc[i * ct:(i + 1) * ct]
-        if started[i]:
-            ctx.add(a, srcbuf, a, L, 1, stream=stream)
-        else:
-            ctx.mul_scalar(srcbuf, 1, a, L, 1, stream=stream)
-            started[i] = True
+        ctx.rotate(inner[plan.n_plain * ct:], [g * plan.baby for _, g in plan.groups[plan.n_plain:]], turned[plan.n_plain * ct:], L, n_giant, rest,
+                   stream=stream)
+    # 4. per output block the sum over g, as products with the plaintext 1 (modular additions: the same words in any
+    #    order), then the rescale
+    ctx.plain_mac(turned, n_groups, plan.ones, 1, plan.member, plan.n_out, acc, L, stream=stream)
     ctx.rescale(acc, out, L, plan.n_out, rest, stream=stream)
 
 
