@@ -358,7 +358,39 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
                                              "giant_rotations": sum(len(pl.groups) - pl.n_plain for pl in bs),
                                              "plaintext_products": sum(len(pl.terms) for pl in bs), "levels": [11, lvl_b],
                                              "what": "the same network, every matrix in baby-step / giant-step form (other bits, same decrypted result)"}
-    del keys_b, evk_s, xin_s, wsb, plans_b
+    del keys_b, wsb, plans_b
+    # a 3x32x32 image (Table 1's input size) through the same layer kinds at small width: conv 8@5x5, x, pool + conv 16@5x5,
+    # x, pool + FC 64, x, FC 10; period 8192 = every slot of N = 2^14; 15161 diagonals encoded on the device at plan time
+    topo_c = "single_image_cifar"
+
+    def encode_batch(vecs, scale, level):
+        pts = torch.empty((vecs.shape[0], level, 1 << 14), dtype=torch.int64, device="cuda:0")
+        wse = torch.empty(512 * (1 << 14) * 2, dtype=torch.int64, device="cuda:0")
+        for t0 in range(0, vecs.shape[0], 512):
+            re = torch.from_numpy(__import__("numpy").ascontiguousarray(vecs[t0:t0 + 512])).to("cuda:0")
+            cs.encode_device(re, None, scale, level, re.shape[0], pts[t0:t0 + re.shape[0]], wse)
+        return pts
+
+    t_plan = time.perf_counter()
+    plans_c, n_c, lvl_c, _ = packed.plan_network(cs, wl.cnn_shapes(topo_c), wl.cnn_weights_float(topo_c, 7, sigma=0.1), 11, 2.0 ** 50, to_dev, bsgs=True,
+                                                 encode_batch=encode_batch)
+    torch.cuda.synchronize()
+    t_plan = time.perf_counter() - t_plan
+    bc = [pl for pl in plans_c if isinstance(pl, packed.BsgsPlan)]
+    rots_c = sorted({d for pl in bc for d in pl.rotation_offsets()})
+    keys_c = []
+    for d in rots_c:
+        keys_c.append(uniform_residues(torch, cs.moduli, (cs.beta_top, 2), 1 << 14, gen))
+        cs.galois_key_register(d, keys_c[-1])
+    wsc = torch.empty(packed.network_workspace_bytes(cs, plans_c, 11) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    ms_c = timed(torch, lambda: packed.run_network(cs, xin_s, plans_c, evk_s, 11, wsc), 3)
+    out["single_image_cifar_2e14"] = {"ms_per_image": round(ms_c, 2), "plan_s": round(t_plan, 1), "baby": bc[0].baby, "distinct_keys": len(rots_c),
+                                      "baby_rotations": sum(len(b) for pl in bc for b in pl.babies.values()),
+                                      "giant_rotations": sum(len(pl.groups) - pl.n_plain for pl in bc),
+                                      "plaintext_products": sum(len(pl.terms) for pl in bc),
+                                      "plaintext_GB": round(sum(pl.pts.numel() * 8 for pl in bc) / 1e9, 1), "levels": [11, lvl_c], "period": n_c,
+                                      "what": "one 3x32x32 image, rotation-packed with baby and giant steps: conv 8@5x5, poly2, pool+conv 16@5x5, poly2, pool+FC 64, poly2, FC 10"}
+    del keys_c, evk_s, xin_s, wsc, plans_c
     cs.close()
 
     out.update(conv_layer_workload(torch, ckksmi, wl, gen))

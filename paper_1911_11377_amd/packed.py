@@ -338,8 +338,10 @@ def _i32_table(values, to_dev):
     return to_dev(a.view(np.uint64))
 
 
-def plan_bsgs(ctx, M, n, level, to_dev, encode=None, baby=None):
-    """encode the diagonals of every block of M at scale q_{level-1} in baby-step / giant-step form"""
+def plan_bsgs(ctx, M, n, level, to_dev, encode=None, baby=None, encode_batch=None):
+    """encode the diagonals of every block of M at scale q_{level-1} in baby-step / giant-step form.  encode_batch(vectors
+    [T][N/2] of real slot values, scale, level) -> device [T][level][N], if given, encodes all of them at once (e.g. on
+    the device, ckksmi_encode_device) instead of one host call per diagonal."""
     dg = block_diagonals(M, n, ctx.N // 2)
     baby = baby or bsgs_baby(n)
     enc = encode or (lambda v, s, l: ctx.encode(v, s, l))
@@ -366,12 +368,13 @@ def plan_bsgs(ctx, M, n, level, to_dev, encode=None, baby=None):
                     continue
                 table[k, slot[(j, d % baby)]] = len(terms)
                 terms.append((i, j, g, d % baby))
-                vecs.append(enc(np.roll(dd[d], g * baby).astype(np.complex128), scale, level))
+                vecs.append(np.roll(dd[d], g * baby) if encode_batch else enc(np.roll(dd[d], g * baby).astype(np.complex128), scale, level))
     member = np.full((n_out, len(groups)), -1, dtype=np.int32)
     for k, (i, g) in enumerate(groups):
         member[i, k] = 0
     return BsgsPlan(level, n_in, n_out, baby, babies, slot, n_ct, groups, sum(1 for _, g in groups if g == 0), terms,
-                    to_dev(np.stack(vecs)), _i32_table(table.reshape(-1), to_dev), to_dev(np.ones((level, ctx.N), dtype=np.uint64)),
+                    encode_batch(np.stack(vecs), scale, level) if encode_batch else to_dev(np.stack(vecs)),
+                    _i32_table(table.reshape(-1), to_dev), to_dev(np.ones((level, ctx.N), dtype=np.uint64)),
                     _i32_table(member.reshape(-1), to_dev))
 
 
@@ -430,7 +433,7 @@ def network_period(stages, n_slots):
     return min(n, n_slots)
 
 
-def plan_network(ctx, layer_shapes, weights, level, scale, to_dev, encode=None, bsgs=False):
+def plan_network(ctx, layer_shapes, weights, level, scale, to_dev, encode=None, bsgs=False, encode_batch=None):
     """plans of every stage of a network on one image (BlockPlan, or BsgsPlan with bsgs=True, or
     activation.Poly2Constants), the packing period, the output level and scale"""
     from . import activation
@@ -439,7 +442,7 @@ def plan_network(ctx, layer_shapes, weights, level, scale, to_dev, encode=None, 
     plans = []
     for st in stages:
         if st[0] == "linear":
-            plans.append(plan_bsgs(ctx, st[1], n, level, to_dev, encode) if bsgs else plan_blocks(ctx, st[1], n, level, to_dev, encode))
+            plans.append(plan_bsgs(ctx, st[1], n, level, to_dev, encode, encode_batch=encode_batch) if bsgs else plan_blocks(ctx, st[1], n, level, to_dev, encode))
             level -= 1
         else:
             k = activation.poly2_constants(ctx.q, level, scale)

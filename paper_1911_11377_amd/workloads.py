@@ -139,6 +139,11 @@ CNN_TOPOLOGIES = {
     "single_image_reduced": {"input": (3, 16, 16),
                              "layers": [("conv", 4, 5, 1, 0), ("poly2",), ("pool", 2), ("conv", 6, 3, 1, 0), ("poly2",), ("pool", 2),
                                         ("fc", 16), ("poly2",), ("fc", 2)]},
+    # a 3x32x32 image (the input size of Table 1) through its layer kinds at small width:
+    # 3x32x32 -> 8x28x28 -> 8x14x14 -> 16x10x10 -> 16x5x5 -> 64 -> 10; the longest vector (6272) fills the 8192 slots of N = 2^14
+    "single_image_cifar": {"input": (3, 32, 32),
+                           "layers": [("conv", 8, 5, 1, 0), ("poly2",), ("pool", 2), ("conv", 16, 5, 1, 0), ("poly2",), ("pool", 2),
+                                      ("fc", 64), ("poly2",), ("fc", 10)]},
     "cnn_tiny": {"input": (3, 16, 16),
                  "layers": [("conv", 4, 5, 2, 0), ("square",), ("conv", 4, 3, 2, 0), ("square",), ("conv", 4, 3, 1, 1),
                             ("pool", 2), ("fc", 6), ("square",), ("fc", 2)]},
