@@ -405,6 +405,37 @@ def test_single_image_network_matches_oracle(be, shape, topology):
     pc.case_packed_network(be, shape, seed=381, topology=topology, bsgs=True)
 
 
+def test_grouped_plaintext_products_at_network_size(be):
+    """the launch shape of a 3x32x32 image's widest layer (128 rotated copies, 61 sums, 7655 plaintexts at level 8,
+    N = 2^14): sampled output words against the sum of products in Python integers"""
+    import torch
+
+    announce("grouped plaintext products, 128 x 61 x 7655 at N=2^14")
+    shape, level, n_ct, n_groups = (14, 8, 50, 1, 51, 1), 8, 128, 61
+    ctx = be.context(*shape)
+    N, q = ctx.N, ctx.q
+    r = wl.rng(384, "mac.big")
+    table = np.full((n_groups, n_ct), -1, dtype=np.int32)
+    picks = r.permutation(n_groups * n_ct)[:7655]
+    table.reshape(-1)[np.sort(picks)] = np.arange(7655, dtype=np.int32)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(384)
+    cts = torch.randint(0, 1 << 49, (n_ct, 2, level, N), dtype=torch.int64, device="cuda:0", generator=gen)  # canonical: every prime exceeds 2^49
+    pts = torch.randint(0, 1 << 49, (7655, level, N), dtype=torch.int64, device="cuda:0", generator=gen)
+    tab = torch.from_numpy(np.concatenate([table.reshape(-1), np.zeros(2, np.int32)]).view(np.int64)).to("cuda:0")
+    out = be.empty(n_groups, 2, level, N)
+    ctx.plain_mac(cts, n_ct, pts, 7655, tab, n_groups, out, level)
+    torch.cuda.synchronize()
+    for _ in range(40):
+        g, c, l, w = int(r.integers(n_groups)), int(r.integers(2)), int(r.integers(level)), int(r.integers(N))
+        ss = np.nonzero(table[g] >= 0)[0]
+        xs = cts[torch.from_numpy(ss).to("cuda:0"), c, l, w].cpu().numpy()
+        ys = pts[torch.from_numpy(table[g][ss].astype(np.int64)).to("cuda:0"), l, w].cpu().numpy()
+        want = sum(int(a) * int(b) for a, b in zip(xs, ys)) % int(q[l])
+        assert int(out[g, c, l, w].item()) == want, (g, c, l, w)
+    ctx.close()
+
+
 def test_grouped_plaintext_products(be):
     announce("grouped plaintext products")
     pc.case_plain_mac(be, TINY, seed=382)
