@@ -302,6 +302,13 @@ def secondary_workloads(torch, ckksmi, wl, ctx, a, evk, ws, gen):
     op = torch.empty((2, L - 1, N), dtype=torch.int64, device="cuda:0")
     ms = timed(torch, lambda: packed.linear_transform(c2, a2[0], plan, op, wp), 3)
     out["packed_fc64_2e14"] = {"ms_per_layer": round(ms, 3), "what": "64x64 dense layer on one ciphertext: 63 rotations from one ModUp, level 8 -> 7"}
+    # the same layer with baby and giant steps (8 x 8): 7 hoisted rotations, 7 rotations of the inner sums (offsets 1..7 and 8, 16, .. 56 are registered)
+    plan_b = packed.plan_bsgs(c2, Wd, 64, L, to_dev)
+    wpb = torch.empty(packed.bsgs_workspace_bytes(c2, plan_b) // 8 + 1, dtype=torch.int64, device="cuda:0")
+    ms = timed(torch, lambda: packed.linear_transform_bsgs(c2, a2[0], plan_b, op, wpb), 3)
+    out["packed_fc64_bsgs_2e14"] = {"ms_per_layer": round(ms, 3), "rotation_offsets": len(plan_b.rotation_offsets()),
+                                    "what": "the same layer, baby and giant steps of 8"}
+    del plan_b, wpb
     del lay_keys, wp, op, plan
     del a2, b2, k2, gks, o2, or2, w2, oh, wh
     c2.close()
