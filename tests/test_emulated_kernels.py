@@ -66,6 +66,9 @@ def test_emulated_conv_matrix_cores(be):
     pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=117, Cin=29, H=3, W=3, Oc=8, kh=3, stride=1, pad=1, rows_check=False)
     # one output row of five positions: the four waves take 1 x 4 positions (two tiles, three waves without a position)
     pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=119, Cin=2, H=3, W=7, Oc=8, kh=3, stride=1, pad=0, fc_check=False)
+    # stride 2 with padding, 5 x 5 outputs (waves without a position in both directions), strips of rows that end inside a
+    # 2 x 2 block: the rows below the strip are neither read nor written
+    pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=123, Cin=3, H=9, W=9, Oc=8, kh=3, stride=2, pad=1, fc_check=False)
     # a workgroup walks several tiles / positions: the double-buffered strip, the request for the next position's words
     with be.tuned(2):
         pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=120, Cin=3, H=7, W=6, Oc=8, kh=5, stride=1, pad=1, fc_check=False)    # 2 x 2 blocks, 20 positions

@@ -97,6 +97,8 @@ def test_conv_matrix_cores_shapes(be):
     announce("conv matrix cores, 100 taps and 27 taps")
     pc.case_conv(be, (8, 2, 50, 0, 51, 1), seed=314, Cin=4, H=6, W=5, Oc=17, kh=5, stride=1, pad=0)
     pc.case_conv(be, (8, 2, 50, 0, 51, 1), seed=315, Cin=3, H=4, W=4, Oc=9, kh=3, stride=1, pad=1)
+    announce("conv matrix cores, stride 2 with padding, odd output size, strips of rows that end inside a 2 x 2 block")
+    pc.case_conv(be, (7, 2, 50, 0, 51, 1), seed=320, Cin=3, H=9, W=9, Oc=16, kh=3, stride=2, pad=1)
     announce("conv matrix cores, workgroups that walk several tiles / positions")
     with be.tuned(2):
         pc.case_conv(be, (7, 2, 50, 0, 51, 1), seed=316, Cin=3, H=9, W=8, Oc=33, kh=5, stride=1, pad=1)    # 2 x 2 blocks, 35 positions
