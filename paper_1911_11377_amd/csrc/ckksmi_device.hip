@@ -118,8 +118,9 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
     // limbs actually transformed (the key-switch map skips the limbs of each digit itself)
     const double limbs_work = M.mode == 1 ? (double)items * ((double)M.per_item - M.level) : (double)limbs;
     dim3 grow(limbs, (N1 + R - 1) / R), gcol(limbs, N2 / NTT_TC);
-    // register-tiled kernels for 2^13 <= N <= 2^16
-    const bool v2_rows = c->logN >= 13 && c->logN <= 16, v2_cols = v2_rows;
+    // register-tiled kernels for 2^12 <= N <= 2^16 (always two passes; the generic kernels take one up to N = 2^12)
+    const bool v2_rows = c->logN >= 12 && c->logN <= 16, v2_cols = v2_rows;
+    const bool two_pass = v2_cols || A.LA != 0;
     NttV2Args V;
     V.src = A.src; V.dst = A.dst; V.modc = A.modc; V.tw = forward ? c->d_tww_fwd : c->d_tww_inv; V.tw_ninv = c->d_tw_ninv;
     V.tw_last = A.tw_last; V.fin = fin; V.logN = A.logN; V.map = M; V.p51 = c->p51mask;
@@ -150,7 +151,7 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
         return;
     }
     if (forward) {
-        if (A.LA && (passes & 1)) {
+        if (two_pass && (passes & 1)) {
             if (v2_cols) KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, (ntt_v2_kernel<false, true>), gv2, dim3(V2_THREADS), st, V);
             else KL(c, CKKSMI_K_NTT_FWD_COL, limbs_work, ntt_fwd_kernel<true>, gcol, dim3(NTT_THREADS), st, A);
             // second pass works in place on dst
@@ -167,7 +168,7 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
         // inverse: passes 2 = contiguous (row) pass only, leaving the reduced-double intermediate (register-tiled sizes)
         if (v2_rows) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, (ntt_v2_kernel<true, false>), gv2, dim3(V2_THREADS), st, V);
         else KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
-        if (A.LA && (passes & 1)) {
+        if (two_pass && (passes & 1)) {
             A.src = (const u64d *)dst;
             A.map.src_item_stride = A.map.dst_item_stride;
             V.src = A.src;
@@ -251,6 +252,7 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
         else KL(c, kid, units, (modup_cols_kernel<Q, NS, 1>), grid, block, st, A);                           \
         break;
     switch ((c->logN - 12) * 8 + nsrc) {
+        MODUP_COLS_CASE(0, 1) MODUP_COLS_CASE(0, 2) MODUP_COLS_CASE(0, 3) MODUP_COLS_CASE(0, 4)
         MODUP_COLS_CASE(1, 1) MODUP_COLS_CASE(1, 2) MODUP_COLS_CASE(1, 3) MODUP_COLS_CASE(1, 4)
         MODUP_COLS_CASE(2, 1) MODUP_COLS_CASE(2, 2) MODUP_COLS_CASE(2, 3) MODUP_COLS_CASE(2, 4)
         MODUP_COLS_CASE(3, 1) MODUP_COLS_CASE(3, 2) MODUP_COLS_CASE(3, 3) MODUP_COLS_CASE(3, 4)
@@ -380,7 +382,7 @@ void merged_division(ckksmi_ctx *c, u64 *acc, const u64 *addend, size_t add_item
 // limb joins the special limbs as a conversion source, so one more than k sources must fit.
 inline bool one_conversion_tail_ok(const ckksmi_ctx *c) { return c->fused && c->d_fin_tail != nullptr; }
 
-// Key switch on the register-tiled kernels (2^13 <= N <= 2^16).
+// Key switch on the register-tiled kernels (2^12 <= N <= 2^16).
 // tail: the key switch is followed by a rescale of (result + addend), both components have an addend, and `out` receives
 // the rescaled ciphertexts [items][2][level-1][N] (needs one_conversion_tail_ok).
 // ta != nullptr (the composite multiply; d_eval and addend unused): the polynomial switched is the third tensor component
@@ -735,7 +737,7 @@ int dev_upload_tables(ckksmi_ctx *c) {
         c->d_pmod = upload(c, c->h_pmod.data(), c->h_pmod.size(), ok);
     }
     // register-tiled sizes: constants folded into the last stage of the inverse transforms
-    c->fused = c->logN >= 13 && c->logN <= 16;
+    c->fused = c->logN >= 12 && c->logN <= 16;
     if (c->fused) {
         auto fin = [&](int t, u64 mult, u64 add) {
             const u64 q = c->mod[t];
@@ -1602,7 +1604,7 @@ extern "C" const char *ckksmi_kernel_class_name(const ckksmi_ctx *c, int kernel_
                                                 "encoding kernels", "encryption kernels", "modup_cols_kernel", "conv_mac_mfma_resident_kernel", "conv_mac_mfma_strip_kernel"};
     if (kernel_class < 0 || kernel_class >= CKKSMI_K_COUNT) return "";
     if (c && kernel_class == CKKSMI_K_INNER_HOISTED && !hoisted_tile_ok(c, c->beta_top)) return "inner_product_hoisted_kernel";
-    if (c && c->logN >= 13 && c->logN <= 16) {
+    if (c && c->logN >= 12 && c->logN <= 16) {
         static const char *v2[4] = {"ntt_v2_kernel<false, true>", "ntt_v2_kernel<false, false>", "ntt_v2_kernel<true, false>",
                                     "ntt_v2_kernel<true, true>"};
         if (kernel_class < 4) return v2[kernel_class];

@@ -123,7 +123,7 @@ struct ckksmi_ctx {
     WMul *d_pmod = nullptr;             // device copy (k > 0)
     bool merged_ok = false;             // merged division available: k > 0 and k + 1 <= CKKSMI_MAX_SPECIAL
     P51Mask p51mask = {{0, 0}};
-    bool fused = false;  // 2^13 <= N <= 2^16: register-tiled passes with the limb-wise steps fused into them
+    bool fused = false;  // 2^12 <= N <= 2^16: register-tiled passes with the limb-wise steps fused into them
 
     // registered Galois keys
     std::vector<std::pair<int, const u64 *>> galois;

@@ -1,4 +1,4 @@
-// Fused key-switch / DivRound kernels for 2^13 <= N <= 2^16, built on the register-tiled
+// Fused key-switch / DivRound kernels for 2^12 <= N <= 2^16, built on the register-tiled
 // transform passes of ntt_v2.h.  They remove the HBM round trips between a transform and the
 // limb-wise step next to it:
 //

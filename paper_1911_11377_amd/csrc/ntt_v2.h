@@ -1,4 +1,4 @@
-// Register-tiled limb transforms for N = N1 x 256, N1 = 32 .. 256 (2^13 <= N <= 2^16), gfx950.
+// Register-tiled limb transforms for N = N1 x 256, N1 = 16 .. 256 (2^12 <= N <= 2^16), gfx950.
 //
 // A transform of N = 2^logN points is split into a strided pass over columns (the first
 // k = logN-8 stages, N1 = 2^k-point sub-transforms down the columns of the N1 x 256 matrix)
@@ -327,6 +327,7 @@ __global__ __launch_bounds__(V2_THREADS) void ntt_v2_kernel(NttV2Args A) {
         else ntt_v2_rows<INV, false>(A, lds, t, li);
     } else {
         switch (A.logN) {
+            case 12: if (p51) ntt_v2_cols<INV, 0, true>(A, lds, t, li); else ntt_v2_cols<INV, 0, false>(A, lds, t, li); break;
             case 13: if (p51) ntt_v2_cols<INV, 1, true>(A, lds, t, li); else ntt_v2_cols<INV, 1, false>(A, lds, t, li); break;
             case 14: if (p51) ntt_v2_cols<INV, 2, true>(A, lds, t, li); else ntt_v2_cols<INV, 2, false>(A, lds, t, li); break;
             case 15: if (p51) ntt_v2_cols<INV, 3, true>(A, lds, t, li); else ntt_v2_cols<INV, 3, false>(A, lds, t, li); break;
