@@ -131,7 +131,7 @@ CNN_TOPOLOGIES = {
                                   ("fc", 6), ("poly2",), ("fc", 6), ("poly2",), ("fc", 1)]},
     # a few layers of the same kinds for slow (emulated) checks: 6 -> 4 -> 2 -> 2 -> 2 (padded pooling) -> 2
     "table1_tiny": {"input": (2, 6, 6),
-                    "layers": [("conv", 8, 3, 1, 0), ("poly2",), ("pool", 2), ("conv", 3, 3, 1, 1), ("poly2",), ("pool", 2, 1), ("fc", 2)]},
+                    "layers": [("conv", 4, 3, 1, 0), ("poly2",), ("pool", 2), ("conv", 3, 3, 1, 1), ("poly2",), ("pool", 2, 1), ("fc", 2)]},
     # one image in the rotation-packed layout: strided convolution, activation, pooling merged into the layer after it
     "single_image_tiny": {"input": (2, 8, 8),
                           "layers": [("conv", 3, 3, 2, 1), ("poly2",), ("pool", 2), ("fc", 4), ("poly2",), ("fc", 2)]},

@@ -60,7 +60,7 @@ def test_emulated_conv(be):
 def test_emulated_conv_matrix_cores(be):
     """the three matrix-core kernels: strips shared by 2 x 2 and 1 x 4 positions, weight digits resident, weight digits
     streaming; full and quad steps, two channel groups (the second mostly empty), zero padding, a 51-bit prime, strips of rows"""
-    pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=115, Cin=3, H=4, W=3, Oc=34, kh=5, stride=1, pad=2)     # 75 taps: full + quad step
+    pc.case_conv(be, (6, 2, 51, 0, 52, 1), seed=115, Cin=3, H=3, W=3, Oc=34, kh=5, stride=1, pad=2)     # 75 taps: full + quad step
     pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=116, Cin=4, H=5, W=5, Oc=8, kh=5, stride=1, pad=0, rows_check=False)    # 100 taps
     # 261 taps: more steps than stay in LDS, the streaming kernel; its FC part has 87 taps (two full steps)
     pc.case_conv(be, (6, 1, 50, 0, 51, 1), seed=117, Cin=29, H=3, W=3, Oc=8, kh=3, stride=1, pad=1, rows_check=False)
