@@ -501,7 +501,7 @@ def cnn_in_strips(torch, ckksmi, wl, gen, preset, topology, what):
 
 
 def op_byte_models(N, level, k, alpha, batch):
-    """bytes of one HMult + relinearise + rescale under the two models of the survey's measurement plan (limb = 8N bytes):
+    """bytes of one HMult + relinearise + rescale under two traffic models (limb = 8N bytes):
     compulsory = read two ciphertexts, write one, the key once per batch; stage-wise = every stage reads its inputs once and
     writes its outputs once, nothing fused (tensor, inverse transform of d2, ModUp, forward transforms, inner product,
     ModDown, rescale; transforms counted once per limb)"""
