@@ -104,9 +104,9 @@ def test_emulated_fused_hybrid_at_2e16(be):
         pc.case_rescale(be, (16, 3, 50, 0, 51, 1), seed=113, batch=2, levels=[3])
 
 
-@pytest.mark.parametrize("logN", [13, 14, 15])
+@pytest.mark.parametrize("logN", [12, 13, 14, 15])
 def test_emulated_fused_path_other_sizes(be, logN):
-    """2^13 <= N < 2^16: general column geometry (N1 = 32, 64, 128), 40-, 50- and 51-bit primes"""
+    """2^12 <= N < 2^16: general column geometry (N1 = 16, 32, 64, 128), 40-, 50- and 51-bit primes"""
     with be.tuned(8):
         pc.case_ntt(be, (logN, 2, 50, 1, 51, 1), seed=116, batch=3)
         pc.case_relin_and_composite(be, (logN, 3, 50, 2, 51, 2), seed=117, batch=2, levels=[3, 2])

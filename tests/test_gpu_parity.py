@@ -273,6 +273,7 @@ FEW_PAIRS = (("qm1", "qm1"), ("half_lo", "half_hi"), ("alt", "qm1"), ("onehot", 
 @pytest.mark.parametrize("shape,level,kw", [
     ((5, 5, 40, 2, 41, 2), 5, {}),
     ((9, 9, 51, 2, 51, 2), 9, {}),
+    ((12, 6, 51, 2, 51, 2), 6, {"conv": False, "pairs": FEW_PAIRS}),      # smallest register-tiled size (16-point columns)
     ((13, 24, 50, 3, 51, 3), 24, {"conv": False}),                        # 8 digits of 50-bit primes: eight terms per reduction
     ((14, 15, 51, 3, 51, 3), 15, {"conv": False, "pairs": FEW_PAIRS}),    # 51-bit primes: reduced every four terms
     ((15, 4, 50, 1, 51, 1), 4, {"pairs": FEW_PAIRS}),
