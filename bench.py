@@ -613,11 +613,14 @@ def main():
     import numpy as np
     import torch
 
+    from paper_1911_11377_amd import build as lib_build
     from paper_1911_11377_amd import ckksmi
     from paper_1911_11377_amd import workloads as wl
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if not os.path.exists(lib_build.LIB):  # the library that is built is the one that runs; nothing built yet: build once
+        lib_build.build(force=True)
     if args.conv_only:
         g3 = torch.Generator(device="cuda:0")
         g3.manual_seed(wl.BASE_SEED + 3)
