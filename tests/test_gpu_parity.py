@@ -257,6 +257,22 @@ def test_2e16_rotation_sampled(be):
     ctx.close()
 
 
+@pytest.mark.parametrize("seed", [9000, 9001, 9002])
+def test_more_seeds_through_the_register_tiled_kernels(be, seed):
+    """other random draws (operands, keys, weights) through every fused sequence, word for word"""
+    announce("seed %d" % seed)
+    pc.case_relin_and_composite(be, (13, 4, 50, 2, 51, 2), seed=seed, batch=3, levels=[4, 3])
+    pc.case_relin_and_composite(be, (12, 3, 50, 1, 51, 1), seed=seed, batch=2, levels=[3])
+    pc.case_relin_and_composite(be, (14, 5, 40, 3, 41, 3), seed=seed, batch=2, levels=[5, 2])
+    pc.case_merged_product(be, (13, 4, 50, 2, 51, 2), seed=seed, batch=2, levels=[4, 2])
+    pc.case_rotate(be, (13, 4, 50, 2, 51, 2), seed=seed, rotations=[1, 5, 100], batch=3, level=4)
+    pc.case_rotate_hoisted(be, (13, 4, 50, 2, 51, 2), seed=seed, rotations=[1, 2, 9], batch=2, level=3)
+    pc.case_sum_of_products(be, (13, 4, 50, 2, 51, 2), seed=seed, terms=3, batch=2, levels=[4])
+    pc.case_rescale(be, (15, 3, 50, 0, 51, 1), seed=seed, batch=2, levels=[3, 2])
+    pc.case_conv(be, (8, 2, 51, 0, 52, 1), seed=seed, Cin=3, H=7, W=7, Oc=34, kh=5, stride=1, pad=2, rows_check=False)
+    pc.case_ntt(be, (16, 2, 50, 1, 51, 1), seed=seed, batch=2)
+
+
 def test_item_loops_on_gpu(be):
     """few workgroups per launch, so that every register-tiled kernel loops over several items"""
     announce("item loops")
