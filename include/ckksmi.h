@@ -207,7 +207,8 @@ int ckksmi_hmul_sum_relin_rescale(ckksmi_ctx *ctx, const uint64_t *a, const uint
  * CKKSMI_EUNSUPPORTED when the context has more than 3 special primes. */
 int ckksmi_hmul_relin_rescale_merged(ckksmi_ctx *ctx, const uint64_t *a, const uint64_t *b, const uint64_t *evk, uint64_t *out /*[2][level-1][N]*/, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 /* left rotation of item i by rot[i] slots (host array; each needs a registered
- * key): automorphism X -> X^g first, then key switch of the second component */
+ * key): automorphism X -> X^g first, then key switch of the second component.
+ * out must not overlap a (out == a is refused): several kernels of the call read the input. */
 int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [batch]*/, uint64_t *out, int level, int batch, void *ws, size_t ws_bytes, void *stream);
 
 /* Encoding and encryption on the device (section 2.1), for feeding many fresh ciphertexts without the host in the way.

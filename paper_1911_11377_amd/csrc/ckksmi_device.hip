@@ -100,8 +100,9 @@ LimbMap table_map(const int *index, int n_limbs, size_t src_stride, size_t dst_s
 
 // transform `items` groups of map.per_item limbs; forward: coefficient -> evaluation
 // passes: 3 = whole transform, 1 = strided (column) pass only, 2 = contiguous (row) pass only
+// gal (inverse row pass of the register-tiled sizes only): item i's input is read through the automorphism X -> X^(gal->g[i])
 void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const LimbMap &M, size_t items, hipStream_t st,
-                const FinConst *fin = nullptr, int passes = 3) {
+                const FinConst *fin = nullptr, int passes = 3, const GaloisTab *gal = nullptr) {
     if (items == 0 || M.per_item == 0) return;
     NttArgs A;
     A.src = (const u64d *)src;
@@ -166,7 +167,8 @@ void launch_ntt(ckksmi_ctx *c, bool forward, const u64 *src, u64 *dst, const Lim
         }
     } else {
         // inverse: passes 2 = contiguous (row) pass only, leaving the reduced-double intermediate (register-tiled sizes)
-        if (v2_rows) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, (ntt_v2_kernel<true, false>), gv2, dim3(V2_THREADS), st, V);
+        if (v2_rows && gal) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_v2_inv_rows_gal_kernel, gv2, dim3(V2_THREADS), st, V, *gal);
+        else if (v2_rows) KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, (ntt_v2_kernel<true, false>), gv2, dim3(V2_THREADS), st, V);
         else KL(c, CKKSMI_K_NTT_INV_ROW, limbs_work, ntt_inv_kernel<false>, grow, dim3(NTT_THREADS), st, A);
         if (two_pass && (passes & 1)) {
             A.src = (const u64d *)dst;
@@ -391,7 +393,7 @@ inline bool one_conversion_tail_ok(const ckksmi_ctx *c) { return c->fused && c->
 void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyTab &K, int items, int level, const u64 *addend,
                    size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, u64 *ws, hipStream_t st,
                    bool tail = false, bool merged = false, const HoistPlan *hoist = nullptr, const u64 *ta = nullptr, const u64 *tb = nullptr,
-                   int terms = 1) {
+                   int terms = 1, const GaloisTab *gal = nullptr) {
     const size_t N = c->N;
     const int E = level + c->k, beta = (level + c->alpha - 1) / c->alpha;
     const int R = hoist ? hoist->R : 1;  // hoisted rotations: R accumulator pairs per item
@@ -404,7 +406,7 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     // y_i = d_i * qhat_i^-1 comes straight out of the inverse transform (row pass here, column pass inside the conversion
     // kernel); the conversion rides on the column pass of the forward transform of its results
     const FinConst *fin_up = c->d_fin_modup + (size_t)level * c->n_q;
-    if (!ta) launch_ntt(c, false, d_eval, ymid, table_map(idx, level, d_stride, (size_t)level * N), items, st, fin_up, 2);
+    if (!ta) launch_ntt(c, false, d_eval, ymid, table_map(idx, level, d_stride, (size_t)level * N), items, st, fin_up, 2, gal);
     launch_modup_cols(c, 0, ymid, 0, dtA, items, level, 0, nullptr, (double)items * (beta * E - level), st, fin_up);
     int sidx[CKKSMI_MAX_SPECIAL];
     for (int m = 0; m < c->k; m++) sidx[m] = c->n_q + m;
@@ -434,7 +436,8 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
     RI.Pinv = c->divround[0].Binv;
     RI.addend = (const u64d *)addend; RI.add_item_stride = add_item_stride; RI.add_comp_stride = add_comp_stride;
     RI.ta = (const u64d *)ta; RI.tb = (const u64d *)tb; RI.terms = terms; RI.keep_acc = merged ? 1 : 0; RI.Pmod = c->d_pmod;
-    KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
+    if (gal) KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_gal_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K, *gal);
+    else KL(c, CKKSMI_K_ROWS_INNER, (double)items * E, rows_inner_kernel, dim3(RI.kt * items, tiles / RI.kt, E), dim3(V2_THREADS), st, RI, K);
     if (merged) {
         merged_division(c, acc, ta ? nullptr : addend, add_item_stride, add_comp_stride, out, tmp, items, level, st);
         return;
@@ -1218,6 +1221,15 @@ extern "C" int ckksmi_rotate(ckksmi_ctx *c, const uint64_t *a, const int *rot, u
         u64 *sig = (u64 *)ws;  // [items][2][level][N]
         u64 *rest = sig + (size_t)items * 2 * level * N;
         const size_t total = (size_t)items * 2 * level * N;
+        if (c->fused) {
+            // register-tiled sizes: no rotated copy is written; the kernels that read c1 (inverse row pass, the own digit's
+            // term of the inner product) and c0 (the addend) read them through the automorphism
+            const u64 *ai = a + (size_t)b0 * 2 * level * N;
+            ks_core_fused(c, ai + (size_t)level * N, (size_t)2 * level * N, K, items, level, ai, (size_t)2 * level * N, 0, 0,
+                          out + (size_t)b0 * 2 * level * N, rest, S(stream), false, false, nullptr, nullptr, nullptr, 1, &G);
+            b0 += items;
+            continue;
+        }
         KL(c, CKKSMI_K_AUTOMORPH, (double)items * 2 * level, automorphism_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream), (const u64d *)(a + (size_t)b0 * 2 * level * N),
                       (u64d *)sig, G, c->logN, 2 * level, total);
         ks_core(c, sig + (size_t)level * N, (size_t)2 * level * N, K, items, level, sig, (size_t)2 * level * N, 0, 0,

@@ -660,6 +660,17 @@ __device__ __forceinline__ unsigned automorphism_source(unsigned j, unsigned g, 
     return __brev((e - 1u) >> 1) >> (32 - logN);
 }
 
+// The automorphism seen from the row-pair layout of the register-tiled kernels.  j and j + 1 (j even) differ in the top
+// bit of brev(j), so their sources differ in the lowest bit only: the two words of a result pair are the two words of ONE
+// source pair, in either order.  The low eight bits of j reach only the low eight bits of the source: a 256-word row comes
+// from one source row, and 32 neighbouring words of it from 32 neighbouring words.  A kernel that reads rows in pairs can
+// therefore read THROUGH the automorphism with the same 16-byte accesses and the same cache lines per instruction.
+__device__ __forceinline__ ulonglong2 galois_pair_load(const u64d *limb, unsigned j_even, unsigned g, int logN) {
+    const unsigned src = automorphism_source(j_even, g, logN);
+    const ulonglong2 v = ((const ulonglong2 *)limb)[src >> 1];
+    return (src & 1u) ? make_ulonglong2(v.y, v.x) : v;
+}
+
 // grid: x = word block, y = extended limb, z = rotation
 __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_kernel(HoistArgs A) {
     const unsigned N = 1u << A.logN;

@@ -478,9 +478,11 @@ struct RowsInnerArgs {
     const WMul *Pmod;    // [T] P mod q_i
 };
 
-template <bool P51>
+// GAL (a rotation): the source polynomial d_eval and the addend are read through the automorphism X -> X^g of their item
+// (gal->g[item]), so that no rotated copy of the ciphertext is ever written
+template <bool P51, bool GAL = false>
 __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const KeyTab &K, double *lds, double *tw1_lds, double *tw2_lds, int t,
-                                                unsigned x) {
+                                                unsigned x, const GaloisTab *gal = nullptr) {
     constexpr int F1 = P51 ? 0xA : 0x8, F2 = P51 ? 0x2 : 0x0;
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
@@ -509,7 +511,7 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     // accumulator 2*s + b belongs to the word at column 32*s + 2*lo4 + b of row hi4.
     // The digit that contains this limb needs no transform: its operand is the source polynomial itself.
     const int j_own = (int)x < A.level ? (int)x / A.alpha : -1;
-    const bool tensor_mode = A.ta != nullptr && j_own >= 0;
+    const bool tensor_mode = !GAL && A.ta != nullptr && j_own >= 0;
     int pending = 1;  // terms in the accumulators since their last reduction (the own digit's term counts)
     if (tensor_mode) {
         // d0, d1, d2 of the thread's 16 words from the operands (summed over the terms, balanced-reduced)
@@ -567,11 +569,12 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     } else if (j_own >= 0) {
         const u64d *k0 = key + (((size_t)j_own * 2 + 0) * A.T + t) * N + tile0;
         const u64d *k1 = key + (((size_t)j_own * 2 + 1) * A.T + t) * N + tile0;
-        const u64d *src = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N + tile0;
+        const u64d *limb = A.d_eval + (size_t)item * A.d_eval_item_stride + (size_t)x * N, *src = limb + tile0;
         ulonglong2 kr0[8], kr1[8], xo[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            xo[s] = ((const ulonglong2 *)src)[row_pair_index(hi4, lo4, s)];
+            if (GAL) xo[s] = galois_pair_load(limb, (unsigned)tile0 + hi4 * 256u + 32u * s + 2u * lo4, gal->g[item], A.logN);
+            else xo[s] = ((const ulonglong2 *)src)[row_pair_index(hi4, lo4, s)];
             kr0[s] = ((const ulonglong2 *)k0)[row_pair_index(hi4, lo4, s)];
             kr1[s] = ((const ulonglong2 *)k1)[row_pair_index(hi4, lo4, s)];
         }
@@ -677,15 +680,21 @@ __device__ __forceinline__ void rows_inner_body(const RowsInnerArgs &A, const Ke
     }
     if (!tensor_mode && A.fold_tail && (int)x < A.level) {
         const WMul Pi = A.Pinv[t];
-        const u64d *d0 = A.addend + (size_t)item * A.add_item_stride + (size_t)x * N + tile0;
+        const u64d *l0 = A.addend + (size_t)item * A.add_item_stride + (size_t)x * N, *d0 = l0 + tile0;
         const bool both = A.fold_tail == 1;  // 2: only the first component has an addend (rotation)
-        const u64d *d1 = both ? d0 + A.add_comp_stride : d0;
+        const u64d *l1 = both ? l0 + A.add_comp_stride : l0, *d1 = l1 + tile0;
         const double has1 = both ? 1.0 : 0.0;
         ulonglong2 dw0[8], dw1[8];
 #pragma unroll
         for (int s = 0; s < 8; s++) {
-            dw0[s] = ((const ulonglong2 *)d0)[row_pair_index(hi4, lo4, s)];
-            dw1[s] = ((const ulonglong2 *)d1)[row_pair_index(hi4, lo4, s)];
+            if (GAL) {
+                const unsigned j = (unsigned)tile0 + hi4 * 256u + 32u * s + 2u * lo4;
+                dw0[s] = galois_pair_load(l0, j, gal->g[item], A.logN);
+                dw1[s] = both ? galois_pair_load(l1, j, gal->g[item], A.logN) : dw0[s];
+            } else {
+                dw0[s] = ((const ulonglong2 *)d0)[row_pair_index(hi4, lo4, s)];
+                dw1[s] = ((const ulonglong2 *)d1)[row_pair_index(hi4, lo4, s)];
+            }
         }
 #pragma unroll
         for (int s = 0; s < 8; s++) {
@@ -715,6 +724,19 @@ __global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_kernel(RowsInnerArgs
         rows_inner_body<true>(A, K, lds, tw1_lds, tw2_lds, t, x);
     else
         rows_inner_body<false>(A, K, lds, tw1_lds, tw2_lds, t, x);
+}
+
+// the same for rotations: source polynomial and addend read through the items' automorphisms (no tensor mode here)
+__global__ __launch_bounds__(V2_THREADS, 2) void rows_inner_gal_kernel(RowsInnerArgs A, KeyTab K, GaloisTab G) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ double tw1_lds[16 * 16];
+    __shared__ double tw2_lds[15 * 256];
+    const unsigned x = blockIdx.z;
+    const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
+    if (is_p51(A.p51, t))
+        rows_inner_body<true, true>(A, K, lds, tw1_lds, tw2_lds, t, x, &G);
+    else
+        rows_inner_body<false, true>(A, K, lds, tw1_lds, tw2_lds, t, x, &G);
 }
 
 // ------------------------------------------------------------------ row pass + DivRound final step

@@ -244,8 +244,10 @@ __device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int
     }
 }
 
-template <bool INV, bool P51>
-__device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int t, unsigned li) {
+// GAL (inverse only): the input is read through the automorphism X -> X^g of its item (G->g[item]): a rotation's
+// polynomial enters its key switch without a pass of its own
+template <bool INV, bool P51, bool GAL = false>
+__device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int t, unsigned li, const GaloisTab *G = nullptr) {
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[t].p, pinv = A.modc[t].pinv;
     const double *tw = A.tw + (size_t)t * N;
@@ -288,7 +290,10 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
                 // (row-pair layout: 16 bytes per lane and load)
                 ulonglong2 raw[8];
 #pragma unroll
-                for (int s = 0; s < 8; s++) raw[s] = ((const ulonglong2 *)(src + tile0))[row_pair_index(hi4, lo4, s)];
+                for (int s = 0; s < 8; s++) {
+                    if (GAL) raw[s] = galois_pair_load(src, (unsigned)tile0 + hi4 * 256u + 32u * s + 2u * lo4, G->g[it], A.logN);
+                    else raw[s] = ((const ulonglong2 *)(src + tile0))[row_pair_index(hi4, lo4, s)];
+                }
                 NTT_SCHED_FENCE();
 #pragma unroll
                 for (int s = 0; s < 8; s++) {
@@ -312,6 +317,16 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
         }
         ROW_GROUP_SYNC();
     }
+}
+
+// inverse row pass of a rotation's polynomial: same grid as ntt_v2_kernel, input read through the items' automorphisms
+__global__ __launch_bounds__(V2_THREADS) void ntt_v2_inv_rows_gal_kernel(NttV2Args A, GaloisTab G) {
+    __shared__ double lds[16 * V2_GS];
+    unsigned item_unused, li;
+    const int t = resolve_limb(A.map, blockIdx.y, item_unused, li);
+    if (t < 0) return;
+    if (is_p51(A.p51, t)) ntt_v2_rows<true, true, true>(A, lds, t, li, &G);
+    else ntt_v2_rows<true, false, true>(A, lds, t, li, &G);
 }
 
 // grid: x = tile (N/4096), y = limb slot within an item, z = chunk of items

@@ -52,6 +52,14 @@ def test_emulated_rotate(be, shape, level):
     pc.case_rotate(be, shape, seed=106, rotations=[1, 3, 7], batch=4, level=level)
 
 
+def test_emulated_rotate_register_tiled_sizes(be):
+    """2^12 <= N: no rotated copy is written; the inverse row pass and the fused inner product read c1 and c0 through the
+    automorphism (rows of pairs); several items per workgroup, partial last digit"""
+    pc.case_rotate(be, (12, 3, 50, 2, 51, 2), seed=126, rotations=[1, 3, 700], batch=3, level=3)
+    with be.tuned(8):
+        pc.case_rotate(be, (13, 2, 51, 1, 51, 1), seed=127, rotations=[5, 2047, 4095], batch=4, level=2)
+
+
 def test_emulated_conv(be):
     pc.case_conv(be, TINY, seed=107, Cin=2, H=5, W=5, Oc=9, kh=3, stride=2, pad=0)
     pc.case_conv(be, TINY, seed=108, Cin=1, H=4, W=4, Oc=2, kh=3, stride=1, pad=1, level=2)
