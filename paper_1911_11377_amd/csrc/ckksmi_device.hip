@@ -269,7 +269,7 @@ void launch_modup_cols(ckksmi_ctx *c, int mode, const u64 *y, size_t y_stride, u
 void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_row_stride, const u64 *addend, size_t add_item_stride,
                        size_t add_comp_stride, int add_both, u64 *out, const WMul *Binv, int nc, int rows, hipStream_t st, int limb0 = 0,
                        int limb_count = -1, size_t out_row_stride = 0, const WMul *pre = nullptr, const WMul *xmul = nullptr,
-                       const ScalarTab *stab = nullptr, bool zsub = false) {
+                       const ScalarTab *stab = nullptr, bool zsub = false, const RowsFinalGal *gal = nullptr) {
     RowsFinalArgs A;
     A.zsub = zsub ? 1 : 0;
     A.pre = pre;
@@ -287,6 +287,8 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
     const unsigned xch = zchunks_for(c, tiles * nz, rows, A.rows_per_x);
     if (stab)
         KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_scalar_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A, *stab);
+    else if (gal)
+        KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_gal_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A, *gal);
     else
         KL(c, CKKSMI_K_ROWS_FINAL, (double)rows * nz, rows_final_kernel, dim3(xch, tiles, nz), dim3(V2_THREADS), st, A);
 }
@@ -296,12 +298,13 @@ void launch_rows_final(ckksmi_ctx *c, const u64 *tmpA, const u64 *x, size_t x_ro
 // zsub: the kept limbs already hold x * Bbar^-1 + addend, out = x - NTT(r - h) * Bbar^-1.
 void divround_rows(ckksmi_ctx *c, const DivRoundDev &D, const FinConst *fin, const int *bidx, const u64 *b_limbs, size_t b_stride,
                    u64 *b_scratch, size_t bs_stride, const u64 *x, size_t x_stride, u64 *tmp, int nc, int rows, const u64 *addend,
-                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, hipStream_t st, bool zsub = false) {
+                   size_t add_item_stride, size_t add_comp_stride, int add_both, u64 *out, hipStream_t st, bool zsub = false,
+                   const RowsFinalGal *gal = nullptr) {
     // inverse row pass of the dropped limbs; the conversion kernel runs their inverse column pass itself
     launch_ntt(c, false, b_limbs, b_scratch, table_map(bidx, D.nb, b_stride, bs_stride), rows, st, fin, 2);
     launch_modup_cols(c, 1, b_scratch, bs_stride, tmp, rows, 0, nc, &D, (double)rows * nc, st, fin);
     launch_rows_final(c, tmp, x, x_stride, addend, add_item_stride, add_comp_stride, add_both, out, D.Binv, nc, rows, st, 0, -1, 0, nullptr, nullptr,
-                      nullptr, zsub);
+                      nullptr, zsub, gal);
 }
 
 // Rotations with a shared ModUp: R rotations of every item of a key-switch sweep (see inner_product_hoisted_kernel)
@@ -309,7 +312,9 @@ struct HoistPlan {
     int R;
     unsigned g[CKKSMI_MAX_KEYS], ginv[CKKSMI_MAX_KEYS];
     const u64 *key[CKKSMI_MAX_KEYS];
-    const u64 *sig;  // sigma_r(c0) of every item: [items][R][level][N], the addend of the first component
+    const u64 *sig;  // sigma_r(c0) of every item: [items][R][level][N], the addend of the first component (generic kernels)
+    const u64 *c0;   // register-tiled sizes: the input ciphertexts (item stride c0_stride words), whose first component the
+    size_t c0_stride;  // last pass reads through the automorphisms instead
 };
 
 // the gather through LDS needs runs of 256 words and at most INNER_MAX_BETA digits; otherwise the plain gather kernel
@@ -419,8 +424,11 @@ void ks_core_fused(ckksmi_ctx *c, const u64 *d_eval, size_t d_stride, const KeyT
         M1.src_item_stride = M1.dst_item_stride = (size_t)beta * E * N;
         launch_ntt(c, true, dtA, dtA, M1, items, st, nullptr, 2);
         launch_hoisted_inner(c, *hoist, dtA, d_eval, d_stride, acc, items, level, st);
+        RowsFinalGal FG;
+        FG.R = R;
+        for (int r = 0; r < CKKSMI_MAX_KEYS; r++) FG.g[r] = r < R ? hoist->g[r] : 1u;
         divround_rows(c, c->divround[0], c->d_fin_moddown, sidx, specials, (size_t)E * N, specials, (size_t)E * N, acc, (size_t)E * N, tmp, level,
-                      items * R * 2, hoist->sig, (size_t)level * N, 0, 0, out, st);
+                      items * R * 2, hoist->c0, hoist->c0_stride, 0, 0, out, st, false, &FG);
         return;
     }
     RowsInnerArgs RI;
@@ -1380,9 +1388,11 @@ extern "C" int ckksmi_rotate_hoisted(ckksmi_ctx *c, const uint64_t *a, const int
         HA.logN = c->logN; HA.level = level; HA.R = n_rot;
         for (int r = 0; r < n_rot; r++) HA.g[r] = H.g[r];
         const size_t total = (size_t)items * n_rot * level * N;
-        KL(c, CKKSMI_K_AUTOMORPH_BCAST, (double)items * n_rot * level, automorphism_bcast_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream),
-           (const u64d *)ain, (unsigned long long)((size_t)2 * level * N), (u64d *)sig, HA, total);
-        H.sig = sig;
+        // register-tiled sizes: the last pass reads sigma_r(c0) from the input through the automorphism; otherwise it is written here
+        if (!c->fused)
+            KL(c, CKKSMI_K_AUTOMORPH_BCAST, (double)items * n_rot * level, automorphism_bcast_kernel, dim3(ew_blocks(total)), dim3(EW_THREADS), S(stream),
+               (const u64d *)ain, (unsigned long long)((size_t)2 * level * N), (u64d *)sig, HA, total);
+        H.sig = sig; H.c0 = ain; H.c0_stride = (size_t)2 * level * N;
         ks_core(c, ain + (size_t)level * N, (size_t)2 * level * N, K, items, level, nullptr, 0, 0, 0, out + (size_t)b0 * n_rot * 2 * level * N, rest,
                 S(stream), false, &H);
     }

@@ -762,9 +762,14 @@ struct RowsFinalArgs {
     P51Mask p51;
 };
 
-template <bool P51>
+// Rotations from a shared ModUp: rows come in pairs (item, rotation r), R rotations per item; the first row of a pair adds
+// sigma_r(c0 of its item), read through the automorphism from the input ciphertext itself (A.addend = c0 of item 0,
+// A.add_item_stride = words between the items' ciphertexts)
+struct RowsFinalGal { int R; unsigned g[CKKSMI_MAX_KEYS]; };
+
+template <bool P51, bool GAL = false>
 __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *lds, double *tw1_lds, int i, bool xm_val = false,
-                                                WMul xmv = WMul{0.0, 0.0}) {
+                                                WMul xmv = WMul{0.0, 0.0}, const RowsFinalGal *gal = nullptr) {
     const unsigned N = 1u << A.logN, N1 = N >> 8;
     const double p = A.modc[i].p, pinv = A.modc[i].pinv;
     const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15;
@@ -789,7 +794,13 @@ __device__ __forceinline__ void rows_final_body(const RowsFinalArgs &A, double *
 #pragma unroll
         for (int s = 0; s < 8; s++) {
             xr[s] = ((const ulonglong2 *)xin)[row_pair_index(hi4, lo4, s)];
-            ar[s] = ((const ulonglong2 *)ad)[row_pair_index(hi4, lo4, s)];
+            if (GAL && add) {
+                const unsigned pair = row / 2u, item = pair / (unsigned)gal->R, r = pair % (unsigned)gal->R;
+                ar[s] = galois_pair_load(A.addend + (size_t)item * A.add_item_stride + (size_t)i * N,
+                                         (unsigned)tile0 + hi4 * 256u + 32u * s + 2u * lo4, gal->g[r], A.logN);
+            } else {
+                ar[s] = ((const ulonglong2 *)ad)[row_pair_index(hi4, lo4, s)];
+            }
         }
         SCHED_FENCE();
         rows_fwd_to_lds<P51>(A.tmpA + ((size_t)row * A.nc + i) * N + tile0, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
@@ -834,6 +845,17 @@ __global__ __launch_bounds__(V2_THREADS) void rows_final_kernel(RowsFinalArgs A)
         rows_final_body<true>(A, lds, tw1_lds, i);
     else
         rows_final_body<false>(A, lds, tw1_lds, i);
+}
+
+// the same for rotations from a shared ModUp: the addend sigma_r(c0) is read through the automorphism
+__global__ __launch_bounds__(V2_THREADS) void rows_final_gal_kernel(RowsFinalArgs A, RowsFinalGal G) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ double tw1_lds[16 * 16];
+    const int i = A.limb0 + (int)blockIdx.z;
+    if (is_p51(A.p51, i))
+        rows_final_body<true, true>(A, lds, tw1_lds, i, false, WMul{0.0, 0.0}, &G);
+    else
+        rows_final_body<false, true>(A, lds, tw1_lds, i, false, WMul{0.0, 0.0}, &G);
 }
 
 // the same with the kept limb multiplied by a per-call scalar first: out = (c*x - r) * Binv (+ addend): rescale of c*x
