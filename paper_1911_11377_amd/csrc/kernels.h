@@ -730,12 +730,15 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_kernel(Hoist
 // The same sums organised around the SOURCE: a workgroup stages one 256-word run of every lifted digit of a few items
 // in LDS (read from HBM once for all rotations), then walks the rotations: rotation r sends this run to exactly one
 // 256-word run of its output (found through the inverse automorphism), gathered out of LDS.
+// Words travel in pairs: an output pair (2m, 2m + 1) is one source pair, possibly with its words exchanged (see
+// galois_pair_load), so key words, staged words and results all move 16 bytes per lane.  The first 128 threads form the
+// first component's sums, the other 128 the second's (each key word is read once).
 #define HOIST_LDS_WORDS 8192  // 64 KiB: items_per_wg * beta * 256 words
 // grid: x = source run (N/256), y = extended limb, z = (chunk of items_per_wg items, chunk of rots_per_wg rotations)
 __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(HoistArgs A) {
     __shared__ double tile[HOIST_LDS_WORDS];
     const unsigned N = 1u << A.logN;
-    const unsigned tid = threadIdx.x, src0 = blockIdx.x * 256u, x = blockIdx.y;
+    const unsigned tid = threadIdx.x, pr = tid & 127u, comp = tid >> 7, src0 = blockIdx.x * 256u, x = blockIdx.y;
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
     const ModConst mc = A.modc[t];
     const int j_own = (A.d_eval && (int)x < A.level) ? (int)x / A.alpha : -1;
@@ -743,61 +746,73 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
     const int r_begin = (int)(blockIdx.z / (unsigned)A.item_chunks) * A.rots_per_wg;
     const int r_end = r_begin + A.rots_per_wg < A.R ? r_begin + A.rots_per_wg : A.R;
     const int n_items = (item0 + A.items_per_wg < A.items ? item0 + A.items_per_wg : A.items) - item0;
-    for (int ii = 0; ii < n_items; ii++) {
-        // all digits of an item requested together (a load per iteration followed by its LDS write would serialise them)
-        const size_t item = (size_t)(item0 + ii);
-        u64d raw[INNER_MAX_BETA];
+    {
+        // the staged rows (item, digit), at most HOIST_LDS_WORDS / 256 = 32 of them: the two halves of the workgroup take
+        // them in turn, all of a half's rows requested together (a load per iteration followed by its LDS write would
+        // serialise them)
+        const int n_rows = n_items * A.beta;
+        ulonglong2 raw[HOIST_LDS_WORDS / 512];
 #pragma unroll
-        for (int j = 0; j < INNER_MAX_BETA; j++)
-            if (j < A.beta) {
+        for (int k = 0; k < HOIST_LDS_WORDS / 512; k++) {
+            const int q = 2 * k + (int)comp;
+            if (q < n_rows) {
+                const size_t item = (size_t)(item0 + q / A.beta);
+                const int j = q % A.beta;
                 const u64d *row = j == j_own ? A.d_eval + item * A.d_eval_item_stride + (size_t)x * N : A.dt + ((item * A.beta + j) * A.E + x) * N;
-                raw[j] = row[src0 + tid];
+                raw[k] = ((const ulonglong2 *)(row + src0))[pr];
             }
+        }
 #pragma unroll
-        for (int j = 0; j < INNER_MAX_BETA; j++)
-            if (j < A.beta) tile[(ii * A.beta + j) * 256 + tid] = u2d(raw[j]);
+        for (int k = 0; k < HOIST_LDS_WORDS / 512; k++) {
+            const int q = 2 * k + (int)comp;
+            if (q < n_rows) ((double2 *)(tile + q * 256))[pr] = make_double2(u2d(raw[k].x), u2d(raw[k].y));
+        }
     }
     __syncthreads();
     // the key words of rotation r + 1 are requested before the sums of rotation r, so their latency is covered
-    double kn0[INNER_MAX_BETA], kn1[INNER_MAX_BETA];
-    unsigned m_next = (automorphism_source(src0, A.ginv[r_begin], A.logN) & ~255u) + tid;  // this run's image under the first rotation
+    ulonglong2 kn[INNER_MAX_BETA];
+    unsigned m_next = (automorphism_source(src0, A.ginv[r_begin], A.logN) & ~255u) + 2u * pr;  // this run's image under the first rotation
 #pragma unroll
     for (int j = 0; j < INNER_MAX_BETA; j++)
-        if (j < A.beta) {
-            kn0[j] = u2d(A.key[r_begin][(((size_t)j * 2 + 0) * A.T + t) * N + m_next]);
-            kn1[j] = u2d(A.key[r_begin][(((size_t)j * 2 + 1) * A.T + t) * N + m_next]);
-        }
+        if (j < A.beta) kn[j] = *(const ulonglong2 *)(A.key[r_begin] + (((size_t)j * 2 + comp) * A.T + t) * N + m_next);
     for (int r = r_begin; r < r_end; r++) {
         const unsigned m = m_next;
-        const unsigned s = automorphism_source(m, A.g[r], A.logN) - src0;  // below 256
+        const unsigned s = automorphism_source(m, A.g[r], A.logN) - src0;  // below 256; the word after m comes from s ^ 1
+        const bool swap = s & 1u;
         double k0[INNER_MAX_BETA], k1[INNER_MAX_BETA];
 #pragma unroll
         for (int j = 0; j < INNER_MAX_BETA; j++) {
-            k0[j] = kn0[j];
-            k1[j] = kn1[j];
+            k0[j] = u2d(kn[j].x);
+            k1[j] = u2d(kn[j].y);
         }
         if (r + 1 < r_end) {
-            m_next = (automorphism_source(src0, A.ginv[r + 1], A.logN) & ~255u) + tid;
+            m_next = (automorphism_source(src0, A.ginv[r + 1], A.logN) & ~255u) + 2u * pr;
             const u64d *key = A.key[r + 1];
 #pragma unroll
             for (int j = 0; j < INNER_MAX_BETA; j++)
-                if (j < A.beta) {
-                    kn0[j] = u2d(key[(((size_t)j * 2 + 0) * A.T + t) * N + m_next]);
-                    kn1[j] = u2d(key[(((size_t)j * 2 + 1) * A.T + t) * N + m_next]);
-                }
+                if (j < A.beta) kn[j] = *(const ulonglong2 *)(key + (((size_t)j * 2 + comp) * A.T + t) * N + m_next);
         }
         for (int ii = 0; ii < n_items; ii++) {
-            double a0 = 0.0, a1 = 0.0;
+            double a0 = 0.0, a1 = 0.0;  // the sums of the words m and m + 1
 #pragma unroll
             for (int j = 0; j < INNER_MAX_BETA; j++)
                 if (j < A.beta) {
-                    const double v = tile[(ii * A.beta + j) * 256 + s];
-                    a0 = reduce_balanced(a0 + mulmod(v, k0[j], mc.p, mc.pinv), mc.p, mc.pinv);
-                    a1 = reduce_balanced(a1 + mulmod(v, k1[j], mc.p, mc.pinv), mc.p, mc.pinv);
+                    const double2 vv = *(const double2 *)(tile + (ii * A.beta + j) * 256 + (s & ~1u));
+                    const double v0 = swap ? vv.y : vv.x, v1 = swap ? vv.x : vv.y;
+                    // a reduced sum (p/2 + 1) and two products (1.25p each) stay below 3p + 1 < 2^53
+                    a0 += mulmod(v0, k0[j], mc.p, mc.pinv);
+                    a1 += mulmod(v1, k1[j], mc.p, mc.pinv);
+                    if (j & 1) {
+                        a0 = reduce_balanced(a0, mc.p, mc.pinv);
+                        a1 = reduce_balanced(a1, mc.p, mc.pinv);
+                    }
                 }
-            const size_t row = ((size_t)(item0 + ii) * A.R + r) * 2;
-            A.acc[((row + 0) * A.E + x) * N + m] = d2u(canon_small(a0, mc.p));
-            A.acc[((row + 1) * A.E + x) * N + m] = d2u(canon_small(a1, mc.p));
+            if (A.beta & 1) {
+                a0 = reduce_balanced(a0, mc.p, mc.pinv);
+                a1 = reduce_balanced(a1, mc.p, mc.pinv);
+            }
+            const size_t row = ((size_t)(item0 + ii) * A.R + r) * 2 + comp;
+            *(ulonglong2 *)(A.acc + (row * A.E + x) * N + m) = make_ulonglong2(d2u(canon_small(a0, mc.p)), d2u(canon_small(a1, mc.p)));
         }
     }
 }
