@@ -339,8 +339,22 @@ void launch_hoisted_inner(ckksmi_ctx *c, const HoistPlan &H, const u64 *dt, cons
         A.rots_per_wg = (H.R + rot_chunks - 1) / rot_chunks;
         rot_chunks = (H.R + A.rots_per_wg - 1) / A.rots_per_wg;
         const unsigned z = (unsigned)(A.item_chunks * rot_chunks);
-        KL(c, CKKSMI_K_INNER_HOISTED, (double)items * H.R * A.E, inner_product_hoisted_tile_kernel, dim3((unsigned)(c->N / 256), A.E, z),
-           dim3(EW_THREADS), st, A);
+        const int need = A.items_per_wg * A.beta * 256;  // staged words
+        const dim3 grid((unsigned)(c->N / 256), A.E, z);
+        const double work = (double)items * H.R * A.E;
+#define HOIST_TILE(LW, MB) KL(c, CKKSMI_K_INNER_HOISTED, work, (inner_product_hoisted_tile_kernel<LW, MB>), grid, dim3(EW_THREADS), st, A)
+#define HOIST_TILE_LW(MB)                      \
+    do {                                       \
+        if (need <= 1024) HOIST_TILE(1024, MB);       \
+        else if (need <= 2048) HOIST_TILE(2048, MB);  \
+        else if (need <= 4096) HOIST_TILE(4096, MB);  \
+        else HOIST_TILE(HOIST_LDS_WORDS, MB);         \
+    } while (0)
+        if (A.beta <= 4) HOIST_TILE_LW(4);
+        else if (A.beta <= 8) HOIST_TILE_LW(8);
+        else HOIST_TILE_LW(INNER_MAX_BETA);
+#undef HOIST_TILE_LW
+#undef HOIST_TILE
         return;
     }
     KL(c, CKKSMI_K_INNER_HOISTED, (double)items * H.R * A.E, inner_product_hoisted_kernel, dim3(ew_blocks(c->N), A.E, H.R), dim3(EW_THREADS), st, A);

@@ -733,10 +733,14 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_kernel(Hoist
 // Words travel in pairs: an output pair (2m, 2m + 1) is one source pair, possibly with its words exchanged (see
 // galois_pair_load), so key words, staged words and results all move 16 bytes per lane.  The first 128 threads form the
 // first component's sums, the other 128 the second's (each key word is read once).
-#define HOIST_LDS_WORDS 8192  // 64 KiB: items_per_wg * beta * 256 words
+#define HOIST_LDS_WORDS 8192  // 64 KiB: items_per_wg * beta * 256 words at most
+// LW: words of LDS, the smallest of 1024 .. HOIST_LDS_WORDS that holds the staged rows (few items: more workgroups per
+// compute unit, whose dependent key reads then overlap); MB: bound on the number of digits (4, 8 or INNER_MAX_BETA), which
+// sizes the registers that hold a rotation's key words
 // grid: x = source run (N/256), y = extended limb, z = (chunk of items_per_wg items, chunk of rots_per_wg rotations)
+template <int LW, int MB>
 __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(HoistArgs A) {
-    __shared__ double tile[HOIST_LDS_WORDS];
+    __shared__ double tile[LW];
     const unsigned N = 1u << A.logN;
     const unsigned tid = threadIdx.x, pr = tid & 127u, comp = tid >> 7, src0 = blockIdx.x * 256u, x = blockIdx.y;
     const int t = (int)x < A.level ? (int)x : A.n_q + (int)x - A.level;
@@ -747,13 +751,13 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
     const int r_end = r_begin + A.rots_per_wg < A.R ? r_begin + A.rots_per_wg : A.R;
     const int n_items = (item0 + A.items_per_wg < A.items ? item0 + A.items_per_wg : A.items) - item0;
     {
-        // the staged rows (item, digit), at most HOIST_LDS_WORDS / 256 = 32 of them: the two halves of the workgroup take
+        // the staged rows (item, digit), at most LW / 256 of them: the two halves of the workgroup take
         // them in turn, all of a half's rows requested together (a load per iteration followed by its LDS write would
         // serialise them)
         const int n_rows = n_items * A.beta;
-        ulonglong2 raw[HOIST_LDS_WORDS / 512];
+        ulonglong2 raw[LW / 512];
 #pragma unroll
-        for (int k = 0; k < HOIST_LDS_WORDS / 512; k++) {
+        for (int k = 0; k < LW / 512; k++) {
             const int q = 2 * k + (int)comp;
             if (q < n_rows) {
                 const size_t item = (size_t)(item0 + q / A.beta);
@@ -763,25 +767,25 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
             }
         }
 #pragma unroll
-        for (int k = 0; k < HOIST_LDS_WORDS / 512; k++) {
+        for (int k = 0; k < LW / 512; k++) {
             const int q = 2 * k + (int)comp;
             if (q < n_rows) ((double2 *)(tile + q * 256))[pr] = make_double2(u2d(raw[k].x), u2d(raw[k].y));
         }
     }
     __syncthreads();
     // the key words of rotation r + 1 are requested before the sums of rotation r, so their latency is covered
-    ulonglong2 kn[INNER_MAX_BETA];
+    ulonglong2 kn[MB];
     unsigned m_next = (automorphism_source(src0, A.ginv[r_begin], A.logN) & ~255u) + 2u * pr;  // this run's image under the first rotation
 #pragma unroll
-    for (int j = 0; j < INNER_MAX_BETA; j++)
+    for (int j = 0; j < MB; j++)
         if (j < A.beta) kn[j] = *(const ulonglong2 *)(A.key[r_begin] + (((size_t)j * 2 + comp) * A.T + t) * N + m_next);
     for (int r = r_begin; r < r_end; r++) {
         const unsigned m = m_next;
         const unsigned s = automorphism_source(m, A.g[r], A.logN) - src0;  // below 256; the word after m comes from s ^ 1
         const bool swap = s & 1u;
-        double k0[INNER_MAX_BETA], k1[INNER_MAX_BETA];
+        double k0[MB], k1[MB];
 #pragma unroll
-        for (int j = 0; j < INNER_MAX_BETA; j++) {
+        for (int j = 0; j < MB; j++) {
             k0[j] = u2d(kn[j].x);
             k1[j] = u2d(kn[j].y);
         }
@@ -789,13 +793,13 @@ __global__ __launch_bounds__(EW_THREADS) void inner_product_hoisted_tile_kernel(
             m_next = (automorphism_source(src0, A.ginv[r + 1], A.logN) & ~255u) + 2u * pr;
             const u64d *key = A.key[r + 1];
 #pragma unroll
-            for (int j = 0; j < INNER_MAX_BETA; j++)
+            for (int j = 0; j < MB; j++)
                 if (j < A.beta) kn[j] = *(const ulonglong2 *)(key + (((size_t)j * 2 + comp) * A.T + t) * N + m_next);
         }
         for (int ii = 0; ii < n_items; ii++) {
             double a0 = 0.0, a1 = 0.0;  // the sums of the words m and m + 1
 #pragma unroll
-            for (int j = 0; j < INNER_MAX_BETA; j++)
+            for (int j = 0; j < MB; j++)
                 if (j < A.beta) {
                     const double2 vv = *(const double2 *)(tile + (ii * A.beta + j) * 256 + (s & ~1u));
                     const double v0 = swap ? vv.y : vv.x, v1 = swap ? vv.x : vv.y;
