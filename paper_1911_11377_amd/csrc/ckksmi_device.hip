@@ -930,11 +930,11 @@ extern "C" int ckksmi_plain_mac(ckksmi_ctx *c, const uint64_t *cts, int n_ct, co
     if (n_ct < 1 || n_pts < 0) return CKKSMI_EINVAL;
     if (!cts || !out || !term || (n_pts && !pts) || !al16(cts) || !al16(pts) || !al16(out)) return CKKSMI_EINVAL;
     if (n_groups == 0) return CKKSMI_OK;
-    if ((n_groups + PM_GROUPS - 1) / PM_GROUPS > 65535 || level > 65535) return CKKSMI_EUNSUPPORTED;
+    if ((n_groups + PM_GROUPS - 1) / PM_GROUPS > 65535 || level > 65535 || c->N < 2) return CKKSMI_EUNSUPPORTED;  // words go in pairs
     const size_t ct_words = 2 * (size_t)level * c->N;
     if (out < cts + (size_t)n_ct * ct_words && cts < out + (size_t)n_groups * ct_words) return CKKSMI_EINVAL;  // the sums read every input
     Guard g(c);
-    KL(c, CKKSMI_K_ELEMWISE, (double)n_pts * 2 * level, plain_mac_kernel, dim3(ew_blocks(c->N), level, (n_groups + PM_GROUPS - 1) / PM_GROUPS),
+    KL(c, CKKSMI_K_ELEMWISE, (double)n_pts * 2 * level, plain_mac_kernel, dim3(ew_blocks(c->N / 2), level, (n_groups + PM_GROUPS - 1) / PM_GROUPS),
        dim3(EW_THREADS), S(stream), (const u64d *)cts, n_ct, (const u64d *)pts, n_pts, (const int *)term, n_groups, (u64d *)out, c->d_mod, c->logN, level);
     return g.rc();
 }

@@ -242,38 +242,67 @@ __global__ __launch_bounds__(EW_THREADS) void mul_plain_kernel(const u64d *a, co
 // grid: x = word blocks, y = limb, z = chunks of PM_GROUPS groups: a thread loads the word of ciphertext s once for the
 // chunk's groups (the ciphertexts are re-read once per chunk, the plaintexts once in all).  A table entry beyond the
 // plaintexts counts as "none", so a wrong table gives wrong sums, never an access outside the buffers.  The running
-// sums stay balanced-reduced: |sum| <= p/2 + 1 before a product (|.| <= p) is added.
+// sums are balanced-reduced after every second term.
 #define PM_GROUPS 8
+// the word pairs of source ciphertext `sct` and of the plaintexts its PM_GROUPS table entries name (0 where there is none)
+__device__ __forceinline__ void plain_mac_fetch(const u64d *cts, const u64d *pts, const int *term, int sct, int n_ct, int n_pts, int n_groups, int g0,
+                                                size_t ct_words, size_t pt_words, size_t off, ulonglong2 &x0, ulonglong2 &x1,
+                                                ulonglong2 (&y)[PM_GROUPS]) {
+    const u64d *x = cts + (size_t)sct * ct_words + off;
+    x0 = *(const ulonglong2 *)x;
+    x1 = *(const ulonglong2 *)(x + pt_words);
+#pragma unroll
+    for (int k = 0; k < PM_GROUPS; k++) {
+        const int t = g0 + k < n_groups ? term[(size_t)(g0 + k) * n_ct + sct] : -1;  // the same for every thread
+        y[k] = (t >= 0 && t < n_pts) ? *(const ulonglong2 *)(pts + (size_t)t * pt_words + off) : make_ulonglong2(0ull, 0ull);
+    }
+}
+
+// a thread owns two neighbouring words (16 bytes per lane and access); grid x = blocks over N/2 pairs
 __global__ __launch_bounds__(EW_THREADS) void plain_mac_kernel(const u64d *cts, int n_ct, const u64d *pts, int n_pts, const int *term, int n_groups,
                                                                u64d *out, const ModConst *modc, int logN, int level) {
     const size_t N = (size_t)1 << logN;
-    const size_t w = (size_t)blockIdx.x * EW_THREADS + threadIdx.x;
+    const size_t w = 2 * ((size_t)blockIdx.x * EW_THREADS + threadIdx.x);
     if (w >= N) return;
     const int i = (int)blockIdx.y, g0 = (int)blockIdx.z * PM_GROUPS;
     const ModConst mc = modc[i];
     const size_t ct_words = 2 * (size_t)level * N, pt_words = (size_t)level * N, off = (size_t)i * N + w;
-    double a0[PM_GROUPS], a1[PM_GROUPS];
+    double a0[PM_GROUPS][2], a1[PM_GROUPS][2];
 #pragma unroll
-    for (int k = 0; k < PM_GROUPS; k++) a0[k] = a1[k] = 0.0;
+    for (int k = 0; k < PM_GROUPS; k++) a0[k][0] = a0[k][1] = a1[k][0] = a1[k][1] = 0.0;
+    // the words of source sct + 1 are requested before the products of source sct, so that their latency (table entry,
+    // then plaintext word) lies under arithmetic; an absent term is a product with 0
+    ulonglong2 xn0 = make_ulonglong2(0ull, 0ull), xn1 = xn0, yn[PM_GROUPS];
+    if (n_ct > 0) plain_mac_fetch(cts, pts, term, 0, n_ct, n_pts, n_groups, g0, ct_words, pt_words, off, xn0, xn1, yn);
     for (int sct = 0; sct < n_ct; sct++) {
-        const u64d *x = cts + (size_t)sct * ct_words + off;
-        const double x0 = u2d(x[0]), x1 = u2d(x[pt_words]);
+        const double x0[2] = {u2d(xn0.x), u2d(xn0.y)}, x1[2] = {u2d(xn1.x), u2d(xn1.y)};
+        double y[PM_GROUPS][2];
 #pragma unroll
         for (int k = 0; k < PM_GROUPS; k++) {
-            if (g0 + k >= n_groups) continue;                      // uniform
-            const int t = term[(size_t)(g0 + k) * n_ct + sct];     // the same for every thread
-            if (t < 0 || t >= n_pts) continue;
-            const double y = u2d(pts[(size_t)t * pt_words + off]);
-            a0[k] = reduce_balanced(a0[k] + mulmod(x0, y, mc.p, mc.pinv), mc.p, mc.pinv);
-            a1[k] = reduce_balanced(a1[k] + mulmod(x1, y, mc.p, mc.pinv), mc.p, mc.pinv);
+            y[k][0] = u2d(yn[k].x);
+            y[k][1] = u2d(yn[k].y);
+        }
+        if (sct + 1 < n_ct) plain_mac_fetch(cts, pts, term, sct + 1, n_ct, n_pts, n_groups, g0, ct_words, pt_words, off, xn0, xn1, yn);
+#pragma unroll
+        for (int k = 0; k < PM_GROUPS; k++) {
+#pragma unroll
+            for (int b = 0; b < 2; b++) {
+                // a reduced sum (p/2 + 1) and two products (1.25p each) stay below 3p + 1 < 2^53
+                a0[k][b] += mulmod(x0[b], y[k][b], mc.p, mc.pinv);
+                a1[k][b] += mulmod(x1[b], y[k][b], mc.p, mc.pinv);
+                if (sct & 1) {
+                    a0[k][b] = reduce_balanced(a0[k][b], mc.p, mc.pinv);
+                    a1[k][b] = reduce_balanced(a1[k][b], mc.p, mc.pinv);
+                }
+            }
         }
     }
 #pragma unroll
     for (int k = 0; k < PM_GROUPS; k++) {
         if (g0 + k >= n_groups) continue;
         u64d *o = out + (size_t)(g0 + k) * ct_words + off;
-        o[0] = d2u(canon(a0[k], mc.p, mc.pinv));
-        o[pt_words] = d2u(canon(a1[k], mc.p, mc.pinv));
+        *(ulonglong2 *)o = make_ulonglong2(d2u(canon(a0[k][0], mc.p, mc.pinv)), d2u(canon(a0[k][1], mc.p, mc.pinv)));
+        *(ulonglong2 *)(o + pt_words) = make_ulonglong2(d2u(canon(a1[k][0], mc.p, mc.pinv)), d2u(canon(a1[k][1], mc.p, mc.pinv)));
     }
 }
 
