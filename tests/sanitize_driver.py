@@ -68,4 +68,8 @@ pc.case_conv(be, (7, 2, 51, 0, 52, 1), seed=15, Cin=2, H=3, W=3, Oc=9, kh=3, str
 with be.tuned(8):
     pc.case_relin_and_composite(be, (13, 2, 50, 1, 51, 1), seed=16, batch=2, levels=[2])
     pc.case_ntt(be, (13, 1, 50, 1, 51, 1), seed=17, batch=2)
+    # rotations at a register-tiled size: the pair loads through the automorphism (plain and from a shared ModUp)
+    pc.case_rotate(be, (12, 2, 50, 1, 51, 1), seed=18, rotations=[1, 700], batch=2)
+    pc.case_rotate_hoisted(be, (12, 2, 50, 1, 51, 1), seed=19, rotations=(1, 700), batch=2)
+pc.case_plain_mac(be, (6, 3, 30, 1, 31, 1), seed=20)
 print("emulated kernel pass done", flush=True)
