@@ -1318,6 +1318,27 @@ extern "C" int ckksmi_encrypt_device(ckksmi_ctx *c, const uint64_t *pk, const ui
         const int items = std::min(chunk, batch - b0);
         u64 *small = (u64 *)ws;  // [items][3][level][N]: r, e0, e1
         const int64_t *src[3] = {r, e0, e1};
+        if (c->fused) {
+            // register-tiled sizes: the column pass reads the small coefficients themselves, the row pass forms the ciphertext
+            NttV2Args V;
+            memset(&V, 0, sizeof(V));
+            V.modc = c->d_mod; V.tw = c->d_tww_fwd; V.logN = c->logN; V.p51 = c->p51mask; V.items = items;
+            V.map = table_map(idx, level, N, (size_t)3 * level * N);  // source: one int64 polynomial per item
+            const unsigned tiles = (unsigned)(N / 4096);
+            const unsigned zc = zchunks_for(c, tiles * level, items, V.items_per_z);
+            for (int which = 0; which < 3; which++) {
+                V.src = (const u64d *)(src[which] + (size_t)b0 * N);
+                V.dst = (u64d *)(small + (size_t)which * level * N);
+                KL(c, CKKSMI_K_ENCRYPT, (double)items * level, ntt_v2_fwd_cols_small_kernel, dim3(tiles, level, zc), dim3(V2_THREADS), st, V);
+            }
+            EncryptRowsArgs E;
+            E.mid = (const u64d *)small; E.pk = (const u64d *)pk; E.pt = (const u64d *)(pt + (size_t)b0 * level * N);
+            E.ct = (u64d *)(ct + (size_t)b0 * 2 * level * N); E.modc = c->d_mod; E.tw = c->d_tww_fwd; E.logN = c->logN; E.level = level;
+            E.n_q = c->n_q; E.items = items; E.p51 = c->p51mask;
+            const unsigned xc = zchunks_for(c, tiles * level, items, E.items_per_x);
+            KL(c, CKKSMI_K_ENCRYPT, (double)items * level, encrypt_rows_kernel, dim3(xc, tiles, level), dim3(V2_THREADS), st, E);
+            continue;
+        }
         const size_t rows_total = (size_t)items * N;
         for (int which = 0; which < 3; which++)
             KL(c, CKKSMI_K_ENCRYPT, (double)items * level, small_to_rns_kernel, dim3(ew_blocks(rows_total)), dim3(EW_THREADS), st,

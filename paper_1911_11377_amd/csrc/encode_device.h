@@ -158,6 +158,84 @@ __global__ __launch_bounds__(EW_THREADS) void encrypt_combine_kernel(const u64d 
     ct[(item * 2 * level + level + i) * N + n] = d2u(c1);
 }
 
+// The same on the register-tiled kernels (2^12 <= N <= 2^16), after the forward column pass of r, e0, e1
+// (ntt_v2_fwd_cols_small_kernel): a workgroup takes the three polynomials' tiles of one limb through the forward row pass one
+// after the other and forms both ciphertext words while the results are on chip, so that the transformed r, e0, e1 are
+// never written.  mid: [items][3][level][N] column-pass output (reduced doubles).
+struct EncryptRowsArgs {
+    const u64d *mid, *pk, *pt;
+    u64d *ct;
+    const ModConst *modc;
+    const double *tw;  // forward twiddles
+    int logN, level, n_q, items, items_per_x;
+    P51Mask p51;
+};
+
+template <bool P51>
+__device__ __forceinline__ void encrypt_rows_body(const EncryptRowsArgs &A, double *lds, double *tw1_lds, int i) {
+    const unsigned N = 1u << A.logN, N1 = N >> 8;
+    const double p = A.modc[i].p, pinv = A.modc[i].pinv;
+    const unsigned tid = threadIdx.x, hi4 = tid >> 4, lo4 = tid & 15, tile = blockIdx.y;
+    double tw2[15];
+    load_row_twiddles(A.tw + (size_t)i * N, N1, tile, hi4, lo4, tw1_lds, tw2);
+    const size_t tile0 = (size_t)tile * 4096, st = (size_t)A.level * N;
+    // the public key's words of this tile serve every item of the workgroup
+    ulonglong2 kb[8], ka[8];
+#pragma unroll
+    for (int s = 0; s < 8; s++) {
+        kb[s] = ((const ulonglong2 *)(A.pk + (size_t)i * N + tile0))[row_pair_index(hi4, lo4, s)];
+        ka[s] = ((const ulonglong2 *)(A.pk + ((size_t)A.n_q + i) * N + tile0))[row_pair_index(hi4, lo4, s)];
+    }
+    const unsigned it0 = blockIdx.x * (unsigned)A.items_per_x;
+    const unsigned it1 = (it0 + A.items_per_x < (unsigned)A.items) ? it0 + A.items_per_x : (unsigned)A.items;
+    for (unsigned it = it0; it < it1; it++) {
+        const u64d *mid = A.mid + ((size_t)it * 3 * A.level + i) * N + tile0;
+        ulonglong2 mm[8];
+#pragma unroll
+        for (int s = 0; s < 8; s++) mm[s] = ((const ulonglong2 *)(A.pt + ((size_t)it * A.level + i) * N + tile0))[row_pair_index(hi4, lo4, s)];
+        rows_fwd_to_lds<P51>(mid, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+        double r[16];
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const double *rr = lds + hi4 * V2_GS + row_pair_lds(lo4, s);
+            r[2 * s] = rr[0];
+            r[2 * s + 1] = rr[1];
+        }
+        ROW_GROUP_SYNC();
+        rows_fwd_to_lds<P51>(mid + st, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+        u64d *c0 = A.ct + ((size_t)it * 2 * A.level + i) * N + tile0, *c1 = c0 + st;
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            // a product (1.25p), a balanced-reduced word and a canonical one: below 4p
+            const double *ee = lds + hi4 * V2_GS + row_pair_lds(lo4, s);
+            const double v0 = mulmod(r[2 * s], u2d(kb[s].x), p, pinv) + ee[0] + u2d(mm[s].x);
+            const double v1 = mulmod(r[2 * s + 1], u2d(kb[s].y), p, pinv) + ee[1] + u2d(mm[s].y);
+            ((ulonglong2 *)c0)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
+        }
+        ROW_GROUP_SYNC();
+        rows_fwd_to_lds<P51>(mid + 2 * st, lds, tw1_lds, tw2, p, pinv, hi4, lo4);
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const double *ee = lds + hi4 * V2_GS + row_pair_lds(lo4, s);
+            const double v0 = mulmod(r[2 * s], u2d(ka[s].x), p, pinv) + ee[0];
+            const double v1 = mulmod(r[2 * s + 1], u2d(ka[s].y), p, pinv) + ee[1];
+            ((ulonglong2 *)c1)[row_pair_index(hi4, lo4, s)] = make_ulonglong2(d2u(canon(v0, p, pinv)), d2u(canon(v1, p, pinv)));
+        }
+        ROW_GROUP_SYNC();
+    }
+}
+
+// grid: x = chunk of items, y = row tile (N/4096), z = limb
+__global__ __launch_bounds__(V2_THREADS) void encrypt_rows_kernel(EncryptRowsArgs A) {
+    __shared__ double lds[16 * V2_GS];
+    __shared__ double tw1_lds[16 * 16];
+    const int i = (int)blockIdx.z;
+    if (is_p51(A.p51, i))
+        encrypt_rows_body<true>(A, lds, tw1_lds, i);
+    else
+        encrypt_rows_body<false>(A, lds, tw1_lds, i);
+}
+
 // ---------------------------------------------------------------- sampling
 // Counter-based (Philox4x32-10: Salmon, Moraes, Dror, Shaw 2011), one block per coefficient: counter
 // (t, kind, lo32(p), hi32(p)) for coefficient t of polynomial p, key = the two halves of the seed.

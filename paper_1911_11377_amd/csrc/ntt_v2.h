@@ -191,7 +191,9 @@ struct ColsMasks {
     static constexpr int I2 = P51 ? 0x2 : 0;              // inverse round 1 from a reduced value, last stage multiplies
 };
 
-template <bool INV, int Q, bool P51>
+// SMALL (forward only): the source is a polynomial with small signed coefficients, one int64 per coefficient and the same
+// for every limb (item i at (const long long *)A.src + i * src_item_stride): its residues are the values themselves
+template <bool INV, int Q, bool P51, bool SMALL = false>
 __device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int t, unsigned li) {
     typedef ColsGeom<Q> Geo;
     typedef ColsMasks<Q, P51> Mk;
@@ -216,7 +218,11 @@ __device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int
         double x[16];
         if (!INV) {
 #pragma unroll
-            for (int e = 0; e < 16; e++) x[e] = u2d(src[geo.g1(e)]);
+            for (int e = 0; e < 16; e++) {
+                // exact for magnitudes below 2^53, which the reduction brings into the range of the first round
+                if (SMALL) x[e] = reduce_balanced((double)((const long long *)A.src + (size_t)it * A.map.src_item_stride)[geo.g1(e)], p, pinv);
+                else x[e] = u2d(src[geo.g1(e)]);
+            }
             fwd_round<Mk::F1>(x, tw1, p, pinv);
 #pragma unroll
             for (int e = 0; e < 16; e++) lds[geo.l1(e)] = x[e];
@@ -316,6 +322,23 @@ __device__ __forceinline__ void ntt_v2_rows(const NttV2Args &A, double *lds, int
             for (int e = 0; e < 16; e++) dst[tile0 + hi4 * 256 + lo4 + 16 * e] = mid_store(x[e], p, pinv);
         }
         ROW_GROUP_SYNC();
+    }
+}
+
+// forward column pass of polynomials given as small signed integers (|coefficient| far below every modulus): same grid as
+// ntt_v2_kernel; the residues are never written out limb by limb
+__global__ __launch_bounds__(V2_THREADS) void ntt_v2_fwd_cols_small_kernel(NttV2Args A) {
+    __shared__ double lds[16 * V2_GS];
+    unsigned item_unused, li;
+    const int t = resolve_limb(A.map, blockIdx.y, item_unused, li);
+    if (t < 0) return;
+    const bool p51 = is_p51(A.p51, t);
+    switch (A.logN) {
+        case 12: if (p51) ntt_v2_cols<false, 0, true, true>(A, lds, t, li); else ntt_v2_cols<false, 0, false, true>(A, lds, t, li); break;
+        case 13: if (p51) ntt_v2_cols<false, 1, true, true>(A, lds, t, li); else ntt_v2_cols<false, 1, false, true>(A, lds, t, li); break;
+        case 14: if (p51) ntt_v2_cols<false, 2, true, true>(A, lds, t, li); else ntt_v2_cols<false, 2, false, true>(A, lds, t, li); break;
+        case 15: if (p51) ntt_v2_cols<false, 3, true, true>(A, lds, t, li); else ntt_v2_cols<false, 3, false, true>(A, lds, t, li); break;
+        default: if (p51) ntt_v2_cols<false, 4, true, true>(A, lds, t, li); else ntt_v2_cols<false, 4, false, true>(A, lds, t, li); break;
     }
 }
 

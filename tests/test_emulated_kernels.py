@@ -179,6 +179,12 @@ def test_emulated_device_encode_and_encrypt(be, shape, log_scale):
     pc.case_encode_encrypt_device(be, shape, seed=136, batch=2, log_scale=log_scale)
     if shape == TINY:
         pc.case_encode_encrypt_device(be, shape, seed=137, batch=3, level=2, log_scale=25, complex_slots=False, small_ws=True)
+    if shape[0] == 12:
+        # the fused encryption (column pass from the small coefficients, row pass forming the ciphertext): 51-bit primes,
+        # workgroups looping over items, a level below the top, the batch swept in chunks
+        with be.tuned(2):
+            pc.case_encode_encrypt_device(be, (12, 3, 51, 1, 51, 1), seed=138, batch=3, level=2, log_scale=40, small_ws=True)
+            pc.case_encode_encrypt_device(be, (12, 3, 51, 1, 51, 1), seed=139, batch=5, log_scale=40)
 
 
 def test_emulated_device_sampler(be):
