@@ -218,7 +218,7 @@ int ckksmi_rotate(ckksmi_ctx *ctx, const uint64_t *a, const int *rot /*host [bat
  * the stream before returning (a coefficient of 2^62 or more is reported as CKKSMI_EINVAL).
  * ckksmi_encrypt_device: ct = (r*b + e0 + m, r*a + e1) exactly as ckksmi_encrypt; pk: device [2][n_q][N]; pt: device
  * [batch][level][N]; r, e0, e1: device int64 [batch][N] (the caller draws them: ternary r, small errors; magnitudes
- * below 2^52); ct: device [batch][2][level][N], must not overlap pt; ws: device, 3*level*N*8 bytes per item (a smaller
+ * below 2^51); ct: device [batch][2][level][N], must not overlap pt; ws: device, 3*level*N*8 bytes per item (a smaller
  * one makes several sweeps). */
 /* Small polynomials drawn on the device (the randomness of encryption and key generation, section 2.1; the paper names
  * no distribution: ternary and rounded Gaussian are the usual ones).  Counter-based (Philox4x32-10, one block per

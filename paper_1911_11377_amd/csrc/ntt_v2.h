@@ -219,8 +219,12 @@ __device__ __forceinline__ void ntt_v2_cols(const NttV2Args &A, double *lds, int
         if (!INV) {
 #pragma unroll
             for (int e = 0; e < 16; e++) {
-                // exact for magnitudes below 2^53, which the reduction brings into the range of the first round
-                if (SMALL) x[e] = reduce_balanced((double)((const long long *)A.src + (size_t)it * A.map.src_item_stride)[geo.g1(e)], p, pinv);
+                // magnitudes below 2^51: shifted to a non-negative integer, which becomes a double without a conversion
+                // instruction (those issue at a quarter of the rate); the reduction brings it into the range of the first round
+                if (SMALL) {
+                    const long long v = ((const long long *)A.src + (size_t)it * A.map.src_item_stride)[geo.g1(e)];
+                    x[e] = reduce_balanced(u2d((unsigned long long)(v + (1ll << 51))) - 2251799813685248.0, p, pinv);
+                }
                 else x[e] = u2d(src[geo.g1(e)]);
             }
             fwd_round<Mk::F1>(x, tw1, p, pinv);
